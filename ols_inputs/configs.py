@@ -1,0 +1,77 @@
+"""Workload descriptions for the five Overlap Local-SGD configurations.
+
+Pure data: the hyper-parameters of each configuration (worker count m, model
+shape, batch size, tau, alpha, gamma, local momentum mu, iteration count K) and
+the recipe constants of the synthetic inputs.  Nothing of the method's
+arithmetic lives here; both the CPU oracle's tests and the HIP path's tests /
+benchmark read these records and then do their own computation.
+
+Hyper-parameter names follow the paper's Section 2 notation: gamma = learning
+rate, alpha = pull-back strength, tau = local steps per round, m = workers.
+`mu` is the local (per-worker) momentum factor, which the paper uses but does
+not name; the paper's beta is the anchor momentum factor (`beta_z` here).
+"""
+from dataclasses import dataclass, field, replace
+from typing import Optional, Tuple
+
+BASE_SEED = 20200209
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    kind: str                      # "lsq" | "mlp" | "stream"
+    m: int
+    tau: int
+    alpha: float
+    gamma: float
+    mu: float
+    K: int                         # local iterations per worker
+    batch: int = 0
+    dims: Tuple[int, ...] = ()     # MLP layer widths, input first
+    d_flat: int = 0                # lsq / stream: parameter count
+    nb: int = 0                    # fixed, unshuffled batches per worker (cycled)
+    gemm_dtype: str = "f32"        # "f32" | "bf16"
+    noniid_classes: int = 0        # >0: each worker's labels come from this many classes
+    n_classes: int = 10
+    grad_sigma: float = 0.1        # stream: gradients ~ N(0, sigma^2)
+    grad_pool: int = 2             # stream: number of distinct gradient tensors cycled
+    seed: int = BASE_SEED
+    beta_z: float = 0.0            # anchor momentum (0 = plain anchor average)
+    nesterov: bool = True
+
+    @property
+    def d(self) -> int:
+        if self.kind == "mlp":
+            return sum(self.dims[l] * self.dims[l + 1] + self.dims[l + 1]
+                       for l in range(len(self.dims) - 1))
+        return self.d_flat
+
+    @property
+    def rounds(self) -> int:
+        return self.K // self.tau
+
+    def scaled(self, **kw) -> "Config":
+        """A copy with some fields replaced (used for small parity cases)."""
+        return replace(self, **kw)
+
+
+# Section 4 of the paper fixes batch 128 per node, 16 nodes, alpha = 0.6 for
+# tau >= 2; the remaining numbers are the configurations' own.
+CONFIGS = {
+    1: Config(name="cfg1_lsq_m4", kind="lsq", m=4, tau=2, alpha=0.6, gamma=0.01,
+              mu=0.0, K=50, batch=32, d_flat=1024, nb=50),
+    2: Config(name="cfg2_mlp_f32_m16", kind="mlp", m=16, tau=2, alpha=0.6, gamma=0.05,
+              mu=0.9, K=200, batch=128, dims=(3072, 512, 10), nb=24),
+    3: Config(name="cfg3_mlp_bf16_m16", kind="mlp", m=16, tau=4, alpha=0.5, gamma=0.05,
+              mu=0.9, K=200, batch=256, dims=(3072, 2048, 2048, 2048, 10), nb=12,
+              gemm_dtype="bf16"),
+    4: Config(name="cfg4_stream_m16", kind="stream", m=16, tau=2, alpha=0.6, gamma=0.1,
+              mu=0.9, K=200, d_flat=11_200_000),
+    5: Config(name="cfg5_mlp_noniid_m64", kind="mlp", m=64, tau=8, alpha=0.5, gamma=0.05,
+              mu=0.9, K=400, batch=64, dims=(3072, 1024, 10), nb=12, noniid_classes=2),
+}
+
+
+def get(idx: int) -> Config:
+    return CONFIGS[idx]
