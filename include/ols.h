@@ -1,0 +1,234 @@
+/*
+ * ols.h -- C boundary of the Overlap Local-SGD hot path on one MI355X (gfx950).
+ *
+ * The library holds m simulated workers as m model replicas resident in HBM and
+ * runs the iteration of arXiv 2002.09539, Section 2 ("Proposed Algorithm"):
+ *
+ *   local step   x_{k+1/2}^{(i)} = x_k^{(i)} - gamma g_i(x_k^{(i)}; xi_k^{(i)})
+ *   pull-back    x_{k+1}^{(i)}   = x_{k+1/2}^{(i)} - alpha (x_{k+1/2}^{(i)} - z_k)    when (k+1) mod tau == 0
+ *   anchor       z_{k+1}         = (1/m) sum_i x_{k+1}^{(i)}                          when (k+1) mod tau == 0
+ *
+ * with the anchor refresh running on a side stream while the next round's local
+ * steps run on the main stream (the overlap the paper describes around its
+ * timeline figure), and the optional momentum variant of the same section.
+ *
+ * General conventions
+ *   - Every pointer named *_dev is DEVICE memory owned by the caller and must stay
+ *     valid until ols_destroy or until it is re-bound.  The library allocates no
+ *     device memory; it owns only HIP events.  Streams are hipStream_t handles
+ *     passed as void* and are owned by the caller (default priority).
+ *   - All state tensors are fp32.  Replica-major layout: row i of x/buf/g is worker
+ *     i's flat parameter / momentum / gradient vector; rows are `ld` elements apart,
+ *     ld = ols_row_stride(d) (d rounded up to a multiple of 64 so rows are 256-byte
+ *     aligned).  Elements [d, ld) of every row are padding: the caller zero-fills
+ *     them once and never reads them.
+ *   - Every call returns OLS_OK (0) or a negative error code; ols_last_error()
+ *     returns a thread-local message for the last failure.  Calls are asynchronous
+ *     with respect to the host unless stated otherwise.  A handle is not thread-safe.
+ *   - There is no CPU fallback: every step runs in HIP kernels, and a missing
+ *     device makes the first launching call fail with OLS_EHIP.
+ */
+#ifndef OLS_H
+#define OLS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define OLS_API __attribute__((visibility("default")))
+#else
+#define OLS_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ols_ctx* ols_handle;
+
+enum {
+    OLS_OK = 0,
+    OLS_EINVAL = -1, /* bad argument                                  */
+    OLS_ESTATE = -2, /* call out of order for the algorithm's schedule */
+    OLS_EHIP = -3,   /* HIP runtime failure                            */
+    OLS_ENOMEM = -4  /* caller-provided workspace too small            */
+};
+
+/* keys of ols_set_option */
+enum {
+    OLS_OPT_NESTEROV = 1,      /* 1 (default): local step direction g + mu buf; 0: heavy ball (direction buf) */
+    OLS_OPT_FUSE_PULL = 2,     /* 1 (default): the tau-th local step of a round defers its parameter write and
+                                  ols_sync_pull applies step + pull-back in ONE pass over HBM; 0: two passes.
+                                  Both orders execute the same fp32 operation sequence per element.           */
+    OLS_OPT_SERIALIZE = 3,     /* 1: the anchor refresh runs on the main stream (no overlap); default 0       */
+    OLS_OPT_DRY_RUN = 4,       /* 1: advance the schedule and record the launch trace but launch nothing
+                                  (host-logic tests on machines without a GPU); default 0                     */
+    OLS_OPT_KERNEL_TIMING = 5, /* 1: bracket every kernel with HIP events on its own stream and accumulate
+                                  per-kernel durations (see ols_kernel_stats); default 0                      */
+    OLS_OPT_TRACE = 6,         /* 1: keep a host-side log of launches (see ols_trace_get); default 0          */
+    OLS_OPT_MEAN_SPLIT = 7,    /* anchor-mean kernel: 0 = choose from (m, d); 1, 2 or 4 = number of wavefronts
+                                  of a workgroup the replica axis is split over before the LDS tree combine   */
+    OLS_OPT_FUSE_MEAN = 8      /* 1: ols_sync_pull also produces the new anchor in the same pass (each thread
+                                  owns a parameter column across all m replicas); ols_anchor_update_async then
+                                  only publishes it.  Removes the separate reduction instead of hiding it.
+                                  default 0                                                                   */
+};
+
+/* kernel kinds for ols_kernel_stats / the launch trace */
+enum {
+    OLS_K_INIT = 0,
+    OLS_K_STEP = 1,       /* momentum / plain local step                */
+    OLS_K_STEP_PULL = 2,  /* fused local step + pull-back               */
+    OLS_K_PULL = 3,       /* stand-alone pull-back                      */
+    OLS_K_MEAN = 4,       /* replica-axis mean (anchor refresh)         */
+    OLS_K_STEP_PULL_MEAN = 5,
+    OLS_K_LSQ_RESID = 6,
+    OLS_K_LSQ_GRAD = 7,
+    OLS_K_GEMM_FWD = 8,   /* hidden layer forward, bias + ReLU epilogue */
+    OLS_K_GEMM_DW = 9,    /* weight gradient A^T dZ                     */
+    OLS_K_GEMM_DA = 10,   /* back-propagated delta dZ W^T, ReLU mask    */
+    OLS_K_HEAD_FWD = 11,  /* output layer + softmax cross-entropy       */
+    OLS_K_HEAD_BWD = 12,  /* output layer gradients and delta           */
+    OLS_K_BIAS_GRAD = 13,
+    OLS_K_CAST = 14,      /* fp32 -> bf16 operand conversion            */
+    OLS_K_COUNT = 15
+};
+
+typedef struct ols_trace_entry {
+    int32_t kind;      /* OLS_K_*                                         */
+    int32_t stream;    /* 0 = main, 1 = side                              */
+    int32_t src_buf;   /* which replica buffer was read: 0 = x, 1 = x_alt */
+    int32_t dst_buf;   /* which replica buffer was written (-1: none)     */
+    int32_t waited;    /* 1 if the launch was preceded by a cross-stream event wait */
+    int32_t k;         /* local iterations completed when it was enqueued */
+} ols_trace_entry;
+
+/* ---- life cycle ------------------------------------------------------------------------------ */
+
+/* Creates the schedule state for m workers with d parameters each (Section 2 notation: tau local
+ * steps per round, pull-back strength alpha, learning rate gamma).  beta is the LOCAL momentum
+ * factor mu of the "Momentum Variant" paragraph (0 disables the momentum buffer); the paper's own
+ * beta (anchor momentum) is set with ols_set_anchor_momentum.
+ * Requires m >= 1, d >= 1, tau >= 1, 0 <= alpha <= 1, gamma > 0, 0 <= beta < 1.
+ * Touches no device.  Returns NULL on error (see ols_last_error). */
+OLS_API ols_handle ols_create(int m, int64_t d, int tau, float alpha, float gamma, float beta);
+
+/* Destroys the handle and its events.  Drains both streams first if anything was launched. */
+OLS_API int ols_destroy(ols_handle h);
+
+/* Row stride (elements) the state tensors must use for d parameters: d rounded up to 64. */
+OLS_API int64_t ols_row_stride(int64_t d);
+
+/* Binds caller-owned device state.
+ *   x_dev      [m][ld]  replica parameters (current buffer)
+ *   x_alt_dev  [m][ld]  second replica buffer for the overlap, or NULL.  With it, the first update
+ *                       after an anchor refresh is written out-of-place so the side stream can
+ *                       still read the round-boundary models; without it that update first waits
+ *                       for the refresh (gradient computation still overlaps).
+ *   buf_dev    [m][ld]  local momentum buffers; may be NULL iff beta == 0
+ *   g_dev      [m][ld]  stochastic gradients (written by the attached model, or by the caller)
+ *   z_dev      [ld]     anchor model
+ *   ld         must equal ols_row_stride(d)
+ *   main_stream, side_stream  hipStream_t; side_stream may equal main_stream (forces serial order)
+ * All pointers must be 256-byte aligned.  Errors: OLS_EINVAL. */
+OLS_API int ols_bind(ols_handle h, float* x_dev, float* x_alt_dev, float* buf_dev, float* g_dev, float* z_dev,
+             int64_t ld, void* main_stream, void* side_stream);
+
+/* Sets x^{(i)} = z = x0 for every worker (Theorem 1's common starting point), zeroes the momentum
+ * buffers and resets k to 0.  x0_dev: [d] fp32 on the device.  Asynchronous on the main stream. */
+OLS_API int ols_init_params(ols_handle h, const float* x0_dev);
+
+/* Anchor momentum of the "Momentum Variant" paragraph: v <- beta_z v + (mean_i x^{(i)} - z),
+ * z <- z + v.  v_dev: [ld] device buffer (zero-filled by the caller), or NULL with beta_z == 0 to
+ * return to the plain average.  Must be called before the first local step. */
+OLS_API int ols_set_anchor_momentum(ols_handle h, float beta_z, float* v_dev);
+
+/* Changes the learning rate gamma for subsequent local steps (Section 4 uses a schedule). */
+OLS_API int ols_set_lr(ols_handle h, float gamma);
+
+/* ---- models that produce the stochastic gradients g_i --------------------------------------- */
+
+/* Linear least squares: loss_i = (1/B) sum_s 0.5 (a_s . x^{(i)} - y_s)^2 over the worker's batch of
+ * B rows; g_i = (1/B) A^T (A x^{(i)} - y).  Inputs per ols_set_batch: A [B][d] fp32, y [B] fp32. */
+OLS_API int ols_attach_lsq(ols_handle h, int batch);
+
+/* ReLU multi-layer perceptron with softmax cross-entropy (mean over the batch).
+ *   dims[0..n_layers]: layer widths, input first; the last is the class count (<= 32).
+ *   Flat parameter layout per layer l: W_l row-major [dims[l]][dims[l+1]] then b_l [dims[l+1]];
+ *   d must equal the sum.  dims[0..n_layers-1] and batch must be multiples of 4.
+ *   gemm_dtype 0: fp32 MFMA; 1: bf16 operands (round-to-nearest-even), fp32 accumulate, fp32 master
+ *   weights and gradients.
+ * Inputs per ols_set_batch: X [B][dims[0]] fp32, labels [B] int32 in [0, classes). */
+OLS_API int ols_attach_mlp(ols_handle h, int n_layers, const int* dims, int batch, int gemm_dtype);
+
+/* Bytes of caller-provided device workspace the attached model needs (activations, deltas, per-sample
+ * losses, bf16 operand copies).  0 when no model is attached. */
+OLS_API int64_t ols_workspace_bytes(ols_handle h);
+OLS_API int ols_bind_workspace(ols_handle h, void* ws_dev, int64_t bytes); /* 256-byte aligned; OLS_ENOMEM if short */
+
+/* Mini-batches for the NEXT local step: worker i reads X_dev + i * x_worker_stride (elements) and
+ * y_dev + i * y_worker_stride (elements of int32 labels or fp32 targets).  Pointers only; no copy. */
+OLS_API int ols_set_batch(ols_handle h, const float* X_dev, int64_t x_worker_stride, const void* y_dev,
+                  int64_t y_worker_stride);
+
+/* Without an attached model the caller supplies gradients itself: rebinds g ([m][ld] device) for the
+ * next local step. */
+OLS_API int ols_set_gradient(ols_handle h, float* g_dev);
+
+/* ---- the iteration --------------------------------------------------------------------------- */
+
+/* Iteration k for every worker: gradients of the attached model at x_k^{(i)} on the current batch,
+ * then the local (momentum) step; k <- k + 1.  When the new k is a multiple of tau a pull is due:
+ * with OLS_OPT_FUSE_PULL the parameter write is left pending for ols_sync_pull.
+ * OLS_ESTATE if unbound / uninitialised, if a pull or an anchor refresh is due, or if a model is
+ * attached but no batch or workspace is set. */
+OLS_API int ols_local_step(ols_handle h);
+
+/* Pull-back of every replica toward the anchor z_k (the anchor produced by the PREVIOUS round's
+ * refresh; the main stream first waits for that refresh if it is still in flight, so the result
+ * does not depend on timing).  Legal only when k > 0 and k mod tau == 0 and not yet pulled. */
+OLS_API int ols_sync_pull(ols_handle h);
+
+/* Anchor refresh z <- (1/m) sum_i x^{(i)} over the post-pull models, enqueued on the side stream
+ * behind the pull and overlapped with the following local steps.  Legal only right after a pull. */
+OLS_API int ols_anchor_update_async(ols_handle h);
+
+/* ---- results --------------------------------------------------------------------------------- */
+
+/* Copies d floats: which = 0..m-1 a replica, -1 the anchor z.  which = -2 computes the replica mean
+ * (1/m) sum_i x^{(i)} into dst, which must then be a 256-byte aligned DEVICE buffer of
+ * ols_row_stride(d) floats.  Drains both streams first (synchronous).  OLS_ESTATE while a fused pull
+ * is pending.  dst_is_device selects the kind of dst. */
+OLS_API int ols_get_params(ols_handle h, int which, float* dst, int dst_is_device);
+
+/* Mean mini-batch loss of each worker at the most recent local step, per_worker_host [m].
+ * Synchronous. */
+OLS_API int ols_get_loss(ols_handle h, float* per_worker_host);
+
+/* Blocks until both streams have drained. */
+OLS_API int ols_sync(ols_handle h);
+
+OLS_API int ols_set_option(ols_handle h, int key, int64_t value);
+
+/* Local iterations completed so far (k). */
+OLS_API int64_t ols_iteration(ols_handle h);
+
+/* ---- instrumentation ------------------------------------------------------------------------- */
+
+/* Accumulated HIP-event timing of one kernel kind since OLS_OPT_KERNEL_TIMING was enabled.
+ * Synchronous (drains the streams). */
+OLS_API int ols_kernel_stats(ols_handle h, int kind, int64_t* launches, double* total_ms);
+OLS_API const char* ols_kernel_name(int kind);
+
+/* Launch trace (OLS_OPT_TRACE): number of entries, and entry idx.  The trace keeps the first 65536
+ * launches after it is enabled. */
+OLS_API int64_t ols_trace_count(ols_handle h);
+OLS_API int ols_trace_get(ols_handle h, int64_t idx, ols_trace_entry* out);
+
+OLS_API const char* ols_last_error(void);
+OLS_API const char* ols_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OLS_H */

@@ -1,0 +1,230 @@
+// Grouped fp32 GEMMs on the matrix cores (v_mfma_f32_32x32x2_f32) for the hidden layers of the
+// per-worker MLPs: one group per worker, all groups in one launch.
+//
+//   FWD  C[M][N] = relu(A[M][K] W[K][N] + bias[N])      activations; A rows are samples
+//   DW   C[M][N] = A[K][M]^T B[K][N]                     weight gradient; contraction over the batch
+//   DA   C[M][N] = (A[M][K] B[N][K]^T) * [mask > 0]      back-propagated delta through ReLU
+//
+// (forward / backward of the mini-batch loss whose gradient is the g_i of Section 2, arXiv 2002.09539.)
+//
+// Tiling: a workgroup of four wavefronts owns a BM x BN output tile; each wavefront owns TM x TN blocks
+// of 32 x 32 held in accumulator registers.  K is consumed in slices of BK staged through LDS in the
+// operands' own memory order with 16-byte vector copies, double-buffered so that the global loads of
+// slice t+1 are in flight while slice t feeds the matrix cores.  An operand whose contraction index is
+// contiguous in memory ("KC") is read from LDS as one 16-byte vector per lane that serves four
+// consecutive MFMA steps; an operand whose row index is contiguous ("RC") is read one dword per step.
+// Both use the same lane -> k assignment (k = 8 q + 4 (lane / 32) + e), which is all the contraction
+// needs.  Row padding keeps both read patterns free of LDS bank conflicts.
+//
+// Workgroup ids are remapped so that consecutive tiles of one worker land on the same XCD (workgroups
+// are dealt round-robin to the 8 XCDs, each with its own L2), keeping a worker's weights in one L2.
+#include "ols_internal.h"
+
+namespace ols {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+enum GemmMode { kFwd = 0, kDw = 1, kDa = 2 };
+
+constexpr int kThreads = 256;
+constexpr int kXcds = 8;
+
+struct GemmDev {
+    const float* a;
+    const float* b;
+    float* c;
+    const float* bias;
+    const float* mask;
+    int64_t sa, sb, sc, sbias, smask;
+    int M, N, K, lda, ldb, ldc;
+    int tiles_m, tiles_n, total_tiles, chunk;
+};
+
+// One operand tile of ROWS x BK in LDS.  KC: stored [ROWS][BK + 4]; RC: stored [BK][ROWS + 4].
+template <int ROWS, int BK, bool KC>
+struct Tile {
+    static constexpr int kPitch = KC ? BK + 4 : ROWS + 4;
+    static constexpr int kLines = KC ? ROWS : BK;         // lines of contiguous memory
+    static constexpr int kLineLen = KC ? BK : ROWS;       // elements per line
+    static constexpr int kVecPerLine = kLineLen / 4;
+    static constexpr int kVecs = kLines * kVecPerLine;
+    static constexpr int kPerThread = (kVecs + kThreads - 1) / kThreads;
+    static constexpr int kFloats = kLines * kPitch;
+
+    // Global -> registers.  `base` points at the operand of this group; (row0, k0) is the tile origin;
+    // rows / klen bound the valid region (zero fill outside).  Row and k extents are multiples of 4.
+    __device__ static void load(f4 (&r)[kPerThread], const float* __restrict__ base, int ld, int row0, int k0,
+                                int rows, int klen) {
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t) {
+            const int v = threadIdx.x + t * kThreads;
+            f4 val = {0.f, 0.f, 0.f, 0.f};
+            if (kVecs % kThreads == 0 || v < kVecs) {
+                const int line = v / kVecPerLine, off = (v % kVecPerLine) * 4;
+                const int row = KC ? row0 + line : row0 + off;
+                const int k = KC ? k0 + off : k0 + line;
+                if (row < rows && k < klen) {
+                    const int64_t idx = KC ? (int64_t)row * ld + k : (int64_t)k * ld + row;
+                    val = *(const f4*)(base + idx);
+                }
+            }
+            r[t] = val;
+        }
+    }
+    __device__ static void store(float* lds, const f4 (&r)[kPerThread]) {
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t) {
+            const int v = threadIdx.x + t * kThreads;
+            if (kVecs % kThreads == 0 || v < kVecs) {
+                const int line = v / kVecPerLine, off = (v % kVecPerLine) * 4;
+                *(f4*)(lds + line * kPitch + off) = r[t];
+            }
+        }
+    }
+    // Fragment of the 32-row block starting at `r0` for k-octet q: four values, one per MFMA step e,
+    // value e belonging to k = 8 q + 4 half + e.
+    __device__ static f4 frag(const float* lds, int r0, int q, int lane32, int half) {
+        if (KC) return *(const f4*)(lds + (r0 + lane32) * kPitch + 8 * q + 4 * half);
+        f4 v;
+        const float* p = lds + (8 * q + 4 * half) * kPitch + r0 + lane32;
+        v.x = p[0];
+        v.y = p[kPitch];
+        v.z = p[2 * kPitch];
+        v.w = p[3 * kPitch];
+        return v;
+    }
+};
+
+template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
+    constexpr bool A_KC = MODE != kDw;   // FWD, DA: A[M][K];  DW: A[K][M]
+    constexpr bool B_KC = MODE == kDa;   // DA: B[N][K];  FWD, DW: B[K][N]
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    static_assert(WAVES_M * WAVES_N * 64 == kThreads, "four wavefronts");
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile shape");
+    using TA = Tile<BM, BK, A_KC>;
+    using TB = Tile<BN, BK, B_KC>;
+    __shared__ __attribute__((aligned(16))) float lds_a[2][TA::kFloats];
+    __shared__ __attribute__((aligned(16))) float lds_b[2][TB::kFloats];
+
+    // XCD-aware tile id: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous tile range
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int tile = xcd * p.chunk + slot;
+    if (slot >= p.chunk || tile >= p.total_tiles) return;
+    const int per_group = p.tiles_m * p.tiles_n;
+    const int group = tile / per_group;
+    const int tm = (tile % per_group) / p.tiles_n, tn = tile % p.tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const float* A = p.a + (int64_t)group * p.sa;
+    const float* B = p.b + (int64_t)group * p.sb;
+
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int lane32 = lane % 32, half = lane / 32;
+    const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+
+    f16v acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    f4 ra[TA::kPerThread], rb[TB::kPerThread];
+    const int nk = (p.K + BK - 1) / BK;
+    TA::load(ra, A, p.lda, m0, 0, p.M, p.K);
+    TB::load(rb, B, p.ldb, n0, 0, p.N, p.K);
+    TA::store(lds_a[0], ra);
+    TB::store(lds_b[0], rb);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) {
+            TA::load(ra, A, p.lda, m0, (kt + 1) * BK, p.M, p.K);
+            TB::load(rb, B, p.ldb, n0, (kt + 1) * BK, p.N, p.K);
+        }
+#pragma unroll
+        for (int q = 0; q < BK / 8; ++q) {
+            f4 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = TA::frag(lds_a[cur], wm0 + 32 * i, q, lane32, half);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = TB::frag(lds_b[cur], wn0 + 32 * j, q, lane32, half);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][e], fb[j][e], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) {
+            TA::store(lds_a[cur ^ 1], ra);
+            TB::store(lds_b[cur ^ 1], rb);
+        }
+        __syncthreads();
+    }
+
+    // Epilogue.  Accumulator register r of a lane holds C[row][col] with col = lane % 32 and
+    // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block.
+    float* C = p.c + (int64_t)group * p.sc;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn0 + 32 * j + lane32;
+            if (col >= p.N) continue;
+            float bias = 0.0f;
+            if (MODE == kFwd) bias = p.bias[(int64_t)group * p.sbias + col];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
+                if (row >= p.M) continue;
+                float v = acc[i][j][r];
+                if (MODE == kFwd) v = fmaxf(v + bias, 0.0f);
+                if (MODE == kDa) v = p.mask[(int64_t)group * p.smask + (int64_t)row * p.ldc + col] > 0.0f ? v : 0.0f;
+                C[(int64_t)row * p.ldc + col] = v;
+            }
+        }
+    }
+}
+
+static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
+    if (!g.a || !g.b || !g.c || g.groups < 1 || g.M < 1 || g.N < 1 || g.K < 1) return hipErrorInvalidValue;
+    // 16-byte vector loads: every line start must be aligned and extents multiples of 4
+    if (!aligned16(g.a) || !aligned16(g.b) || g.lda % 4 || g.ldb % 4 || g.sa % 4 || g.sb % 4) return hipErrorInvalidValue;
+    const bool a_kc = MODE != kDw, b_kc = MODE == kDa;
+    if ((a_kc ? g.K : g.M) % 4 || (b_kc ? g.K : g.N) % 4) return hipErrorInvalidValue;
+    if (g.lda < (a_kc ? g.K : g.M) || g.ldb < (b_kc ? g.K : g.N) || g.ldc < g.N) return hipErrorInvalidValue;
+    if (MODE == kFwd && !g.bias) return hipErrorInvalidValue;
+    if (MODE == kDa && !g.mask) return hipErrorInvalidValue;
+    GemmDev p;
+    p.a = (const float*)g.a;
+    p.b = (const float*)g.b;
+    p.c = (float*)g.c;
+    p.bias = g.bias;
+    p.mask = (const float*)g.mask;
+    p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sbias = g.sbias; p.smask = g.smask;
+    p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
+    p.tiles_m = (g.M + BM - 1) / BM;
+    p.tiles_n = (g.N + BN - 1) / BN;
+    const int64_t total = (int64_t)g.groups * p.tiles_m * p.tiles_n;
+    if (total > (1 << 30)) return hipErrorInvalidValue;
+    p.total_tiles = (int)total;
+    p.chunk = (int)((total + kXcds - 1) / kXcds);
+    gemm_f32_kernel<MODE, BM, BN, BK, WAVES_M, WAVES_N><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s) { return gemm_launch<kFwd, 64, 64, 32, 2, 2>(g, s); }
+hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDw, 128, 128, 16, 2, 2>(g, s); }
+hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDa, 64, 64, 32, 2, 2>(g, s); }
+
+}  // namespace ols

@@ -1,0 +1,243 @@
+// Output layer of the per-worker MLP (class count C <= 32) with softmax cross-entropy, its gradients,
+// and the bias-gradient column sums.  The output width is far too small for matrix cores, so these run
+// on the vector ALUs; they are a few MFLOP per worker and latency-bound.
+//
+// Per worker i with last hidden activations h [B][H], weights W [H][C], bias b [C], labels y [B]
+// (the mini-batch loss whose gradient is the g_i of Section 2, arXiv 2002.09539):
+//   logits = h W + b;  loss_s = logsumexp(logits_s) - logits_s[y_s];  dlogits = (softmax - onehot) / B
+//   dW = h^T dlogits;  db = colsum(dlogits);  dz = (dlogits W^T) * [h > 0]
+#include "ols_internal.h"
+
+namespace ols {
+
+constexpr int kThreads = 256;
+constexpr int kWave = 64;
+constexpr int kMaxC = 32;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float(((unsigned int)v) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    unsigned int u = __float_as_uint(f);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+template <bool BF>
+__device__ __forceinline__ float load_act(const void* p, int64_t idx) {
+    return BF ? bf16_to_f32(((const uint16_t*)p)[idx]) : ((const float*)p)[idx];
+}
+
+// one wavefront per sample; grid (ceil(B / 4), m)
+template <bool BF, int CMAX>
+__global__ __launch_bounds__(kThreads) void head_fwd_kernel(const void* __restrict__ h, int64_t h_stride,
+                                                            const float* __restrict__ x, int64_t ld, int64_t w_off,
+                                                            int64_t b_off, const int32_t* __restrict__ labels,
+                                                            int64_t label_stride, float* __restrict__ dlogits,
+                                                            float* __restrict__ loss_parts, int B, int H, int C) {
+    __shared__ float s_logit[kThreads / kWave][kMaxC];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int i = blockIdx.y;
+    const int s = blockIdx.x * (kThreads / kWave) + wave;
+    const bool live = s < B;
+    const float* W = x + (int64_t)i * ld + w_off;
+    float acc[CMAX];
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) acc[c] = 0.0f;
+    if (live) {
+        const int64_t hbase = (int64_t)i * h_stride + (int64_t)s * H;
+        for (int k = lane; k < H; k += kWave) {
+            const float hv = load_act<BF>(h, hbase + k);
+            const float* wr = W + (int64_t)k * C;
+#pragma unroll
+            for (int c = 0; c < CMAX; ++c)
+                if (c < C) acc[c] = __fmaf_rn(hv, wr[c], acc[c]);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) {
+        float v = acc[c];
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+        if (lane == 0) s_logit[wave][c] = v;
+    }
+    __syncthreads();
+    if (!live) return;
+    // lane c owns class c
+    const float logit = lane < C ? s_logit[wave][lane] + x[(int64_t)i * ld + b_off + lane] : -INFINITY;
+    float mx = logit;
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    const float ex = lane < C ? expf(logit - mx) : 0.0f;
+    float sum = ex;
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+    const int label = labels[(int64_t)i * label_stride + s];
+    const float picked = __shfl(logit, label, kWave);
+    if (lane == 0) loss_parts[(int64_t)i * B + s] = (logf(sum) + mx) - picked;
+    if (lane < C) {
+        const float p = ex / sum;
+        dlogits[((int64_t)i * B + s) * C + lane] = (p - (lane == label ? 1.0f : 0.0f)) / (float)B;
+    }
+}
+
+// dW[k][c] = sum_s h[s][k] dlogits[s][c], db[c] = sum_s dlogits[s][c];  grid (ceil(H / 256), m)
+template <bool BF, int CMAX>
+__global__ __launch_bounds__(kThreads) void head_dw_kernel(const void* __restrict__ h, int64_t h_stride,
+                                                           const float* __restrict__ dlogits, float* __restrict__ g,
+                                                           int64_t ld, int64_t w_off, int64_t b_off, int B, int H,
+                                                           int C) {
+    constexpr int kRows = 128;  // samples staged per pass
+    __shared__ float s_dl[kRows * kMaxC];
+    const int i = blockIdx.y;
+    const int k = blockIdx.x * kThreads + threadIdx.x;
+    float acc[CMAX];
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) acc[c] = 0.0f;
+    float bias_acc = 0.0f;
+    for (int s0 = 0; s0 < B; s0 += kRows) {
+        const int rows = min(kRows, B - s0);
+        __syncthreads();
+        for (int t = threadIdx.x; t < rows * C; t += kThreads) s_dl[t] = dlogits[((int64_t)i * B + s0) * C + t];
+        __syncthreads();
+        if (k < H) {
+            for (int s = 0; s < rows; ++s) {
+                const float hv = load_act<BF>(h, (int64_t)i * h_stride + (int64_t)(s0 + s) * H + k);
+#pragma unroll
+                for (int c = 0; c < CMAX; ++c)
+                    if (c < C) acc[c] = __fmaf_rn(hv, s_dl[s * C + c], acc[c]);
+            }
+        }
+        if (blockIdx.x == 0 && threadIdx.x < C)
+            for (int s = 0; s < rows; ++s) bias_acc += s_dl[s * C + threadIdx.x];
+    }
+    if (k < H) {
+        float* out = g + (int64_t)i * ld + w_off + (int64_t)k * C;
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c)
+            if (c < C) out[c] = acc[c];
+    }
+    if (blockIdx.x == 0 && threadIdx.x < C) g[(int64_t)i * ld + b_off + threadIdx.x] = bias_acc;
+}
+
+// dz[s][k] = (sum_c dlogits[s][c] W[k][c]) * [h[s][k] > 0];  grid (ceil(H / 256), ceil(B / ROWS), m)
+template <bool BF, int CMAX, int ROWS>
+__global__ __launch_bounds__(kThreads) void head_dz_kernel(const void* __restrict__ h, int64_t h_stride,
+                                                           const float* __restrict__ x, int64_t ld, int64_t w_off,
+                                                           const float* __restrict__ dlogits, void* __restrict__ dz,
+                                                           void* __restrict__ dz_t, int B, int H, int C) {
+    __shared__ float s_dl[ROWS * kMaxC];
+    const int i = blockIdx.z;
+    const int s0 = blockIdx.y * ROWS;
+    const int rows = min(ROWS, B - s0);
+    for (int t = threadIdx.x; t < rows * C; t += kThreads) s_dl[t] = dlogits[((int64_t)i * B + s0) * C + t];
+    __syncthreads();
+    const int k = blockIdx.x * kThreads + threadIdx.x;
+    if (k >= H) return;
+    float w[CMAX];
+    const float* wr = x + (int64_t)i * ld + w_off + (int64_t)k * C;
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) w[c] = c < C ? wr[c] : 0.0f;
+    uint16_t tr[ROWS];
+#pragma unroll
+    for (int s = 0; s < ROWS; ++s) {
+        tr[s] = 0;
+        if (s < rows) {
+            const int64_t idx = (int64_t)(s0 + s) * H + k;
+            float acc = 0.0f;
+#pragma unroll
+            for (int c = 0; c < CMAX; ++c)
+                if (c < C) acc = __fmaf_rn(s_dl[s * C + c], w[c], acc);
+            const float hv = load_act<BF>(h, (int64_t)i * h_stride + idx);
+            const float v = hv > 0.0f ? acc : 0.0f;
+            if (BF) {
+                tr[s] = f32_to_bf16(v);
+                ((uint16_t*)dz)[(int64_t)i * B * H + idx] = tr[s];
+            } else {
+                ((float*)dz)[(int64_t)i * B * H + idx] = v;
+            }
+        }
+    }
+    if (BF && dz_t) {  // transposed copy [H][B]: ROWS consecutive samples of column k
+        uint16_t* o = (uint16_t*)dz_t + (int64_t)i * B * H + (int64_t)k * B + s0;
+        if (rows == ROWS && ROWS == 8) {
+            typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+            u4 pk;
+            pk.x = tr[0] | ((unsigned)tr[1] << 16);
+            pk.y = tr[2] | ((unsigned)tr[3] << 16);
+            pk.z = tr[4] | ((unsigned)tr[5] << 16);
+            pk.w = tr[6] | ((unsigned)tr[7] << 16);
+            *(u4*)o = pk;
+        } else {
+            for (int s = 0; s < rows; ++s) o[s] = tr[s];
+        }
+    }
+}
+
+// g[b_off + n] = sum_s dz[s][n];  grid (ceil(N / 256), m)
+template <bool BF>
+__global__ __launch_bounds__(kThreads) void bias_grad_kernel(const void* __restrict__ dz, int64_t dz_stride,
+                                                             float* __restrict__ g, int64_t ld, int64_t b_off, int B,
+                                                             int N) {
+    const int i = blockIdx.y;
+    const int n = blockIdx.x * kThreads + threadIdx.x;
+    if (n >= N) return;
+    float acc = 0.0f;
+    for (int s = 0; s < B; ++s) acc += load_act<BF>(dz, (int64_t)i * dz_stride + (int64_t)s * N + n);
+    g[(int64_t)i * ld + b_off + n] = acc;
+}
+
+static bool head_args_ok(const HeadArgs& a) {
+    return a.h && a.x && a.g && a.labels && a.dlogits && a.loss_parts && a.m >= 1 && a.m <= 65535 && a.B >= 1 &&
+           a.H >= 1 && a.C >= 1 && a.C <= kMaxC && a.w_off >= 0 && a.b_off >= 0 &&
+           a.w_off + (int64_t)a.H * a.C <= a.ld && a.b_off + a.C <= a.ld;
+}
+
+hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
+    if (!head_args_ok(a)) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((a.B + 3) / 4), (unsigned)a.m);
+#define OLS_HEAD_FWD(BF, CM)                                                                                       \
+    head_fwd_kernel<BF, CM><<<grid, kThreads, 0, s>>>(a.h, a.h_stride, a.x, a.ld, a.w_off, a.b_off, a.labels,      \
+                                                      a.label_stride, a.dlogits, a.loss_parts, a.B, a.H, a.C)
+    if (a.h_bf16) {
+        if (a.C <= 16) OLS_HEAD_FWD(true, 16); else OLS_HEAD_FWD(true, 32);
+    } else {
+        if (a.C <= 16) OLS_HEAD_FWD(false, 16); else OLS_HEAD_FWD(false, 32);
+    }
+#undef OLS_HEAD_FWD
+    return hipGetLastError();
+}
+
+hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s) {
+    if (!head_args_ok(a)) return hipErrorInvalidValue;
+    dim3 grid_w((unsigned)((a.H + kThreads - 1) / kThreads), (unsigned)a.m);
+#define OLS_HEAD_DW(BF, CM)                                                                                        \
+    head_dw_kernel<BF, CM><<<grid_w, kThreads, 0, s>>>(a.h, a.h_stride, a.dlogits, a.g, a.ld, a.w_off, a.b_off,    \
+                                                       a.B, a.H, a.C)
+    if (a.h_bf16) {
+        if (a.C <= 16) OLS_HEAD_DW(true, 16); else OLS_HEAD_DW(true, 32);
+    } else {
+        if (a.C <= 16) OLS_HEAD_DW(false, 16); else OLS_HEAD_DW(false, 32);
+    }
+#undef OLS_HEAD_DW
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !a.dz) return e;
+    constexpr int kRows = 8;
+    const unsigned by = (unsigned)((a.B + kRows - 1) / kRows);
+    if (by > 65535u || a.m > 65535) return hipErrorInvalidValue;
+    dim3 grid_z((unsigned)((a.H + kThreads - 1) / kThreads), by, (unsigned)a.m);
+#define OLS_HEAD_DZ(BF, CM)                                                                                        \
+    head_dz_kernel<BF, CM, kRows><<<grid_z, kThreads, 0, s>>>(a.h, a.h_stride, a.x, a.ld, a.w_off, a.dlogits,      \
+                                                              a.dz, a.dz_t, a.B, a.H, a.C)
+    if (a.h_bf16) {
+        if (a.C <= 16) OLS_HEAD_DZ(true, 16); else OLS_HEAD_DZ(true, 32);
+    } else {
+        if (a.C <= 16) OLS_HEAD_DZ(false, 16); else OLS_HEAD_DZ(false, 32);
+    }
+#undef OLS_HEAD_DZ
+    return hipGetLastError();
+}
+
+hipError_t launch_bias_grad(const void* dz, bool dz_bf16, int64_t dz_stride, float* g, int64_t ld, int64_t b_off,
+                            int m, int B, int N, hipStream_t s) {
+    if (!dz || !g || m < 1 || m > 65535 || B < 1 || N < 1 || b_off < 0 || b_off + N > ld) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((N + kThreads - 1) / kThreads), (unsigned)m);
+    if (dz_bf16) bias_grad_kernel<true><<<grid, kThreads, 0, s>>>(dz, dz_stride, g, ld, b_off, B, N);
+    else bias_grad_kernel<false><<<grid, kThreads, 0, s>>>(dz, dz_stride, g, ld, b_off, B, N);
+    return hipGetLastError();
+}
+
+}  // namespace ols

@@ -1,0 +1,837 @@
+// C boundary and schedule of the Overlap Local-SGD hot path (arXiv 2002.09539, Section 2).
+//
+// The host side here only orders kernels on two caller-owned streams and checks the call order the
+// algorithm prescribes; every arithmetic step runs in the kernels of the other translation units.
+//
+// Overlap (the paper's timeline figure, carried out inside one GPU): after the pull-back at the end of
+// round a the main stream records `ev_pulled`; the side stream waits for it, reduces the replica axis
+// into the anchor and records `ev_anchor_done`; the main stream waits for that event only before the
+// NEXT pull-back, which is the first consumer of the refreshed anchor.  The refresh must see the
+// round-boundary models while the next round already updates them, so the first update after a refresh
+// is written out-of-place into the second replica buffer (same HBM traffic) and the buffers swap roles;
+// without a second buffer that first update waits for the refresh instead.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "ols_internal.h"
+
+using namespace ols;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+const char* kKernelNames[OLS_K_COUNT] = {
+    "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
+    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "bias_grad",      "cast_bf16"};
+
+enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2 };
+
+struct TimedLaunch {
+    int kind;
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct ols_ctx {
+    // problem
+    int m = 0, tau = 1;
+    int64_t d = 0, ld = 0;
+    float alpha = 0, gamma = 0, mu = 0, beta_z = 0;
+    // bound state
+    float* x[2] = {nullptr, nullptr};
+    int cur = 0;
+    float *buf = nullptr, *g = nullptr, *z = nullptr, *v = nullptr;
+    hipStream_t stream[2] = {nullptr, nullptr};
+    bool bound = false, inited = false, launched = false;
+    // options
+    bool nesterov = true, fuse_pull = true, serialize = false, dry = false, timing = false, trace = false,
+         fuse_mean = false;
+    int mean_split = 0;
+    // schedule
+    int64_t k = 0;
+    bool pull_due = false, pending_update = false, anchor_due = false, anchor_inflight = false,
+         first_after_anchor = false, anchor_precomputed = false, next_waited = false;
+    hipEvent_t ev_pulled = nullptr, ev_anchor_done = nullptr;
+    // model
+    int model = MODEL_NONE, B = 0, gemm_dtype = 0;
+    std::vector<int> dims;
+    std::vector<int64_t> w_off, b_off;
+    char* ws = nullptr;
+    int64_t ws_bytes = 0, ws_need = 0;
+    // workspace sub-buffers (byte offsets)
+    std::vector<int64_t> off_act, off_act_t, off_dz, off_dz_t;
+    int64_t off_dlogits = 0, off_loss = 0, off_resid = 0, off_shadow = 0, off_x0 = 0, off_x0_t = 0;
+    const float* X = nullptr;
+    const void* y = nullptr;
+    int64_t xs = 0, ys = 0;
+    bool batch_set = false;
+    // instrumentation
+    std::vector<TimedLaunch> timed;
+    std::vector<hipEvent_t> event_pool;
+    int64_t stat_count[OLS_K_COUNT] = {0};
+    double stat_ms[OLS_K_COUNT] = {0};
+    std::vector<ols_trace_entry> trace_log;
+};
+
+namespace {
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(OLS_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int ensure_events(ols_ctx* c) {
+    if (c->ev_pulled || c->dry) return OLS_OK;
+    hipError_t e = hipEventCreateWithFlags(&c->ev_pulled, hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+    e = hipEventCreateWithFlags(&c->ev_anchor_done, hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+    return OLS_OK;
+}
+
+int drain_timers(ols_ctx* c) {
+    for (TimedLaunch& t : c->timed) {
+        hipError_t e = hipEventSynchronize(t.stop);
+        if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+        float ms = 0.0f;
+        e = hipEventElapsedTime(&ms, t.start, t.stop);
+        if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        c->stat_count[t.kind] += 1;
+        c->stat_ms[t.kind] += ms;
+        c->event_pool.push_back(t.start);
+        c->event_pool.push_back(t.stop);
+    }
+    c->timed.clear();
+    return OLS_OK;
+}
+
+int get_timer_event(ols_ctx* c, hipEvent_t* ev) {
+    if (!c->event_pool.empty()) {
+        *ev = c->event_pool.back();
+        c->event_pool.pop_back();
+        return OLS_OK;
+    }
+    hipError_t e = hipEventCreate(ev);
+    if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+    return OLS_OK;
+}
+
+// Enqueue one kernel: trace entry, optional event bracket on the kernel's own stream, launch.
+template <class F>
+int enqueue(ols_ctx* c, int kind, int stream_id, int src_buf, int dst_buf, F&& launch) {
+    if (c->trace && c->trace_log.size() < 65536) {
+        ols_trace_entry t;
+        t.kind = kind;
+        t.stream = stream_id;
+        t.src_buf = src_buf;
+        t.dst_buf = dst_buf;
+        t.waited = c->next_waited ? 1 : 0;
+        t.k = (int32_t)c->k;
+        c->trace_log.push_back(t);
+    }
+    c->next_waited = false;
+    if (c->dry) return OLS_OK;
+    hipStream_t s = c->stream[stream_id];
+    TimedLaunch t;
+    if (c->timing) {
+        if (c->timed.size() >= 8192) {
+            int rc = drain_timers(c);
+            if (rc) return rc;
+        }
+        t.kind = kind;
+        int rc = get_timer_event(c, &t.start);
+        if (rc) return rc;
+        rc = get_timer_event(c, &t.stop);
+        if (rc) return rc;
+        hipError_t e = hipEventRecord(t.start, s);
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+    }
+    hipError_t e = launch(s);
+    c->launched = true;
+    if (e != hipSuccess) return fail(OLS_EHIP, "launch of %s failed: %s", kKernelNames[kind], hipGetErrorString(e));
+    if (c->timing) {
+        e = hipEventRecord(t.stop, s);
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+        c->timed.push_back(t);
+    }
+    return OLS_OK;
+}
+
+// The main stream must not pass this point before the in-flight anchor refresh has finished.
+int main_waits_for_anchor(ols_ctx* c) {
+    if (!c->anchor_inflight) return OLS_OK;
+    c->anchor_inflight = false;
+    c->next_waited = true;
+    if (c->dry) return OLS_OK;
+    hipError_t e = hipStreamWaitEvent(c->stream[0], c->ev_anchor_done, 0);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent");
+    return OLS_OK;
+}
+
+int64_t align256(int64_t v) { return round_up(v, 256); }
+
+uint16_t* shadow_ptr(ols_ctx* c) {
+    return (c->model == MODEL_MLP && c->gemm_dtype == 1 && c->ws) ? (uint16_t*)(c->ws + c->off_shadow) : nullptr;
+}
+
+void plan_workspace(ols_ctx* c) {
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        int64_t o = off;
+        off = align256(off + bytes);
+        return o;
+    };
+    const int64_t m = c->m, B = c->B;
+    c->off_act.clear();
+    c->off_act_t.clear();
+    c->off_dz.clear();
+    c->off_dz_t.clear();
+    if (c->model == MODEL_LSQ) {
+        c->off_resid = take(m * B * 4);
+        c->off_loss = take(m * B * 4);
+    } else if (c->model == MODEL_MLP) {
+        const int L = (int)c->dims.size() - 1;
+        const bool bf = c->gemm_dtype == 1;
+        const int64_t es = bf ? 2 : 4;
+        c->off_act.assign(L, 0);
+        c->off_act_t.assign(L, 0);
+        c->off_dz.assign(L, 0);
+        c->off_dz_t.assign(L, 0);
+        for (int l = 1; l < L; ++l) {  // hidden activations a_l and deltas dz_l, [m][B][dims[l]]
+            c->off_act[l] = take(m * B * c->dims[l] * es);
+            c->off_dz[l] = take(m * B * c->dims[l] * es);
+            if (bf) {
+                c->off_act_t[l] = take(m * B * c->dims[l] * es);
+                c->off_dz_t[l] = take(m * B * c->dims[l] * es);
+            }
+        }
+        if (bf) {
+            c->off_x0 = take(m * B * c->dims[0] * 2);
+            c->off_x0_t = take(m * B * c->dims[0] * 2);
+            c->off_shadow = take(m * c->ld * 2);
+        }
+        c->off_dlogits = take(m * B * c->dims[L] * 4);
+        c->off_loss = take(m * B * 4);
+    }
+    c->ws_need = off;
+}
+
+// Forward + backward of the attached model into g, on the main stream.
+int compute_gradients(ols_ctx* c) {
+    const float* xc = c->x[c->cur];
+    const int m = c->m, B = c->B;
+    if (c->model == MODEL_LSQ) {
+        float* resid = (float*)(c->ws + c->off_resid);
+        float* loss = (float*)(c->ws + c->off_loss);
+        int rc = enqueue(c, OLS_K_LSQ_RESID, 0, c->cur, -1, [&](hipStream_t s) {
+            return launch_lsq_resid(c->X, c->xs, (const float*)c->y, c->ys, xc, c->ld, resid, loss, m, B, c->d, s);
+        });
+        if (rc) return rc;
+        return enqueue(c, OLS_K_LSQ_GRAD, 0, c->cur, -1,
+                       [&](hipStream_t s) { return launch_lsq_grad(c->X, c->xs, resid, c->g, c->ld, m, B, c->d, s); });
+    }
+    if (c->model != MODEL_MLP) return OLS_OK;
+
+    const int L = (int)c->dims.size() - 1;
+    const bool bf = c->gemm_dtype == 1;
+    const int64_t es = bf ? 2 : 4;
+    const uint16_t* shadow = shadow_ptr(c);
+    auto act = [&](int l) -> const void* { return l == 0 ? (bf ? (const void*)(c->ws + c->off_x0) : (const void*)c->X)
+                                                          : (const void*)(c->ws + c->off_act[l]); };
+    auto act_stride = [&](int l) -> int64_t { return (l == 0 && !bf) ? c->xs : (int64_t)B * c->dims[l]; };
+    auto act_t = [&](int l) -> const void* { return l == 0 ? (const void*)(c->ws + c->off_x0_t)
+                                                            : (const void*)(c->ws + c->off_act_t[l]); };
+    (void)es;
+    int rc;
+    if (bf) {
+        rc = enqueue(c, OLS_K_CAST, 0, -1, -1, [&](hipStream_t s) {
+            return launch_cast_bf16(c->X, c->xs, (uint16_t*)(c->ws + c->off_x0), (uint16_t*)(c->ws + c->off_x0_t), m, B,
+                                    c->dims[0], s);
+        });
+        if (rc) return rc;
+    }
+    // hidden layers forward
+    for (int l = 0; l < L - 1; ++l) {
+        GemmArgs ga = {};
+        ga.a = act(l);
+        ga.sa = act_stride(l);
+        ga.lda = c->dims[l];
+        ga.b = bf ? (const void*)(shadow + c->w_off[l]) : (const void*)(xc + c->w_off[l]);
+        ga.sb = c->ld;
+        ga.ldb = c->dims[l + 1];
+        ga.c = c->ws + c->off_act[l + 1];
+        ga.sc = (int64_t)B * c->dims[l + 1];
+        ga.ldc = c->dims[l + 1];
+        ga.c_t = bf ? (void*)(c->ws + c->off_act_t[l + 1]) : nullptr;
+        ga.sct = ga.sc;
+        ga.bias = xc + c->b_off[l];
+        ga.sbias = c->ld;
+        ga.groups = m;
+        ga.M = B;
+        ga.N = c->dims[l + 1];
+        ga.K = c->dims[l];
+        rc = enqueue(c, OLS_K_GEMM_FWD, 0, c->cur, -1,
+                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_fwd(ga, s) : launch_gemm_f32_fwd(ga, s); });
+        if (rc) return rc;
+    }
+    // output layer, loss, and its gradients
+    HeadArgs ha = {};
+    ha.h = act(L - 1);
+    ha.h_stride = act_stride(L - 1);
+    ha.h_bf16 = bf;
+    ha.x = xc;
+    ha.g = c->g;
+    ha.ld = c->ld;
+    ha.w_off = c->w_off[L - 1];
+    ha.b_off = c->b_off[L - 1];
+    ha.labels = (const int32_t*)c->y;
+    ha.label_stride = c->ys;
+    ha.dlogits = (float*)(c->ws + c->off_dlogits);
+    ha.loss_parts = (float*)(c->ws + c->off_loss);
+    ha.dz = L > 1 ? (void*)(c->ws + c->off_dz[L - 1]) : nullptr;
+    ha.dz_t = (L > 1 && bf) ? (void*)(c->ws + c->off_dz_t[L - 1]) : nullptr;
+    ha.m = m;
+    ha.B = B;
+    ha.H = c->dims[L - 1];
+    ha.C = c->dims[L];
+    rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); });
+    if (rc) return rc;
+    rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); });
+    if (rc) return rc;
+    // hidden layers backward
+    for (int l = L - 2; l >= 0; --l) {
+        const void* dz = c->ws + c->off_dz[l + 1];
+        const int64_t dz_stride = (int64_t)B * c->dims[l + 1];
+        GemmArgs gw = {};
+        if (bf) {  // contraction over the batch wants batch-contiguous operands: the transposed copies
+            gw.a = act_t(l);
+            gw.sa = (int64_t)B * c->dims[l];
+            gw.lda = B;
+            gw.b = c->ws + c->off_dz_t[l + 1];
+            gw.sb = dz_stride;
+            gw.ldb = B;
+        } else {
+            gw.a = act(l);
+            gw.sa = act_stride(l);
+            gw.lda = c->dims[l];
+            gw.b = dz;
+            gw.sb = dz_stride;
+            gw.ldb = c->dims[l + 1];
+        }
+        gw.c = c->g + c->w_off[l];
+        gw.sc = c->ld;
+        gw.ldc = c->dims[l + 1];
+        gw.groups = m;
+        gw.M = c->dims[l];
+        gw.N = c->dims[l + 1];
+        gw.K = B;
+        rc = enqueue(c, OLS_K_GEMM_DW, 0, -1, -1,
+                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s) : launch_gemm_f32_dw(gw, s); });
+        if (rc) return rc;
+        rc = enqueue(c, OLS_K_BIAS_GRAD, 0, -1, -1, [&](hipStream_t s) {
+            return launch_bias_grad(dz, bf, dz_stride, c->g, c->ld, c->b_off[l], m, B, c->dims[l + 1], s);
+        });
+        if (rc) return rc;
+        if (l > 0) {
+            GemmArgs gd = {};
+            gd.a = dz;
+            gd.sa = dz_stride;
+            gd.lda = c->dims[l + 1];
+            gd.b = bf ? (const void*)(shadow + c->w_off[l]) : (const void*)(xc + c->w_off[l]);
+            gd.sb = c->ld;
+            gd.ldb = c->dims[l + 1];
+            gd.mask = act(l);
+            gd.smask = act_stride(l);
+            gd.c = c->ws + c->off_dz[l];
+            gd.sc = (int64_t)B * c->dims[l];
+            gd.ldc = c->dims[l];
+            gd.c_t = bf ? (void*)(c->ws + c->off_dz_t[l]) : nullptr;
+            gd.sct = gd.sc;
+            gd.groups = m;
+            gd.M = B;
+            gd.N = c->dims[l];
+            gd.K = c->dims[l + 1];
+            rc = enqueue(c, OLS_K_GEMM_DA, 0, c->cur, -1,
+                         [&](hipStream_t s) { return bf ? launch_gemm_bf16_da(gd, s) : launch_gemm_f32_da(gd, s); });
+            if (rc) return rc;
+        }
+    }
+    return OLS_OK;
+}
+
+UpdateArgs update_args(ols_ctx* c, int src, int dst, bool pull) {
+    UpdateArgs u = {};
+    u.g = c->g;
+    u.x_in = c->x[src];
+    u.x_out = c->x[dst];
+    u.buf = c->mu != 0.0f ? c->buf : nullptr;
+    u.z = c->z;
+    u.shadow = shadow_ptr(c);
+    u.m = c->m;
+    u.ld = c->ld;
+    u.gamma = c->gamma;
+    u.mu = c->mu;
+    u.alpha = c->alpha;
+    u.nesterov = c->nesterov;
+    u.pull = pull;
+    return u;
+}
+
+// Chooses source / destination replica buffers for an update that rewrites the parameters.
+int pick_buffers(ols_ctx* c, int* src, int* dst) {
+    *src = c->cur;
+    *dst = c->cur;
+    if (c->first_after_anchor) {
+        c->first_after_anchor = false;
+        if (c->x[1] && !c->serialize) {
+            *dst = 1 - c->cur;  // the side stream may still be reading x[cur]
+        } else {
+            int rc = main_waits_for_anchor(c);  // in-place write must not overtake the refresh
+            if (rc) return rc;
+        }
+    }
+    return OLS_OK;
+}
+
+int need(ols_ctx* c) {
+    if (!c) return fail(OLS_EINVAL, "null handle");
+    return OLS_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* ols_last_error(void) { return g_err; }
+const char* ols_version(void) { return "ols 0.1 (gfx950)"; }
+const char* ols_kernel_name(int kind) { return (kind >= 0 && kind < OLS_K_COUNT) ? kKernelNames[kind] : "?"; }
+int64_t ols_row_stride(int64_t d) { return d < 1 ? 0 : round_up(d, 64); }
+
+ols_handle ols_create(int m, int64_t d, int tau, float alpha, float gamma, float beta) {
+    if (m < 1 || m > 4096) return fail(OLS_EINVAL, "m must be in [1, 4096], got %d", m), nullptr;
+    if (d < 1) return fail(OLS_EINVAL, "d must be >= 1"), nullptr;
+    if (tau < 1) return fail(OLS_EINVAL, "tau must be >= 1, got %d", tau), nullptr;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return fail(OLS_EINVAL, "alpha must be in [0, 1]"), nullptr;
+    if (!(gamma > 0.0f)) return fail(OLS_EINVAL, "gamma must be > 0"), nullptr;
+    if (!(beta >= 0.0f && beta < 1.0f)) return fail(OLS_EINVAL, "beta (local momentum) must be in [0, 1)"), nullptr;
+    ols_ctx* c = new ols_ctx();
+    c->m = m;
+    c->d = d;
+    c->ld = ols_row_stride(d);
+    c->tau = tau;
+    c->alpha = alpha;
+    c->gamma = gamma;
+    c->mu = beta;
+    return c;
+}
+
+int ols_destroy(ols_handle c) {
+    if (!c) return OLS_OK;
+    if (c->launched) {
+        (void)hipStreamSynchronize(c->stream[0]);
+        (void)hipStreamSynchronize(c->stream[1]);
+    }
+    for (TimedLaunch& t : c->timed) {
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
+    for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
+    if (c->ev_pulled) (void)hipEventDestroy(c->ev_pulled);
+    if (c->ev_anchor_done) (void)hipEventDestroy(c->ev_anchor_done);
+    delete c;
+    return OLS_OK;
+}
+
+int ols_bind(ols_handle c, float* x, float* x_alt, float* buf, float* g, float* z, int64_t ld, void* main_stream,
+             void* side_stream) {
+    if (int rc = need(c)) return rc;
+    if (!x || !g || !z) return fail(OLS_EINVAL, "x, g and z must be non-null");
+    if (c->mu != 0.0f && !buf) return fail(OLS_EINVAL, "buf is required when the local momentum is non-zero");
+    if (ld != c->ld) return fail(OLS_EINVAL, "ld must be ols_row_stride(d) = %lld, got %lld", (long long)c->ld,
+                                 (long long)ld);
+    const void* ptrs[] = {x, x_alt, buf, g, z};
+    for (const void* p : ptrs)
+        if (reinterpret_cast<uintptr_t>(p) & 255u) return fail(OLS_EINVAL, "device pointers must be 256-byte aligned");
+    if (x_alt == x) return fail(OLS_EINVAL, "x_alt must differ from x");
+    c->x[0] = x;
+    c->x[1] = x_alt;
+    c->cur = 0;
+    c->buf = buf;
+    c->g = g;
+    c->z = z;
+    c->stream[0] = (hipStream_t)main_stream;
+    c->stream[1] = (hipStream_t)side_stream;
+    c->bound = true;
+    c->inited = false;
+    return OLS_OK;
+}
+
+int ols_init_params(ols_handle c, const float* x0) {
+    if (int rc = need(c)) return rc;
+    if (!c->bound) return fail(OLS_ESTATE, "ols_bind must precede ols_init_params");
+    if (!x0) return fail(OLS_EINVAL, "x0 is null");
+    if (c->model == MODEL_MLP && c->gemm_dtype == 1 && !c->ws)
+        return fail(OLS_ESTATE, "with bf16 GEMMs the workspace (it holds the bf16 weights) is bound before ols_init_params");
+    if (int rc = ensure_events(c)) return rc;
+    if (c->launched && !c->dry) {  // re-initialisation: nothing may still be reading the old state
+        (void)hipStreamSynchronize(c->stream[0]);
+        (void)hipStreamSynchronize(c->stream[1]);
+    }
+    c->cur = 0;
+    int rc = enqueue(c, OLS_K_INIT, 0, -1, 0, [&](hipStream_t s) {
+        return launch_init(c->x[0], c->x[1], c->buf, c->z, shadow_ptr(c), x0, c->m, c->d, c->ld, s);
+    });
+    if (rc) return rc;
+    c->k = 0;
+    c->pull_due = c->pending_update = c->anchor_due = c->anchor_inflight = c->first_after_anchor = false;
+    c->anchor_precomputed = false;
+    c->inited = true;
+    return OLS_OK;
+}
+
+int ols_set_anchor_momentum(ols_handle c, float beta_z, float* v) {
+    if (int rc = need(c)) return rc;
+    if (c->k != 0) return fail(OLS_ESTATE, "anchor momentum must be set before the first local step");
+    if (!(beta_z >= 0.0f && beta_z < 1.0f)) return fail(OLS_EINVAL, "beta_z must be in [0, 1)");
+    if (beta_z != 0.0f && !v) return fail(OLS_EINVAL, "v is required when beta_z is non-zero");
+    if (reinterpret_cast<uintptr_t>(v) & 255u) return fail(OLS_EINVAL, "v must be 256-byte aligned");
+    c->beta_z = beta_z;
+    c->v = beta_z != 0.0f ? v : nullptr;
+    return OLS_OK;
+}
+
+int ols_set_lr(ols_handle c, float gamma) {
+    if (int rc = need(c)) return rc;
+    if (!(gamma > 0.0f)) return fail(OLS_EINVAL, "gamma must be > 0");
+    if (c->pending_update) return fail(OLS_ESTATE, "a deferred local step is pending; call ols_sync_pull first");
+    c->gamma = gamma;
+    return OLS_OK;
+}
+
+int ols_attach_lsq(ols_handle c, int batch) {
+    if (int rc = need(c)) return rc;
+    if (batch < 1 || batch > 8192) return fail(OLS_EINVAL, "batch must be in [1, 8192]");
+    if (c->k != 0) return fail(OLS_ESTATE, "models are attached before the first local step");
+    c->model = MODEL_LSQ;
+    c->B = batch;
+    c->ws = nullptr;
+    c->batch_set = false;
+    plan_workspace(c);
+    return OLS_OK;
+}
+
+int ols_attach_mlp(ols_handle c, int n_layers, const int* dims, int batch, int gemm_dtype) {
+    if (int rc = need(c)) return rc;
+    if (c->k != 0) return fail(OLS_ESTATE, "models are attached before the first local step");
+    if (n_layers < 1 || n_layers > 64 || !dims) return fail(OLS_EINVAL, "n_layers must be in [1, 64]");
+    if (gemm_dtype != 0 && gemm_dtype != 1) return fail(OLS_EINVAL, "gemm_dtype must be 0 (fp32) or 1 (bf16)");
+    if (gemm_dtype == 1 && c->inited)
+        return fail(OLS_ESTATE, "a bf16 model is attached (and its workspace bound) before ols_init_params");
+    if (batch < 4 || batch % 4 != 0 || batch > 65536) return fail(OLS_EINVAL, "batch must be a multiple of 4 in [4, 65536]");
+    int64_t total = 0;
+    for (int l = 0; l <= n_layers; ++l) {
+        if (dims[l] < 1) return fail(OLS_EINVAL, "dims[%d] must be >= 1", l);
+        if (l < n_layers && dims[l] % 4 != 0) return fail(OLS_EINVAL, "dims[%d] = %d must be a multiple of 4", l, dims[l]);
+        if (l < n_layers && gemm_dtype == 1 && dims[l] % 8 != 0)
+            return fail(OLS_EINVAL, "bf16 GEMMs need dims[%d] = %d to be a multiple of 8", l, dims[l]);
+    }
+    if (gemm_dtype == 1 && batch % 8 != 0) return fail(OLS_EINVAL, "bf16 GEMMs need the batch to be a multiple of 8");
+    if (dims[n_layers] > 32) return fail(OLS_EINVAL, "the class count must be <= 32, got %d", dims[n_layers]);
+    std::vector<int64_t> w_off(n_layers), b_off(n_layers);
+    for (int l = 0; l < n_layers; ++l) {
+        w_off[l] = total;
+        total += (int64_t)dims[l] * dims[l + 1];
+        b_off[l] = total;
+        total += dims[l + 1];
+    }
+    if (total != c->d) return fail(OLS_EINVAL, "layer sizes give %lld parameters but d = %lld", (long long)total,
+                                   (long long)c->d);
+    c->model = MODEL_MLP;
+    c->B = batch;
+    c->gemm_dtype = gemm_dtype;
+    c->dims.assign(dims, dims + n_layers + 1);
+    c->w_off = w_off;
+    c->b_off = b_off;
+    c->ws = nullptr;
+    c->batch_set = false;
+    plan_workspace(c);
+    return OLS_OK;
+}
+
+int64_t ols_workspace_bytes(ols_handle c) { return c ? c->ws_need : 0; }
+
+int ols_bind_workspace(ols_handle c, void* ws, int64_t bytes) {
+    if (int rc = need(c)) return rc;
+    if (c->model == MODEL_NONE) return fail(OLS_ESTATE, "no model attached");
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return fail(OLS_EINVAL, "workspace must be non-null and 256-byte aligned");
+    if (bytes < c->ws_need) return fail(OLS_ENOMEM, "workspace has %lld bytes, %lld needed", (long long)bytes,
+                                        (long long)c->ws_need);
+    if (c->inited && c->model == MODEL_MLP && c->gemm_dtype == 1)
+        return fail(OLS_ESTATE, "with bf16 GEMMs the workspace (it holds the bf16 weights) is bound before ols_init_params");
+    c->ws = (char*)ws;
+    c->ws_bytes = bytes;
+    return OLS_OK;
+}
+
+int ols_set_batch(ols_handle c, const float* X, int64_t x_worker_stride, const void* y, int64_t y_worker_stride) {
+    if (int rc = need(c)) return rc;
+    if (c->model == MODEL_NONE) return fail(OLS_ESTATE, "no model attached");
+    if (!X || !y) return fail(OLS_EINVAL, "X and y must be non-null");
+    if ((reinterpret_cast<uintptr_t>(X) & 15u) || (x_worker_stride % 4) != 0)
+        return fail(OLS_EINVAL, "X must be 16-byte aligned with a worker stride that is a multiple of 4 elements");
+    const int64_t row = c->model == MODEL_LSQ ? c->d : (int64_t)c->dims[0];
+    if (x_worker_stride < (int64_t)c->B * row && c->m > 1 && x_worker_stride != 0)
+        return fail(OLS_EINVAL, "x_worker_stride %lld is smaller than one batch (%lld elements)",
+                    (long long)x_worker_stride, (long long)(c->B * row));
+    if (y_worker_stride < c->B && c->m > 1 && y_worker_stride != 0)
+        return fail(OLS_EINVAL, "y_worker_stride is smaller than one batch");
+    c->X = X;
+    c->xs = x_worker_stride;
+    c->y = y;
+    c->ys = y_worker_stride;
+    c->batch_set = true;
+    return OLS_OK;
+}
+
+int ols_set_gradient(ols_handle c, float* g) {
+    if (int rc = need(c)) return rc;
+    if (c->model != MODEL_NONE) return fail(OLS_ESTATE, "the attached model writes the gradients itself");
+    if (!g || (reinterpret_cast<uintptr_t>(g) & 255u)) return fail(OLS_EINVAL, "g must be non-null and 256-byte aligned");
+    if (c->pending_update) return fail(OLS_ESTATE, "a deferred local step still needs the current gradients");
+    c->g = g;
+    return OLS_OK;
+}
+
+int ols_local_step(ols_handle c) {
+    if (int rc = need(c)) return rc;
+    if (!c->bound || !c->inited) return fail(OLS_ESTATE, "ols_bind and ols_init_params must precede ols_local_step");
+    if (c->pull_due) return fail(OLS_ESTATE, "k = %lld is a multiple of tau: ols_sync_pull is due", (long long)c->k);
+    if (c->anchor_due) return fail(OLS_ESTATE, "ols_anchor_update_async is due after the pull");
+    if (c->model != MODEL_NONE) {
+        if (!c->ws) return fail(OLS_ESTATE, "the attached model needs ols_bind_workspace");
+        if (!c->batch_set) return fail(OLS_ESTATE, "the attached model needs ols_set_batch");
+    }
+    if (int rc = compute_gradients(c)) return rc;
+    c->k += 1;
+    const bool boundary = c->k % c->tau == 0;
+    if (boundary && c->fuse_pull) {
+        c->pending_update = true;  // applied together with the pull-back in one pass
+        c->pull_due = true;
+        return OLS_OK;
+    }
+    int src, dst;
+    if (int rc = pick_buffers(c, &src, &dst)) return rc;
+    UpdateArgs u = update_args(c, src, dst, false);
+    int rc = enqueue(c, OLS_K_STEP, 0, src, dst, [&](hipStream_t s) { return launch_step(u, s); });
+    if (rc) return rc;
+    c->cur = dst;
+    if (boundary) c->pull_due = true;
+    return OLS_OK;
+}
+
+int ols_sync_pull(ols_handle c) {
+    if (int rc = need(c)) return rc;
+    if (!c->pull_due) return fail(OLS_ESTATE, "no pull is due at k = %lld (tau = %d)", (long long)c->k, c->tau);
+    // the anchor about to be read is the one the previous round's refresh produces
+    if (int rc = main_waits_for_anchor(c)) return rc;
+    int src = c->cur, dst = c->cur;
+    if (c->first_after_anchor) {  // only when tau == 1: nothing was written since the refresh, which has now finished
+        c->first_after_anchor = false;
+    }
+    int rc;
+    if (c->fuse_mean && !shadow_ptr(c)) {
+        StepPullMeanArgs a = {};
+        a.u = update_args(c, src, dst, true);
+        a.z_out = c->z;
+        a.v = c->v;
+        a.beta_z = c->beta_z;
+        a.with_step = c->pending_update;
+        rc = enqueue(c, OLS_K_STEP_PULL_MEAN, 0, src, dst, [&](hipStream_t s) { return launch_step_pull_mean(a, s); });
+        c->anchor_precomputed = true;
+    } else if (c->pending_update) {
+        UpdateArgs u = update_args(c, src, dst, true);
+        rc = enqueue(c, OLS_K_STEP_PULL, 0, src, dst, [&](hipStream_t s) { return launch_step(u, s); });
+    } else {
+        rc = enqueue(c, OLS_K_PULL, 0, src, dst, [&](hipStream_t s) {
+            return launch_pull(c->x[c->cur], c->z, shadow_ptr(c), c->m, c->ld, c->alpha, s);
+        });
+    }
+    if (rc) return rc;
+    if (!c->dry) {
+        hipError_t e = hipEventRecord(c->ev_pulled, c->stream[0]);
+        if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+    }
+    c->pending_update = false;
+    c->pull_due = false;
+    c->anchor_due = true;
+    return OLS_OK;
+}
+
+int ols_anchor_update_async(ols_handle c) {
+    if (int rc = need(c)) return rc;
+    if (!c->anchor_due) return fail(OLS_ESTATE, "ols_anchor_update_async is legal only right after ols_sync_pull");
+    c->anchor_due = false;
+    if (c->anchor_precomputed) {  // the pull pass already produced the new anchor on the main stream
+        c->anchor_precomputed = false;
+        return OLS_OK;
+    }
+    const int sid = (c->serialize || c->stream[1] == c->stream[0]) ? 0 : 1;
+    if (sid == 1 && !c->dry) {
+        hipError_t e = hipStreamWaitEvent(c->stream[1], c->ev_pulled, 0);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent");
+    }
+    if (sid == 1) c->next_waited = true;
+    MeanArgs a = {};
+    a.x = c->x[c->cur];
+    a.z = c->z;
+    a.v = c->v;
+    a.m = c->m;
+    a.ld = c->ld;
+    a.beta_z = c->beta_z;
+    a.split = c->mean_split;
+    int rc = enqueue(c, OLS_K_MEAN, sid, c->cur, -1, [&](hipStream_t s) { return launch_mean(a, s); });
+    if (rc) return rc;
+    if (sid == 1) {
+        if (!c->dry) {
+            hipError_t e = hipEventRecord(c->ev_anchor_done, c->stream[1]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+        }
+        c->anchor_inflight = true;
+        c->first_after_anchor = true;
+    }
+    return OLS_OK;
+}
+
+int ols_sync(ols_handle c) {
+    if (int rc = need(c)) return rc;
+    if (!c->bound || c->dry) return OLS_OK;
+    hipError_t e = hipStreamSynchronize(c->stream[0]);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize(main)");
+    e = hipStreamSynchronize(c->stream[1]);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize(side)");
+    // everything has finished: no cross-stream wait is needed any more
+    c->anchor_inflight = false;
+    c->first_after_anchor = false;
+    return OLS_OK;
+}
+
+int ols_get_params(ols_handle c, int which, float* dst, int dst_is_device) {
+    if (int rc = need(c)) return rc;
+    if (!c->bound || !c->inited) return fail(OLS_ESTATE, "nothing to read before ols_init_params");
+    if (c->pending_update) return fail(OLS_ESTATE, "a deferred local step is pending; call ols_sync_pull first");
+    if (!dst) return fail(OLS_EINVAL, "dst is null");
+    if (which < -2 || which >= c->m) return fail(OLS_EINVAL, "which must be in [-2, m)");
+    if (c->dry) return OLS_OK;
+    if (int rc = ols_sync(c)) return rc;
+    if (which == -2) {
+        if (!dst_is_device) return fail(OLS_EINVAL, "the replica mean is computed into a device destination");
+        if (reinterpret_cast<uintptr_t>(dst) & 255u) return fail(OLS_EINVAL, "dst must be 256-byte aligned");
+        MeanArgs a = {};
+        a.x = c->x[c->cur];
+        a.z = dst;  // ols_row_stride(d) floats
+        a.m = c->m;
+        a.ld = c->ld;
+        a.split = c->mean_split;
+        hipError_t e = launch_mean(a, c->stream[0]);
+        if (e != hipSuccess) return hip_fail(e, "replica mean");
+        e = hipStreamSynchronize(c->stream[0]);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+        return OLS_OK;
+    }
+    const float* src = which == -1 ? c->z : c->x[c->cur] + (int64_t)which * c->ld;
+    hipError_t e = hipMemcpy(dst, src, (size_t)c->d * sizeof(float),
+                             dst_is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+    return OLS_OK;
+}
+
+int ols_get_loss(ols_handle c, float* per_worker_host) {
+    if (int rc = need(c)) return rc;
+    if (c->model == MODEL_NONE || !c->ws) return fail(OLS_ESTATE, "no model with a workspace is attached");
+    if (!per_worker_host) return fail(OLS_EINVAL, "null destination");
+    if (c->dry) return OLS_OK;
+    hipError_t e = hipStreamSynchronize(c->stream[0]);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    std::vector<float> parts((size_t)c->m * c->B);
+    e = hipMemcpy(parts.data(), c->ws + c->off_loss, parts.size() * sizeof(float), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+    for (int i = 0; i < c->m; ++i) {  // fixed-order mean of the per-sample losses the kernels produced
+        double acc = 0.0;
+        for (int s = 0; s < c->B; ++s) acc += parts[(size_t)i * c->B + s];
+        per_worker_host[i] = (float)(acc / c->B);
+    }
+    return OLS_OK;
+}
+
+int ols_set_option(ols_handle c, int key, int64_t value) {
+    if (int rc = need(c)) return rc;
+    switch (key) {
+        case OLS_OPT_NESTEROV: c->nesterov = value != 0; break;
+        case OLS_OPT_FUSE_PULL:
+            if (c->pending_update) return fail(OLS_ESTATE, "cannot change fusion while a deferred step is pending");
+            c->fuse_pull = value != 0;
+            break;
+        case OLS_OPT_SERIALIZE: c->serialize = value != 0; break;
+        case OLS_OPT_DRY_RUN:
+            if (c->launched) return fail(OLS_ESTATE, "dry-run mode must be chosen before anything is launched");
+            c->dry = value != 0;
+            break;
+        case OLS_OPT_KERNEL_TIMING:
+            if (!value && c->timing) {
+                if (int rc = drain_timers(c)) return rc;
+            }
+            c->timing = value != 0;
+            break;
+        case OLS_OPT_TRACE:
+            c->trace = value != 0;
+            if (value) c->trace_log.clear();
+            break;
+        case OLS_OPT_MEAN_SPLIT:
+            if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
+                return fail(OLS_EINVAL, "mean split must be 0, 1, 2, 4, 8 or 16");
+            c->mean_split = (int)value;
+            break;
+        case OLS_OPT_FUSE_MEAN:
+            if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "cannot change fusion in the middle of a synchronisation");
+            c->fuse_mean = value != 0;
+            break;
+        default: return fail(OLS_EINVAL, "unknown option %d", key);
+    }
+    return OLS_OK;
+}
+
+int64_t ols_iteration(ols_handle c) { return c ? c->k : -1; }
+
+int ols_kernel_stats(ols_handle c, int kind, int64_t* launches, double* total_ms) {
+    if (int rc = need(c)) return rc;
+    if (kind < 0 || kind >= OLS_K_COUNT) return fail(OLS_EINVAL, "bad kernel kind");
+    if (int rc = drain_timers(c)) return rc;
+    if (launches) *launches = c->stat_count[kind];
+    if (total_ms) *total_ms = c->stat_ms[kind];
+    return OLS_OK;
+}
+
+int64_t ols_trace_count(ols_handle c) { return c ? (int64_t)c->trace_log.size() : 0; }
+
+int ols_trace_get(ols_handle c, int64_t idx, ols_trace_entry* out) {
+    if (int rc = need(c)) return rc;
+    if (!out || idx < 0 || idx >= (int64_t)c->trace_log.size()) return fail(OLS_EINVAL, "trace index out of range");
+    *out = c->trace_log[idx];
+    return OLS_OK;
+}
+
+}  // extern "C"

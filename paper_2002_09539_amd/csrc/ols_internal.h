@@ -1,0 +1,109 @@
+// Internal declarations shared by the translation units of libols (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ols.h"
+
+namespace ols {
+
+// ---------------------------------------------------------------------------------------------
+// Launchers.  Each validates its operand shapes on the host and returns a hipError_t; kernels
+// themselves live in the matching kernels_*.hip file.  All pointers are device pointers.
+// ---------------------------------------------------------------------------------------------
+
+struct UpdateArgs {
+    const float* g;     // [m][ld] gradients
+    const float* x_in;  // [m][ld] parameters read
+    float* x_out;       // [m][ld] parameters written (may alias x_in)
+    float* buf;         // [m][ld] momentum buffers, in place (nullptr iff mu == 0)
+    const float* z;     // [ld] anchor, read when pull
+    uint16_t* shadow;   // [m][ld] bf16 copy of x_out written in the same pass, or nullptr
+    int m;
+    int64_t ld;
+    float gamma, mu, alpha;
+    bool nesterov, pull;
+};
+hipError_t launch_step(const UpdateArgs& a, hipStream_t s);                      // local step (+ pull-back)
+hipError_t launch_pull(float* x, const float* z, uint16_t* shadow, int m, int64_t ld, float alpha,
+                       hipStream_t s);                                            // stand-alone pull-back
+hipError_t launch_init(float* x, float* x_alt, float* buf, float* z, uint16_t* shadow, const float* x0, int m,
+                       int64_t d, int64_t ld, hipStream_t s);
+
+struct MeanArgs {
+    const float* x;  // [m][ld]
+    float* z;        // [ld] anchor (read-modify-write when v != nullptr)
+    float* v;        // [ld] anchor momentum buffer or nullptr
+    int m;
+    int64_t ld;
+    float beta_z;
+    int split;  // 0 auto, else wavefronts sharing the replica axis (1, 2, 4)
+};
+hipError_t launch_mean(const MeanArgs& a, hipStream_t s);
+int mean_auto_split(int m, int64_t ld);
+
+// step + pull-back + anchor refresh in one pass: one thread owns a column across all replicas
+struct StepPullMeanArgs {
+    UpdateArgs u;   // u.pull must be true
+    float* z_out;   // [ld] new anchor (may alias u.z)
+    float* v;       // anchor momentum or nullptr
+    float beta_z;
+    bool with_step; // false: pull-back + mean only (parameters already stepped)
+};
+hipError_t launch_step_pull_mean(const StepPullMeanArgs& a, hipStream_t s);
+
+// linear least squares
+hipError_t launch_lsq_resid(const float* A, int64_t a_stride, const float* y, int64_t y_stride, const float* x,
+                            int64_t ld, float* resid, float* loss_parts, int m, int B, int64_t d, hipStream_t s);
+hipError_t launch_lsq_grad(const float* A, int64_t a_stride, const float* resid, float* g, int64_t ld, int m, int B,
+                           int64_t d, hipStream_t s);
+
+// grouped GEMMs over the m workers (group strides in elements)
+struct GemmArgs {
+    const void* a;      // operand A, group stride sa
+    const void* b;      // operand B, group stride sb
+    void* c;            // output, group stride sc
+    const float* bias;  // fwd: [N] per group, stride sbias
+    const void* mask;   // dA: activations whose sign gates the output, same shape as c, stride smask
+    void* c_t;          // bf16 only: optional transposed copy of the output [N][M], stride sct (or nullptr)
+    int64_t sa, sb, sc, sbias, smask, sct;
+    int groups;
+    int M, N, K;        // output M x N, contraction length K
+    int lda, ldb, ldc;  // leading dimensions (elements) of the operands as stored
+};
+// fp32 MFMA.  fwd: C[M][N] = relu(A[M][K] W[K][N] + bias);  dw: C[M][N] = A[K][M]^T B[K][N];
+// da: C[M][N] = (A[M][K] B[N][K]^T) * (mask > 0)
+hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s);
+// bf16 operands, fp32 accumulate
+hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_bf16_da(const GemmArgs& g, hipStream_t s);
+hipError_t launch_cast_bf16(const float* src, int64_t src_stride, uint16_t* dst, uint16_t* dst_t, int groups, int rows,
+                            int cols, hipStream_t s);
+
+// output layer (N = classes <= 32) on plain vector ALUs
+struct HeadArgs {
+    const void* h;        // [m][B][H] last hidden activations (fp32, or bf16 when h_bf16)
+    int64_t h_stride;     // elements between workers in h
+    bool h_bf16;
+    const float* x;       // [m][ld] parameters; W_L at w_off, b_L at b_off within a row
+    float* g;             // [m][ld] gradients, same offsets
+    int64_t ld, w_off, b_off;
+    const int32_t* labels;
+    int64_t label_stride;
+    float* dlogits;       // [m][B][C]
+    float* loss_parts;    // [m][B] per-sample losses
+    void* dz;             // [m][B][H] delta for the last hidden layer (fp32 or bf16), masked by h > 0
+    void* dz_t;           // bf16 only: transposed copy [m][H][B] or nullptr
+    int m, B, H, C;
+};
+hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s);
+hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s);
+hipError_t launch_bias_grad(const void* dz, bool dz_bf16, int64_t dz_stride, float* g, int64_t ld, int64_t b_off,
+                            int m, int B, int N, hipStream_t s);
+
+inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
+
+}  // namespace ols

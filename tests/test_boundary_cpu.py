@@ -1,0 +1,222 @@
+"""Host-side tests of the C boundary that need no GPU: the library loads, exports every declared
+symbol, validates its arguments, and enforces the call order of the algorithm (Section 2 of
+arXiv 2002.09539: tau local steps, then the pull-back, then the anchor refresh).  The schedule is
+exercised in dry-run mode, where nothing is launched and the launch trace is recorded."""
+import os
+import re
+
+import pytest
+
+from paper_2002_09539_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000  # 256-byte aligned stand-in addresses; never dereferenced in dry-run mode
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ols.h")).read()
+    return sorted(set(re.findall(r"OLS_API [\w\s\*]+?\b(ols_\w+)\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    names = declared_symbols()
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(B._SIGNATURES), "binding and header disagree"
+    assert "gfx950" in B.ols_version()
+
+
+def test_row_stride():
+    assert B.ols_row_stride(1) == 64 and B.ols_row_stride(64) == 64 and B.ols_row_stride(65) == 128
+    assert B.ols_row_stride(1578506) == 1578560 and B.ols_row_stride(0) == 0
+
+
+@pytest.mark.parametrize("args", [(0, 8, 2, .5, .1, 0.), (4, 0, 2, .5, .1, 0.), (4, 8, 0, .5, .1, 0.),
+                                  (4, 8, 2, 1.5, .1, 0.), (4, 8, 2, -.1, .1, 0.), (4, 8, 2, .5, 0., 0.),
+                                  (4, 8, 2, .5, .1, 1.0), (4, 8, 2, .5, .1, -0.1)])
+def test_create_rejects_bad_arguments(args):
+    with pytest.raises(B.OlsError) as e:
+        B.ols_create(*args)
+    assert e.value.code == B.OLS_EINVAL and len(str(e.value)) > 20
+
+
+def dry(m=4, d=100, tau=2, alpha=0.6, gamma=0.1, mu=0.9, alt=True, trace=True):
+    h = B.ols_create(m, d, tau, alpha, gamma, mu)
+    B.ols_set_option(h, B.OLS_OPT_DRY_RUN, 1)
+    if trace:
+        B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    ld = B.ols_row_stride(d)
+    B.ols_bind(h, FAKE, FAKE + (1 << 30) if alt else None, FAKE + (2 << 30) if mu else None, FAKE + (3 << 30),
+               FAKE + (4 << 30), ld, None, 8)
+    return h
+
+
+def code_of(fn, *a):
+    with pytest.raises(B.OlsError) as e:
+        fn(*a)
+    return e.value.code
+
+
+def test_bind_validation():
+    h = B.ols_create(4, 100, 2, 0.6, 0.1, 0.9)
+    ld = B.ols_row_stride(100)
+    assert code_of(B.ols_bind, h, FAKE, None, None, FAKE, FAKE, ld, None, None) == B.OLS_EINVAL   # buf missing
+    assert code_of(B.ols_bind, h, FAKE, None, FAKE, FAKE, FAKE, 100, None, None) == B.OLS_EINVAL  # wrong ld
+    assert code_of(B.ols_bind, h, FAKE + 4, None, FAKE, FAKE, FAKE, ld, None, None) == B.OLS_EINVAL  # alignment
+    assert code_of(B.ols_bind, h, FAKE, FAKE, FAKE, FAKE, FAKE, ld, None, None) == B.OLS_EINVAL   # x_alt == x
+    assert code_of(B.ols_local_step, h) == B.OLS_ESTATE                                           # unbound
+    B.ols_destroy(h)
+
+
+def test_call_order_is_enforced():
+    h = dry(tau=2)
+    assert code_of(B.ols_local_step, h) == B.OLS_ESTATE          # before init
+    B.ols_init_params(h, FAKE)
+    assert code_of(B.ols_sync_pull, h) == B.OLS_ESTATE           # k = 0
+    B.ols_local_step(h)
+    assert code_of(B.ols_sync_pull, h) == B.OLS_ESTATE           # k = 1, tau = 2
+    assert code_of(B.ols_anchor_update_async, h) == B.OLS_ESTATE
+    B.ols_local_step(h)
+    assert B.ols_iteration(h) == 2
+    assert code_of(B.ols_local_step, h) == B.OLS_ESTATE          # pull due
+    assert code_of(B.ols_get_params, h, 0, FAKE, 1) == B.OLS_ESTATE  # deferred write pending
+    assert code_of(B.ols_set_gradient, h, FAKE) == B.OLS_ESTATE
+    B.ols_sync_pull(h)
+    assert code_of(B.ols_sync_pull, h) == B.OLS_ESTATE           # already pulled
+    assert code_of(B.ols_local_step, h) == B.OLS_ESTATE          # anchor refresh due
+    B.ols_anchor_update_async(h)
+    assert code_of(B.ols_anchor_update_async, h) == B.OLS_ESTATE
+    B.ols_local_step(h)
+    B.ols_destroy(h)
+
+
+def kinds(trace):
+    return [B.ols_kernel_name(t["kind"]) for t in trace]
+
+
+def run_rounds(h, rounds, tau):
+    B.ols_init_params(h, FAKE)
+    for _ in range(rounds):
+        for _ in range(tau):
+            B.ols_local_step(h)
+        B.ols_sync_pull(h)
+        B.ols_anchor_update_async(h)
+
+
+def test_overlap_schedule_with_second_buffer():
+    """The first update after a refresh goes out-of-place so the side stream still sees the
+    round-boundary models; the main stream waits for the refresh only at the next pull."""
+    h = dry(tau=3)
+    run_rounds(h, 3, 3)
+    tr = B.ols_trace(h)
+    assert kinds(tr) == ["init"] + ["step", "step", "step_pull", "mean"] * 3
+    r1, r2, r3 = tr[1:5], tr[5:9], tr[9:13]
+    # round 1: no refresh in flight yet -> in place on buffer 0, no waits
+    assert [(t["src_buf"], t["dst_buf"], t["waited"]) for t in r1[:3]] == [(0, 0, 0)] * 3
+    assert r1[3]["stream"] == 1 and r1[3]["src_buf"] == 0 and r1[3]["waited"] == 1   # side waits for the pull
+    # round 2: first step reads 0 writes 1 without waiting; later in place on 1; pull waits for refresh 1
+    assert [(t["src_buf"], t["dst_buf"], t["waited"]) for t in r2[:3]] == [(0, 1, 0), (1, 1, 0), (1, 1, 1)]
+    assert r2[3]["src_buf"] == 1
+    assert [(t["src_buf"], t["dst_buf"], t["waited"]) for t in r3[:3]] == [(1, 0, 0), (0, 0, 0), (0, 0, 1)]
+    assert all(t["stream"] == 0 for t in tr if B.ols_kernel_name(t["kind"]) != "mean")
+    B.ols_destroy(h)
+
+
+def test_schedule_without_second_buffer_waits_before_first_write():
+    h = dry(tau=2, alt=False)
+    run_rounds(h, 2, 2)
+    tr = B.ols_trace(h)
+    assert kinds(tr) == ["init", "step", "step_pull", "mean", "step", "step_pull", "mean"]
+    assert tr[4]["waited"] == 1 and (tr[4]["src_buf"], tr[4]["dst_buf"]) == (0, 0)   # in-place write waits
+    assert tr[5]["waited"] == 0                                                     # already waited
+    B.ols_destroy(h)
+
+
+def test_serialized_and_unfused_schedules():
+    h = dry(tau=2)
+    B.ols_set_option(h, B.OLS_OPT_SERIALIZE, 1)
+    B.ols_set_option(h, B.OLS_OPT_FUSE_PULL, 0)
+    run_rounds(h, 2, 2)
+    tr = B.ols_trace(h)
+    assert kinds(tr) == ["init"] + ["step", "step", "pull", "mean"] * 2
+    assert all(t["stream"] == 0 and t["waited"] == 0 for t in tr)
+    assert all(t["dst_buf"] in (0, -1) for t in tr)
+    B.ols_destroy(h)
+
+
+def test_tau_one_and_fused_mean_schedules():
+    h = dry(tau=1)
+    run_rounds(h, 3, 1)
+    tr = B.ols_trace(h)
+    assert kinds(tr) == ["init"] + ["step_pull", "mean"] * 3
+    assert [t["waited"] for t in tr[1::2]] == [0, 1, 1]          # each pull needs the previous refresh
+    B.ols_destroy(h)
+    h = dry(tau=2)
+    B.ols_set_option(h, B.OLS_OPT_FUSE_MEAN, 1)
+    run_rounds(h, 2, 2)
+    assert kinds(B.ols_trace(h)) == ["init"] + ["step", "step_pull_mean"] * 2
+    B.ols_destroy(h)
+
+
+def test_trailing_steps_need_no_pull():
+    h = dry(tau=4)
+    B.ols_init_params(h, FAKE)
+    for _ in range(3):
+        B.ols_local_step(h)
+    assert B.ols_iteration(h) == 3
+    B.ols_get_params(h, 0, FAKE, 1)      # legal: nothing pending (dry run copies nothing)
+    B.ols_destroy(h)
+
+
+def test_model_attachment_validation():
+    h = dry(d=3 * 8 + 8 + 8 * 4 + 4, mu=0.0)
+    assert code_of(B.ols_attach_mlp, h, [3, 8, 4], 8, 0) == B.OLS_EINVAL      # dims[0] not a multiple of 4
+    B.ols_destroy(h)
+    d = 8 * 12 + 12 + 12 * 5 + 5
+    h = dry(d=d, mu=0.0)
+    assert code_of(B.ols_attach_mlp, h, [8, 12, 5], 6, 0) == B.OLS_EINVAL     # batch not a multiple of 4
+    assert code_of(B.ols_attach_mlp, h, [8, 12, 40], 8, 0) == B.OLS_EINVAL    # too many classes
+    assert code_of(B.ols_attach_mlp, h, [8, 16, 5], 8, 0) == B.OLS_EINVAL     # d mismatch
+    assert code_of(B.ols_attach_mlp, h, [8, 12, 5], 8, 2) == B.OLS_EINVAL     # dtype
+    B.ols_attach_mlp(h, [8, 12, 5], 8, 0)
+    need = B.ols_workspace_bytes(h)
+    assert need >= 4 * (2 * 8 * 12 + 8 * 5 + 8) * 4
+    assert code_of(B.ols_bind_workspace, h, FAKE, need - 1) == B.OLS_ENOMEM
+    B.ols_init_params(h, FAKE)
+    assert code_of(B.ols_local_step, h) == B.OLS_ESTATE                       # no workspace
+    B.ols_bind_workspace(h, FAKE, need)
+    assert code_of(B.ols_local_step, h) == B.OLS_ESTATE                       # no batch
+    assert code_of(B.ols_set_batch, h, FAKE, 8 * 8 - 4, FAKE, 8) == B.OLS_EINVAL  # worker stride too small
+    B.ols_set_batch(h, FAKE, 8 * 8, FAKE, 8)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_local_step(h)
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw", "bias_grad", "step"]
+    assert code_of(B.ols_set_gradient, h, FAKE) == B.OLS_ESTATE               # the model owns g
+    B.ols_destroy(h)
+
+
+def test_deep_mlp_launch_plan():
+    dims = [8, 12, 16, 20, 5]
+    d = sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(4))
+    h = dry(d=d, mu=0.9)
+    B.ols_attach_mlp(h, dims, 8, 0)
+    B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+    B.ols_init_params(h, FAKE)
+    B.ols_set_batch(h, FAKE, 64, FAKE, 8)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_local_step(h)
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd"] * 3 + ["head_fwd", "head_bwd"] + \
+        ["gemm_dw", "bias_grad", "gemm_da"] * 2 + ["gemm_dw", "bias_grad", "step"]
+    B.ols_destroy(h)
+
+
+def test_option_validation():
+    h = dry()
+    assert code_of(B.ols_set_option, h, 99, 1) == B.OLS_EINVAL
+    assert code_of(B.ols_set_option, h, B.OLS_OPT_MEAN_SPLIT, 3) == B.OLS_EINVAL
+    assert code_of(B.ols_set_lr, h, 0.0) == B.OLS_EINVAL
+    assert code_of(B.ols_set_anchor_momentum, h, 0.7, None) == B.OLS_EINVAL
+    B.ols_set_anchor_momentum(h, 0.7, FAKE)
+    B.ols_destroy(h)

@@ -1,0 +1,103 @@
+"""GPU parity of the per-worker MLP forward/backward (grouped MFMA GEMMs, output layer, bias
+gradients) and of whole MLP runs against the CPU oracle, through the C boundary."""
+import numpy as np
+import pytest
+
+import ols_inputs as I
+from ols_inputs import generate as G
+from oracle import ols_oracle as O
+from oracle import workloads as OW
+from tests.helpers import l2_ratio, max_norm_ratio
+
+pytestmark = pytest.mark.gpu
+
+GRAD_TOL = 2e-5     # fp32 MFMA accumulation over K <= 3072 terms against the fp64 oracle, max-norm relative
+E2E_TOL = 1e-3
+
+
+def make_session(*a, **kw):
+    from paper_2002_09539_amd.session import Session
+    return Session(*a, **kw)
+
+
+def small_mlp_case(m, dims, batch, nb, seed, noniid=0):
+    cfg = I.get(2).scaled(m=m, dims=tuple(dims), batch=batch, nb=nb, seed=seed, noniid_classes=noniid,
+                          n_classes=dims[-1])
+    X, labels = G.mlp_data(cfg)
+    x0 = G.mlp_init(cfg)
+    return cfg, X, labels, x0
+
+
+def layer_slices(dims):
+    out, off = [], 0
+    for l in range(len(dims) - 1):
+        w = slice(off, off + dims[l] * dims[l + 1])
+        off = w.stop
+        b = slice(off, off + dims[l + 1])
+        off = b.stop
+        out.append((w, b))
+    return out
+
+
+@pytest.mark.parametrize("m,dims,batch", [
+    (3, (100, 72, 10), 36),            # ragged in every tile dimension
+    (2, (64, 96, 40, 7), 20),          # two hidden layers: exercises the delta GEMM
+    (2, (256, 192, 132, 10), 132),     # several tiles per dimension plus tails
+    (5, (128, 64, 64, 64, 16), 64),    # exact tile multiples, three hidden layers
+    (2, (40, 12), 8),                  # no hidden layer at all
+    (4, (3072, 512, 10), 128),         # configuration 2's layer shapes
+    (4, (3072, 1024, 10), 64),         # configuration 5's layer shapes
+])
+def test_gradient_and_loss_match_oracle(m, dims, batch):
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 1, seed=101)
+    x0 = x0 + G.generic_normal(3, 1, x0.shape, sigma=0.02)      # non-zero biases as well
+    with make_session(m, cfg.d, 2, 0.6, 0.05, 0.0) as s:
+        s.attach_mlp(dims, batch, "f32")
+        Xd, yd = s.upload(X), s.upload(labels)
+        s.init_params(x0)
+        s.set_batch(Xd[:, 0], yd[:, 0])
+        s.local_step()
+        g, losses = s.gradient(), s.losses()
+    for i in range(m):
+        loss, grad = O.mlp_loss_grad(x0, dims, X[i, 0], labels[i, 0])
+        assert abs(losses[i] - loss) <= 1e-5 * abs(loss)
+        for l, (w, b) in enumerate(layer_slices(dims)):
+            assert max_norm_ratio(g[i][w], grad[w]) <= GRAD_TOL, "worker %d dW%d" % (i, l)
+            assert max_norm_ratio(g[i][b], grad[b]) <= GRAD_TOL, "worker %d db%d" % (i, l)
+
+
+@pytest.mark.parametrize("m,dims,batch,tau,K,noniid", [
+    (4, (96, 64, 10), 32, 2, 12, 0),
+    (6, (64, 48, 32, 10), 16, 3, 10, 2),
+])
+def test_small_mlp_runs_match_oracle(m, dims, batch, tau, K, noniid):
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 3, seed=202, noniid=noniid)
+    st = O.run(x0, m, tau, 0.6, 0.05, K, OW.mlp_grad_fn(dims, X, labels), mu=0.9)
+    with make_session(m, cfg.d, tau, 0.6, 0.05, 0.9) as s:
+        s.attach_mlp(dims, batch, "f32")
+        Xd, yd = s.upload(X), s.upload(labels)
+        s.init_params(x0)
+        losses = []
+        s.run(K, lambda k: s.set_batch(Xd[:, k % 3], yd[:, k % 3]), losses=losses)
+        x, z = s.all_params(), s.params(-1)
+    assert max(l2_ratio(x[i], st["x"][i]) for i in range(m)) <= E2E_TOL
+    assert l2_ratio(z, st["z"]) <= E2E_TOL
+    np.testing.assert_allclose(np.array(losses), st["losses"], rtol=1e-3)
+
+
+def test_config2_shapes_short_run():
+    """Configuration 2's model, batch and hyper-parameters on 4 of the 16 workers for 3 rounds."""
+    cfg = I.get(2).scaled(m=4, nb=3, K=6)
+    X, labels = G.mlp_data(cfg)
+    x0 = G.mlp_init(cfg)
+    st = OW.run_config(cfg, x0, OW.mlp_grad_fn(cfg.dims, X, labels))
+    with make_session(cfg.m, cfg.d, cfg.tau, cfg.alpha, cfg.gamma, cfg.mu) as s:
+        s.attach_mlp(cfg.dims, cfg.batch, "f32")
+        Xd, yd = s.upload(X), s.upload(labels)
+        s.init_params(x0)
+        losses = []
+        s.run(cfg.K, lambda k: s.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb]), losses=losses)
+        x, z = s.all_params(), s.params(-1)
+    assert max(l2_ratio(x[i], st["x"][i]) for i in range(cfg.m)) <= E2E_TOL
+    assert l2_ratio(z, st["z"]) <= E2E_TOL
+    np.testing.assert_allclose(np.array(losses), st["losses"], rtol=1e-3)
