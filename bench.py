@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the Overlap Local-SGD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+A step is one iteration of the whole hot path for all m workers (per-worker forward/backward, local
+momentum step, and on every tau-th step the pull-back and the overlapped anchor refresh) on synthetic
+CIFAR-10-shaped inputs already resident in HBM.  Prints ONE JSON line: worker-iterations/s, the
+roofline of the dominant kernel from HIP-event timing on the kernel's own stream, and the CPU oracle
+timed on a bounded sample of the same workload as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=2, help="workload number (BASELINE configs are 1-based)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
+    ap.add_argument("--serialize", type=int, default=0, help="1: anchor refresh on the main stream (no overlap)")
+    ap.add_argument("--fuse-mean", type=int, default=0, help="1: step + pull-back + anchor refresh in one pass")
+    ap.add_argument("--no-second-buffer", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    return ap.parse_args()
+
+
+def algorithmic_work(cfg, ld):
+    """Per-launch algorithmic bytes / flops of each kernel kind (element-replicas x bytes, 2 M N K)."""
+    m = cfg.m
+    er = m * ld                        # element-replicas one streaming launch touches
+    mom = 8 if cfg.mu != 0.0 else 0    # read + write of the momentum buffer
+    shadow = 2 if cfg.gemm_dtype == "bf16" else 0
+    work = {
+        "step": ("hbm", er * (12 + mom + shadow)),
+        "step_pull": ("hbm", er * (12 + mom + shadow) + 4 * ld),
+        "pull": ("hbm", er * (8 + shadow) + 4 * ld),
+        "mean": ("hbm", (4 * m + 4) * ld),
+        "step_pull_mean": ("hbm", er * (12 + mom) + 8 * ld),
+    }
+    if cfg.kind == "mlp":
+        dims, B = cfg.dims, cfg.batch
+        L = len(dims) - 1
+        fwd = [2.0 * m * B * dims[l] * dims[l + 1] for l in range(L - 1)]
+        work["gemm_fwd"] = ("mfma", sum(fwd) / max(len(fwd), 1))
+        work["gemm_dw"] = ("mfma", sum(fwd) / max(len(fwd), 1))
+        da = [2.0 * m * B * dims[l] * dims[l + 1] for l in range(1, L - 1)]
+        if da:
+            work["gemm_da"] = ("mfma", sum(da) / len(da))
+    return work
+
+
+def build_workload(cfg, sess, torch):
+    """Uploads the configuration's synthetic inputs; returns the per-iteration input binder."""
+    from ols_inputs import generate as G
+    if cfg.kind == "mlp":
+        X, labels = G.mlp_data(cfg)
+        Xd, yd = sess.upload(X), sess.upload(labels)
+        x0 = G.mlp_init(cfg)
+        sess.attach_mlp(cfg.dims, cfg.batch, cfg.gemm_dtype)
+        sess.init_params(x0)
+        return (lambda k: sess.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb])), (X, labels, x0)
+    if cfg.kind == "lsq":
+        A, y, _, x0 = G.lsq_data(cfg)
+        Ad, yd = sess.upload(A), sess.upload(y)
+        sess.attach_lsq(cfg.batch)
+        sess.init_params(x0)
+        return (lambda k: sess.set_batch(Ad[:, k % cfg.nb], yd[:, k % cfg.nb])), (A, y, x0)
+    # update-only stream: a pool of gradient tensors cycled per iteration
+    x0 = G.stream_x0(cfg)
+    pool = []
+    for j in range(cfg.grad_pool):
+        t = torch.zeros(cfg.m, sess.ld, dtype=torch.float32, device=sess.device)
+        t[:, : cfg.d] = torch.from_numpy(G.stream_gradient(cfg, j)).to(sess.device)
+        pool.append(t)
+    torch.cuda.synchronize()
+    sess.bind(pool[0])
+    sess.init_params(x0)
+    return (lambda k: sess.set_gradient(pool[k % len(pool)])), (None, None, x0)
+
+
+def cpu_baseline(cfg, host_inputs, seconds):
+    """The oracle as it stands, timed on this machine's host cores on a prefix of the same workload."""
+    from oracle import workloads as OW
+    from ols_inputs import generate as G
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    if cfg.kind == "mlp":
+        X, labels, x0 = host_inputs
+        grad_fn = OW.mlp_grad_fn(cfg.dims, X, labels)
+        m_eff, d_eff = cfg.m, cfg.d
+    elif cfg.kind == "lsq":
+        A, y, x0 = host_inputs
+        grad_fn = OW.lsq_grad_fn(A, y)
+        m_eff, d_eff = cfg.m, cfg.d
+    else:  # the update is element-wise: time the oracle on a slice of the columns
+        d_eff = 1 << 20
+        x0 = host_inputs[2][:d_eff]
+        grads = [G.stream_gradient(cfg, j, d=d_eff) for j in range(cfg.grad_pool)]
+        grad_fn = OW.stream_grad_fn(grads)
+        m_eff = cfg.m
+    # one round to calibrate, then as many rounds as fit the time budget
+    t0 = time.perf_counter()
+    OW.run_config(cfg, x0, grad_fn, K=cfg.tau)
+    per_round = time.perf_counter() - t0
+    rounds = int(max(1, min(cfg.rounds, seconds / max(per_round, 1e-6))))
+    t0 = time.perf_counter()
+    OW.run_config(cfg, x0, grad_fn, K=rounds * cfg.tau)
+    dt = time.perf_counter() - t0
+    value = m_eff * rounds * cfg.tau / dt * (d_eff / cfg.d)
+    sample = "first %d iterations (%d rounds) of the workload, all %d workers" % (rounds * cfg.tau, rounds, cfg.m)
+    if d_eff != cfg.d:
+        sample += ", first %d of %d parameter columns (rate scaled by the column fraction)" % (d_eff, cfg.d)
+    return {"value": value, "unit": "worker-iterations/s", "cores": cores, "kind": "oracle", "sample": sample,
+            "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the m workers are replicas inside one MI355X); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import ols_inputs as I
+    from paper_2002_09539_amd import binding as B
+    from paper_2002_09539_amd.session import Session
+
+    cfg = I.get(args.config)
+    K = args.steps if args.steps is not None else cfg.K
+    W = args.warmup if args.warmup is not None else 4 * cfg.tau
+    K = max(cfg.tau, K // cfg.tau * cfg.tau)     # whole rounds, so every timed region ends on a refresh
+    W = max(cfg.tau, W // cfg.tau * cfg.tau)
+
+    sess = Session(cfg.m, cfg.d, cfg.tau, cfg.alpha, cfg.gamma, cfg.mu,
+                   overlap_buffer=not args.no_second_buffer, own_gradient=cfg.kind != "stream")
+    sess.set_option(B.OLS_OPT_NESTEROV, int(cfg.nesterov))
+    sess.set_option(B.OLS_OPT_SERIALIZE, args.serialize)
+    sess.set_option(B.OLS_OPT_FUSE_MEAN, args.fuse_mean)
+    feed, host_inputs = build_workload(cfg, sess, torch)
+
+    def region(steps):
+        sess.sync()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sess.run(steps, feed)
+        sess.sync()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    region(W)
+    elapsed = region(K)
+    value = cfg.m * K / elapsed
+
+    kernels, roofline = {}, None
+    if not args.no_kernel_timing:
+        sess.set_option(B.OLS_OPT_KERNEL_TIMING, 1)
+        timed_elapsed = region(K)
+        stats = sess.kernel_stats()
+        sess.set_option(B.OLS_OPT_KERNEL_TIMING, 0)
+        work = algorithmic_work(cfg, sess.ld)
+        for name, (n, ms) in stats.items():
+            entry = {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms}
+            if name in work:
+                bound, amount = work[name]
+                rate = amount / (ms / n * 1e-3)
+                if bound == "hbm":
+                    entry.update(bound="hbm", achieved=rate / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                                 frac=rate / 1e9 / HBM_PEAK_GBS, per_launch=amount)
+                else:
+                    peak = MFMA_PEAK_TFLOPS[cfg.gemm_dtype]
+                    entry.update(bound="mfma", achieved=rate / 1e12, peak=peak, unit="TFLOP/s",
+                                 frac=rate / 1e12 / peak, per_launch=amount)
+            kernels[name] = entry
+        ranked = sorted((e["total_ms"], n) for n, e in kernels.items() if "bound" in e)
+        if ranked:
+            dom = ranked[-1][1]
+            e = kernels[dom]
+            traffic = None
+            tpath = os.path.join(ROOT, "profiles", "traffic.json")
+            if os.path.exists(tpath):
+                traffic = json.load(open(tpath)).get("cfg%d" % args.config, {}).get(dom)
+            roofline = {"kernel": dom, "bound": e["bound"], "achieved": e["achieved"], "peak": e["peak"],
+                        "unit": e["unit"], "frac": e["frac"], "traffic": traffic,
+                        "avg_launch_us": e["avg_us"], "algorithmic_per_launch": e["per_launch"]}
+        kernels["_region_ms_with_event_timing"] = 1e3 * timed_elapsed
+
+    base = cpu_baseline(cfg, host_inputs, args.cpu_seconds) if args.cpu_seconds > 0 else None
+    sess.close()
+
+    out = {
+        "metric": "worker-iterations/sec at m replicas",
+        "value": value,
+        "unit": "worker-iterations/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": 1e3 * elapsed / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.gemm_dtype if cfg.kind == "mlp" else "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
+                   "dims": list(cfg.dims), "overlap": "serialized" if args.serialize else
+                   ("fused-mean" if args.fuse_mean else "side-stream"),
+                   "second_buffer": not args.no_second_buffer},
+        "roofline": roofline,
+        "cpu_baseline": base,
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
