@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--fuse-mean", type=int, default=0, help="1: step + pull-back + anchor refresh in one pass")
     ap.add_argument("--no-second-buffer", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--opt", action="append", default=[], help="KEY=VALUE library option (numeric key), repeatable")
     return ap.parse_args()
 
 
@@ -153,6 +154,9 @@ def main():
     sess.set_option(B.OLS_OPT_NESTEROV, int(cfg.nesterov))
     sess.set_option(B.OLS_OPT_SERIALIZE, args.serialize)
     sess.set_option(B.OLS_OPT_FUSE_MEAN, args.fuse_mean)
+    for kv in args.opt:
+        key, val = kv.split("=")
+        sess.set_option(int(key), int(val))
     feed, host_inputs = build_workload(cfg, sess, torch)
 
     def region(steps):

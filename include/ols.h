@@ -66,12 +66,16 @@ enum {
     OLS_OPT_KERNEL_TIMING = 5, /* 1: bracket every kernel with HIP events on its own stream and accumulate
                                   per-kernel durations (see ols_kernel_stats); default 0                      */
     OLS_OPT_TRACE = 6,         /* 1: keep a host-side log of launches (see ols_trace_get); default 0          */
-    OLS_OPT_MEAN_SPLIT = 7,    /* anchor-mean kernel: 0 = choose from (m, d); 1, 2 or 4 = number of wavefronts
-                                  of a workgroup the replica axis is split over before the LDS tree combine   */
-    OLS_OPT_FUSE_MEAN = 8      /* 1: ols_sync_pull also produces the new anchor in the same pass (each thread
+    OLS_OPT_MEAN_SPLIT = 7,    /* anchor-mean kernel: 0 = choose from (m, d); 1, 2, 4, 8 or 16 = number of
+                                  lane groups / wavefronts of a workgroup sharing the replica axis (combined by
+                                  wavefront shuffles, then an LDS tree)                                       */
+    OLS_OPT_FUSE_MEAN = 8,     /* 1: ols_sync_pull also produces the new anchor in the same pass (each thread
                                   owns a parameter column across all m replicas); ols_anchor_update_async then
                                   only publishes it.  Removes the separate reduction instead of hiding it.
                                   default 0                                                                   */
+    OLS_OPT_GEMM_VARIANT_FWD = 9,  /* tile-shape variant of the forward / weight-gradient / delta GEMM kernels; */
+    OLS_OPT_GEMM_VARIANT_DW = 10,  /* 0 (default) is the tuned choice, other values exist for re-measurement;  */
+    OLS_OPT_GEMM_VARIANT_DA = 11   /* an unknown variant makes the next local step fail with OLS_EHIP          */
 };
 
 /* kernel kinds for ols_kernel_stats / the launch trace */

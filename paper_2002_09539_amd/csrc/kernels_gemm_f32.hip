@@ -36,7 +36,8 @@ struct GemmDev {
     float* c;
     const float* bias;
     const float* mask;
-    int64_t sa, sb, sc, sbias, smask;
+    float* colsum;
+    int64_t sa, sb, sc, sbias, smask, scolsum;
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
 };
@@ -96,7 +97,7 @@ struct Tile {
     }
 };
 
-template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int DEPTH, int NACC>
 __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     constexpr bool A_KC = MODE != kDw;   // FWD, DA: A[M][K];  DW: A[K][M]
     constexpr bool B_KC = MODE == kDa;   // DA: B[N][K];  FWD, DW: B[K][N]
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     constexpr int TM = WM / 32, TN = WN / 32;
     static_assert(WAVES_M * WAVES_N * 64 == kThreads, "four wavefronts");
     static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile shape");
+    static_assert(DEPTH == 1 || DEPTH == 2, "global prefetch distance in K slices");
     using TA = Tile<BM, BK, A_KC>;
     using TB = Tile<BN, BK, B_KC>;
     __shared__ __attribute__((aligned(16))) float lds_a[2][TA::kFloats];
@@ -125,49 +127,128 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     const int lane32 = lane % 32, half = lane / 32;
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
-    f16v acc[TM][TN];
+    // NACC independent accumulator chains per 32 x 32 block (alternate MFMA steps), summed at the end: a
+    // wavefront whose tile is a single block would otherwise issue only dependent MFMAs back to back.
+    f16v acc[TM][TN][NACC];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int a = 0; a < NACC; ++a)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][a][r] = 0.0f;
 
-    f4 ra[TA::kPerThread], rb[TB::kPerThread];
-    const int nk = (p.K + BK - 1) / BK;
-    TA::load(ra, A, p.lda, m0, 0, p.M, p.K);
-    TB::load(rb, B, p.ldb, n0, 0, p.N, p.K);
-    TA::store(lds_a[0], ra);
-    TB::store(lds_b[0], rb);
-    __syncthreads();
+    // DW only: the tiles of the first tile row also reduce the columns of B over the batch, which is
+    // the bias gradient of the layer (sum over samples of the delta), in sample order.
+    const bool col_sums = MODE == kDw && p.colsum != nullptr && tm == 0 && threadIdx.x < BN;
+    float col_acc = 0.0f;
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            TA::load(ra, A, p.lda, m0, (kt + 1) * BK, p.M, p.K);
-            TB::load(rb, B, p.ldb, n0, (kt + 1) * BK, p.N, p.K);
+    // Fragment registers are double-buffered across k-octets, and the order "issue the LDS reads of
+    // octet q+1, then the MFMAs of octet q" is pinned with scheduling barriers: a wavefront stalls at
+    // the issue of an MFMA while the matrix pipe is busy, so reads placed behind the MFMAs would start
+    // only when the pipe is about to drain and their latency would be exposed on every octet.
+    constexpr int Q = BK / 8;
+    static_assert(Q % 2 == 0, "BK must be a multiple of 16");
+    f4 fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int buf, int cur, int q) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[buf][i] = TA::frag(lds_a[cur], wm0 + 32 * i, q, lane32, half);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = TB::frag(lds_b[cur], wn0 + 32 * j, q, lane32, half);
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j][e % NACC] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[buf][i][e], fb[buf][j][e],
+                                                                               acc[i][j][e % NACC], 0, 0, 0);
+    };
+    // One K slice out of lds[cur].  On entry the fragments of octet 0 are already in (or on their way
+    // to) buffer 0.  Before the last octet's MFMAs the staged registers of the next slice are published
+    // to lds[cur ^ 1], the workgroup synchronises once, and the first fragments of that slice are
+    // requested, so the barrier and the LDS latency hide behind the remaining MFMAs.
+    auto slice = [&](int cur, const f4 (&na)[TA::kPerThread], const f4 (&nb)[TB::kPerThread], bool has_next) {
+#pragma unroll
+        for (int q = 0; q + 1 < Q; ++q) {
+            load_frags((q + 1) & 1, cur, q + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(q & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        if (MODE == kDw && col_sums) {
 #pragma unroll
-        for (int q = 0; q < BK / 8; ++q) {
-            f4 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = TA::frag(lds_a[cur], wm0 + 32 * i, q, lane32, half);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = TB::frag(lds_b[cur], wn0 + 32 * j, q, lane32, half);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][e], fb[j][e], acc[i][j], 0, 0, 0);
+            for (int k = 0; k < BK; ++k) col_acc += lds_b[cur][k * TB::kPitch + threadIdx.x];
         }
-        if (kt + 1 < nk) {
-            TA::store(lds_a[cur ^ 1], ra);
-            TB::store(lds_b[cur ^ 1], rb);
+        if (has_next) {
+            TA::store(lds_a[cur ^ 1], na);
+            TB::store(lds_b[cur ^ 1], nb);
         }
         __syncthreads();
+        if (has_next) load_frags(0, cur ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas((Q - 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    const int nk = (p.K + BK - 1) / BK;
+    if (DEPTH == 1) {
+        f4 ra[TA::kPerThread], rb[TB::kPerThread];
+        TA::load(ra, A, p.lda, m0, 0, p.M, p.K);
+        TB::load(rb, B, p.ldb, n0, 0, p.N, p.K);
+        TA::store(lds_a[0], ra);
+        TB::store(lds_b[0], rb);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const bool has_next = kt + 1 < nk;
+            if (has_next) {
+                TA::load(ra, A, p.lda, m0, (kt + 1) * BK, p.M, p.K);
+                TB::load(rb, B, p.ldb, n0, (kt + 1) * BK, p.N, p.K);
+            }
+            slice(kt & 1, ra, rb, has_next);
+        }
+    } else {
+        // Two K slices of global loads in flight: while slice t feeds the matrix cores from LDS, slice
+        // t+1 waits in registers and slice t+2 is on its way from HBM.
+        f4 ra0[TA::kPerThread], rb0[TB::kPerThread], ra1[TA::kPerThread], rb1[TB::kPerThread];
+        TA::load(ra0, A, p.lda, m0, 0, p.M, p.K);
+        TB::load(rb0, B, p.ldb, n0, 0, p.N, p.K);
+        TA::load(ra1, A, p.lda, m0, BK, p.M, p.K);   // zero fill when K <= BK
+        TB::load(rb1, B, p.ldb, n0, BK, p.N, p.K);
+        TA::store(lds_a[0], ra0);
+        TB::store(lds_b[0], rb0);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        // slices are consumed in pairs; an odd trailing slice is paired with an all-zero one (its loads
+        // fall outside K and are zero-filled), which keeps the loop body free of data-dependent exits
+        const int nk2 = (nk + 1) & ~1;
+        for (int kt = 0; kt < nk2; kt += 2) {
+            if (kt + 2 < nk2) {
+                TA::load(ra0, A, p.lda, m0, (kt + 2) * BK, p.M, p.K);
+                TB::load(rb0, B, p.ldb, n0, (kt + 2) * BK, p.N, p.K);
+            }
+            slice(0, ra1, rb1, true);
+            if (kt + 3 < nk2) {
+                TA::load(ra1, A, p.lda, m0, (kt + 3) * BK, p.M, p.K);
+                TB::load(rb1, B, p.ldb, n0, (kt + 3) * BK, p.N, p.K);
+            }
+            slice(1, ra0, rb0, kt + 2 < nk2);
+        }
     }
+    if (NACC > 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int a = 1; a < NACC; ++a) acc[i][j][0] = acc[i][j][0] + acc[i][j][a];
+    }
+    if (MODE == kDw && col_sums && n0 + (int)threadIdx.x < p.N)
+        p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = col_acc;
 
     // Epilogue.  Accumulator register r of a lane holds C[row][col] with col = lane % 32 and
     // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block.
@@ -184,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
                 if (row >= p.M) continue;
-                float v = acc[i][j][r];
+                float v = acc[i][j][0][r];
                 if (MODE == kFwd) v = fmaxf(v + bias, 0.0f);
                 if (MODE == kDa) v = p.mask[(int64_t)group * p.smask + (int64_t)row * p.ldc + col] > 0.0f ? v : 0.0f;
                 C[(int64_t)row * p.ldc + col] = v;
@@ -195,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
 
 static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
-template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int DEPTH, int NACC = 1>
 static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (!g.a || !g.b || !g.c || g.groups < 1 || g.M < 1 || g.N < 1 || g.K < 1) return hipErrorInvalidValue;
     // 16-byte vector loads: every line start must be aligned and extents multiples of 4
@@ -211,7 +292,8 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     p.c = (float*)g.c;
     p.bias = g.bias;
     p.mask = (const float*)g.mask;
-    p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sbias = g.sbias; p.smask = g.smask;
+    p.colsum = MODE == kDw ? g.colsum : nullptr;
+    p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sbias = g.sbias; p.smask = g.smask; p.scolsum = g.scolsum;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
     p.tiles_m = (g.M + BM - 1) / BM;
     p.tiles_n = (g.N + BN - 1) / BN;
@@ -219,12 +301,44 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (total > (1 << 30)) return hipErrorInvalidValue;
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
-    gemm_f32_kernel<MODE, BM, BN, BK, WAVES_M, WAVES_N><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
+    gemm_f32_kernel<MODE, BM, BN, BK, WAVES_M, WAVES_N, DEPTH, NACC><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s) { return gemm_launch<kFwd, 64, 64, 32, 2, 2>(g, s); }
-hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDw, 128, 128, 16, 2, 2>(g, s); }
-hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDa, 64, 64, 32, 2, 2>(g, s); }
+// Tile shapes.  Variant 0 is the default; the others exist so that the choice can be re-measured
+// (OLS_OPT_GEMM_VARIANT_*).  LDS per workgroup stays below 80 KiB so two workgroups fit a compute unit.
+hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s, int variant) {
+    switch (variant) {
+        case 0: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 2>(g, s);
+        case 1: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 2>(g, s);
+        case 2: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 1>(g, s);
+        case 3: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 1>(g, s);
+        case 4: return gemm_launch<kFwd, 128, 64, 32, 2, 2, 2>(g, s);
+        case 5: return gemm_launch<kFwd, 64, 128, 32, 2, 2, 2>(g, s);
+        case 6: return gemm_launch<kFwd, 128, 128, 16, 2, 2, 2>(g, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant) {
+    switch (variant) {
+        case 0: return gemm_launch<kDw, 128, 128, 16, 2, 2, 2>(g, s);
+        case 1: return gemm_launch<kDw, 128, 128, 16, 2, 2, 1>(g, s);
+        case 2: return gemm_launch<kDw, 128, 128, 32, 2, 2, 2>(g, s);
+        case 3: return gemm_launch<kDw, 128, 128, 32, 2, 2, 1>(g, s);
+        case 4: return gemm_launch<kDw, 64, 128, 32, 2, 2, 2>(g, s);
+        case 5: return gemm_launch<kDw, 128, 64, 32, 2, 2, 2>(g, s);
+        case 6: return gemm_launch<kDw, 64, 64, 32, 2, 2, 2>(g, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s, int variant) {
+    switch (variant) {
+        case 0: return gemm_launch<kDa, 64, 64, 64, 2, 2, 2>(g, s);
+        case 1: return gemm_launch<kDa, 64, 64, 32, 2, 2, 2>(g, s);
+        case 2: return gemm_launch<kDa, 64, 64, 32, 2, 2, 1>(g, s);
+        case 3: return gemm_launch<kDa, 128, 64, 32, 2, 2, 2>(g, s);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 }  // namespace ols

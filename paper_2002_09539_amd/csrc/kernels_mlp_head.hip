@@ -24,66 +24,85 @@ __device__ __forceinline__ float load_act(const void* p, int64_t idx) {
     return BF ? bf16_to_f32(((const uint16_t*)p)[idx]) : ((const float*)p)[idx];
 }
 
-// one wavefront per sample; grid (ceil(B / 4), m)
-template <bool BF, int CMAX>
+// SPW samples per wavefront (each weight row fetched once serves all of them);
+// grid (ceil(B / (4 SPW)), m)
+template <bool BF, int CMAX, int SPW>
 __global__ __launch_bounds__(kThreads) void head_fwd_kernel(const void* __restrict__ h, int64_t h_stride,
                                                             const float* __restrict__ x, int64_t ld, int64_t w_off,
                                                             int64_t b_off, const int32_t* __restrict__ labels,
                                                             int64_t label_stride, float* __restrict__ dlogits,
                                                             float* __restrict__ loss_parts, int B, int H, int C) {
-    __shared__ float s_logit[kThreads / kWave][kMaxC];
+    __shared__ float s_logit[kThreads / kWave][SPW][kMaxC];
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int i = blockIdx.y;
-    const int s = blockIdx.x * (kThreads / kWave) + wave;
-    const bool live = s < B;
+    const int s0 = (blockIdx.x * (kThreads / kWave) + wave) * SPW;
     const float* W = x + (int64_t)i * ld + w_off;
-    float acc[CMAX];
+    float acc[SPW][CMAX];
 #pragma unroll
-    for (int c = 0; c < CMAX; ++c) acc[c] = 0.0f;
-    if (live) {
-        const int64_t hbase = (int64_t)i * h_stride + (int64_t)s * H;
-        for (int k = lane; k < H; k += kWave) {
-            const float hv = load_act<BF>(h, hbase + k);
-            const float* wr = W + (int64_t)k * C;
+    for (int j = 0; j < SPW; ++j)
 #pragma unroll
-            for (int c = 0; c < CMAX; ++c)
-                if (c < C) acc[c] = __fmaf_rn(hv, wr[c], acc[c]);
+        for (int c = 0; c < CMAX; ++c) acc[j][c] = 0.0f;
+    for (int k = lane; k < H; k += kWave) {
+        float hv[SPW];
+#pragma unroll
+        for (int j = 0; j < SPW; ++j)
+            hv[j] = s0 + j < B ? load_act<BF>(h, (int64_t)i * h_stride + (int64_t)(s0 + j) * H + k) : 0.0f;
+        const float* wr = W + (int64_t)k * C;
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+            if (c < C) {
+                const float w = wr[c];
+#pragma unroll
+                for (int j = 0; j < SPW; ++j) acc[j][c] = __fmaf_rn(hv[j], w, acc[j][c]);
+            }
         }
     }
 #pragma unroll
-    for (int c = 0; c < CMAX; ++c) {
-        float v = acc[c];
-        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-        if (lane == 0) s_logit[wave][c] = v;
+    for (int j = 0; j < SPW; ++j) {
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) {
+            float v = acc[j][c];
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+            if (lane == 0) s_logit[wave][j][c] = v;
+        }
     }
     __syncthreads();
-    if (!live) return;
     // lane c owns class c
-    const float logit = lane < C ? s_logit[wave][lane] + x[(int64_t)i * ld + b_off + lane] : -INFINITY;
-    float mx = logit;
-    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-    const float ex = lane < C ? expf(logit - mx) : 0.0f;
-    float sum = ex;
-    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
-    const int label = labels[(int64_t)i * label_stride + s];
-    const float picked = __shfl(logit, label, kWave);
-    if (lane == 0) loss_parts[(int64_t)i * B + s] = (logf(sum) + mx) - picked;
-    if (lane < C) {
-        const float p = ex / sum;
-        dlogits[((int64_t)i * B + s) * C + lane] = (p - (lane == label ? 1.0f : 0.0f)) / (float)B;
+    const float bias = lane < C ? x[(int64_t)i * ld + b_off + lane] : 0.0f;
+#pragma unroll
+    for (int j = 0; j < SPW; ++j) {
+        const int s = s0 + j;
+        if (s >= B) break;
+        const float logit = lane < C ? s_logit[wave][j][lane] + bias : -INFINITY;
+        float mx = logit;
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        const float ex = lane < C ? expf(logit - mx) : 0.0f;
+        float sum = ex;
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+        const int label = labels[(int64_t)i * label_stride + s];
+        const float picked = __shfl(logit, label, kWave);
+        if (lane == 0) loss_parts[(int64_t)i * B + s] = (logf(sum) + mx) - picked;
+        if (lane < C) {
+            const float p = ex / sum;
+            dlogits[((int64_t)i * B + s) * C + lane] = (p - (lane == label ? 1.0f : 0.0f)) / (float)B;
+        }
     }
 }
 
-// dW[k][c] = sum_s h[s][k] dlogits[s][c], db[c] = sum_s dlogits[s][c];  grid (ceil(H / 256), m)
+// dW[k][c] = sum_s h[s][k] dlogits[s][c], db[c] = sum_s dlogits[s][c].  A workgroup owns 32 hidden units
+// k; its 8 lane groups of 32 take the samples s = j, j + 8, ... and are combined by a fixed-order sum
+// through LDS.  grid (ceil(H / 32), m)
 template <bool BF, int CMAX>
 __global__ __launch_bounds__(kThreads) void head_dw_kernel(const void* __restrict__ h, int64_t h_stride,
                                                            const float* __restrict__ dlogits, float* __restrict__ g,
                                                            int64_t ld, int64_t w_off, int64_t b_off, int B, int H,
                                                            int C) {
-    constexpr int kRows = 128;  // samples staged per pass
+    constexpr int kCols = 32, kGroups = kThreads / kCols, kRows = 256;
     __shared__ float s_dl[kRows * kMaxC];
+    __shared__ float s_part[kGroups][CMAX][kCols + 1];
     const int i = blockIdx.y;
-    const int k = blockIdx.x * kThreads + threadIdx.x;
+    const int kk = threadIdx.x % kCols, grp = threadIdx.x / kCols;
+    const int k = blockIdx.x * kCols + kk;
     float acc[CMAX];
 #pragma unroll
     for (int c = 0; c < CMAX; ++c) acc[c] = 0.0f;
@@ -94,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void head_dw_kernel(const void* __restric
         for (int t = threadIdx.x; t < rows * C; t += kThreads) s_dl[t] = dlogits[((int64_t)i * B + s0) * C + t];
         __syncthreads();
         if (k < H) {
-            for (int s = 0; s < rows; ++s) {
+            for (int s = grp; s < rows; s += kGroups) {
                 const float hv = load_act<BF>(h, (int64_t)i * h_stride + (int64_t)(s0 + s) * H + k);
 #pragma unroll
                 for (int c = 0; c < CMAX; ++c)
@@ -104,11 +123,15 @@ __global__ __launch_bounds__(kThreads) void head_dw_kernel(const void* __restric
         if (blockIdx.x == 0 && threadIdx.x < C)
             for (int s = 0; s < rows; ++s) bias_acc += s_dl[s * C + threadIdx.x];
     }
-    if (k < H) {
-        float* out = g + (int64_t)i * ld + w_off + (int64_t)k * C;
 #pragma unroll
-        for (int c = 0; c < CMAX; ++c)
-            if (c < C) out[c] = acc[c];
+    for (int c = 0; c < CMAX; ++c) s_part[grp][c][kk] = acc[c];
+    __syncthreads();
+    // thread t finishes outputs (k = t % 32, c = t / 32, t / 32 + 8, ...): consecutive lanes -> consecutive k
+    for (int c = grp; c < C; c += kGroups) {
+        float v = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kGroups; ++j) v += s_part[j][c][kk];
+        if (k < H) g[(int64_t)i * ld + w_off + (int64_t)k * C + c] = v;
     }
     if (blockIdx.x == 0 && threadIdx.x < C) g[(int64_t)i * ld + b_off + threadIdx.x] = bias_acc;
 }
@@ -188,10 +211,12 @@ static bool head_args_ok(const HeadArgs& a) {
 
 hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
     if (!head_args_ok(a)) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((a.B + 3) / 4), (unsigned)a.m);
+    constexpr int kSpw = 2;
+    dim3 grid((unsigned)((a.B + 4 * kSpw - 1) / (4 * kSpw)), (unsigned)a.m);
 #define OLS_HEAD_FWD(BF, CM)                                                                                       \
-    head_fwd_kernel<BF, CM><<<grid, kThreads, 0, s>>>(a.h, a.h_stride, a.x, a.ld, a.w_off, a.b_off, a.labels,      \
-                                                      a.label_stride, a.dlogits, a.loss_parts, a.B, a.H, a.C)
+    head_fwd_kernel<BF, CM, kSpw><<<grid, kThreads, 0, s>>>(a.h, a.h_stride, a.x, a.ld, a.w_off, a.b_off,          \
+                                                            a.labels, a.label_stride, a.dlogits, a.loss_parts,     \
+                                                            a.B, a.H, a.C)
     if (a.h_bf16) {
         if (a.C <= 16) OLS_HEAD_FWD(true, 16); else OLS_HEAD_FWD(true, 32);
     } else {
@@ -203,7 +228,7 @@ hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
 
 hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s) {
     if (!head_args_ok(a)) return hipErrorInvalidValue;
-    dim3 grid_w((unsigned)((a.H + kThreads - 1) / kThreads), (unsigned)a.m);
+    dim3 grid_w((unsigned)((a.H + 31) / 32), (unsigned)a.m);
 #define OLS_HEAD_DW(BF, CM)                                                                                        \
     head_dw_kernel<BF, CM><<<grid_w, kThreads, 0, s>>>(a.h, a.h_stride, a.dlogits, a.g, a.ld, a.w_off, a.b_off,    \
                                                        a.B, a.H, a.C)

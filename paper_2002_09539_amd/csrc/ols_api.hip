@@ -61,6 +61,7 @@ struct ols_ctx {
     bool nesterov = true, fuse_pull = true, serialize = false, dry = false, timing = false, trace = false,
          fuse_mean = false;
     int mean_split = 0;
+    int gemm_variant[3] = {0, 0, 0};  // fwd, dw, da
     // schedule
     int64_t k = 0;
     bool pull_due = false, pending_update = false, anchor_due = false, anchor_inflight = false,
@@ -284,7 +285,7 @@ int compute_gradients(ols_ctx* c) {
         ga.N = c->dims[l + 1];
         ga.K = c->dims[l];
         rc = enqueue(c, OLS_K_GEMM_FWD, 0, c->cur, -1,
-                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_fwd(ga, s) : launch_gemm_f32_fwd(ga, s); });
+                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_fwd(ga, s) : launch_gemm_f32_fwd(ga, s, c->gemm_variant[0]); });
         if (rc) return rc;
     }
     // output layer, loss, and its gradients
@@ -334,17 +335,23 @@ int compute_gradients(ols_ctx* c) {
         gw.c = c->g + c->w_off[l];
         gw.sc = c->ld;
         gw.ldc = c->dims[l + 1];
+        if (!bf) {  // the fp32 kernel reduces the bias gradient while the delta streams through LDS
+            gw.colsum = c->g + c->b_off[l];
+            gw.scolsum = c->ld;
+        }
         gw.groups = m;
         gw.M = c->dims[l];
         gw.N = c->dims[l + 1];
         gw.K = B;
         rc = enqueue(c, OLS_K_GEMM_DW, 0, -1, -1,
-                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s) : launch_gemm_f32_dw(gw, s); });
+                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s) : launch_gemm_f32_dw(gw, s, c->gemm_variant[1]); });
         if (rc) return rc;
-        rc = enqueue(c, OLS_K_BIAS_GRAD, 0, -1, -1, [&](hipStream_t s) {
-            return launch_bias_grad(dz, bf, dz_stride, c->g, c->ld, c->b_off[l], m, B, c->dims[l + 1], s);
-        });
-        if (rc) return rc;
+        if (bf) {
+            rc = enqueue(c, OLS_K_BIAS_GRAD, 0, -1, -1, [&](hipStream_t s) {
+                return launch_bias_grad(dz, bf, dz_stride, c->g, c->ld, c->b_off[l], m, B, c->dims[l + 1], s);
+            });
+            if (rc) return rc;
+        }
         if (l > 0) {
             GemmArgs gd = {};
             gd.a = dz;
@@ -365,7 +372,7 @@ int compute_gradients(ols_ctx* c) {
             gd.N = c->dims[l];
             gd.K = c->dims[l + 1];
             rc = enqueue(c, OLS_K_GEMM_DA, 0, c->cur, -1,
-                         [&](hipStream_t s) { return bf ? launch_gemm_bf16_da(gd, s) : launch_gemm_f32_da(gd, s); });
+                         [&](hipStream_t s) { return bf ? launch_gemm_bf16_da(gd, s) : launch_gemm_f32_da(gd, s, c->gemm_variant[2]); });
             if (rc) return rc;
         }
     }
@@ -804,6 +811,12 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
             if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
                 return fail(OLS_EINVAL, "mean split must be 0, 1, 2, 4, 8 or 16");
             c->mean_split = (int)value;
+            break;
+        case OLS_OPT_GEMM_VARIANT_FWD:
+        case OLS_OPT_GEMM_VARIANT_DW:
+        case OLS_OPT_GEMM_VARIANT_DA:
+            if (value < 0 || value > 15) return fail(OLS_EINVAL, "GEMM variant out of range");
+            c->gemm_variant[key - OLS_OPT_GEMM_VARIANT_FWD] = (int)value;
             break;
         case OLS_OPT_FUSE_MEAN:
             if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "cannot change fusion in the middle of a synchronisation");

@@ -66,16 +66,17 @@ struct GemmArgs {
     const float* bias;  // fwd: [N] per group, stride sbias
     const void* mask;   // dA: activations whose sign gates the output, same shape as c, stride smask
     void* c_t;          // bf16 only: optional transposed copy of the output [N][M], stride sct (or nullptr)
-    int64_t sa, sb, sc, sbias, smask, sct;
+    float* colsum;      // dw: optional [N] per group, receives the column sums of B (the bias gradient)
+    int64_t sa, sb, sc, sbias, smask, sct, scolsum;
     int groups;
     int M, N, K;        // output M x N, contraction length K
     int lda, ldb, ldc;  // leading dimensions (elements) of the operands as stored
 };
 // fp32 MFMA.  fwd: C[M][N] = relu(A[M][K] W[K][N] + bias);  dw: C[M][N] = A[K][M]^T B[K][N];
 // da: C[M][N] = (A[M][K] B[N][K]^T) * (mask > 0)
-hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s);
-hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s);
-hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s, int variant);
+hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant);
+hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s, int variant);
 // bf16 operands, fp32 accumulate
 hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s);

@@ -192,7 +192,7 @@ def test_model_attachment_validation():
     B.ols_set_batch(h, FAKE, 8 * 8, FAKE, 8)
     B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
     B.ols_local_step(h)
-    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw", "bias_grad", "step"]
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw", "step"]
     assert code_of(B.ols_set_gradient, h, FAKE) == B.OLS_ESTATE               # the model owns g
     B.ols_destroy(h)
 
@@ -208,7 +208,7 @@ def test_deep_mlp_launch_plan():
     B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
     B.ols_local_step(h)
     assert kinds(B.ols_trace(h)) == ["gemm_fwd"] * 3 + ["head_fwd", "head_bwd"] + \
-        ["gemm_dw", "bias_grad", "gemm_da"] * 2 + ["gemm_dw", "bias_grad", "step"]
+        ["gemm_dw", "gemm_da"] * 2 + ["gemm_dw", "step"]
     B.ols_destroy(h)
 
 
