@@ -140,10 +140,14 @@ def mlp_unpack(x, dims):
 def mlp_loss_grad(x, dims, X, labels, bf16_operands=False):
     """ReLU MLP with softmax cross-entropy, mean over the batch.
 
-    Returns (loss, flat gradient in the layout of `x`).  With bf16_operands the
-    two operands of every matrix product are first rounded to bfloat16 (weights,
-    activations, back-propagated deltas); products and sums stay in double.
-    This is a diagnostic mode for the bf16-GEMM device path, not the gate.
+    Returns (loss, flat gradient in the layout of `x`).
+
+    bf16_operands is a DIAGNOSTIC mode for a device path that feeds its hidden-layer matrix
+    products with bfloat16 operands: the stored activations and back-propagated deltas of the
+    hidden layers, and the weights of the hidden layers, are rounded to bfloat16 wherever they
+    enter a product (or a bias-gradient sum, which reads the stored delta); products and sums
+    stay in double, and the output layer keeps its weights and its delta unrounded.  The gate for
+    such a path is still the unrounded computation (bf16_operands=False).
     """
     q = round_to_bf16 if bf16_operands else (lambda a: np.asarray(a, F64))
     x = np.asarray(x, F64)
@@ -152,8 +156,9 @@ def mlp_loss_grad(x, dims, X, labels, bf16_operands=False):
     B = X.shape[0]
     acts = [np.asarray(X, F64)]
     for l, (W, b) in enumerate(layers):
-        pre = q(acts[-1]) @ q(W) + b
-        acts.append(np.maximum(pre, 0.0) if l < L - 1 else pre)
+        hidden = l < L - 1
+        pre = q(acts[-1]) @ (q(W) if hidden else W) + b
+        acts.append(np.maximum(pre, 0.0) if hidden else pre)
     logits = acts[-1]
     shifted = logits - logits.max(axis=1, keepdims=True)
     logsumexp = np.log(np.exp(shifted).sum(axis=1))
@@ -165,12 +170,14 @@ def mlp_loss_grad(x, dims, X, labels, bf16_operands=False):
     g = np.empty_like(x)
     g_layers = mlp_unpack(g, dims)
     for l in range(L - 1, -1, -1):
+        hidden = l < L - 1
         W, _ = layers[l]
         gW, gb = g_layers[l]
-        gW[...] = q(acts[l]).T @ q(delta)
-        gb[...] = delta.sum(axis=0)
+        d_in = q(delta) if hidden else delta
+        gW[...] = q(acts[l]).T @ d_in
+        gb[...] = d_in.sum(axis=0)
         if l > 0:
-            delta = (q(delta) @ q(W).T) * (acts[l] > 0.0)
+            delta = (d_in @ (q(W) if hidden else W).T) * (acts[l] > 0.0)
     return loss, g
 
 

@@ -434,3 +434,25 @@ def test_fp32_store_rounds_once_per_update():
         np.testing.assert_array_equal(st["x"][i], (half - 0.6 * (half - x64)).astype(np.float32))
         np.testing.assert_array_equal(st["buf"][i], buf.astype(np.float32))
     assert st["x"].dtype == np.float32 and st["z"].dtype == np.float32
+
+
+def test_bf16_diagnostic_mode():
+    """The bf16-operand mode rounds only what enters hidden-layer products: with no hidden layer
+    and bf16-representable inputs it changes nothing; on a small MLP it stays within bf16
+    rounding of the exact gradient."""
+    dims = (8, 5)
+    x = rand(8 * 5 + 5, 190)
+    X = O.round_to_bf16(rand((6, 8), 191).astype(np.float32))
+    lab = np.random.default_rng(192).integers(0, 5, 6)
+    a = O.mlp_loss_grad(x, dims, X, lab)
+    b = O.mlp_loss_grad(x, dims, X, lab, bf16_operands=True)
+    assert a[0] == b[0] and np.array_equal(a[1], b[1])
+    dims = (16, 12, 10, 4)
+    d = sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(3))
+    x = 0.4 * rand(d, 193)
+    X = rand((8, 16), 194)
+    lab = np.random.default_rng(195).integers(0, 4, 8)
+    a = O.mlp_loss_grad(x, dims, X, lab)
+    b = O.mlp_loss_grad(x, dims, X, lab, bf16_operands=True)
+    assert abs(a[0] - b[0]) < 2e-2 * abs(a[0]) and a[0] != b[0]
+    assert np.abs(a[1] - b[1]).max() < 3e-2 * np.abs(a[1]).max()
