@@ -48,7 +48,8 @@ struct GemmDevB {
     uint16_t* c_t;
     const float* bias;
     const uint16_t* mask;
-    int64_t sa, sb, sc, sct, sbias, smask;
+    float* colsum;
+    int64_t sa, sb, sc, sct, sbias, smask, scolsum;
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
 };
@@ -169,6 +170,11 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    // DW only: the first tile row also sums each row of Bt (a delta column over the batch), which is
+    // the bias gradient of the layer, in sample order.
+    const bool row_sums = MODE == kDw && p.colsum != nullptr && tm == 0 && threadIdx.x < BN;
+    float row_acc = 0.0f;
+
     u4 ra[TA::kPerThread];
     u4 rbk[TBK::kPerThread];
     typename TBN::Regs rbn;
@@ -208,9 +214,20 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
                                                                         __builtin_bit_cast(bf16x8, fb[j]), acc[i][j],
                                                                         0, 0, 0);
         }
+        if (MODE == kDw && row_sums) {
+            const uint16_t* row = lds_b[cur] + threadIdx.x * kPitch;
+#pragma unroll
+            for (int k = 0; k < BK; k += 2) {
+                const unsigned int pair = *(const unsigned int*)(row + k);
+                row_acc += bf16_to_f32(pair & 0xFFFFu);
+                row_acc += bf16_to_f32(pair >> 16);
+            }
+        }
         if (kt + 1 < nk) store_tiles(cur ^ 1);
         __syncthreads();
     }
+    if (MODE == kDw && row_sums && n0 + (int)threadIdx.x < p.N)
+        p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = row_acc;
 
     // Epilogue.  Accumulator register r of a lane is C[row][col] with col = lane % 32 and
     // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block: four consecutive rows per r / 4.
@@ -276,7 +293,9 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     p.c_t = MODE == kDw ? nullptr : (uint16_t*)g.c_t;
     p.bias = g.bias;
     p.mask = (const uint16_t*)g.mask;
+    p.colsum = MODE == kDw ? g.colsum : nullptr;
     p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sct = g.sct; p.sbias = g.sbias; p.smask = g.smask;
+    p.scolsum = g.scolsum;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
     p.tiles_m = (g.M + BM - 1) / BM;
     p.tiles_n = (g.N + BN - 1) / BN;

@@ -76,15 +76,22 @@ __global__ __launch_bounds__(kThreads) void head_fwd_kernel(const void* __restri
         const float logit = lane < C ? s_logit[wave][j][lane] + bias : -INFINITY;
         float mx = logit;
         for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-        const float ex = lane < C ? expf(logit - mx) : 0.0f;
-        float sum = ex;
-        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, kWave);
         const int label = labels[(int64_t)i * label_stride + s];
+        const float ex = lane < C ? expf(logit - mx) : 0.0f;
+        // Sum of the other classes' terms separately: near convergence softmax[label] is within an ulp
+        // of 1, and both the loss log(1 + others / own) and the label's delta -(others / total) keep
+        // full relative accuracy this way, where log(total) - logit and softmax - 1 would cancel.
+        float others = lane == label ? 0.0f : ex;
+        for (int off = 32; off >= 1; off >>= 1) others += __shfl_xor(others, off, kWave);
+        const float own = __shfl(ex, label, kWave);
+        const float sum = others + own;
         const float picked = __shfl(logit, label, kWave);
-        if (lane == 0) loss_parts[(int64_t)i * B + s] = (logf(sum) + mx) - picked;
+        if (lane == 0) {
+            loss_parts[(int64_t)i * B + s] = own > 1e-30f ? log1pf(others / own) : (logf(sum) + mx) - picked;
+        }
         if (lane < C) {
-            const float p = ex / sum;
-            dlogits[((int64_t)i * B + s) * C + lane] = (p - (lane == label ? 1.0f : 0.0f)) / (float)B;
+            const float d = lane == label ? -(others / sum) : ex / sum;
+            dlogits[((int64_t)i * B + s) * C + lane] = d / (float)B;
         }
     }
 }

@@ -335,10 +335,9 @@ int compute_gradients(ols_ctx* c) {
         gw.c = c->g + c->w_off[l];
         gw.sc = c->ld;
         gw.ldc = c->dims[l + 1];
-        if (!bf) {  // the fp32 kernel reduces the bias gradient while the delta streams through LDS
-            gw.colsum = c->g + c->b_off[l];
-            gw.scolsum = c->ld;
-        }
+        // the kernel also reduces the bias gradient while the delta streams through LDS
+        gw.colsum = c->g + c->b_off[l];
+        gw.scolsum = c->ld;
         gw.groups = m;
         gw.M = c->dims[l];
         gw.N = c->dims[l + 1];
@@ -346,12 +345,6 @@ int compute_gradients(ols_ctx* c) {
         rc = enqueue(c, OLS_K_GEMM_DW, 0, -1, -1,
                      [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s) : launch_gemm_f32_dw(gw, s, c->gemm_variant[1]); });
         if (rc) return rc;
-        if (bf) {
-            rc = enqueue(c, OLS_K_BIAS_GRAD, 0, -1, -1, [&](hipStream_t s) {
-                return launch_bias_grad(dz, bf, dz_stride, c->g, c->ld, c->b_off[l], m, B, c->dims[l + 1], s);
-            });
-            if (rc) return rc;
-        }
         if (l > 0) {
             GemmArgs gd = {};
             gd.a = dz;
