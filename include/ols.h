@@ -75,7 +75,9 @@ enum {
                                   default 0                                                                   */
     OLS_OPT_GEMM_VARIANT_FWD = 9,  /* tile-shape variant of the forward / weight-gradient / delta GEMM kernels; */
     OLS_OPT_GEMM_VARIANT_DW = 10,  /* 0 (default) is the tuned choice, other values exist for re-measurement;  */
-    OLS_OPT_GEMM_VARIANT_DA = 11   /* an unknown variant makes the next local step fail with OLS_EHIP          */
+    OLS_OPT_GEMM_VARIANT_DA = 11,  /* an unknown variant makes the next local step fail with OLS_EHIP          */
+    OLS_OPT_GEMM_SPLITK = 12       /* fp32 forward GEMM: K ranges per output tile where the shape calls for
+                                      splitting (0 = from the shape, 1 = never, up to 8)                       */
 };
 
 /* kernel kinds for ols_kernel_stats / the launch trace */

@@ -38,8 +38,10 @@ struct GemmDev {
     const float* mask;
     float* colsum;
     int64_t sa, sb, sc, sbias, smask, scolsum;
+    float* partial;      // split-K: raw partial sums [split][group][M][N]
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
+    int splits, k_chunk, groups;
 };
 
 // One operand tile of ROWS x BK in LDS.  KC: stored [ROWS][BK + 4]; RC: stored [BK][ROWS + 4].
@@ -54,32 +56,35 @@ struct Tile {
     static constexpr int kFloats = kLines * kPitch;
 
     // Global -> registers.  `base` points at the operand of this group; (row0, k0) is the tile origin;
-    // rows / klen bound the valid region (zero fill outside).  Row and k extents are multiples of 4.
-    __device__ static void load(f4 (&r)[kPerThread], const float* __restrict__ base, int ld, int row0, int k0,
-                                int rows, int klen) {
+    // rows / klen bound the valid region.  Row and k extents are multiples of 4.
+    // Every lane ALWAYS issues its load (out-of-range lanes re-read the operand's first vector) and the
+    // zero fill is applied only when the registers are written to LDS: with no branch around the loads
+    // and no use of their result in between, the compiler can count outstanding loads and let a later
+    // slice's loads stay in flight while an earlier slice is stored.
+    __device__ static unsigned load(f4 (&r)[kPerThread], const float* __restrict__ base, int ld, int row0, int k0,
+                                    int rows, int klen) {
+        unsigned okmask = 0;
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
             const int v = threadIdx.x + t * kThreads;
-            f4 val = {0.f, 0.f, 0.f, 0.f};
-            if (kVecs % kThreads == 0 || v < kVecs) {
-                const int line = v / kVecPerLine, off = (v % kVecPerLine) * 4;
-                const int row = KC ? row0 + line : row0 + off;
-                const int k = KC ? k0 + off : k0 + line;
-                if (row < rows && k < klen) {
-                    const int64_t idx = KC ? (int64_t)row * ld + k : (int64_t)k * ld + row;
-                    val = *(const f4*)(base + idx);
-                }
-            }
-            r[t] = val;
+            const int line = v / kVecPerLine, off = (v % kVecPerLine) * 4;
+            const int row = KC ? row0 + line : row0 + off;
+            const int k = KC ? k0 + off : k0 + line;
+            const bool ok = (kVecs % kThreads == 0 || v < kVecs) && row < rows && k < klen;
+            const int64_t idx = KC ? (int64_t)row * ld + k : (int64_t)k * ld + row;
+            r[t] = *(const f4*)(base + (ok ? idx : 0));
+            okmask |= ok ? (1u << t) : 0u;
         }
+        return okmask;
     }
-    __device__ static void store(float* lds, const f4 (&r)[kPerThread]) {
+    __device__ static void store(float* lds, const f4 (&r)[kPerThread], unsigned okmask) {
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
             const int v = threadIdx.x + t * kThreads;
             if (kVecs % kThreads == 0 || v < kVecs) {
                 const int line = v / kVecPerLine, off = (v % kVecPerLine) * 4;
-                *(f4*)(lds + line * kPitch + off) = r[t];
+                const f4 zero = {0.f, 0.f, 0.f, 0.f};
+                *(f4*)(lds + line * kPitch + off) = (okmask >> t) & 1u ? r[t] : zero;
             }
         }
     }
@@ -97,7 +102,7 @@ struct Tile {
     }
 };
 
-template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int DEPTH, int NACC>
+template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int DEPTH>
 __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     constexpr bool A_KC = MODE != kDw;   // FWD, DA: A[M][K];  DW: A[K][M]
     constexpr bool B_KC = MODE == kDa;   // DA: B[N][K];  FWD, DW: B[K][N]
@@ -115,10 +120,13 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const int tile = xcd * p.chunk + slot;
     if (slot >= p.chunk || tile >= p.total_tiles) return;
-    const int per_group = p.tiles_m * p.tiles_n;
+    const int per_split = p.tiles_m * p.tiles_n, per_group = per_split * p.splits;
     const int group = tile / per_group;
-    const int tm = (tile % per_group) / p.tiles_n, tn = tile % p.tiles_n;
+    const int split = (tile % per_group) / per_split;
+    const int tm = (tile % per_split) / p.tiles_n, tn = tile % p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
+    // split-K: this workgroup contracts over [k_lo, k_hi) only and leaves a raw partial sum
+    const int k_lo = split * p.k_chunk, k_hi = min(p.K, k_lo + p.k_chunk);
 
     const float* A = p.a + (int64_t)group * p.sa;
     const float* B = p.b + (int64_t)group * p.sb;
@@ -127,17 +135,13 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     const int lane32 = lane % 32, half = lane / 32;
     const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
-    // NACC independent accumulator chains per 32 x 32 block (alternate MFMA steps), summed at the end: a
-    // wavefront whose tile is a single block would otherwise issue only dependent MFMAs back to back.
-    f16v acc[TM][TN][NACC];
+    f16v acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int a = 0; a < NACC; ++a)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][a][r] = 0.0f;
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     // DW only: the tiles of the first tile row also reduce the columns of B over the batch, which is
     // the bias gradient of the layer (sum over samples of the delta), in sample order.
@@ -164,14 +168,14 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j][e % NACC] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[buf][i][e], fb[buf][j][e],
-                                                                               acc[i][j][e % NACC], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[buf][i][e], fb[buf][j][e], acc[i][j], 0, 0, 0);
     };
     // One K slice out of lds[cur].  On entry the fragments of octet 0 are already in (or on their way
     // to) buffer 0.  Before the last octet's MFMAs the staged registers of the next slice are published
     // to lds[cur ^ 1], the workgroup synchronises once, and the first fragments of that slice are
     // requested, so the barrier and the LDS latency hide behind the remaining MFMAs.
-    auto slice = [&](int cur, const f4 (&na)[TA::kPerThread], const f4 (&nb)[TB::kPerThread], bool has_next) {
+    auto slice = [&](int cur, const f4 (&na)[TA::kPerThread], unsigned oka, const f4 (&nb)[TB::kPerThread],
+                     unsigned okb) {
 #pragma unroll
         for (int q = 0; q + 1 < Q; ++q) {
             load_frags((q + 1) & 1, cur, q + 1);
@@ -183,76 +187,62 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
 #pragma unroll
             for (int k = 0; k < BK; ++k) col_acc += lds_b[cur][k * TB::kPitch + threadIdx.x];
         }
-        if (has_next) {
-            TA::store(lds_a[cur ^ 1], na);
-            TB::store(lds_b[cur ^ 1], nb);
-        }
+        TA::store(lds_a[cur ^ 1], na, oka);
+        TB::store(lds_b[cur ^ 1], nb, okb);
         __syncthreads();
-        if (has_next) load_frags(0, cur ^ 1, 0);
+        load_frags(0, cur ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
         mfmas((Q - 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int nk = (p.K + BK - 1) / BK;
+    // The loop bodies below are free of data-dependent branches: loads past the end of the K range are
+    // zero-filled dummies and the tile published after the last slice is never consumed.
+    const int nk = (k_hi - k_lo + BK - 1) / BK;
     if (DEPTH == 1) {
         f4 ra[TA::kPerThread], rb[TB::kPerThread];
-        TA::load(ra, A, p.lda, m0, 0, p.M, p.K);
-        TB::load(rb, B, p.ldb, n0, 0, p.N, p.K);
-        TA::store(lds_a[0], ra);
-        TB::store(lds_b[0], rb);
+        unsigned oka = TA::load(ra, A, p.lda, m0, k_lo, p.M, k_hi);
+        unsigned okb = TB::load(rb, B, p.ldb, n0, k_lo, p.N, k_hi);
+        TA::store(lds_a[0], ra, oka);
+        TB::store(lds_b[0], rb, okb);
         __syncthreads();
         load_frags(0, 0, 0);
         for (int kt = 0; kt < nk; ++kt) {
-            const bool has_next = kt + 1 < nk;
-            if (has_next) {
-                TA::load(ra, A, p.lda, m0, (kt + 1) * BK, p.M, p.K);
-                TB::load(rb, B, p.ldb, n0, (kt + 1) * BK, p.N, p.K);
-            }
-            slice(kt & 1, ra, rb, has_next);
+            oka = TA::load(ra, A, p.lda, m0, k_lo + (kt + 1) * BK, p.M, k_hi);
+            okb = TB::load(rb, B, p.ldb, n0, k_lo + (kt + 1) * BK, p.N, k_hi);
+            slice(kt & 1, ra, oka, rb, okb);
         }
     } else {
         // Two K slices of global loads in flight: while slice t feeds the matrix cores from LDS, slice
-        // t+1 waits in registers and slice t+2 is on its way from HBM.
+        // t+1 waits in registers and slice t+2 is on its way from HBM.  Slices are consumed in pairs; an
+        // odd trailing slice is paired with an all-zero one.
         f4 ra0[TA::kPerThread], rb0[TB::kPerThread], ra1[TA::kPerThread], rb1[TB::kPerThread];
-        TA::load(ra0, A, p.lda, m0, 0, p.M, p.K);
-        TB::load(rb0, B, p.ldb, n0, 0, p.N, p.K);
-        TA::load(ra1, A, p.lda, m0, BK, p.M, p.K);   // zero fill when K <= BK
-        TB::load(rb1, B, p.ldb, n0, BK, p.N, p.K);
-        TA::store(lds_a[0], ra0);
-        TB::store(lds_b[0], rb0);
+        unsigned oka0 = TA::load(ra0, A, p.lda, m0, k_lo, p.M, k_hi);
+        unsigned okb0 = TB::load(rb0, B, p.ldb, n0, k_lo, p.N, k_hi);
+        unsigned oka1 = TA::load(ra1, A, p.lda, m0, k_lo + BK, p.M, k_hi);
+        unsigned okb1 = TB::load(rb1, B, p.ldb, n0, k_lo + BK, p.N, k_hi);
+        TA::store(lds_a[0], ra0, oka0);
+        TB::store(lds_b[0], rb0, okb0);
         __syncthreads();
         load_frags(0, 0, 0);
-        // slices are consumed in pairs; an odd trailing slice is paired with an all-zero one (its loads
-        // fall outside K and are zero-filled), which keeps the loop body free of data-dependent exits
         const int nk2 = (nk + 1) & ~1;
         for (int kt = 0; kt < nk2; kt += 2) {
-            if (kt + 2 < nk2) {
-                TA::load(ra0, A, p.lda, m0, (kt + 2) * BK, p.M, p.K);
-                TB::load(rb0, B, p.ldb, n0, (kt + 2) * BK, p.N, p.K);
-            }
-            slice(0, ra1, rb1, true);
-            if (kt + 3 < nk2) {
-                TA::load(ra1, A, p.lda, m0, (kt + 3) * BK, p.M, p.K);
-                TB::load(rb1, B, p.ldb, n0, (kt + 3) * BK, p.N, p.K);
-            }
-            slice(1, ra0, rb0, kt + 2 < nk2);
+            oka0 = TA::load(ra0, A, p.lda, m0, k_lo + (kt + 2) * BK, p.M, k_hi);
+            okb0 = TB::load(rb0, B, p.ldb, n0, k_lo + (kt + 2) * BK, p.N, k_hi);
+            slice(0, ra1, oka1, rb1, okb1);
+            oka1 = TA::load(ra1, A, p.lda, m0, k_lo + (kt + 3) * BK, p.M, k_hi);
+            okb1 = TB::load(rb1, B, p.ldb, n0, k_lo + (kt + 3) * BK, p.N, k_hi);
+            slice(1, ra0, oka0, rb0, okb0);
         }
-    }
-    if (NACC > 1) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int a = 1; a < NACC; ++a) acc[i][j][0] = acc[i][j][0] + acc[i][j][a];
     }
     if (MODE == kDw && col_sums && n0 + (int)threadIdx.x < p.N)
         p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = col_acc;
 
     // Epilogue.  Accumulator register r of a lane holds C[row][col] with col = lane % 32 and
     // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block.
-    float* C = p.c + (int64_t)group * p.sc;
+    const bool raw = MODE == kFwd && p.splits > 1;
+    float* C = raw ? p.partial + ((int64_t)split * p.groups + group) * p.M * p.N : p.c + (int64_t)group * p.sc;
+    const int ldc = raw ? p.N : p.ldc;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -260,23 +250,44 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
             const int col = n0 + wn0 + 32 * j + lane32;
             if (col >= p.N) continue;
             float bias = 0.0f;
-            if (MODE == kFwd) bias = p.bias[(int64_t)group * p.sbias + col];
+            if (MODE == kFwd && !raw) bias = p.bias[(int64_t)group * p.sbias + col];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
                 if (row >= p.M) continue;
-                float v = acc[i][j][0][r];
-                if (MODE == kFwd) v = fmaxf(v + bias, 0.0f);
+                float v = acc[i][j][r];
+                if (MODE == kFwd && !raw) v = fmaxf(v + bias, 0.0f);
                 if (MODE == kDa) v = p.mask[(int64_t)group * p.smask + (int64_t)row * p.ldc + col] > 0.0f ? v : 0.0f;
-                C[(int64_t)row * p.ldc + col] = v;
+                C[(int64_t)row * ldc + col] = v;
             }
         }
     }
 }
 
+// out[g][row][col] = relu(sum_s partial[s][g][row][col] + bias[g][col]); one lane per 4 columns
+__global__ __launch_bounds__(kThreads) void splitk_finish_kernel(const f4* __restrict__ partial, int splits,
+                                                                 const float* __restrict__ bias, int64_t sbias,
+                                                                 float* __restrict__ out, int64_t sc, int ldc, int groups,
+                                                                 int M, int N) {
+    const int n4 = N / 4;
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t per_split = (int64_t)groups * M * n4;
+    if (v >= per_split) return;
+    const int c4 = (int)(v % n4);
+    const int row = (int)((v / n4) % M);
+    const int g = (int)(v / ((int64_t)n4 * M));
+    f4 acc = partial[v];
+    for (int s = 1; s < splits; ++s) acc = acc + partial[(int64_t)s * per_split + v];
+    const f4 b = *(const f4*)(bias + (int64_t)g * sbias + 4 * c4);
+    f4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = fmaxf(acc[e] + b[e], 0.0f);
+    *(f4*)(out + (int64_t)g * sc + (int64_t)row * ldc + 4 * c4) = r;
+}
+
 static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
-template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int DEPTH, int NACC = 1>
+template <int MODE, int BM, int BN, int BK, int WAVES_M, int WAVES_N, int DEPTH>
 static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (!g.a || !g.b || !g.c || g.groups < 1 || g.M < 1 || g.N < 1 || g.K < 1) return hipErrorInvalidValue;
     // 16-byte vector loads: every line start must be aligned and extents multiples of 4
@@ -297,32 +308,68 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
     p.tiles_m = (g.M + BM - 1) / BM;
     p.tiles_n = (g.N + BN - 1) / BN;
-    const int64_t total = (int64_t)g.groups * p.tiles_m * p.tiles_n;
+    p.groups = g.groups;
+    p.splits = 1;
+    p.k_chunk = g.K;
+    p.partial = nullptr;
+    if (MODE == kFwd && g.splits > 1) {
+        if (!g.partial) return hipErrorInvalidValue;
+        p.k_chunk = (int)round_up((g.K + g.splits - 1) / g.splits, BK);
+        p.splits = (g.K + p.k_chunk - 1) / p.k_chunk;   // never an empty split
+        p.partial = g.partial;
+    }
+    const int64_t total = (int64_t)g.groups * p.splits * p.tiles_m * p.tiles_n;
     if (total > (1 << 30)) return hipErrorInvalidValue;
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
-    gemm_f32_kernel<MODE, BM, BN, BK, WAVES_M, WAVES_N, DEPTH, NACC><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
+    gemm_f32_kernel<MODE, BM, BN, BK, WAVES_M, WAVES_N, DEPTH><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.splits == 1) return e;
+    // second pass of a split-K forward GEMM: sum the partials, add the bias, apply the ReLU
+    const int64_t vecs = (int64_t)g.groups * g.M * (g.N / 4);
+    splitk_finish_kernel<<<(unsigned)((vecs + kThreads - 1) / kThreads), kThreads, 0, s>>>(
+        (const f4*)p.partial, p.splits, g.bias, g.sbias, (float*)g.c, g.sc, g.ldc, g.groups, g.M, g.N);
     return hipGetLastError();
 }
 
-// Tile shapes.  Variant 0 is the default; the others exist so that the choice can be re-measured
+// Tile shapes.  Variant 0 is the default (for the forward GEMM: chosen from the shape); the others exist so
+// that the choice can be re-measured
 // (OLS_OPT_GEMM_VARIANT_*).  LDS per workgroup stays below 80 KiB so two workgroups fit a compute unit.
+// Shape-driven choice for the forward GEMM.  Measured on configuration 2 (M = 128, N = 512, K = 3072,
+// 16 groups): every tile shape lands within a few percent once there are several workgroups per compute
+// unit, because the matrix pipe idles whenever a wavefront waits at the slice barrier or for its loads
+// and only other resident workgroups fill those gaps; so: 64 x 64 tiles, and K ranges until the launch
+// has about four workgroups per compute unit.
+void gemm_f32_fwd_plan(int groups, int M, int N, int K, int* variant, int* splits) {
+    *variant = 2;
+    const int64_t tiles = (int64_t)groups * ((M + 63) / 64) * ((N + 63) / 64);
+    int s = 1;
+    while (tiles * s < 1024 && K / (2 * s) >= 256 && s < 8) s *= 2;
+    *splits = s;
+}
+
 hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s, int variant) {
+    if (variant == 0) {
+        int sp;
+        gemm_f32_fwd_plan(g.groups, g.M, g.N, g.K, &variant, &sp);
+    }
     switch (variant) {
-        case 0: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 2>(g, s);
-        case 1: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 2>(g, s);
-        case 2: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 1>(g, s);
-        case 3: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 1>(g, s);
-        case 4: return gemm_launch<kFwd, 128, 64, 32, 2, 2, 2>(g, s);
-        case 5: return gemm_launch<kFwd, 64, 128, 32, 2, 2, 2>(g, s);
-        case 6: return gemm_launch<kFwd, 128, 128, 16, 2, 2, 2>(g, s);
+        case 1: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 2>(g, s);
+        case 2: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 2>(g, s);
+        case 3: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 1>(g, s);
+        case 4: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 1>(g, s);
+        case 5: return gemm_launch<kFwd, 128, 64, 32, 2, 2, 2>(g, s);
+        case 6: return gemm_launch<kFwd, 64, 128, 32, 2, 2, 2>(g, s);
+        case 7: return gemm_launch<kFwd, 128, 128, 16, 2, 2, 2>(g, s);
+        case 8: return gemm_launch<kFwd, 128, 128, 32, 2, 2, 2>(g, s);
+        case 9: return gemm_launch<kFwd, 128, 128, 32, 2, 2, 1>(g, s);
         default: return hipErrorInvalidValue;
     }
 }
 hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant) {
     switch (variant) {
-        case 0: return gemm_launch<kDw, 128, 128, 16, 2, 2, 2>(g, s);
-        case 1: return gemm_launch<kDw, 128, 128, 16, 2, 2, 1>(g, s);
+        case 0: return gemm_launch<kDw, 128, 128, 16, 2, 2, 1>(g, s);
+        case 1: return gemm_launch<kDw, 128, 128, 16, 2, 2, 2>(g, s);
         case 2: return gemm_launch<kDw, 128, 128, 32, 2, 2, 2>(g, s);
         case 3: return gemm_launch<kDw, 128, 128, 32, 2, 2, 1>(g, s);
         case 4: return gemm_launch<kDw, 64, 128, 32, 2, 2, 2>(g, s);

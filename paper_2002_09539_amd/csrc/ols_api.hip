@@ -14,6 +14,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -62,6 +63,9 @@ struct ols_ctx {
          fuse_mean = false;
     int mean_split = 0;
     int gemm_variant[3] = {0, 0, 0};  // fwd, dw, da
+    int splitk = 0;                   // 0: from the shape
+    std::vector<int> fwd_splits;      // planned K ranges per hidden layer (fp32 forward GEMM)
+    int64_t off_partial = 0;
     // schedule
     int64_t k = 0;
     bool pull_due = false, pending_update = false, anchor_due = false, anchor_inflight = false,
@@ -219,6 +223,17 @@ void plan_workspace(ols_ctx* c) {
                 c->off_dz_t[l] = take(m * B * c->dims[l] * es);
             }
         }
+        c->fwd_splits.assign(L, 1);
+        if (!bf) {  // scratch for the split-K forward GEMMs: room for up to 8 K ranges where splitting is planned
+            int64_t need_partial = 0;
+            for (int l = 0; l < L - 1; ++l) {
+                int variant, splits;
+                gemm_f32_fwd_plan(c->m, c->B, c->dims[l + 1], c->dims[l], &variant, &splits);
+                c->fwd_splits[l] = splits;
+                if (splits > 1) need_partial = std::max<int64_t>(need_partial, 8 * m * B * c->dims[l + 1] * 4);
+            }
+            if (need_partial) c->off_partial = take(need_partial);
+        }
         if (bf) {
             c->off_x0 = take(m * B * c->dims[0] * 2);
             c->off_x0_t = take(m * B * c->dims[0] * 2);
@@ -284,6 +299,10 @@ int compute_gradients(ols_ctx* c) {
         ga.M = B;
         ga.N = c->dims[l + 1];
         ga.K = c->dims[l];
+        if (!bf && c->fwd_splits[l] > 1) {  // a forced count applies only where scratch was planned
+            ga.splits = c->splitk > 0 ? c->splitk : c->fwd_splits[l];
+            ga.partial = (float*)(c->ws + c->off_partial);
+        }
         rc = enqueue(c, OLS_K_GEMM_FWD, 0, c->cur, -1,
                      [&](hipStream_t s) { return bf ? launch_gemm_bf16_fwd(ga, s) : launch_gemm_f32_fwd(ga, s, c->gemm_variant[0]); });
         if (rc) return rc;
@@ -810,6 +829,10 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
         case OLS_OPT_GEMM_VARIANT_DA:
             if (value < 0 || value > 15) return fail(OLS_EINVAL, "GEMM variant out of range");
             c->gemm_variant[key - OLS_OPT_GEMM_VARIANT_FWD] = (int)value;
+            break;
+        case OLS_OPT_GEMM_SPLITK:
+            if (value < 0 || value > 8) return fail(OLS_EINVAL, "split-K count must be in [0, 8]");
+            c->splitk = (int)value;
             break;
         case OLS_OPT_FUSE_MEAN:
             if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "cannot change fusion in the middle of a synchronisation");

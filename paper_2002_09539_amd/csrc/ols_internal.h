@@ -67,6 +67,8 @@ struct GemmArgs {
     const void* mask;   // dA: activations whose sign gates the output, same shape as c, stride smask
     void* c_t;          // bf16 only: optional transposed copy of the output [N][M], stride sct (or nullptr)
     float* colsum;      // dw: optional [N] per group, receives the column sums of B (the bias gradient)
+    float* partial;     // fp32 fwd with splits > 1: scratch of splits * groups * M * N floats
+    int splits;         // fp32 fwd: number of K ranges contracted by separate workgroups (<= 1: none)
     int64_t sa, sb, sc, sbias, smask, sct, scolsum;
     int groups;
     int M, N, K;        // output M x N, contraction length K
@@ -75,6 +77,7 @@ struct GemmArgs {
 // fp32 MFMA.  fwd: C[M][N] = relu(A[M][K] W[K][N] + bias);  dw: C[M][N] = A[K][M]^T B[K][N];
 // da: C[M][N] = (A[M][K] B[N][K]^T) * (mask > 0)
 hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s, int variant);
+void gemm_f32_fwd_plan(int groups, int M, int N, int K, int* variant, int* splits);
 hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant);
 hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s, int variant);
 // bf16 operands, fp32 accumulate
