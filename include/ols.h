@@ -76,8 +76,13 @@ enum {
     OLS_OPT_GEMM_VARIANT_FWD = 9,  /* tile-shape variant of the forward / weight-gradient / delta GEMM kernels; */
     OLS_OPT_GEMM_VARIANT_DW = 10,  /* 0 (default) is the tuned choice, other values exist for re-measurement;  */
     OLS_OPT_GEMM_VARIANT_DA = 11,  /* an unknown variant makes the next local step fail with OLS_EHIP          */
-    OLS_OPT_GEMM_SPLITK = 12       /* fp32 forward GEMM: K ranges per output tile where the shape calls for
+    OLS_OPT_GEMM_SPLITK = 12,      /* fp32 forward GEMM: K ranges per output tile where the shape calls for
                                       splitting (0 = from the shape, 1 = never, up to 8)                       */
+    OLS_OPT_FUSE_GEMM_UPDATE = 13  /* 1 (default): with an attached MLP the kernels that form the gradients apply
+                                      the local step (and on the tau-th step the pull-back) where each gradient
+                                      element is produced, so g is never written nor re-read and ols_sync_pull only
+                                      publishes the result; 0: gradients go to g and the streaming kernels update.
+                                      Both routes execute the same fp32 operation sequence per element.           */
 };
 
 /* kernel kinds for ols_kernel_stats / the launch trace */

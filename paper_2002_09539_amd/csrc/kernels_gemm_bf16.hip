@@ -20,6 +20,7 @@
 // The epilogues that produce bf16 activations / deltas also write the transposed copy the
 // weight-gradient GEMM needs (an accumulator lane holds 4 consecutive rows of one column, i.e. one
 // 8-byte piece of the transposed matrix).
+#include "gemm_epilogue.h"
 #include "ols_internal.h"
 
 namespace ols {
@@ -49,6 +50,8 @@ struct GemmDevB {
     const float* bias;
     const uint16_t* mask;
     float* colsum;
+    FusedUpdate upd;     // DW: update applied in the epilogue instead of storing the gradient
+    int64_t upd_w_off, upd_b_off;
     int64_t sa, sb, sc, sct, sbias, smask, scolsum;
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
@@ -145,8 +148,10 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
     using TBK = TileKC<BN, BK>;
     using TBN = TileNC<BN, BK>;
     constexpr int kPitch = TA::kPitch;
-    __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][TA::kElems];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][TBK::kElems];
+    constexpr int kLdsElems = 2 * TA::kElems + 2 * TBK::kElems;
+    __shared__ __attribute__((aligned(16))) uint16_t lds_all[kLdsElems];
+    auto lds_a = [&](int buf) { return lds_all + buf * TA::kElems; };
+    auto lds_b = [&](int buf) { return lds_all + 2 * TA::kElems + buf * TBK::kElems; };
 
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const int tile = xcd * p.chunk + slot;
@@ -184,9 +189,9 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
         else TBK::load(rbk, B, p.ldb, n0, k0, p.N, p.K);
     };
     auto store_tiles = [&](int buf) {
-        TA::store(lds_a[buf], ra);
-        if (MODE == kFwd) TBN::store(lds_b[buf], rbn);
-        else TBK::store(lds_b[buf], rbk);
+        TA::store(lds_a(buf), ra);
+        if (MODE == kFwd) TBN::store(lds_b(buf), rbn);
+        else TBK::store(lds_b(buf), rbk);
     };
     auto frag = [&](const uint16_t* lds, int r0, int s) {
         return *(const u4*)(lds + (r0 + lane32) * kPitch + 16 * s + 8 * half);
@@ -203,9 +208,9 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
         for (int s = 0; s < S; ++s) {
             u4 fa[TM], fb[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = frag(lds_a[cur], wm0 + 32 * i, s);
+            for (int i = 0; i < TM; ++i) fa[i] = frag(lds_a(cur), wm0 + 32 * i, s);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = frag(lds_b[cur], wn0 + 32 * j, s);
+            for (int j = 0; j < TN; ++j) fb[j] = frag(lds_b(cur), wn0 + 32 * j, s);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -215,7 +220,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
                                                                         0, 0, 0);
         }
         if (MODE == kDw && row_sums) {
-            const uint16_t* row = lds_b[cur] + threadIdx.x * kPitch;
+            const uint16_t* row = lds_b(cur) + threadIdx.x * kPitch;
 #pragma unroll
             for (int k = 0; k < BK; k += 2) {
                 const unsigned int pair = *(const unsigned int*)(row + k);
@@ -226,8 +231,27 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
         if (kt + 1 < nk) store_tiles(cur ^ 1);
         __syncthreads();
     }
-    if (MODE == kDw && row_sums && n0 + (int)threadIdx.x < p.N)
-        p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = row_acc;
+    if (MODE == kDw && row_sums && n0 + (int)threadIdx.x < p.N) {
+        if (p.upd.enabled) {   // bias: gradient is the sum just formed
+            const int64_t col = p.upd_b_off + n0 + threadIdx.x, idx = (int64_t)group * p.upd.ld + col;
+            fused_update_apply(p.upd, idx, col, row_acc, p.upd.x_in[idx], p.upd.mu != 0.0f ? p.upd.buf[idx] : 0.0f);
+        } else {
+            p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = row_acc;
+        }
+    }
+    if (MODE == kDw && p.upd.enabled) {
+        constexpr int kFit = ((kLdsElems / 2) / (BN + 4)) / 32 * 32;   // fp32 rows the operand LDS can stage
+        constexpr int RP = kFit >= BM ? BM : kFit;
+        static_assert(RP >= 32, "operand LDS too small to stage the gradient tile");
+        DwOut o;
+        o.g = (float*)p.c + (int64_t)group * p.sc;
+        o.ldg = p.ldc;
+        o.upd = p.upd;
+        o.upd_base = (int64_t)group * p.upd.ld + p.upd_w_off;
+        o.col_base = p.upd_w_off;
+        dw_epilogue_staged<BM, BN, TM, TN, RP, kThreads>((float*)lds_all, acc, o, m0, n0, wm0, wn0, p.M, p.N);
+        return;
+    }
 
     // Epilogue.  Accumulator register r of a lane is C[row][col] with col = lane % 32 and
     // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block: four consecutive rows per r / 4.
@@ -294,6 +318,15 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     p.bias = g.bias;
     p.mask = (const uint16_t*)g.mask;
     p.colsum = MODE == kDw ? g.colsum : nullptr;
+    p.upd = g.upd;
+    p.upd_w_off = g.upd_w_off;
+    p.upd_b_off = g.upd_b_off;
+    if (MODE != kDw) p.upd.enabled = 0;
+    if (p.upd.enabled) {
+        if (!p.upd.x_in || !p.upd.x_out || (p.upd.mu != 0.0f && !p.upd.buf) || (p.upd.pull && !p.upd.z) || !g.colsum ||
+            g.ldc != g.N)
+            return hipErrorInvalidValue;
+    }
     p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sct = g.sct; p.sbias = g.sbias; p.smask = g.smask;
     p.scolsum = g.scolsum;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;

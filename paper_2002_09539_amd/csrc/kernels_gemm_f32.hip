@@ -18,6 +18,7 @@
 //
 // Workgroup ids are remapped so that consecutive tiles of one worker land on the same XCD (workgroups
 // are dealt round-robin to the 8 XCDs, each with its own L2), keeping a worker's weights in one L2.
+#include "gemm_epilogue.h"
 #include "ols_internal.h"
 
 namespace ols {
@@ -39,6 +40,8 @@ struct GemmDev {
     float* colsum;
     int64_t sa, sb, sc, sbias, smask, scolsum;
     float* partial;      // split-K: raw partial sums [split][group][M][N]
+    FusedUpdate upd;     // DW: update applied in the epilogue instead of storing the gradient
+    int64_t upd_w_off, upd_b_off;
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
     int splits, k_chunk, groups;
@@ -113,8 +116,10 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     static_assert(DEPTH == 1 || DEPTH == 2, "global prefetch distance in K slices");
     using TA = Tile<BM, BK, A_KC>;
     using TB = Tile<BN, BK, B_KC>;
-    __shared__ __attribute__((aligned(16))) float lds_a[2][TA::kFloats];
-    __shared__ __attribute__((aligned(16))) float lds_b[2][TB::kFloats];
+    constexpr int kLdsFloats = 2 * TA::kFloats + 2 * TB::kFloats;
+    __shared__ __attribute__((aligned(16))) float lds_all[kLdsFloats];
+    auto lds_a = [&](int buf) { return lds_all + buf * TA::kFloats; };
+    auto lds_b = [&](int buf) { return lds_all + 2 * TA::kFloats + buf * TB::kFloats; };
 
     // XCD-aware tile id: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous tile range
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
@@ -157,9 +162,9 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     f4 fa[2][TM], fb[2][TN];
     auto load_frags = [&](int buf, int cur, int q) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[buf][i] = TA::frag(lds_a[cur], wm0 + 32 * i, q, lane32, half);
+        for (int i = 0; i < TM; ++i) fa[buf][i] = TA::frag(lds_a(cur), wm0 + 32 * i, q, lane32, half);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[buf][j] = TB::frag(lds_b[cur], wn0 + 32 * j, q, lane32, half);
+        for (int j = 0; j < TN; ++j) fb[buf][j] = TB::frag(lds_b(cur), wn0 + 32 * j, q, lane32, half);
     };
     auto mfmas = [&](int buf) {
 #pragma unroll
@@ -185,10 +190,10 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
         }
         if (MODE == kDw && col_sums) {
 #pragma unroll
-            for (int k = 0; k < BK; ++k) col_acc += lds_b[cur][k * TB::kPitch + threadIdx.x];
+            for (int k = 0; k < BK; ++k) col_acc += lds_b(cur)[k * TB::kPitch + threadIdx.x];
         }
-        TA::store(lds_a[cur ^ 1], na, oka);
-        TB::store(lds_b[cur ^ 1], nb, okb);
+        TA::store(lds_a(cur ^ 1), na, oka);
+        TB::store(lds_b(cur ^ 1), nb, okb);
         __syncthreads();
         load_frags(0, cur ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -203,8 +208,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
         f4 ra[TA::kPerThread], rb[TB::kPerThread];
         unsigned oka = TA::load(ra, A, p.lda, m0, k_lo, p.M, k_hi);
         unsigned okb = TB::load(rb, B, p.ldb, n0, k_lo, p.N, k_hi);
-        TA::store(lds_a[0], ra, oka);
-        TB::store(lds_b[0], rb, okb);
+        TA::store(lds_a(0), ra, oka);
+        TB::store(lds_b(0), rb, okb);
         __syncthreads();
         load_frags(0, 0, 0);
         for (int kt = 0; kt < nk; ++kt) {
@@ -221,8 +226,8 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
         unsigned okb0 = TB::load(rb0, B, p.ldb, n0, k_lo, p.N, k_hi);
         unsigned oka1 = TA::load(ra1, A, p.lda, m0, k_lo + BK, p.M, k_hi);
         unsigned okb1 = TB::load(rb1, B, p.ldb, n0, k_lo + BK, p.N, k_hi);
-        TA::store(lds_a[0], ra0, oka0);
-        TB::store(lds_b[0], rb0, okb0);
+        TA::store(lds_a(0), ra0, oka0);
+        TB::store(lds_b(0), rb0, okb0);
         __syncthreads();
         load_frags(0, 0, 0);
         const int nk2 = (nk + 1) & ~1;
@@ -235,8 +240,28 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
             slice(1, ra0, oka0, rb0, okb0);
         }
     }
-    if (MODE == kDw && col_sums && n0 + (int)threadIdx.x < p.N)
-        p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = col_acc;
+    if (MODE == kDw && col_sums && n0 + (int)threadIdx.x < p.N) {
+        if (p.upd.enabled) {   // bias: gradient is the column sum just formed
+            const int64_t col = p.upd_b_off + n0 + threadIdx.x, idx = (int64_t)group * p.upd.ld + col;
+            fused_update_apply(p.upd, idx, col, col_acc, p.upd.x_in[idx], p.upd.mu != 0.0f ? p.upd.buf[idx] : 0.0f);
+        } else {
+            p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = col_acc;
+        }
+    }
+    if (MODE == kDw && p.upd.enabled) {
+        // rows of the tile staged per pass: as many as the operand LDS holds
+        constexpr int kFit = (kLdsFloats / (BN + 4)) / 32 * 32;
+        constexpr int RP = kFit >= BM ? BM : kFit;
+        static_assert(RP >= 32, "operand LDS too small to stage the gradient tile");
+        DwOut o;
+        o.g = p.c + (int64_t)group * p.sc;
+        o.ldg = p.ldc;
+        o.upd = p.upd;
+        o.upd_base = (int64_t)group * p.upd.ld + p.upd_w_off;
+        o.col_base = p.upd_w_off;
+        dw_epilogue_staged<BM, BN, TM, TN, RP, kThreads>(lds_all, acc, o, m0, n0, wm0, wn0, p.M, p.N);
+        return;
+    }
 
     // Epilogue.  Accumulator register r of a lane holds C[row][col] with col = lane % 32 and
     // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block.
@@ -304,6 +329,15 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     p.bias = g.bias;
     p.mask = (const float*)g.mask;
     p.colsum = MODE == kDw ? g.colsum : nullptr;
+    p.upd = g.upd;
+    p.upd_w_off = g.upd_w_off;
+    p.upd_b_off = g.upd_b_off;
+    if (MODE != kDw) p.upd.enabled = 0;
+    if (p.upd.enabled) {
+        if (!p.upd.x_in || !p.upd.x_out || (p.upd.mu != 0.0f && !p.upd.buf) || (p.upd.pull && !p.upd.z) || !g.colsum ||
+            g.ldc != g.N)
+            return hipErrorInvalidValue;
+    }
     p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sbias = g.sbias; p.smask = g.smask; p.scolsum = g.scolsum;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
     p.tiles_m = (g.M + BM - 1) / BM;

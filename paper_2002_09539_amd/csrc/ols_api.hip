@@ -60,7 +60,7 @@ struct ols_ctx {
     bool bound = false, inited = false, launched = false;
     // options
     bool nesterov = true, fuse_pull = true, serialize = false, dry = false, timing = false, trace = false,
-         fuse_mean = false;
+         fuse_mean = false, fuse_gemm_update = true;
     int mean_split = 0;
     int gemm_variant[3] = {0, 0, 0};  // fwd, dw, da
     int splitk = 0;                   // 0: from the shape
@@ -69,7 +69,7 @@ struct ols_ctx {
     // schedule
     int64_t k = 0;
     bool pull_due = false, pending_update = false, anchor_due = false, anchor_inflight = false,
-         first_after_anchor = false, anchor_precomputed = false, next_waited = false;
+         first_after_anchor = false, anchor_precomputed = false, next_waited = false, pulled_in_step = false;
     hipEvent_t ev_pulled = nullptr, ev_anchor_done = nullptr;
     // model
     int model = MODEL_NONE, B = 0, gemm_dtype = 0;
@@ -245,8 +245,11 @@ void plan_workspace(ols_ctx* c) {
     c->ws_need = off;
 }
 
-// Forward + backward of the attached model into g, on the main stream.
-int compute_gradients(ols_ctx* c) {
+// Forward + backward of the attached model on the main stream.  Without `upd` the gradients go to g;
+// with it (MLP only) every gradient element is consumed where it is produced: the kernels that form
+// the weight, bias and output-layer gradients apply the local step (+ pull-back) themselves, reading
+// x[src_buf] and writing x[dst_buf], and g is not written.
+int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_buf) {
     const float* xc = c->x[c->cur];
     const int m = c->m, B = c->B;
     if (c->model == MODEL_LSQ) {
@@ -327,43 +330,16 @@ int compute_gradients(ols_ctx* c) {
     ha.B = B;
     ha.H = c->dims[L - 1];
     ha.C = c->dims[L];
+    if (upd) ha.upd = *upd;
     rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); });
     if (rc) return rc;
-    rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); });
+    rc = enqueue(c, OLS_K_HEAD_BWD, 0, src_buf, upd ? dst_buf : -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); });
     if (rc) return rc;
-    // hidden layers backward
+    // hidden layers backward.  The delta GEMM of a layer reads that layer's weights, so it runs before
+    // the weight-gradient GEMM, which may update them in place.
     for (int l = L - 2; l >= 0; --l) {
         const void* dz = c->ws + c->off_dz[l + 1];
         const int64_t dz_stride = (int64_t)B * c->dims[l + 1];
-        GemmArgs gw = {};
-        if (bf) {  // contraction over the batch wants batch-contiguous operands: the transposed copies
-            gw.a = act_t(l);
-            gw.sa = (int64_t)B * c->dims[l];
-            gw.lda = B;
-            gw.b = c->ws + c->off_dz_t[l + 1];
-            gw.sb = dz_stride;
-            gw.ldb = B;
-        } else {
-            gw.a = act(l);
-            gw.sa = act_stride(l);
-            gw.lda = c->dims[l];
-            gw.b = dz;
-            gw.sb = dz_stride;
-            gw.ldb = c->dims[l + 1];
-        }
-        gw.c = c->g + c->w_off[l];
-        gw.sc = c->ld;
-        gw.ldc = c->dims[l + 1];
-        // the kernel also reduces the bias gradient while the delta streams through LDS
-        gw.colsum = c->g + c->b_off[l];
-        gw.scolsum = c->ld;
-        gw.groups = m;
-        gw.M = c->dims[l];
-        gw.N = c->dims[l + 1];
-        gw.K = B;
-        rc = enqueue(c, OLS_K_GEMM_DW, 0, -1, -1,
-                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s) : launch_gemm_f32_dw(gw, s, c->gemm_variant[1]); });
-        if (rc) return rc;
         if (l > 0) {
             GemmArgs gd = {};
             gd.a = dz;
@@ -387,6 +363,40 @@ int compute_gradients(ols_ctx* c) {
                          [&](hipStream_t s) { return bf ? launch_gemm_bf16_da(gd, s) : launch_gemm_f32_da(gd, s, c->gemm_variant[2]); });
             if (rc) return rc;
         }
+        GemmArgs gw = {};
+        if (bf) {  // contraction over the batch wants batch-contiguous operands: the transposed copies
+            gw.a = act_t(l);
+            gw.sa = (int64_t)B * c->dims[l];
+            gw.lda = B;
+            gw.b = c->ws + c->off_dz_t[l + 1];
+            gw.sb = dz_stride;
+            gw.ldb = B;
+        } else {
+            gw.a = act(l);
+            gw.sa = act_stride(l);
+            gw.lda = c->dims[l];
+            gw.b = dz;
+            gw.sb = dz_stride;
+            gw.ldb = c->dims[l + 1];
+        }
+        gw.c = c->g + c->w_off[l];
+        gw.sc = c->ld;
+        gw.ldc = c->dims[l + 1];
+        // the kernel also reduces the bias gradient while the delta streams through LDS
+        gw.colsum = c->g + c->b_off[l];
+        gw.scolsum = c->ld;
+        if (upd) {
+            gw.upd = *upd;
+            gw.upd_w_off = c->w_off[l];
+            gw.upd_b_off = c->b_off[l];
+        }
+        gw.groups = m;
+        gw.M = c->dims[l];
+        gw.N = c->dims[l + 1];
+        gw.K = B;
+        rc = enqueue(c, OLS_K_GEMM_DW, 0, upd ? src_buf : -1, upd ? dst_buf : -1,
+                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s) : launch_gemm_f32_dw(gw, s, c->gemm_variant[1]); });
+        if (rc) return rc;
     }
     return OLS_OK;
 }
@@ -517,7 +527,7 @@ int ols_init_params(ols_handle c, const float* x0) {
     if (rc) return rc;
     c->k = 0;
     c->pull_due = c->pending_update = c->anchor_due = c->anchor_inflight = c->first_after_anchor = false;
-    c->anchor_precomputed = false;
+    c->anchor_precomputed = c->pulled_in_step = false;
     c->inited = true;
     return OLS_OK;
 }
@@ -644,9 +654,39 @@ int ols_local_step(ols_handle c) {
         if (!c->ws) return fail(OLS_ESTATE, "the attached model needs ols_bind_workspace");
         if (!c->batch_set) return fail(OLS_ESTATE, "the attached model needs ols_set_batch");
     }
-    if (int rc = compute_gradients(c)) return rc;
+    const bool boundary = (c->k + 1) % c->tau == 0;
+    if (c->model == MODEL_MLP && c->fuse_gemm_update && !(boundary && c->fuse_mean)) {
+        // the gradient kernels apply the update themselves; on a boundary step the pull-back as well,
+        // so the anchor of the previous round must have landed before they start
+        int src, dst;
+        if (int rc = pick_buffers(c, &src, &dst)) return rc;
+        if (boundary) {
+            if (int rc = main_waits_for_anchor(c)) return rc;
+        }
+        FusedUpdate u = {};
+        u.x_in = c->x[src];
+        u.x_out = c->x[dst];
+        u.buf = c->mu != 0.0f ? c->buf : nullptr;
+        u.z = c->z;
+        u.shadow = shadow_ptr(c);
+        u.ld = c->ld;
+        u.gamma = c->gamma;
+        u.mu = c->mu;
+        u.alpha = c->alpha;
+        u.nesterov = c->nesterov ? 1 : 0;
+        u.pull = boundary ? 1 : 0;
+        u.enabled = 1;
+        if (int rc = compute_gradients(c, &u, src, dst)) return rc;
+        c->cur = dst;
+        c->k += 1;
+        if (boundary) {
+            c->pull_due = true;
+            c->pulled_in_step = true;
+        }
+        return OLS_OK;
+    }
+    if (int rc = compute_gradients(c, nullptr, c->cur, -1)) return rc;
     c->k += 1;
-    const bool boundary = c->k % c->tau == 0;
     if (boundary && c->fuse_pull) {
         c->pending_update = true;  // applied together with the pull-back in one pass
         c->pull_due = true;
@@ -665,6 +705,16 @@ int ols_local_step(ols_handle c) {
 int ols_sync_pull(ols_handle c) {
     if (int rc = need(c)) return rc;
     if (!c->pull_due) return fail(OLS_ESTATE, "no pull is due at k = %lld (tau = %d)", (long long)c->k, c->tau);
+    if (c->pulled_in_step) {  // the boundary step's gradient kernels already applied step + pull-back
+        c->pulled_in_step = false;
+        if (!c->dry) {
+            hipError_t e = hipEventRecord(c->ev_pulled, c->stream[0]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+        }
+        c->pull_due = false;
+        c->anchor_due = true;
+        return OLS_OK;
+    }
     // the anchor about to be read is the one the previous round's refresh produces
     if (int rc = main_waits_for_anchor(c)) return rc;
     int src = c->cur, dst = c->cur;
@@ -829,6 +879,10 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
         case OLS_OPT_GEMM_VARIANT_DA:
             if (value < 0 || value > 15) return fail(OLS_EINVAL, "GEMM variant out of range");
             c->gemm_variant[key - OLS_OPT_GEMM_VARIANT_FWD] = (int)value;
+            break;
+        case OLS_OPT_FUSE_GEMM_UPDATE:
+            if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "cannot change fusion in the middle of a synchronisation");
+            c->fuse_gemm_update = value != 0;
             break;
         case OLS_OPT_GEMM_SPLITK:
             if (value < 0 || value > 8) return fail(OLS_EINVAL, "split-K count must be in [0, 8]");

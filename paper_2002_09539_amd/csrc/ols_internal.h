@@ -58,6 +58,43 @@ hipError_t launch_lsq_resid(const float* A, int64_t a_stride, const float* y, in
 hipError_t launch_lsq_grad(const float* A, int64_t a_stride, const float* resid, float* g, int64_t ld, int m, int B,
                            int64_t d, hipStream_t s);
 
+// Local step (+ pull-back) applied where a gradient element is produced, instead of writing the
+// gradient to HBM and streaming it back in a separate pass.  Same fp32 operation sequence as the
+// streaming kernels of kernels_update.hip, so both routes give identical bits.
+struct FusedUpdate {
+    const float* x_in;  // [m][ld] parameters read
+    float* x_out;       // [m][ld] parameters written (may alias x_in)
+    float* buf;         // [m][ld] momentum buffers (nullptr iff mu == 0)
+    const float* z;     // [ld] anchor (pull-back steps)
+    uint16_t* shadow;   // [m][ld] bf16 copy of the new parameters, or nullptr
+    int64_t ld;
+    float gamma, mu, alpha;
+    int nesterov, pull;
+    int enabled;
+};
+
+#if defined(__HIPCC__)
+// idx = worker * ld + col (col = position inside the replica row)
+__device__ __forceinline__ void fused_update_apply(const FusedUpdate& u, int64_t idx, int64_t col, float g, float x,
+                                                   float b) {
+    float xh;
+    if (u.mu != 0.0f) {
+        b = __fmaf_rn(u.mu, b, g);
+        const float dir = u.nesterov ? __fmaf_rn(u.mu, b, g) : b;
+        xh = __fmaf_rn(-u.gamma, dir, x);
+        u.buf[idx] = b;
+    } else {
+        xh = __fmaf_rn(-u.gamma, g, x);
+    }
+    if (u.pull) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, u.z[col]), xh);
+    u.x_out[idx] = xh;
+    if (u.shadow) {
+        const unsigned int w = __float_as_uint(xh);
+        u.shadow[idx] = (uint16_t)((w + 0x7FFFu + ((w >> 16) & 1u)) >> 16);
+    }
+}
+#endif
+
 // grouped GEMMs over the m workers (group strides in elements)
 struct GemmArgs {
     const void* a;      // operand A, group stride sa
@@ -69,6 +106,9 @@ struct GemmArgs {
     float* colsum;      // dw: optional [N] per group, receives the column sums of B (the bias gradient)
     float* partial;     // fp32 fwd with splits > 1: scratch of splits * groups * M * N floats
     int splits;         // fp32 fwd: number of K ranges contracted by separate workgroups (<= 1: none)
+    FusedUpdate upd;    // dw: when enabled, c is NOT written; the update of W (c's position in the replica row is
+    int64_t upd_w_off;  //     upd_w_off) and of the bias (upd_b_off, from the column sums) is applied instead
+    int64_t upd_b_off;
     int64_t sa, sb, sc, sbias, smask, sct, scolsum;
     int groups;
     int M, N, K;        // output M x N, contraction length K
@@ -102,6 +142,7 @@ struct HeadArgs {
     void* dz;             // [m][B][H] delta for the last hidden layer (fp32 or bf16), masked by h > 0
     void* dz_t;           // bf16 only: transposed copy [m][H][B] or nullptr
     int m, B, H, C;
+    FusedUpdate upd;      // when enabled the output layer's parameters are updated instead of writing g
 };
 hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s);
 hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s);

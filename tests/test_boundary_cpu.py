@@ -191,8 +191,19 @@ def test_model_attachment_validation():
     assert code_of(B.ols_set_batch, h, FAKE, 8 * 8 - 4, FAKE, 8) == B.OLS_EINVAL  # worker stride too small
     B.ols_set_batch(h, FAKE, 8 * 8, FAKE, 8)
     B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_local_step(h)          # default: the gradient kernels apply the update themselves
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw"]
+    B.ols_local_step(h)          # boundary step (tau = 2): pull-back applied there as well
+    B.ols_sync_pull(h)           # ... so the pull launches nothing
+    B.ols_anchor_update_async(h)
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw"] * 2 + ["mean"]
+    B.ols_set_option(h, B.OLS_OPT_FUSE_GEMM_UPDATE, 0)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
     B.ols_local_step(h)
-    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw", "step"]
+    B.ols_local_step(h)
+    B.ols_sync_pull(h)
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw", "step"] + \
+        ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw", "step_pull"]
     assert code_of(B.ols_set_gradient, h, FAKE) == B.OLS_ESTATE               # the model owns g
     B.ols_destroy(h)
 
@@ -207,8 +218,33 @@ def test_deep_mlp_launch_plan():
     B.ols_set_batch(h, FAKE, 64, FAKE, 8)
     B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
     B.ols_local_step(h)
+    # each layer's delta GEMM precedes its weight-gradient GEMM (which may update the weights in place)
     assert kinds(B.ols_trace(h)) == ["gemm_fwd"] * 3 + ["head_fwd", "head_bwd"] + \
-        ["gemm_dw", "gemm_da"] * 2 + ["gemm_dw", "step"]
+        ["gemm_da", "gemm_dw"] * 2 + ["gemm_dw"]
+    tr = B.ols_trace(h)
+    assert all((t["src_buf"], t["dst_buf"]) == (0, 0) for t in tr if B.ols_kernel_name(t["kind"]) == "gemm_dw")
+    B.ols_destroy(h)
+
+
+def test_fused_update_uses_second_buffer_after_refresh():
+    dims = [8, 12, 5]
+    d = sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(2))
+    h = dry(d=d, mu=0.9, tau=2)
+    B.ols_attach_mlp(h, dims, 8, 0)
+    B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+    B.ols_init_params(h, FAKE)
+    B.ols_set_batch(h, FAKE, 64, FAKE, 8)
+    for _ in range(2):
+        B.ols_local_step(h)
+        B.ols_local_step(h)
+        B.ols_sync_pull(h)
+        B.ols_anchor_update_async(h)
+    B.ols_local_step(h)
+    tr = [t for t in B.ols_trace(h) if B.ols_kernel_name(t["kind"]) in ("gemm_dw", "mean")]
+    bufs = [(B.ols_kernel_name(t["kind"]), t["src_buf"], t["dst_buf"], t["waited"]) for t in tr]
+    assert bufs == [("gemm_dw", 0, 0, 0), ("gemm_dw", 0, 0, 0), ("mean", 0, -1, 1),
+                    ("gemm_dw", 0, 1, 0), ("gemm_dw", 1, 1, 0), ("mean", 1, -1, 1),
+                    ("gemm_dw", 1, 0, 0)]
     B.ols_destroy(h)
 
 

@@ -9,6 +9,8 @@ from oracle import ols_oracle as O
 from oracle import workloads as OW
 from tests.helpers import l2_ratio, max_norm_ratio
 
+from paper_2002_09539_amd import binding as B
+
 pytestmark = pytest.mark.gpu
 
 GRAD_TOL = 2e-5     # fp32 MFMA accumulation over K <= 3072 terms against the fp64 oracle, max-norm relative
@@ -52,6 +54,7 @@ def test_gradient_and_loss_match_oracle(m, dims, batch):
     cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 1, seed=101)
     x0 = x0 + G.generic_normal(3, 1, x0.shape, sigma=0.02)      # non-zero biases as well
     with make_session(m, cfg.d, 2, 0.6, 0.05, 0.0) as s:
+        s.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, 0)     # keep the gradients in g so they can be read
         s.attach_mlp(dims, batch, "f32")
         Xd, yd = s.upload(X), s.upload(labels)
         s.init_params(x0)
@@ -122,6 +125,7 @@ def test_bf16_gradient_and_loss(m, dims, batch):
     cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 1, seed=303)
     x0 = x0 + G.generic_normal(5, 2, x0.shape, sigma=0.02)
     with make_session(m, cfg.d, 2, 0.6, 0.05, 0.0) as s:
+        s.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, 0)     # keep the gradients in g so they can be read
         s.attach_mlp(dims, batch, "bf16")
         Xd, yd = s.upload(X), s.upload(labels)
         s.init_params(x0)
@@ -158,3 +162,24 @@ def test_bf16_small_run_loss_tracks_oracle():
     rel = np.abs(np.array(losses) - st["losses"]) / np.abs(st["losses"])
     assert rel.max() <= BF16_LOSS_TOL
     assert max(l2_ratio(x[i], st["x"][i]) for i in range(m)) <= 2e-2
+
+
+@pytest.mark.parametrize("dtype,dims,batch", [("f32", (96, 64, 40, 10), 36), ("bf16", (128, 72, 64, 10), 40)])
+@pytest.mark.parametrize("tau,second_buffer", [(1, True), (2, True), (3, False)])
+def test_update_fused_into_gradient_kernels_is_bit_identical(dtype, dims, batch, tau, second_buffer):
+    """The gradient kernels applying the step (+ pull-back) in their epilogues must leave exactly the
+    state the separate streaming kernels leave (same fp32 operation sequence per element)."""
+    m, K = 3, 7
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 2, seed=505)
+    states = []
+    for fused in (1, 0):
+        with make_session(m, cfg.d, tau, 0.6, 0.05, 0.9, overlap_buffer=second_buffer) as s:
+            s.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, fused)
+            s.attach_mlp(dims, batch, dtype)
+            Xd, yd = s.upload(X), s.upload(labels)
+            s.init_params(x0)
+            losses = []
+            s.run(K, lambda k: s.set_batch(Xd[:, k % 2], yd[:, k % 2]), losses=losses)
+            states.append((s.all_params(), s.params(-1), s.momentum(), np.array(losses)))
+    for a, b in zip(states[0], states[1]):
+        assert np.array_equal(a, b)
