@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--fuse-mean", type=int, default=0, help="1: step + pull-back + anchor refresh in one pass")
     ap.add_argument("--no-second-buffer", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the timed region run one plain element-wise copy kernel of this size (reads and "
+                         "writes that many MiB): the known-size reference the HBM traffic counters are scaled by")
     ap.add_argument("--opt", action="append", default=[], help="KEY=VALUE library option (numeric key), repeatable")
     return ap.parse_args()
 
@@ -167,6 +170,15 @@ def main():
         sess.sync()
         torch.cuda.synchronize()
         return time.perf_counter() - t0
+
+    if args.calibration_copy_mib > 0:
+        n = args.calibration_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=sess.device)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 1.0, out=dst)          # one vectorised element-wise kernel: n floats in, n floats out
+        torch.cuda.synchronize()
+        del src, dst
 
     region(W)
     elapsed = region(K)

@@ -7,7 +7,7 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libols.so")
+LIB_PATH = os.environ.get("OLS_LIBRARY", os.path.join(HERE, "libols.so"))   # override: an alternative build
 
 OLS_OK, OLS_EINVAL, OLS_ESTATE, OLS_EHIP, OLS_ENOMEM = 0, -1, -2, -3, -4
 (OLS_OPT_NESTEROV, OLS_OPT_FUSE_PULL, OLS_OPT_SERIALIZE, OLS_OPT_DRY_RUN, OLS_OPT_KERNEL_TIMING, OLS_OPT_TRACE,

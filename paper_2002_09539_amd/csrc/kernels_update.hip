@@ -18,11 +18,28 @@ namespace ols {
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
-constexpr int kUnroll = 4;  // 16-byte vectors per lane per array
+#ifndef OLS_UPDATE_THREADS
+#define OLS_UPDATE_THREADS 256
+#endif
+#ifndef OLS_UPDATE_UNROLL
+#define OLS_UPDATE_UNROLL 1
+#endif
+#ifndef OLS_UPDATE_NONTEMPORAL
+#define OLS_UPDATE_NONTEMPORAL 1
+#endif
+constexpr int kThreads = OLS_UPDATE_THREADS;
+// 16-byte vectors per lane per array.  Measured on the d = 11.2 M, m = 16 stream (local step, us):
+// 1 -> 601, 2 -> 628, 4 -> 618, 8 -> 655 (256 threads); 512 x 2 -> 619, 1024 x 2 -> 654; plain instead of
+// non-temporal accesses -> 656.  All within a few percent of 6 TB/s, the most this memory system gave.
+constexpr int kUnroll = OLS_UPDATE_UNROLL;
 
+#if OLS_UPDATE_NONTEMPORAL
 __device__ __forceinline__ f4 ld_stream(const f4* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void st_stream(f4* p, f4 v) { __builtin_nontemporal_store(v, p); }
+#else
+__device__ __forceinline__ f4 ld_stream(const f4* p) { return *p; }
+__device__ __forceinline__ void st_stream(f4* p, f4 v) { *p = v; }
+#endif
 
 __device__ __forceinline__ unsigned int bf16_rne(float f) {
     unsigned int u = __float_as_uint(f);
@@ -45,13 +62,20 @@ __device__ __forceinline__ float pull_elem(float xh, float z, float alpha) {
     return __fmaf_rn(-alpha, __fsub_rn(xh, z), xh);
 }
 
-// grid.x covers the row in spans of kThreads * kUnroll vectors, grid.y is the replica.
+// One workgroup per (replica, span of kThreads * kUnroll vectors); the replica is the SLOW part of the
+// linear workgroup id, so consecutive workgroups stream through one row.  Measured alternatives on the
+// d = 11.2 M, m = 16 stream (step + pull-back, 617 us): replica as the fast index halves the re-reads of
+// the anchor z (HBM fetches 2.51 GB instead of 2.87 GB, algorithmic 2.19 GB) but takes 660 us, and one
+// workgroup looping over all replicas with z in registers reaches the algorithmic traffic but takes
+// 677 us -- row-wise streaming is what the memory system rewards, the extra z fetches are served by the
+// last-level cache.
 template <bool MOM, bool NEST, bool PULL, bool SHADOW>
 __global__ __launch_bounds__(kThreads) void step_kernel(const f4* __restrict__ g, const f4* x_in, f4* x_out,
                                                         f4* buf, const f4* __restrict__ z, u2* __restrict__ shadow,
-                                                        int64_t n4, float gamma, float mu, float alpha) {
-    const int64_t row = (int64_t)blockIdx.y * n4;
-    const int64_t c0 = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+                                                        int64_t n4, int m, float gamma, float mu, float alpha) {
+    const int64_t spans = (n4 + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+    const int64_t row = (int64_t)(blockIdx.x / spans) * n4;
+    const int64_t c0 = (int64_t)(blockIdx.x % spans) * (kThreads * kUnroll) + threadIdx.x;
     f4 vg[kUnroll], vx[kUnroll], vb[kUnroll], vz[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
@@ -86,9 +110,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(const f4* __restrict__ g
 
 template <bool SHADOW>
 __global__ __launch_bounds__(kThreads) void pull_kernel(f4* x, const f4* __restrict__ z, u2* __restrict__ shadow,
-                                                        int64_t n4, float alpha) {
-    const int64_t row = (int64_t)blockIdx.y * n4;
-    const int64_t c0 = (int64_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+                                                        int64_t n4, int m, float alpha) {
+    const int64_t spans = (n4 + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+    const int64_t row = (int64_t)(blockIdx.x / spans) * n4;
+    const int64_t c0 = (int64_t)(blockIdx.x % spans) * (kThreads * kUnroll) + threadIdx.x;
     f4 vx[kUnroll], vz[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
@@ -133,27 +158,34 @@ __global__ __launch_bounds__(kThreads) void init_kernel(float* x, float* x_alt, 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 template <bool MOM, bool NEST, bool PULL>
-static void dispatch_shadow(const UpdateArgs& a, dim3 grid, hipStream_t s) {
+static void dispatch_shadow(const UpdateArgs& a, unsigned grid, hipStream_t s) {
     const int64_t n4 = a.ld / 4;
     if (a.shadow)
         step_kernel<MOM, NEST, PULL, true><<<grid, kThreads, 0, s>>>((const f4*)a.g, (const f4*)a.x_in, (f4*)a.x_out,
                                                                     (f4*)a.buf, (const f4*)a.z, (u2*)a.shadow, n4,
-                                                                    a.gamma, a.mu, a.alpha);
+                                                                    a.m, a.gamma, a.mu, a.alpha);
     else
         step_kernel<MOM, NEST, PULL, false><<<grid, kThreads, 0, s>>>((const f4*)a.g, (const f4*)a.x_in,
                                                                      (f4*)a.x_out, (f4*)a.buf, (const f4*)a.z,
-                                                                     nullptr, n4, a.gamma, a.mu, a.alpha);
+                                                                     nullptr, n4, a.m, a.gamma, a.mu, a.alpha);
+}
+
+static bool grid_for(int m, int64_t ld, unsigned* grid) {
+    const int64_t per_block = (int64_t)kThreads * kUnroll;
+    const int64_t blocks = ((ld / 4 + per_block - 1) / per_block) * m;
+    if (blocks < 1 || blocks > 0x7FFFFFFF) return false;
+    *grid = (unsigned)blocks;
+    return true;
 }
 
 hipError_t launch_step(const UpdateArgs& a, hipStream_t s) {
-    if (a.m < 1 || a.m > 65535 || a.ld < 4 || a.ld % 4 != 0) return hipErrorInvalidValue;
+    if (a.m < 1 || a.ld < 4 || a.ld % 4 != 0) return hipErrorInvalidValue;
     if (!a.g || !a.x_in || !a.x_out || (a.mu != 0.0f && !a.buf) || (a.pull && !a.z)) return hipErrorInvalidValue;
     if (!aligned16(a.g) || !aligned16(a.x_in) || !aligned16(a.x_out) || !aligned16(a.buf) || !aligned16(a.z) ||
         !aligned16(a.shadow))
         return hipErrorInvalidValue;
-    const int64_t n4 = a.ld / 4;
-    const int64_t per_block = (int64_t)kThreads * kUnroll;
-    dim3 grid((unsigned)((n4 + per_block - 1) / per_block), (unsigned)a.m);
+    unsigned grid;
+    if (!grid_for(a.m, a.ld, &grid)) return hipErrorInvalidValue;
     const bool mom = a.mu != 0.0f;
     if (mom) {
         if (a.nesterov) {
@@ -171,13 +203,13 @@ hipError_t launch_step(const UpdateArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_pull(float* x, const float* z, uint16_t* shadow, int m, int64_t ld, float alpha, hipStream_t s) {
-    if (m < 1 || m > 65535 || ld < 4 || ld % 4 != 0 || !x || !z) return hipErrorInvalidValue;
+    if (m < 1 || ld < 4 || ld % 4 != 0 || !x || !z) return hipErrorInvalidValue;
     if (!aligned16(x) || !aligned16(z) || !aligned16(shadow)) return hipErrorInvalidValue;
+    unsigned grid;
+    if (!grid_for(m, ld, &grid)) return hipErrorInvalidValue;
     const int64_t n4 = ld / 4;
-    const int64_t per_block = (int64_t)kThreads * kUnroll;
-    dim3 grid((unsigned)((n4 + per_block - 1) / per_block), (unsigned)m);
-    if (shadow) pull_kernel<true><<<grid, kThreads, 0, s>>>((f4*)x, (const f4*)z, (u2*)shadow, n4, alpha);
-    else pull_kernel<false><<<grid, kThreads, 0, s>>>((f4*)x, (const f4*)z, nullptr, n4, alpha);
+    if (shadow) pull_kernel<true><<<grid, kThreads, 0, s>>>((f4*)x, (const f4*)z, (u2*)shadow, n4, m, alpha);
+    else pull_kernel<false><<<grid, kThreads, 0, s>>>((f4*)x, (const f4*)z, nullptr, n4, m, alpha);
     return hipGetLastError();
 }
 
