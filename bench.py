@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--serialize", type=int, default=0, help="1: anchor refresh on the main stream (no overlap)")
     ap.add_argument("--fuse-mean", type=int, default=0, help="1: step + pull-back + anchor refresh in one pass")
     ap.add_argument("--no-second-buffer", action="store_true")
+    ap.add_argument("--fuse-gemm-update", type=int, default=1,
+                    help="1 (default): gradient kernels apply the local step themselves; 0: separate streaming pass")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed region run one plain element-wise copy kernel of this size (reads and "
@@ -42,7 +44,7 @@ def parse():
     return ap.parse_args()
 
 
-def algorithmic_work(cfg, ld):
+def algorithmic_work(cfg, ld, fused_update=True):
     """Per-launch algorithmic bytes / flops of each kernel kind (element-replicas x bytes, 2 M N K)."""
     m = cfg.m
     er = m * ld                        # element-replicas one streaming launch touches
@@ -61,6 +63,15 @@ def algorithmic_work(cfg, ld):
         fwd = [2.0 * m * B * dims[l] * dims[l + 1] for l in range(L - 1)]
         work["gemm_fwd"] = ("mfma", sum(fwd) / max(len(fwd), 1))
         work["gemm_dw"] = ("mfma", sum(fwd) / max(len(fwd), 1))
+        if fused_update and L > 1:
+            # the weight-gradient kernel also applies the local step: it reads and writes the layer's
+            # parameters and momentum (16 B per element-replica, 8 B without momentum, + 2 B bf16 shadow)
+            # and reads its two operands; those bytes, not the flops, bound it
+            es = 2 if cfg.gemm_dtype == "bf16" else 4
+            per_elem = 8 + mom + shadow
+            dw_bytes = [m * (dims[l] * dims[l + 1] * per_elem + B * (dims[l] + dims[l + 1]) * es) for l in range(L - 1)]
+            work["gemm_dw"] = ("hbm", sum(dw_bytes) / len(dw_bytes))
+            work["gemm_dw_flops"] = sum(fwd) / len(fwd)
         da = [2.0 * m * B * dims[l] * dims[l + 1] for l in range(1, L - 1)]
         if da:
             work["gemm_da"] = ("mfma", sum(da) / len(da))
@@ -157,6 +168,7 @@ def main():
     sess.set_option(B.OLS_OPT_NESTEROV, int(cfg.nesterov))
     sess.set_option(B.OLS_OPT_SERIALIZE, args.serialize)
     sess.set_option(B.OLS_OPT_FUSE_MEAN, args.fuse_mean)
+    sess.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, args.fuse_gemm_update)
     for kv in args.opt:
         key, val = kv.split("=")
         sess.set_option(int(key), int(val))
@@ -190,7 +202,7 @@ def main():
         timed_elapsed = region(K)
         stats = sess.kernel_stats()
         sess.set_option(B.OLS_OPT_KERNEL_TIMING, 0)
-        work = algorithmic_work(cfg, sess.ld)
+        work = algorithmic_work(cfg, sess.ld, fused_update=bool(args.fuse_gemm_update) and not args.fuse_mean)
         for name, (n, ms) in stats.items():
             entry = {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms}
             if name in work:
@@ -203,6 +215,8 @@ def main():
                     peak = MFMA_PEAK_TFLOPS[cfg.gemm_dtype]
                     entry.update(bound="mfma", achieved=rate / 1e12, peak=peak, unit="TFLOP/s",
                                  frac=rate / 1e12 / peak, per_launch=amount)
+            if name + "_flops" in work:
+                entry["mfma_tflops"] = work[name + "_flops"] / (ms / n * 1e-3) / 1e12
             kernels[name] = entry
         ranked = sorted((e["total_ms"], n) for n, e in kernels.items() if "bound" in e)
         if ranked:
@@ -236,7 +250,8 @@ def main():
         "config": {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
                    "dims": list(cfg.dims), "overlap": "serialized" if args.serialize else
                    ("fused-mean" if args.fuse_mean else "side-stream"),
-                   "second_buffer": not args.no_second_buffer},
+                   "second_buffer": not args.no_second_buffer,
+                   "update": "in-gradient-kernels" if (args.fuse_gemm_update and cfg.kind == "mlp") else "streaming"},
         "roofline": roofline,
         "cpu_baseline": base,
         "kernels": kernels,
