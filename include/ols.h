@@ -100,7 +100,7 @@ enum {
     OLS_K_GEMM_DA = 10,   /* back-propagated delta dZ W^T, ReLU mask    */
     OLS_K_HEAD_FWD = 11,  /* output layer + softmax cross-entropy       */
     OLS_K_HEAD_BWD = 12,  /* output layer gradients and delta           */
-    OLS_K_BIAS_GRAD = 13,
+    OLS_K_RESERVED = 13,  /* unused (bias gradients are formed inside the weight-gradient kernels) */
     OLS_K_CAST = 14,      /* fp32 -> bf16 operand conversion            */
     OLS_K_COUNT = 15
 };

@@ -14,7 +14,7 @@ OLS_OK, OLS_EINVAL, OLS_ESTATE, OLS_EHIP, OLS_ENOMEM = 0, -1, -2, -3, -4
  OLS_OPT_MEAN_SPLIT, OLS_OPT_FUSE_MEAN, OLS_OPT_GEMM_VARIANT_FWD, OLS_OPT_GEMM_VARIANT_DW,
  OLS_OPT_GEMM_VARIANT_DA, OLS_OPT_GEMM_SPLITK, OLS_OPT_FUSE_GEMM_UPDATE) = range(1, 14)
 (OLS_K_INIT, OLS_K_STEP, OLS_K_STEP_PULL, OLS_K_PULL, OLS_K_MEAN, OLS_K_STEP_PULL_MEAN, OLS_K_LSQ_RESID,
- OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_BIAS_GRAD,
+ OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_RESERVED,
  OLS_K_CAST, OLS_K_COUNT) = range(16)
 
 

@@ -1,5 +1,4 @@
-// Output layer of the per-worker MLP (class count C <= 32) with softmax cross-entropy, its gradients,
-// and the bias-gradient column sums.  The output width is far too small for matrix cores, so these run
+// Output layer of the per-worker MLP (class count C <= 32) with softmax cross-entropy and its gradients.  The output width is far too small for matrix cores, so these run
 // on the vector ALUs; they are a few MFLOP per worker and latency-bound.
 //
 // Per worker i with last hidden activations h [B][H], weights W [H][C], bias b [C], labels y [B]
@@ -278,19 +277,6 @@ __global__ __launch_bounds__(kThreads) void head_dz_kernel(const void* __restric
     }
 }
 
-// g[b_off + n] = sum_s dz[s][n];  grid (ceil(N / 256), m)
-template <bool BF>
-__global__ __launch_bounds__(kThreads) void bias_grad_kernel(const void* __restrict__ dz, int64_t dz_stride,
-                                                             float* __restrict__ g, int64_t ld, int64_t b_off, int B,
-                                                             int N) {
-    const int i = blockIdx.y;
-    const int n = blockIdx.x * kThreads + threadIdx.x;
-    if (n >= N) return;
-    float acc = 0.0f;
-    for (int s = 0; s < B; ++s) acc += load_act<BF>(dz, (int64_t)i * dz_stride + (int64_t)s * N + n);
-    g[(int64_t)i * ld + b_off + n] = acc;
-}
-
 static bool head_args_ok(const HeadArgs& a) {
     return a.h && a.x && a.g && a.labels && a.dlogits && a.loss_parts && a.m >= 1 && a.m <= 65535 && a.B >= 1 &&
            a.H >= 1 && a.C >= 1 && a.C <= kMaxC && a.w_off >= 0 && a.b_off >= 0 &&
@@ -347,15 +333,6 @@ hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s) {
         if (a.C <= 16) OLS_HEAD_DW(false, 16); else OLS_HEAD_DW(false, 32);
     }
 #undef OLS_HEAD_DW
-    return hipGetLastError();
-}
-
-hipError_t launch_bias_grad(const void* dz, bool dz_bf16, int64_t dz_stride, float* g, int64_t ld, int64_t b_off,
-                            int m, int B, int N, hipStream_t s) {
-    if (!dz || !g || m < 1 || m > 65535 || B < 1 || N < 1 || b_off < 0 || b_off + N > ld) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((N + kThreads - 1) / kThreads), (unsigned)m);
-    if (dz_bf16) bias_grad_kernel<true><<<grid, kThreads, 0, s>>>(dz, dz_stride, g, ld, b_off, B, N);
-    else bias_grad_kernel<false><<<grid, kThreads, 0, s>>>(dz, dz_stride, g, ld, b_off, B, N);
     return hipGetLastError();
 }
 

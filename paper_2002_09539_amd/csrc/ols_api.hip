@@ -36,7 +36,7 @@ int fail(int code, const char* fmt, ...) {
 
 const char* kKernelNames[OLS_K_COUNT] = {
     "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
-    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "bias_grad",      "cast_bf16"};
+    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "reserved",       "cast_bf16"};
 
 enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2 };
 

@@ -146,9 +146,6 @@ struct HeadArgs {
 };
 hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s);
 hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s);
-hipError_t launch_bias_grad(const void* dz, bool dz_bf16, int64_t dz_stride, float* g, int64_t ld, int64_t b_off,
-                            int m, int B, int N, hipStream_t s);
-
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
 
 }  // namespace ols
