@@ -1,26 +1,45 @@
-// Output layer of the per-worker MLP (class count C <= 32) with softmax cross-entropy and its gradients.  The output width is far too small for matrix cores, so these run
-// on the vector ALUs; they are a few MFLOP per worker and latency-bound.
+// Output layer of the per-worker MLP (class count C <= 32) with softmax cross-entropy, the delta it
+// sends back to the last hidden layer, and its own gradients.  The output width is far too small for
+// matrix cores, so these run on the vector ALUs.  They are a few MFLOP per worker: what they cost is
+// (a) the chain of dependent memory round trips and (b) instruction fetch -- a launch this small runs
+// every instruction a handful of times, so long unrolled code is paid for line by line from a cold
+// instruction cache.  Hence the shape of both kernels: all global reads of a pass are issued together
+// and land in LDS, and the arithmetic runs in short rolled loops over LDS.
+//
+//   head_fwd_kernel   logits, loss, dlogits AND the hidden delta dz in one launch.  Sixteen lanes (one
+//                     DPP row) share a sample; the 16 partial logits are combined with DPP row
+//                     rotations, every lane then evaluates the softmax redundantly, and the staged
+//                     activations (ReLU mask) and weights are reused for dz.
+//   head_dw_kernel    dW = h^T dlogits, db = colsum(dlogits), consumed by the fused update or stored.
 //
 // Per worker i with last hidden activations h [B][H], weights W [H][C], bias b [C], labels y [B]
 // (the mini-batch loss whose gradient is the g_i of Section 2, arXiv 2002.09539):
 //   logits = h W + b;  loss_s = logsumexp(logits_s) - logits_s[y_s];  dlogits = (softmax - onehot) / B
 //   dW = h^T dlogits;  db = colsum(dlogits);  dz = (dlogits W^T) * [h > 0]
+// The class dimension is padded to CMAX (16 or 32) with zeros in LDS so that no inner loop branches on C.
 #include "ols_internal.h"
 
 namespace ols {
 
-constexpr int kThreads = 256;
-constexpr int kWave = 64;
+constexpr int kRow = 16;     // lanes of one DPP row
 constexpr int kMaxC = 32;
 
-__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float(((unsigned int)v) << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-    unsigned int u = __float_as_uint(f);
-    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned int f32_to_bf16(float f) {
+    const unsigned int u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
-// Sum over the 64 lanes of a wavefront, result valid in every lane: four rotate-and-add steps inside
-// each row of 16 lanes on the vector ALU (DPP row_ror), then two cross-row exchanges.
-__device__ __forceinline__ float wave_sum(float v) {
+// low (e = 0) or high (e = 1) bf16 of a packed word
+__device__ __forceinline__ float bf16_elem(unsigned int word, int e) {
+    return __uint_as_float((e & 1) ? (word & 0xFFFF0000u) : (word << 16));
+}
+
+// Sum over the 16 lanes of a DPP row, the same bits in every lane of the row (each step adds a lane's
+// value to that of its partner 8, 4, 2, 1 lanes away, which is symmetric).
+__device__ __forceinline__ float row_sum(float v) {
 #define OLS_ROW_ROR_ADD(n)                                                                                  \
     v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + (n), 0xF, 0xF, false))
     OLS_ROW_ROR_ADD(8);
@@ -28,305 +47,442 @@ __device__ __forceinline__ float wave_sum(float v) {
     OLS_ROW_ROR_ADD(2);
     OLS_ROW_ROR_ADD(1);
 #undef OLS_ROW_ROR_ADD
-    v += __shfl_xor(v, 16, kWave);
-    v += __shfl_xor(v, 32, kWave);
     return v;
 }
 
-template <bool BF>
-__device__ __forceinline__ float load_act(const void* p, int64_t idx) {
-    return BF ? bf16_to_f32(((const uint16_t*)p)[idx]) : ((const float*)p)[idx];
+__device__ __forceinline__ float row_max(float v) {
+#define OLS_ROW_ROR_MAX(n)                                                                                  \
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + (n), 0xF, 0xF, false)))
+    OLS_ROW_ROR_MAX(8);
+    OLS_ROW_ROR_MAX(4);
+    OLS_ROW_ROR_MAX(2);
+    OLS_ROW_ROR_MAX(1);
+#undef OLS_ROW_ROR_MAX
+    return v;
 }
 
-// Stages `rows` rows of the output-layer weights W [H][C] (contiguous in memory) into LDS with
-// fully coalesced loads; row pitch CP = C | 1 is odd so that lanes reading different rows at the same
-// column hit different banks.  Loads are issued eight at a time before any of them is consumed: a
-// dependent global round trip costs of the order of a microsecond here, so they must overlap.
-__device__ __forceinline__ void stage_weights(float* s_w, const float* __restrict__ W, int k0, int rows, int C, int CP) {
-    const float* src = W + (int64_t)k0 * C;
-    const int total = rows * C;
-    for (int base = 0; base < total; base += kThreads * 8) {
-        float tmp[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int t = base + u * kThreads + threadIdx.x;
-            tmp[u] = t < total ? src[t] : 0.0f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int t = base + u * kThreads + threadIdx.x;
-            if (t < total) s_w[(t / C) * CP + (t % C)] = tmp[u];
-        }
-    }
+// LDS row pitch (floats) of a CMAX-wide weight / delta row: a multiple of 4 so rows are read as 16-byte
+// vectors, and an odd number of such vectors so that 16 lanes reading consecutive rows hit distinct banks.
+__host__ __device__ constexpr int row_pitch(int C) { return 4 * (((C + 3) / 4) | 1); }
+
+struct HeadDev {
+    const void* h;
+    const float* x;
+    const int32_t* labels;
+    float* dlogits;
+    float* loss_parts;
+    void* dz;
+    void* dz_t;
+    int64_t h_stride, ld, w_off, b_off, label_stride;
+    int B, H, C;
+};
+
+constexpr int kHeadThreads = 256;
+constexpr int kHeadSamples = kHeadThreads / kRow;   // samples per workgroup of the forward kernel (16)
+
+// KC = hidden units staged per pass (512 or 1024); activation rows are staged at pitch KC + 4
+__host__ __device__ constexpr int head_fwd_lds_floats(int CMAX, int KC) {
+    return KC * row_pitch(CMAX) + kHeadSamples * (KC + 4) + kHeadSamples * CMAX;
 }
 
-// A workgroup owns 4 * SPW samples of one worker (SPW = 64 / CMAX per wavefront); the weight matrix
-// streams through LDS in chunks of kChunk rows shared by all of them.  The softmax of a wavefront's SPW
-// samples runs in parallel on lane groups of CMAX lanes.  grid (ceil(B / (4 SPW)), m)
-template <bool BF, int CMAX>
-__global__ __launch_bounds__(kThreads) void head_fwd_kernel(const void* __restrict__ h, int64_t h_stride,
-                                                            const float* __restrict__ x, int64_t ld, int64_t w_off,
-                                                            int64_t b_off, const int32_t* __restrict__ labels,
-                                                            int64_t label_stride, float* __restrict__ dlogits,
-                                                            float* __restrict__ loss_parts, int B, int H, int C) {
-    constexpr int SPW = kWave / CMAX;
-    constexpr int kChunk = 256, kIters = kChunk / kWave;
-    __shared__ float s_w[kChunk * (CMAX + 1)];
-    __shared__ float s_logit[kThreads / kWave][SPW][CMAX];
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+// grid (ceil(B / 16), m); dynamic LDS: head_fwd_lds_floats(CMAX, KC) floats (+ the transposition buffer when BF)
+template <bool BF, int CMAX, int KC>
+__global__ __launch_bounds__(kHeadThreads) void head_fwd_kernel(HeadDev p) {
+    constexpr int THREADS = kHeadThreads, S = kHeadSamples, HP = KC + 4;
+    constexpr int P = row_pitch(CMAX);         // LDS pitch of a weight row
+    constexpr int NW = KC * CMAX / THREADS;    // staged weights per lane, all in flight at once
+    constexpr int J = KC / (4 * kRow);         // 4-wide activation vectors per lane per pass (8)
+    constexpr int TP = 4 * S + 8;              // uint16 per 4 k in the transposition buffer (16-byte pad)
+    extern __shared__ __attribute__((aligned(16))) float s_dyn[];
+    float* s_w = s_dyn;                        // [KC slots][P]
+    float* s_h = s_dyn + KC * P;               // [S][HP]
+    float* s_d = s_h + S * HP;                 // [S][CMAX] dlogits of the workgroup's samples
+    uint16_t* s_t = (uint16_t*)(s_d + S * CMAX); // [16][TP], bf16 only
+
+    const int C = p.C, H = p.H, B = p.B;
     const int i = blockIdx.y;
-    const int s0 = (blockIdx.x * (kThreads / kWave) + wave) * SPW;
-    const float* W = x + (int64_t)i * ld + w_off;
-    const int CP = C | 1;
-    float acc[SPW][CMAX];
+    const int row = threadIdx.x / kRow, sub = threadIdx.x % kRow;
+    const int s0 = blockIdx.x * S, s = s0 + row;
+    const bool live = s < B;
+    const int cls = threadIdx.x % CMAX;
+    const float* W = p.x + (int64_t)i * p.ld + p.w_off;
+
+    float bias[CMAX / kRow];   // lane sub owns class sub (and sub + 16)
 #pragma unroll
-    for (int j = 0; j < SPW; ++j)
+    for (int c0 = 0; c0 < CMAX / kRow; ++c0)
+        bias[c0] = kRow * c0 + sub < C ? p.x[(int64_t)i * p.ld + p.b_off + kRow * c0 + sub] : 0.0f;
+    const int label = live ? p.labels[(int64_t)i * p.label_stride + s] : 0;
+
+    // One pass: KC rows of W from k0 (zero beyond H and beyond C) and the same KC activations of the 16
+    // samples (zero beyond H and beyond the batch) into LDS; every load is issued before the first store.
+    // Weight row kl goes to slot (kl % 4) * (KC / 4) + kl / 4: element e of a lane's vector j then sits at
+    // slot e * (KC / 4) + sub + 16 j, consecutive across the lanes of a DPP row, and at pitch P their
+    // 16-byte reads fall into distinct banks.
+    auto stage = [&](int k0) {
+        const float* src = W + (int64_t)k0 * C + cls;
+        const int rows = H - k0;
+        float tw[NW];
 #pragma unroll
-        for (int c = 0; c < CMAX; ++c) acc[j][c] = 0.0f;
-    for (int k0 = 0; k0 < H; k0 += kChunk) {
-        const int rows = min(kChunk, H - k0);
-        // this chunk's activations first (independent of the staging), all loads in flight together
-        float hv[kIters][SPW];
+        for (int u = 0; u < NW; ++u) {
+            const int kl = threadIdx.x / CMAX + u * (THREADS / CMAX);
+            tw[u] = (cls < C && kl < rows) ? src[kl * C] : 0.0f;
+        }
+        if constexpr (BF) {
+            constexpr int NH = S * KC / 8 / THREADS;   // 16-byte vectors of 8 bf16 per lane (4)
+            u4 th[NH];
 #pragma unroll
-        for (int it = 0; it < kIters; ++it)
-#pragma unroll
-            for (int j = 0; j < SPW; ++j) {
-                const int kk = lane + it * kWave;
-                hv[it][j] = (kk < rows && s0 + j < B)
-                                ? load_act<BF>(h, (int64_t)i * h_stride + (int64_t)(s0 + j) * H + k0 + kk) : 0.0f;
+            for (int u = 0; u < NH; ++u) {
+                const int f = threadIdx.x + u * THREADS, r = f / (KC / 8), kv = 8 * (f % (KC / 8));
+                th[u] = u4{0u, 0u, 0u, 0u};
+                if (s0 + r < B && k0 + kv < H)
+                    th[u] = *(const u4*)((const uint16_t*)p.h + (int64_t)i * p.h_stride + (int64_t)(s0 + r) * H + k0 + kv);
             }
-        __syncthreads();
-        stage_weights(s_w, W, k0, rows, C, CP);
-        __syncthreads();
 #pragma unroll
-        for (int it = 0; it < kIters; ++it) {
-            const int kk = lane + it * kWave;
-            if (kk < rows) {
+            for (int u = 0; u < NH; ++u) {
+                const int f = threadIdx.x + u * THREADS, r = f / (KC / 8), kv = 8 * (f % (KC / 8));
+                *(f4*)(s_h + r * HP + kv) = f4{bf16_elem(th[u].x, 0), bf16_elem(th[u].x, 1), bf16_elem(th[u].y, 0),
+                                               bf16_elem(th[u].y, 1)};
+                *(f4*)(s_h + r * HP + kv + 4) = f4{bf16_elem(th[u].z, 0), bf16_elem(th[u].z, 1), bf16_elem(th[u].w, 0),
+                                                   bf16_elem(th[u].w, 1)};
+            }
+        } else {
+            constexpr int NH = S * KC / 4 / THREADS;   // 16-byte vectors of 4 floats per lane (8)
+            f4 th[NH];
 #pragma unroll
-                for (int c = 0; c < CMAX; ++c) {
-                    if (c < C) {
-                        const float w = s_w[kk * CP + c];
+            for (int u = 0; u < NH; ++u) {
+                const int f = threadIdx.x + u * THREADS, r = f / (KC / 4), kv = 4 * (f % (KC / 4));
+                th[u] = f4{0.f, 0.f, 0.f, 0.f};
+                if (s0 + r < B && k0 + kv < H)
+                    th[u] = *(const f4*)((const float*)p.h + (int64_t)i * p.h_stride + (int64_t)(s0 + r) * H + k0 + kv);
+            }
 #pragma unroll
-                        for (int j = 0; j < SPW; ++j) acc[j][c] = __fmaf_rn(hv[it][j], w, acc[j][c]);
+            for (int u = 0; u < NH; ++u) {
+                const int f = threadIdx.x + u * THREADS, r = f / (KC / 4), kv = 4 * (f % (KC / 4));
+                *(f4*)(s_h + r * HP + kv) = th[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NW; ++u) {
+            const int kl = threadIdx.x / CMAX + u * (THREADS / CMAX);
+            s_w[((kl % 4) * (KC / 4) + kl / 4) * P + cls] = tw[u];
+        }
+    };
+
+    // Passes 0 .. n - 1 accumulate the logits over the chunks of H, the last of them ends with the softmax;
+    // passes n .. 2 n - 1 (only when dz is wanted) produce dz chunk by chunk.  One loop, so that the staging
+    // code exists once.  With a single chunk the weights and activations staged for the logits are still in
+    // LDS for dz; otherwise they are fetched again (they hit L2).
+    float acc[CMAX], d[CMAX];
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c) acc[c] = d[c] = 0.0f;
+    const int n = (H + KC - 1) / KC;
+    const int passes = p.dz ? 2 * n : n;
+#pragma unroll 1
+    for (int pass = 0; pass < passes; ++pass) {
+        const bool backward = pass >= n;
+        const int k0 = (backward ? pass - n : pass) * KC;
+        if (!(backward && n == 1)) {
+            if (pass > 0) __syncthreads();   // the previous pass is no longer read
+            stage(k0);
+            __syncthreads();
+        }
+        if (!backward) {
+#pragma unroll 1
+            for (int j = 0; j < J; ++j) {
+                const f4 hv = *(const f4*)(s_h + row * HP + 4 * (sub + kRow * j));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float* wr = s_w + (e * (KC / 4) + sub + kRow * j) * P;
+#pragma unroll
+                    for (int c4 = 0; c4 < CMAX / 4; ++c4) {
+                        const f4 w = *(const f4*)(wr + 4 * c4);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) acc[4 * c4 + q] = __fmaf_rn(hv[e], w[q], acc[4 * c4 + q]);
                     }
                 }
             }
+            if (pass != n - 1) continue;
+            // Softmax with the classes spread over the 16 lanes of the row: lane sub owns class sub (and
+            // sub + 16 when CMAX = 32), so each lane evaluates one or two exponentials instead of CMAX.
+            // The other classes' terms are summed separately from the label's: near convergence
+            // softmax[label] is within an ulp of 1, and both the loss log(1 + others / own) and the
+            // label's delta -(others / total) keep full relative accuracy this way, where
+            // log(total) - logit and softmax - 1 would cancel.
+            float logit[CMAX / kRow], ex[CMAX / kRow];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int c0 = 0; c0 < CMAX / kRow; ++c0) {
+                float v = 0.0f;
+#pragma unroll
+                for (int c = 0; c < kRow; ++c) {
+                    const float full = row_sum(acc[kRow * c0 + c]);   // every lane takes part in every sum
+                    v = c == sub ? full : v;
+                }
+                logit[c0] = kRow * c0 + sub < C ? v + bias[c0] : -INFINITY;
+                mx = fmaxf(mx, logit[c0]);
+            }
+            mx = row_max(mx);
+            float others = 0.0f, own = 0.0f, picked = 0.0f;
+#pragma unroll
+            for (int c0 = 0; c0 < CMAX / kRow; ++c0) {
+                ex[c0] = expf(logit[c0] - mx);            // exp(-inf) = 0 for the padding
+                const bool is_label = kRow * c0 + sub == label;
+                own += is_label ? ex[c0] : 0.0f;
+                picked += is_label ? logit[c0] : 0.0f;
+                others += is_label ? 0.0f : ex[c0];
+            }
+            others = row_sum(others);
+            own = row_sum(own);          // one non-zero term
+            picked = row_sum(picked);    // one non-zero term
+            const float sum = others + own;
+            const float scale = 1.0f / (sum * (float)B);   // dlogits = (softmax - onehot) / B
+            if (live && sub == 0)
+                p.loss_parts[(int64_t)i * B + s] = own > 1e-30f ? log1pf(others / own) : (logf(sum) + mx) - picked;
+#pragma unroll
+            for (int c0 = 0; c0 < CMAX / kRow; ++c0) {
+                const int c = kRow * c0 + sub;
+                const float dv = (c == label ? -others : ex[c0]) * scale;   // 0 for the padding
+                s_d[row * CMAX + c] = dv;
+                if (live && c < C) p.dlogits[((int64_t)i * B + s) * C + c] = dv;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int c4 = 0; c4 < CMAX / 4; ++c4) {
+                const f4 v = *(const f4*)(s_d + row * CMAX + 4 * c4);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) d[4 * c4 + q] = v[q];
+            }
+            continue;
         }
-    }
+        // dz[s][k] = (sum_c dlogits[s][c] W[k][c]) * [h[s][k] > 0]
+#pragma unroll 1
+        for (int j = 0; j < J; ++j) {
+            const int kl = 4 * (sub + kRow * j), kv = k0 + kl;
+            const f4 hv = *(const f4*)(s_h + row * HP + kl);
+            f4 out;
 #pragma unroll
-    for (int j = 0; j < SPW; ++j) {
+            for (int e = 0; e < 4; ++e) {
+                const float* wr = s_w + (e * (KC / 4) + sub + kRow * j) * P;
+                float a = 0.0f;
 #pragma unroll
-        for (int c = 0; c < CMAX; ++c) {
-            const float v = wave_sum(acc[j][c]);
-            if (lane == 0) s_logit[wave][j][c] = v;
+                for (int c4 = 0; c4 < CMAX / 4; ++c4) {
+                    const f4 w = *(const f4*)(wr + 4 * c4);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) a = __fmaf_rn(d[4 * c4 + q], w[q], a);   // padding: d = 0, w = 0
+                }
+                out[e] = hv[e] > 0.0f ? a : 0.0f;
+            }
+            if constexpr (BF) {
+                const unsigned int h0 = f32_to_bf16(out[0]), h1 = f32_to_bf16(out[1]), h2 = f32_to_bf16(out[2]),
+                                   h3 = f32_to_bf16(out[3]);
+                if (live && kv < H)
+                    *(u2*)((uint16_t*)p.dz + (int64_t)i * B * H + (int64_t)s * H + kv) = u2{h0 | (h1 << 16), h2 | (h3 << 16)};
+                if (p.dz_t) {
+                    // transposed copy [H][B]: iteration j covers the 64 consecutive k from k0 + 64 j; the 16
+                    // samples of this workgroup are 32 bytes per k, stored as two 16-byte pieces.  (B is a
+                    // multiple of 8 on this path: a piece is live or not as a whole.)
+                    s_t[sub * TP + 0 * S + row] = (uint16_t)h0;
+                    s_t[sub * TP + 1 * S + row] = (uint16_t)h1;
+                    s_t[sub * TP + 2 * S + row] = (uint16_t)h2;
+                    s_t[sub * TP + 3 * S + row] = (uint16_t)h3;
+                    __syncthreads();
+                    const int kk = threadIdx.x / 2, piece = threadIdx.x % 2;
+                    if (kk < 64 && k0 + 64 * j + kk < H && s0 + 8 * piece < B) {
+                        const u4 v = *(const u4*)(s_t + (kk / 4) * TP + (kk % 4) * S + 8 * piece);
+                        *(u4*)((uint16_t*)p.dz_t + (int64_t)i * B * H + (int64_t)(k0 + 64 * j + kk) * B + s0 + 8 * piece) = v;
+                    }
+                    __syncthreads();
+                }
+            } else {
+                if (live && kv < H) *(f4*)((float*)p.dz + (int64_t)i * B * H + (int64_t)s * H + kv) = out;
+            }
         }
-    }
-    __syncthreads();
-    // lane group j (CMAX lanes) owns sample s0 + j; lane c of the group owns class c
-    const int j = lane / CMAX, c = lane % CMAX;
-    const int s = s0 + j;
-    const bool live = s < B, mine = live && c < C;
-    const float logit = mine ? s_logit[wave][j][c] + x[(int64_t)i * ld + b_off + c] : -INFINITY;
-    float mx = logit;
-#pragma unroll
-    for (int off = CMAX / 2; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-    const int label = live ? labels[(int64_t)i * label_stride + s] : 0;
-    const float ex = mine ? expf(logit - mx) : 0.0f;
-    // Sum of the other classes' terms separately: near convergence softmax[label] is within an ulp of 1,
-    // and both the loss log(1 + others / own) and the label's delta -(others / total) keep full relative
-    // accuracy this way, where log(total) - logit and softmax - 1 would cancel.
-    float others = c == label ? 0.0f : ex;
-#pragma unroll
-    for (int off = CMAX / 2; off >= 1; off >>= 1) others += __shfl_xor(others, off, kWave);
-    const int src_lane = j * CMAX + (label & (CMAX - 1));
-    const float own = __shfl(ex, src_lane, kWave);
-    const float picked = __shfl(logit, src_lane, kWave);
-    const float sum = others + own;
-    if (live && c == 0)
-        loss_parts[(int64_t)i * B + s] = own > 1e-30f ? log1pf(others / own) : (logf(sum) + mx) - picked;
-    if (mine) {
-        const float d = c == label ? -(others / sum) : ex / sum;
-        dlogits[((int64_t)i * B + s) * C + c] = d / (float)B;
     }
 }
 
-// dW[k][c] = sum_s h[s][k] dlogits[s][c], db[c] = sum_s dlogits[s][c].  A workgroup owns 32 hidden units
-// k; its 8 lane groups of 32 take the samples s = j, j + 8, ... and are combined by a fixed-order sum
-// through LDS.  grid (ceil(H / 32), m)
+// dW[k][c] = sum_s h[s][k] dlogits[s][c], db[c] = sum_s dlogits[s][c].  A workgroup owns 32 hidden units of
+// one worker; the activations of those units and the dlogits pass through LDS; lane (k, class quad, part)
+// sums its part of the samples in sample order, and the parts are added in a fixed order.  The parameters
+// and momenta the fused update will need are requested at the start.  grid (ceil(H / 32), m)
 template <bool BF, int CMAX>
-__global__ __launch_bounds__(kThreads) void head_dw_kernel(const void* __restrict__ h, int64_t h_stride,
-                                                           const float* __restrict__ dlogits, float* __restrict__ g,
-                                                           int64_t ld, int64_t w_off, int64_t b_off, int B, int H,
-                                                           int C, FusedUpdate upd) {
-    constexpr int kCols = 32, kGroups = kThreads / kCols, kRows = 256;
-    __shared__ float s_dl[kRows * kMaxC];
-    __shared__ float s_part[kGroups][CMAX][kCols + 1];
+__global__ __launch_bounds__(256) void head_dw_kernel(const void* __restrict__ h, int64_t h_stride,
+                                                      const float* __restrict__ dlogits, float* __restrict__ g,
+                                                      int64_t ld, int64_t w_off, int64_t b_off, int B, int H, int C,
+                                                      FusedUpdate upd) {
+    constexpr int kThreads = 256, KW = 32;
+    constexpr int kRows = CMAX > 16 ? 128 : 256;      // samples staged per pass (LDS stays below 64 KiB)
+    constexpr int P = row_pitch(CMAX);
+    constexpr int CQ = CMAX / 4;                      // class quads
+    constexpr int NP = kThreads / (KW * CQ);          // parts the samples are split into (2 or 1)
+    constexpr int kOut = KW * CMAX / kThreads;        // output elements per lane (class-padded)
+    constexpr int kStage = kRows * CMAX / kThreads;   // staged dlogits per lane
+    constexpr int kTile = kRows * KW / 4 / kThreads;  // staged 4-wide activation vectors per lane (8)
+    __shared__ __attribute__((aligned(16))) float s_dl[kRows * P];
+    __shared__ __attribute__((aligned(16))) float s_h[kRows * KW];
+    __shared__ float s_part[NP][KW * CMAX];
     const int i = blockIdx.y;
-    const int kk = threadIdx.x % kCols, grp = threadIdx.x / kCols;
-    const int k = blockIdx.x * kCols + kk;
-    float acc[CMAX];
+    const int cls = threadIdx.x % CMAX;
+    const int kq = threadIdx.x % KW, cq = (threadIdx.x / KW) % CQ, part = threadIdx.x / (KW * CQ);
+    const int k_base = blockIdx.x * KW;
+    const bool bias_lane = blockIdx.x == 0 && (int)threadIdx.x < C;
+
+    // Operands of the fused update.  Output o of lane t is class t % CMAX of row k_base + t / CMAX + o (256 / CMAX).
+    float ux[kOut], ub[kOut], uz[kOut], bx = 0.0f, bb = 0.0f, bz = 0.0f;
+    if (upd.enabled) {
 #pragma unroll
-    for (int c = 0; c < CMAX; ++c) acc[c] = 0.0f;
+        for (int o = 0; o < kOut; ++o) {
+            const int kk = k_base + threadIdx.x / CMAX + o * (kThreads / CMAX);
+            ux[o] = ub[o] = uz[o] = 0.0f;
+            if (cls < C && kk < H) {
+                const int64_t col = w_off + (int64_t)kk * C + cls, idx = (int64_t)i * ld + col;
+                ux[o] = upd.x_in[idx];
+                if (upd.mu != 0.0f) ub[o] = upd.buf[idx];
+                if (upd.pull) uz[o] = upd.z[col];
+            }
+        }
+        if (bias_lane) {
+            const int64_t col = b_off + threadIdx.x, idx = (int64_t)i * ld + col;
+            bx = upd.x_in[idx];
+            if (upd.mu != 0.0f) bb = upd.buf[idx];
+            if (upd.pull) bz = upd.z[col];
+        }
+    }
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
     float bias_acc = 0.0f;
     for (int s0 = 0; s0 < B; s0 += kRows) {
         const int rows = min(kRows, B - s0);
-        __syncthreads();
-        for (int t = threadIdx.x; t < rows * C; t += kThreads) s_dl[t] = dlogits[((int64_t)i * B + s0) * C + t];
-        __syncthreads();
-        if (k < H) {
-            constexpr int kBatch = 8;   // activation loads in flight per lane
-            for (int sb = grp; sb < rows; sb += kGroups * kBatch) {
-                float hv[kBatch];
+        if (s0 > 0) __syncthreads();
+        {   // dlogits rows (zero beyond C and beyond the batch) and the activation tile, one round trip
+            const float* src = dlogits + ((int64_t)i * B + s0) * C + cls;
+            float tmp[kStage];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const int s = sb + u * kGroups;
-                    hv[u] = s < rows ? load_act<BF>(h, (int64_t)i * h_stride + (int64_t)(s0 + s) * H + k) : 0.0f;
-                }
+            for (int u = 0; u < kStage; ++u) {
+                const int r = threadIdx.x / CMAX + u * (kThreads / CMAX);
+                tmp[u] = (cls < C && r < rows) ? src[r * C] : 0.0f;
+            }
+            f4 th[kTile];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const int s = sb + u * kGroups;
-                    if (s < rows) {
-#pragma unroll
-                        for (int c = 0; c < CMAX; ++c)
-                            if (c < C) acc[c] = __fmaf_rn(hv[u], s_dl[s * C + c], acc[c]);
+            for (int u = 0; u < kTile; ++u) {
+                const int f = threadIdx.x + u * kThreads, r = f / (KW / 4), k = k_base + 4 * (f % (KW / 4));
+                th[u] = f4{0.f, 0.f, 0.f, 0.f};
+                if (r < rows && k < H) {   // H is a multiple of 4
+                    const int64_t idx = (int64_t)i * h_stride + (int64_t)(s0 + r) * H + k;
+                    if constexpr (BF) {
+                        const u2 w = *(const u2*)((const uint16_t*)h + idx);
+                        th[u] = f4{bf16_elem(w.x, 0), bf16_elem(w.x, 1), bf16_elem(w.y, 0), bf16_elem(w.y, 1)};
+                    } else {
+                        th[u] = *(const f4*)((const float*)h + idx);
                     }
                 }
             }
+#pragma unroll
+            for (int u = 0; u < kStage; ++u) {
+                const int r = threadIdx.x / CMAX + u * (kThreads / CMAX);
+                s_dl[r * P + cls] = tmp[u];
+            }
+#pragma unroll
+            for (int u = 0; u < kTile; ++u) *(f4*)(s_h + 4 * (threadIdx.x + u * kThreads)) = th[u];
         }
-        if (blockIdx.x == 0 && threadIdx.x < C)
-            for (int s = 0; s < rows; ++s) bias_acc += s_dl[s * C + threadIdx.x];
+        __syncthreads();
+#pragma unroll 4
+        for (int sidx = part; sidx < rows; sidx += NP) {
+            const float hv = s_h[sidx * KW + kq];
+            const f4 dl = *(const f4*)(s_dl + sidx * P + 4 * cq);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = __fmaf_rn(hv, dl[q], acc[q]);
+        }
+        if (bias_lane)
+            for (int sidx = 0; sidx < rows; ++sidx) bias_acc += s_dl[sidx * P + threadIdx.x];
     }
 #pragma unroll
-    for (int c = 0; c < CMAX; ++c) s_part[grp][c][kk] = acc[c];
+    for (int q = 0; q < 4; ++q) s_part[part][kq * CMAX + 4 * cq + q] = acc[q];
     __syncthreads();
-    // the 32 rows of this workgroup are one contiguous run of 32 C floats in g: lane t finishes
-    // element t of that run (row t / C, class t % C), summing the lane groups in a fixed order
-    const int k_base = blockIdx.x * kCols;
-    for (int t = threadIdx.x; t < kCols * C; t += kThreads) {
-        const int kl = t / C, c = t % C;
-        float v = 0.0f;
 #pragma unroll
-        for (int j = 0; j < kGroups; ++j) v += s_part[j][c][kl];
-        if (k_base + kl < H) {
-            const int64_t col = w_off + (int64_t)k_base * C + t, idx = (int64_t)i * ld + col;
-            if (upd.enabled) fused_update_apply(upd, idx, col, v, upd.x_in[idx], upd.mu != 0.0f ? upd.buf[idx] : 0.0f);
+    for (int o = 0; o < kOut; ++o) {
+        const int t = threadIdx.x + o * kThreads;   // = (row inside the workgroup) * CMAX + class
+        const int kk = k_base + t / CMAX;
+        if (cls < C && kk < H) {
+            float v = s_part[0][t];
+#pragma unroll
+            for (int q = 1; q < NP; ++q) v += s_part[q][t];
+            const int64_t idx = (int64_t)i * ld + w_off + (int64_t)kk * C + cls;
+            if (upd.enabled) fused_update_store(upd, idx, v, ux[o], ub[o], uz[o]);
             else g[idx] = v;
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x < C) {
-        const int64_t col = b_off + threadIdx.x, idx = (int64_t)i * ld + col;
-        if (upd.enabled) fused_update_apply(upd, idx, col, bias_acc, upd.x_in[idx], upd.mu != 0.0f ? upd.buf[idx] : 0.0f);
+    if (bias_lane) {
+        const int64_t idx = (int64_t)i * ld + b_off + threadIdx.x;
+        if (upd.enabled) fused_update_store(upd, idx, bias_acc, bx, bb, bz);
         else g[idx] = bias_acc;
-    }
-}
-
-// dz[s][k] = (sum_c dlogits[s][c] W[k][c]) * [h[s][k] > 0];  grid (ceil(H / 256), ceil(B / ROWS), m)
-template <bool BF, int CMAX, int ROWS>
-__global__ __launch_bounds__(kThreads) void head_dz_kernel(const void* __restrict__ h, int64_t h_stride,
-                                                           const float* __restrict__ x, int64_t ld, int64_t w_off,
-                                                           const float* __restrict__ dlogits, void* __restrict__ dz,
-                                                           void* __restrict__ dz_t, int B, int H, int C) {
-    __shared__ float s_dl[ROWS * kMaxC];
-    __shared__ float s_w[kThreads * (CMAX + 1)];
-    const int i = blockIdx.z;
-    const int s0 = blockIdx.y * ROWS;
-    const int rows = min(ROWS, B - s0);
-    const int k0 = blockIdx.x * kThreads;
-    const int CP = C | 1;
-    for (int t = threadIdx.x; t < rows * C; t += kThreads) s_dl[t] = dlogits[((int64_t)i * B + s0) * C + t];
-    stage_weights(s_w, x + (int64_t)i * ld + w_off, k0, min(kThreads, H - k0), C, CP);
-    __syncthreads();
-    const int k = k0 + threadIdx.x;
-    if (k >= H) return;
-    float w[CMAX];
-#pragma unroll
-    for (int c = 0; c < CMAX; ++c) w[c] = c < C ? s_w[threadIdx.x * CP + c] : 0.0f;
-    uint16_t tr[ROWS];
-#pragma unroll
-    for (int s = 0; s < ROWS; ++s) {
-        tr[s] = 0;
-        if (s < rows) {
-            const int64_t idx = (int64_t)(s0 + s) * H + k;
-            float acc = 0.0f;
-#pragma unroll
-            for (int c = 0; c < CMAX; ++c)
-                if (c < C) acc = __fmaf_rn(s_dl[s * C + c], w[c], acc);
-            const float hv = load_act<BF>(h, (int64_t)i * h_stride + idx);
-            const float v = hv > 0.0f ? acc : 0.0f;
-            if (BF) {
-                tr[s] = f32_to_bf16(v);
-                ((uint16_t*)dz)[(int64_t)i * B * H + idx] = tr[s];
-            } else {
-                ((float*)dz)[(int64_t)i * B * H + idx] = v;
-            }
-        }
-    }
-    if (BF && dz_t) {  // transposed copy [H][B]: ROWS consecutive samples of column k
-        uint16_t* o = (uint16_t*)dz_t + (int64_t)i * B * H + (int64_t)k * B + s0;
-        if (rows == ROWS && ROWS == 8) {
-            typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-            u4 pk;
-            pk.x = tr[0] | ((unsigned)tr[1] << 16);
-            pk.y = tr[2] | ((unsigned)tr[3] << 16);
-            pk.z = tr[4] | ((unsigned)tr[5] << 16);
-            pk.w = tr[6] | ((unsigned)tr[7] << 16);
-            *(u4*)o = pk;
-        } else {
-            for (int s = 0; s < rows; ++s) o[s] = tr[s];
-        }
     }
 }
 
 static bool head_args_ok(const HeadArgs& a) {
     return a.h && a.x && a.g && a.labels && a.dlogits && a.loss_parts && a.m >= 1 && a.m <= 65535 && a.B >= 1 &&
-           a.H >= 1 && a.C >= 1 && a.C <= kMaxC && a.w_off >= 0 && a.b_off >= 0 &&
-           a.w_off + (int64_t)a.H * a.C <= a.ld && a.b_off + a.C <= a.ld;
+           a.H >= 4 && a.H % 4 == 0 && a.C >= 1 && a.C <= kMaxC && a.w_off >= 0 && a.b_off >= 0 &&
+           a.w_off + (int64_t)a.H * a.C <= a.ld && a.b_off + a.C <= a.ld &&
+           (reinterpret_cast<uintptr_t>(a.h) & 15u) == 0 && a.h_stride % 4 == 0;
 }
 
-hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
-    if (!head_args_ok(a)) return hipErrorInvalidValue;
-    const int spw = a.C <= 16 ? 4 : 2;   // samples per wavefront = 64 / CMAX
-    dim3 grid((unsigned)((a.B + 4 * spw - 1) / (4 * spw)), (unsigned)a.m);
-#define OLS_HEAD_FWD(BF, CM)                                                                                       \
-    head_fwd_kernel<BF, CM><<<grid, kThreads, 0, s>>>(a.h, a.h_stride, a.x, a.ld, a.w_off, a.b_off, a.labels,      \
-                                                      a.label_stride, a.dlogits, a.loss_parts, a.B, a.H, a.C)
-    if (a.h_bf16) {
-        if (a.C <= 16) OLS_HEAD_FWD(true, 16); else OLS_HEAD_FWD(true, 32);
-    } else {
-        if (a.C <= 16) OLS_HEAD_FWD(false, 16); else OLS_HEAD_FWD(false, 32);
+template <bool BF, int CMAX, int KC>
+static hipError_t head_fwd_launch(const HeadDev& p, int m, hipStream_t s) {
+    size_t lds = (size_t)head_fwd_lds_floats(CMAX, KC) * sizeof(float);
+    if (BF) lds += (size_t)kRow * (4 * kHeadSamples + 8) * sizeof(uint16_t);
+    auto kern = head_fwd_kernel<BF, CMAX, KC>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
     }
-#undef OLS_HEAD_FWD
+    dim3 grid((unsigned)((p.B + kHeadSamples - 1) / kHeadSamples), (unsigned)m);
+    kern<<<grid, kHeadThreads, lds, s>>>(p);
     return hipGetLastError();
 }
 
+// logits, loss, dlogits, and (when a.dz is set) the delta of the last hidden layer
+hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
+    if (!head_args_ok(a)) return hipErrorInvalidValue;
+    // 16-byte activation vectors: 4 floats or 8 bf16; the transposed bf16 copy is written in pieces of 8 samples
+    if (a.h_bf16 && (a.H % 8 || a.h_stride % 8)) return hipErrorInvalidValue;
+    if (a.dz && (reinterpret_cast<uintptr_t>(a.dz) & 15u)) return hipErrorInvalidValue;
+    if (a.dz_t && (!a.h_bf16 || !a.dz || a.B % 8 || (reinterpret_cast<uintptr_t>(a.dz_t) & 15u)))
+        return hipErrorInvalidValue;
+    HeadDev p;
+    p.h = a.h;
+    p.x = a.x;
+    p.labels = a.labels;
+    p.dlogits = a.dlogits;
+    p.loss_parts = a.loss_parts;
+    p.dz = a.dz;
+    p.dz_t = a.dz_t;
+    p.h_stride = a.h_stride;
+    p.ld = a.ld;
+    p.w_off = a.w_off;
+    p.b_off = a.b_off;
+    p.label_stride = a.label_stride;
+    p.B = a.B;
+    p.H = a.H;
+    p.C = a.C;
+    // Wider layers are staged 1024 hidden units at a time (146 KiB of LDS with 16 classes): half as many
+    // dependent passes, and up to H = 1024 the delta reuses what the logits staged.
+    const bool wide = a.H > 512 && a.C <= 16;
+    if (a.h_bf16) {
+        if (a.C > 16) return head_fwd_launch<true, 32, 512>(p, a.m, s);
+        return wide ? head_fwd_launch<true, 16, 1024>(p, a.m, s) : head_fwd_launch<true, 16, 512>(p, a.m, s);
+    }
+    if (a.C > 16) return head_fwd_launch<false, 32, 512>(p, a.m, s);
+    return wide ? head_fwd_launch<false, 16, 1024>(p, a.m, s) : head_fwd_launch<false, 16, 512>(p, a.m, s);
+}
+
+// gradients of the output layer's weights and bias (stored to g, or consumed by the fused update)
 hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s) {
     if (!head_args_ok(a)) return hipErrorInvalidValue;
     if (a.upd.enabled && (!a.upd.x_in || !a.upd.x_out || (a.upd.mu != 0.0f && !a.upd.buf) || (a.upd.pull && !a.upd.z) ||
                           a.upd.ld != a.ld))
         return hipErrorInvalidValue;
-    // the delta for the last hidden layer first: it reads the output weights, which the gradient kernel
-    // may then update in place
-    if (a.dz) {
-        constexpr int kRows = 8;
-        const unsigned by = (unsigned)((a.B + kRows - 1) / kRows);
-        if (by > 65535u || a.m > 65535) return hipErrorInvalidValue;
-        dim3 grid_z((unsigned)((a.H + kThreads - 1) / kThreads), by, (unsigned)a.m);
-#define OLS_HEAD_DZ(BF, CM)                                                                                        \
-    head_dz_kernel<BF, CM, kRows><<<grid_z, kThreads, 0, s>>>(a.h, a.h_stride, a.x, a.ld, a.w_off, a.dlogits,      \
-                                                              a.dz, a.dz_t, a.B, a.H, a.C)
-        if (a.h_bf16) {
-            if (a.C <= 16) OLS_HEAD_DZ(true, 16); else OLS_HEAD_DZ(true, 32);
-        } else {
-            if (a.C <= 16) OLS_HEAD_DZ(false, 16); else OLS_HEAD_DZ(false, 32);
-        }
-#undef OLS_HEAD_DZ
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    dim3 grid_w((unsigned)((a.H + 31) / 32), (unsigned)a.m);
-#define OLS_HEAD_DW(BF, CM)                                                                                        \
-    head_dw_kernel<BF, CM><<<grid_w, kThreads, 0, s>>>(a.h, a.h_stride, a.dlogits, a.g, a.ld, a.w_off, a.b_off,    \
-                                                       a.B, a.H, a.C, a.upd)
+    dim3 grid((unsigned)((a.H + 31) / 32), (unsigned)a.m);
+#define OLS_HEAD_DW(BF, CM)                                                                                       \
+    head_dw_kernel<BF, CM><<<grid, 256, 0, s>>>(a.h, a.h_stride, a.dlogits, a.g, a.ld, a.w_off, a.b_off, a.B,     \
+                                               a.H, a.C, a.upd)
     if (a.h_bf16) {
         if (a.C <= 16) OLS_HEAD_DW(true, 16); else OLS_HEAD_DW(true, 32);
     } else {

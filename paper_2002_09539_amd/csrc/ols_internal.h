@@ -93,6 +93,25 @@ __device__ __forceinline__ void fused_update_apply(const FusedUpdate& u, int64_t
         u.shadow[idx] = (uint16_t)((w + 0x7FFFu + ((w >> 16) & 1u)) >> 16);
     }
 }
+// The same with the anchor value passed in as well (all operands were fetched ahead of the gradient).
+__device__ __forceinline__ void fused_update_store(const FusedUpdate& u, int64_t idx, float g, float x, float b,
+                                                   float z) {
+    float xh;
+    if (u.mu != 0.0f) {
+        b = __fmaf_rn(u.mu, b, g);
+        const float dir = u.nesterov ? __fmaf_rn(u.mu, b, g) : b;
+        xh = __fmaf_rn(-u.gamma, dir, x);
+        u.buf[idx] = b;
+    } else {
+        xh = __fmaf_rn(-u.gamma, g, x);
+    }
+    if (u.pull) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, z), xh);
+    u.x_out[idx] = xh;
+    if (u.shadow) {
+        const unsigned int w = __float_as_uint(xh);
+        u.shadow[idx] = (uint16_t)((w + 0x7FFFu + ((w >> 16) & 1u)) >> 16);
+    }
+}
 #endif
 
 // grouped GEMMs over the m workers (group strides in elements)
