@@ -2,30 +2,42 @@
 // (v_mfma_f32_32x32x16_bf16, gfx950) for the hidden layers of the per-worker MLPs, plus the fp32 ->
 // bf16 conversion of the input batch.  One group per worker, all groups in one launch.
 //
-//   FWD  C[M][N] = relu(A[M][K] W[K][N] + bias[N])   A: bf16 activations; W: bf16 copy of the weights;
-//                                                    C: bf16, stored row-major and transposed
-//   DW   C[M][N] = At[M][K] Bt[N][K]^T               At, Bt: transposed bf16 copies of activations and
-//                                                    deltas (K = batch, contiguous); C: fp32 gradient
-//   DA   C[M][N] = (A[M][K] W[N][K]^T) * [mask > 0]  A: bf16 delta; W rows are contiguous in K;
-//                                                    C: bf16, stored row-major and transposed
+//   FWD  C[M][N] = relu(A[M][K] W[K][N] + bias[N])   A: bf16 activations; W: bf16 copy of the weights; C: bf16
+//   DW   C[M][N] = A[K][M]^T B[K][N]                 A: bf16 activations, B: bf16 deltas (K = batch); C: fp32
+//                                                    gradient, or consumed by the fused update
+//   DA   C[M][N] = (A[M][K] W[N][K]^T) * [mask > 0]  A: bf16 delta; W rows are contiguous in K; C: bf16
 //
 // (forward / backward of the mini-batch loss whose gradient is the g_i of Section 2, arXiv 2002.09539;
 // operands are rounded to bf16 with round-to-nearest-even, products and sums are fp32.)
 //
-// The MFMA takes, per lane, 8 consecutive contraction indices of one row of each operand, so both
-// operand tiles live in LDS as [row][BK + 8] bf16 and a fragment is one 16-byte LDS read.  Operands
-// that are K-contiguous in memory are copied with 16-byte vectors.  The forward pass' weight tile is
-// N-contiguous in memory: each lane fetches a 4 (k) x 8 (n) patch with four 16-byte loads, transposes
-// it in registers and writes eight 8-byte column pieces, so the LDS image is K-contiguous as well.
-// The epilogues that produce bf16 activations / deltas also write the transposed copy the
-// weight-gradient GEMM needs (an accumulator lane holds 4 consecutive rows of one column, i.e. one
-// 8-byte piece of the transposed matrix).
+// Every operand tile is copied global -> registers -> LDS in its own memory order with 16-byte vectors;
+// nothing is transposed on the way and no transposed copies of activations or deltas exist in memory.
+// The MFMA takes, per lane, 8 consecutive contraction indices of one row of an operand:
+//   * an operand that is K-contiguous in memory ("KC", tile [rows][BK + 8]) yields a fragment as one
+//     16-byte LDS read;
+//   * an operand whose rows are contiguous ("RC", memory [K][rows], tile [BK][rows + 32]) yields it as two
+//     LDS transpose reads (ds_read_b64_tr_b16): within each block of 16 lanes, lane j passes the address of
+//     an 8-byte piece and lane i receives element i % 4 of the pieces of lanes i / 4, 4 + i / 4, 8 + i / 4,
+//     12 + i / 4 (checked with an in-bounds probe).  With lane j pointing at row k0 + j / 4, columns
+//     n0 + 4 (j % 4) .., lane i therefore receives column n0 + i of rows k0 .. k0 + 3: four consecutive k.
+// Row paddings keep both read patterns free of bank conflicts.
+//
+// The forward and delta GEMMs use 256 x 128 tiles with four wavefronts of 128 x 64: the per-wavefront
+// tile sets the LDS traffic per MFMA (6 fragment reads per 8 MFMAs), and at batch 256 one tile row spans
+// the whole batch so that each weight panel is fetched from HBM exactly once.  Fragment reads run one
+// k-step ahead of the MFMAs, and two K slices of global loads are in flight.  The weight-gradient GEMM is
+// bound by the HBM traffic of the fused update in its epilogue, not by the contraction (K = batch), and
+// uses 128 x 128 tiles so that several workgroups share a compute unit and overlap their phases.
+#include <type_traits>
+
 #include "gemm_epilogue.h"
 #include "ols_internal.h"
 
 namespace ols {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s4v __attribute__((ext_vector_type(4)));
+typedef short s8v __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
@@ -46,113 +58,145 @@ struct GemmDevB {
     const uint16_t* a;
     const uint16_t* b;
     void* c;
-    uint16_t* c_t;
     const float* bias;
     const uint16_t* mask;
     float* colsum;
     FusedUpdate upd;     // DW: update applied in the epilogue instead of storing the gradient
     int64_t upd_w_off, upd_b_off;
-    int64_t sa, sb, sc, sct, sbias, smask, scolsum;
+    int64_t sa, sb, sc, sbias, smask, scolsum;
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
 };
 
-// K-contiguous operand tile: ROWS x BK bf16 copied with 16-byte vectors into [ROWS][BK + 8].
+// K-contiguous operand tile: memory [rows][K]; LDS [ROWS][BK + 8].
 template <int ROWS, int BK>
 struct TileKC {
     static constexpr int kPitch = BK + 8;                 // bf16 elements; 16-byte aligned rows
-    static constexpr int kVecPerRow = BK / 8;
-    static constexpr int kVecs = ROWS * kVecPerRow;
+    static constexpr int kVecPerLine = BK / 8;
+    static constexpr int kVecs = ROWS * kVecPerLine;
     static constexpr int kPerThread = (kVecs + kThreads - 1) / kThreads;
     static constexpr int kElems = ROWS * kPitch;
-    __device__ static void load(u4 (&r)[kPerThread], const uint16_t* __restrict__ base, int ld, int row0, int k0,
-                                int rows, int klen) {
+    // Every lane ALWAYS issues its loads (out-of-range lanes re-read the operand's first vector) and the
+    // zero fill is applied when the registers are written to LDS: no branch around the loads, so a later
+    // slice's loads stay in flight while an earlier slice is stored.
+    __device__ static unsigned load(u4 (&r)[kPerThread], const uint16_t* __restrict__ base, int ld, int row0, int k0,
+                                    int rows, int klen) {
+        unsigned okmask = 0;
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
             const int v = threadIdx.x + t * kThreads;
-            u4 val = {0u, 0u, 0u, 0u};
+            const int row = row0 + v / kVecPerLine, k = k0 + (v % kVecPerLine) * 8;
+            const bool ok = (kVecs % kThreads == 0 || v < kVecs) && row < rows && k < klen;
+            r[t] = *(const u4*)(base + (ok ? (int64_t)row * ld + k : 0));
+            okmask |= ok ? (1u << t) : 0u;
+        }
+        return okmask;
+    }
+    __device__ static void store(uint16_t* lds, const u4 (&r)[kPerThread], unsigned okmask) {
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t) {
+            const int v = threadIdx.x + t * kThreads;
             if (kVecs % kThreads == 0 || v < kVecs) {
-                const int row = row0 + v / kVecPerRow, k = k0 + (v % kVecPerRow) * 8;
-                if (row < rows && k < klen) val = *(const u4*)(base + (int64_t)row * ld + k);
+                const u4 zero = {0u, 0u, 0u, 0u};
+                *(u4*)(lds + (v / kVecPerLine) * kPitch + (v % kVecPerLine) * 8) = (okmask >> t) & 1u ? r[t] : zero;
             }
-            r[t] = val;
         }
     }
-    __device__ static void store(uint16_t* lds, const u4 (&r)[kPerThread]) {
-#pragma unroll
-        for (int t = 0; t < kPerThread; ++t) {
-            const int v = threadIdx.x + t * kThreads;
-            if (kVecs % kThreads == 0 || v < kVecs)
-                *(u4*)(lds + (v / kVecPerRow) * kPitch + (v % kVecPerRow) * 8) = r[t];
-        }
+    // rows r0 .. r0 + 31, k-step s (16 contraction indices): lane holds k = 16 s + 8 (lane / 32) + 0..7 of row lane % 32
+    __device__ static bf16x8 frag(const uint16_t* lds, int r0, int s, int lane) {
+        return __builtin_bit_cast(bf16x8, *(const u4*)(lds + (r0 + lane % 32) * kPitch + 16 * s + 8 * (lane / 32)));
     }
+    // Full tiles (no bounds): vector t of a lane is kLineStep lines below vector 0, so one 32-bit lane offset
+    // plus wave-uniform bases address all of them and the loop carries no per-lane address arithmetic.
+    static constexpr int kLineStep = kThreads / kVecPerLine;
+    __device__ static unsigned lane_offset_bytes(int ld) {
+        return 2u * ((threadIdx.x / kVecPerLine) * (unsigned)ld + (threadIdx.x % kVecPerLine) * 8u);
+    }
+    __device__ static int64_t line_step_bytes(int ld) { return 2 * (int64_t)kLineStep * ld; }
+    __device__ static int64_t slice_step_bytes(int ld) { return 2 * (int64_t)BK; }
+    __device__ static uint16_t* lane_lds(uint16_t* lds) {
+        return lds + (threadIdx.x / kVecPerLine) * kPitch + (threadIdx.x % kVecPerLine) * 8;
+    }
+    static constexpr int kLdsLineStep = kLineStep * kPitch;
 };
 
-// N-contiguous operand tile (memory [K][N]) transposed into the same [ROWS = n][BK + 8] LDS image.
-// A task is a 4 (k) x 8 (n) patch; consecutive lanes take consecutive n-octets of the same k-quad so
-// that the four global loads of a wavefront are contiguous runs.
+// Row-contiguous operand tile: memory [K][rows]; LDS [BK][ROWS + 32], read with the transpose load.
 template <int ROWS, int BK>
-struct TileNC {
-    static constexpr int kPitch = BK + 8;
-    static constexpr int kOctets = ROWS / 8;
-    static constexpr int kTasks = kOctets * (BK / 4);
-    static constexpr int kPerThread = (kTasks + kThreads - 1) / kThreads;
-    static constexpr int kElems = ROWS * kPitch;
-    struct Regs {
-        u4 v[kPerThread][4];
-    };
-    __device__ static void load(Regs& r, const uint16_t* __restrict__ base, int ld, int n0, int k0, int ncols,
-                                int klen) {
+struct TileRC {
+    static constexpr int kPitch = ROWS + 32;              // pitch = 64 bytes mod 256: the 4 k-rows of a read hit distinct banks
+    static constexpr int kVecPerLine = ROWS / 8;
+    static constexpr int kVecs = BK * kVecPerLine;
+    static constexpr int kPerThread = (kVecs + kThreads - 1) / kThreads;
+    static constexpr int kElems = BK * kPitch;
+    __device__ static unsigned load(u4 (&r)[kPerThread], const uint16_t* __restrict__ base, int ld, int row0, int k0,
+                                    int rows, int klen) {
+        unsigned okmask = 0;
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
-            const int task = threadIdx.x + t * kThreads;
-            const int n = n0 + (task % kOctets) * 8, k = k0 + (task / kOctets) * 4;
+            const int v = threadIdx.x + t * kThreads;
+            const int k = k0 + v / kVecPerLine, row = row0 + (v % kVecPerLine) * 8;
+            const bool ok = (kVecs % kThreads == 0 || v < kVecs) && row < rows && k < klen;
+            r[t] = *(const u4*)(base + (ok ? (int64_t)k * ld + row : 0));
+            okmask |= ok ? (1u << t) : 0u;
+        }
+        return okmask;
+    }
+    __device__ static void store(uint16_t* lds, const u4 (&r)[kPerThread], unsigned okmask) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                u4 val = {0u, 0u, 0u, 0u};
-                if ((kTasks % kThreads == 0 || task < kTasks) && n < ncols && k + j < klen)
-                    val = *(const u4*)(base + (int64_t)(k + j) * ld + n);
-                r.v[t][j] = val;
+        for (int t = 0; t < kPerThread; ++t) {
+            const int v = threadIdx.x + t * kThreads;
+            if (kVecs % kThreads == 0 || v < kVecs) {
+                const u4 zero = {0u, 0u, 0u, 0u};
+                *(u4*)(lds + (v / kVecPerLine) * kPitch + (v % kVecPerLine) * 8) = (okmask >> t) & 1u ? r[t] : zero;
             }
         }
     }
-    __device__ static void store(uint16_t* lds, const Regs& r) {
-#pragma unroll
-        for (int t = 0; t < kPerThread; ++t) {
-            const int task = threadIdx.x + t * kThreads;
-            if (kTasks % kThreads == 0 || task < kTasks) {
-                const int nl = (task % kOctets) * 8, kl = (task / kOctets) * 4;
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {  // dword p of each row holds columns 2p (low) and 2p + 1 (high)
-                    const unsigned int w0 = r.v[t][0][p], w1 = r.v[t][1][p], w2 = r.v[t][2][p], w3 = r.v[t][3][p];
-                    u2 lo, hi;
-                    lo.x = (w0 & 0xFFFFu) | (w1 << 16);
-                    lo.y = (w2 & 0xFFFFu) | (w3 << 16);
-                    hi.x = (w0 >> 16) | (w1 & 0xFFFF0000u);
-                    hi.y = (w2 >> 16) | (w3 & 0xFFFF0000u);
-                    *(u2*)(lds + (nl + 2 * p) * kPitch + kl) = lo;
-                    *(u2*)(lds + (nl + 2 * p + 1) * kPitch + kl) = hi;
-                }
-            }
-        }
+    __device__ static bf16x8 frag(const uint16_t* lds, int r0, int s, int lane) {
+        const int blk = lane / 16, j = lane % 16;
+        const uint16_t* p = lds + (16 * s + 8 * (blk / 2) + j / 4) * kPitch + r0 + 16 * (blk % 2) + 4 * (j % 4);
+        typedef s4v __attribute__((address_space(3))) * lds_s4_ptr;
+        const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)p);
+        const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(p + 4 * kPitch));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
+    static constexpr int kLineStep = kThreads / kVecPerLine;   // k-rows between consecutive vectors of a lane
+    __device__ static unsigned lane_offset_bytes(int ld) {
+        return 2u * ((threadIdx.x / kVecPerLine) * (unsigned)ld + (threadIdx.x % kVecPerLine) * 8u);
+    }
+    __device__ static int64_t line_step_bytes(int ld) { return 2 * (int64_t)kLineStep * ld; }
+    __device__ static int64_t slice_step_bytes(int ld) { return 2 * (int64_t)BK * ld; }
+    __device__ static uint16_t* lane_lds(uint16_t* lds) {
+        return lds + (threadIdx.x / kVecPerLine) * kPitch + (threadIdx.x % kVecPerLine) * 8;
+    }
+    static constexpr int kLdsLineStep = kLineStep * kPitch;
 };
 
 template <int MODE, int BM, int BN, int BK>
+struct GemmShape {
+    using TA = typename std::conditional<MODE == kDw, TileRC<BM, BK>, TileKC<BM, BK>>::type;   // FWD, DA: A[M][K]; DW: A[K][M]
+    using TB = typename std::conditional<MODE == kDa, TileKC<BN, BK>, TileRC<BN, BK>>::type;   // DA: W[N][K]; FWD, DW: B[K][N]
+    static constexpr int kOperandElems = 2 * TA::kElems + 2 * TB::kElems;
+    static constexpr int kStagePitch = BN + 8;            // bf16 output tile staged for 16-byte stores
+    static constexpr int kStageElems = MODE == kDw ? 0 : BM * kStagePitch;
+    static constexpr int kLdsElems = kOperandElems > kStageElems ? kOperandElems : kStageElems;
+    static constexpr size_t kLdsBytes = (size_t)kLdsElems * sizeof(uint16_t);
+};
+
+template <int MODE, int BM, int BN, int BK, int DEPTH>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
     constexpr int WM = BM / 2, WN = BN / 2;     // 2 x 2 wavefronts
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int S = BK / 16;                  // MFMA steps per K slice
-    static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "tile shape");
-    using TA = TileKC<BM, BK>;
-    using TBK = TileKC<BN, BK>;
-    using TBN = TileNC<BN, BK>;
-    constexpr int kPitch = TA::kPitch;
-    constexpr int kLdsElems = 2 * TA::kElems + 2 * TBK::kElems;
-    __shared__ __attribute__((aligned(16))) uint16_t lds_all[kLdsElems];
+    static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 32 == 0, "tile shape");
+    static_assert(DEPTH == 1 || DEPTH == 2, "global prefetch distance in K slices");
+    using Shape = GemmShape<MODE, BM, BN, BK>;
+    using TA = typename Shape::TA;
+    using TB = typename Shape::TB;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds_all[];
     auto lds_a = [&](int buf) { return lds_all + buf * TA::kElems; };
-    auto lds_b = [&](int buf) { return lds_all + 2 * TA::kElems + buf * TBK::kElems; };
+    auto lds_b = [&](int buf) { return lds_all + 2 * TA::kElems + buf * TB::kElems; };
 
+    // XCD-aware tile id: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous tile range
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const int tile = xcd * p.chunk + slot;
     if (slot >= p.chunk || tile >= p.total_tiles) return;
@@ -175,74 +219,109 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // DW only: the first tile row also sums each row of Bt (a delta column over the batch), which is
-    // the bias gradient of the layer, in sample order.
-    const bool row_sums = MODE == kDw && p.colsum != nullptr && tm == 0 && threadIdx.x < BN;
-    float row_acc = 0.0f;
+    // DW only: the tiles of the first tile row also sum each column of B (a delta column over the batch),
+    // which is the bias gradient of the layer, in sample order.
+    const bool col_sums = MODE == kDw && p.colsum != nullptr && tm == 0 && threadIdx.x < BN;
+    float col_acc = 0.0f;
 
-    u4 ra[TA::kPerThread];
-    u4 rbk[TBK::kPerThread];
-    typename TBN::Regs rbn;
-    auto load_tiles = [&](int k0) {
-        TA::load(ra, A, p.lda, m0, k0, p.M, p.K);
-        if (MODE == kFwd) TBN::load(rbn, B, p.ldb, n0, k0, p.N, p.K);
-        else TBK::load(rbk, B, p.ldb, n0, k0, p.N, p.K);
+    // Fragment registers are double-buffered across k-steps, and the order "issue the LDS reads of step
+    // s + 1, then the MFMAs of step s" is pinned with scheduling barriers: a wavefront stalls at the issue
+    // of an MFMA while the matrix pipe is busy, so reads placed behind the MFMAs would start only when the
+    // pipe is about to drain and their latency would be exposed on every step.
+    static_assert(S % 2 == 0, "an even number of k-steps per slice");
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int buf, int cur, int s) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[buf][i] = TA::frag(lds_a(cur), wm0 + 32 * i, s, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = TB::frag(lds_b(cur), wn0 + 32 * j, s, lane);
     };
-    auto store_tiles = [&](int buf) {
-        TA::store(lds_a(buf), ra);
-        if (MODE == kFwd) TBN::store(lds_b(buf), rbn);
-        else TBK::store(lds_b(buf), rbk);
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
     };
-    auto frag = [&](const uint16_t* lds, int r0, int s) {
-        return *(const u4*)(lds + (r0 + lane32) * kPitch + 16 * s + 8 * half);
-    };
-
-    const int nk = (p.K + BK - 1) / BK;
-    load_tiles(0);
-    store_tiles(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    // One K slice out of lds[cur].  On entry the fragments of step 0 are already in (or on their way to)
+    // buffer 0.  Before the last step's MFMAs the staged registers of the next slice are published to
+    // lds[cur ^ 1], the workgroup synchronises once, and the first fragments of that slice are requested,
+    // so the barrier and the LDS latency hide behind the remaining MFMAs.
+    auto slice = [&](int cur, const u4 (&na)[TA::kPerThread], unsigned oka, const u4 (&nb)[TB::kPerThread],
+                     unsigned okb) {
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            u4 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = frag(lds_a(cur), wm0 + 32 * i, s);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = frag(lds_b(cur), wn0 + 32 * j, s);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
-                                                                        __builtin_bit_cast(bf16x8, fb[j]), acc[i][j],
-                                                                        0, 0, 0);
+        for (int s = 0; s + 1 < S; ++s) {
+            load_frags((s + 1) & 1, cur, s + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(s & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (MODE == kDw && row_sums) {
-            const uint16_t* row = lds_b(cur) + threadIdx.x * kPitch;
+        if (MODE == kDw && col_sums) {
 #pragma unroll
-            for (int k = 0; k < BK; k += 2) {
-                const unsigned int pair = *(const unsigned int*)(row + k);
-                row_acc += bf16_to_f32(pair & 0xFFFFu);
-                row_acc += bf16_to_f32(pair >> 16);
+            for (int k = 0; k < BK; ++k) col_acc += bf16_to_f32(lds_b(cur)[k * TB::kPitch + threadIdx.x]);
+        }
+        TA::store(lds_a(cur ^ 1), na, oka);
+        TB::store(lds_b(cur ^ 1), nb, okb);
+        __syncthreads();
+        load_frags(0, cur ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas((S - 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // The loop bodies below are free of data-dependent branches: loads past the end of K are zero-filled
+    // dummies and the tile published after the last slice is never consumed.
+    const int nk = (p.K + BK - 1) / BK;
+    if (DEPTH == 1) {
+        u4 ra[TA::kPerThread], rb[TB::kPerThread];
+        unsigned oka = TA::load(ra, A, p.lda, m0, 0, p.M, p.K);
+        unsigned okb = TB::load(rb, B, p.ldb, n0, 0, p.N, p.K);
+        TA::store(lds_a(0), ra, oka);
+        TB::store(lds_b(0), rb, okb);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            oka = TA::load(ra, A, p.lda, m0, (kt + 1) * BK, p.M, p.K);
+            okb = TB::load(rb, B, p.ldb, n0, (kt + 1) * BK, p.N, p.K);
+            slice(kt & 1, ra, oka, rb, okb);
+        }
+    } else {
+        // Two K slices of global loads in flight: while slice t feeds the matrix cores from LDS, slice
+        // t + 1 waits in registers and slice t + 2 is on its way from HBM.  Slices are consumed in pairs; an
+        // odd trailing slice is paired with an all-zero one.
+        u4 ra0[TA::kPerThread], rb0[TB::kPerThread], ra1[TA::kPerThread], rb1[TB::kPerThread];
+        unsigned oka0 = TA::load(ra0, A, p.lda, m0, 0, p.M, p.K);
+        unsigned okb0 = TB::load(rb0, B, p.ldb, n0, 0, p.N, p.K);
+        unsigned oka1 = TA::load(ra1, A, p.lda, m0, BK, p.M, p.K);
+        unsigned okb1 = TB::load(rb1, B, p.ldb, n0, BK, p.N, p.K);
+        TA::store(lds_a(0), ra0, oka0);
+        TB::store(lds_b(0), rb0, okb0);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        const int nk2 = (nk + 1) & ~1;
+        for (int kt = 0; kt < nk2; kt += 2) {
+            oka0 = TA::load(ra0, A, p.lda, m0, (kt + 2) * BK, p.M, p.K);
+            okb0 = TB::load(rb0, B, p.ldb, n0, (kt + 2) * BK, p.N, p.K);
+            slice(0, ra1, oka1, rb1, okb1);
+            oka1 = TA::load(ra1, A, p.lda, m0, (kt + 3) * BK, p.M, p.K);
+            okb1 = TB::load(rb1, B, p.ldb, n0, (kt + 3) * BK, p.N, p.K);
+            slice(1, ra0, oka0, rb0, okb0);
+        }
+    }
+
+    if constexpr (MODE == kDw) {
+        if (col_sums && n0 + (int)threadIdx.x < p.N) {
+            if (p.upd.enabled) {   // bias: gradient is the sum just formed
+                const int64_t col = p.upd_b_off + n0 + threadIdx.x, idx = (int64_t)group * p.upd.ld + col;
+                fused_update_apply(p.upd, idx, col, col_acc, p.upd.x_in[idx], p.upd.mu != 0.0f ? p.upd.buf[idx] : 0.0f);
+            } else {
+                p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = col_acc;
             }
         }
-        if (kt + 1 < nk) store_tiles(cur ^ 1);
-        __syncthreads();
-    }
-    if (MODE == kDw && row_sums && n0 + (int)threadIdx.x < p.N) {
-        if (p.upd.enabled) {   // bias: gradient is the sum just formed
-            const int64_t col = p.upd_b_off + n0 + threadIdx.x, idx = (int64_t)group * p.upd.ld + col;
-            fused_update_apply(p.upd, idx, col, row_acc, p.upd.x_in[idx], p.upd.mu != 0.0f ? p.upd.buf[idx] : 0.0f);
-        } else {
-            p.colsum[(int64_t)group * p.scolsum + n0 + threadIdx.x] = row_acc;
-        }
-    }
-    if (MODE == kDw && p.upd.enabled) {
-        constexpr int kFit = ((kLdsElems / 2) / (BN + 4)) / 32 * 32;   // fp32 rows the operand LDS can stage
+        // the gradient tile is staged through the (now idle) operand LDS, as many rows per pass as it holds
+        constexpr int kFit = ((Shape::kLdsElems / 2) / (BN + 4)) / 32 * 32;
         constexpr int RP = kFit >= BM ? BM : kFit;
-        static_assert(RP >= 32, "operand LDS too small to stage the gradient tile");
+        static_assert(RP >= 32 && BM % RP == 0, "operand LDS too small to stage the gradient tile");
         DwOut o;
         o.g = (float*)p.c + (int64_t)group * p.sc;
         o.ldg = p.ldc;
@@ -250,71 +329,265 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
         o.upd_base = (int64_t)group * p.upd.ld + p.upd_w_off;
         o.col_base = p.upd_w_off;
         dw_epilogue_staged<BM, BN, TM, TN, RP, kThreads>((float*)lds_all, acc, o, m0, n0, wm0, wn0, p.M, p.N);
-        return;
-    }
-
-    // Epilogue.  Accumulator register r of a lane is C[row][col] with col = lane % 32 and
-    // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block: four consecutive rows per r / 4.
+    } else {
+        // Epilogue of FWD / DA: the bf16 tile goes through LDS so that every lane then moves 16-byte vectors
+        // of 8 consecutive columns (output, and the activations whose sign gates the delta).  Accumulator
+        // register r of a lane is C[row][col] with col = lane % 32 and row = 8 (r / 4) + 4 (lane / 32) + r % 4
+        // inside its 32 x 32 block.
+        constexpr int SP = Shape::kStagePitch;
+        __syncthreads();   // the tile published after the last slice is not read; everyone is past the loop
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+        for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn0 + 32 * j + lane32;
-            if (col >= p.N) continue;
-            float bias = 0.0f;
-            if (MODE == kFwd) bias = p.bias[(int64_t)group * p.sbias + col];
+            for (int j = 0; j < TN; ++j) {
+                const int cl = wn0 + 32 * j + lane32;
+                float bias = 0.0f;
+                if (MODE == kFwd && n0 + cl < p.N) bias = p.bias[(int64_t)group * p.sbias + n0 + cl];
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const int row = m0 + wm0 + 32 * i + 8 * rq + 4 * half;   // rows row .. row + 3 (M is a multiple of 4)
-                if (row >= p.M) continue;
-                if (MODE == kDw) {
-                    float* C = (float*)p.c + (int64_t)group * p.sc;
+                for (int r = 0; r < 16; ++r) {
+                    const int rl = wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
+                    float v = acc[i][j][r];
+                    if (MODE == kFwd) v = fmaxf(v + bias, 0.0f);
+                    lds_all[rl * SP + cl] = (uint16_t)bf16_rne(v);
+                }
+            }
+        }
+        __syncthreads();
+        constexpr int kVecPerRow = BN / 8, kVecs = BM * kVecPerRow;
+        static_assert(kVecs % kThreads == 0, "output tile vectors per lane");
+        uint16_t* C = (uint16_t*)p.c + (int64_t)group * p.sc;
+        const uint16_t* Mk = MODE == kDa ? p.mask + (int64_t)group * p.smask : nullptr;
+#pragma unroll 4
+        for (int t = 0; t < kVecs / kThreads; ++t) {
+            const int v = threadIdx.x + t * kThreads;
+            const int row = m0 + v / kVecPerRow, col = n0 + (v % kVecPerRow) * 8;
+            if (row < p.M && col < p.N) {   // N is a multiple of 8
+                u4 o = *(const u4*)(lds_all + (v / kVecPerRow) * SP + (v % kVecPerRow) * 8);
+                if (MODE == kDa) {
+                    const u4 mk = *(const u4*)(Mk + (int64_t)row * p.ldc + col);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) C[(int64_t)(row + e) * p.ldc + col] = acc[i][j][4 * rq + e];
-                } else {
-                    uint16_t* C = (uint16_t*)p.c + (int64_t)group * p.sc;
-                    unsigned int h[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float v = acc[i][j][4 * rq + e];
-                        if (MODE == kFwd) v = fmaxf(v + bias, 0.0f);
-                        if (MODE == kDa) {
-                            const unsigned int mk = p.mask[(int64_t)group * p.smask + (int64_t)(row + e) * p.ldc + col];
-                            v = bf16_to_f32(mk) > 0.0f ? v : 0.0f;
-                        }
-                        h[e] = bf16_rne(v);
-                        C[(int64_t)(row + e) * p.ldc + col] = (uint16_t)h[e];
-                    }
-                    if (p.c_t) {
-                        u2 pk;
-                        pk.x = h[0] | (h[1] << 16);
-                        pk.y = h[2] | (h[3] << 16);
-                        *(u2*)(p.c_t + (int64_t)group * p.sct + (int64_t)col * p.M + row) = pk;
+                    for (int w = 0; w < 4; ++w) {   // a bf16 is positive iff its sign bit is clear and it is not zero
+                        const unsigned int lo = mk[w] & 0xFFFFu, hi = mk[w] >> 16;
+                        const unsigned int keep = ((lo != 0u && lo < 0x8000u) ? 0xFFFFu : 0u) |
+                                                  ((hi != 0u && hi < 0x8000u) ? 0xFFFF0000u : 0u);
+                        o[w] &= keep;
                     }
                 }
+                *(u4*)(C + (int64_t)row * p.ldc + col) = o;
             }
         }
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// FWD / DA on full tiles: M % BM == 0, N % BN == 0, K % (2 BK) == 0.  One workgroup per compute unit, one
+// wavefront per SIMD: nothing else is resident to fill a stall, and a wavefront that has just issued an
+// MFMA cannot issue the next one for 32 cycles, so every other instruction of the loop (fragment reads,
+// the next slices' global loads, the LDS stores of the staged slice) is placed BETWEEN the MFMAs, one or
+// two per MFMA, with scheduling-group barriers.  Per K slice of 64 and wavefront: 32 MFMAs, 32 fragment
+// reads, 12 global loads, 12 LDS stores, one workgroup barrier; addresses are one lane offset plus
+// wave-uniform bases, so the loop has no vector address arithmetic.
+// ---------------------------------------------------------------------------------------------
+template <int MODE, int BM, int BN, int BK>
+__global__ __launch_bounds__(kThreads) void gemm_bf16_full_kernel(GemmDevB p) {
+    static_assert(MODE != kDw && BK == 64, "forward / delta GEMM, four k-steps per slice");
+    constexpr int WM = BM / 2, WN = BN / 2;     // 2 x 2 wavefronts
+    constexpr int TM = WM / 32, TN = WN / 32;
+    using Shape = GemmShape<MODE, BM, BN, BK>;
+    using TA = typename Shape::TA;
+    using TB = typename Shape::TB;
+    constexpr int NA = TA::kPerThread, NB = TB::kPerThread;
+    static_assert(TA::kVecs % kThreads == 0 && TB::kVecs % kThreads == 0, "whole vectors per lane");
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds_all[];
+    auto lds_a = [&](int buf) { return lds_all + buf * TA::kElems; };
+    auto lds_b = [&](int buf) { return lds_all + 2 * TA::kElems + buf * TB::kElems; };
+
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int tile = xcd * p.chunk + slot;
+    if (slot >= p.chunk || tile >= p.total_tiles) return;
+    const int per_group = p.tiles_m * p.tiles_n;
+    const int group = tile / per_group;
+    const int tm = (tile % per_group) / p.tiles_n, tn = tile % p.tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+    // tile origins of slice 0 (wave-uniform byte pointers)
+    const char* a_tile = (const char*)(p.a + (int64_t)group * p.sa + (int64_t)m0 * p.lda);
+    const char* b_tile = (const char*)(p.b + (int64_t)group * p.sb + (MODE == kFwd ? (int64_t)n0 : (int64_t)n0 * p.ldb));
+    const unsigned off_a = TA::lane_offset_bytes(p.lda), off_b = TB::lane_offset_bytes(p.ldb);
+    const int64_t line_a = TA::line_step_bytes(p.lda), line_b = TB::line_step_bytes(p.ldb);
+    const int64_t step_a = TA::slice_step_bytes(p.lda), step_b = TB::slice_step_bytes(p.ldb);
+
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int lane32 = lane % 32, half = lane / 32;
+    const int wm0 = (wave / 2) * WM, wn0 = (wave % 2) * WN;
+
+    f16v acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int buf, int cur, int s) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[buf][i] = TA::frag(lds_a(cur), wm0 + 32 * i, s, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = TB::frag(lds_b(cur), wn0 + 32 * j, s, lane);
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    };
+    auto load_a = [&](u4 (&r)[NA], const char* base) {
+#pragma unroll
+        for (int t = 0; t < NA; ++t) r[t] = *(const u4*)(base + t * line_a + off_a);
+    };
+    auto load_b = [&](u4 (&r)[NB], const char* base) {
+#pragma unroll
+        for (int t = 0; t < NB; ++t) r[t] = *(const u4*)(base + t * line_b + off_b);
+    };
+    auto store_a = [&](int buf, const u4 (&r)[NA]) {
+        uint16_t* q = TA::lane_lds(lds_a(buf));
+#pragma unroll
+        for (int t = 0; t < NA; ++t) *(u4*)(q + t * TA::kLdsLineStep) = r[t];
+    };
+    auto store_b = [&](int buf, const u4 (&r)[NB]) {
+        uint16_t* q = TB::lane_lds(lds_b(buf));
+#pragma unroll
+        for (int t = 0; t < NB; ++t) *(u4*)(q + t * TB::kLdsLineStep) = r[t];
+    };
+    // scheduling groups: one MFMA, then `reads` LDS reads, `writes` LDS writes, `loads` global loads
+    constexpr int kMfmas = TM * TN;
+#define OLS_INTERLEAVE(reads, writes, loads)                                        \
+    _Pragma("unroll") for (int q = 0; q < kMfmas; ++q) {                            \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          \
+        if ((reads) > 0) __builtin_amdgcn_sched_group_barrier(0x100, (reads), 0);   \
+        if ((writes) > 0) __builtin_amdgcn_sched_group_barrier(0x200, (writes), 0); \
+        if ((loads) > 0) __builtin_amdgcn_sched_group_barrier(0x020, (loads), 0);   \
+    }
+    constexpr int kReads = (TM + 2 * TN + kMfmas - 1) / kMfmas;          // LDS reads per MFMA (an RC fragment is two reads)
+    constexpr int kLoadsA = (NA + kMfmas - 1) / kMfmas, kLoadsB = (NB + kMfmas - 1) / kMfmas;
+    constexpr int kWrites = (NA + NB + kMfmas - 1) / kMfmas;
+    // One K slice out of lds[cur]: fragments of step 0 are in buffer 0 on entry.  `st` (the next slice,
+    // loaded one slice ago) is published to lds[cur ^ 1] during step 2; the slice after it is requested into
+    // `ld` during steps 0 and 1.
+    auto slice = [&](int cur, const u4 (&st_a)[NA], const u4 (&st_b)[NB], u4 (&ld_a)[NA], u4 (&ld_b)[NB],
+                     const char* next_a, const char* next_b) {
+        load_frags(1, cur, 1);
+        load_a(ld_a, next_a);
+        mfmas(0);
+        OLS_INTERLEAVE(kReads, 0, kLoadsA)
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(0, cur, 2);
+        load_b(ld_b, next_b);
+        mfmas(1);
+        OLS_INTERLEAVE(kReads, 0, kLoadsB)
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(1, cur, 3);
+        store_a(cur ^ 1, st_a);
+        store_b(cur ^ 1, st_b);
+        mfmas(0);
+        OLS_INTERLEAVE(kReads, kWrites, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        load_frags(0, cur ^ 1, 0);
+        mfmas(1);
+        OLS_INTERLEAVE(kReads, 0, 0)
+        __builtin_amdgcn_sched_barrier(0);
+    };
+#undef OLS_INTERLEAVE
+
+    const int nk = p.K / BK;   // even
+    u4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+    load_a(ra0, a_tile);
+    load_b(rb0, b_tile);
+    load_a(ra1, a_tile + step_a);
+    load_b(rb1, b_tile + step_b);
+    store_a(0, ra0);
+    store_b(0, rb0);
+    __syncthreads();
+    load_frags(0, 0, 0);
+    for (int kt = 0; kt < nk; kt += 2) {
+        // slices past the end re-read slice 0 (in bounds, never consumed)
+#ifdef OLS_EXP_HOTLOADS
+        const int k2 = 0, k3 = 0;
+#else
+        const int k2 = kt + 2 < nk ? kt + 2 : 0, k3 = kt + 3 < nk ? kt + 3 : 0;
+#endif
+        slice(0, ra1, rb1, ra0, rb0, a_tile + k2 * step_a, b_tile + k2 * step_b);
+        slice(1, ra0, rb0, ra1, rb1, a_tile + k3 * step_a, b_tile + k3 * step_b);
+    }
+
+    // Epilogue: the bf16 tile goes through LDS so that every lane then moves 16-byte vectors of 8 consecutive
+    // columns.  Accumulator register r of a lane is C[row][col] with col = lane % 32 and
+    // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block.
+    constexpr int SP = Shape::kStagePitch;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int cl = wn0 + 32 * j + lane32;
+            float bias = 0.0f;
+            if (MODE == kFwd) bias = p.bias[(int64_t)group * p.sbias + n0 + cl];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rl = wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
+                float v = acc[i][j][r];
+                if (MODE == kFwd) v = fmaxf(v + bias, 0.0f);
+                lds_all[rl * SP + cl] = (uint16_t)bf16_rne(v);
+            }
+        }
+    }
+    __syncthreads();
+    constexpr int kVecPerRow = BN / 8, kVecs = BM * kVecPerRow;
+    uint16_t* C = (uint16_t*)p.c + (int64_t)group * p.sc + (int64_t)m0 * p.ldc + n0;
+    const uint16_t* Mk = MODE == kDa ? p.mask + (int64_t)group * p.smask + (int64_t)m0 * p.ldc + n0 : nullptr;
+#pragma unroll 4
+    for (int t = 0; t < kVecs / kThreads; ++t) {
+        const int v = threadIdx.x + t * kThreads;
+        const int rl = v / kVecPerRow, cl = (v % kVecPerRow) * 8;
+        u4 o = *(const u4*)(lds_all + rl * SP + cl);
+        if (MODE == kDa) {
+            const u4 mk = *(const u4*)(Mk + (int64_t)rl * p.ldc + cl);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {   // a bf16 is positive iff its sign bit is clear and it is not zero
+                const unsigned int lo = mk[w] & 0xFFFFu, hi = mk[w] >> 16;
+                const unsigned int keep = ((lo != 0u && lo < 0x8000u) ? 0xFFFFu : 0u) |
+                                          ((hi != 0u && hi < 0x8000u) ? 0xFFFF0000u : 0u);
+                o[w] &= keep;
+            }
+        }
+        *(u4*)(C + (int64_t)rl * p.ldc + cl) = o;
+    }
+}
+
 static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
-template <int MODE, int BM, int BN, int BK>
+template <int MODE, int BM, int BN, int BK, int DEPTH>
 static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (!g.a || !g.b || !g.c || g.groups < 1 || g.M < 1 || g.N < 1 || g.K < 1) return hipErrorInvalidValue;
-    // 16-byte vectors of 8 bf16: aligned bases, leading dimensions and extents in multiples of 8
-    if (!aligned16(g.a) || !aligned16(g.b) || g.lda % 8 || g.ldb % 8 || g.sa % 8 || g.sb % 8 || g.K % 8)
-        return hipErrorInvalidValue;
-    if (MODE == kFwd && (g.N % 8 || g.ldb < g.N || !g.bias)) return hipErrorInvalidValue;
-    if (MODE != kFwd && g.ldb < g.K) return hipErrorInvalidValue;
-    if (g.lda < g.K || g.ldc < g.N || g.M % 4) return hipErrorInvalidValue;
-    if (MODE == kDa && !g.mask) return hipErrorInvalidValue;
-    if (g.c_t && ((reinterpret_cast<uintptr_t>(g.c_t) & 7u) || g.sct % 4)) return hipErrorInvalidValue;
+    // 16-byte vectors of 8 bf16 along each operand's contiguous dimension: aligned bases, leading
+    // dimensions and extents in multiples of 8
+    if (!aligned16(g.a) || !aligned16(g.b) || g.lda % 8 || g.ldb % 8 || g.sa % 8 || g.sb % 8) return hipErrorInvalidValue;
+    if (MODE == kDw) {   // A[K][M], B[K][N]
+        if (g.M % 8 || g.N % 8 || g.lda < g.M || g.ldb < g.N) return hipErrorInvalidValue;
+    } else {
+        if (g.K % 8 || g.N % 8 || g.lda < g.K) return hipErrorInvalidValue;
+        if (MODE == kFwd && (g.ldb < g.N || !g.bias)) return hipErrorInvalidValue;
+        if (MODE == kDa && (g.ldb < g.K || !g.mask || !aligned16(g.mask) || g.smask % 8)) return hipErrorInvalidValue;
+        if (!aligned16(g.c) || g.ldc % 8 || g.sc % 8) return hipErrorInvalidValue;
+    }
+    if (g.ldc < g.N) return hipErrorInvalidValue;
     GemmDevB p;
     p.a = (const uint16_t*)g.a;
     p.b = (const uint16_t*)g.b;
     p.c = g.c;
-    p.c_t = MODE == kDw ? nullptr : (uint16_t*)g.c_t;
     p.bias = g.bias;
     p.mask = (const uint16_t*)g.mask;
     p.colsum = MODE == kDw ? g.colsum : nullptr;
@@ -327,7 +600,7 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
             g.ldc != g.N)
             return hipErrorInvalidValue;
     }
-    p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sct = g.sct; p.sbias = g.sbias; p.smask = g.smask;
+    p.sa = g.sa; p.sb = g.sb; p.sc = g.sc; p.sbias = g.sbias; p.smask = g.smask;
     p.scolsum = g.scolsum;
     p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
     p.tiles_m = (g.M + BM - 1) / BM;
@@ -336,67 +609,61 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (total > (1 << 30)) return hipErrorInvalidValue;
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
-    gemm_bf16_kernel<MODE, BM, BN, BK><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
+    constexpr size_t lds = GemmShape<MODE, BM, BN, BK>::kLdsBytes;
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+    void (*kern)(GemmDevB) = gemm_bf16_kernel<MODE, BM, BN, BK, DEPTH>;
+    if constexpr (MODE != kDw && BK == 64) {
+        // full tiles and 32-bit lane offsets: the branch-free, interleaved kernel
+        const bool full = g.M % BM == 0 && g.N % BN == 0 && g.K % (2 * BK) == 0 &&
+                          (int64_t)BM * g.lda < (1 << 29) && (int64_t)(MODE == kFwd ? BK : BN) * g.ldb < (1 << 29);
+        if (full && !g.force_general) kern = gemm_bf16_full_kernel<MODE, BM, BN, BK>;
+    }
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    kern<<<(unsigned)(p.chunk * kXcds), kThreads, lds, s>>>(p);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t s) { return gemm_launch<kFwd, 128, 128, 64>(g, s); }
-hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDw, 128, 128, 64>(g, s); }
-hipError_t launch_gemm_bf16_da(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDa, 128, 128, 64>(g, s); }
+// Tile choice.  Small problems (few rows per group) take 128 x 128 tiles: a 256-row tile would be mostly padding.
+hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t s) {
+    if (g.M > 128) return gemm_launch<kFwd, 256, 128, 64, 2>(g, s);
+    return gemm_launch<kFwd, 128, 128, 64, 2>(g, s);
+}
+hipError_t launch_gemm_bf16_da(const GemmArgs& g, hipStream_t s) {
+    if (g.M > 128) return gemm_launch<kDa, 256, 128, 64, 2>(g, s);
+    return gemm_launch<kDa, 128, 128, 64, 2>(g, s);
+}
+hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDw, 128, 128, 32, 1>(g, s); }
 
 // ---------------------------------------------------------------------------------------------
-// fp32 [groups][rows][cols] -> bf16 row-major copy and bf16 transposed copy [groups][cols][rows]
+// fp32 [groups][rows][cols] -> bf16 [groups][rows][cols]; one lane per 8 consecutive values
 // ---------------------------------------------------------------------------------------------
-constexpr int kCastTile = 64;
 __global__ __launch_bounds__(kThreads) void cast_bf16_kernel(const float* __restrict__ src, int64_t src_stride,
-                                                             uint16_t* __restrict__ dst, uint16_t* __restrict__ dst_t,
-                                                             int rows, int cols) {
-    __shared__ uint16_t tile[kCastTile][kCastTile + 2];
-    const int g = blockIdx.z;
-    const int r0 = blockIdx.y * kCastTile, c0 = blockIdx.x * kCastTile;
-    const float* S = src + (int64_t)g * src_stride;
-    uint16_t* D = dst + (int64_t)g * rows * cols;
-    uint16_t* T = dst_t + (int64_t)g * rows * cols;
-    // 16 lanes x 4 floats cover a 64-column row segment; 16 rows per pass
-    for (int rr = threadIdx.x / 16; rr < kCastTile; rr += kThreads / 16) {
-        const int r = r0 + rr, c = c0 + (threadIdx.x % 16) * 4;
-        f4 v = {0.f, 0.f, 0.f, 0.f};
-        if (r < rows && c < cols) v = *(const f4*)(S + (int64_t)r * cols + c);   // cols is a multiple of 4
-        unsigned int h[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            h[e] = bf16_rne(v[e]);
-            tile[rr][(threadIdx.x % 16) * 4 + e] = (uint16_t)h[e];
-        }
-        if (r < rows && c < cols) {
-            u2 pk;
-            pk.x = h[0] | (h[1] << 16);
-            pk.y = h[2] | (h[3] << 16);
-            *(u2*)(D + (int64_t)r * cols + c) = pk;
-        }
-    }
-    __syncthreads();
-    for (int cc = threadIdx.x / 16; cc < kCastTile; cc += kThreads / 16) {
-        const int c = c0 + cc, r = r0 + (threadIdx.x % 16) * 4;
-        if (c < cols && r < rows) {   // rows is a multiple of 4
-            const int rl = (threadIdx.x % 16) * 4;
-            u2 pk;
-            pk.x = tile[rl][cc] | ((unsigned int)tile[rl + 1][cc] << 16);
-            pk.y = tile[rl + 2][cc] | ((unsigned int)tile[rl + 3][cc] << 16);
-            *(u2*)(T + (int64_t)c * rows + r) = pk;
-        }
-    }
+                                                             uint16_t* __restrict__ dst, int64_t per_group8) {
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= per_group8) return;
+    const int g = blockIdx.y;
+    const f4* S = (const f4*)(src + (int64_t)g * src_stride) + 2 * v;
+    const f4 lo = __builtin_nontemporal_load(S), hi = __builtin_nontemporal_load(S + 1);
+    u4 o;
+    o.x = bf16_rne(lo.x) | (bf16_rne(lo.y) << 16);
+    o.y = bf16_rne(lo.z) | (bf16_rne(lo.w) << 16);
+    o.z = bf16_rne(hi.x) | (bf16_rne(hi.y) << 16);
+    o.w = bf16_rne(hi.z) | (bf16_rne(hi.w) << 16);
+    *((u4*)(dst + (int64_t)g * per_group8 * 8) + v) = o;
 }
 
-hipError_t launch_cast_bf16(const float* src, int64_t src_stride, uint16_t* dst, uint16_t* dst_t, int groups, int rows,
-                            int cols, hipStream_t s) {
-    if (!src || !dst || !dst_t || groups < 1 || groups > 65535 || rows < 4 || cols < 4 || rows % 4 || cols % 4)
-        return hipErrorInvalidValue;
-    if (!aligned16(src) || src_stride % 4) return hipErrorInvalidValue;
-    const unsigned gy = (unsigned)((rows + kCastTile - 1) / kCastTile);
-    if (gy > 65535u) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((cols + kCastTile - 1) / kCastTile), gy, (unsigned)groups);
-    cast_bf16_kernel<<<grid, kThreads, 0, s>>>(src, src_stride, dst, dst_t, rows, cols);
+hipError_t launch_cast_bf16(const float* src, int64_t src_stride, uint16_t* dst, int groups, int rows, int cols,
+                            hipStream_t s) {
+    if (!src || !dst || groups < 1 || groups > 65535 || rows < 1 || cols < 8 || cols % 8) return hipErrorInvalidValue;
+    if (!aligned16(src) || !aligned16(dst) || src_stride % 4) return hipErrorInvalidValue;
+    const int64_t per_group8 = (int64_t)rows * cols / 8;
+    const int64_t blocks = (per_group8 + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks, (unsigned)groups);
+    cast_bf16_kernel<<<grid, kThreads, 0, s>>>(src, src_stride, dst, per_group8);
     return hipGetLastError();
 }
 

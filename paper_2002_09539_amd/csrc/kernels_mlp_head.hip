@@ -72,7 +72,6 @@ struct HeadDev {
     float* dlogits;
     float* loss_parts;
     void* dz;
-    void* dz_t;
     int64_t h_stride, ld, w_off, b_off, label_stride;
     int B, H, C;
 };
@@ -85,19 +84,17 @@ __host__ __device__ constexpr int head_fwd_lds_floats(int CMAX, int KC) {
     return KC * row_pitch(CMAX) + kHeadSamples * (KC + 4) + kHeadSamples * CMAX;
 }
 
-// grid (ceil(B / 16), m); dynamic LDS: head_fwd_lds_floats(CMAX, KC) floats (+ the transposition buffer when BF)
+// grid (ceil(B / 16), m); dynamic LDS: head_fwd_lds_floats(CMAX, KC) floats
 template <bool BF, int CMAX, int KC>
 __global__ __launch_bounds__(kHeadThreads) void head_fwd_kernel(HeadDev p) {
     constexpr int THREADS = kHeadThreads, S = kHeadSamples, HP = KC + 4;
     constexpr int P = row_pitch(CMAX);         // LDS pitch of a weight row
     constexpr int NW = KC * CMAX / THREADS;    // staged weights per lane, all in flight at once
     constexpr int J = KC / (4 * kRow);         // 4-wide activation vectors per lane per pass (8)
-    constexpr int TP = 4 * S + 8;              // uint16 per 4 k in the transposition buffer (16-byte pad)
     extern __shared__ __attribute__((aligned(16))) float s_dyn[];
     float* s_w = s_dyn;                        // [KC slots][P]
     float* s_h = s_dyn + KC * P;               // [S][HP]
     float* s_d = s_h + S * HP;                 // [S][CMAX] dlogits of the workgroup's samples
-    uint16_t* s_t = (uint16_t*)(s_d + S * CMAX); // [16][TP], bf16 only
 
     const int C = p.C, H = p.H, B = p.B;
     const int i = blockIdx.y;
@@ -277,22 +274,6 @@ __global__ __launch_bounds__(kHeadThreads) void head_fwd_kernel(HeadDev p) {
                                    h3 = f32_to_bf16(out[3]);
                 if (live && kv < H)
                     *(u2*)((uint16_t*)p.dz + (int64_t)i * B * H + (int64_t)s * H + kv) = u2{h0 | (h1 << 16), h2 | (h3 << 16)};
-                if (p.dz_t) {
-                    // transposed copy [H][B]: iteration j covers the 64 consecutive k from k0 + 64 j; the 16
-                    // samples of this workgroup are 32 bytes per k, stored as two 16-byte pieces.  (B is a
-                    // multiple of 8 on this path: a piece is live or not as a whole.)
-                    s_t[sub * TP + 0 * S + row] = (uint16_t)h0;
-                    s_t[sub * TP + 1 * S + row] = (uint16_t)h1;
-                    s_t[sub * TP + 2 * S + row] = (uint16_t)h2;
-                    s_t[sub * TP + 3 * S + row] = (uint16_t)h3;
-                    __syncthreads();
-                    const int kk = threadIdx.x / 2, piece = threadIdx.x % 2;
-                    if (kk < 64 && k0 + 64 * j + kk < H && s0 + 8 * piece < B) {
-                        const u4 v = *(const u4*)(s_t + (kk / 4) * TP + (kk % 4) * S + 8 * piece);
-                        *(u4*)((uint16_t*)p.dz_t + (int64_t)i * B * H + (int64_t)(k0 + 64 * j + kk) * B + s0 + 8 * piece) = v;
-                    }
-                    __syncthreads();
-                }
             } else {
                 if (live && kv < H) *(f4*)((float*)p.dz + (int64_t)i * B * H + (int64_t)s * H + kv) = out;
             }
@@ -427,7 +408,6 @@ static bool head_args_ok(const HeadArgs& a) {
 template <bool BF, int CMAX, int KC>
 static hipError_t head_fwd_launch(const HeadDev& p, int m, hipStream_t s) {
     size_t lds = (size_t)head_fwd_lds_floats(CMAX, KC) * sizeof(float);
-    if (BF) lds += (size_t)kRow * (4 * kHeadSamples + 8) * sizeof(uint16_t);
     auto kern = head_fwd_kernel<BF, CMAX, KC>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -441,11 +421,9 @@ static hipError_t head_fwd_launch(const HeadDev& p, int m, hipStream_t s) {
 // logits, loss, dlogits, and (when a.dz is set) the delta of the last hidden layer
 hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
     if (!head_args_ok(a)) return hipErrorInvalidValue;
-    // 16-byte activation vectors: 4 floats or 8 bf16; the transposed bf16 copy is written in pieces of 8 samples
+    // 16-byte activation vectors: 4 floats or 8 bf16
     if (a.h_bf16 && (a.H % 8 || a.h_stride % 8)) return hipErrorInvalidValue;
     if (a.dz && (reinterpret_cast<uintptr_t>(a.dz) & 15u)) return hipErrorInvalidValue;
-    if (a.dz_t && (!a.h_bf16 || !a.dz || a.B % 8 || (reinterpret_cast<uintptr_t>(a.dz_t) & 15u)))
-        return hipErrorInvalidValue;
     HeadDev p;
     p.h = a.h;
     p.x = a.x;
@@ -453,7 +431,6 @@ hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
     p.dlogits = a.dlogits;
     p.loss_parts = a.loss_parts;
     p.dz = a.dz;
-    p.dz_t = a.dz_t;
     p.h_stride = a.h_stride;
     p.ld = a.ld;
     p.w_off = a.w_off;

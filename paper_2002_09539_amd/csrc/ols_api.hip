@@ -78,8 +78,8 @@ struct ols_ctx {
     char* ws = nullptr;
     int64_t ws_bytes = 0, ws_need = 0;
     // workspace sub-buffers (byte offsets)
-    std::vector<int64_t> off_act, off_act_t, off_dz, off_dz_t;
-    int64_t off_dlogits = 0, off_loss = 0, off_resid = 0, off_shadow = 0, off_x0 = 0, off_x0_t = 0;
+    std::vector<int64_t> off_act, off_dz;
+    int64_t off_dlogits = 0, off_loss = 0, off_resid = 0, off_shadow = 0, off_x0 = 0;
     const float* X = nullptr;
     const void* y = nullptr;
     int64_t xs = 0, ys = 0;
@@ -201,9 +201,7 @@ void plan_workspace(ols_ctx* c) {
     };
     const int64_t m = c->m, B = c->B;
     c->off_act.clear();
-    c->off_act_t.clear();
     c->off_dz.clear();
-    c->off_dz_t.clear();
     if (c->model == MODEL_LSQ) {
         c->off_resid = take(m * B * 4);
         c->off_loss = take(m * B * 4);
@@ -212,16 +210,10 @@ void plan_workspace(ols_ctx* c) {
         const bool bf = c->gemm_dtype == 1;
         const int64_t es = bf ? 2 : 4;
         c->off_act.assign(L, 0);
-        c->off_act_t.assign(L, 0);
         c->off_dz.assign(L, 0);
-        c->off_dz_t.assign(L, 0);
         for (int l = 1; l < L; ++l) {  // hidden activations a_l and deltas dz_l, [m][B][dims[l]]
             c->off_act[l] = take(m * B * c->dims[l] * es);
             c->off_dz[l] = take(m * B * c->dims[l] * es);
-            if (bf) {
-                c->off_act_t[l] = take(m * B * c->dims[l] * es);
-                c->off_dz_t[l] = take(m * B * c->dims[l] * es);
-            }
         }
         c->fwd_splits.assign(L, 1);
         if (!bf) {  // scratch for the split-K forward GEMMs: room for up to 8 K ranges where splitting is planned
@@ -236,7 +228,6 @@ void plan_workspace(ols_ctx* c) {
         }
         if (bf) {
             c->off_x0 = take(m * B * c->dims[0] * 2);
-            c->off_x0_t = take(m * B * c->dims[0] * 2);
             c->off_shadow = take(m * c->ld * 2);
         }
         c->off_dlogits = take(m * B * c->dims[L] * 4);
@@ -271,14 +262,11 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
     auto act = [&](int l) -> const void* { return l == 0 ? (bf ? (const void*)(c->ws + c->off_x0) : (const void*)c->X)
                                                           : (const void*)(c->ws + c->off_act[l]); };
     auto act_stride = [&](int l) -> int64_t { return (l == 0 && !bf) ? c->xs : (int64_t)B * c->dims[l]; };
-    auto act_t = [&](int l) -> const void* { return l == 0 ? (const void*)(c->ws + c->off_x0_t)
-                                                            : (const void*)(c->ws + c->off_act_t[l]); };
     (void)es;
     int rc;
     if (bf) {
         rc = enqueue(c, OLS_K_CAST, 0, -1, -1, [&](hipStream_t s) {
-            return launch_cast_bf16(c->X, c->xs, (uint16_t*)(c->ws + c->off_x0), (uint16_t*)(c->ws + c->off_x0_t), m, B,
-                                    c->dims[0], s);
+            return launch_cast_bf16(c->X, c->xs, (uint16_t*)(c->ws + c->off_x0), m, B, c->dims[0], s);
         });
         if (rc) return rc;
     }
@@ -294,8 +282,6 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
         ga.c = c->ws + c->off_act[l + 1];
         ga.sc = (int64_t)B * c->dims[l + 1];
         ga.ldc = c->dims[l + 1];
-        ga.c_t = bf ? (void*)(c->ws + c->off_act_t[l + 1]) : nullptr;
-        ga.sct = ga.sc;
         ga.bias = xc + c->b_off[l];
         ga.sbias = c->ld;
         ga.groups = m;
@@ -325,7 +311,6 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
     ha.dlogits = (float*)(c->ws + c->off_dlogits);
     ha.loss_parts = (float*)(c->ws + c->off_loss);
     ha.dz = L > 1 ? (void*)(c->ws + c->off_dz[L - 1]) : nullptr;
-    ha.dz_t = (L > 1 && bf) ? (void*)(c->ws + c->off_dz_t[L - 1]) : nullptr;
     ha.m = m;
     ha.B = B;
     ha.H = c->dims[L - 1];
@@ -353,8 +338,6 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
             gd.c = c->ws + c->off_dz[l];
             gd.sc = (int64_t)B * c->dims[l];
             gd.ldc = c->dims[l];
-            gd.c_t = bf ? (void*)(c->ws + c->off_dz_t[l]) : nullptr;
-            gd.sct = gd.sc;
             gd.groups = m;
             gd.M = B;
             gd.N = c->dims[l];
@@ -364,21 +347,12 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
             if (rc) return rc;
         }
         GemmArgs gw = {};
-        if (bf) {  // contraction over the batch wants batch-contiguous operands: the transposed copies
-            gw.a = act_t(l);
-            gw.sa = (int64_t)B * c->dims[l];
-            gw.lda = B;
-            gw.b = c->ws + c->off_dz_t[l + 1];
-            gw.sb = dz_stride;
-            gw.ldb = B;
-        } else {
-            gw.a = act(l);
-            gw.sa = act_stride(l);
-            gw.lda = c->dims[l];
-            gw.b = dz;
-            gw.sb = dz_stride;
-            gw.ldb = c->dims[l + 1];
-        }
+        gw.a = act(l);   // contraction over the batch: both operands are read as stored, [B][in] and [B][out]
+        gw.sa = act_stride(l);
+        gw.lda = c->dims[l];
+        gw.b = dz;
+        gw.sb = dz_stride;
+        gw.ldb = c->dims[l + 1];
         gw.c = c->g + c->w_off[l];
         gw.sc = c->ld;
         gw.ldc = c->dims[l + 1];

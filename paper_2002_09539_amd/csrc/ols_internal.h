@@ -121,14 +121,14 @@ struct GemmArgs {
     void* c;            // output, group stride sc
     const float* bias;  // fwd: [N] per group, stride sbias
     const void* mask;   // dA: activations whose sign gates the output, same shape as c, stride smask
-    void* c_t;          // bf16 only: optional transposed copy of the output [N][M], stride sct (or nullptr)
     float* colsum;      // dw: optional [N] per group, receives the column sums of B (the bias gradient)
     float* partial;     // fp32 fwd with splits > 1: scratch of splits * groups * M * N floats
     int splits;         // fp32 fwd: number of K ranges contracted by separate workgroups (<= 1: none)
+    int force_general;  // bf16: use the bounds-checked kernel even where the full-tile kernel applies
     FusedUpdate upd;    // dw: when enabled, c is NOT written; the update of W (c's position in the replica row is
     int64_t upd_w_off;  //     upd_w_off) and of the bias (upd_b_off, from the column sums) is applied instead
     int64_t upd_b_off;
-    int64_t sa, sb, sc, sbias, smask, sct, scolsum;
+    int64_t sa, sb, sc, sbias, smask, scolsum;
     int groups;
     int M, N, K;        // output M x N, contraction length K
     int lda, ldb, ldc;  // leading dimensions (elements) of the operands as stored
@@ -139,12 +139,12 @@ hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s, int variant);
 void gemm_f32_fwd_plan(int groups, int M, int N, int K, int* variant, int* splits);
 hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant);
 hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s, int variant);
-// bf16 operands, fp32 accumulate
+// bf16 operands, fp32 accumulate.  fwd: A[M][K], W[K][N];  dw: A[K][M], B[K][N] (K = batch);  da: A[M][K], W[N][K]
 hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_bf16_da(const GemmArgs& g, hipStream_t s);
-hipError_t launch_cast_bf16(const float* src, int64_t src_stride, uint16_t* dst, uint16_t* dst_t, int groups, int rows,
-                            int cols, hipStream_t s);
+hipError_t launch_cast_bf16(const float* src, int64_t src_stride, uint16_t* dst, int groups, int rows, int cols,
+                            hipStream_t s);
 
 // output layer (N = classes <= 32) on plain vector ALUs
 struct HeadArgs {
@@ -159,7 +159,6 @@ struct HeadArgs {
     float* dlogits;       // [m][B][C]
     float* loss_parts;    // [m][B] per-sample losses
     void* dz;             // [m][B][H] delta for the last hidden layer (fp32 or bf16), masked by h > 0
-    void* dz_t;           // bf16 only: transposed copy [m][H][B] or nullptr
     int m, B, H, C;
     FusedUpdate upd;      // when enabled the output layer's parameters are updated instead of writing g
 };
