@@ -30,6 +30,17 @@ __device__ __forceinline__ unsigned int ep_bf16(float f) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+#ifndef OLS_EPILOGUE_NONTEMPORAL
+#define OLS_EPILOGUE_NONTEMPORAL 1
+#endif
+#if OLS_EPILOGUE_NONTEMPORAL
+__device__ __forceinline__ ep_f4 ep_load_stream(const ep_f4* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void ep_store_stream(ep_f4* p, ep_f4 v) { __builtin_nontemporal_store(v, p); }
+#else
+__device__ __forceinline__ ep_f4 ep_load_stream(const ep_f4* p) { return *p; }
+__device__ __forceinline__ void ep_store_stream(ep_f4* p, ep_f4 v) { *p = v; }
+#endif
+
 // One vector of 4 gradient entries at (row, col .. col + 3) of the layer's weight matrix.
 __device__ __forceinline__ void dw_consume(const DwOut& o, int N, int row, int col, ep_f4 g, ep_f4 x, ep_f4 b, ep_f4 z) {
     const FusedUpdate& u = o.upd;
@@ -48,8 +59,9 @@ __device__ __forceinline__ void dw_consume(const DwOut& o, int N, int row, int c
         if (u.pull) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, z[e]), xh);
         xn[e] = xh;
     }
-    *(ep_f4*)(u.x_out + o.upd_base + off) = xn;
-    if (u.mu != 0.0f) *(ep_f4*)(u.buf + o.upd_base + off) = bn;
+    // the state streams through once per step: non-temporal accesses keep it from displacing the operands in L2
+    ep_store_stream((ep_f4*)(u.x_out + o.upd_base + off), xn);
+    if (u.mu != 0.0f) ep_store_stream((ep_f4*)(u.buf + o.upd_base + off), bn);
     if (u.shadow) {
         ep_u2 pk;
         pk.x = ep_bf16(xn[0]) | (ep_bf16(xn[1]) << 16);
@@ -100,8 +112,8 @@ __device__ __forceinline__ void dw_epilogue_staged(float* stage, const ep_f16 (&
                 if (!ok) rows[u] = -1;
                 if (fused) {   // every lane issues its loads (out-of-range lanes re-read element 0)
                     const int64_t off = ok ? (int64_t)rows[u] * N + cols[u] : 0;
-                    xv[u] = *(const ep_f4*)(o.upd.x_in + o.upd_base + off);
-                    if (mom) bv[u] = *(const ep_f4*)(o.upd.buf + o.upd_base + off);
+                    xv[u] = ep_load_stream((const ep_f4*)(o.upd.x_in + o.upd_base + off));
+                    if (mom) bv[u] = ep_load_stream((const ep_f4*)(o.upd.buf + o.upd_base + off));
                     if (pull) zv[u] = *(const ep_f4*)(o.upd.z + o.col_base + off);
                 }
             }

@@ -320,8 +320,8 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
         }
         // the gradient tile is staged through the (now idle) operand LDS, as many rows per pass as it holds
         constexpr int kFit = ((Shape::kLdsElems / 2) / (BN + 4)) / 32 * 32;
-        constexpr int RP = kFit >= BM ? BM : kFit;
-        static_assert(RP >= 32 && BM % RP == 0, "operand LDS too small to stage the gradient tile");
+        constexpr int RP = kFit >= BM ? BM : (kFit >= 64 ? 64 : 32);   // a power-of-two share of the tile's rows
+        static_assert(kFit >= 32 && BM % RP == 0, "operand LDS too small to stage the gradient tile");
         DwOut o;
         o.g = (float*)p.c + (int64_t)group * p.sc;
         o.ldg = p.ldc;
@@ -635,7 +635,20 @@ hipError_t launch_gemm_bf16_da(const GemmArgs& g, hipStream_t s) {
     if (g.M > 128) return gemm_launch<kDa, 256, 128, 64, 2>(g, s);
     return gemm_launch<kDa, 128, 128, 64, 2>(g, s);
 }
-hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s) { return gemm_launch<kDw, 128, 128, 32, 1>(g, s); }
+hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s, int variant) {
+    // Measured on configuration 3 (K = batch = 256, fused update): 64 x 128 x 32 tiles leave four workgroups per
+    // compute unit and take 284 us per launch; 128 x 128: 309, 128 x 64: 294, 64 x 64: 295, BK = 64: 319-341.
+    switch (variant) {
+        case 0:
+        case 1: return gemm_launch<kDw, 64, 128, 32, 1>(g, s);
+        case 6: return gemm_launch<kDw, 128, 128, 32, 1>(g, s);
+        case 2: return gemm_launch<kDw, 128, 64, 32, 1>(g, s);
+        case 3: return gemm_launch<kDw, 64, 64, 32, 1>(g, s);
+        case 4: return gemm_launch<kDw, 128, 128, 64, 1>(g, s);
+        case 5: return gemm_launch<kDw, 64, 128, 64, 1>(g, s);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 // ---------------------------------------------------------------------------------------------
 // fp32 [groups][rows][cols] -> bf16 [groups][rows][cols]; one lane per 8 consecutive values

@@ -369,7 +369,7 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
         gw.N = c->dims[l + 1];
         gw.K = B;
         rc = enqueue(c, OLS_K_GEMM_DW, 0, upd ? src_buf : -1, upd ? dst_buf : -1,
-                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s) : launch_gemm_f32_dw(gw, s, c->gemm_variant[1]); });
+                     [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s, c->gemm_variant[1]) : launch_gemm_f32_dw(gw, s, c->gemm_variant[1]); });
         if (rc) return rc;
     }
     return OLS_OK;

@@ -141,7 +141,7 @@ hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant);
 hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s, int variant);
 // bf16 operands, fp32 accumulate.  fwd: A[M][K], W[K][N];  dw: A[K][M], B[K][N] (K = batch);  da: A[M][K], W[N][K]
 hipError_t launch_gemm_bf16_fwd(const GemmArgs& g, hipStream_t s);
-hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s, int variant);
 hipError_t launch_gemm_bf16_da(const GemmArgs& g, hipStream_t s);
 hipError_t launch_cast_bf16(const float* src, int64_t src_stride, uint16_t* dst, int groups, int rows, int cols,
                             hipStream_t s);
