@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
     ap.add_argument("--serialize", type=int, default=0, help="1: anchor refresh on the main stream (no overlap)")
     ap.add_argument("--fuse-mean", type=int, default=0, help="1: step + pull-back + anchor refresh in one pass")
+    ap.add_argument("--mixing", choices=["none", "paper", "averaging"], default="none",
+                    help="general mixing X <- X W at the synchronisation points: the paper's W or periodic averaging "
+                         "applied by the one-pass mixing kernel instead of pull-back + anchor average")
     ap.add_argument("--no-second-buffer", action="store_true")
     ap.add_argument("--fuse-gemm-update", type=int, default=1,
                     help="1 (default): gradient kernels apply the local step themselves; 0: separate streaming pass")
@@ -56,6 +59,7 @@ def algorithmic_work(cfg, ld, fused_update=True):
         "pull": ("hbm", er * (8 + shadow) + 4 * ld),
         "mean": ("hbm", (4 * m + 4) * ld),
         "step_pull_mean": ("hbm", er * (12 + mom) + 8 * ld),
+        "mix": ("hbm", (8 * (m + 1) + shadow * m) * ld),     # every row of [x, z] read once and written once
     }
     if cfg.kind == "mlp":
         dims, B = cfg.dims, cfg.batch
@@ -173,6 +177,16 @@ def main():
         key, val = kv.split("=")
         sess.set_option(int(key), int(val))
     feed, host_inputs = build_workload(cfg, sess, torch)
+    if args.mixing != "none":
+        # the matrix is an INPUT of the path (the caller's choice of W); only its entries are written here
+        Wm = np.zeros((cfg.m + 1, cfg.m + 1), np.float32)
+        if args.mixing == "paper":      # Section 2, matrix-form update rule
+            Wm[:cfg.m, :cfg.m] = (1.0 - cfg.alpha) * np.eye(cfg.m)
+            Wm[:cfg.m, cfg.m] = (1.0 - cfg.alpha) / cfg.m
+            Wm[cfg.m, :] = cfg.alpha
+        else:                           # Local SGD's periodic averaging (first display of Section 2)
+            Wm[:cfg.m, :] = 1.0 / cfg.m
+        sess.set_mixing(Wm)
 
     def region(steps):
         sess.sync()
@@ -248,8 +262,8 @@ def main():
         "dtype": cfg.gemm_dtype if cfg.kind == "mlp" else "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
-                   "dims": list(cfg.dims), "overlap": "serialized" if args.serialize else
-                   ("fused-mean" if args.fuse_mean else "side-stream"),
+                   "dims": list(cfg.dims), "overlap": ("mixing-kernel:" + args.mixing) if args.mixing != "none" else
+                   ("serialized" if args.serialize else ("fused-mean" if args.fuse_mean else "side-stream")),
                    "second_buffer": not args.no_second_buffer,
                    "update": "in-gradient-kernels" if (args.fuse_gemm_update and cfg.kind == "mlp") else "streaming"},
         "roofline": roofline,

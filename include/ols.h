@@ -100,7 +100,7 @@ enum {
     OLS_K_GEMM_DA = 10,   /* back-propagated delta dZ W^T, ReLU mask    */
     OLS_K_HEAD_FWD = 11,  /* output layer + softmax cross-entropy       */
     OLS_K_HEAD_BWD = 12,  /* output layer gradients and delta           */
-    OLS_K_RESERVED = 13,  /* unused (bias gradients are formed inside the weight-gradient kernels) */
+    OLS_K_MIX = 13,       /* general mixing X <- X W (ols_set_mixing)    */
     OLS_K_CAST = 14,      /* fp32 -> bf16 operand conversion            */
     OLS_K_COUNT = 15
 };
@@ -153,6 +153,19 @@ OLS_API int ols_init_params(ols_handle h, const float* x0_dev);
  * z <- z + v.  v_dev: [ld] device buffer (zero-filled by the caller), or NULL with beta_z == 0 to
  * return to the plain average.  Must be called before the first local step. */
 OLS_API int ols_set_anchor_momentum(ols_handle h, float beta_z, float* v_dev);
+
+/* General mixing (Section 2, "Matrix-Form Update Rule": X_{k+1} = (X_k - gamma G_k) W_k with
+ * X = [x^(1), ..., x^(m), z]; the section notes that other column-stochastic W can take the place of
+ * the one printed there).  w_dev: (m + 1) x (m + 1) fp32, row-major, on the DEVICE, caller-owned and
+ * valid until replaced; entry [i][j] is the weight of row i of X in output row j.  While a matrix is
+ * set, every synchronisation point applies X <- X W in one pass on the main stream in place of the
+ * pull-back and the anchor average: the tau-th local step is a plain local step, ols_sync_pull
+ * launches the mixing kernel (each output row is the fma chain over i = 0..m in fp32) and
+ * ols_anchor_update_async only completes the call sequence (the anchor is row m of the product, so
+ * there is nothing left to overlap).  NULL returns to the paper's pull-back + anchor average.
+ * m <= 128.  Not combinable with anchor momentum.  OLS_ESTATE in the middle of a synchronisation.
+ * The matrix is not checked for column-stochasticity: that is the caller's modelling choice. */
+OLS_API int ols_set_mixing(ols_handle h, const float* w_dev);
 
 /* Changes the learning rate gamma for subsequent local steps (Section 4 uses a schedule). */
 OLS_API int ols_set_lr(ols_handle h, float gamma);

@@ -100,6 +100,31 @@ def mixing_matrix(m, alpha):
     return W
 
 
+def periodic_averaging_matrix(m):
+    """W of Local SGD's synchronisation (first display of Section 2): every model becomes the
+    mean of the m half-step models; the extra (anchor) column takes the same mean and row m,
+    the old anchor, contributes nothing.  Column-stochastic."""
+    W = np.zeros((m + 1, m + 1), F64)
+    W[:m, :] = 1.0 / m
+    return W
+
+
+def elastic_symmetric_matrix(m, alpha):
+    """A symmetric, doubly stochastic W of the kind Section 3 ascribes to elastic averaging:
+    x_i <- x_i - alpha (x_i - z) and z <- z + alpha sum_i (x_i - z)."""
+    W = np.zeros((m + 1, m + 1), F64)
+    W[:m, :m] = (1.0 - alpha) * np.eye(m)
+    W[m, :m] = alpha
+    W[:m, m] = alpha
+    W[m, m] = 1.0 - m * alpha
+    return W
+
+
+def mix(X, W):
+    """X W for X = [x^(1..m), z] of shape d x (m+1): output column j is sum_i W[i][j] X[:, i]."""
+    return np.asarray(X, F64) @ np.asarray(W, F64)
+
+
 def matrix_form_step(X, G, gamma, W):
     """X_{k+1} = (X_k - gamma G_k) W_k with X = [x^(1..m), z] of shape d x (m+1)."""
     return (np.asarray(X, F64) - gamma * np.asarray(G, F64)) @ W
@@ -224,6 +249,35 @@ def run(x0, m, tau, alpha, gamma, K, grad_fn, mu=0.0, nesterov=True, beta_z=0.0,
         if on_step is not None:
             on_step(k, state)
     return state
+
+
+def run_general_mixing(x0, m, tau, gamma, K, grad_fn, W, mu=0.0, nesterov=True, store=np.float32):
+    """The iteration X_{k+1} = (X_k - gamma G_k) W_k of Section 2 with an arbitrary matrix W at the
+    synchronisation steps ((k+1) mod tau == 0; identity otherwise), local momentum as in `run`.
+    W is given in double; a device applies it in fp32, so callers comparing against one pass
+    W.astype(float32).  Returns the same dict as `run` (v is None)."""
+    x0 = np.asarray(x0)
+    d = x0.shape[0]
+    W = np.asarray(W, F64)
+    assert W.shape == (m + 1, m + 1)
+    x = np.repeat(x0.astype(store)[None, :], m, axis=0)
+    z = x0.astype(store).copy()
+    buf = np.zeros((m, d), store) if mu != 0.0 else None
+    losses = np.zeros((K, m), F64)
+    for k in range(K):
+        for i in range(m):
+            loss, g = grad_fn(i, k, x[i])
+            losses[k, i] = loss
+            x_half, b_new = local_momentum_step(x[i], None if buf is None else buf[i], g, gamma, mu, nesterov)
+            if buf is not None:
+                buf[i] = b_new.astype(store)
+            x[i] = x_half.astype(store)
+        if (k + 1) % tau == 0:
+            X = np.concatenate([x.astype(F64), z.astype(F64)[None, :]], axis=0).T      # d x (m+1)
+            Xn = mix(X, W)
+            x[...] = Xn[:, :m].T.astype(store)
+            z[...] = Xn[:, m].astype(store)
+    return dict(x=x, buf=buf, z=z, v=None, losses=losses)
 
 
 def run_matrix_form(x0, m, tau, alpha, gamma, K, grad_fn):

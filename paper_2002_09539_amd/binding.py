@@ -14,7 +14,7 @@ OLS_OK, OLS_EINVAL, OLS_ESTATE, OLS_EHIP, OLS_ENOMEM = 0, -1, -2, -3, -4
  OLS_OPT_MEAN_SPLIT, OLS_OPT_FUSE_MEAN, OLS_OPT_GEMM_VARIANT_FWD, OLS_OPT_GEMM_VARIANT_DW,
  OLS_OPT_GEMM_VARIANT_DA, OLS_OPT_GEMM_SPLITK, OLS_OPT_FUSE_GEMM_UPDATE) = range(1, 14)
 (OLS_K_INIT, OLS_K_STEP, OLS_K_STEP_PULL, OLS_K_PULL, OLS_K_MEAN, OLS_K_STEP_PULL_MEAN, OLS_K_LSQ_RESID,
- OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_RESERVED,
+ OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_MIX,
  OLS_K_CAST, OLS_K_COUNT) = range(16)
 
 
@@ -38,6 +38,7 @@ _SIGNATURES = {
     "ols_bind": (C.c_int, [_H, _P, _P, _P, _P, _P, C.c_int64, _P, _P]),
     "ols_init_params": (C.c_int, [_H, _P]),
     "ols_set_anchor_momentum": (C.c_int, [_H, C.c_float, _P]),
+    "ols_set_mixing": (C.c_int, [_H, _P]),
     "ols_set_lr": (C.c_int, [_H, C.c_float]),
     "ols_attach_lsq": (C.c_int, [_H, C.c_int]),
     "ols_attach_mlp": (C.c_int, [_H, C.c_int, C.POINTER(C.c_int), C.c_int, C.c_int]),
@@ -122,6 +123,10 @@ def ols_init_params(h, x0):
 
 def ols_set_anchor_momentum(h, beta_z, v):
     _check(load().ols_set_anchor_momentum(h, beta_z, v))
+
+
+def ols_set_mixing(h, w):
+    _check(load().ols_set_mixing(h, w))
 
 
 def ols_set_lr(h, gamma):

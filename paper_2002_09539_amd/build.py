@@ -17,6 +17,7 @@ SOURCES = [
     "ols_api.hip",
     "kernels_update.hip",
     "kernels_mean.hip",
+    "kernels_mix.hip",
     "kernels_lsq.hip",
     "kernels_mlp_head.hip",
     "kernels_gemm_f32.hip",

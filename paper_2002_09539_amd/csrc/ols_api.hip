@@ -36,7 +36,7 @@ int fail(int code, const char* fmt, ...) {
 
 const char* kKernelNames[OLS_K_COUNT] = {
     "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
-    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "reserved",       "cast_bf16"};
+    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16"};
 
 enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2 };
 
@@ -56,6 +56,7 @@ struct ols_ctx {
     float* x[2] = {nullptr, nullptr};
     int cur = 0;
     float *buf = nullptr, *g = nullptr, *z = nullptr, *v = nullptr;
+    const float* mix_w = nullptr;   // general mixing matrix (device), or nullptr: the paper's pull-back + average
     hipStream_t stream[2] = {nullptr, nullptr};
     bool bound = false, inited = false, launched = false;
     // options
@@ -511,9 +512,21 @@ int ols_set_anchor_momentum(ols_handle c, float beta_z, float* v) {
     if (c->k != 0) return fail(OLS_ESTATE, "anchor momentum must be set before the first local step");
     if (!(beta_z >= 0.0f && beta_z < 1.0f)) return fail(OLS_EINVAL, "beta_z must be in [0, 1)");
     if (beta_z != 0.0f && !v) return fail(OLS_EINVAL, "v is required when beta_z is non-zero");
+    if (beta_z != 0.0f && c->mix_w) return fail(OLS_EINVAL, "anchor momentum cannot be combined with general mixing");
     if (reinterpret_cast<uintptr_t>(v) & 255u) return fail(OLS_EINVAL, "v must be 256-byte aligned");
     c->beta_z = beta_z;
     c->v = beta_z != 0.0f ? v : nullptr;
+    return OLS_OK;
+}
+
+int ols_set_mixing(ols_handle c, const float* w_dev) {
+    if (int rc = need(c)) return rc;
+    if (c->pull_due || c->anchor_due || c->pending_update)
+        return fail(OLS_ESTATE, "the mixing matrix cannot change in the middle of a synchronisation");
+    if (w_dev && c->m > kMixMaxWorkers) return fail(OLS_EINVAL, "general mixing supports m <= %d", kMixMaxWorkers);
+    if (w_dev && c->beta_z != 0.0f) return fail(OLS_EINVAL, "general mixing cannot be combined with anchor momentum");
+    if (reinterpret_cast<uintptr_t>(w_dev) & 3u) return fail(OLS_EINVAL, "w_dev must be 4-byte aligned");
+    c->mix_w = w_dev;
     return OLS_OK;
 }
 
@@ -629,12 +642,13 @@ int ols_local_step(ols_handle c) {
         if (!c->batch_set) return fail(OLS_ESTATE, "the attached model needs ols_set_batch");
     }
     const bool boundary = (c->k + 1) % c->tau == 0;
-    if (c->model == MODEL_MLP && c->fuse_gemm_update && !(boundary && c->fuse_mean)) {
+    const bool paper_sync = c->mix_w == nullptr;   // the synchronisation is the paper's pull-back + anchor average
+    if (c->model == MODEL_MLP && c->fuse_gemm_update && !(boundary && c->fuse_mean && paper_sync)) {
         // the gradient kernels apply the update themselves; on a boundary step the pull-back as well,
         // so the anchor of the previous round must have landed before they start
         int src, dst;
         if (int rc = pick_buffers(c, &src, &dst)) return rc;
-        if (boundary) {
+        if (boundary && paper_sync) {
             if (int rc = main_waits_for_anchor(c)) return rc;
         }
         FusedUpdate u = {};
@@ -648,20 +662,20 @@ int ols_local_step(ols_handle c) {
         u.mu = c->mu;
         u.alpha = c->alpha;
         u.nesterov = c->nesterov ? 1 : 0;
-        u.pull = boundary ? 1 : 0;
+        u.pull = (boundary && paper_sync) ? 1 : 0;
         u.enabled = 1;
         if (int rc = compute_gradients(c, &u, src, dst)) return rc;
         c->cur = dst;
         c->k += 1;
         if (boundary) {
             c->pull_due = true;
-            c->pulled_in_step = true;
+            c->pulled_in_step = paper_sync;
         }
         return OLS_OK;
     }
     if (int rc = compute_gradients(c, nullptr, c->cur, -1)) return rc;
     c->k += 1;
-    if (boundary && c->fuse_pull) {
+    if (boundary && c->fuse_pull && paper_sync) {
         c->pending_update = true;  // applied together with the pull-back in one pass
         c->pull_due = true;
         return OLS_OK;
@@ -691,6 +705,22 @@ int ols_sync_pull(ols_handle c) {
     }
     // the anchor about to be read is the one the previous round's refresh produces
     if (int rc = main_waits_for_anchor(c)) return rc;
+    if (c->mix_w) {  // X <- X W over [x^(1..m), z] in one pass; the new anchor is row m of the product
+        c->first_after_anchor = false;
+        MixArgs a = {};
+        a.x = c->x[c->cur];
+        a.z = c->z;
+        a.shadow = shadow_ptr(c);
+        a.w = c->mix_w;
+        a.m = c->m;
+        a.ld = c->ld;
+        int rc = enqueue(c, OLS_K_MIX, 0, c->cur, c->cur, [&](hipStream_t s) { return launch_mix(a, s); });
+        if (rc) return rc;
+        c->pull_due = false;
+        c->anchor_due = true;
+        c->anchor_precomputed = true;
+        return OLS_OK;
+    }
     int src = c->cur, dst = c->cur;
     if (c->first_after_anchor) {  // only when tau == 1: nothing was written since the refresh, which has now finished
         c->first_after_anchor = false;

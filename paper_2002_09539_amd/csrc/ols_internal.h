@@ -52,6 +52,18 @@ struct StepPullMeanArgs {
 };
 hipError_t launch_step_pull_mean(const StepPullMeanArgs& a, hipStream_t s);
 
+// general mixing X <- X W over the m + 1 rows [x^(1..m), z]
+constexpr int kMixMaxWorkers = 128;
+struct MixArgs {
+    float* x;          // [m][ld] replicas, updated in place
+    float* z;          // [ld] anchor (row m of X), updated in place
+    uint16_t* shadow;  // [m][ld] bf16 copy of the new replicas, or nullptr
+    const float* w;    // [(m + 1)][(m + 1)] row-major on the device
+    int m;
+    int64_t ld;
+};
+hipError_t launch_mix(const MixArgs& a, hipStream_t s);
+
 // linear least squares
 hipError_t launch_lsq_resid(const float* A, int64_t a_stride, const float* y, int64_t y_stride, const float* x,
                             int64_t ld, float* resid, float* loss_parts, int m, int B, int64_t d, hipStream_t s);

@@ -52,6 +52,17 @@ class Session:
         torch.cuda.synchronize(self.device)
         B.ols_set_anchor_momentum(self.h, beta_z, _ptr(self.v))
 
+    def set_mixing(self, W):
+        """General mixing X <- X W at every synchronisation point; W: (m+1) x (m+1) host array, or None."""
+        if W is None:
+            B.ols_set_mixing(self.h, None)
+            self.w = None
+            return
+        W = np.ascontiguousarray(W, dtype=np.float32)
+        assert W.shape == (self.m + 1, self.m + 1)
+        self.w = self.upload(W)
+        B.ols_set_mixing(self.h, _ptr(self.w))
+
     def attach_lsq(self, batch):
         B.ols_attach_lsq(self.h, batch)
         self._workspace()

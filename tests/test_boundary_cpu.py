@@ -256,3 +256,41 @@ def test_option_validation():
     assert code_of(B.ols_set_anchor_momentum, h, 0.7, None) == B.OLS_EINVAL
     B.ols_set_anchor_momentum(h, 0.7, FAKE)
     B.ols_destroy(h)
+
+
+def test_general_mixing_replaces_pull_and_average_in_the_schedule():
+    """With a mixing matrix set, a synchronisation point is: plain local step, one mixing pass on the
+    main stream, no pull-back kernel and no anchor-mean kernel."""
+    h = dry(m=4, tau=2, mu=0.9)
+    B.ols_init_params(h, FAKE)
+    B.ols_set_mixing(h, FAKE + (5 << 30))
+    for _ in range(2):
+        B.ols_local_step(h)
+        B.ols_local_step(h)
+        assert code_of(B.ols_local_step, h) == B.OLS_ESTATE        # the synchronisation is due
+        assert code_of(B.ols_set_mixing, h, None) == B.OLS_ESTATE  # not in the middle of one
+        B.ols_sync_pull(h)
+        B.ols_anchor_update_async(h)
+    kinds = [B.ols_kernel_name(e["kind"]) for e in B.ols_trace(h)]
+    assert kinds == ["init", "step", "step", "mix", "step", "step", "mix"]
+    assert all(e["stream"] == 0 for e in B.ols_trace(h))
+    # back to the paper's synchronisation
+    B.ols_set_mixing(h, None)
+    B.ols_local_step(h)
+    B.ols_local_step(h)
+    B.ols_sync_pull(h)
+    B.ols_anchor_update_async(h)
+    kinds = [B.ols_kernel_name(e["kind"]) for e in B.ols_trace(h)][7:]
+    assert kinds == ["step", "step_pull", "mean"]
+    B.ols_destroy(h)
+
+
+def test_general_mixing_argument_checks():
+    h = B.ols_create(200, 64, 2, 0.5, 0.1, 0.0)
+    assert code_of(B.ols_set_mixing, h, FAKE) == B.OLS_EINVAL          # more than 128 workers
+    B.ols_destroy(h)
+    h = dry(m=4, tau=2, mu=0.0)
+    assert code_of(B.ols_set_mixing, h, FAKE + 2) == B.OLS_EINVAL      # alignment
+    B.ols_set_anchor_momentum(h, 0.7, FAKE + (6 << 30))
+    assert code_of(B.ols_set_mixing, h, FAKE) == B.OLS_EINVAL          # anchor momentum is set
+    B.ols_destroy(h)
