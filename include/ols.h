@@ -78,6 +78,8 @@ enum {
     OLS_OPT_GEMM_VARIANT_DA = 11,  /* an unknown variant makes the next local step fail with OLS_EHIP          */
     OLS_OPT_GEMM_SPLITK = 12,      /* fp32 forward GEMM: K ranges per output tile where the shape calls for
                                       splitting (0 = from the shape, 1 = never, up to 8)                       */
+    OLS_OPT_GEMM_FORCE_GENERAL = 14, /* 1: bf16 forward / delta GEMMs always take the bounds-checked kernel, also on
+                                      shapes the full-tile kernel covers (both give identical bits); default 0     */
     OLS_OPT_FUSE_GEMM_UPDATE = 13  /* 1 (default): with an attached MLP the kernels that form the gradients apply
                                       the local step (and on the tau-th step the pull-back) where each gradient
                                       element is produced, so g is never written nor re-read and ols_sync_pull only

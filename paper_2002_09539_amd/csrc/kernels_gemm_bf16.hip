@@ -381,7 +381,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
 
 
 // ---------------------------------------------------------------------------------------------
-// FWD / DA on full tiles: M % BM == 0, N % BN == 0, K % (2 BK) == 0.  One workgroup per compute unit, one
+// FWD / DA on full tiles: M % BM == 0, N % BN == 0, K % (NSETS BK) == 0.  One workgroup per compute unit, one
 // wavefront per SIMD: nothing else is resident to fill a stall, and a wavefront that has just issued an
 // MFMA cannot issue the next one for 32 cycles, so every other instruction of the loop (fragment reads,
 // the next slices' global loads, the LDS stores of the staged slice) is placed BETWEEN the MFMAs, one or
@@ -389,9 +389,10 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
 // reads, 12 global loads, 12 LDS stores, one workgroup barrier; addresses are one lane offset plus
 // wave-uniform bases, so the loop has no vector address arithmetic.
 // ---------------------------------------------------------------------------------------------
-template <int MODE, int BM, int BN, int BK>
+template <int MODE, int BM, int BN, int BK, int NSETS>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_full_kernel(GemmDevB p) {
     static_assert(MODE != kDw && BK == 64, "forward / delta GEMM, four k-steps per slice");
+    static_assert(NSETS % 2 == 0, "the LDS buffer of a slice is its parity");
     constexpr int WM = BM / 2, WN = BN / 2;     // 2 x 2 wavefronts
     constexpr int TM = WM / 32, TN = WN / 32;
     using Shape = GemmShape<MODE, BM, BN, BK>;
@@ -471,28 +472,28 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_full_kernel(GemmDevB p) {
         if ((loads) > 0) __builtin_amdgcn_sched_group_barrier(0x020, (loads), 0);   \
     }
     constexpr int kReads = (TM + 2 * TN + kMfmas - 1) / kMfmas;          // LDS reads per MFMA (an RC fragment is two reads)
-    constexpr int kLoadsA = (NA + kMfmas - 1) / kMfmas, kLoadsB = (NB + kMfmas - 1) / kMfmas;
+    constexpr int kLoads = (NA + NB + kMfmas - 1) / kMfmas;
     constexpr int kWrites = (NA + NB + kMfmas - 1) / kMfmas;
-    // One K slice out of lds[cur]: fragments of step 0 are in buffer 0 on entry.  `st` (the next slice,
-    // loaded one slice ago) is published to lds[cur ^ 1] during step 2; the slice after it is requested into
-    // `ld` during steps 0 and 1.
-    auto slice = [&](int cur, const u4 (&st_a)[NA], const u4 (&st_b)[NB], u4 (&ld_a)[NA], u4 (&ld_b)[NB],
-                     const char* next_a, const char* next_b) {
+    // One K slice out of lds[cur]: fragments of step 0 are in buffer 0 on entry.  The register set `r` holds
+    // the NEXT slice (requested NSETS slices ago): it is published to lds[cur ^ 1] during step 0 and the
+    // same registers then request the slice NSETS further on during step 1.  lds[cur ^ 1] was last read
+    // before the previous slice's barrier, so it may be overwritten from the start of this slice.
+    auto slice = [&](int cur, u4 (&r_a)[NA], u4 (&r_b)[NB], const char* next_a, const char* next_b) {
         load_frags(1, cur, 1);
-        load_a(ld_a, next_a);
-        mfmas(0);
-        OLS_INTERLEAVE(kReads, 0, kLoadsA)
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(0, cur, 2);
-        load_b(ld_b, next_b);
-        mfmas(1);
-        OLS_INTERLEAVE(kReads, 0, kLoadsB)
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(1, cur, 3);
-        store_a(cur ^ 1, st_a);
-        store_b(cur ^ 1, st_b);
+        store_a(cur ^ 1, r_a);
+        store_b(cur ^ 1, r_b);
         mfmas(0);
         OLS_INTERLEAVE(kReads, kWrites, 0)
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(0, cur, 2);
+        load_a(r_a, next_a);
+        load_b(r_b, next_b);
+        mfmas(1);
+        OLS_INTERLEAVE(kReads, 0, kLoads)
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(1, cur, 3);
+        mfmas(0);
+        OLS_INTERLEAVE(kReads, 0, 0)
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         load_frags(0, cur ^ 1, 0);
@@ -502,25 +503,35 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_full_kernel(GemmDevB p) {
     };
 #undef OLS_INTERLEAVE
 
-    const int nk = p.K / BK;   // even
-    u4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
-    load_a(ra0, a_tile);
-    load_b(rb0, b_tile);
-    load_a(ra1, a_tile + step_a);
-    load_b(rb1, b_tile + step_b);
-    store_a(0, ra0);
-    store_b(0, rb0);
+    // NSETS register sets form a ring: at the start of slice t they hold slices t + 1 .. t + NSETS (landed or
+    // on their way), so every load has NSETS - 1 slice times to arrive.
+    const int nk = p.K / BK;   // a multiple of NSETS
+    u4 ra[NSETS][NA], rb[NSETS][NB];
+    load_a(ra[0], a_tile);
+    load_b(rb[0], b_tile);
+#pragma unroll
+    for (int u = 1; u < NSETS; ++u) {
+        load_a(ra[u], a_tile + u * step_a);
+        load_b(rb[u], b_tile + u * step_b);
+    }
+    store_a(0, ra[0]);
+    store_b(0, rb[0]);
+    {
+        const int kn = NSETS < nk ? NSETS : 0;   // set 0 is free again: it takes slice NSETS
+        load_a(ra[0], a_tile + kn * step_a);
+        load_b(rb[0], b_tile + kn * step_b);
+    }
     __syncthreads();
     load_frags(0, 0, 0);
-    for (int kt = 0; kt < nk; kt += 2) {
-        // slices past the end re-read slice 0 (in bounds, never consumed)
-#ifdef OLS_EXP_HOTLOADS
-        const int k2 = 0, k3 = 0;
-#else
-        const int k2 = kt + 2 < nk ? kt + 2 : 0, k3 = kt + 3 < nk ? kt + 3 : 0;
-#endif
-        slice(0, ra1, rb1, ra0, rb0, a_tile + k2 * step_a, b_tile + k2 * step_b);
-        slice(1, ra0, rb0, ra1, rb1, a_tile + k3 * step_a, b_tile + k3 * step_b);
+    for (int kt = 0; kt < nk; kt += NSETS) {
+#pragma unroll
+        for (int u = 0; u < NSETS; ++u) {
+            // this slice is t = kt + u; it publishes slice t + 1 (set (u + 1) % NSETS) and requests slice
+            // t + 1 + NSETS into the same set; slices past the end re-read slice 0 (in bounds, never consumed)
+            const int tn = kt + u + 1 + NSETS;
+            const int kn = tn < nk ? tn : 0;
+            slice(u & 1, ra[(u + 1) % NSETS], rb[(u + 1) % NSETS], a_tile + kn * step_a, b_tile + kn * step_b);
+        }
     }
 
     // Epilogue: the bf16 tile goes through LDS so that every lane then moves 16-byte vectors of 8 consecutive
@@ -614,9 +625,12 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     void (*kern)(GemmDevB) = gemm_bf16_kernel<MODE, BM, BN, BK, DEPTH>;
     if constexpr (MODE != kDw && BK == 64) {
         // full tiles and 32-bit lane offsets: the branch-free, interleaved kernel
-        const bool full = g.M % BM == 0 && g.N % BN == 0 && g.K % (2 * BK) == 0 &&
+        // Register sets of operand slices in flight.  Four sets (three slices of lead time) were measured equal to
+        // two on configuration 3: the loop is bound by the LDS pipe (fragment reads + tile stores), not by load latency.
+        constexpr int kSets = 2;
+        const bool full = g.M % BM == 0 && g.N % BN == 0 && g.K % (kSets * BK) == 0 &&
                           (int64_t)BM * g.lda < (1 << 29) && (int64_t)(MODE == kFwd ? BK : BN) * g.ldb < (1 << 29);
-        if (full && !g.force_general) kern = gemm_bf16_full_kernel<MODE, BM, BN, BK>;
+        if (full && !g.force_general) kern = gemm_bf16_full_kernel<MODE, BM, BN, BK, kSets>;
     }
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

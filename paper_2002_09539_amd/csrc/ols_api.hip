@@ -65,6 +65,7 @@ struct ols_ctx {
     int mean_split = 0;
     int gemm_variant[3] = {0, 0, 0};  // fwd, dw, da
     int splitk = 0;                   // 0: from the shape
+    bool gemm_force_general = false;
     std::vector<int> fwd_splits;      // planned K ranges per hidden layer (fp32 forward GEMM)
     int64_t off_partial = 0;
     // schedule
@@ -285,6 +286,7 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
         ga.ldc = c->dims[l + 1];
         ga.bias = xc + c->b_off[l];
         ga.sbias = c->ld;
+        ga.force_general = c->gemm_force_general ? 1 : 0;
         ga.groups = m;
         ga.M = B;
         ga.N = c->dims[l + 1];
@@ -339,6 +341,7 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
             gd.c = c->ws + c->off_dz[l];
             gd.sc = (int64_t)B * c->dims[l];
             gd.ldc = c->dims[l];
+            gd.force_general = c->gemm_force_general ? 1 : 0;
             gd.groups = m;
             gd.M = B;
             gd.N = c->dims[l];
@@ -892,6 +895,7 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
             if (value < 0 || value > 8) return fail(OLS_EINVAL, "split-K count must be in [0, 8]");
             c->splitk = (int)value;
             break;
+        case OLS_OPT_GEMM_FORCE_GENERAL: c->gemm_force_general = value != 0; break;
         case OLS_OPT_FUSE_MEAN:
             if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "cannot change fusion in the middle of a synchronisation");
             c->fuse_mean = value != 0;

@@ -183,3 +183,22 @@ def test_update_fused_into_gradient_kernels_is_bit_identical(dtype, dims, batch,
             states.append((s.all_params(), s.params(-1), s.momentum(), np.array(losses)))
     for a, b in zip(states[0], states[1]):
         assert np.array_equal(a, b)
+
+
+def test_bf16_full_tile_kernel_matches_bounds_checked_kernel_bit_for_bit():
+    """Configuration 3's layer shapes take the branch-free full-tile forward / delta kernels; forcing the
+    bounds-checked kernel on the same shapes must give identical bits (same slices, same MFMA order)."""
+    m, dims, batch, K = 2, (3072, 2048, 2048, 2048, 10), 256, 3
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 2, seed=606)
+    states = []
+    for force in (0, 1):
+        with make_session(m, cfg.d, 2, 0.5, 0.05, 0.9) as s:
+            s.set_option(B.OLS_OPT_GEMM_FORCE_GENERAL, force)
+            s.attach_mlp(dims, batch, "bf16")
+            Xd, yd = s.upload(X), s.upload(labels)
+            s.init_params(x0)
+            losses = []
+            s.run(K, lambda k: s.set_batch(Xd[:, k % 2], yd[:, k % 2]), losses=losses)
+            states.append((s.all_params(), s.params(-1), np.array(losses)))
+    for a, b in zip(states[0], states[1]):
+        assert np.array_equal(a, b)
