@@ -49,6 +49,9 @@ def layer_slices(dims):
     (2, (40, 12), 8),                  # no hidden layer at all
     (4, (3072, 512, 10), 128),         # configuration 2's layer shapes
     (4, (3072, 1024, 10), 64),         # configuration 5's layer shapes
+    (2, (64, 48, 24), 12),             # more than 16 classes: the 32-class variant of the output-layer kernels
+    (2, (96, 1040, 32), 20),           # 32 classes, last hidden layer wider than two staging passes, ragged
+    (2, (64, 1544, 10), 24),           # last hidden layer wider than one 1024-unit pass, ragged
 ])
 def test_gradient_and_loss_match_oracle(m, dims, batch):
     cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 1, seed=101)
@@ -118,6 +121,7 @@ BF16_LOSS_TOL = 2e-2        # the benchmark specification's bar for bf16-GEMM ru
     (3, (128, 128, 128, 128, 16), 64),   # exact multiples, three hidden layers
     (2, (64, 8), 16),                    # no hidden layer
     (2, (3072, 2048, 2048, 10), 256),    # configuration 3's layer shapes
+    (2, (64, 1544, 24), 24),             # 24 classes and a ragged last hidden layer wider than a staging pass
 ])
 def test_bf16_gradient_and_loss(m, dims, batch):
     """Against the oracle with the same operand rounding (tight), and against the unrounded oracle
