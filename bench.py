@@ -32,7 +32,10 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload number (BASELINE configs are 1-based)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
     ap.add_argument("--serialize", type=int, default=0, help="1: anchor refresh on the main stream (no overlap)")
-    ap.add_argument("--fuse-mean", type=int, default=0, help="1: step + pull-back + anchor refresh in one pass")
+    ap.add_argument("--fuse-mean", type=int, default=None,
+                    help="1: step + pull-back + anchor refresh in one pass.  Default: 1 on the update-only stream "
+                         "(configuration 4 asks for the fused step + pull-back + mean, and an HBM-bound stream gains "
+                         "nothing from overlapping a second HBM-bound kernel), 0 elsewhere (side-stream refresh)")
     ap.add_argument("--mixing", choices=["none", "paper", "averaging"], default="none",
                     help="general mixing X <- X W at the synchronisation points: the paper's W or periodic averaging "
                          "applied by the one-pass mixing kernel instead of pull-back + anchor average")
@@ -162,6 +165,8 @@ def main():
     from paper_2002_09539_amd.session import Session
 
     cfg = I.get(args.config)
+    if args.fuse_mean is None:
+        args.fuse_mean = 1 if (cfg.kind == "stream" and not args.serialize and args.mixing == "none") else 0
     K = args.steps if args.steps is not None else cfg.K
     W = args.warmup if args.warmup is not None else 4 * cfg.tau
     K = max(cfg.tau, K // cfg.tau * cfg.tau)     # whole rounds, so every timed region ends on a refresh

@@ -30,11 +30,20 @@ __device__ __forceinline__ f4 shfl_xor_f4(f4 v, int mask) {
 
 // SW wavefront groups x SL lane groups share the replica axis; a workgroup covers
 // kThreads / (SW * SL) column vectors.
-template <int SW, int SL, bool ANCHOR_MOM>
-__global__ __launch_bounds__(kThreads) void mean_kernel(const f4* __restrict__ x, f4* z, f4* v, int m, int64_t n4,
-                                                        float beta_z) {
+// Workgroup size of the unsplit kernel and independent row loads in flight per lane.  Measured on the
+// d = 11.2 M, m = 16 stream (us per refresh, nothing else running): 256 threads x 4 rows: 129, 128 x 4: 130,
+// 64 x 4: 126, 64 x 8: 123, 64 x 16: 124.
+#ifndef OLS_MEAN_THREADS
+#define OLS_MEAN_THREADS 64
+#endif
+#ifndef OLS_MEAN_ROWS
+#define OLS_MEAN_ROWS 8
+#endif
+template <int THREADS, int SW, int SL, bool ANCHOR_MOM>
+__global__ __launch_bounds__(THREADS) void mean_kernel(const f4* __restrict__ x, f4* z, f4* v, int m, int64_t n4,
+                                                       float beta_z) {
     constexpr int G = SW * SL;
-    constexpr int kWavesPerGroup = (kThreads / kWave) / SW;   // wavefronts that form one wave group
+    constexpr int kWavesPerGroup = (THREADS / kWave) / SW;   // wavefronts that form one wave group
     constexpr int kColsPerWave = kWave / SL;
     constexpr int kCols = kColsPerWave * kWavesPerGroup;      // column vectors per workgroup
     const int wave = threadIdx.x / kWave;
@@ -48,16 +57,14 @@ __global__ __launch_bounds__(kThreads) void mean_kernel(const f4* __restrict__ x
 
     f4 acc = {0.f, 0.f, 0.f, 0.f};
     if (live) {
+        constexpr int R = OLS_MEAN_ROWS;
         int i = first;
-        for (; i + 3 * G < m; i += 4 * G) {                   // four independent loads in flight
-            const f4 a0 = __builtin_nontemporal_load(x + (int64_t)i * n4 + c);
-            const f4 a1 = __builtin_nontemporal_load(x + (int64_t)(i + G) * n4 + c);
-            const f4 a2 = __builtin_nontemporal_load(x + (int64_t)(i + 2 * G) * n4 + c);
-            const f4 a3 = __builtin_nontemporal_load(x + (int64_t)(i + 3 * G) * n4 + c);
-            acc = acc + a0;
-            acc = acc + a1;
-            acc = acc + a2;
-            acc = acc + a3;
+        for (; i + (R - 1) * G < m; i += R * G) {             // R independent loads in flight, added in row order
+            f4 a[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) a[r] = __builtin_nontemporal_load(x + (int64_t)(i + r * G) * n4 + c);
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc = acc + a[r];
         }
         for (; i < m; i += G) acc = acc + __builtin_nontemporal_load(x + (int64_t)i * n4 + c);
     }
@@ -106,15 +113,15 @@ int mean_auto_split(int m, int64_t ld) {
     return g;
 }
 
-template <int SW, int SL>
+template <int THREADS, int SW, int SL>
 static void mean_dispatch(const MeanArgs& a, hipStream_t s) {
     const int64_t n4 = a.ld / 4;
-    const int cols = kThreads / (SW * SL);
+    const int cols = THREADS / (SW * SL);
     const unsigned grid = (unsigned)((n4 + cols - 1) / cols);
     if (a.v)
-        mean_kernel<SW, SL, true><<<grid, kThreads, 0, s>>>((const f4*)a.x, (f4*)a.z, (f4*)a.v, a.m, n4, a.beta_z);
+        mean_kernel<THREADS, SW, SL, true><<<grid, THREADS, 0, s>>>((const f4*)a.x, (f4*)a.z, (f4*)a.v, a.m, n4, a.beta_z);
     else
-        mean_kernel<SW, SL, false><<<grid, kThreads, 0, s>>>((const f4*)a.x, (f4*)a.z, nullptr, a.m, n4, 0.0f);
+        mean_kernel<THREADS, SW, SL, false><<<grid, THREADS, 0, s>>>((const f4*)a.x, (f4*)a.z, nullptr, a.m, n4, 0.0f);
 }
 
 hipError_t launch_mean(const MeanArgs& a, hipStream_t s) {
@@ -123,11 +130,11 @@ hipError_t launch_mean(const MeanArgs& a, hipStream_t s) {
         return hipErrorInvalidValue;
     int g = a.split > 0 ? a.split : mean_auto_split(a.m, a.ld);
     switch (g) {
-        case 1: mean_dispatch<1, 1>(a, s); break;
-        case 2: mean_dispatch<2, 1>(a, s); break;
-        case 4: mean_dispatch<4, 1>(a, s); break;
-        case 8: mean_dispatch<4, 2>(a, s); break;
-        case 16: mean_dispatch<4, 4>(a, s); break;
+        case 1: mean_dispatch<OLS_MEAN_THREADS, 1, 1>(a, s); break;
+        case 2: mean_dispatch<kThreads, 2, 1>(a, s); break;
+        case 4: mean_dispatch<kThreads, 4, 1>(a, s); break;
+        case 8: mean_dispatch<kThreads, 4, 2>(a, s); break;
+        case 16: mean_dispatch<kThreads, 4, 4>(a, s); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -136,16 +143,26 @@ hipError_t launch_mean(const MeanArgs& a, hipStream_t s) {
 // ---------------------------------------------------------------------------------------------
 // step + pull-back + anchor refresh in one pass (column owner)
 // ---------------------------------------------------------------------------------------------
+// Launch shape, measured on the d = 11.2 M, m = 16 stream (us per launch; threads per workgroup x rows of
+// loads in flight per lane): 256 x 4: 681, 64 x 4: 652, 128 x 4: 680, 512 x 4: 698, 256 x 16: 662,
+// 64 x 8: 644, 64 x 16: 634 -- single-wavefront workgroups with a whole 16-replica column in flight.
+#ifndef OLS_SPM_THREADS
+#define OLS_SPM_THREADS 64
+#endif
+#ifndef OLS_SPM_ROWS
+#define OLS_SPM_ROWS 16
+#endif
+constexpr int kSpmThreads = OLS_SPM_THREADS;
 template <bool WITH_STEP, bool MOM, bool NEST, bool ANCHOR_MOM>
-__global__ __launch_bounds__(kThreads) void step_pull_mean_kernel(const f4* __restrict__ g, const f4* x_in, f4* x_out,
+__global__ __launch_bounds__(kSpmThreads) void step_pull_mean_kernel(const f4* __restrict__ g, const f4* x_in, f4* x_out,
                                                                   f4* buf, const f4* z_in, f4* z_out, f4* v, int m,
                                                                   int64_t n4, float gamma, float mu, float alpha,
                                                                   float beta_z) {
-    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t c = (int64_t)blockIdx.x * kSpmThreads + threadIdx.x;
     if (c >= n4) return;
     const f4 zo = z_in[c];
     f4 acc = {0.f, 0.f, 0.f, 0.f};
-    constexpr int R = 4;  // rows in flight
+    constexpr int R = OLS_SPM_ROWS;  // rows in flight
     for (int i0 = 0; i0 < m; i0 += R) {
         f4 vg[R], vx[R], vb[R];
 #pragma unroll
@@ -206,13 +223,13 @@ template <bool WITH_STEP, bool MOM, bool NEST>
 static void spm_dispatch(const StepPullMeanArgs& a, hipStream_t s) {
     const UpdateArgs& u = a.u;
     const int64_t n4 = u.ld / 4;
-    const unsigned grid = (unsigned)((n4 + kThreads - 1) / kThreads);
+    const unsigned grid = (unsigned)((n4 + kSpmThreads - 1) / kSpmThreads);
     if (a.v)
-        step_pull_mean_kernel<WITH_STEP, MOM, NEST, true><<<grid, kThreads, 0, s>>>(
+        step_pull_mean_kernel<WITH_STEP, MOM, NEST, true><<<grid, kSpmThreads, 0, s>>>(
             (const f4*)u.g, (const f4*)u.x_in, (f4*)u.x_out, (f4*)u.buf, (const f4*)u.z, (f4*)a.z_out, (f4*)a.v, u.m, n4,
             u.gamma, u.mu, u.alpha, a.beta_z);
     else
-        step_pull_mean_kernel<WITH_STEP, MOM, NEST, false><<<grid, kThreads, 0, s>>>(
+        step_pull_mean_kernel<WITH_STEP, MOM, NEST, false><<<grid, kSpmThreads, 0, s>>>(
             (const f4*)u.g, (const f4*)u.x_in, (f4*)u.x_out, (f4*)u.buf, (const f4*)u.z, (f4*)a.z_out, nullptr, u.m, n4,
             u.gamma, u.mu, u.alpha, 0.0f);
 }

@@ -19,7 +19,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
 #ifndef OLS_UPDATE_THREADS
-#define OLS_UPDATE_THREADS 256
+#define OLS_UPDATE_THREADS 64
 #endif
 #ifndef OLS_UPDATE_UNROLL
 #define OLS_UPDATE_UNROLL 1
@@ -28,9 +28,10 @@ typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 #define OLS_UPDATE_NONTEMPORAL 1
 #endif
 constexpr int kThreads = OLS_UPDATE_THREADS;
-// 16-byte vectors per lane per array.  Measured on the d = 11.2 M, m = 16 stream (local step, us):
-// 1 -> 601, 2 -> 628, 4 -> 618, 8 -> 655 (256 threads); 512 x 2 -> 619, 1024 x 2 -> 654; plain instead of
-// non-temporal accesses -> 656.  All within a few percent of 6 TB/s, the most this memory system gave.
+// Workgroup size and 16-byte vectors per lane per array.  Measured on the d = 11.2 M, m = 16 stream (local
+// step, us): 64 threads x 1 -> 552, 128 x 1 -> 584, 256 x 1 -> 599, 256 x 2 -> 628, 256 x 4 -> 618,
+// 256 x 8 -> 655, 512 x 2 -> 619, 1024 x 2 -> 654; plain instead of non-temporal accesses (256 x 1) -> 656.
+// Single-wavefront workgroups stream best: 6.5 TB/s.
 constexpr int kUnroll = OLS_UPDATE_UNROLL;
 
 #if OLS_UPDATE_NONTEMPORAL
