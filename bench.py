@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--mixing", choices=["none", "paper", "averaging"], default="none",
                     help="general mixing X <- X W at the synchronisation points: the paper's W or periodic averaging "
                          "applied by the one-pass mixing kernel instead of pull-back + anchor average")
+    ap.add_argument("--anchor-delay-us", type=int, default=0,
+                    help="emulated communication latency ahead of every anchor refresh (OLS_OPT_ANCHOR_DELAY_US); "
+                         "with --serialize 1 it blocks the main stream, otherwise the side stream hides it")
     ap.add_argument("--no-second-buffer", action="store_true")
     ap.add_argument("--fuse-gemm-update", type=int, default=1,
                     help="1 (default): gradient kernels apply the local step themselves; 0: separate streaming pass")
@@ -166,7 +169,8 @@ def main():
 
     cfg = I.get(args.config)
     if args.fuse_mean is None:
-        args.fuse_mean = 1 if (cfg.kind == "stream" and not args.serialize and args.mixing == "none") else 0
+        args.fuse_mean = 1 if (cfg.kind == "stream" and not args.serialize and args.mixing == "none"
+                               and not args.anchor_delay_us) else 0
     K = args.steps if args.steps is not None else cfg.K
     W = args.warmup if args.warmup is not None else 4 * cfg.tau
     K = max(cfg.tau, K // cfg.tau * cfg.tau)     # whole rounds, so every timed region ends on a refresh
@@ -177,6 +181,7 @@ def main():
     sess.set_option(B.OLS_OPT_NESTEROV, int(cfg.nesterov))
     sess.set_option(B.OLS_OPT_SERIALIZE, args.serialize)
     sess.set_option(B.OLS_OPT_FUSE_MEAN, args.fuse_mean)
+    sess.set_option(B.OLS_OPT_ANCHOR_DELAY_US, args.anchor_delay_us)
     sess.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, args.fuse_gemm_update)
     for kv in args.opt:
         key, val = kv.split("=")
@@ -269,7 +274,7 @@ def main():
         "config": {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
                    "dims": list(cfg.dims), "overlap": ("mixing-kernel:" + args.mixing) if args.mixing != "none" else
                    ("serialized" if args.serialize else ("fused-mean" if args.fuse_mean else "side-stream")),
-                   "second_buffer": not args.no_second_buffer,
+                   "second_buffer": not args.no_second_buffer, "anchor_delay_us": args.anchor_delay_us,
                    "update": "in-gradient-kernels" if (args.fuse_gemm_update and cfg.kind == "mlp") else "streaming"},
         "roofline": roofline,
         "cpu_baseline": base,

@@ -80,6 +80,13 @@ enum {
                                       splitting (0 = from the shape, 1 = never, up to 8)                       */
     OLS_OPT_GEMM_FORCE_GENERAL = 14, /* 1: bf16 forward / delta GEMMs always take the bounds-checked kernel, also on
                                       shapes the full-tile kernel covers (both give identical bits); default 0     */
+    OLS_OPT_ANCHOR_DELAY_US = 15,  /* emulated communication latency, 0 (default) .. 1000000 microseconds: a kernel
+                                      that only waits that long runs ahead of every anchor refresh on the refresh's
+                                      stream, standing in for the all-reduce time of a real cluster (Section 2: the
+                                      latency is hidden while it is shorter than tau local steps; Section 4's
+                                      comparison with blocking synchronisation is OLS_OPT_SERIALIZE = 1 with the same
+                                      delay).  Results do not depend on it.  Ignored where the anchor is produced by
+                                      the pull pass itself (OLS_OPT_FUSE_MEAN, ols_set_mixing).                    */
     OLS_OPT_FUSE_GEMM_UPDATE = 13  /* 1 (default): with an attached MLP the kernels that form the gradients apply
                                       the local step (and on the tau-th step the pull-back) where each gradient
                                       element is produced, so g is never written nor re-read and ols_sync_pull only
@@ -104,7 +111,8 @@ enum {
     OLS_K_HEAD_BWD = 12,  /* output layer gradients and delta           */
     OLS_K_MIX = 13,       /* general mixing X <- X W (ols_set_mixing)    */
     OLS_K_CAST = 14,      /* fp32 -> bf16 operand conversion            */
-    OLS_K_COUNT = 15
+    OLS_K_DELAY = 15,     /* emulated communication latency (OLS_OPT_ANCHOR_DELAY_US) */
+    OLS_K_COUNT = 16
 };
 
 typedef struct ols_trace_entry {

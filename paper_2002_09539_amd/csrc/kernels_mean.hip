@@ -234,6 +234,33 @@ static void spm_dispatch(const StepPullMeanArgs& a, hipStream_t s) {
             u.gamma, u.mu, u.alpha, 0.0f);
 }
 
+// Emulated communication latency ahead of the anchor refresh (the delay that Section 2, arXiv 2002.09539 argues
+// is hidden as long as it is shorter than tau local steps): one wavefront sleeps until the constant-rate wall
+// clock has advanced by `ticks`.  Two exit conditions, each reached by itself: the clock, and a bound on the
+// number of sleep periods (one period lasts well below a microsecond at any engine clock, so `max_spins` of
+// eight per requested microsecond is never the one that ends a healthy wait by much).
+__global__ __launch_bounds__(64) void delay_kernel(long long ticks, long long max_spins) {
+    const long long t0 = wall_clock64();
+    for (long long i = 0; i < max_spins; ++i) {
+        if (wall_clock64() - t0 >= ticks) break;
+        __builtin_amdgcn_s_sleep(8);
+    }
+}
+
+hipError_t launch_delay(int64_t microseconds, hipStream_t s) {
+    if (microseconds < 1 || microseconds > 1000000) return hipErrorInvalidValue;
+    int dev = 0, khz = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+    if (e != hipSuccess) return e;
+    if (khz < 1) return hipErrorInvalidValue;
+    const long long ticks = (long long)microseconds * khz / 1000;
+    // s_sleep 8 idles about 512 engine clocks: at least 0.15 us between 1 and 3.4 GHz
+    delay_kernel<<<1, 64, 0, s>>>(ticks, (long long)microseconds * 8 + 64);
+    return hipGetLastError();
+}
+
 hipError_t launch_step_pull_mean(const StepPullMeanArgs& a, hipStream_t s) {
     const UpdateArgs& u = a.u;
     if (u.m < 1 || u.ld < 4 || u.ld % 4 != 0 || !u.x_in || !u.x_out || !u.z || !a.z_out) return hipErrorInvalidValue;

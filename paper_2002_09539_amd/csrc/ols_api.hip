@@ -36,7 +36,7 @@ int fail(int code, const char* fmt, ...) {
 
 const char* kKernelNames[OLS_K_COUNT] = {
     "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
-    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16"};
+    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16", "delay"};
 
 enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2 };
 
@@ -63,6 +63,7 @@ struct ols_ctx {
     bool nesterov = true, fuse_pull = true, serialize = false, dry = false, timing = false, trace = false,
          fuse_mean = false, fuse_gemm_update = true;
     int mean_split = 0;
+    int64_t anchor_delay_us = 0;   // emulated communication latency ahead of every anchor refresh
     int gemm_variant[3] = {0, 0, 0};  // fwd, dw, da
     int splitk = 0;                   // 0: from the shape
     bool gemm_force_general = false;
@@ -771,6 +772,11 @@ int ols_anchor_update_async(ols_handle c) {
         if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent");
     }
     if (sid == 1) c->next_waited = true;
+    if (c->anchor_delay_us > 0) {
+        const int64_t us = c->anchor_delay_us;
+        int rc = enqueue(c, OLS_K_DELAY, sid, -1, -1, [&](hipStream_t s) { return launch_delay(us, s); });
+        if (rc) return rc;
+    }
     MeanArgs a = {};
     a.x = c->x[c->cur];
     a.z = c->z;
@@ -896,6 +902,10 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
             c->splitk = (int)value;
             break;
         case OLS_OPT_GEMM_FORCE_GENERAL: c->gemm_force_general = value != 0; break;
+        case OLS_OPT_ANCHOR_DELAY_US:
+            if (value < 0 || value > 1000000) return fail(OLS_EINVAL, "the anchor delay must be 0 .. 1000000 microseconds");
+            c->anchor_delay_us = value;
+            break;
         case OLS_OPT_FUSE_MEAN:
             if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "cannot change fusion in the middle of a synchronisation");
             c->fuse_mean = value != 0;

@@ -51,6 +51,8 @@ struct StepPullMeanArgs {
     bool with_step; // false: pull-back + mean only (parameters already stepped)
 };
 hipError_t launch_step_pull_mean(const StepPullMeanArgs& a, hipStream_t s);
+// one wavefront that waits `microseconds` (1 .. 1 000 000) of wall-clock time: emulated communication latency
+hipError_t launch_delay(int64_t microseconds, hipStream_t s);
 
 // general mixing X <- X W over the m + 1 rows [x^(1..m), z]
 constexpr int kMixMaxWorkers = 128;

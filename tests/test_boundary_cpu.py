@@ -160,6 +160,34 @@ def test_tau_one_and_fused_mean_schedules():
     B.ols_destroy(h)
 
 
+def test_emulated_communication_delay_precedes_every_refresh_on_its_stream():
+    h = dry(tau=2)
+    B.ols_set_option(h, B.OLS_OPT_ANCHOR_DELAY_US, 250)
+    run_rounds(h, 2, 2)
+    tr = B.ols_trace(h)
+    assert kinds(tr) == ["init"] + ["step", "step_pull", "delay", "mean"] * 2
+    assert [t["stream"] for t in tr if t["kind"] in (B.OLS_K_DELAY, B.OLS_K_MEAN)] == [1] * 4
+    assert [t["waited"] for t in tr if t["kind"] == B.OLS_K_DELAY] == [1, 1]   # the side stream waits for the pull
+    B.ols_destroy(h)
+    h = dry(tau=2)   # blocking synchronisation with the same latency: everything on the main stream
+    B.ols_set_option(h, B.OLS_OPT_SERIALIZE, 1)
+    B.ols_set_option(h, B.OLS_OPT_ANCHOR_DELAY_US, 250)
+    run_rounds(h, 1, 2)
+    tr = B.ols_trace(h)
+    assert kinds(tr) == ["init", "step", "step_pull", "delay", "mean"] and all(t["stream"] == 0 for t in tr)
+    B.ols_destroy(h)
+    h = dry(tau=2)   # no refresh kernel, nothing to delay
+    B.ols_set_option(h, B.OLS_OPT_FUSE_MEAN, 1)
+    B.ols_set_option(h, B.OLS_OPT_ANCHOR_DELAY_US, 250)
+    run_rounds(h, 1, 2)
+    assert kinds(B.ols_trace(h)) == ["init", "step", "step_pull_mean"]
+    for bad in (-1, 1000001):
+        with pytest.raises(B.OlsError) as e:
+            B.ols_set_option(h, B.OLS_OPT_ANCHOR_DELAY_US, bad)
+        assert e.value.code == B.OLS_EINVAL
+    B.ols_destroy(h)
+
+
 def test_trailing_steps_need_no_pull():
     h = dry(tau=4)
     B.ols_init_params(h, FAKE)

@@ -113,6 +113,29 @@ def test_schedule_variants_are_bit_identical():
             assert np.array_equal(base[t], other[t]), "%s differs in %s" % (name, t)
 
 
+def test_emulated_communication_delay_changes_timing_not_results():
+    """A refresh that arrives late (the next pull has to wait for it, the stated reading of a slow anchor)
+    and a refresh delayed on the main stream give the bits of the undelayed run; the delay kernel really
+    waits, and its wait ends (kernel statistics)."""
+    from paper_2002_09539_amd import binding as B
+    m, d, tau, K = 16, 300000, 2, 12
+    cfg, x0, grads = stream_case(m, d, 4)
+    base = final_state(m, d, tau, 0.9, K, x0, grads)
+    for name, options in {"late refresh": [(B.OLS_OPT_ANCHOR_DELAY_US, 3000)],
+                          "late, no second buffer": [(B.OLS_OPT_ANCHOR_DELAY_US, 3000)],
+                          "blocking": [(B.OLS_OPT_ANCHOR_DELAY_US, 500), (B.OLS_OPT_SERIALIZE, 1)]}.items():
+        other = final_state(m, d, tau, 0.9, K, x0, grads, options=options, overlap_buffer=name != "late, no second buffer")
+        for t in ("x", "z", "buf"):
+            assert np.array_equal(base[t], other[t]), "%s differs in %s" % (name, t)
+    with make_session(m, d, tau, 0.6, 0.1, 0.9, own_gradient=False) as s:
+        s.set_option(B.OLS_OPT_ANCHOR_DELAY_US, 2000)
+        s.set_option(B.OLS_OPT_KERNEL_TIMING, 1)
+        run_stream_gpu(s, x0, grads, 4, snapshots=False)
+        s.sync()
+        n, ms = s.kernel_stats()["delay"]
+    assert n == 2 and 1.9 <= ms / n <= 2.6, (n, ms)
+
+
 @pytest.mark.parametrize("split", [1, 2, 4, 8, 16])
 def test_mean_split_variants_match_oracle(split):
     from paper_2002_09539_amd import binding as B
