@@ -206,6 +206,7 @@ def test_stream_config_full_size_sampled_columns():
     """Configuration 4 at its full size (m = 16, d = 11.2 M) and at a ragged neighbour
     (d = 11,173,962), in the launch configuration the benchmark times.  The update is element-wise
     and the mean is column-wise, so the oracle recomputes a sample of columns exactly."""
+    from paper_2002_09539_amd import binding as B
     cfg = I.get(4)
     rng = np.random.default_rng(5)
     for d in (cfg.d, 11_173_962):
@@ -213,17 +214,21 @@ def test_stream_config_full_size_sampled_columns():
         cols = np.unique(np.concatenate([rng.integers(0, d, 4000), [0, 1, 2, 3, d - 4, d - 3, d - 2, d - 1]]))
         x0 = G.stream_x0(cfg, d=d)
         grads = [G.stream_gradient(cfg, j, d=d) for j in range(cfg.grad_pool)]
-        with make_session(m, d, cfg.tau, cfg.alpha, cfg.gamma, cfg.mu, own_gradient=False) as s:
-            run_stream_gpu(s, x0, grads, K, snapshots=False)
-            x = s.all_params()[:, cols]
-            z = s.params(-1)[cols]
-            buf = s.momentum()[:, cols]
         st = O.run(x0[cols], m, cfg.tau, cfg.alpha, cfg.gamma, K,
                    OW.stream_grad_fn([g[:, cols] for g in grads]), mu=cfg.mu)
+        # the benchmark's default on this configuration is the single fused pass at the synchronisation points
+        # (OLS_OPT_FUSE_MEAN = 1); its --fuse-mean 0 variant runs separate kernels with the mean on the side stream
+        for fuse_mean in (1, 0):
+            with make_session(m, d, cfg.tau, cfg.alpha, cfg.gamma, cfg.mu, own_gradient=False) as s:
+                s.set_option(B.OLS_OPT_FUSE_MEAN, fuse_mean)
+                run_stream_gpu(s, x0, grads, K, snapshots=False)
+                x = s.all_params()[:, cols]
+                z = s.params(-1)[cols]
+                buf = s.momentum()[:, cols]
+            assert max_norm_ratio(x, st["x"]) <= PER_STEP_TOL * 3, (d, fuse_mean)
+            assert max_norm_ratio(z, st["z"]) <= PER_STEP_TOL * 3, (d, fuse_mean)
+            assert max_norm_ratio(buf, st["buf"]) <= PER_STEP_TOL * 3, (d, fuse_mean)
         del grads
-        assert max_norm_ratio(x, st["x"]) <= PER_STEP_TOL * 3
-        assert max_norm_ratio(z, st["z"]) <= PER_STEP_TOL * 3
-        assert max_norm_ratio(buf, st["buf"]) <= PER_STEP_TOL * 3
 
 
 def test_lsq_gradient_and_loss_single_step():
