@@ -87,6 +87,11 @@ enum {
                                       comparison with blocking synchronisation is OLS_OPT_SERIALIZE = 1 with the same
                                       delay).  Results do not depend on it.  Ignored where the anchor is produced by
                                       the pull pass itself (OLS_OPT_FUSE_MEAN, ols_set_mixing).                    */
+    OLS_OPT_HEAD_DW_GUEST = 16,    /* 1 (default): with an attached MLP that has a hidden layer, the output layer's
+                                      weight / bias gradients (and their fused update) are computed by extra
+                                      workgroups at the front of the launch of the last hidden layer's
+                                      weight-gradient GEMM instead of a kernel of their own (OLS_K_HEAD_BWD then
+                                      does not appear); same arithmetic, identical bits                          */
     OLS_OPT_FUSE_GEMM_UPDATE = 13  /* 1 (default): with an attached MLP the kernels that form the gradients apply
                                       the local step (and on the tau-th step the pull-back) where each gradient
                                       element is produced, so g is never written nor re-read and ols_sync_pull only

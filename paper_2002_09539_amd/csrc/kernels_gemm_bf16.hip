@@ -31,6 +31,7 @@
 #include <type_traits>
 
 #include "gemm_epilogue.h"
+#include "head_dw_body.h"
 #include "ols_internal.h"
 
 namespace ols {
@@ -66,6 +67,7 @@ struct GemmDevB {
     int64_t sa, sb, sc, sbias, smask, scolsum;
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
+    HeadDwDev guest;     // DW: output-layer gradients computed by the first guest.blocks workgroups (0: none)
 };
 
 // K-contiguous operand tile: memory [rows][K]; LDS [ROWS][BK + 8].
@@ -196,8 +198,18 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
     auto lds_a = [&](int buf) { return lds_all + buf * TA::kElems; };
     auto lds_b = [&](int buf) { return lds_all + 2 * TA::kElems + buf * TB::kElems; };
 
+    // Guest workgroups come first in the launch, so they start at once and their latency-bound work runs
+    // beside the tiles of the GEMM.  Their number is a multiple of 8: the tiles keep their XCD assignment.
+    int bid = blockIdx.x;
+    if (MODE == kDw) {
+        if (bid < p.guest.blocks) {
+            head_dw_guest<(int)(Shape::kLdsBytes / sizeof(float))>(p.guest, (float*)lds_all, bid);
+            return;
+        }
+        bid -= p.guest.blocks;
+    }
     // XCD-aware tile id: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous tile range
-    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int xcd = bid % kXcds, slot = bid / kXcds;
     const int tile = xcd * p.chunk + slot;
     if (slot >= p.chunk || tile >= p.total_tiles) return;
     const int per_group = p.tiles_m * p.tiles_n;
@@ -595,7 +607,12 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
         if (!aligned16(g.c) || g.ldc % 8 || g.sc % 8) return hipErrorInvalidValue;
     }
     if (g.ldc < g.N) return hipErrorInvalidValue;
-    GemmDevB p;
+    GemmDevB p = {};
+    if (g.guest) {
+        if (MODE != kDw) return hipErrorInvalidValue;
+        hipError_t ge = head_dw_prepare(*g.guest, &p.guest);
+        if (ge != hipSuccess) return ge;
+    }
     p.a = (const uint16_t*)g.a;
     p.b = (const uint16_t*)g.b;
     p.c = g.c;
@@ -636,7 +653,7 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    kern<<<(unsigned)(p.chunk * kXcds), kThreads, lds, s>>>(p);
+    kern<<<(unsigned)(p.guest.blocks + p.chunk * kXcds), kThreads, lds, s>>>(p);
     return hipGetLastError();
 }
 

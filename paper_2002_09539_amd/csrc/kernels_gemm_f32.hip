@@ -19,6 +19,7 @@
 // Workgroup ids are remapped so that consecutive tiles of one worker land on the same XCD (workgroups
 // are dealt round-robin to the 8 XCDs, each with its own L2), keeping a worker's weights in one L2.
 #include "gemm_epilogue.h"
+#include "head_dw_body.h"
 #include "ols_internal.h"
 
 namespace ols {
@@ -45,6 +46,7 @@ struct GemmDev {
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
     int splits, k_chunk, groups;
+    HeadDwDev guest;     // DW: output-layer gradients computed by the first guest.blocks workgroups (0: none)
 };
 
 // One operand tile of ROWS x BK in LDS.  KC: stored [ROWS][BK + 4]; RC: stored [BK][ROWS + 4].
@@ -121,8 +123,18 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     auto lds_a = [&](int buf) { return lds_all + buf * TA::kFloats; };
     auto lds_b = [&](int buf) { return lds_all + 2 * TA::kFloats + buf * TB::kFloats; };
 
+    // Guest workgroups come first in the launch, so they start at once and their latency-bound work runs
+    // beside the tiles of the GEMM.  Their number is a multiple of 8: the tiles keep their XCD assignment.
+    int bid = blockIdx.x;
+    if (MODE == kDw) {
+        if (bid < p.guest.blocks) {
+            head_dw_guest<kLdsFloats>(p.guest, lds_all, bid);
+            return;
+        }
+        bid -= p.guest.blocks;
+    }
     // XCD-aware tile id: hardware deals workgroup b to XCD b % 8; give each XCD a contiguous tile range
-    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int xcd = bid % kXcds, slot = bid / kXcds;
     const int tile = xcd * p.chunk + slot;
     if (slot >= p.chunk || tile >= p.total_tiles) return;
     const int per_split = p.tiles_m * p.tiles_n, per_group = per_split * p.splits;
@@ -322,7 +334,12 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (g.lda < (a_kc ? g.K : g.M) || g.ldb < (b_kc ? g.K : g.N) || g.ldc < g.N) return hipErrorInvalidValue;
     if (MODE == kFwd && !g.bias) return hipErrorInvalidValue;
     if (MODE == kDa && !g.mask) return hipErrorInvalidValue;
-    GemmDev p;
+    GemmDev p = {};
+    if (g.guest) {
+        if (MODE != kDw) return hipErrorInvalidValue;
+        hipError_t ge = head_dw_prepare(*g.guest, &p.guest);
+        if (ge != hipSuccess) return ge;
+    }
     p.a = (const float*)g.a;
     p.b = (const float*)g.b;
     p.c = (float*)g.c;
@@ -356,7 +373,7 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (total > (1 << 30)) return hipErrorInvalidValue;
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
-    gemm_f32_kernel<MODE, BM, BN, BK, WAVES_M, WAVES_N, DEPTH><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
+    gemm_f32_kernel<MODE, BM, BN, BK, WAVES_M, WAVES_N, DEPTH><<<(unsigned)(p.guest.blocks + p.chunk * kXcds), kThreads, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits == 1) return e;
     // second pass of a split-K forward GEMM: sum the partials, add the bias, apply the ReLU

@@ -10,13 +10,15 @@
 //                     DPP row) share a sample; the 16 partial logits are combined with DPP row
 //                     rotations, every lane then evaluates the softmax redundantly, and the staged
 //                     activations (ReLU mask) and weights are reused for dz.
-//   head_dw_kernel    dW = h^T dlogits, db = colsum(dlogits), consumed by the fused update or stored.
+//   head_dw_kernel    dW = h^T dlogits, db = colsum(dlogits), consumed by the fused update or stored (body in
+//                     head_dw_body.h; by default it runs as guest workgroups of a weight-gradient GEMM instead).
 //
 // Per worker i with last hidden activations h [B][H], weights W [H][C], bias b [C], labels y [B]
 // (the mini-batch loss whose gradient is the g_i of Section 2, arXiv 2002.09539):
 //   logits = h W + b;  loss_s = logsumexp(logits_s) - logits_s[y_s];  dlogits = (softmax - onehot) / B
 //   dW = h^T dlogits;  db = colsum(dlogits);  dz = (dlogits W^T) * [h > 0]
 // The class dimension is padded to CMAX (16 or 32) with zeros in LDS so that no inner loop branches on C.
+#include "head_dw_body.h"
 #include "ols_internal.h"
 
 namespace ols {
@@ -32,11 +34,6 @@ __device__ __forceinline__ unsigned int f32_to_bf16(float f) {
     const unsigned int u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
-// low (e = 0) or high (e = 1) bf16 of a packed word
-__device__ __forceinline__ float bf16_elem(unsigned int word, int e) {
-    return __uint_as_float((e & 1) ? (word & 0xFFFF0000u) : (word << 16));
-}
-
 // Sum over the 16 lanes of a DPP row, the same bits in every lane of the row (each step adds a lane's
 // value to that of its partner 8, 4, 2, 1 lanes away, which is symmetric).
 __device__ __forceinline__ float row_sum(float v) {
@@ -61,10 +58,6 @@ __device__ __forceinline__ float row_max(float v) {
     return v;
 }
 
-// LDS row pitch (floats) of a CMAX-wide weight / delta row: a multiple of 4 so rows are read as 16-byte
-// vectors, and an odd number of such vectors so that 16 lanes reading consecutive rows hit distinct banks.
-__host__ __device__ constexpr int row_pitch(int C) { return 4 * (((C + 3) / 4) | 1); }
-
 struct HeadDev {
     const void* h;
     const float* x;
@@ -81,14 +74,14 @@ constexpr int kHeadSamples = kHeadThreads / kRow;   // samples per workgroup of 
 
 // KC = hidden units staged per pass (512 or 1024); activation rows are staged at pitch KC + 4
 __host__ __device__ constexpr int head_fwd_lds_floats(int CMAX, int KC) {
-    return KC * row_pitch(CMAX) + kHeadSamples * (KC + 4) + kHeadSamples * CMAX;
+    return KC * head_row_pitch(CMAX) + kHeadSamples * (KC + 4) + kHeadSamples * CMAX;
 }
 
 // grid (ceil(B / 16), m); dynamic LDS: head_fwd_lds_floats(CMAX, KC) floats
 template <bool BF, int CMAX, int KC>
 __global__ __launch_bounds__(kHeadThreads) void head_fwd_kernel(HeadDev p) {
     constexpr int THREADS = kHeadThreads, S = kHeadSamples, HP = KC + 4;
-    constexpr int P = row_pitch(CMAX);         // LDS pitch of a weight row
+    constexpr int P = head_row_pitch(CMAX);         // LDS pitch of a weight row
     constexpr int NW = KC * CMAX / THREADS;    // staged weights per lane, all in flight at once
     constexpr int J = KC / (4 * kRow);         // 4-wide activation vectors per lane per pass (8)
     extern __shared__ __attribute__((aligned(16))) float s_dyn[];
@@ -137,10 +130,10 @@ __global__ __launch_bounds__(kHeadThreads) void head_fwd_kernel(HeadDev p) {
 #pragma unroll
             for (int u = 0; u < NH; ++u) {
                 const int f = threadIdx.x + u * THREADS, r = f / (KC / 8), kv = 8 * (f % (KC / 8));
-                *(f4*)(s_h + r * HP + kv) = f4{bf16_elem(th[u].x, 0), bf16_elem(th[u].x, 1), bf16_elem(th[u].y, 0),
-                                               bf16_elem(th[u].y, 1)};
-                *(f4*)(s_h + r * HP + kv + 4) = f4{bf16_elem(th[u].z, 0), bf16_elem(th[u].z, 1), bf16_elem(th[u].w, 0),
-                                                   bf16_elem(th[u].w, 1)};
+                *(f4*)(s_h + r * HP + kv) = f4{head_bf16_elem(th[u].x, 0), head_bf16_elem(th[u].x, 1), head_bf16_elem(th[u].y, 0),
+                                               head_bf16_elem(th[u].y, 1)};
+                *(f4*)(s_h + r * HP + kv + 4) = f4{head_bf16_elem(th[u].z, 0), head_bf16_elem(th[u].z, 1), head_bf16_elem(th[u].w, 0),
+                                                   head_bf16_elem(th[u].w, 1)};
             }
         } else {
             constexpr int NH = S * KC / 4 / THREADS;   // 16-byte vectors of 4 floats per lane (8)
@@ -281,121 +274,13 @@ __global__ __launch_bounds__(kHeadThreads) void head_fwd_kernel(HeadDev p) {
     }
 }
 
-// dW[k][c] = sum_s h[s][k] dlogits[s][c], db[c] = sum_s dlogits[s][c].  A workgroup owns 32 hidden units of
-// one worker; the activations of those units and the dlogits pass through LDS; lane (k, class quad, part)
-// sums its part of the samples in sample order, and the parts are added in a fixed order.  The parameters
-// and momenta the fused update will need are requested at the start.  grid (ceil(H / 32), m)
+// Output-layer gradients as a kernel of their own (the body lives in head_dw_body.h, where it also serves as a
+// guest of the weight-gradient GEMM's launch).  grid (ceil(H / 32), m)
 template <bool BF, int CMAX>
-__global__ __launch_bounds__(256) void head_dw_kernel(const void* __restrict__ h, int64_t h_stride,
-                                                      const float* __restrict__ dlogits, float* __restrict__ g,
-                                                      int64_t ld, int64_t w_off, int64_t b_off, int B, int H, int C,
-                                                      FusedUpdate upd) {
-    constexpr int kThreads = 256, KW = 32;
+__global__ __launch_bounds__(kHeadDwThreads) void head_dw_kernel(HeadDwDev a) {
     constexpr int kRows = CMAX > 16 ? 128 : 256;      // samples staged per pass (LDS stays below 64 KiB)
-    constexpr int P = row_pitch(CMAX);
-    constexpr int CQ = CMAX / 4;                      // class quads
-    constexpr int NP = kThreads / (KW * CQ);          // parts the samples are split into (2 or 1)
-    constexpr int kOut = KW * CMAX / kThreads;        // output elements per lane (class-padded)
-    constexpr int kStage = kRows * CMAX / kThreads;   // staged dlogits per lane
-    constexpr int kTile = kRows * KW / 4 / kThreads;  // staged 4-wide activation vectors per lane (8)
-    __shared__ __attribute__((aligned(16))) float s_dl[kRows * P];
-    __shared__ __attribute__((aligned(16))) float s_h[kRows * KW];
-    __shared__ float s_part[NP][KW * CMAX];
-    const int i = blockIdx.y;
-    const int cls = threadIdx.x % CMAX;
-    const int kq = threadIdx.x % KW, cq = (threadIdx.x / KW) % CQ, part = threadIdx.x / (KW * CQ);
-    const int k_base = blockIdx.x * KW;
-    const bool bias_lane = blockIdx.x == 0 && (int)threadIdx.x < C;
-
-    // Operands of the fused update.  Output o of lane t is class t % CMAX of row k_base + t / CMAX + o (256 / CMAX).
-    float ux[kOut], ub[kOut], uz[kOut], bx = 0.0f, bb = 0.0f, bz = 0.0f;
-    if (upd.enabled) {
-#pragma unroll
-        for (int o = 0; o < kOut; ++o) {
-            const int kk = k_base + threadIdx.x / CMAX + o * (kThreads / CMAX);
-            ux[o] = ub[o] = uz[o] = 0.0f;
-            if (cls < C && kk < H) {
-                const int64_t col = w_off + (int64_t)kk * C + cls, idx = (int64_t)i * ld + col;
-                ux[o] = upd.x_in[idx];
-                if (upd.mu != 0.0f) ub[o] = upd.buf[idx];
-                if (upd.pull) uz[o] = upd.z[col];
-            }
-        }
-        if (bias_lane) {
-            const int64_t col = b_off + threadIdx.x, idx = (int64_t)i * ld + col;
-            bx = upd.x_in[idx];
-            if (upd.mu != 0.0f) bb = upd.buf[idx];
-            if (upd.pull) bz = upd.z[col];
-        }
-    }
-    f4 acc = {0.f, 0.f, 0.f, 0.f};
-    float bias_acc = 0.0f;
-    for (int s0 = 0; s0 < B; s0 += kRows) {
-        const int rows = min(kRows, B - s0);
-        if (s0 > 0) __syncthreads();
-        {   // dlogits rows (zero beyond C and beyond the batch) and the activation tile, one round trip
-            const float* src = dlogits + ((int64_t)i * B + s0) * C + cls;
-            float tmp[kStage];
-#pragma unroll
-            for (int u = 0; u < kStage; ++u) {
-                const int r = threadIdx.x / CMAX + u * (kThreads / CMAX);
-                tmp[u] = (cls < C && r < rows) ? src[r * C] : 0.0f;
-            }
-            f4 th[kTile];
-#pragma unroll
-            for (int u = 0; u < kTile; ++u) {
-                const int f = threadIdx.x + u * kThreads, r = f / (KW / 4), k = k_base + 4 * (f % (KW / 4));
-                th[u] = f4{0.f, 0.f, 0.f, 0.f};
-                if (r < rows && k < H) {   // H is a multiple of 4
-                    const int64_t idx = (int64_t)i * h_stride + (int64_t)(s0 + r) * H + k;
-                    if constexpr (BF) {
-                        const u2 w = *(const u2*)((const uint16_t*)h + idx);
-                        th[u] = f4{bf16_elem(w.x, 0), bf16_elem(w.x, 1), bf16_elem(w.y, 0), bf16_elem(w.y, 1)};
-                    } else {
-                        th[u] = *(const f4*)((const float*)h + idx);
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kStage; ++u) {
-                const int r = threadIdx.x / CMAX + u * (kThreads / CMAX);
-                s_dl[r * P + cls] = tmp[u];
-            }
-#pragma unroll
-            for (int u = 0; u < kTile; ++u) *(f4*)(s_h + 4 * (threadIdx.x + u * kThreads)) = th[u];
-        }
-        __syncthreads();
-#pragma unroll 4
-        for (int sidx = part; sidx < rows; sidx += NP) {
-            const float hv = s_h[sidx * KW + kq];
-            const f4 dl = *(const f4*)(s_dl + sidx * P + 4 * cq);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) acc[q] = __fmaf_rn(hv, dl[q], acc[q]);
-        }
-        if (bias_lane)
-            for (int sidx = 0; sidx < rows; ++sidx) bias_acc += s_dl[sidx * P + threadIdx.x];
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) s_part[part][kq * CMAX + 4 * cq + q] = acc[q];
-    __syncthreads();
-#pragma unroll
-    for (int o = 0; o < kOut; ++o) {
-        const int t = threadIdx.x + o * kThreads;   // = (row inside the workgroup) * CMAX + class
-        const int kk = k_base + t / CMAX;
-        if (cls < C && kk < H) {
-            float v = s_part[0][t];
-#pragma unroll
-            for (int q = 1; q < NP; ++q) v += s_part[q][t];
-            const int64_t idx = (int64_t)i * ld + w_off + (int64_t)kk * C + cls;
-            if (upd.enabled) fused_update_store(upd, idx, v, ux[o], ub[o], uz[o]);
-            else g[idx] = v;
-        }
-    }
-    if (bias_lane) {
-        const int64_t idx = (int64_t)i * ld + b_off + threadIdx.x;
-        if (upd.enabled) fused_update_store(upd, idx, bias_acc, bx, bb, bz);
-        else g[idx] = bias_acc;
-    }
+    __shared__ __attribute__((aligned(16))) float lds[head_dw_lds_floats(CMAX, kRows)];
+    head_dw_body<BF, CMAX, kRows>(a, lds, blockIdx.x, blockIdx.y);
 }
 
 static bool head_args_ok(const HeadArgs& a) {
@@ -450,22 +335,47 @@ hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
     return wide ? head_fwd_launch<false, 16, 1024>(p, a.m, s) : head_fwd_launch<false, 16, 512>(p, a.m, s);
 }
 
-// gradients of the output layer's weights and bias (stored to g, or consumed by the fused update)
-hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s) {
+// Validates the arguments of the output layer's gradient pass and lays them out for the device.
+hipError_t head_dw_prepare(const HeadArgs& a, HeadDwDev* out) {
     if (!head_args_ok(a)) return hipErrorInvalidValue;
     if (a.upd.enabled && (!a.upd.x_in || !a.upd.x_out || (a.upd.mu != 0.0f && !a.upd.buf) || (a.upd.pull && !a.upd.z) ||
                           a.upd.ld != a.ld))
         return hipErrorInvalidValue;
-    dim3 grid((unsigned)((a.H + 31) / 32), (unsigned)a.m);
-#define OLS_HEAD_DW(BF, CM)                                                                                       \
-    head_dw_kernel<BF, CM><<<grid, 256, 0, s>>>(a.h, a.h_stride, a.dlogits, a.g, a.ld, a.w_off, a.b_off, a.B,     \
-                                               a.H, a.C, a.upd)
+    HeadDwDev d = {};
+    d.h = a.h;
+    d.dlogits = a.dlogits;
+    d.g = a.g;
+    d.h_stride = a.h_stride;
+    d.ld = a.ld;
+    d.w_off = a.w_off;
+    d.b_off = a.b_off;
+    d.B = a.B;
+    d.H = a.H;
+    d.C = a.C;
+    d.bf16 = a.h_bf16 ? 1 : 0;
+    d.grid_x = (a.H + kHeadDwUnits - 1) / kHeadDwUnits;
+    const int64_t live = (int64_t)d.grid_x * a.m;
+    if (live > (1 << 24)) return hipErrorInvalidValue;
+    d.live = (int)live;
+    d.blocks = (int)round_up(live, 8);   // a host launch keeps its own workgroup -> XCD assignment
+    d.upd = a.upd;
+    *out = d;
+    return hipSuccess;
+}
+
+// gradients of the output layer's weights and bias (stored to g, or consumed by the fused update)
+hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s) {
+    HeadDwDev d;
+    hipError_t e = head_dw_prepare(a, &d);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)d.grid_x, (unsigned)a.m);
     if (a.h_bf16) {
-        if (a.C <= 16) OLS_HEAD_DW(true, 16); else OLS_HEAD_DW(true, 32);
+        if (a.C <= 16) head_dw_kernel<true, 16><<<grid, kHeadDwThreads, 0, s>>>(d);
+        else head_dw_kernel<true, 32><<<grid, kHeadDwThreads, 0, s>>>(d);
     } else {
-        if (a.C <= 16) OLS_HEAD_DW(false, 16); else OLS_HEAD_DW(false, 32);
+        if (a.C <= 16) head_dw_kernel<false, 16><<<grid, kHeadDwThreads, 0, s>>>(d);
+        else head_dw_kernel<false, 32><<<grid, kHeadDwThreads, 0, s>>>(d);
     }
-#undef OLS_HEAD_DW
     return hipGetLastError();
 }
 

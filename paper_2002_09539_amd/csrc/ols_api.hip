@@ -67,6 +67,7 @@ struct ols_ctx {
     int gemm_variant[3] = {0, 0, 0};  // fwd, dw, da
     int splitk = 0;                   // 0: from the shape
     bool gemm_force_general = false;
+    bool head_dw_guest = true;        // output-layer gradients ride in the last hidden layer's weight-gradient launch
     std::vector<int> fwd_splits;      // planned K ranges per hidden layer (fp32 forward GEMM)
     int64_t off_partial = 0;
     // schedule
@@ -322,8 +323,13 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
     if (upd) ha.upd = *upd;
     rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); });
     if (rc) return rc;
-    rc = enqueue(c, OLS_K_HEAD_BWD, 0, src_buf, upd ? dst_buf : -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); });
-    if (rc) return rc;
+    // The output layer's own gradients either ride along in the weight-gradient launch of layer L - 2 below
+    // (nothing between here and there reads the output layer's parameters) or get a kernel of their own.
+    const bool guest = c->head_dw_guest && L >= 2;
+    if (!guest) {
+        rc = enqueue(c, OLS_K_HEAD_BWD, 0, src_buf, upd ? dst_buf : -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); });
+        if (rc) return rc;
+    }
     // hidden layers backward.  The delta GEMM of a layer reads that layer's weights, so it runs before
     // the weight-gradient GEMM, which may update them in place.
     for (int l = L - 2; l >= 0; --l) {
@@ -369,6 +375,7 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
             gw.upd_w_off = c->w_off[l];
             gw.upd_b_off = c->b_off[l];
         }
+        gw.guest = (guest && l == L - 2) ? &ha : nullptr;
         gw.groups = m;
         gw.M = c->dims[l];
         gw.N = c->dims[l + 1];
@@ -902,6 +909,7 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
             c->splitk = (int)value;
             break;
         case OLS_OPT_GEMM_FORCE_GENERAL: c->gemm_force_general = value != 0; break;
+        case OLS_OPT_HEAD_DW_GUEST: c->head_dw_guest = value != 0; break;
         case OLS_OPT_ANCHOR_DELAY_US:
             if (value < 0 || value > 1000000) return fail(OLS_EINVAL, "the anchor delay must be 0 .. 1000000 microseconds");
             c->anchor_delay_us = value;

@@ -128,6 +128,8 @@ __device__ __forceinline__ void fused_update_store(const FusedUpdate& u, int64_t
 }
 #endif
 
+struct HeadArgs;
+
 // grouped GEMMs over the m workers (group strides in elements)
 struct GemmArgs {
     const void* a;      // operand A, group stride sa
@@ -139,6 +141,8 @@ struct GemmArgs {
     float* partial;     // fp32 fwd with splits > 1: scratch of splits * groups * M * N floats
     int splits;         // fp32 fwd: number of K ranges contracted by separate workgroups (<= 1: none)
     int force_general;  // bf16: use the bounds-checked kernel even where the full-tile kernel applies
+    const HeadArgs* guest;  // dw: the output layer's weight / bias gradients (launch_head_bwd's work) are computed by
+                            // extra workgroups at the front of this launch; nullptr: none
     FusedUpdate upd;    // dw: when enabled, c is NOT written; the update of W (c's position in the replica row is
     int64_t upd_w_off;  //     upd_w_off) and of the bias (upd_b_off, from the column sums) is applied instead
     int64_t upd_b_off;

@@ -219,12 +219,13 @@ def test_model_attachment_validation():
     assert code_of(B.ols_set_batch, h, FAKE, 8 * 8 - 4, FAKE, 8) == B.OLS_EINVAL  # worker stride too small
     B.ols_set_batch(h, FAKE, 8 * 8, FAKE, 8)
     B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
-    B.ols_local_step(h)          # default: the gradient kernels apply the update themselves
-    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw"]
+    B.ols_local_step(h)          # default: the gradient kernels apply the update themselves, and the output
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "gemm_dw"]   # layer's gradients ride in gemm_dw's launch
     B.ols_local_step(h)          # boundary step (tau = 2): pull-back applied there as well
     B.ols_sync_pull(h)           # ... so the pull launches nothing
     B.ols_anchor_update_async(h)
-    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "head_bwd", "gemm_dw"] * 2 + ["mean"]
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd", "head_fwd", "gemm_dw"] * 2 + ["mean"]
+    B.ols_set_option(h, B.OLS_OPT_HEAD_DW_GUEST, 0)   # output-layer gradients in a kernel of their own
     B.ols_set_option(h, B.OLS_OPT_FUSE_GEMM_UPDATE, 0)
     B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
     B.ols_local_step(h)
@@ -247,8 +248,7 @@ def test_deep_mlp_launch_plan():
     B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
     B.ols_local_step(h)
     # each layer's delta GEMM precedes its weight-gradient GEMM (which may update the weights in place)
-    assert kinds(B.ols_trace(h)) == ["gemm_fwd"] * 3 + ["head_fwd", "head_bwd"] + \
-        ["gemm_da", "gemm_dw"] * 2 + ["gemm_dw"]
+    assert kinds(B.ols_trace(h)) == ["gemm_fwd"] * 3 + ["head_fwd"] + ["gemm_da", "gemm_dw"] * 2 + ["gemm_dw"]
     tr = B.ols_trace(h)
     assert all((t["src_buf"], t["dst_buf"]) == (0, 0) for t in tr if B.ols_kernel_name(t["kind"]) == "gemm_dw")
     B.ols_destroy(h)

@@ -189,6 +189,35 @@ def test_update_fused_into_gradient_kernels_is_bit_identical(dtype, dims, batch,
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("dtype,dims,batch", [("f32", (96, 72, 10), 36), ("f32", (64, 48, 100, 24), 132),
+                                              ("bf16", (128, 72, 64, 10), 40), ("bf16", (64, 1040, 32), 72)])
+@pytest.mark.parametrize("fused", [1, 0])
+def test_output_layer_gradients_as_guest_workgroups_are_bit_identical(dtype, dims, batch, fused):
+    """The output layer's weight / bias gradients computed by extra workgroups of the weight-gradient GEMM's launch
+    (default) or by a kernel of their own: same per-lane summation order, so identical bits -- with the update
+    fused into the gradient kernels and without, up to 16 and up to 32 classes, widths that are no multiple of
+    the 32 hidden units a workgroup owns, batches that are no multiple of the samples staged per pass."""
+    m, K = 3, 5
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 2, seed=707)
+    states = []
+    for guest in (1, 0):
+        with make_session(m, cfg.d, 2, 0.6, 0.05, 0.9) as s:
+            s.set_option(B.OLS_OPT_HEAD_DW_GUEST, guest)
+            s.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, fused)
+            s.set_option(B.OLS_OPT_KERNEL_TIMING, 1)
+            s.attach_mlp(dims, batch, dtype)
+            Xd, yd = s.upload(X), s.upload(labels)
+            s.init_params(x0)
+            losses = []
+            s.run(K, lambda k: s.set_batch(Xd[:, k % 2], yd[:, k % 2]), losses=losses)
+            s.sync()
+            assert ("head_bwd" in s.kernel_stats()) == (guest == 0)
+            grads = s.gradient() if not fused else None
+            states.append((s.all_params(), s.params(-1), s.momentum(), np.array(losses), grads))
+    for a, b in zip(states[0], states[1]):
+        assert (a is None and b is None) or np.array_equal(a, b)
+
+
 def test_bf16_full_tile_kernel_matches_bounds_checked_kernel_bit_for_bit():
     """Configuration 3's layer shapes take the branch-free full-tile forward / delta kernels; forcing the
     bounds-checked kernel on the same shapes must give identical bits (same slices, same MFMA order)."""
