@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--anchor-delay-us", type=int, default=0,
                     help="emulated communication latency ahead of every anchor refresh (OLS_OPT_ANCHOR_DELAY_US); "
                          "with --serialize 1 it blocks the main stream, otherwise the side stream hides it")
+    ap.add_argument("--loop", choices=["library", "python"], default="library",
+                    help="who drives the iterations of a configuration with an attached model: ols_run_steps, or one "
+                         "call per step from Python")
     ap.add_argument("--no-second-buffer", action="store_true")
     ap.add_argument("--fuse-gemm-update", type=int, default=1,
                     help="1 (default): gradient kernels apply the local step themselves; 0: separate streaming pass")
@@ -97,13 +100,13 @@ def build_workload(cfg, sess, torch):
         x0 = G.mlp_init(cfg)
         sess.attach_mlp(cfg.dims, cfg.batch, cfg.gemm_dtype)
         sess.init_params(x0)
-        return (lambda k: sess.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb])), (X, labels, x0)
+        return (lambda k: sess.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb])), (X, labels, x0), (Xd, yd)
     if cfg.kind == "lsq":
         A, y, _, x0 = G.lsq_data(cfg)
         Ad, yd = sess.upload(A), sess.upload(y)
         sess.attach_lsq(cfg.batch)
         sess.init_params(x0)
-        return (lambda k: sess.set_batch(Ad[:, k % cfg.nb], yd[:, k % cfg.nb])), (A, y, x0)
+        return (lambda k: sess.set_batch(Ad[:, k % cfg.nb], yd[:, k % cfg.nb])), (A, y, x0), (Ad, yd)
     # update-only stream: a pool of gradient tensors cycled per iteration
     x0 = G.stream_x0(cfg)
     pool = []
@@ -114,7 +117,7 @@ def build_workload(cfg, sess, torch):
     torch.cuda.synchronize()
     sess.bind(pool[0])
     sess.init_params(x0)
-    return (lambda k: sess.set_gradient(pool[k % len(pool)])), (None, None, x0)
+    return (lambda k: sess.set_gradient(pool[k % len(pool)])), (None, None, x0), None
 
 
 def cpu_baseline(cfg, host_inputs, seconds):
@@ -186,7 +189,9 @@ def main():
     for kv in args.opt:
         key, val = kv.split("=")
         sess.set_option(int(key), int(val))
-    feed, host_inputs = build_workload(cfg, sess, torch)
+    feed, host_inputs, resident = build_workload(cfg, sess, torch)
+    if args.loop == "python":
+        resident = None
     if args.mixing != "none":
         # the matrix is an INPUT of the path (the caller's choice of W); only its entries are written here
         Wm = np.zeros((cfg.m + 1, cfg.m + 1), np.float32)
@@ -202,7 +207,10 @@ def main():
         sess.sync()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        sess.run(steps, feed)
+        if resident is not None:      # the iteration loop runs inside the library (ols_run_steps)
+            sess.run_resident(steps, *resident)
+        else:
+            sess.run(steps, feed)
         sess.sync()
         torch.cuda.synchronize()
         return time.perf_counter() - t0
@@ -275,6 +283,7 @@ def main():
                    "dims": list(cfg.dims), "overlap": ("mixing-kernel:" + args.mixing) if args.mixing != "none" else
                    ("serialized" if args.serialize else ("fused-mean" if args.fuse_mean else "side-stream")),
                    "second_buffer": not args.no_second_buffer, "anchor_delay_us": args.anchor_delay_us,
+                   "loop": "library" if resident is not None else "python",
                    "update": "in-gradient-kernels" if (args.fuse_gemm_update and cfg.kind == "mlp") else "streaming"},
         "roofline": roofline,
         "cpu_baseline": base,

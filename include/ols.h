@@ -92,7 +92,8 @@ enum {
                                       workgroups at the front of the launch of the last hidden layer's
                                       weight-gradient GEMM instead of a kernel of their own (OLS_K_HEAD_BWD then
                                       does not appear); same arithmetic, identical bits                          */
-    OLS_OPT_FUSE_GEMM_UPDATE = 13  /* 1 (default): with an attached MLP the kernels that form the gradients apply
+    OLS_OPT_FUSE_GEMM_UPDATE = 13  /* 1 (default): with an attached MLP (or a least-squares model of at most 64 samples
+                                      per batch and 4096 parameters) the kernels that form the gradients apply
                                       the local step (and on the tau-th step the pull-back) where each gradient
                                       element is produced, so g is never written nor re-read and ols_sync_pull only
                                       publishes the result; 0: gradients go to g and the streaming kernels update.
@@ -117,7 +118,8 @@ enum {
     OLS_K_MIX = 13,       /* general mixing X <- X W (ols_set_mixing)    */
     OLS_K_CAST = 14,      /* fp32 -> bf16 operand conversion            */
     OLS_K_DELAY = 15,     /* emulated communication latency (OLS_OPT_ANCHOR_DELAY_US) */
-    OLS_K_COUNT = 16
+    OLS_K_LSQ_STEP = 16,  /* least squares, small problems: gradient and local step in one launch */
+    OLS_K_COUNT = 17
 };
 
 typedef struct ols_trace_entry {
@@ -231,6 +233,16 @@ OLS_API int ols_sync_pull(ols_handle h);
 /* Anchor refresh z <- (1/m) sum_i x^{(i)} over the post-pull models, enqueued on the side stream
  * behind the pull and overlapped with the following local steps.  Legal only right after a pull. */
 OLS_API int ols_anchor_update_async(ols_handle h);
+
+/* `steps` iterations in the order of the three calls above (ols_local_step; after every tau-th one
+ * ols_sync_pull and ols_anchor_update_async) driven from inside the library, for workloads whose steps
+ * are so short that the caller's loop would be the bottleneck.  The attached model's mini-batches come
+ * from a resident data set visited cyclically and unshuffled (Section 4: the data is partitioned and not
+ * shuffled): iteration k reads batch k mod nb of X_dev [m][nb][B][row] fp32 and y_dev [m][nb][B]
+ * (int32 labels or fp32 targets), k being the handle's iteration count.  Same launches as the
+ * separate calls; stops at the first error and returns it.  OLS_ESTATE without an attached model or
+ * when a pull or an anchor refresh is due. */
+OLS_API int ols_run_steps(ols_handle h, int64_t steps, const float* X_dev, const void* y_dev, int nb);
 
 /* ---- results --------------------------------------------------------------------------------- */
 

@@ -16,7 +16,7 @@ OLS_OK, OLS_EINVAL, OLS_ESTATE, OLS_EHIP, OLS_ENOMEM = 0, -1, -2, -3, -4
  OLS_OPT_ANCHOR_DELAY_US, OLS_OPT_HEAD_DW_GUEST) = range(1, 17)
 (OLS_K_INIT, OLS_K_STEP, OLS_K_STEP_PULL, OLS_K_PULL, OLS_K_MEAN, OLS_K_STEP_PULL_MEAN, OLS_K_LSQ_RESID,
  OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_MIX,
- OLS_K_CAST, OLS_K_DELAY, OLS_K_COUNT) = range(17)
+ OLS_K_CAST, OLS_K_DELAY, OLS_K_LSQ_STEP, OLS_K_COUNT) = range(18)
 
 
 class ols_trace_entry(C.Structure):
@@ -46,6 +46,7 @@ _SIGNATURES = {
     "ols_workspace_bytes": (C.c_int64, [_H]),
     "ols_bind_workspace": (C.c_int, [_H, _P, C.c_int64]),
     "ols_set_batch": (C.c_int, [_H, _P, C.c_int64, _P, C.c_int64]),
+    "ols_run_steps": (C.c_int, [_H, C.c_int64, _P, _P, C.c_int]),
     "ols_set_gradient": (C.c_int, [_H, _P]),
     "ols_local_step": (C.c_int, [_H]),
     "ols_sync_pull": (C.c_int, [_H]),
@@ -153,6 +154,10 @@ def ols_bind_workspace(h, ws, nbytes):
 
 def ols_set_batch(h, X, x_worker_stride, y, y_worker_stride):
     _check(load().ols_set_batch(h, X, x_worker_stride, y, y_worker_stride))
+
+
+def ols_run_steps(h, steps, X, y, nb):
+    _check(load().ols_run_steps(h, steps, X, y, nb))
 
 
 def ols_set_gradient(h, g):

@@ -36,7 +36,7 @@ int fail(int code, const char* fmt, ...) {
 
 const char* kKernelNames[OLS_K_COUNT] = {
     "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
-    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16", "delay"};
+    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16", "delay",    "lsq_step"};
 
 enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2 };
 
@@ -250,6 +250,12 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
     if (c->model == MODEL_LSQ) {
         float* resid = (float*)(c->ws + c->off_resid);
         float* loss = (float*)(c->ws + c->off_loss);
+        if (upd) {   // small problem: one launch forms the gradient and applies the step
+            const FusedUpdate u = *upd;
+            return enqueue(c, OLS_K_LSQ_STEP, 0, src_buf, dst_buf, [&](hipStream_t s) {
+                return launch_lsq_step(c->X, c->xs, (const float*)c->y, c->ys, loss, m, B, c->d, u, s);
+            });
+        }
         int rc = enqueue(c, OLS_K_LSQ_RESID, 0, c->cur, -1, [&](hipStream_t s) {
             return launch_lsq_resid(c->X, c->xs, (const float*)c->y, c->ys, xc, c->ld, resid, loss, m, B, c->d, s);
         });
@@ -654,7 +660,8 @@ int ols_local_step(ols_handle c) {
     }
     const bool boundary = (c->k + 1) % c->tau == 0;
     const bool paper_sync = c->mix_w == nullptr;   // the synchronisation is the paper's pull-back + anchor average
-    if (c->model == MODEL_MLP && c->fuse_gemm_update && !(boundary && c->fuse_mean && paper_sync)) {
+    const bool grad_kernels_update = c->model == MODEL_MLP || (c->model == MODEL_LSQ && lsq_step_fits(c->B, c->d));
+    if (grad_kernels_update && c->fuse_gemm_update && !(boundary && c->fuse_mean && paper_sync)) {
         // the gradient kernels apply the update themselves; on a boundary step the pull-back as well,
         // so the anchor of the previous round must have landed before they start
         int src, dst;
@@ -801,6 +808,31 @@ int ols_anchor_update_async(ols_handle c) {
         }
         c->anchor_inflight = true;
         c->first_after_anchor = true;
+    }
+    return OLS_OK;
+}
+
+int ols_run_steps(ols_handle c, int64_t steps, const float* X, const void* y, int nb) {
+    if (int rc = need(c)) return rc;
+    if (c->model == MODEL_NONE) return fail(OLS_ESTATE, "ols_run_steps needs an attached model");
+    if (steps < 0 || nb < 1 || !X || !y) return fail(OLS_EINVAL, "steps >= 0, nb >= 1 and non-null data are required");
+    if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "a pull or an anchor refresh is due");
+    const int64_t row = c->model == MODEL_LSQ ? c->d : (int64_t)c->dims[0];
+    const int64_t x_batch = (int64_t)c->B * row, y_batch = c->B;   // elements per batch
+    const size_t y_elem = 4;                                          // int32 labels and fp32 targets alike
+    for (int64_t it = 0; it < steps; ++it) {
+        const int64_t b = c->k % nb;
+        int rc = ols_set_batch(c, X + b * x_batch, (int64_t)nb * x_batch, (const char*)y + (size_t)(b * y_batch) * y_elem,
+                               (int64_t)nb * y_batch);
+        if (rc) return rc;
+        rc = ols_local_step(c);
+        if (rc) return rc;
+        if (c->pull_due) {
+            rc = ols_sync_pull(c);
+            if (rc) return rc;
+            rc = ols_anchor_update_async(c);
+            if (rc) return rc;
+        }
     }
     return OLS_OK;
 }

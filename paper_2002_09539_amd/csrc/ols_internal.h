@@ -128,6 +128,11 @@ __device__ __forceinline__ void fused_update_store(const FusedUpdate& u, int64_t
 }
 #endif
 
+// least squares, small problems: residual, loss, gradient and the local step (+ pull-back) in one launch
+bool lsq_step_fits(int B, int64_t d);
+hipError_t launch_lsq_step(const float* A, int64_t a_stride, const float* y, int64_t y_stride, float* loss_parts, int m,
+                           int B, int64_t d, const FusedUpdate& u, hipStream_t s);
+
 struct HeadArgs;
 
 // grouped GEMMs over the m workers (group strides in elements)

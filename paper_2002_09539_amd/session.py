@@ -128,6 +128,12 @@ class Session:
                 B.ols_sync_pull(self.h)
                 B.ols_anchor_update_async(self.h)
 
+    def run_resident(self, K, X, y):
+        """K iterations over a resident data set X: device [m][nb][B][in] fp32, y: device [m][nb][B], batch
+        k mod nb at iteration k; the loop runs inside the library (ols_run_steps)."""
+        assert X.is_contiguous() and y.is_contiguous() and X.shape[:2] == y.shape[:2] and X.dtype == torch.float32
+        B.ols_run_steps(self.h, K, _ptr(X), _ptr(y), X.shape[1])
+
     # ---- results -----------------------------------------------------------------------------
     def params(self, which):
         out = np.empty(self.d, dtype=np.float32)

@@ -237,6 +237,36 @@ def test_model_attachment_validation():
     B.ols_destroy(h)
 
 
+def test_least_squares_launch_plan():
+    h = dry(d=100, mu=0.9, tau=2)
+    B.ols_attach_lsq(h, 8)
+    B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+    B.ols_init_params(h, FAKE)
+    B.ols_set_batch(h, FAKE, 8 * 100, FAKE, 8)
+    def one_round(tau):
+        for _ in range(tau):
+            B.ols_local_step(h)
+        B.ols_sync_pull(h)
+        B.ols_anchor_update_async(h)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    one_round(2)
+    assert kinds(B.ols_trace(h)) == ["lsq_step", "lsq_step", "mean"]   # small problem: one launch per local step
+    B.ols_set_option(h, B.OLS_OPT_FUSE_GEMM_UPDATE, 0)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    one_round(2)
+    assert kinds(B.ols_trace(h)) == ["lsq_resid", "lsq_grad", "step", "lsq_resid", "lsq_grad", "step_pull", "mean"]
+    B.ols_destroy(h)
+    h = dry(d=5000, mu=0.9, tau=1)          # too wide for one workgroup: separate kernels
+    B.ols_attach_lsq(h, 8)
+    B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+    B.ols_init_params(h, FAKE)
+    B.ols_set_batch(h, FAKE, 8 * 5000, FAKE, 8)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    one_round(1)
+    assert kinds(B.ols_trace(h)) == ["lsq_resid", "lsq_grad", "step_pull", "mean"]
+    B.ols_destroy(h)
+
+
 def test_deep_mlp_launch_plan():
     dims = [8, 12, 16, 20, 5]
     d = sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(4))

@@ -218,6 +218,25 @@ def test_output_layer_gradients_as_guest_workgroups_are_bit_identical(dtype, dim
         assert (a is None and b is None) or np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_library_driven_loop_equals_one_call_per_step(dtype):
+    m, dims, batch, K = 3, (64, 40, 10), 24, 9
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 4, seed=909)
+    outs = []
+    for library in (True, False):
+        with make_session(m, cfg.d, 2, 0.6, 0.05, 0.9) as s:
+            s.attach_mlp(dims, batch, dtype)
+            Xd, yd = s.upload(X), s.upload(labels)
+            s.init_params(x0)
+            if library:
+                s.run_resident(K, Xd, yd)
+            else:
+                s.run(K, lambda k: s.set_batch(Xd[:, k % 4], yd[:, k % 4]))
+            outs.append((s.all_params(), s.params(-1), s.momentum(), s.losses()))
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+
+
 def test_bf16_full_tile_kernel_matches_bounds_checked_kernel_bit_for_bit():
     """Configuration 3's layer shapes take the branch-free full-tile forward / delta kernels; forcing the
     bounds-checked kernel on the same shapes must give identical bits (same slices, same MFMA order)."""

@@ -235,7 +235,9 @@ def test_lsq_gradient_and_loss_single_step():
     cfg = I.get(1)
     A, y, w_star, _ = G.lsq_data(cfg.scaled(nb=1))
     x0 = G.generic_normal(11, 0, (cfg.d,), sigma=0.05)
+    from paper_2002_09539_amd import binding as B
     with make_session(cfg.m, cfg.d, cfg.tau, cfg.alpha, cfg.gamma, cfg.mu) as s:
+        s.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, 0)     # keep the gradients in g so they can be read
         s.attach_lsq(cfg.batch)
         Ad, yd = s.upload(A), s.upload(y)
         s.init_params(x0)
@@ -266,6 +268,62 @@ def test_config1_least_squares_end_to_end():
     assert l2_ratio(z, st["z"]) <= E2E_TOL
     np.testing.assert_allclose(np.array(losses_g), losses_o, rtol=1e-3)
     assert losses_o[-5:].mean() < 0.9 * losses_o[:5].mean()        # the run actually optimises
+
+
+@pytest.mark.parametrize("m,d,batch,tau,mu,fused", [(4, 1024, 32, 2, 0.0, 1), (3, 1500, 20, 2, 0.9, 1), (5, 2048, 32, 3, 0.9, 1),
+                                                    (2, 7, 4, 1, 0.9, 1), (3, 4100, 8, 2, 0.9, 1), (2, 4096, 64, 2, 0.9, 1), (3, 1500, 20, 2, 0.9, 0)])
+def test_least_squares_runs_match_oracle(m, d, batch, tau, mu, fused):
+    """Small problems take the single-launch kernel (gradient + local step + pull-back), larger ones (d = 4100) and
+    the unfused route the separate residual / gradient / update kernels; either way parameters, anchor, momentum
+    and losses follow the oracle."""
+    from paper_2002_09539_amd import binding as B
+    cfg = I.get(1).scaled(m=m, d_flat=d, batch=batch, tau=tau, mu=mu, nb=3, K=3 * tau + 1)
+    A, y, _, _ = G.lsq_data(cfg)
+    x0 = G.generic_normal(12, 0, (d,), sigma=0.05)
+    st = OW.run_config(cfg, x0, OW.lsq_grad_fn(A, y))
+    with make_session(m, d, tau, cfg.alpha, cfg.gamma, mu) as s:
+        s.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, fused)
+        s.set_option(B.OLS_OPT_KERNEL_TIMING, 1)
+        s.attach_lsq(batch)
+        Ad, yd = s.upload(A), s.upload(y)
+        s.init_params(x0)
+        losses = []
+        s.run(cfg.K, lambda k: s.set_batch(Ad[:, k % cfg.nb], yd[:, k % cfg.nb]), losses=losses)
+        x, z, buf = s.all_params(), s.params(-1), s.momentum()
+        s.sync()
+        assert ("lsq_step" in s.kernel_stats()) == (fused == 1 and d <= 4096)
+    assert max(max_norm_ratio(x[i], st["x"][i]) for i in range(m)) <= 1e-5
+    assert max_norm_ratio(z, st["z"]) <= 1e-5
+    if mu:
+        assert max(max_norm_ratio(buf[i], st["buf"][i]) for i in range(m)) <= 1e-5
+    np.testing.assert_allclose(np.array(losses), st["losses"], rtol=1e-5)
+
+
+def test_library_driven_loop_equals_one_call_per_step():
+    """ols_run_steps issues the launches of the separate calls: identical bits, for both models."""
+    from paper_2002_09539_amd import binding as B
+    import torch
+    cfg = I.get(1).scaled(nb=5, K=11)
+    A, y, _, x0 = G.lsq_data(cfg)
+    x0 = G.generic_normal(13, 0, (cfg.d,), sigma=0.05)
+    outs = []
+    for library in (True, False):
+        with make_session(cfg.m, cfg.d, cfg.tau, cfg.alpha, cfg.gamma, 0.9) as s:
+            s.attach_lsq(cfg.batch)
+            Ad, yd = s.upload(A), s.upload(y)
+            s.init_params(x0)
+            if library:
+                s.run_resident(4, Ad, yd)       # in two pieces: the batch index follows the iteration count
+                s.run_resident(cfg.K - 4, Ad, yd)
+            else:
+                s.run(cfg.K, lambda k: s.set_batch(Ad[:, k % cfg.nb], yd[:, k % cfg.nb]))
+            outs.append((s.all_params(), s.params(-1), s.momentum(), s.losses()))
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    with make_session(cfg.m, cfg.d, cfg.tau, cfg.alpha, cfg.gamma, 0.9) as s:    # error paths
+        with pytest.raises(B.OlsError) as e:
+            B.ols_run_steps(s.h, 1, 256, 256, 1)
+        assert e.value.code == B.OLS_ESTATE             # no model attached
 
 
 def test_identical_data_keeps_replicas_bit_identical():
