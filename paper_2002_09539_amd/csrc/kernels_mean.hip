@@ -146,6 +146,8 @@ hipError_t launch_mean(const MeanArgs& a, hipStream_t s) {
 // Launch shape, measured on the d = 11.2 M, m = 16 stream (us per launch; threads per workgroup x rows of
 // loads in flight per lane): 256 x 4: 681, 64 x 4: 652, 128 x 4: 680, 512 x 4: 698, 256 x 16: 662,
 // 64 x 8: 644, 64 x 16: 634 -- single-wavefront workgroups with a whole 16-replica column in flight.
+// Two or four 16-byte columns per lane (2-4 KiB contiguous per wavefront and row) with proportionally fewer rows
+// in flight were slower (667-691).
 #ifndef OLS_SPM_THREADS
 #define OLS_SPM_THREADS 64
 #endif
