@@ -267,6 +267,40 @@ def test_least_squares_launch_plan():
     B.ols_destroy(h)
 
 
+def test_library_driven_loop_issues_the_launches_of_the_separate_calls():
+    def attach():
+        h = dry(d=100, mu=0.9, tau=3)
+        B.ols_attach_lsq(h, 8)
+        B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+        B.ols_init_params(h, FAKE)
+        B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+        return h
+    h = attach()
+    B.ols_run_steps(h, 4, FAKE, FAKE, 5)
+    B.ols_run_steps(h, 3, FAKE, FAKE, 5)
+    assert B.ols_iteration(h) == 7
+    a = [(t["kind"], t["stream"], t["src_buf"], t["dst_buf"], t["waited"], t["k"]) for t in B.ols_trace(h)]
+    for bad in ((-1, FAKE, FAKE, 5), (1, None, FAKE, 5), (1, FAKE, None, 5), (1, FAKE, FAKE, 0)):
+        assert code_of(B.ols_run_steps, h, *bad) == B.OLS_EINVAL
+    B.ols_local_step(h)
+    B.ols_local_step(h)                                   # k = 9: a pull is due
+    assert code_of(B.ols_run_steps, h, 1, FAKE, FAKE, 5) == B.OLS_ESTATE
+    B.ols_destroy(h)
+    h = attach()
+    for k in range(7):
+        B.ols_set_batch(h, FAKE, 5 * 8 * 100, FAKE, 5 * 8)
+        B.ols_local_step(h)
+        if (k + 1) % 3 == 0:
+            B.ols_sync_pull(h)
+            B.ols_anchor_update_async(h)
+    b = [(t["kind"], t["stream"], t["src_buf"], t["dst_buf"], t["waited"], t["k"]) for t in B.ols_trace(h)]
+    assert a == b and len(a) == 7 + 2
+    B.ols_destroy(h)
+    h = dry(d=100)
+    assert code_of(B.ols_run_steps, h, 1, FAKE, FAKE, 1) == B.OLS_ESTATE      # no model attached
+    B.ols_destroy(h)
+
+
 def test_deep_mlp_launch_plan():
     dims = [8, 12, 16, 20, 5]
     d = sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(4))
