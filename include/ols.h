@@ -78,7 +78,7 @@ enum {
     OLS_OPT_GEMM_VARIANT_DA = 11,  /* an unknown variant makes the next local step fail with OLS_EHIP          */
     OLS_OPT_GEMM_SPLITK = 12,      /* fp32 forward GEMM: K ranges per output tile where the shape calls for
                                       splitting (0 = from the shape, 1 = never, up to 8)                       */
-    OLS_OPT_GEMM_FORCE_GENERAL = 14, /* 1: bf16 forward / delta GEMMs always take the bounds-checked kernel, also on
+    OLS_OPT_GEMM_FORCE_GENERAL = 14, /* 1: the GEMMs always take their bounds-checked kernel, also on
                                       shapes the full-tile kernel covers (both give identical bits); default 0     */
     OLS_OPT_ANCHOR_DELAY_US = 15,  /* emulated communication latency, 0 (default) .. 1000000 microseconds: a kernel
                                       that only waits that long runs ahead of every anchor refresh on the refresh's

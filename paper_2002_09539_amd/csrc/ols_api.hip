@@ -382,6 +382,7 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
             gw.upd_b_off = c->b_off[l];
         }
         gw.guest = (guest && l == L - 2) ? &ha : nullptr;
+        gw.force_general = c->gemm_force_general ? 1 : 0;
         gw.groups = m;
         gw.M = c->dims[l];
         gw.N = c->dims[l + 1];

@@ -145,7 +145,7 @@ struct GemmArgs {
     float* colsum;      // dw: optional [N] per group, receives the column sums of B (the bias gradient)
     float* partial;     // fp32 fwd with splits > 1: scratch of splits * groups * M * N floats
     int splits;         // fp32 fwd: number of K ranges contracted by separate workgroups (<= 1: none)
-    int force_general;  // bf16: use the bounds-checked kernel even where the full-tile kernel applies
+    int force_general;  // use the bounds-checked kernel even where the full-tile kernel applies
     const HeadArgs* guest;  // dw: the output layer's weight / bias gradients (launch_head_bwd's work) are computed by
                             // extra workgroups at the front of this launch; nullptr: none
     FusedUpdate upd;    // dw: when enabled, c is NOT written; the update of W (c's position in the replica row is

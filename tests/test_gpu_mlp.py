@@ -237,6 +237,27 @@ def test_library_driven_loop_equals_one_call_per_step(dtype):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("m,dims,batch", [(2, (3072, 512, 10), 128),          # configuration 2: split-K forward GEMM
+                                          (3, (1024, 256, 128, 10), 64),    # delta GEMM, single tile row
+                                          (2, (3072, 1024, 10), 64)])       # configuration 5
+def test_f32_full_tile_kernels_match_bounds_checked_kernels_bit_for_bit(m, dims, batch):
+    """Layer shapes that are whole numbers of tiles take the fp32 GEMM kernels without bounds checks (uniform base
+    plus fixed lane offsets); forcing the bounds-checked kernels on the same shapes must give identical bits."""
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 2, seed=1010)
+    states = []
+    for force in (0, 1):
+        with make_session(m, cfg.d, 2, 0.6, 0.05, 0.9) as s:
+            s.set_option(B.OLS_OPT_GEMM_FORCE_GENERAL, force)
+            s.attach_mlp(dims, batch, "f32")
+            Xd, yd = s.upload(X), s.upload(labels)
+            s.init_params(x0)
+            losses = []
+            s.run(5, lambda k: s.set_batch(Xd[:, k % 2], yd[:, k % 2]), losses=losses)
+            states.append((s.all_params(), s.params(-1), s.momentum(), np.array(losses)))
+    for a, b in zip(states[0], states[1]):
+        assert np.array_equal(a, b)
+
+
 def test_bf16_full_tile_kernel_matches_bounds_checked_kernel_bit_for_bit():
     """Configuration 3's layer shapes take the branch-free full-tile forward / delta kernels; forcing the
     bounds-checked kernel on the same shapes must give identical bits (same slices, same MFMA order)."""
