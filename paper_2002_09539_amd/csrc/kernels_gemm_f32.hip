@@ -273,22 +273,27 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
                 slice(kt & 1, ra, 0u, rb, 0u);
             }
         } else {
-            f4 ra0[TA::kPerThread], rb0[TB::kPerThread], ra1[TA::kPerThread], rb1[TB::kPerThread];
-            TA::load_full(ra0, base_a(0), offa);
-            TB::load_full(rb0, base_b(0), offb);
-            TA::load_full(ra1, base_a(1), offa);
-            TB::load_full(rb1, base_b(1), offb);
-            TA::store_full(lds_a(0), ra0);
-            TB::store_full(lds_b(0), rb0);
+            // A ring of DEPTH register sets: while slice t feeds the matrix cores from LDS, slices t + 1 .. t + DEPTH - 1
+            // wait in registers and slice t + DEPTH is requested into the set that slice t left.  (Four sets were
+            // measured no faster than two at the same bytes in flight, and slower at twice the bytes; so was a K order
+            // rotated per tile to spread concurrent workgroups over memory channels.)
+            f4 ra[DEPTH][TA::kPerThread], rb[DEPTH][TB::kPerThread];
+#pragma unroll
+            for (int j = 0; j < DEPTH; ++j) {
+                TA::load_full(ra[j], base_a(j), offa);
+                TB::load_full(rb[j], base_b(j), offb);
+            }
+            TA::store_full(lds_a(0), ra[0]);
+            TB::store_full(lds_b(0), rb[0]);
             __syncthreads();
             load_frags(0, 0, 0);
-            for (int kt = 0; kt < nk; kt += 2) {   // nk is even
-                TA::load_full(ra0, base_a(kt + 2), offa);
-                TB::load_full(rb0, base_b(kt + 2), offb);
-                slice(0, ra1, 0u, rb1, 0u);
-                TA::load_full(ra1, base_a(kt + 3), offa);
-                TB::load_full(rb1, base_b(kt + 3), offb);
-                slice(1, ra0, 0u, rb0, 0u);
+            for (int kt = 0; kt < nk; kt += DEPTH) {   // nk is a multiple of DEPTH
+#pragma unroll
+                for (int u = 0; u < DEPTH; ++u) {
+                    TA::load_full(ra[u], base_a(kt + u + DEPTH), offa);
+                    TB::load_full(rb[u], base_b(kt + u + DEPTH), offb);
+                    slice(u & 1, ra[(u + 1) % DEPTH], 0u, rb[(u + 1) % DEPTH], 0u);
+                }
             }
         }
     } else if (DEPTH == 1) {
