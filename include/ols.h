@@ -78,6 +78,13 @@ enum {
     OLS_OPT_GEMM_VARIANT_DA = 11,  /* an unknown variant makes the next local step fail with OLS_EHIP          */
     OLS_OPT_GEMM_SPLITK = 12,      /* fp32 forward GEMM: K ranges per output tile where the shape calls for
                                       splitting (0 = from the shape, 1 = never, up to 8)                       */
+    OLS_OPT_FUSE_GEMM_UPDATE = 13, /* 1 (default): with an attached MLP (or a least-squares model of at most 64 samples
+                                      per batch and 4096 parameters) the kernels that form the gradients apply
+                                      the local step (and on the tau-th step the pull-back) where each gradient
+                                      element is produced, so g is never written nor re-read and ols_sync_pull only
+                                      publishes the result; 0: gradients go to g and the streaming kernels update.
+                                      With an MLP both routes execute the same fp32 operation sequence per element
+                                      (identical bits); the one-launch least-squares kernel sums in another order. */
     OLS_OPT_GEMM_FORCE_GENERAL = 14, /* 1: the GEMMs always take their bounds-checked kernel, also on
                                       shapes the full-tile kernel covers (both give identical bits); default 0     */
     OLS_OPT_ANCHOR_DELAY_US = 15,  /* emulated communication latency, 0 (default) .. 1000000 microseconds: a kernel
@@ -87,17 +94,11 @@ enum {
                                       comparison with blocking synchronisation is OLS_OPT_SERIALIZE = 1 with the same
                                       delay).  Results do not depend on it.  Ignored where the anchor is produced by
                                       the pull pass itself (OLS_OPT_FUSE_MEAN, ols_set_mixing).                    */
-    OLS_OPT_HEAD_DW_GUEST = 16,    /* 1 (default): with an attached MLP that has a hidden layer, the output layer's
+    OLS_OPT_HEAD_DW_GUEST = 16     /* 1 (default): with an attached MLP that has a hidden layer, the output layer's
                                       weight / bias gradients (and their fused update) are computed by extra
                                       workgroups at the front of the launch of the last hidden layer's
                                       weight-gradient GEMM instead of a kernel of their own (OLS_K_HEAD_BWD then
                                       does not appear); same arithmetic, identical bits                          */
-    OLS_OPT_FUSE_GEMM_UPDATE = 13  /* 1 (default): with an attached MLP (or a least-squares model of at most 64 samples
-                                      per batch and 4096 parameters) the kernels that form the gradients apply
-                                      the local step (and on the tau-th step the pull-back) where each gradient
-                                      element is produced, so g is never written nor re-read and ols_sync_pull only
-                                      publishes the result; 0: gradients go to g and the streaming kernels update.
-                                      Both routes execute the same fp32 operation sequence per element.           */
 };
 
 /* kernel kinds for ols_kernel_stats / the launch trace */
