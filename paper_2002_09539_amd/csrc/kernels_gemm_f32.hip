@@ -46,6 +46,7 @@ struct GemmDev {
     int M, N, K, lda, ldb, ldc;
     int tiles_m, tiles_n, total_tiles, chunk;
     int splits, k_chunk, groups;
+    int wgs_per_xcd;     // persistent weight-gradient kernel: workgroups per XCD (each walks several tiles)
     HeadDwDev guest;     // DW: output-layer gradients computed by the first guest.blocks workgroups (0: none)
 };
 
@@ -381,6 +382,218 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmDev p) {
     }
 }
 
+// Weight gradient with the fused update as a persistent, software-pipelined kernel.
+//
+// In gemm_f32_kernel a workgroup first contracts (matrix cores busy, HBM idle), then streams the state of its
+// tile (HBM busy, matrix cores idle); whether the two phases of different workgroups overlap is left to chance.
+// Here a workgroup walks over several 64 x 64 tiles, and the update of tile t - 1 is spread over the K loop of
+// tile t: the gradient tile waits transposed in its own LDS region, and every quarter of the K loop ("group")
+// consumes one 16-byte vector per lane of it -- whose parameters and momenta were requested two groups earlier --
+// and requests another.  Every wavefront therefore issues MFMAs and state traffic all the time.  The operand
+// ring runs across tile boundaries as well, so the first slices of the next tile are on their way while the
+// last ones of this tile feed the matrix cores.
+//   group g of tile t:   consume vector g of tile t - 1;   request vector g + 2 of tile t - 1 (g < 2)
+//                                                          or vector g - 2 of tile t     (g >= 2)
+// Two register sets of state vectors alternate.  K = 64 SPG (SPG slices of 16 per group); full tiles only;
+// same MFMA order and same update arithmetic as gemm_f32_kernel + dw_epilogue_staged, so identical bits.
+struct DwTile {
+    int group, tm, m0, n0;
+    int64_t upd_base;   // group * ld + w_off + m0 * N + n0: element (m0, n0) of this worker's weight matrix
+    int64_t col_base;   // w_off + m0 * N + n0: the same inside a replica row (anchor)
+};
+
+#ifndef OLS_DWP_WAVES
+#define OLS_DWP_WAVES 4
+#endif
+template <int SPG, bool PULL>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(OLS_DWP_WAVES)))
+void gemm_f32_dw_pipelined_kernel(GemmDev p) {
+    constexpr int BM = 64, BN = 64, BK = 16, NK = 4 * SPG, kVecs = 4;   // vectors per lane of a 64 x 64 tile
+    using TA = Tile<BM, BK, false>;   // A[K][M]
+    using TB = Tile<BN, BK, false>;   // B[K][N]
+    static_assert(TA::kPerThread == 1 && TB::kPerThread == 1, "one 16-byte vector per lane and operand slice");
+    constexpr int kOperand = 2 * TA::kFloats + 2 * TB::kFloats;
+    constexpr int kPitch = BN + 4;
+    __shared__ __attribute__((aligned(16))) float lds_all[kOperand + BM * kPitch];
+    float* stage = lds_all + kOperand;
+    auto lds_a = [&](int buf) { return lds_all + buf * TA::kFloats; };
+    auto lds_b = [&](int buf) { return lds_all + 2 * TA::kFloats + buf * TB::kFloats; };
+
+    int bid = blockIdx.x;
+    if (bid < p.guest.blocks) {
+        head_dw_guest<kOperand + BM * kPitch>(p.guest, lds_all, bid);
+        return;
+    }
+    bid -= p.guest.blocks;
+    // workgroup `slot` of XCD `xcd` walks tiles xcd * chunk + slot, + k_chunk (workgroups per XCD), ...
+    const int xcd = bid % kXcds, slot = bid / kXcds, stride = p.wgs_per_xcd;
+    const int tile_end = min((xcd + 1) * p.chunk, p.total_tiles);
+    int tile = xcd * p.chunk + slot;
+    if (tile >= tile_end) return;
+    const int per_group = p.tiles_m * p.tiles_n;
+    const FusedUpdate& u = p.upd;
+    const bool mom = u.mu != 0.0f;
+
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, lane32 = lane % 32, half = lane / 32;
+    const int wm0 = (wave / 2) * 32, wn0 = (wave % 2) * 32;
+
+    auto decode = [&](int t) {
+        DwTile d;
+        d.group = t / per_group;
+        d.tm = (t % per_group) / p.tiles_n;
+        d.m0 = d.tm * BM;
+        d.n0 = (t % p.tiles_n) * BN;
+        d.col_base = p.upd_w_off + (int64_t)d.m0 * p.N + d.n0;
+        d.upd_base = (int64_t)d.group * u.ld + d.col_base;
+        return d;
+    };
+    // operand slice s of tile d: uniform base pointers; the lane's 16-byte vector sits at a fixed offset
+    unsigned offa[1], offb[1];
+    TA::lane_offsets(offa, p.lda);
+    TB::lane_offsets(offb, p.ldb);
+    auto load_slice = [&](f4 (&ra)[1], f4 (&rb)[1], const DwTile& d, int sl) {
+        const char* a = (const char*)(p.a + (int64_t)d.group * p.sa + (int64_t)(sl * BK) * p.lda + d.m0);
+        const char* b = (const char*)(p.b + (int64_t)d.group * p.sb + (int64_t)(sl * BK) * p.ldb + d.n0);
+        TA::load_full(ra, a, offa);
+        TB::load_full(rb, b, offb);
+    };
+
+    // state vector v of a tile: row v * 16 + tid / 16, columns 4 (tid % 16) .. + 3 of the tile; addresses are a
+    // uniform base per tile plus a 32-bit byte offset per lane
+    const int my_row = threadIdx.x / 16, my_c4 = threadIdx.x % 16;
+    const unsigned my_off = 4u * (unsigned)(my_row * p.N + 4 * my_c4);   // byte offset of vector 0 inside the tile
+    const unsigned vec_step = 64u * (unsigned)p.N;                        // bytes between consecutive vectors of a lane
+    const float* my_stage = stage + my_row * kPitch + 4 * my_c4;
+    f4 sx[2], sb[2], sz[PULL ? 2 : 1];
+    auto issue = [&](int set, const DwTile& d, int v) {
+        const unsigned o = my_off + (unsigned)v * vec_step;
+        sx[set] = ep_load_stream((const ep_f4*)((const char*)(u.x_in + d.upd_base) + o));
+        if (mom) sb[set] = ep_load_stream((const ep_f4*)((const char*)(u.buf + d.upd_base) + o));
+        if (PULL) sz[PULL ? set : 0] = *(const ep_f4*)((const char*)(u.z + d.col_base) + o);
+    };
+    auto consume = [&](int set, const DwTile& d, int v) {
+        const f4 gv = *(const f4*)(my_stage + v * 16 * kPitch);
+        const unsigned o = my_off + (unsigned)v * vec_step;
+        f4 xn, bn;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {   // the operation sequence of dw_consume
+            float xh;
+            if (mom) {
+                bn[e] = __fmaf_rn(u.mu, sb[set][e], gv[e]);
+                const float dir = u.nesterov ? __fmaf_rn(u.mu, bn[e], gv[e]) : bn[e];
+                xh = __fmaf_rn(-u.gamma, dir, sx[set][e]);
+            } else {
+                xh = __fmaf_rn(-u.gamma, gv[e], sx[set][e]);
+            }
+            if (PULL) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, sz[PULL ? set : 0][e]), xh);
+            xn[e] = xh;
+        }
+        ep_store_stream((ep_f4*)((char*)(u.x_out + d.upd_base) + o), xn);
+        if (mom) ep_store_stream((ep_f4*)((char*)(u.buf + d.upd_base) + o), bn);
+        if (u.shadow) {
+            ep_u2 pk;
+            pk.x = ep_bf16(xn[0]) | (ep_bf16(xn[1]) << 16);
+            pk.y = ep_bf16(xn[2]) | (ep_bf16(xn[3]) << 16);
+            *(ep_u2*)((char*)(u.shadow + d.upd_base) + o / 2) = pk;
+        }
+    };
+
+    f16v acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    f4 fa[2], fb[2];
+    auto load_frags = [&](int buf, int cur, int q) {
+        fa[buf] = TA::frag(lds_a(cur), wm0, q, lane32, half);
+        fb[buf] = TB::frag(lds_b(cur), wn0, q, lane32, half);
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[buf][e], fb[buf][e], acc, 0, 0, 0);
+    };
+
+    DwTile cur = decode(tile), prev = cur;
+    bool have_prev = false;
+    f4 ra[2][1], rb[2][1];
+    load_slice(ra[0], rb[0], cur, 0);
+    load_slice(ra[1], rb[1], cur, 1);
+    TA::store_full(lds_a(0), ra[0]);
+    TB::store_full(lds_b(0), rb[0]);
+    __syncthreads();
+    load_frags(0, 0, 0);
+
+    while (true) {
+        const int next_tile = tile + stride;
+        const bool has_next = next_tile < tile_end;
+        const DwTile nxt = decode(has_next ? next_tile : tile);
+        const bool col_sums = p.colsum != nullptr && cur.tm == 0 && threadIdx.x < BN;
+        float col_acc = 0.0f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if (have_prev) consume(g & 1, prev, g);
+            if (g < 2) {
+                if (have_prev) issue(g & 1, prev, g + 2);
+            } else {
+                issue(g & 1, cur, g - 2);
+            }
+#pragma unroll
+            for (int ss = 0; ss < SPG; ++ss) {
+                constexpr int kDummy = 0;
+                (void)kDummy;
+                const int s = g * SPG + ss;          // static after unrolling
+                const int lb = s & 1;                // LDS buffer holding slice s; its register set is free again
+                // operand slice two jobs ahead: this tile's, the next tile's, or (at the very end) a dummy re-read
+                if (s + 2 < NK) load_slice(ra[lb], rb[lb], cur, s + 2);
+                else load_slice(ra[lb], rb[lb], has_next ? nxt : cur, has_next ? s + 2 - NK : NK - 1);
+                load_frags(1, lb, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfmas(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (col_sums) {
+#pragma unroll
+                    for (int k = 0; k < BK; ++k) col_acc += lds_b(lb)[k * TB::kPitch + threadIdx.x];
+                }
+                TA::store_full(lds_a(lb ^ 1), ra[lb ^ 1]);   // the next job (possibly slice 0 of the next tile)
+                TB::store_full(lds_b(lb ^ 1), rb[lb ^ 1]);
+                __syncthreads();
+                if (s + 1 < NK) {
+                    load_frags(0, lb ^ 1, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfmas(1);
+                    __builtin_amdgcn_sched_barrier(0);
+                } else {
+                    mfmas(1);   // the tile's last MFMAs: the accumulators are complete after them
+                }
+            }
+        }
+        // bias gradient of the tiles of the first tile row: the column sums just formed, updated on the spot
+        if (col_sums) {
+            const int64_t col = p.upd_b_off + cur.n0 + threadIdx.x, idx = (int64_t)cur.group * u.ld + col;
+            fused_update_apply(u, idx, col, col_acc, u.x_in[idx], mom ? u.buf[idx] : 0.0f);
+        }
+        // Every lane has read its last vector of the previous gradient tile (group 3, at least one barrier ago):
+        // the stage takes this tile's gradient, transposed so that lanes own 16-byte vectors of rows.
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            stage[(wm0 + 8 * (r / 4) + 4 * half + (r % 4)) * kPitch + wn0 + lane32] = acc[r];
+            acc[r] = 0.0f;
+        }
+        __syncthreads();
+        prev = cur;
+        have_prev = true;
+        if (!has_next) break;
+        tile = next_tile;
+        cur = nxt;
+        load_frags(0, 0, 0);   // slice 0 of the new tile was published to LDS buffer 0 by the last job above
+    }
+    // drain: the last tile's update (vectors 0 and 1 were requested during its last two groups)
+    consume(0, prev, 0);
+    issue(0, prev, 2);
+    consume(1, prev, 1);
+    issue(1, prev, 3);
+    consume(0, prev, 2);
+    consume(1, prev, 3);
+}
+
 // out[g][row][col] = relu(sum_s partial[s][g][row][col] + bias[g][col]); one lane per 4 columns
 __global__ __launch_bounds__(kThreads) void splitk_finish_kernel(const f4* __restrict__ partial, int splits,
                                                                  const float* __restrict__ bias, int64_t sbias,
@@ -477,6 +690,58 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
+#ifndef OLS_DWP_WGS_PER_CU
+#define OLS_DWP_WGS_PER_CU 4
+#endif
+// shapes the persistent pipelined weight-gradient kernel covers: fused update, full 64 x 64 tiles, K = 64, 128 or 256
+static bool dw_pipelined_fits(const GemmArgs& g) {
+    if (!g.upd.enabled || g.M % 64 || g.N % 64 || (g.K != 64 && g.K != 128 && g.K != 256)) return false;
+    if (g.lda % 4 || g.ldb % 4 || g.sa % 4 || g.sb % 4 || g.ldc != g.N || g.lda >= (1 << 22) || g.ldb >= (1 << 22)) return false;
+    if ((int64_t)g.M * g.N >= ((int64_t)1 << 30)) return false;   // 32-bit element offsets inside a weight matrix
+    if (!aligned16(g.a) || !aligned16(g.b) || !aligned16(g.upd.x_in) || !aligned16(g.upd.x_out) || !aligned16(g.upd.buf) ||
+        !aligned16(g.upd.z) || !aligned16(g.upd.shadow) || g.upd_w_off % 4 || g.upd.ld % 4)
+        return false;
+    return true;
+}
+static hipError_t dw_pipelined_launch(const GemmArgs& g, hipStream_t s) {
+    if (!g.a || !g.b || g.groups < 1 || !dw_pipelined_fits(g)) return hipErrorInvalidValue;
+    if (!g.upd.x_in || !g.upd.x_out || (g.upd.mu != 0.0f && !g.upd.buf) || (g.upd.pull && !g.upd.z) || !g.colsum)
+        return hipErrorInvalidValue;
+    if (g.lda < g.M || g.ldb < g.N) return hipErrorInvalidValue;
+    GemmDev p = {};
+    if (g.guest) {
+        hipError_t ge = head_dw_prepare(*g.guest, &p.guest);
+        if (ge != hipSuccess) return ge;
+    }
+    p.a = (const float*)g.a;
+    p.b = (const float*)g.b;
+    p.colsum = g.colsum;
+    p.upd = g.upd;
+    p.upd_w_off = g.upd_w_off;
+    p.upd_b_off = g.upd_b_off;
+    p.sa = g.sa; p.sb = g.sb; p.scolsum = g.scolsum;
+    p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
+    p.tiles_m = g.M / 64;
+    p.tiles_n = g.N / 64;
+    p.groups = g.groups;
+    const int64_t total = (int64_t)g.groups * p.tiles_m * p.tiles_n;
+    if (total > (1 << 30)) return hipErrorInvalidValue;
+    p.total_tiles = (int)total;
+    p.chunk = (int)((total + kXcds - 1) / kXcds);
+    p.wgs_per_xcd = p.chunk < 32 * OLS_DWP_WGS_PER_CU ? p.chunk : 32 * OLS_DWP_WGS_PER_CU;   // 32 compute units per XCD
+    const unsigned grid = (unsigned)(p.guest.blocks + p.wgs_per_xcd * kXcds);
+#define OLS_DWP(SPG)                                                                                   \
+    do {                                                                                               \
+        if (g.upd.pull) gemm_f32_dw_pipelined_kernel<SPG, true><<<grid, kThreads, 0, s>>>(p);          \
+        else gemm_f32_dw_pipelined_kernel<SPG, false><<<grid, kThreads, 0, s>>>(p);                    \
+    } while (0)
+    if (g.K == 64) OLS_DWP(1);
+    else if (g.K == 128) OLS_DWP(2);
+    else OLS_DWP(4);
+#undef OLS_DWP
+    return hipGetLastError();
+}
+
 // Tile shapes.  Variant 0 is the default (for the forward GEMM: chosen from the shape); the others exist so
 // that the choice can be re-measured
 // (OLS_OPT_GEMM_VARIANT_*).  LDS per workgroup stays below 80 KiB so two workgroups fit a compute unit.
@@ -518,7 +783,11 @@ hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant) {
         // smaller tiles (more workgroups whose compute and epilogue phases interleave) win; with the small
         // tiles a second K slice of global loads in flight costs one register and gains 3 % (configuration 2:
         // 103.3 -> 100.3 us).
-        if (!g.upd.enabled) variant = 1;
+        // The persistent kernel that spreads a tile's update over the next tile's K loop wins where a tile has
+        // enough K slices to hide the state's latency behind (K = 128, configuration 2: 0.1853 -> 0.1826 ms per
+        // step); with K = 64 (configuration 5) it loses (665 us against 585 us per launch).
+        if (g.upd.enabled && g.K == 128 && dw_pipelined_fits(g)) variant = 16;
+        else if (!g.upd.enabled) variant = 1;
         else variant = (int64_t)g.groups * ((g.M + 127) / 128) * ((g.N + 127) / 128) < 4096 ? 11 : 8;
     }
     switch (variant) {
@@ -534,6 +803,7 @@ hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant) {
         case 10: return gemm_launch<kDw, 128, 64, 16, 2, 2, 1>(g, s);
         case 11: return gemm_launch<kDw, 64, 64, 16, 2, 2, 2>(g, s);
         case 12: return gemm_launch<kDw, 64, 128, 16, 2, 2, 2>(g, s);
+        case 16: return dw_pipelined_launch(g, s);
         default: return hipErrorInvalidValue;
     }
 }

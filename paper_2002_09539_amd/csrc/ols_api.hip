@@ -930,7 +930,7 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
         case OLS_OPT_GEMM_VARIANT_FWD:
         case OLS_OPT_GEMM_VARIANT_DW:
         case OLS_OPT_GEMM_VARIANT_DA:
-            if (value < 0 || value > 15) return fail(OLS_EINVAL, "GEMM variant out of range");
+            if (value < 0 || value > 31) return fail(OLS_EINVAL, "GEMM variant out of range");
             c->gemm_variant[key - OLS_OPT_GEMM_VARIANT_FWD] = (int)value;
             break;
         case OLS_OPT_FUSE_GEMM_UPDATE:

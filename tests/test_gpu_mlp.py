@@ -258,6 +258,29 @@ def test_f32_full_tile_kernels_match_bounds_checked_kernels_bit_for_bit(m, dims,
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("m,dims,batch,tau", [(2, (3072, 512, 10), 128, 2),      # configuration 2: K = 128
+                                              (3, (256, 192, 128, 10), 64, 3),   # K = 64, two hidden layers
+                                              (2, (128, 64, 10), 256, 1),        # K = 256, one tile per worker
+                                              (5, (1024, 1024, 10), 64, 2)])     # more tiles than workgroups walk at once
+def test_pipelined_weight_gradient_kernel_is_bit_identical(m, dims, batch, tau):
+    """The persistent weight-gradient kernel that spreads the update of one tile over the K loop of the next must
+    leave exactly the state of the kernel that contracts and updates tile by tile (same MFMA order, same update
+    arithmetic)."""
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 2, seed=1111)
+    states = []
+    for variant in (16, 11):
+        with make_session(m, cfg.d, tau, 0.6, 0.05, 0.9) as s:
+            s.set_option(B.OLS_OPT_GEMM_VARIANT_DW, variant)
+            s.attach_mlp(dims, batch, "f32")
+            Xd, yd = s.upload(X), s.upload(labels)
+            s.init_params(x0)
+            losses = []
+            s.run(2 * tau + 1, lambda k: s.set_batch(Xd[:, k % 2], yd[:, k % 2]), losses=losses)
+            states.append((s.all_params(), s.params(-1), s.momentum(), np.array(losses)))
+    for a, b in zip(states[0], states[1]):
+        assert np.array_equal(a, b)
+
+
 def test_bf16_full_tile_kernel_matches_bounds_checked_kernel_bit_for_bit():
     """Configuration 3's layer shapes take the branch-free full-tile forward / delta kernels; forcing the
     bounds-checked kernel on the same shapes must give identical bits (same slices, same MFMA order)."""
