@@ -405,10 +405,29 @@ struct DwTile {
 #ifndef OLS_DWP_WAVES
 #define OLS_DWP_WAVES 4
 #endif
-template <int SPG, bool PULL>
+template <bool V>
+struct DwFlag {
+    static constexpr bool value = V;
+};
+// The hardware counts a wavefront's outstanding vector-memory operations in issue order: waiting for an operand
+// slice also waits for every state load and store issued before that slice was requested.  The number of memory
+// operations between a request and its wait must therefore not depend on run-time branches (the compiler assumes
+// the shortest path and would wait for operations that are still young on the longer one): momentum and pull-back
+// are template parameters, and the first tile of a workgroup, which has no predecessor to update, is its own copy
+// of the loop body.  Measured on 16 x (3072 x 512, K = 128): 101.6 -> 99.8 us per launch.  Measured without gain
+// on top of that: four operand register sets (state traffic gets three slices of time before an operand wait
+// reaches it; 98.8 us at three wavefronts per SIMD), four state register sets (a whole tile of state in flight,
+// requested during the tile's own K loop; 100.6 us) and a state layout in which a tile's 4096 elements are
+// contiguous (100.8 us).  Knock-out builds (wrong values on purpose, same memory touched) split the 100 us: state
+// traffic alone 77 us (5.6 TB/s), + the operand loads 94 us (393 MB of L2 hits cost 17 us, half of them 9 us),
+// + the MFMAs 100 us; operands + MFMAs without the state traffic take 61 us.  The three parts add up rather than
+// overlap: L2 hits and HBM streams pass through the same L2 channels, and the matrix work hides all but 6 us.
+template <int SPG, bool PULL, bool MOM>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(OLS_DWP_WAVES)))
 void gemm_f32_dw_pipelined_kernel(GemmDev p) {
-    constexpr int BM = 64, BN = 64, BK = 16, NK = 4 * SPG, kVecs = 4;   // vectors per lane of a 64 x 64 tile
+    constexpr int RING = 2;   // register sets of the operand ring
+    constexpr int BM = 64, BN = 64, BK = 16, NK = 4 * SPG;   // four 16-byte vectors per lane of a 64 x 64 tile
+    static_assert(NK % RING == 0 && RING % 2 == 0, "register set and LDS buffer of a slice are static");
     using TA = Tile<BM, BK, false>;   // A[K][M]
     using TB = Tile<BN, BK, false>;   // B[K][N]
     static_assert(TA::kPerThread == 1 && TB::kPerThread == 1, "one 16-byte vector per lane and operand slice");
@@ -432,7 +451,6 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
     if (tile >= tile_end) return;
     const int per_group = p.tiles_m * p.tiles_n;
     const FusedUpdate& u = p.upd;
-    const bool mom = u.mu != 0.0f;
 
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, lane32 = lane % 32, half = lane / 32;
     const int wm0 = (wave / 2) * 32, wn0 = (wave % 2) * 32;
@@ -464,11 +482,11 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
     const unsigned my_off = 4u * (unsigned)(my_row * p.N + 4 * my_c4);   // byte offset of vector 0 inside the tile
     const unsigned vec_step = 64u * (unsigned)p.N;                        // bytes between consecutive vectors of a lane
     const float* my_stage = stage + my_row * kPitch + 4 * my_c4;
-    f4 sx[2], sb[2], sz[PULL ? 2 : 1];
+    f4 sx[2], sb[MOM ? 2 : 1], sz[PULL ? 2 : 1];
     auto issue = [&](int set, const DwTile& d, int v) {
         const unsigned o = my_off + (unsigned)v * vec_step;
         sx[set] = ep_load_stream((const ep_f4*)((const char*)(u.x_in + d.upd_base) + o));
-        if (mom) sb[set] = ep_load_stream((const ep_f4*)((const char*)(u.buf + d.upd_base) + o));
+        if (MOM) sb[MOM ? set : 0] = ep_load_stream((const ep_f4*)((const char*)(u.buf + d.upd_base) + o));
         if (PULL) sz[PULL ? set : 0] = *(const ep_f4*)((const char*)(u.z + d.col_base) + o);
     };
     auto consume = [&](int set, const DwTile& d, int v) {
@@ -478,8 +496,8 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {   // the operation sequence of dw_consume
             float xh;
-            if (mom) {
-                bn[e] = __fmaf_rn(u.mu, sb[set][e], gv[e]);
+            if (MOM) {
+                bn[e] = __fmaf_rn(u.mu, sb[MOM ? set : 0][e], gv[e]);
                 const float dir = u.nesterov ? __fmaf_rn(u.mu, bn[e], gv[e]) : bn[e];
                 xh = __fmaf_rn(-u.gamma, dir, sx[set][e]);
             } else {
@@ -489,13 +507,7 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
             xn[e] = xh;
         }
         ep_store_stream((ep_f4*)((char*)(u.x_out + d.upd_base) + o), xn);
-        if (mom) ep_store_stream((ep_f4*)((char*)(u.buf + d.upd_base) + o), bn);
-        if (u.shadow) {
-            ep_u2 pk;
-            pk.x = ep_bf16(xn[0]) | (ep_bf16(xn[1]) << 16);
-            pk.y = ep_bf16(xn[2]) | (ep_bf16(xn[3]) << 16);
-            *(ep_u2*)((char*)(u.shadow + d.upd_base) + o / 2) = pk;
-        }
+        if (MOM) ep_store_stream((ep_f4*)((char*)(u.buf + d.upd_base) + o), bn);
     };
 
     f16v acc;
@@ -512,16 +524,18 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
     };
 
     DwTile cur = decode(tile), prev = cur;
-    bool have_prev = false;
-    f4 ra[2][1], rb[2][1];
-    load_slice(ra[0], rb[0], cur, 0);
-    load_slice(ra[1], rb[1], cur, 1);
+    f4 ra[RING][1], rb[RING][1];
+#pragma unroll
+    for (int j = 0; j < RING; ++j) load_slice(ra[j], rb[j], cur, j);
     TA::store_full(lds_a(0), ra[0]);
     TB::store_full(lds_b(0), rb[0]);
     __syncthreads();
     load_frags(0, 0, 0);
 
-    while (true) {
+    // one tile: its K loop with the update of the previous tile (if there is one) spread over it; returns whether
+    // the workgroup has another tile, in which case `cur` is that tile and its slice 0 is in LDS buffer 0
+    auto run_tile = [&](auto have_prev_flag) -> bool {
+        constexpr bool kHavePrev = decltype(have_prev_flag)::value;
         const int next_tile = tile + stride;
         const bool has_next = next_tile < tile_end;
         const DwTile nxt = decode(has_next ? next_tile : tile);
@@ -529,21 +543,20 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
         float col_acc = 0.0f;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            if (have_prev) consume(g & 1, prev, g);
+            if (kHavePrev) consume(g & 1, prev, g);
             if (g < 2) {
-                if (have_prev) issue(g & 1, prev, g + 2);
+                if (kHavePrev) issue(g & 1, prev, g + 2);
             } else {
                 issue(g & 1, cur, g - 2);
             }
 #pragma unroll
             for (int ss = 0; ss < SPG; ++ss) {
-                constexpr int kDummy = 0;
-                (void)kDummy;
                 const int s = g * SPG + ss;          // static after unrolling
-                const int lb = s & 1;                // LDS buffer holding slice s; its register set is free again
-                // operand slice two jobs ahead: this tile's, the next tile's, or (at the very end) a dummy re-read
-                if (s + 2 < NK) load_slice(ra[lb], rb[lb], cur, s + 2);
-                else load_slice(ra[lb], rb[lb], has_next ? nxt : cur, has_next ? s + 2 - NK : NK - 1);
+                const int lb = s & 1;                // LDS buffer holding slice s
+                const int rs = s % RING;             // its register set is free again
+                // operand slice RING jobs ahead: this tile's, the next tile's, or (at the very end) a dummy re-read
+                if (s + RING < NK) load_slice(ra[rs], rb[rs], cur, s + RING);
+                else load_slice(ra[rs], rb[rs], has_next ? nxt : cur, has_next ? s + RING - NK : NK - 1);
                 load_frags(1, lb, 1);
                 __builtin_amdgcn_sched_barrier(0);
                 mfmas(0);
@@ -552,8 +565,8 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
 #pragma unroll
                     for (int k = 0; k < BK; ++k) col_acc += lds_b(lb)[k * TB::kPitch + threadIdx.x];
                 }
-                TA::store_full(lds_a(lb ^ 1), ra[lb ^ 1]);   // the next job (possibly slice 0 of the next tile)
-                TB::store_full(lds_b(lb ^ 1), rb[lb ^ 1]);
+                TA::store_full(lds_a(lb ^ 1), ra[(s + 1) % RING]);   // the next job (possibly slice 0 of the next tile)
+                TB::store_full(lds_b(lb ^ 1), rb[(s + 1) % RING]);
                 __syncthreads();
                 if (s + 1 < NK) {
                     load_frags(0, lb ^ 1, 0);
@@ -568,7 +581,7 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
         // bias gradient of the tiles of the first tile row: the column sums just formed, updated on the spot
         if (col_sums) {
             const int64_t col = p.upd_b_off + cur.n0 + threadIdx.x, idx = (int64_t)cur.group * u.ld + col;
-            fused_update_apply(u, idx, col, col_acc, u.x_in[idx], mom ? u.buf[idx] : 0.0f);
+            fused_update_apply(u, idx, col, col_acc, u.x_in[idx], MOM ? u.buf[idx] : 0.0f);
         }
         // Every lane has read its last vector of the previous gradient tile (group 3, at least one barrier ago):
         // the stage takes this tile's gradient, transposed so that lanes own 16-byte vectors of rows.
@@ -579,12 +592,14 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
         }
         __syncthreads();
         prev = cur;
-        have_prev = true;
-        if (!has_next) break;
+        if (!has_next) return false;
         tile = next_tile;
         cur = nxt;
         load_frags(0, 0, 0);   // slice 0 of the new tile was published to LDS buffer 0 by the last job above
-    }
+        return true;
+    };
+    bool more = run_tile(DwFlag<false>{});
+    while (more) more = run_tile(DwFlag<true>{});
     // drain: the last tile's update (vectors 0 and 1 were requested during its last two groups)
     consume(0, prev, 0);
     issue(0, prev, 2);
@@ -699,7 +714,7 @@ static bool dw_pipelined_fits(const GemmArgs& g) {
     if (g.lda % 4 || g.ldb % 4 || g.sa % 4 || g.sb % 4 || g.ldc != g.N || g.lda >= (1 << 22) || g.ldb >= (1 << 22)) return false;
     if ((int64_t)g.M * g.N >= ((int64_t)1 << 30)) return false;   // 32-bit element offsets inside a weight matrix
     if (!aligned16(g.a) || !aligned16(g.b) || !aligned16(g.upd.x_in) || !aligned16(g.upd.x_out) || !aligned16(g.upd.buf) ||
-        !aligned16(g.upd.z) || !aligned16(g.upd.shadow) || g.upd_w_off % 4 || g.upd.ld % 4)
+        !aligned16(g.upd.z) || g.upd.shadow || g.upd_w_off % 4 || g.upd.ld % 4)   // fp32 GEMMs keep no bf16 copy
         return false;
     return true;
 }
@@ -730,14 +745,19 @@ static hipError_t dw_pipelined_launch(const GemmArgs& g, hipStream_t s) {
     p.chunk = (int)((total + kXcds - 1) / kXcds);
     p.wgs_per_xcd = p.chunk < 32 * OLS_DWP_WGS_PER_CU ? p.chunk : 32 * OLS_DWP_WGS_PER_CU;   // 32 compute units per XCD
     const unsigned grid = (unsigned)(p.guest.blocks + p.wgs_per_xcd * kXcds);
-#define OLS_DWP(SPG)                                                                                   \
-    do {                                                                                               \
-        if (g.upd.pull) gemm_f32_dw_pipelined_kernel<SPG, true><<<grid, kThreads, 0, s>>>(p);          \
-        else gemm_f32_dw_pipelined_kernel<SPG, false><<<grid, kThreads, 0, s>>>(p);                    \
+#define OLS_DWP2(SPG, PULL, MOM) gemm_f32_dw_pipelined_kernel<SPG, PULL, MOM><<<grid, kThreads, 0, s>>>(p)
+#define OLS_DWP(SPG)                                                      \
+    do {                                                                  \
+        const bool mom = g.upd.mu != 0.0f;                                \
+        if (g.upd.pull && mom) OLS_DWP2(SPG, true, true);                 \
+        else if (g.upd.pull) OLS_DWP2(SPG, true, false);                  \
+        else if (mom) OLS_DWP2(SPG, false, true);                         \
+        else OLS_DWP2(SPG, false, false);                                 \
     } while (0)
     if (g.K == 64) OLS_DWP(1);
     else if (g.K == 128) OLS_DWP(2);
     else OLS_DWP(4);
+#undef OLS_DWP2
 #undef OLS_DWP
     return hipGetLastError();
 }
