@@ -28,6 +28,9 @@ step direction g + mu buf), heavy-ball as an option, buffer initially zero and
 untouched by the pull-back; mini-batch losses are means over the batch; the
 ReLU derivative at 0 is 0; the anchor averages the post-pull models.
 
+The stale-average synchronisation of "Related Works" (`stale_average_sync`,
+`run_stale_average`) is pinned by tests/test_oracle_stale_average_pins.py.
+
 Pinned by tests/test_oracle_pins.py (closed forms on quadratics, the mixing
 matrix identities and virtual-sequence recursion of Appendix A, degenerate
 cases alpha in {0,1}, tau = 1, m = 1, finite differences, and CPU library
@@ -278,6 +281,44 @@ def run_general_mixing(x0, m, tau, gamma, K, grad_fn, W, mu=0.0, nesterov=True, 
             x[...] = Xn[:, :m].T.astype(store)
             z[...] = Xn[:, m].astype(store)
     return dict(x=x, buf=buf, z=z, v=None, losses=losses)
+
+
+def stale_average_sync(x, snap, z):
+    """The synchronisation of the stale-average alternative described in "Related Works" (the local
+    updates of the last tau iterations are applied to the average of the models as they stood tau
+    iterations before): x^(i) <- z + (x^(i) - s^(i)), where s^(i) is worker i's model right after the
+    previous synchronisation and z the average of those.  Returns the new models (double)."""
+    x = np.asarray(x, F64)
+    snap = np.asarray(snap, F64)
+    return np.asarray(z, F64)[None, :] + (x - snap)
+
+
+def run_stale_average(x0, m, tau, gamma, K, grad_fn, mu=0.0, nesterov=True, store=np.float32):
+    """K iterations of local SGD whose synchronisation is `stale_average_sync`: local steps as in `run`,
+    and after every tau-th one each model becomes (average of the previous synchronisation's models) +
+    (its own progress since then); the new models are then remembered and averaged for the next
+    synchronisation.  Initially every model and the average equal x0.  Returns the dict of `run`
+    plus snap [m][d]; z is the average of the models after the last synchronisation."""
+    x0 = np.asarray(x0)
+    d = x0.shape[0]
+    x = np.repeat(x0.astype(store)[None, :], m, axis=0)
+    snap = x.copy()
+    z = x0.astype(store).copy()
+    buf = np.zeros((m, d), store) if mu != 0.0 else None
+    losses = np.zeros((K, m), F64)
+    for k in range(K):
+        for i in range(m):
+            loss, g = grad_fn(i, k, x[i])
+            losses[k, i] = loss
+            x_half, b_new = local_momentum_step(x[i], None if buf is None else buf[i], g, gamma, mu, nesterov)
+            if buf is not None:
+                buf[i] = b_new.astype(store)
+            x[i] = x_half.astype(store)
+        if (k + 1) % tau == 0:
+            x[...] = stale_average_sync(x, snap, z).astype(store)
+            snap[...] = x
+            z[...] = anchor_average(x).astype(store)
+    return dict(x=x, buf=buf, z=z, v=None, snap=snap, losses=losses)
 
 
 def run_matrix_form(x0, m, tau, alpha, gamma, K, grad_fn):
