@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed region run one plain element-wise copy kernel of this size (reads and "
                          "writes that many MiB): the known-size reference the HBM traffic counters are scaled by")
+    ap.add_argument("--sync-rule", choices=["paper", "stale-average"], default="paper",
+                    help="synchronisation rule: the paper's pull-back + anchor average, or the stale-average "
+                         "alternative of its related-work section (x <- z + (x - snapshot); the CPU baseline is then "
+                         "not run, it times the paper's rule)")
     ap.add_argument("--opt", action="append", default=[], help="KEY=VALUE library option (numeric key), repeatable")
     return ap.parse_args()
 
@@ -69,6 +73,7 @@ def algorithmic_work(cfg, ld, fused_update=True):
         "mean": ("hbm", (4 * m + 4) * ld),
         "step_pull_mean": ("hbm", er * (12 + mom) + 8 * ld),
         "mix": ("hbm", (8 * (m + 1) + shadow * m) * ld),     # every row of [x, z] read once and written once
+        "stale_sync": ("hbm", er * (16 + shadow) + 4 * ld),  # x and snapshot read and written, z read
     }
     if cfg.kind == "mlp":
         dims, B = cfg.dims, cfg.batch
@@ -173,7 +178,7 @@ def main():
     cfg = I.get(args.config)
     if args.fuse_mean is None:
         args.fuse_mean = 1 if (cfg.kind == "stream" and not args.serialize and args.mixing == "none"
-                               and not args.anchor_delay_us) else 0
+                               and not args.anchor_delay_us and args.sync_rule == "paper") else 0
     # Defaults: at least the configuration's own iteration count and about a second of timed work; the warm-up covers
     # every resident batch once and lets the clocks settle (with 8 warm-up steps configuration 2 measured 0.195 ms per
     # step over the next 200, with 200 warm-up steps 0.185 ms; longer runs stay at 0.185).
@@ -205,6 +210,8 @@ def main():
         else:                           # Local SGD's periodic averaging (first display of Section 2)
             Wm[:cfg.m, :] = 1.0 / cfg.m
         sess.set_mixing(Wm)
+    if args.sync_rule != "paper":
+        sess.set_stale_average()
 
     def region(steps):
         sess.sync()
@@ -266,7 +273,7 @@ def main():
                         "avg_launch_us": e["avg_us"], "algorithmic_per_launch": e["per_launch"]}
         kernels["_region_ms_with_event_timing"] = 1e3 * timed_elapsed
 
-    base = cpu_baseline(cfg, host_inputs, args.cpu_seconds) if args.cpu_seconds > 0 else None
+    base = cpu_baseline(cfg, host_inputs, args.cpu_seconds) if args.cpu_seconds > 0 and args.sync_rule == "paper" else None
     sess.close()
 
     out = {
@@ -283,7 +290,8 @@ def main():
         "dtype": cfg.gemm_dtype if cfg.kind == "mlp" else "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
-                   "dims": list(cfg.dims), "overlap": ("mixing-kernel:" + args.mixing) if args.mixing != "none" else
+                   "dims": list(cfg.dims), "sync_rule": args.sync_rule,
+                   "overlap": ("mixing-kernel:" + args.mixing) if args.mixing != "none" else
                    ("serialized" if args.serialize else ("fused-mean" if args.fuse_mean else "side-stream")),
                    "second_buffer": not args.no_second_buffer, "anchor_delay_us": args.anchor_delay_us,
                    "loop": "library" if resident is not None else "python",

@@ -120,7 +120,8 @@ enum {
     OLS_K_CAST = 14,      /* fp32 -> bf16 operand conversion            */
     OLS_K_DELAY = 15,     /* emulated communication latency (OLS_OPT_ANCHOR_DELAY_US) */
     OLS_K_LSQ_STEP = 16,  /* least squares, small problems: gradient and local step in one launch */
-    OLS_K_COUNT = 17
+    OLS_K_STALE_SYNC = 17, /* stale-average synchronisation (ols_set_stale_average) */
+    OLS_K_COUNT = 18
 };
 
 typedef struct ols_trace_entry {
@@ -184,6 +185,18 @@ OLS_API int ols_set_anchor_momentum(ols_handle h, float beta_z, float* v_dev);
  * m <= 128.  Not combinable with anchor momentum.  OLS_ESTATE in the middle of a synchronisation.
  * The matrix is not checked for column-stochasticity: that is the caller's modelling choice. */
 OLS_API int ols_set_mixing(ols_handle h, const float* w_dev);
+
+/* Stale-average synchronisation, the alternative way of decoupling communication from computation that
+ * "Related Works" describes: a round's local updates are applied to the average of the models as they
+ * stood tau iterations before.  snap_dev: [m][ld] fp32 device buffer, 256-byte aligned, caller-owned and
+ * valid until replaced; the call fills it with the current models (on the main stream).  While it is set,
+ * every tau-th local step is a plain local step, ols_sync_pull computes
+ *     x^(i) <- z + (x^(i) - snap^(i)),   snap^(i) <- the new x^(i)        (fp32, z + (x - snap) as written)
+ * in one pass on the main stream (z: the average of the snapshots, produced by the previous round's
+ * refresh), and ols_anchor_update_async averages the new models on the side stream, overlapped with the
+ * next round.  alpha is not used.  Legal only after ols_init_params and before the first local step (a
+ * later ols_init_params refills the buffer); NULL returns to the paper's rule.  Not combinable with general mixing or anchor momentum. */
+OLS_API int ols_set_stale_average(ols_handle h, float* snap_dev);
 
 /* Changes the learning rate gamma for subsequent local steps (Section 4 uses a schedule). */
 OLS_API int ols_set_lr(ols_handle h, float gamma);

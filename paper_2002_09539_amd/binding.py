@@ -16,7 +16,7 @@ OLS_OK, OLS_EINVAL, OLS_ESTATE, OLS_EHIP, OLS_ENOMEM = 0, -1, -2, -3, -4
  OLS_OPT_ANCHOR_DELAY_US, OLS_OPT_HEAD_DW_GUEST) = range(1, 17)
 (OLS_K_INIT, OLS_K_STEP, OLS_K_STEP_PULL, OLS_K_PULL, OLS_K_MEAN, OLS_K_STEP_PULL_MEAN, OLS_K_LSQ_RESID,
  OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_MIX,
- OLS_K_CAST, OLS_K_DELAY, OLS_K_LSQ_STEP, OLS_K_COUNT) = range(18)
+ OLS_K_CAST, OLS_K_DELAY, OLS_K_LSQ_STEP, OLS_K_STALE_SYNC, OLS_K_COUNT) = range(19)
 
 
 class ols_trace_entry(C.Structure):
@@ -40,6 +40,7 @@ _SIGNATURES = {
     "ols_init_params": (C.c_int, [_H, _P]),
     "ols_set_anchor_momentum": (C.c_int, [_H, C.c_float, _P]),
     "ols_set_mixing": (C.c_int, [_H, _P]),
+    "ols_set_stale_average": (C.c_int, [_H, _P]),
     "ols_set_lr": (C.c_int, [_H, C.c_float]),
     "ols_attach_lsq": (C.c_int, [_H, C.c_int]),
     "ols_attach_mlp": (C.c_int, [_H, C.c_int, C.POINTER(C.c_int), C.c_int, C.c_int]),
@@ -129,6 +130,10 @@ def ols_set_anchor_momentum(h, beta_z, v):
 
 def ols_set_mixing(h, w):
     _check(load().ols_set_mixing(h, w))
+
+
+def ols_set_stale_average(h, snap):
+    _check(load().ols_set_stale_average(h, snap))
 
 
 def ols_set_lr(h, gamma):

@@ -137,6 +137,38 @@ __global__ __launch_bounds__(kThreads) void pull_kernel(f4* x, const f4* __restr
     }
 }
 
+// Stale-average synchronisation ("Related Works": a round's local updates are applied to the average of the models
+// of tau iterations before): x <- z + (x - snap), snap <- the new x; z is the average of the old snapshots.
+template <bool SHADOW>
+__global__ __launch_bounds__(kThreads) void stale_sync_kernel(f4* x, f4* snap, const f4* __restrict__ z,
+                                                              u2* __restrict__ shadow, int64_t n4, int m) {
+    const int64_t spans = (n4 + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+    const int64_t row = (int64_t)(blockIdx.x / spans) * n4;
+    const int64_t c0 = (int64_t)(blockIdx.x % spans) * (kThreads * kUnroll) + threadIdx.x;
+    f4 vx[kUnroll], vs[kUnroll], vz[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t c = c0 + u * kThreads;
+        if (c < n4) {
+            vx[u] = ld_stream(x + row + c);
+            vs[u] = ld_stream(snap + row + c);
+            vz[u] = z[c];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        const int64_t c = c0 + u * kThreads;
+        if (c < n4) {
+            f4 xo;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xo[e] = __fadd_rn(vz[u][e], __fsub_rn(vx[u][e], vs[u][e]));
+            st_stream(x + row + c, xo);
+            st_stream(snap + row + c, xo);
+            if (SHADOW) shadow[row + c] = pack_bf16x4(xo);
+        }
+    }
+}
+
 // x rows, x_alt rows and z take x0 (zero beyond d); buf rows are cleared; grid.y = m + 1 (last = z).
 __global__ __launch_bounds__(kThreads) void init_kernel(float* x, float* x_alt, float* buf, float* z,
                                                         uint16_t* shadow, const float* __restrict__ x0, int m,
@@ -211,6 +243,18 @@ hipError_t launch_pull(float* x, const float* z, uint16_t* shadow, int m, int64_
     const int64_t n4 = ld / 4;
     if (shadow) pull_kernel<true><<<grid, kThreads, 0, s>>>((f4*)x, (const f4*)z, (u2*)shadow, n4, m, alpha);
     else pull_kernel<false><<<grid, kThreads, 0, s>>>((f4*)x, (const f4*)z, nullptr, n4, m, alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_stale_sync(float* x, float* snap, const float* z, uint16_t* shadow, int m, int64_t ld,
+                             hipStream_t s) {
+    if (m < 1 || ld < 4 || ld % 4 != 0 || !x || !snap || !z || x == snap) return hipErrorInvalidValue;
+    if (!aligned16(x) || !aligned16(snap) || !aligned16(z) || !aligned16(shadow)) return hipErrorInvalidValue;
+    unsigned grid;
+    if (!grid_for(m, ld, &grid)) return hipErrorInvalidValue;
+    const int64_t n4 = ld / 4;
+    if (shadow) stale_sync_kernel<true><<<grid, kThreads, 0, s>>>((f4*)x, (f4*)snap, (const f4*)z, (u2*)shadow, n4, m);
+    else stale_sync_kernel<false><<<grid, kThreads, 0, s>>>((f4*)x, (f4*)snap, (const f4*)z, nullptr, n4, m);
     return hipGetLastError();
 }
 

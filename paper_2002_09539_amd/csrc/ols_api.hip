@@ -36,7 +36,8 @@ int fail(int code, const char* fmt, ...) {
 
 const char* kKernelNames[OLS_K_COUNT] = {
     "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
-    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16", "delay",    "lsq_step"};
+    "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16", "delay",    "lsq_step",
+    "stale_sync"};
 
 enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2 };
 
@@ -57,6 +58,7 @@ struct ols_ctx {
     int cur = 0;
     float *buf = nullptr, *g = nullptr, *z = nullptr, *v = nullptr;
     const float* mix_w = nullptr;   // general mixing matrix (device), or nullptr: the paper's pull-back + average
+    float* snap = nullptr;          // [m][ld] models of the previous synchronisation (stale-average rule), or nullptr
     hipStream_t stream[2] = {nullptr, nullptr};
     bool bound = false, inited = false, launched = false;
     // options
@@ -518,6 +520,11 @@ int ols_init_params(ols_handle c, const float* x0) {
         return launch_init(c->x[0], c->x[1], c->buf, c->z, shadow_ptr(c), x0, c->m, c->d, c->ld, s);
     });
     if (rc) return rc;
+    if (c->snap && !c->dry) {  // the remembered models restart from the common point as well
+        hipError_t e = hipMemcpyAsync(c->snap, c->x[0], (size_t)c->m * c->ld * sizeof(float), hipMemcpyDeviceToDevice,
+                                      c->stream[0]);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(snap)");
+    }
     c->k = 0;
     c->pull_due = c->pending_update = c->anchor_due = c->anchor_inflight = c->first_after_anchor = false;
     c->anchor_precomputed = c->pulled_in_step = false;
@@ -531,6 +538,7 @@ int ols_set_anchor_momentum(ols_handle c, float beta_z, float* v) {
     if (!(beta_z >= 0.0f && beta_z < 1.0f)) return fail(OLS_EINVAL, "beta_z must be in [0, 1)");
     if (beta_z != 0.0f && !v) return fail(OLS_EINVAL, "v is required when beta_z is non-zero");
     if (beta_z != 0.0f && c->mix_w) return fail(OLS_EINVAL, "anchor momentum cannot be combined with general mixing");
+    if (beta_z != 0.0f && c->snap) return fail(OLS_EINVAL, "anchor momentum cannot be combined with the stale-average rule");
     if (reinterpret_cast<uintptr_t>(v) & 255u) return fail(OLS_EINVAL, "v must be 256-byte aligned");
     c->beta_z = beta_z;
     c->v = beta_z != 0.0f ? v : nullptr;
@@ -543,8 +551,26 @@ int ols_set_mixing(ols_handle c, const float* w_dev) {
         return fail(OLS_ESTATE, "the mixing matrix cannot change in the middle of a synchronisation");
     if (w_dev && c->m > kMixMaxWorkers) return fail(OLS_EINVAL, "general mixing supports m <= %d", kMixMaxWorkers);
     if (w_dev && c->beta_z != 0.0f) return fail(OLS_EINVAL, "general mixing cannot be combined with anchor momentum");
+    if (w_dev && c->snap) return fail(OLS_EINVAL, "general mixing cannot be combined with the stale-average rule");
     if (reinterpret_cast<uintptr_t>(w_dev) & 3u) return fail(OLS_EINVAL, "w_dev must be 4-byte aligned");
     c->mix_w = w_dev;
+    return OLS_OK;
+}
+
+int ols_set_stale_average(ols_handle c, float* snap) {
+    if (int rc = need(c)) return rc;
+    if (!c->bound || !c->inited) return fail(OLS_ESTATE, "ols_bind and ols_init_params must precede ols_set_stale_average");
+    if (c->k != 0) return fail(OLS_ESTATE, "the synchronisation rule must be chosen before the first local step");
+    if (snap && (c->mix_w || c->beta_z != 0.0f))
+        return fail(OLS_EINVAL, "the stale-average rule cannot be combined with general mixing or anchor momentum");
+    if (reinterpret_cast<uintptr_t>(snap) & 255u) return fail(OLS_EINVAL, "snap must be 256-byte aligned");
+    if (snap && (snap == c->x[0] || snap == c->x[1])) return fail(OLS_EINVAL, "snap must not alias the replicas");
+    if (snap && !c->dry) {  // every model starts from the common point, and so do the remembered ones
+        hipError_t e = hipMemcpyAsync(snap, c->x[c->cur], (size_t)c->m * c->ld * sizeof(float), hipMemcpyDeviceToDevice,
+                                      c->stream[0]);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(snap)");
+    }
+    c->snap = snap;
     return OLS_OK;
 }
 
@@ -660,7 +686,8 @@ int ols_local_step(ols_handle c) {
         if (!c->batch_set) return fail(OLS_ESTATE, "the attached model needs ols_set_batch");
     }
     const bool boundary = (c->k + 1) % c->tau == 0;
-    const bool paper_sync = c->mix_w == nullptr;   // the synchronisation is the paper's pull-back + anchor average
+    // whether the synchronisation is the paper's pull-back + anchor average
+    const bool paper_sync = c->mix_w == nullptr && c->snap == nullptr;
     const bool grad_kernels_update = c->model == MODEL_MLP || (c->model == MODEL_LSQ && lsq_step_fits(c->B, c->d));
     if (grad_kernels_update && c->fuse_gemm_update && !(boundary && c->fuse_mean && paper_sync)) {
         // the gradient kernels apply the update themselves; on a boundary step the pull-back as well,
@@ -738,6 +765,20 @@ int ols_sync_pull(ols_handle c) {
         c->pull_due = false;
         c->anchor_due = true;
         c->anchor_precomputed = true;
+        return OLS_OK;
+    }
+    if (c->snap) {  // x <- z + (x - snap), snap <- x; the average of the new models follows on the side stream
+        c->first_after_anchor = false;
+        int rc = enqueue(c, OLS_K_STALE_SYNC, 0, c->cur, c->cur, [&](hipStream_t s) {
+            return launch_stale_sync(c->x[c->cur], c->snap, c->z, shadow_ptr(c), c->m, c->ld, s);
+        });
+        if (rc) return rc;
+        if (!c->dry) {
+            hipError_t e = hipEventRecord(c->ev_pulled, c->stream[0]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventRecord");
+        }
+        c->pull_due = false;
+        c->anchor_due = true;
         return OLS_OK;
     }
     int src = c->cur, dst = c->cur;

@@ -27,6 +27,8 @@ struct UpdateArgs {
 hipError_t launch_step(const UpdateArgs& a, hipStream_t s);                      // local step (+ pull-back)
 hipError_t launch_pull(float* x, const float* z, uint16_t* shadow, int m, int64_t ld, float alpha,
                        hipStream_t s);                                            // stand-alone pull-back
+hipError_t launch_stale_sync(float* x, float* snap, const float* z, uint16_t* shadow, int m, int64_t ld,
+                             hipStream_t s);                                      // x <- z + (x - snap); snap <- x
 hipError_t launch_init(float* x, float* x_alt, float* buf, float* z, uint16_t* shadow, const float* x0, int m,
                        int64_t d, int64_t ld, hipStream_t s);
 

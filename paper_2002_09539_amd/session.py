@@ -63,6 +63,12 @@ class Session:
         self.w = self.upload(W)
         B.ols_set_mixing(self.h, _ptr(self.w))
 
+    def set_stale_average(self, on=True):
+        """Stale-average synchronisation in place of pull-back + anchor average (after init, before the first step)."""
+        self.snap = torch.empty_like(self.x) if on else None
+        torch.cuda.synchronize(self.device)
+        B.ols_set_stale_average(self.h, _ptr(self.snap))
+
     def attach_lsq(self, batch):
         B.ols_attach_lsq(self.h, batch)
         self._workspace()

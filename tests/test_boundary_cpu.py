@@ -386,3 +386,48 @@ def test_general_mixing_argument_checks():
     B.ols_set_anchor_momentum(h, 0.7, FAKE + (6 << 30))
     assert code_of(B.ols_set_mixing, h, FAKE) == B.OLS_EINVAL          # anchor momentum is set
     B.ols_destroy(h)
+
+
+def test_stale_average_rule_in_the_schedule():
+    """With the stale-average rule a synchronisation point is: plain local step, one synchronisation pass
+    on the main stream, then the replica mean on the side stream (it overlaps the next round)."""
+    h = dry(m=4, tau=2, mu=0.9)
+    assert code_of(B.ols_set_stale_average, h, FAKE + (7 << 30)) == B.OLS_ESTATE   # before ols_init_params
+    B.ols_init_params(h, FAKE)
+    assert code_of(B.ols_set_stale_average, h, FAKE + (7 << 30) + 4) == B.OLS_EINVAL   # alignment
+    assert code_of(B.ols_set_stale_average, h, FAKE) == B.OLS_EINVAL                   # aliases the replicas
+    B.ols_set_stale_average(h, FAKE + (7 << 30))
+    assert code_of(B.ols_set_mixing, h, FAKE + (5 << 30)) == B.OLS_EINVAL
+    assert code_of(B.ols_set_anchor_momentum, h, 0.7, FAKE + (6 << 30)) == B.OLS_EINVAL
+    for _ in range(2):
+        B.ols_local_step(h)
+        B.ols_local_step(h)
+        assert code_of(B.ols_local_step, h) == B.OLS_ESTATE
+        B.ols_sync_pull(h)
+        B.ols_anchor_update_async(h)
+    tr = B.ols_trace(h)
+    assert [B.ols_kernel_name(e["kind"]) for e in tr] == ["init", "step", "step", "stale_sync", "mean",
+                                                          "step", "step", "stale_sync", "mean"]
+    assert [e["stream"] for e in tr] == [0, 0, 0, 0, 1, 0, 0, 0, 1]
+    # the second synchronisation reads the average the first refresh produced: the main stream waits for it
+    assert [e["waited"] for e in tr if B.ols_kernel_name(e["kind"]) == "stale_sync"] == [0, 1]
+    assert code_of(B.ols_set_stale_average, h, None) == B.OLS_ESTATE   # not after the first local step
+    B.ols_destroy(h)
+
+
+def test_stale_average_rule_with_an_attached_mlp_uses_plain_gradient_kernels():
+    dims = [8, 12, 5]
+    h = dry(m=2, d=sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(2)), tau=2, mu=0.9)
+    B.ols_attach_mlp(h, dims, 8, 0)
+    B.ols_bind_workspace(h, FAKE + (8 << 30), B.ols_workspace_bytes(h))
+    B.ols_init_params(h, FAKE)
+    B.ols_set_batch(h, FAKE + (9 << 30), 64, FAKE + (10 << 30), 8)
+    B.ols_set_stale_average(h, FAKE + (7 << 30))
+    B.ols_local_step(h)
+    B.ols_local_step(h)
+    B.ols_sync_pull(h)
+    B.ols_anchor_update_async(h)
+    names = [B.ols_kernel_name(e["kind"]) for e in B.ols_trace(h)]
+    assert names[-2:] == ["stale_sync", "mean"]
+    assert "pull" not in names and "step_pull" not in names and "step_pull_mean" not in names
+    B.ols_destroy(h)
