@@ -218,7 +218,10 @@ def run(x0, m, tau, alpha, gamma, K, grad_fn, mu=0.0, nesterov=True, beta_z=0.0,
 
     grad_fn(i, k, x_i) -> (loss, g): worker i's mini-batch loss and gradient at
     iteration k, evaluated at its own current model.  on_step(k, state), if
-    given, is called after iteration k with the live state dict.
+    given, is called after iteration k with the live state dict.  gamma is a
+    number, or a function k -> learning rate of iteration k (Section 4 trains
+    with a warm-up and step decays: the rate then changes between iterations,
+    the update rules stay as they are).
 
     Returns dict(x [m][d], buf [m][d] or None, z [d], v [d] or None,
     losses [K][m]) with the state in the `store` dtype.
@@ -233,11 +236,12 @@ def run(x0, m, tau, alpha, gamma, K, grad_fn, mu=0.0, nesterov=True, beta_z=0.0,
     state = dict(x=x, buf=buf, z=z, v=v, losses=losses)
     for k in range(K):
         sync = (k + 1) % tau == 0
+        gamma_k = gamma(k) if callable(gamma) else gamma
         for i in range(m):
             loss, g = grad_fn(i, k, x[i])
             losses[k, i] = loss
             x_half, b_new = local_momentum_step(x[i], None if buf is None else buf[i],
-                                                g, gamma, mu, nesterov)
+                                                g, gamma_k, mu, nesterov)
             if buf is not None:
                 buf[i] = b_new.astype(store)
             # the pull uses the anchor as it stood before this step's refresh

@@ -47,6 +47,10 @@ class Session:
     def set_option(self, key, value):
         B.ols_set_option(self.h, key, int(value))
 
+    def set_lr(self, gamma):
+        """Learning rate of the local steps from now on (not while a deferred step waits for ols_sync_pull)."""
+        B.ols_set_lr(self.h, float(gamma))
+
     def set_anchor_momentum(self, beta_z):
         self.v = torch.zeros(self.ld, dtype=torch.float32, device=self.device) if beta_z != 0.0 else None
         torch.cuda.synchronize(self.device)

@@ -33,6 +33,24 @@ def test_closed_form_identical_quadratic(tau, alpha):
     np.testing.assert_allclose(st["z"], factor * x0, rtol=1e-13)
 
 
+def test_closed_form_identical_quadratic_with_a_learning_rate_schedule():
+    """gamma_k varies (Section 4: warm-up, then step decays): round r multiplies x by
+    (1 - alpha) prod_{k in r} (1 - gamma_k a) + alpha; a constant schedule is the plain run."""
+    m, d, a, tau, alpha, rounds = 3, 5, 0.7, 3, 0.6, 4
+    x0 = rand(d, 11)
+    gammas = [0.02 * (k + 1) for k in range(5)] + [0.3] * 4 + [0.03] * 3        # warm-up, plateau, decay
+    st = O.run(x0, m, tau, alpha, lambda k: gammas[k], rounds * tau, quad_grad(a, np.zeros((m, d))), store=F64)
+    factor = 1.0
+    for r in range(rounds):
+        rho = np.prod([1.0 - gammas[k] * a for k in range(r * tau, (r + 1) * tau)])
+        factor *= (1.0 - alpha) * rho + alpha
+    np.testing.assert_allclose(st["x"], np.tile(factor * x0, (m, 1)), rtol=1e-13)
+    np.testing.assert_allclose(st["z"], factor * x0, rtol=1e-13)
+    const = O.run(x0, m, tau, alpha, lambda k: 0.3, rounds * tau, quad_grad(a, rand((m, d), 12)), mu=0.9, store=F64)
+    plain = O.run(x0, m, tau, alpha, 0.3, rounds * tau, quad_grad(a, rand((m, d), 12)), mu=0.9, store=F64)
+    np.testing.assert_array_equal(const["x"], plain["x"])
+
+
 def test_closed_form_heterogeneous_quadratic():
     """Mean and deviations of the replicas after each round, F_i = 0.5 a ||x - c_i||^2."""
     m, d, a, gamma, tau, alpha = 4, 6, 0.9, 0.2, 3, 0.6
