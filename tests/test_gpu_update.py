@@ -231,6 +231,47 @@ def test_stream_config_full_size_sampled_columns():
         del grads
 
 
+@pytest.mark.parametrize("fuse_mean", [1, 0])
+def test_replicas_of_more_than_2_31_elements_sampled_columns(fuse_mean):
+    """m * ld = 2.18e9 fp32 elements (8.7 GB per [m][ld] array): every element index of the streaming,
+    pull-back and averaging kernels passes 2^31.  One seeded gradient row serves all workers, scaled per
+    worker by exact powers of two and signs so that the rows differ; the oracle recomputes sampled columns,
+    among them the first and last of the first and last rows' 16-byte vectors."""
+    from paper_2002_09539_amd import binding as B
+    cfg = I.get(4)
+    m, d, tau, K = 33, 66_000_001, 2, 4
+    rng = np.random.default_rng(9)
+    cols = np.unique(np.concatenate([rng.integers(0, d, 3000), [0, 1, 2, 3, d - 4, d - 3, d - 2, d - 1]]))
+    x0 = G.stream_x0(cfg, d=d)
+    row = G.stream_gradient(cfg, 0, d=d, m=1)[0]
+    scales = np.array([(-1.0) ** i * 2.0 ** ((i % 5) - 2) for i in range(m)], np.float32)
+    g_cols = scales[:, None] * row[cols][None, :]
+    st = O.run(x0[cols], m, tau, cfg.alpha, cfg.gamma, K, OW.stream_grad_fn([g_cols]), mu=cfg.mu)
+    with make_session(m, d, tau, cfg.alpha, cfg.gamma, cfg.mu, own_gradient=False) as s:
+        assert s.m * s.ld > 2 ** 31
+        s.set_option(B.OLS_OPT_FUSE_MEAN, fuse_mean)
+        g = torch.zeros(m, s.ld, dtype=torch.float32, device=s.device)
+        g[:, :d] = torch.from_numpy(row).to(s.device)[None, :]
+        g *= torch.from_numpy(scales).to(s.device)[:, None]
+        torch.cuda.synchronize()
+        s.bind(g)
+        s.init_params(x0)
+        s.run(K)
+        s.sync()
+        idx = torch.from_numpy(cols).to(s.device)
+        t = torch.empty(s.ld, dtype=torch.float32, device=s.device)
+        x = np.empty((m, len(cols)), np.float32)
+        for i in range(m):
+            B.ols_get_params(s.h, i, t.data_ptr(), 1)
+            x[i] = t[idx].cpu().numpy()
+        B.ols_get_params(s.h, -1, t.data_ptr(), 1)
+        z = t[idx].cpu().numpy()
+        buf = s.buf[:, idx].cpu().numpy()
+    assert max_norm_ratio(x, st["x"]) <= PER_STEP_TOL * K, fuse_mean
+    assert max_norm_ratio(z, st["z"]) <= PER_STEP_TOL * K, fuse_mean
+    assert max_norm_ratio(buf, st["buf"]) <= PER_STEP_TOL * K, fuse_mean
+
+
 def test_lsq_gradient_and_loss_single_step():
     cfg = I.get(1)
     A, y, w_star, _ = G.lsq_data(cfg.scaled(nb=1))
