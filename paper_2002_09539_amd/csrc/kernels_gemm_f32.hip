@@ -769,12 +769,15 @@ static hipError_t dw_pipelined_launch(const GemmArgs& g, hipStream_t s) {
 // 16 groups): every tile shape lands within a few percent once there are several workgroups per compute
 // unit, because the matrix pipe idles whenever a wavefront waits at the slice barrier or for its loads
 // and only other resident workgroups fill those gaps; so: 64 x 64 tiles, and K ranges until the launch
-// has about four workgroups per compute unit.
+// has about two workgroups per compute unit.  With the full-tile path, per launch including the pass that
+// sums the parts: one K range (256 workgroups) 70.8 us, two 69.1 us, four 71.3 us, eight 82 us; the step as a
+// whole 0.1808 / 0.1798 / 0.1828 / 0.194 ms (fewer parts to write and re-read, and the anchor refresh on the
+// side stream finds more room beside the smaller launch).
 void gemm_f32_fwd_plan(int groups, int M, int N, int K, int* variant, int* splits) {
     *variant = 2;
     const int64_t tiles = (int64_t)groups * ((M + 63) / 64) * ((N + 63) / 64);
     int s = 1;
-    while (tiles * s < 1024 && K / (2 * s) >= 256 && s < 8) s *= 2;
+    while (tiles * s < 512 && K / (2 * s) >= 256 && s < 8) s *= 2;
     *splits = s;
 }
 
