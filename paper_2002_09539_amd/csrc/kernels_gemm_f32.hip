@@ -421,7 +421,9 @@ struct DwFlag {
 // contiguous (100.8 us).  Knock-out builds (wrong values on purpose, same memory touched) split the 100 us: state
 // traffic alone 77 us (5.6 TB/s), + the operand loads 94 us (393 MB of L2 hits cost 17 us, half of them 9 us),
 // + the MFMAs 100 us; operands + MFMAs without the state traffic take 61 us.  The three parts add up rather than
-// overlap: L2 hits and HBM streams pass through the same L2 channels, and the matrix work hides all but 6 us.
+// overlap, and the matrix work hides all but 6 us.  The cost of the operand loads is not their L2 traffic: a
+// generalisation of this kernel to 128 x 64 tiles (a quarter less operand traffic, two workgroups per compute unit,
+// identical bits) measured 96.8 us against 96.4 us for 64 x 64 tiles and is not in the tree.
 template <int SPG, bool PULL, bool MOM>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(OLS_DWP_WAVES)))
 void gemm_f32_dw_pipelined_kernel(GemmDev p) {
@@ -705,8 +707,10 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
+// persistent workgroups per compute unit: measured 16 x (3072 x 512, K = 128): one 125 us, two 97.4 us, three 98.9 us,
+// four 99.7 us per launch
 #ifndef OLS_DWP_WGS_PER_CU
-#define OLS_DWP_WGS_PER_CU 4
+#define OLS_DWP_WGS_PER_CU 2
 #endif
 // shapes the persistent pipelined weight-gradient kernel covers: fused update, full 64 x 64 tiles, K = 64, 128 or 256
 static bool dw_pipelined_fits(const GemmArgs& g) {
