@@ -69,18 +69,16 @@ struct HeadDev {
     int B, H, C;
 };
 
-constexpr int kHeadThreads = 256;
-constexpr int kHeadSamples = kHeadThreads / kRow;   // samples per workgroup of the forward kernel (16)
-
-// KC = hidden units staged per pass (512 or 1024); activation rows are staged at pitch KC + 4
-__host__ __device__ constexpr int head_fwd_lds_floats(int CMAX, int KC) {
-    return KC * head_row_pitch(CMAX) + kHeadSamples * (KC + 4) + kHeadSamples * CMAX;
+// KC = hidden units staged per pass; THREADS / 16 samples per workgroup; activation rows are staged at pitch KC + 4
+__host__ __device__ constexpr int head_fwd_lds_floats(int CMAX, int KC, int THREADS) {
+    return KC * head_row_pitch(CMAX) + (THREADS / kRow) * (KC + 4) + (THREADS / kRow) * CMAX;
 }
 
-// grid (ceil(B / 16), m); dynamic LDS: head_fwd_lds_floats(CMAX, KC) floats
-template <bool BF, int CMAX, int KC>
-__global__ __launch_bounds__(kHeadThreads) void head_fwd_kernel(HeadDev p) {
-    constexpr int THREADS = kHeadThreads, S = kHeadSamples, HP = KC + 4;
+// grid (ceil(B / (THREADS / 16)), m); dynamic LDS: head_fwd_lds_floats(CMAX, KC, THREADS) floats
+template <bool BF, int CMAX, int KC, int THREADS>
+__global__ __launch_bounds__(THREADS) void head_fwd_kernel(HeadDev p) {
+    constexpr int S = THREADS / kRow, HP = KC + 4;
+    static_assert(THREADS % 64 == 0 && (KC * CMAX) % THREADS == 0 && KC % 128 == 0, "staging shape");
     constexpr int P = head_row_pitch(CMAX);         // LDS pitch of a weight row
     constexpr int NW = KC * CMAX / THREADS;    // staged weights per lane, all in flight at once
     constexpr int J = KC / (4 * kRow);         // 4-wide activation vectors per lane per pass (8)
@@ -290,16 +288,17 @@ static bool head_args_ok(const HeadArgs& a) {
            (reinterpret_cast<uintptr_t>(a.h) & 15u) == 0 && a.h_stride % 4 == 0;
 }
 
-template <bool BF, int CMAX, int KC>
+template <bool BF, int CMAX, int KC, int THREADS>
 static hipError_t head_fwd_launch(const HeadDev& p, int m, hipStream_t s) {
-    size_t lds = (size_t)head_fwd_lds_floats(CMAX, KC) * sizeof(float);
-    auto kern = head_fwd_kernel<BF, CMAX, KC>;
+    size_t lds = (size_t)head_fwd_lds_floats(CMAX, KC, THREADS) * sizeof(float);
+    auto kern = head_fwd_kernel<BF, CMAX, KC, THREADS>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    dim3 grid((unsigned)((p.B + kHeadSamples - 1) / kHeadSamples), (unsigned)m);
-    kern<<<grid, kHeadThreads, lds, s>>>(p);
+    constexpr int kSamples = THREADS / kRow;
+    dim3 grid((unsigned)((p.B + kSamples - 1) / kSamples), (unsigned)m);
+    kern<<<grid, THREADS, lds, s>>>(p);
     return hipGetLastError();
 }
 
@@ -326,13 +325,20 @@ hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s) {
     p.C = a.C;
     // Wider layers are staged 1024 hidden units at a time (146 KiB of LDS with 16 classes): half as many
     // dependent passes, and up to H = 1024 the delta reuses what the logits staged.
+    // Workgroup size.  What a workgroup pays per pass is the staging of the weights, whatever the number of its
+    // samples: measured with 64 / 128 / 256 / 512 threads (4 to 32 samples) and 512 staged units, 16 workers x 128
+    // samples x 512 units: 19.5 / 17.0 / 15.4 / 14.0 us; 256 samples x 2048 units: 148 / 60 / 52 / 52 us.  So:
+    // 32 samples per workgroup where one pass covers the layer and the batch has them, 16 otherwise.
     const bool wide = a.H > 512 && a.C <= 16;
+    const bool big = !wide && a.C <= 16 && a.B >= 32;
     if (a.h_bf16) {
-        if (a.C > 16) return head_fwd_launch<true, 32, 512>(p, a.m, s);
-        return wide ? head_fwd_launch<true, 16, 1024>(p, a.m, s) : head_fwd_launch<true, 16, 512>(p, a.m, s);
+        if (a.C > 16) return head_fwd_launch<true, 32, 512, 256>(p, a.m, s);
+        if (big) return head_fwd_launch<true, 16, 512, 512>(p, a.m, s);
+        return wide ? head_fwd_launch<true, 16, 1024, 256>(p, a.m, s) : head_fwd_launch<true, 16, 512, 256>(p, a.m, s);
     }
-    if (a.C > 16) return head_fwd_launch<false, 32, 512>(p, a.m, s);
-    return wide ? head_fwd_launch<false, 16, 1024>(p, a.m, s) : head_fwd_launch<false, 16, 512>(p, a.m, s);
+    if (a.C > 16) return head_fwd_launch<false, 32, 512, 256>(p, a.m, s);
+    if (big) return head_fwd_launch<false, 16, 512, 512>(p, a.m, s);
+    return wide ? head_fwd_launch<false, 16, 1024, 256>(p, a.m, s) : head_fwd_launch<false, 16, 512, 256>(p, a.m, s);
 }
 
 // Validates the arguments of the output layer's gradient pass and lays them out for the device.
