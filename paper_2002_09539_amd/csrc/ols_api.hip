@@ -106,9 +106,16 @@ int hip_fail(hipError_t e, const char* what) {
 
 int ensure_events(ols_ctx* c) {
     if (c->ev_pulled || c->dry) return OLS_OK;
-    hipError_t e = hipEventCreateWithFlags(&c->ev_pulled, hipEventDisableTiming);
+    // The two events order kernels of the two streams of ONE device and are never waited for by the host, so the
+    // system-scope fence of an event is not needed (kernels release at device scope when they end).  Measured with a
+    // probe (two 99 us kernels on the main stream, a small one on the side stream between them, fork and join by
+    // events): the record costs 0.9 us instead of 2.7 us, the whole pattern 6.2 us instead of 10.2 us.
+#ifndef OLS_EVENT_FLAGS
+#define OLS_EVENT_FLAGS (hipEventDisableTiming | hipEventDisableSystemFence)
+#endif
+    hipError_t e = hipEventCreateWithFlags(&c->ev_pulled, OLS_EVENT_FLAGS);
     if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
-    e = hipEventCreateWithFlags(&c->ev_anchor_done, hipEventDisableTiming);
+    e = hipEventCreateWithFlags(&c->ev_anchor_done, OLS_EVENT_FLAGS);
     if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
     return OLS_OK;
 }
