@@ -258,6 +258,24 @@ OLS_API int ols_anchor_update_async(ols_handle h);
  * when a pull or an anchor refresh is due. */
 OLS_API int ols_run_steps(ols_handle h, int64_t steps, const float* X_dev, const void* y_dev, int nb);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): ols_run_steps with the attached model's workspace (activations, deltas, split-K partial
+ * sums, output-layer deltas, per-sample losses) taken from a static device array inside the library instead of a
+ * caller-provided buffer.  The call allocates nothing (no hipMalloc / hipFree, no events); the handle must have
+ * been bound and initialised beforehand, and state, data and streams remain the caller's.
+ *   - The array holds ols_static_workspace_bytes() = 64 MiB, one copy per GPU, kept until the process ends;
+ *     OLS_ENOMEM if ols_workspace_bytes(h) is larger.
+ *   - fp32 models only (least squares, fp32 MLP): the bf16 MLP keeps weights in its workspace (OLS_EINVAL).
+ *   - OLS_ESTATE while OLS_OPT_KERNEL_TIMING is on (timing creates events).
+ *   - The handle's workspace becomes the static array (it replaces one bound with ols_bind_workspace); ols_get_loss
+ *     afterwards reads the per-sample losses from it.  Nothing in it needs clearing between calls: every kernel
+ *     writes what it later reads.
+ *   - Every handle on one GPU shares the one array: calls (and the work they enqueue) that overlap on a GPU race;
+ *     drain the streams (ols_sync) before another handle uses it.
+ * Same launches, same results as ols_run_steps. */
+OLS_API int ols_run_steps_static(ols_handle h, int64_t steps, const float* X_dev, const void* y_dev, int nb);
+OLS_API int64_t ols_static_workspace_bytes(void);
+
 /* ---- results --------------------------------------------------------------------------------- */
 
 /* Copies d floats: which = 0..m-1 a replica, -1 the anchor z.  which = -2 computes the replica mean

@@ -48,6 +48,8 @@ _SIGNATURES = {
     "ols_bind_workspace": (C.c_int, [_H, _P, C.c_int64]),
     "ols_set_batch": (C.c_int, [_H, _P, C.c_int64, _P, C.c_int64]),
     "ols_run_steps": (C.c_int, [_H, C.c_int64, _P, _P, C.c_int]),
+    "ols_run_steps_static": (C.c_int, [_H, C.c_int64, _P, _P, C.c_int]),
+    "ols_static_workspace_bytes": (C.c_int64, []),
     "ols_set_gradient": (C.c_int, [_H, _P]),
     "ols_local_step": (C.c_int, [_H]),
     "ols_sync_pull": (C.c_int, [_H]),
@@ -163,6 +165,14 @@ def ols_set_batch(h, X, x_worker_stride, y, y_worker_stride):
 
 def ols_run_steps(h, steps, X, y, nb):
     _check(load().ols_run_steps(h, steps, X, y, nb))
+
+
+def ols_run_steps_static(h, steps, X, y, nb):
+    _check(load().ols_run_steps_static(h, steps, X, y, nb))
+
+
+def ols_static_workspace_bytes():
+    return load().ols_static_workspace_bytes()
 
 
 def ols_set_gradient(h, g):

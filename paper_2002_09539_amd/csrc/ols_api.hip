@@ -201,6 +201,30 @@ int main_waits_for_anchor(ols_ctx* c) {
 
 int64_t align256(int64_t v) { return round_up(v, 256); }
 
+// Static model workspace for callers that cannot allocate (ols_run_steps_static).  One copy per GPU, held until the
+// process ends.  In host code the array's name is only a stand-in: the device address is looked up once per device
+// with hipGetSymbolAddress and kept in scratch_ptr; everything below uses that pointer.
+constexpr int64_t kStaticWorkspaceBytes = 64ll << 20;
+constexpr int kStaticWorkspaceMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+void* scratch_ptr[kStaticWorkspaceMaxDevices] = {nullptr};
+
+int static_workspace(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(OLS_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kStaticWorkspaceMaxDevices) return fail(OLS_EINVAL, "device index %d is outside [0, %d)", dev,
+                                                                  kStaticWorkspaceMaxDevices);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(OLS_EHIP, "hipGetSymbolAddress(static workspace): %s", hipGetErrorString(e));
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return OLS_OK;
+}
+
 uint16_t* shadow_ptr(ols_ctx* c) {
     return (c->model == MODEL_MLP && c->gemm_dtype == 1 && c->ws) ? (uint16_t*)(c->ws + c->off_shadow) : nullptr;
 }
@@ -884,6 +908,30 @@ int ols_run_steps(ols_handle c, int64_t steps, const float* X, const void* y, in
         }
     }
     return OLS_OK;
+}
+
+int64_t ols_static_workspace_bytes(void) { return kStaticWorkspaceBytes; }
+
+int ols_run_steps_static(ols_handle c, int64_t steps, const float* X, const void* y, int nb) {
+    if (int rc = need(c)) return rc;
+    if (c->model == MODEL_NONE) return fail(OLS_ESTATE, "ols_run_steps_static needs an attached model");
+    if (c->model == MODEL_MLP && c->gemm_dtype == 1)
+        return fail(OLS_EINVAL, "the bf16 model keeps its bf16 weights in the workspace, which must then outlive the call: "
+                                "bind a caller-owned workspace and use ols_run_steps");
+    if (c->timing) return fail(OLS_ESTATE, "per-kernel timing creates events; switch OLS_OPT_KERNEL_TIMING off first");
+    if (c->ws_need > kStaticWorkspaceBytes)
+        return fail(OLS_ENOMEM, "the attached model needs %lld bytes of workspace, the static workspace holds %lld",
+                    (long long)c->ws_need, (long long)kStaticWorkspaceBytes);
+    if (!c->dry) {
+        void* p = nullptr;
+        if (int rc = static_workspace(&p)) return rc;
+        c->ws = (char*)p;
+        c->ws_bytes = kStaticWorkspaceBytes;
+    } else {
+        c->ws = reinterpret_cast<char*>(uintptr_t(256));  // never dereferenced: a dry run launches nothing
+        c->ws_bytes = kStaticWorkspaceBytes;
+    }
+    return ols_run_steps(c, steps, X, y, nb);
 }
 
 int ols_sync(ols_handle c) {

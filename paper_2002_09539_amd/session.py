@@ -77,9 +77,11 @@ class Session:
         B.ols_attach_lsq(self.h, batch)
         self._workspace()
 
-    def attach_mlp(self, dims, batch, gemm_dtype="f32"):
+    def attach_mlp(self, dims, batch, gemm_dtype="f32", workspace=True):
+        """workspace=False leaves the model without a bound workspace (for run_resident_static)."""
         B.ols_attach_mlp(self.h, list(dims), batch, {"f32": 0, "bf16": 1}[gemm_dtype])
-        self._workspace()
+        if workspace:
+            self._workspace()
 
     def _workspace(self):
         n = B.ols_workspace_bytes(self.h)
@@ -143,6 +145,11 @@ class Session:
         k mod nb at iteration k; the loop runs inside the library (ols_run_steps)."""
         assert X.is_contiguous() and y.is_contiguous() and X.shape[:2] == y.shape[:2] and X.dtype == torch.float32
         B.ols_run_steps(self.h, K, _ptr(X), _ptr(y), X.shape[1])
+
+    def run_resident_static(self, K, X, y):
+        """run_resident with the model's workspace in the library's static device array (ols_run_steps_static)."""
+        assert X.is_contiguous() and y.is_contiguous() and X.shape[:2] == y.shape[:2] and X.dtype == torch.float32
+        B.ols_run_steps_static(self.h, K, _ptr(X), _ptr(y), X.shape[1])
 
     # ---- results -----------------------------------------------------------------------------
     def params(self, which):

@@ -431,3 +431,44 @@ def test_stale_average_rule_with_an_attached_mlp_uses_plain_gradient_kernels():
     assert names[-2:] == ["stale_sync", "mean"]
     assert "pull" not in names and "step_pull" not in names and "step_pull_mean" not in names
     B.ols_destroy(h)
+
+
+def test_static_workspace_entry_point_checks_its_limits_without_a_device():
+    """ols_run_steps_static in dry-run mode: the same launches as ols_run_steps, and a clear error for a model that
+    does not fit the 64 MiB static array, for the bf16 model and while per-kernel timing is on."""
+    assert B.ols_static_workspace_bytes() == 64 << 20
+
+    def attach(dims, batch, dtype=0, m=4):
+        d = sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(len(dims) - 1))
+        h = dry(m=m, d=d, mu=0.9, tau=2)
+        B.ols_attach_mlp(h, dims, batch, dtype)
+        return h
+    h = attach([8, 12, 5], 8)
+    B.ols_init_params(h, FAKE)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_run_steps_static(h, 4, FAKE, FAKE, 3)          # no ols_bind_workspace beforehand
+    a = kinds(B.ols_trace(h))
+    B.ols_set_option(h, B.OLS_OPT_KERNEL_TIMING, 1)
+    assert code_of(B.ols_run_steps_static, h, 1, FAKE, FAKE, 3) == B.OLS_ESTATE
+    B.ols_destroy(h)
+    h = attach([8, 12, 5], 8)
+    B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+    B.ols_init_params(h, FAKE)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_run_steps(h, 4, FAKE, FAKE, 3)
+    assert kinds(B.ols_trace(h)) == a and len(a) > 8
+    B.ols_destroy(h)
+    h = attach([64, 2048, 2048, 10], 256, m=16)          # 128 MiB of activations and deltas
+    assert B.ols_workspace_bytes(h) > B.ols_static_workspace_bytes()
+    B.ols_init_params(h, FAKE)
+    assert code_of(B.ols_run_steps_static, h, 1, FAKE, FAKE, 1) == B.OLS_ENOMEM
+    assert "static workspace" in B.last_error()
+    B.ols_destroy(h)
+    h = attach([64, 64, 10], 16, dtype=1)
+    B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+    B.ols_init_params(h, FAKE)
+    assert code_of(B.ols_run_steps_static, h, 1, FAKE, FAKE, 1) == B.OLS_EINVAL
+    B.ols_destroy(h)
+    h = dry(d=100)
+    assert code_of(B.ols_run_steps_static, h, 1, FAKE, FAKE, 1) == B.OLS_ESTATE      # no model attached
+    B.ols_destroy(h)
