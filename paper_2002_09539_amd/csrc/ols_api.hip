@@ -5,8 +5,11 @@
 //
 // Overlap (the paper's timeline figure, carried out inside one GPU): after the pull-back at the end of
 // round a the main stream records `ev_pulled`; the side stream waits for it, reduces the replica axis
-// into the anchor and records `ev_anchor_done`; the main stream waits for that event only before the
-// NEXT pull-back, which is the first consumer of the refreshed anchor.  The refresh must see the
+// into the anchor and records `ev_anchor_done`; the main stream waits for that event only in front of the first
+// launch that consumes the refreshed anchor: the NEXT pull-back -- on the default route, where the kernels that form
+// the gradients apply step and pull-back themselves, the first updating launch of the round's tau-th step (the
+// output layer's gradient kernel, or the weight-gradient launch that hosts its workgroups), after that step's
+// forward and delta kernels.  The refresh must see the
 // round-boundary models while the next round already updates them, so the first update after a refresh
 // is written out-of-place into the second replica buffer (same HBM traffic) and the buffers swap roles;
 // without a second buffer that first update waits for the refresh instead.
@@ -75,7 +78,8 @@ struct ols_ctx {
     // schedule
     int64_t k = 0;
     bool pull_due = false, pending_update = false, anchor_due = false, anchor_inflight = false,
-         first_after_anchor = false, anchor_precomputed = false, next_waited = false, pulled_in_step = false;
+         first_after_anchor = false, anchor_precomputed = false, next_waited = false, pulled_in_step = false,
+         wait_before_update = false;   // the in-flight refresh must land before the step's first updating launch
     hipEvent_t ev_pulled = nullptr, ev_anchor_done = nullptr;
     // model
     int model = MODEL_NONE, B = 0, gemm_dtype = 0;
@@ -199,6 +203,16 @@ int main_waits_for_anchor(ols_ctx* c) {
     return OLS_OK;
 }
 
+// Issued immediately before the first launch of a local step that reads the anchor (pull-back) or overwrites
+// parameters the refresh may still be reading: everything before it in the step only reads the models, so the
+// refresh gets the whole tau steps of compute the paper's schedule allows (Section 2, the sentence after the
+// anchor update rule).
+int wait_if_update_must(ols_ctx* c) {
+    if (!c->wait_before_update) return OLS_OK;
+    c->wait_before_update = false;
+    return main_waits_for_anchor(c);
+}
+
 int64_t align256(int64_t v) { return round_up(v, 256); }
 
 // Static model workspace for callers that cannot allocate (ols_run_steps_static).  One copy per GPU, held until the
@@ -285,6 +299,7 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
         float* loss = (float*)(c->ws + c->off_loss);
         if (upd) {   // small problem: one launch forms the gradient and applies the step
             const FusedUpdate u = *upd;
+            if (int rc = wait_if_update_must(c)) return rc;
             return enqueue(c, OLS_K_LSQ_STEP, 0, src_buf, dst_buf, [&](hipStream_t s) {
                 return launch_lsq_step(c->X, c->xs, (const float*)c->y, c->ys, loss, m, B, c->d, u, s);
             });
@@ -366,6 +381,9 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
     // (nothing between here and there reads the output layer's parameters) or get a kernel of their own.
     const bool guest = c->head_dw_guest && L >= 2;
     if (!guest) {
+        if (upd) {
+            if ((rc = wait_if_update_must(c))) return rc;
+        }
         rc = enqueue(c, OLS_K_HEAD_BWD, 0, src_buf, upd ? dst_buf : -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); });
         if (rc) return rc;
     }
@@ -420,6 +438,9 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
         gw.M = c->dims[l];
         gw.N = c->dims[l + 1];
         gw.K = B;
+        if (upd) {   // first updating launch when the output layer's gradients ride in it
+            if ((rc = wait_if_update_must(c))) return rc;
+        }
         rc = enqueue(c, OLS_K_GEMM_DW, 0, upd ? src_buf : -1, upd ? dst_buf : -1,
                      [&](hipStream_t s) { return bf ? launch_gemm_bf16_dw(gw, s, c->gemm_variant[1]) : launch_gemm_f32_dw(gw, s, c->gemm_variant[1]); });
         if (rc) return rc;
@@ -445,14 +466,18 @@ UpdateArgs update_args(ols_ctx* c, int src, int dst, bool pull) {
     return u;
 }
 
-// Chooses source / destination replica buffers for an update that rewrites the parameters.
-int pick_buffers(ols_ctx* c, int* src, int* dst) {
+// Chooses source / destination replica buffers for an update that rewrites the parameters.  Where the write is in
+// place while the refresh may still be reading, the main stream waits: at once, or (defer) in front of the step's first
+// updating launch.
+int pick_buffers(ols_ctx* c, int* src, int* dst, bool defer = false) {
     *src = c->cur;
     *dst = c->cur;
     if (c->first_after_anchor) {
         c->first_after_anchor = false;
         if (c->x[1] && !c->serialize) {
             *dst = 1 - c->cur;  // the side stream may still be reading x[cur]
+        } else if (defer) {
+            c->wait_before_update = c->anchor_inflight;
         } else {
             int rc = main_waits_for_anchor(c);  // in-place write must not overtake the refresh
             if (rc) return rc;
@@ -558,7 +583,7 @@ int ols_init_params(ols_handle c, const float* x0) {
     }
     c->k = 0;
     c->pull_due = c->pending_update = c->anchor_due = c->anchor_inflight = c->first_after_anchor = false;
-    c->anchor_precomputed = c->pulled_in_step = false;
+    c->anchor_precomputed = c->pulled_in_step = c->wait_before_update = false;
     c->inited = true;
     return OLS_OK;
 }
@@ -721,13 +746,12 @@ int ols_local_step(ols_handle c) {
     const bool paper_sync = c->mix_w == nullptr && c->snap == nullptr;
     const bool grad_kernels_update = c->model == MODEL_MLP || (c->model == MODEL_LSQ && lsq_step_fits(c->B, c->d));
     if (grad_kernels_update && c->fuse_gemm_update && !(boundary && c->fuse_mean && paper_sync)) {
-        // the gradient kernels apply the update themselves; on a boundary step the pull-back as well,
-        // so the anchor of the previous round must have landed before they start
+        // the gradient kernels apply the update themselves; on a boundary step the pull-back as well, so the
+        // anchor of the previous round must have landed before the first of them that updates starts -- not before
+        // the forward pass, the output layer's forward kernel and the delta GEMMs, which only read the models
         int src, dst;
-        if (int rc = pick_buffers(c, &src, &dst)) return rc;
-        if (boundary && paper_sync) {
-            if (int rc = main_waits_for_anchor(c)) return rc;
-        }
+        if (int rc = pick_buffers(c, &src, &dst, true)) return rc;
+        if (boundary && paper_sync && c->anchor_inflight) c->wait_before_update = true;
         FusedUpdate u = {};
         u.x_in = c->x[src];
         u.x_out = c->x[dst];
@@ -742,6 +766,7 @@ int ols_local_step(ols_handle c) {
         u.pull = (boundary && paper_sync) ? 1 : 0;
         u.enabled = 1;
         if (int rc = compute_gradients(c, &u, src, dst)) return rc;
+        if (int rc = wait_if_update_must(c)) return rc;   // (a model without an updating launch: nothing to defer to)
         c->cur = dst;
         c->k += 1;
         if (boundary) {

@@ -334,9 +334,50 @@ def test_fused_update_uses_second_buffer_after_refresh():
     B.ols_local_step(h)
     tr = [t for t in B.ols_trace(h) if B.ols_kernel_name(t["kind"]) in ("gemm_dw", "mean")]
     bufs = [(B.ols_kernel_name(t["kind"]), t["src_buf"], t["dst_buf"], t["waited"]) for t in tr]
+    # the boundary step of round 2 pulls toward the anchor of round 1's refresh: its updating launch waits for it
     assert bufs == [("gemm_dw", 0, 0, 0), ("gemm_dw", 0, 0, 0), ("mean", 0, -1, 1),
-                    ("gemm_dw", 0, 1, 0), ("gemm_dw", 1, 1, 0), ("mean", 1, -1, 1),
+                    ("gemm_dw", 0, 1, 0), ("gemm_dw", 1, 1, 1), ("mean", 1, -1, 1),
                     ("gemm_dw", 1, 0, 0)]
+    B.ols_destroy(h)
+
+
+@pytest.mark.parametrize("tau", [1, 2, 8])
+@pytest.mark.parametrize("guest", [1, 0])
+@pytest.mark.parametrize("alt", [True, False])
+def test_refresh_is_awaited_only_by_the_first_launch_that_needs_it(tau, guest, alt):
+    """Section 2, the sentence after the anchor update rule: the refreshed anchor is needed only by the NEXT pull-back,
+    so the refresh may take tau steps of compute.  On the default route the kernels that form the gradients apply step
+    and pull-back: the wait must sit on the boundary step's first updating launch (the output layer's gradient kernel,
+    or the weight-gradient launch hosting its workgroups) and on no earlier launch of the round -- in particular not
+    on that step's forward, output-layer forward and delta kernels, also when tau = 1.  Without a second replica
+    buffer the first in-place write after a refresh waits instead, again not before that step's forward pass."""
+    dims = [8, 12, 16, 5]
+    d = sum(dims[i] * dims[i + 1] + dims[i + 1] for i in range(3))
+    h = dry(d=d, mu=0.9, tau=tau, alt=alt)
+    B.ols_attach_mlp(h, dims, 8, 0)
+    B.ols_bind_workspace(h, FAKE, B.ols_workspace_bytes(h))
+    B.ols_set_option(h, B.OLS_OPT_HEAD_DW_GUEST, guest)
+    B.ols_init_params(h, FAKE)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_run_steps(h, 3 * tau, FAKE, FAKE, 4)
+    tr = B.ols_trace(h)
+    step_kinds = ["gemm_fwd", "gemm_fwd", "head_fwd"] + ([] if guest else ["head_bwd"]) + ["gemm_da", "gemm_dw", "gemm_dw"]
+    per_round = step_kinds * tau + ["mean"]
+    assert kinds(tr) == per_round * 3
+    first_update = 3                      # index within a step of head_bwd, or of the hosting weight-gradient launch
+    if guest:
+        first_update = step_kinds.index("gemm_dw")
+    n = len(per_round)
+    for r in range(3):
+        rnd = tr[r * n:(r + 1) * n]
+        waits = [i for i, t in enumerate(rnd[:-1]) if t["waited"]]
+        if r == 0:
+            assert waits == []                                   # nothing in flight yet
+        elif alt:
+            assert waits == [(tau - 1) * len(step_kinds) + first_update]   # the boundary step's first updating launch
+        else:
+            assert waits == [first_update]                       # the round's first in-place write
+        assert rnd[-1]["stream"] == 1 and rnd[-1]["waited"] == 1  # the refresh itself waits for the pull
     B.ols_destroy(h)
 
 

@@ -298,3 +298,28 @@ def test_bf16_full_tile_kernel_matches_bounds_checked_kernel_bit_for_bit():
             states.append((s.all_params(), s.params(-1), np.array(losses)))
     for a, b in zip(states[0], states[1]):
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("dtype,dims,batch", [("f32", (96, 64, 40, 10), 36), ("bf16", (128, 72, 64, 10), 40)])
+@pytest.mark.parametrize("tau,second_buffer,guest", [(1, True, 1), (1, False, 1), (2, True, 1), (2, True, 0), (3, False, 0)])
+def test_late_refresh_is_awaited_by_the_first_updating_launch(dtype, dims, batch, tau, second_buffer, guest):
+    """The main stream waits for the anchor refresh only in front of the first launch of a step that pulls toward the
+    anchor or overwrites what the refresh reads (not in front of that step's forward and delta kernels).  With the
+    refresh held back by an emulated latency far longer than a step, any launch that needed the wait and did not get
+    it would read a stale anchor or overwrite the models under the refresh: the overlapped schedule must still leave
+    exactly the bits of the serialised one."""
+    m, K = 3, 3 * tau + 1
+    cfg, X, labels, x0 = small_mlp_case(m, dims, batch, 2, seed=1212)
+    states = []
+    for serialize, delay in ((0, 3000), (1, 0)):
+        with make_session(m, cfg.d, tau, 0.6, 0.05, 0.9, overlap_buffer=second_buffer) as s:
+            s.set_option(B.OLS_OPT_SERIALIZE, serialize)
+            s.set_option(B.OLS_OPT_ANCHOR_DELAY_US, delay)
+            s.set_option(B.OLS_OPT_HEAD_DW_GUEST, guest)
+            s.attach_mlp(dims, batch, dtype)
+            Xd, yd = s.upload(X), s.upload(labels)
+            s.init_params(x0)
+            s.run_resident(K, Xd, yd)
+            states.append((s.all_params(), s.params(-1), s.momentum(), s.losses()))
+    for a, b in zip(states[0], states[1]):
+        assert np.array_equal(a, b)
