@@ -1,13 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the Overlap Local-SGD hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--side-configs 1,2,3,5]
 
-A step is one iteration of the whole hot path for all m workers (per-worker forward/backward, local
-momentum step, and on every tau-th step the pull-back and the overlapped anchor refresh) on synthetic
-CIFAR-10-shaped inputs already resident in HBM.  Prints ONE JSON line: worker-iterations/s, the
-roofline of the dominant kernel from HIP-event timing on the kernel's own stream, and the CPU oracle
-timed on a bounded sample of the same workload as a reported baseline.
+A step is one iteration of the whole hot path for all m workers (the gradient of the iteration -- per-worker
+forward/backward of the attached model, or the caller's gradient tensor on the update-only stream --, the local
+momentum step, and on every tau-th step the pull-back and the anchor refresh) on synthetic inputs already resident in
+HBM.  The headline workload is configuration 4, the update-only stream (m = 16 replicas of a ResNet-18-sized vector):
+it is the one the metric's "fused update / anchor-average HBM GB/s" is defined on.  Prints ONE JSON line:
+worker-iterations/s over exactly K timed steps after exactly W warm-up steps, the roofline of the dominant kernel
+from HIP-event timing on the kernel's own stream, the CPU oracle timed on a bounded sample of the same workload as a
+reported baseline, and under "configs" one compact record per other configuration (its own run length, stated in
+the record): ms per step overlapped and serialised, the dominant kernel and its roofline fraction, the oracle's rate.
 """
 import argparse
 import json
@@ -29,7 +33,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=2, help="workload number (BASELINE configs are 1-based)")
+    ap.add_argument("--config", type=int, default=4, help="headline workload number (BASELINE configs are 1-based)")
+    ap.add_argument("--side-configs", type=str, default=None,
+                    help="comma-separated configurations measured after the headline and reported under \"configs\" "
+                         "(default: 1,2,3,5 when the headline is configuration 4 with default options, else none)")
+    ap.add_argument("--side-cpu-seconds", type=float, default=3.0,
+                    help="target CPU time of the oracle baseline of each side configuration (at least one round)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
     ap.add_argument("--serialize", type=int, default=0, help="1: anchor refresh on the main stream (no overlap)")
     ap.add_argument("--fuse-mean", type=int, default=None,
@@ -126,7 +135,9 @@ def build_workload(cfg, sess, torch):
 
 
 def cpu_baseline(cfg, host_inputs, seconds):
-    """The oracle as it stands, timed on this machine's host cores on a prefix of the same workload."""
+    """The oracle as it stands, timed on this machine's host cores on a prefix of the same workload: one round to
+    calibrate, then as many rounds as fit `seconds` (the calibration round itself where one round already takes
+    longer)."""
     from oracle import workloads as OW
     from ols_inputs import generate as G
     try:
@@ -148,14 +159,15 @@ def cpu_baseline(cfg, host_inputs, seconds):
         grads = [G.stream_gradient(cfg, j, d=d_eff) for j in range(cfg.grad_pool)]
         grad_fn = OW.stream_grad_fn(grads)
         m_eff = cfg.m
-    # one round to calibrate, then as many rounds as fit the time budget
     t0 = time.perf_counter()
     OW.run_config(cfg, x0, grad_fn, K=cfg.tau)
-    per_round = time.perf_counter() - t0
-    rounds = int(max(1, min(cfg.rounds, seconds / max(per_round, 1e-6))))
-    t0 = time.perf_counter()
-    OW.run_config(cfg, x0, grad_fn, K=rounds * cfg.tau)
     dt = time.perf_counter() - t0
+    rounds = 1
+    if dt < 0.5 * seconds:
+        rounds = int(max(1, min(cfg.rounds, seconds / max(dt, 1e-6))))
+        t0 = time.perf_counter()
+        OW.run_config(cfg, x0, grad_fn, K=rounds * cfg.tau)
+        dt = time.perf_counter() - t0
     value = m_eff * rounds * cfg.tau / dt * (d_eff / cfg.d)
     sample = "first %d iterations (%d rounds) of the workload, all %d workers" % (rounds * cfg.tau, rounds, cfg.m)
     if d_eff != cfg.d:
@@ -164,53 +176,56 @@ def cpu_baseline(cfg, host_inputs, seconds):
             "seconds": dt}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the m workers are replicas inside one MI355X); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def mixing_matrix_input(cfg, which):
+    """The caller's W for --mixing: an INPUT of the path; only its entries are written here."""
+    Wm = np.zeros((cfg.m + 1, cfg.m + 1), np.float32)
+    if which == "paper":      # Section 2, matrix-form update rule
+        Wm[:cfg.m, :cfg.m] = (1.0 - cfg.alpha) * np.eye(cfg.m)
+        Wm[:cfg.m, cfg.m] = (1.0 - cfg.alpha) / cfg.m
+        Wm[cfg.m, :] = cfg.alpha
+    else:                     # Local SGD's periodic averaging (first display of Section 2)
+        Wm[:cfg.m, :] = 1.0 / cfg.m
+    return Wm
+
+
+def measure(idx, args, K, W, cpu_seconds, side):
+    """One configuration: W untimed steps, K timed steps (host clock around stream drains), a second pass of K steps
+    with HIP events around every launch for the per-kernel figures, then the schedule variants (same K and W) and the
+    oracle.  `side`: a record for the "configs" key -- default options, variants always measured."""
     import torch
     import ols_inputs as I
     from paper_2002_09539_amd import binding as B
     from paper_2002_09539_amd.session import Session
 
-    cfg = I.get(args.config)
-    if args.fuse_mean is None:
-        args.fuse_mean = 1 if (cfg.kind == "stream" and not args.serialize and args.mixing == "none"
-                               and not args.anchor_delay_us and args.sync_rule == "paper") else 0
-    # Defaults: at least the configuration's own iteration count and about a second of timed work; the warm-up covers
-    # every resident batch once and lets the clocks settle (with 8 warm-up steps configuration 2 measured 0.195 ms per
-    # step over the next 200, with 200 warm-up steps 0.185 ms; longer runs stay at 0.185).
-    K = args.steps if args.steps is not None else max(cfg.K, 1000)
-    W = args.warmup if args.warmup is not None else max(200, 2 * max(cfg.nb, 1))
-    K = max(cfg.tau, K // cfg.tau * cfg.tau)     # whole rounds, so every timed region ends on a refresh
-    W = max(cfg.tau, W // cfg.tau * cfg.tau)
+    cfg = I.get(idx)
+    serialize = 0 if side else args.serialize
+    mixing = "none" if side else args.mixing
+    delay = 0 if side else args.anchor_delay_us
+    sync_rule = "paper" if side else args.sync_rule
+    fuse_gemm_update = 1 if side else args.fuse_gemm_update
+    second_buffer = True if side else not args.no_second_buffer
+    fuse_mean = None if side else args.fuse_mean
+    plain = not serialize and mixing == "none" and not delay and sync_rule == "paper"
+    if fuse_mean is None:
+        fuse_mean = 1 if (cfg.kind == "stream" and plain) else 0
 
     sess = Session(cfg.m, cfg.d, cfg.tau, cfg.alpha, cfg.gamma, cfg.mu,
-                   overlap_buffer=not args.no_second_buffer, own_gradient=cfg.kind != "stream")
+                   overlap_buffer=second_buffer, own_gradient=cfg.kind != "stream")
     sess.set_option(B.OLS_OPT_NESTEROV, int(cfg.nesterov))
-    sess.set_option(B.OLS_OPT_SERIALIZE, args.serialize)
-    sess.set_option(B.OLS_OPT_FUSE_MEAN, args.fuse_mean)
-    sess.set_option(B.OLS_OPT_ANCHOR_DELAY_US, args.anchor_delay_us)
-    sess.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, args.fuse_gemm_update)
-    for kv in args.opt:
-        key, val = kv.split("=")
-        sess.set_option(int(key), int(val))
+    sess.set_option(B.OLS_OPT_SERIALIZE, serialize)
+    sess.set_option(B.OLS_OPT_FUSE_MEAN, fuse_mean)
+    sess.set_option(B.OLS_OPT_ANCHOR_DELAY_US, delay)
+    sess.set_option(B.OLS_OPT_FUSE_GEMM_UPDATE, fuse_gemm_update)
+    if not side:
+        for kv in args.opt:
+            key, val = kv.split("=")
+            sess.set_option(int(key), int(val))
     feed, host_inputs, resident = build_workload(cfg, sess, torch)
-    if args.loop == "python":
+    if not side and args.loop == "python":
         resident = None
-    if args.mixing != "none":
-        # the matrix is an INPUT of the path (the caller's choice of W); only its entries are written here
-        Wm = np.zeros((cfg.m + 1, cfg.m + 1), np.float32)
-        if args.mixing == "paper":      # Section 2, matrix-form update rule
-            Wm[:cfg.m, :cfg.m] = (1.0 - cfg.alpha) * np.eye(cfg.m)
-            Wm[:cfg.m, cfg.m] = (1.0 - cfg.alpha) / cfg.m
-            Wm[cfg.m, :] = cfg.alpha
-        else:                           # Local SGD's periodic averaging (first display of Section 2)
-            Wm[:cfg.m, :] = 1.0 / cfg.m
-        sess.set_mixing(Wm)
-    if args.sync_rule != "paper":
+    if mixing != "none":
+        sess.set_mixing(mixing_matrix_input(cfg, mixing))
+    if sync_rule != "paper":
         sess.set_stale_average()
 
     def region(steps):
@@ -225,7 +240,13 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    if args.calibration_copy_mib > 0:
+    def finish_round():
+        """Untimed: completes the current round, so that options that may not change in mid-round can."""
+        k = B.ols_iteration(sess.h)
+        if k % cfg.tau:
+            region(cfg.tau - k % cfg.tau)
+
+    if not side and args.calibration_copy_mib > 0:
         n = args.calibration_copy_mib * (1 << 20) // 4
         src = torch.ones(n, dtype=torch.float32, device=sess.device)
         dst = torch.empty_like(src)
@@ -234,17 +255,18 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    region(W)
+    if W > 0:
+        region(W)
     elapsed = region(K)
     value = cfg.m * K / elapsed
 
     kernels, roofline = {}, None
-    if not args.no_kernel_timing:
+    if side or not args.no_kernel_timing:
         sess.set_option(B.OLS_OPT_KERNEL_TIMING, 1)
         timed_elapsed = region(K)
         stats = sess.kernel_stats()
         sess.set_option(B.OLS_OPT_KERNEL_TIMING, 0)
-        work = algorithmic_work(cfg, sess.ld, fused_update=bool(args.fuse_gemm_update) and not args.fuse_mean)
+        work = algorithmic_work(cfg, sess.ld, fused_update=bool(fuse_gemm_update) and not fuse_mean)
         for name, (n, ms) in stats.items():
             entry = {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms}
             if name in work:
@@ -264,41 +286,124 @@ def main():
         if ranked:
             dom = ranked[-1][1]
             e = kernels[dom]
+            # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (counters cannot be
+            # read from inside this process); null when the summary does not cover the kernel
             traffic = None
             tpath = os.path.join(ROOT, "profiles", "traffic.json")
-            if os.path.exists(tpath):
-                traffic = json.load(open(tpath)).get("cfg%d" % args.config, {}).get(dom)
+            if os.path.exists(tpath) and plain:
+                traffic = json.load(open(tpath)).get("cfg%d" % idx, {}).get(dom)
             roofline = {"kernel": dom, "bound": e["bound"], "achieved": e["achieved"], "peak": e["peak"],
                         "unit": e["unit"], "frac": e["frac"], "traffic": traffic,
+                        "traffic_source": "profiles/hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)" if traffic else None,
                         "avg_launch_us": e["avg_us"], "algorithmic_per_launch": e["per_launch"]}
         kernels["_region_ms_with_event_timing"] = 1e3 * timed_elapsed
 
-    base = cpu_baseline(cfg, host_inputs, args.cpu_seconds) if args.cpu_seconds > 0 and args.sync_rule == "paper" else None
+    # the other schedules of the same workload, same K and W: the refresh on the side stream beside the next round
+    # (overlapped), and on the main stream (serialised)
+    variants = {}
+    if plain and (side or not args.no_kernel_timing):
+        finish_round()
+        for name, (fm, ser) in (("overlapped_side_stream", (0, 0)), ("serialized", (0, 1))):
+            if fm == fuse_mean and ser == serialize:
+                variants[name] = 1e3 * elapsed / K
+                continue
+            sess.set_option(B.OLS_OPT_FUSE_MEAN, fm)
+            sess.set_option(B.OLS_OPT_SERIALIZE, ser)
+            if W > 0:
+                region(W)
+            variants[name] = 1e3 * region(K) / K
+            finish_round()
+        sess.set_option(B.OLS_OPT_FUSE_MEAN, fuse_mean)
+        sess.set_option(B.OLS_OPT_SERIALIZE, serialize)
+        if fuse_mean:
+            variants["fused_step_pull_mean"] = 1e3 * elapsed / K
+
+    base = cpu_baseline(cfg, host_inputs, cpu_seconds) if cpu_seconds > 0 and sync_rule == "paper" else None
     sess.close()
+    del sess, feed, resident, host_inputs
+    torch.cuda.empty_cache()
+
+    config = {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
+              "dims": list(cfg.dims), "sync_rule": sync_rule,
+              "overlap": ("mixing-kernel:" + mixing) if mixing != "none" else
+              ("serialized" if serialize else ("fused-mean" if fuse_mean else "side-stream")),
+              "second_buffer": second_buffer, "anchor_delay_us": delay,
+              "loop": "library" if cfg.kind != "stream" and not (not side and args.loop == "python") else "python",
+              "update": "in-gradient-kernels" if (fuse_gemm_update and cfg.kind != "stream") else "streaming"}
+    return {"cfg": cfg, "value": value, "steps": K, "warmup": W, "ms_per_step": 1e3 * elapsed / K,
+            "dtype": cfg.gemm_dtype if cfg.kind == "mlp" else "f32", "config": config, "roofline": roofline,
+            "cpu_baseline": base, "kernels": kernels, "ms_per_step_by_schedule": variants}
+
+
+def compact(rec):
+    """The record of a side configuration under "configs"."""
+    r = rec["roofline"] or {}
+    return {"workload": rec["config"]["workload"], "dtype": rec["dtype"], "steps": rec["steps"], "warmup": rec["warmup"],
+            "ms_per_step": rec["ms_per_step"], "worker_iterations_per_s": rec["value"],
+            "ms_per_step_by_schedule": rec["ms_per_step_by_schedule"], "default_schedule": rec["config"]["overlap"],
+            "dominant_kernel": r.get("kernel"), "bound": r.get("bound"), "frac": r.get("frac"),
+            "achieved": r.get("achieved"), "unit": r.get("unit"), "avg_launch_us": r.get("avg_launch_us"),
+            "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in rec["kernels"].items() if isinstance(v, dict)},
+            "kernels_frac": {k: round(v["frac"], 4) for k, v in rec["kernels"].items() if isinstance(v, dict) and "frac" in v},
+            "oracle_worker_iterations_per_s": None if rec["cpu_baseline"] is None else rec["cpu_baseline"]["value"],
+            "oracle_sample": None if rec["cpu_baseline"] is None else rec["cpu_baseline"]["sample"]}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the m workers are replicas inside one MI355X); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import ols_inputs as I
+
+    cfg = I.get(args.config)
+    # Defaults: at least the configuration's own iteration count and about a second of timed work; the warm-up covers
+    # every resident batch once and lets the clocks settle.  --steps and --warmup are honoured exactly as given (a
+    # region may begin and end in mid-round: K consecutive steps contain K / tau synchronisations wherever they start).
+    K = args.steps if args.steps is not None else max(cfg.K, 1000)
+    W = args.warmup if args.warmup is not None else max(200, 2 * max(cfg.nb, 1))
+    if K < 1 or W < 0:
+        print("bench.py: --steps must be >= 1 and --warmup >= 0", file=sys.stderr)
+        sys.exit(2)
+    default_options = (not args.serialize and args.fuse_mean is None and args.mixing == "none" and not args.anchor_delay_us
+                       and args.sync_rule == "paper" and args.fuse_gemm_update == 1 and not args.no_second_buffer
+                       and not args.opt and args.loop == "library" and not args.no_kernel_timing
+                       and not args.calibration_copy_mib)
+    if args.side_configs is None:
+        sides = [1, 2, 3, 5] if (args.config == 4 and default_options) else []
+    else:
+        sides = [int(t) for t in args.side_configs.split(",") if t.strip()]
+
+    head = measure(args.config, args, K, W, args.cpu_seconds, side=False)
+    configs = {}
+    for idx in sides:
+        c = I.get(idx)
+        # run length of a side record: the configuration's own iteration count, at least 1000 steps; 200 warm-up steps
+        try:
+            configs[c.name] = compact(measure(idx, args, max(c.K, 1000), 200, args.side_cpu_seconds, side=True))
+        except Exception as exc:   # a side record must not cost the headline
+            configs[c.name] = {"workload": c.name, "error": "%s: %s" % (type(exc).__name__, exc)}
 
     out = {
         "metric": "worker-iterations/sec at m replicas",
-        "value": value,
+        "value": head["value"],
         "unit": "worker-iterations/s",
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
-        "ms_per_step": 1e3 * elapsed / K,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": cfg.gemm_dtype if cfg.kind == "mlp" else "f32",
+        "dtype": head["dtype"],
         "data": "synthetic",
-        "config": {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
-                   "dims": list(cfg.dims), "sync_rule": args.sync_rule,
-                   "overlap": ("mixing-kernel:" + args.mixing) if args.mixing != "none" else
-                   ("serialized" if args.serialize else ("fused-mean" if args.fuse_mean else "side-stream")),
-                   "second_buffer": not args.no_second_buffer, "anchor_delay_us": args.anchor_delay_us,
-                   "loop": "library" if resident is not None else "python",
-                   "update": "in-gradient-kernels" if (args.fuse_gemm_update and cfg.kind == "mlp") else "streaming"},
-        "roofline": roofline,
-        "cpu_baseline": base,
-        "kernels": kernels,
+        "config": head["config"],
+        "roofline": head["roofline"],
+        "cpu_baseline": head["cpu_baseline"],
+        "ms_per_step_by_schedule": head["ms_per_step_by_schedule"],
+        "kernels": head["kernels"],
+        "configs": configs,
     }
     print(json.dumps(out))
 
