@@ -73,9 +73,14 @@ enum {
                                   owns a parameter column across all m replicas); ols_anchor_update_async then
                                   only publishes it.  Removes the separate reduction instead of hiding it.
                                   default 0                                                                   */
-    OLS_OPT_GEMM_VARIANT_FWD = 9,  /* tile-shape variant of the forward / weight-gradient / delta GEMM kernels; */
-    OLS_OPT_GEMM_VARIANT_DW = 10,  /* 0 (default) is the tuned choice, other values exist for re-measurement;  */
-    OLS_OPT_GEMM_VARIANT_DA = 11,  /* an unknown variant makes the next local step fail with OLS_EHIP          */
+    OLS_OPT_TUNING = 9,            /* TUNING, UNSTABLE -- not part of the interface a caller should rely on.  Selects a
+                                      tile-shape variant of one GEMM kernel for re-measurement: value = 256 * which +
+                                      variant, which = 0 forward, 1 weight gradient, 2 delta GEMM; variant 0 (default)
+                                      lets the library choose from the shape.  The default build carries only the
+                                      variants that choice can pick (bit-identical among themselves where tests say
+                                      so); building with -DOLS_TUNING_VARIANTS adds the others.  A variant the build
+                                      does not carry makes the next local step fail with OLS_EHIP.  (Keys 10 and 11
+                                      are unused.)                                                                 */
     OLS_OPT_GEMM_SPLITK = 12,      /* fp32 forward GEMM: K ranges per output tile where the shape calls for
                                       splitting (0 = from the shape, 1 = never, up to 8)                       */
     OLS_OPT_FUSE_GEMM_UPDATE = 13, /* 1 (default): with an attached MLP (or a least-squares model of at most 64 samples
@@ -232,20 +237,33 @@ OLS_API int ols_set_gradient(ols_handle h, float* g_dev);
 
 /* ---- the iteration --------------------------------------------------------------------------- */
 
-/* Iteration k for every worker: gradients of the attached model at x_k^{(i)} on the current batch,
- * then the local (momentum) step; k <- k + 1.  When the new k is a multiple of tau a pull is due:
- * with OLS_OPT_FUSE_PULL the parameter write is left pending for ols_sync_pull.
+/* Iteration k for every worker -- the FIRST update rule of Section 2 ("Proposed Algorithm"),
+ *     x_{k+1/2}^{(i)} = x_k^{(i)} - gamma g_i(x_k^{(i)}; xi_k^{(i)}),
+ * with the local momentum of the "Momentum Variant" paragraph when beta > 0 (buffer fed by the local gradient
+ * only): the stochastic gradients of the attached model at x_k^{(i)} on the current mini-batch (or the caller's
+ * gradient tensor), then the step; k <- k + 1.  When the new k is a multiple of tau a pull-back is due.  On the
+ * default route (OLS_OPT_FUSE_GEMM_UPDATE with an attached model) the kernels that form the gradients apply the
+ * step, and on that tau-th step also the pull-back toward z_k, where each gradient element is produced; the main
+ * stream waits for the previous round's anchor refresh only in front of the first such launch.  Otherwise, with
+ * OLS_OPT_FUSE_PULL, the tau-th step's parameter write is left pending for ols_sync_pull.
  * OLS_ESTATE if unbound / uninitialised, if a pull or an anchor refresh is due, or if a model is
  * attached but no batch or workspace is set. */
 OLS_API int ols_local_step(ols_handle h);
 
-/* Pull-back of every replica toward the anchor z_k (the anchor produced by the PREVIOUS round's
- * refresh; the main stream first waits for that refresh if it is still in flight, so the result
- * does not depend on timing).  Legal only when k > 0 and k mod tau == 0 and not yet pulled. */
+/* The SECOND update rule of Section 2, applied when (k+1) mod tau == 0 in the paper's indexing:
+ *     x_{k+1}^{(i)} = x_{k+1/2}^{(i)} - alpha (x_{k+1/2}^{(i)} - z_k)        for every replica,
+ * z_k being the anchor produced by the PREVIOUS round's refresh (the sentence after the anchor update rule: the
+ * average started at iteration a tau is needed only for the models of iteration (a+1) tau).  The main stream first
+ * waits for that refresh if it is still in flight, so the result does not depend on timing.  Where the tau-th
+ * local step already applied the pull-back (default route) the call only marks the models as pulled for the
+ * refresh.  Leaves the momentum buffers untouched.  Legal only when k > 0, k mod tau == 0 and not yet pulled. */
 OLS_API int ols_sync_pull(ols_handle h);
 
-/* Anchor refresh z <- (1/m) sum_i x^{(i)} over the post-pull models, enqueued on the side stream
- * behind the pull and overlapped with the following local steps.  Legal only right after a pull. */
+/* The THIRD update rule of Section 2, the anchor refresh
+ *     z_{k+1} = (1/m) sum_i x_{k+1}^{(i)}        over the POST-pull models
+ * (with ols_set_anchor_momentum: v <- beta_z v + (mean - z), z <- z + v), enqueued on the side stream behind the
+ * pull and overlapped with the following tau local steps -- the non-blocking synchronisation of the paper's
+ * timeline figure, here a reduction over the replica axis in HBM.  Legal only right after a pull. */
 OLS_API int ols_anchor_update_async(ols_handle h);
 
 /* `steps` iterations in the order of the three calls above (ols_local_step; after every tau-th one
@@ -278,7 +296,8 @@ OLS_API int64_t ols_static_workspace_bytes(void);
 
 /* ---- results --------------------------------------------------------------------------------- */
 
-/* Copies d floats: which = 0..m-1 a replica, -1 the anchor z.  which = -2 computes the replica mean
+/* Reads the iterates of Section 2: which = 0..m-1 the local model x_k^{(i)} of worker which + 1, -1 the anchor
+ * z_k (the paper does not say which of them "the model" is; both are exposed).  Copies d floats.  which = -2 computes the replica mean
  * (1/m) sum_i x^{(i)} into dst, which must then be a 256-byte aligned DEVICE buffer of
  * ols_row_stride(d) floats.  Drains both streams first (synchronous).  OLS_ESTATE while a fused pull
  * is pending.  dst_is_device selects the kind of dst. */

@@ -11,9 +11,10 @@ LIB_PATH = os.environ.get("OLS_LIBRARY", os.path.join(HERE, "libols.so"))   # ov
 
 OLS_OK, OLS_EINVAL, OLS_ESTATE, OLS_EHIP, OLS_ENOMEM = 0, -1, -2, -3, -4
 (OLS_OPT_NESTEROV, OLS_OPT_FUSE_PULL, OLS_OPT_SERIALIZE, OLS_OPT_DRY_RUN, OLS_OPT_KERNEL_TIMING, OLS_OPT_TRACE,
- OLS_OPT_MEAN_SPLIT, OLS_OPT_FUSE_MEAN, OLS_OPT_GEMM_VARIANT_FWD, OLS_OPT_GEMM_VARIANT_DW,
- OLS_OPT_GEMM_VARIANT_DA, OLS_OPT_GEMM_SPLITK, OLS_OPT_FUSE_GEMM_UPDATE, OLS_OPT_GEMM_FORCE_GENERAL,
- OLS_OPT_ANCHOR_DELAY_US, OLS_OPT_HEAD_DW_GUEST) = range(1, 17)
+ OLS_OPT_MEAN_SPLIT, OLS_OPT_FUSE_MEAN, OLS_OPT_TUNING) = range(1, 10)
+(OLS_OPT_GEMM_SPLITK, OLS_OPT_FUSE_GEMM_UPDATE, OLS_OPT_GEMM_FORCE_GENERAL, OLS_OPT_ANCHOR_DELAY_US,
+ OLS_OPT_HEAD_DW_GUEST) = range(12, 17)
+TUNE_FWD, TUNE_DW, TUNE_DA = 0, 256, 512    # OLS_OPT_TUNING value = one of these + the variant number
 (OLS_K_INIT, OLS_K_STEP, OLS_K_STEP_PULL, OLS_K_PULL, OLS_K_MEAN, OLS_K_STEP_PULL_MEAN, OLS_K_LSQ_RESID,
  OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_MIX,
  OLS_K_CAST, OLS_K_DELAY, OLS_K_LSQ_STEP, OLS_K_STALE_SYNC, OLS_K_COUNT) = range(19)

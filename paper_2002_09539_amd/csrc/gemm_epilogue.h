@@ -25,10 +25,7 @@ struct DwOut {
     int64_t col_base;  // w_off: position of element (0, 0) inside the replica row
 };
 
-__device__ __forceinline__ unsigned int ep_bf16(float f) {
-    const unsigned int u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
+__device__ __forceinline__ unsigned int ep_bf16(float f) { return bf16_bits_rne(f); }
 
 #ifndef OLS_EPILOGUE_NONTEMPORAL
 #define OLS_EPILOGUE_NONTEMPORAL 1
@@ -46,18 +43,12 @@ __device__ __forceinline__ void dw_consume(const DwOut& o, int N, int row, int c
     const FusedUpdate& u = o.upd;
     const int64_t off = (int64_t)row * N + col;
     ep_f4 xn, bn = b;
+    const bool mom = u.mu != 0.0f, nest = u.nesterov != 0, pull = u.pull != 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        float xh;
-        if (u.mu != 0.0f) {
-            bn[e] = __fmaf_rn(u.mu, b[e], g[e]);
-            const float dir = u.nesterov ? __fmaf_rn(u.mu, bn[e], g[e]) : bn[e];
-            xh = __fmaf_rn(-u.gamma, dir, x[e]);
-        } else {
-            xh = __fmaf_rn(-u.gamma, g[e], x[e]);
-        }
-        if (u.pull) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, z[e]), xh);
-        xn[e] = xh;
+        float be = bn[e];
+        xn[e] = local_step_elem(g[e], x[e], be, z[e], u.gamma, u.mu, u.alpha, mom, nest, pull);
+        bn[e] = be;
     }
     // the state streams through once per step: non-temporal accesses keep it from displacing the operands in L2
     ep_store_stream((ep_f4*)(u.x_out + o.upd_base + off), xn);

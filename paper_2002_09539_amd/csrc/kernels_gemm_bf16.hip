@@ -49,10 +49,7 @@ enum GemmMode { kFwd = 0, kDw = 1, kDa = 2 };
 constexpr int kThreads = 256;
 constexpr int kXcds = 8;
 
-__device__ __forceinline__ unsigned int bf16_rne(float f) {
-    unsigned int u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
+__device__ __forceinline__ unsigned int bf16_rne(float f) { return bf16_bits_rne(f); }
 __device__ __forceinline__ float bf16_to_f32(unsigned int h) { return __uint_as_float(h << 16); }
 
 struct GemmDevB {
@@ -650,7 +647,7 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
         if (full && !g.force_general) kern = gemm_bf16_full_kernel<MODE, BM, BN, BK, kSets>;
     }
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
     }
     kern<<<(unsigned)(p.guest.blocks + p.chunk * kXcds), kThreads, lds, s>>>(p);
@@ -672,11 +669,13 @@ hipError_t launch_gemm_bf16_dw(const GemmArgs& g, hipStream_t s, int variant) {
     switch (variant) {
         case 0:
         case 1: return gemm_launch<kDw, 64, 128, 32, 1>(g, s);
+#ifdef OLS_TUNING_VARIANTS
         case 6: return gemm_launch<kDw, 128, 128, 32, 1>(g, s);
         case 2: return gemm_launch<kDw, 128, 64, 32, 1>(g, s);
         case 3: return gemm_launch<kDw, 64, 64, 32, 1>(g, s);
         case 4: return gemm_launch<kDw, 128, 128, 64, 1>(g, s);
         case 5: return gemm_launch<kDw, 64, 128, 64, 1>(g, s);
+#endif
         default: return hipErrorInvalidValue;
     }
 }

@@ -496,17 +496,11 @@ void gemm_f32_dw_pipelined_kernel(GemmDev p) {
         const unsigned o = my_off + (unsigned)v * vec_step;
         f4 xn, bn;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {   // the operation sequence of dw_consume
-            float xh;
-            if (MOM) {
-                bn[e] = __fmaf_rn(u.mu, sb[MOM ? set : 0][e], gv[e]);
-                const float dir = u.nesterov ? __fmaf_rn(u.mu, bn[e], gv[e]) : bn[e];
-                xh = __fmaf_rn(-u.gamma, dir, sx[set][e]);
-            } else {
-                xh = __fmaf_rn(-u.gamma, gv[e], sx[set][e]);
-            }
-            if (PULL) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, sz[PULL ? set : 0][e]), xh);
-            xn[e] = xh;
+        for (int e = 0; e < 4; ++e) {
+            float be = MOM ? sb[MOM ? set : 0][e] : 0.0f;
+            xn[e] = local_step_elem(gv[e], sx[set][e], be, PULL ? sz[PULL ? set : 0][e] : 0.0f, u.gamma, u.mu, u.alpha, MOM,
+                                    u.nesterov != 0, PULL);
+            bn[e] = be;
         }
         ep_store_stream((ep_f4*)((char*)(u.x_out + d.upd_base) + o), xn);
         if (MOM) ep_store_stream((ep_f4*)((char*)(u.buf + d.upd_base) + o), bn);
@@ -769,8 +763,7 @@ static hipError_t dw_pipelined_launch(const GemmArgs& g, hipStream_t s) {
 }
 
 // Tile shapes.  Variant 0 is the default (for the forward GEMM: chosen from the shape); the others exist so
-// that the choice can be re-measured
-// (OLS_OPT_GEMM_VARIANT_*).  LDS per workgroup stays below 80 KiB so two workgroups fit a compute unit.
+// that the choice can be re-measured (OLS_OPT_TUNING; most of them only in builds with -DOLS_TUNING_VARIANTS).  LDS per workgroup stays below 80 KiB so two workgroups fit a compute unit.
 // Shape-driven choice for the forward GEMM.  Measured on configuration 2 (M = 128, N = 512, K = 3072,
 // 16 groups): every tile shape lands within a few percent once there are several workgroups per compute
 // unit, because the matrix pipe idles whenever a wavefront waits at the slice barrier or for its loads
@@ -800,15 +793,17 @@ hipError_t launch_gemm_f32_fwd(const GemmArgs& g, hipStream_t s, int variant) {
         gemm_f32_fwd_plan(g.groups, g.M, g.N, g.K, &variant, &sp);
     }
     switch (variant) {
-        case 1: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 2>(g, s);
         case 2: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 2>(g, s);
+        case 6: return gemm_launch<kFwd, 64, 128, 32, 2, 2, 2>(g, s);
+#ifdef OLS_TUNING_VARIANTS
+        case 1: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 2>(g, s);
         case 3: return gemm_launch<kFwd, 64, 64, 32, 2, 2, 1>(g, s);
         case 4: return gemm_launch<kFwd, 64, 64, 64, 2, 2, 1>(g, s);
         case 5: return gemm_launch<kFwd, 128, 64, 32, 2, 2, 2>(g, s);
-        case 6: return gemm_launch<kFwd, 64, 128, 32, 2, 2, 2>(g, s);
         case 7: return gemm_launch<kFwd, 128, 128, 16, 2, 2, 2>(g, s);
         case 8: return gemm_launch<kFwd, 128, 128, 32, 2, 2, 2>(g, s);
         case 9: return gemm_launch<kFwd, 128, 128, 32, 2, 2, 1>(g, s);
+#endif
         default: return hipErrorInvalidValue;
     }
 }
@@ -828,27 +823,31 @@ hipError_t launch_gemm_f32_dw(const GemmArgs& g, hipStream_t s, int variant) {
     }
     switch (variant) {
         case 1: return gemm_launch<kDw, 128, 128, 16, 2, 2, 1>(g, s);
+        case 8: return gemm_launch<kDw, 64, 128, 16, 2, 2, 1>(g, s);
+        case 11: return gemm_launch<kDw, 64, 64, 16, 2, 2, 2>(g, s);
+        case 16: return dw_pipelined_launch(g, s);
+#ifdef OLS_TUNING_VARIANTS
         case 2: return gemm_launch<kDw, 128, 128, 16, 2, 2, 2>(g, s);
         case 3: return gemm_launch<kDw, 128, 128, 32, 2, 2, 2>(g, s);
         case 4: return gemm_launch<kDw, 64, 128, 32, 2, 2, 2>(g, s);
         case 5: return gemm_launch<kDw, 128, 64, 32, 2, 2, 2>(g, s);
         case 6: return gemm_launch<kDw, 64, 64, 32, 2, 2, 2>(g, s);
         case 7: return gemm_launch<kDw, 64, 64, 32, 2, 2, 1>(g, s);
-        case 8: return gemm_launch<kDw, 64, 128, 16, 2, 2, 1>(g, s);
         case 9: return gemm_launch<kDw, 64, 64, 16, 2, 2, 1>(g, s);
         case 10: return gemm_launch<kDw, 128, 64, 16, 2, 2, 1>(g, s);
-        case 11: return gemm_launch<kDw, 64, 64, 16, 2, 2, 2>(g, s);
         case 12: return gemm_launch<kDw, 64, 128, 16, 2, 2, 2>(g, s);
-        case 16: return dw_pipelined_launch(g, s);
+#endif
         default: return hipErrorInvalidValue;
     }
 }
 hipError_t launch_gemm_f32_da(const GemmArgs& g, hipStream_t s, int variant) {
     switch (variant) {
         case 0: return gemm_launch<kDa, 64, 64, 64, 2, 2, 2>(g, s);
+#ifdef OLS_TUNING_VARIANTS
         case 1: return gemm_launch<kDa, 64, 64, 32, 2, 2, 2>(g, s);
         case 2: return gemm_launch<kDa, 64, 64, 32, 2, 2, 1>(g, s);
         case 3: return gemm_launch<kDa, 128, 64, 32, 2, 2, 2>(g, s);
+#endif
         default: return hipErrorInvalidValue;
     }
 }

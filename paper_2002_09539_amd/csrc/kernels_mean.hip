@@ -88,14 +88,15 @@ __global__ __launch_bounds__(THREADS) void mean_kernel(const f4* __restrict__ x,
         const float fm = (float)m;
         f4 mean;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) mean[e] = __fdiv_rn(acc[e], fm);
+        for (int e = 0; e < 4; ++e) mean[e] = anchor_mean_elem(acc[e], fm);
         if (ANCHOR_MOM) {
-            const f4 zo = z[c], vo = v[c];
-            f4 vn, zn;
+            const f4 zo = z[c];
+            f4 vn = v[c], zn;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                vn[e] = __fmaf_rn(beta_z, vo[e], __fsub_rn(mean[e], zo[e]));
-                zn[e] = __fadd_rn(zo[e], vn[e]);
+                float ve = vn[e];
+                zn[e] = anchor_momentum_elem(mean[e], zo[e], ve, beta_z);
+                vn[e] = ve;
             }
             v[c] = vn;
             z[c] = zn;
@@ -183,18 +184,13 @@ __global__ __launch_bounds__(kSpmThreads) void step_pull_mean_kernel(const f4* _
                 f4 xo, bo;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float xh = vx[r][e];
                     if (WITH_STEP) {
-                        if (MOM) {
-                            const float b = __fmaf_rn(mu, vb[r][e], vg[r][e]);
-                            const float dir = NEST ? __fmaf_rn(mu, b, vg[r][e]) : b;
-                            xh = __fmaf_rn(-gamma, dir, xh);
-                            bo[e] = b;
-                        } else {
-                            xh = __fmaf_rn(-gamma, vg[r][e], xh);
-                        }
+                        float b = MOM ? vb[r][e] : 0.0f;
+                        xo[e] = local_step_elem(vg[r][e], vx[r][e], b, zo[e], gamma, mu, alpha, MOM, NEST, true);
+                        bo[e] = b;
+                    } else {
+                        xo[e] = pull_back_elem(vx[r][e], zo[e], alpha);
                     }
-                    xo[e] = __fmaf_rn(-alpha, __fsub_rn(xh, zo[e]), xh);
                 }
                 __builtin_nontemporal_store(xo, x_out + o);
                 if (WITH_STEP && MOM) __builtin_nontemporal_store(bo, buf + o);
@@ -205,14 +201,14 @@ __global__ __launch_bounds__(kSpmThreads) void step_pull_mean_kernel(const f4* _
     const float fm = (float)m;
     f4 mean;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) mean[e] = __fdiv_rn(acc[e], fm);
+    for (int e = 0; e < 4; ++e) mean[e] = anchor_mean_elem(acc[e], fm);
     if (ANCHOR_MOM) {
-        const f4 vo = v[c];
-        f4 vn, zn;
+        f4 vn = v[c], zn;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            vn[e] = __fmaf_rn(beta_z, vo[e], __fsub_rn(mean[e], zo[e]));
-            zn[e] = __fadd_rn(zo[e], vn[e]);
+            float ve = vn[e];
+            zn[e] = anchor_momentum_elem(mean[e], zo[e], ve, beta_z);
+            vn[e] = ve;
         }
         v[c] = vn;
         z_out[c] = zn;

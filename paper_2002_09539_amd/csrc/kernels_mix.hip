@@ -27,10 +27,7 @@ template <> struct Vec<4> { typedef float type __attribute__((ext_vector_type(4)
 template <> struct Vec<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct Vec<1> { typedef float type; };
 
-__device__ __forceinline__ unsigned int mix_bf16(float f) {
-    const unsigned int u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
+__device__ __forceinline__ unsigned int mix_bf16(float f) { return bf16_bits_rne(f); }
 template <int V> __device__ __forceinline__ float vget(const typename Vec<V>::type& v, int e) { return v[e]; }
 template <> __device__ __forceinline__ float vget<1>(const float& v, int) { return v; }
 template <int V> __device__ __forceinline__ void vset(typename Vec<V>::type& v, int e, float f) { v[e] = f; }

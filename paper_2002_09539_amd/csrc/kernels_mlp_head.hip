@@ -30,10 +30,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ unsigned int f32_to_bf16(float f) {
-    const unsigned int u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
+__device__ __forceinline__ unsigned int f32_to_bf16(float f) { return bf16_bits_rne(f); }
 // Sum over the 16 lanes of a DPP row, the same bits in every lane of the row (each step adds a lane's
 // value to that of its partner 8, 4, 2, 1 lanes away, which is symmetric).
 __device__ __forceinline__ float row_sum(float v) {
@@ -293,7 +290,7 @@ static hipError_t head_fwd_launch(const HeadDev& p, int m, hipStream_t s) {
     size_t lds = (size_t)head_fwd_lds_floats(CMAX, KC, THREADS) * sizeof(float);
     auto kern = head_fwd_kernel<BF, CMAX, KC, THREADS>;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
     }
     constexpr int kSamples = THREADS / kRow;

@@ -42,10 +42,7 @@ __device__ __forceinline__ f4 ld_stream(const f4* p) { return *p; }
 __device__ __forceinline__ void st_stream(f4* p, f4 v) { *p = v; }
 #endif
 
-__device__ __forceinline__ unsigned int bf16_rne(float f) {
-    unsigned int u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
+__device__ __forceinline__ unsigned int bf16_rne(float f) { return bf16_bits_rne(f); }
 __device__ __forceinline__ u2 pack_bf16x4(f4 v) {
     u2 r;
     r.x = bf16_rne(v.x) | (bf16_rne(v.y) << 16);
@@ -53,15 +50,6 @@ __device__ __forceinline__ u2 pack_bf16x4(f4 v) {
     return r;
 }
 
-template <bool NEST>
-__device__ __forceinline__ float step_elem(float g, float x, float& b, float gamma, float mu) {
-    b = __fmaf_rn(mu, b, g);
-    const float dir = NEST ? __fmaf_rn(mu, b, g) : b;
-    return __fmaf_rn(-gamma, dir, x);
-}
-__device__ __forceinline__ float pull_elem(float xh, float z, float alpha) {
-    return __fmaf_rn(-alpha, __fsub_rn(xh, z), xh);
-}
 
 // One workgroup per (replica, span of kThreads * kUnroll vectors); the replica is the SLOW part of the
 // linear workgroup id, so consecutive workgroups stream through one row.  Measured alternatives on the
@@ -96,10 +84,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(const f4* __restrict__ g
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float b = MOM ? vb[u][e] : 0.0f;
-                float xh = MOM ? step_elem<NEST>(vg[u][e], vx[u][e], b, gamma, mu)
-                               : __fmaf_rn(-gamma, vg[u][e], vx[u][e]);
-                if (PULL) xh = pull_elem(xh, vz[u][e], alpha);
-                xo[e] = xh;
+                xo[e] = local_step_elem(vg[u][e], vx[u][e], b, PULL ? vz[u][e] : 0.0f, gamma, mu, alpha, MOM, NEST, PULL);
                 bo[e] = b;
             }
             st_stream(x_out + row + c, xo);
@@ -130,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void pull_kernel(f4* x, const f4* __restr
         if (c < n4) {
             f4 xo;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) xo[e] = pull_elem(vx[u][e], vz[u][e], alpha);
+            for (int e = 0; e < 4; ++e) xo[e] = pull_back_elem(vx[u][e], vz[u][e], alpha);
             st_stream(x + row + c, xo);
             if (SHADOW) shadow[row + c] = pack_bf16x4(xo);
         }

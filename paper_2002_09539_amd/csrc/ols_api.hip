@@ -18,6 +18,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -238,6 +239,27 @@ int static_workspace(void** out) {
     *out = scratch_ptr[dev];
     return OLS_OK;
 }
+
+}  // namespace
+
+namespace ols {
+// Kernels whose dynamic LDS exceeds 64 KiB need the limit raised once per (device, kernel), not per launch.
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes) {
+    static std::mutex mu;
+    static std::vector<std::pair<int, const void*>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const auto& d : done)
+        if (d.first == dev && d.second == kernel) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done.emplace_back(dev, kernel);
+    return e;
+}
+}  // namespace ols
+
+namespace {
 
 uint16_t* shadow_ptr(ols_ctx* c) {
     return (c->model == MODEL_MLP && c->gemm_dtype == 1 && c->ws) ? (uint16_t*)(c->ws + c->off_shadow) : nullptr;
@@ -1048,11 +1070,9 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
                 return fail(OLS_EINVAL, "mean split must be 0, 1, 2, 4, 8 or 16");
             c->mean_split = (int)value;
             break;
-        case OLS_OPT_GEMM_VARIANT_FWD:
-        case OLS_OPT_GEMM_VARIANT_DW:
-        case OLS_OPT_GEMM_VARIANT_DA:
-            if (value < 0 || value > 31) return fail(OLS_EINVAL, "GEMM variant out of range");
-            c->gemm_variant[key - OLS_OPT_GEMM_VARIANT_FWD] = (int)value;
+        case OLS_OPT_TUNING:   // unstable: 256 * which + variant
+            if (value < 0 || value / 256 > 2 || value % 256 > 31) return fail(OLS_EINVAL, "tuning value out of range");
+            c->gemm_variant[value / 256] = (int)(value % 256);
             break;
         case OLS_OPT_FUSE_GEMM_UPDATE:
             if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "cannot change fusion in the middle of a synchronisation");

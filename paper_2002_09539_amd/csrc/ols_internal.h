@@ -90,43 +90,23 @@ struct FusedUpdate {
 };
 
 #if defined(__HIPCC__)
-// idx = worker * ld + col (col = position inside the replica row)
-__device__ __forceinline__ void fused_update_apply(const FusedUpdate& u, int64_t idx, int64_t col, float g, float x,
-                                                   float b) {
-    float xh;
-    if (u.mu != 0.0f) {
-        b = __fmaf_rn(u.mu, b, g);
-        const float dir = u.nesterov ? __fmaf_rn(u.mu, b, g) : b;
-        xh = __fmaf_rn(-u.gamma, dir, x);
-        u.buf[idx] = b;
-    } else {
-        xh = __fmaf_rn(-u.gamma, g, x);
-    }
-    if (u.pull) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, u.z[col]), xh);
-    u.x_out[idx] = xh;
-    if (u.shadow) {
-        const unsigned int w = __float_as_uint(xh);
-        u.shadow[idx] = (uint16_t)((w + 0x7FFFu + ((w >> 16) & 1u)) >> 16);
-    }
-}
-// The same with the anchor value passed in as well (all operands were fetched ahead of the gradient).
+}  // namespace ols
+#include "update_rule.h"
+namespace ols {
+// One element with the anchor value passed in (all operands were fetched ahead of the gradient).
+// idx = worker * ld + position inside the replica row.
 __device__ __forceinline__ void fused_update_store(const FusedUpdate& u, int64_t idx, float g, float x, float b,
                                                    float z) {
-    float xh;
-    if (u.mu != 0.0f) {
-        b = __fmaf_rn(u.mu, b, g);
-        const float dir = u.nesterov ? __fmaf_rn(u.mu, b, g) : b;
-        xh = __fmaf_rn(-u.gamma, dir, x);
-        u.buf[idx] = b;
-    } else {
-        xh = __fmaf_rn(-u.gamma, g, x);
-    }
-    if (u.pull) xh = __fmaf_rn(-u.alpha, __fsub_rn(xh, z), xh);
-    u.x_out[idx] = xh;
-    if (u.shadow) {
-        const unsigned int w = __float_as_uint(xh);
-        u.shadow[idx] = (uint16_t)((w + 0x7FFFu + ((w >> 16) & 1u)) >> 16);
-    }
+    const bool mom = u.mu != 0.0f;
+    const float xn = local_step_elem(g, x, b, z, u.gamma, u.mu, u.alpha, mom, u.nesterov != 0, u.pull != 0);
+    if (mom) u.buf[idx] = b;
+    u.x_out[idx] = xn;
+    if (u.shadow) u.shadow[idx] = (uint16_t)bf16_bits_rne(xn);
+}
+// The same with the anchor read here (col = position inside the replica row).
+__device__ __forceinline__ void fused_update_apply(const FusedUpdate& u, int64_t idx, int64_t col, float g, float x,
+                                                   float b) {
+    fused_update_store(u, idx, g, x, b, u.pull ? u.z[col] : 0.0f);
 }
 #endif
 
@@ -189,6 +169,8 @@ struct HeadArgs {
 };
 hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s);
 hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s);
+// raises a kernel's dynamic-LDS limit once per (device, kernel)
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes);
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
 
 }  // namespace ols

@@ -270,7 +270,7 @@ def test_pipelined_weight_gradient_kernel_is_bit_identical(m, dims, batch, tau):
     states = []
     for variant in (16, 11):
         with make_session(m, cfg.d, tau, 0.6, 0.05, 0.9) as s:
-            s.set_option(B.OLS_OPT_GEMM_VARIANT_DW, variant)
+            s.set_option(B.OLS_OPT_TUNING, B.TUNE_DW + variant)
             s.attach_mlp(dims, batch, "f32")
             Xd, yd = s.upload(X), s.upload(labels)
             s.init_params(x0)
