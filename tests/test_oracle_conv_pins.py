@@ -1,0 +1,196 @@
+"""Pins of the convolutional oracle (oracle/conv_oracle.py) to things other than itself: torch's CPU conv2d and
+autograd as library routines, a pure-Python brute-force convolution, single-tap kernels whose result is a shifted copy
+of the input (tap orientation and zero padding), central finite differences of the whole loss, closed forms of the
+classifier head, and planted mistakes that these pins must notice.  No GPU."""
+import numpy as np
+import pytest
+
+from oracle import conv_oracle as CO
+
+
+def rand(shape, seed, scale=1.0):
+    return np.random.default_rng(seed).standard_normal(shape) * scale
+
+
+def brute_force_conv(inp, W, b):
+    """The definition as nested Python loops (tiny inputs only)."""
+    n, H, Wd, cin = inp.shape
+    cout = W.shape[3]
+    out = np.zeros((n, H, Wd, cout))
+    for i in range(n):
+        for y in range(H):
+            for x in range(Wd):
+                for co in range(cout):
+                    acc = b[co]
+                    for kh in range(3):
+                        for kw in range(3):
+                            yy, xx = y + kh - 1, x + kw - 1
+                            if 0 <= yy < H and 0 <= xx < Wd:
+                                for ci in range(cin):
+                                    acc += inp[i, yy, xx, ci] * W[kh, kw, ci, co]
+                    out[i, y, x, co] = acc
+    return out
+
+
+def test_forward_equals_brute_force_loops():
+    inp, W, b = rand((2, 4, 5, 3), 1), rand((3, 3, 3, 2), 2), rand((2,), 3)
+    np.testing.assert_allclose(CO.conv3x3_forward(inp, W, b), brute_force_conv(inp, W, b), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("kh,kw", [(0, 0), (0, 1), (1, 2), (2, 0), (2, 2), (1, 1)])
+def test_single_tap_kernel_is_a_shifted_copy_with_zero_border(kh, kw):
+    """W = identity over channels at one tap: out[y][x] = in[y + kh - 1][x + kw - 1], zero where that leaves the image.
+    A flipped kernel (true convolution), a transposed tap index or a wrong padding fails here."""
+    C, H, Wd = 3, 5, 6
+    inp = rand((2, H, Wd, C), 4)
+    W = np.zeros((3, 3, C, C))
+    W[kh, kw] = np.eye(C)
+    out = CO.conv3x3_forward(inp, W, np.zeros(C))
+    want = np.zeros_like(inp)
+    for y in range(H):
+        for x in range(Wd):
+            yy, xx = y + kh - 1, x + kw - 1
+            if 0 <= yy < H and 0 <= xx < Wd:
+                want[:, y, x, :] = inp[:, yy, xx, :]
+    np.testing.assert_array_equal(out, want)
+
+
+def test_channel_mixing_direction():
+    """Input channel ci feeds output channel co through W[.][.][ci][co] (a transposed operand fails)."""
+    inp = np.zeros((1, 3, 3, 2))
+    inp[0, 1, 1, 0] = 1.0                          # only input channel 0 is lit
+    W = np.zeros((3, 3, 2, 3))
+    W[1, 1, 0, 2] = 5.0                            # ... and feeds output channel 2
+    W[1, 1, 1, 0] = 7.0
+    out = CO.conv3x3_forward(inp, W, np.zeros(3))
+    assert out[0, 1, 1, 2] == 5.0 and out[0, 1, 1, 0] == 0.0 and out[0, 1, 1, 1] == 0.0
+
+
+def test_forward_and_backward_match_torch_conv2d():
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    inp, W, b, dout = rand((3, 6, 5, 4), 5), rand((3, 3, 4, 7), 6), rand((7,), 7), rand((3, 6, 5, 7), 8)
+    ti = torch.tensor(inp).permute(0, 3, 1, 2).requires_grad_(True)        # NCHW
+    tw = torch.tensor(W).permute(3, 2, 0, 1).contiguous().requires_grad_(True)   # [out][in][kh][kw]
+    tb = torch.tensor(b, requires_grad=True)
+    to = F.conv2d(ti, tw, tb, stride=1, padding=1)
+    np.testing.assert_allclose(CO.conv3x3_forward(inp, W, b), to.detach().permute(0, 2, 3, 1).numpy(), atol=1e-12)
+    to.backward(torch.tensor(dout).permute(0, 3, 1, 2))
+    d_inp, dW, db = CO.conv3x3_backward(inp, W, dout)
+    np.testing.assert_allclose(d_inp, ti.grad.permute(0, 2, 3, 1).numpy(), atol=1e-12)
+    np.testing.assert_allclose(dW, tw.grad.permute(2, 3, 1, 0).numpy(), atol=1e-11)
+    np.testing.assert_allclose(db, tb.grad.numpy(), atol=1e-12)
+
+
+def block_case(seed, B=3, C=4, H=5, Wd=4, classes=3):
+    d = CO.convblock_param_count(C, classes)
+    x = rand((d,), seed, 0.3)
+    X = rand((B, H, Wd, C), seed + 1)
+    labels = np.random.default_rng(seed + 2).integers(0, classes, B)
+    return x, C, classes, X, labels
+
+
+def test_block_gradient_matches_central_finite_differences():
+    x, C, classes, X, labels = block_case(10)
+    loss, g = CO.convblock_loss_grad(x, C, classes, X, labels)
+    rng = np.random.default_rng(0)
+    # every parameter group is probed: both kernels, both conv biases, classifier weights and bias
+    Wa, ba, Wb, bb, Wh, bh = CO.convblock_unpack(np.arange(x.size), C, classes)
+    picks = np.concatenate([rng.choice(grp.ravel(), min(6, grp.size), replace=False) for grp in (Wa, ba, Wb, bb, Wh, bh)])
+    eps = 1e-6
+    for j in picks:
+        e = np.zeros_like(x)
+        e[j] = eps
+        fd = (CO.convblock_loss_grad(x + e, C, classes, X, labels)[0] - CO.convblock_loss_grad(x - e, C, classes, X, labels)[0]) / (2 * eps)
+        assert abs(fd - g[j]) <= 1e-7 * max(1.0, abs(g[j])), (j, fd, g[j])
+    assert loss > 0
+
+
+def test_block_matches_torch_autograd_including_the_flat_layout():
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    x, C, classes, X, labels = block_case(20, B=4, C=3, H=4, Wd=6, classes=5)
+    loss, g = CO.convblock_loss_grad(x, C, classes, X, labels)
+    tx = torch.tensor(x, requires_grad=True)
+    off = 0
+
+    def take(shape):
+        nonlocal off
+        n = int(np.prod(shape))
+        t = tx[off:off + n].reshape(shape)
+        off += n
+        return t
+    Wa, ba, Wb, bb, Wh, bh = (take(s) for s in ((3, 3, C, C), (C,), (3, 3, C, C), (C,), (C, classes), (classes,)))
+    tX = torch.tensor(X).permute(0, 3, 1, 2)
+    a1 = F.relu(F.conv2d(tX, Wa.permute(3, 2, 0, 1), ba, padding=1))
+    a2 = F.relu(F.conv2d(a1, Wb.permute(3, 2, 0, 1), bb, padding=1) + tX)
+    logits = a2.mean(dim=(2, 3)) @ Wh + bh
+    tl = F.cross_entropy(logits, torch.tensor(labels), reduction="mean")
+    tl.backward()
+    assert abs(loss - tl.item()) <= 1e-12 * abs(loss)
+    np.testing.assert_allclose(g, tx.grad.numpy(), atol=1e-12)
+
+
+def test_zero_kernels_reduce_the_block_to_the_shortcut():
+    """Wa = Wb = 0, zero biases: a2 = relu(X), the classifier sees the mean of relu(X): a closed form for the loss."""
+    C, classes, B, H, Wd = 3, 4, 2, 3, 3
+    x = np.zeros(CO.convblock_param_count(C, classes))
+    Wa, ba, Wb, bb, Wh, bh = CO.convblock_unpack(x, C, classes)
+    Wh[...] = rand((C, classes), 30)
+    bh[...] = rand((classes,), 31)
+    X = rand((B, H, Wd, C), 32)
+    labels = np.array([1, 3])
+    loss, g = CO.convblock_loss_grad(x, C, classes, X, labels)
+    logits = np.maximum(X, 0).mean(axis=(1, 2)) @ Wh + bh
+    want = np.mean([np.log(np.exp(l).sum()) - l[y] for l, y in zip(logits, labels)])
+    assert abs(loss - want) <= 1e-13
+    # the first convolution feeds only the (zero) second kernel: its gradient vanishes, the second one's does not
+    gWa, gba, gWb, gbb, _, _ = CO.convblock_unpack(g, C, classes)
+    assert not gWa.any() and not gba.any() and np.abs(gbb).max() > 0
+
+
+# ---- the pins have teeth: a plausible mistake planted in the oracle fails one of them ---------------------
+def _flipped_forward(inp, W, b):
+    return _ORIG_FWD(inp, W[::-1, ::-1], b)            # true convolution instead of cross-correlation
+
+
+def _no_padding_shift(inp, W, b):
+    return _ORIG_FWD(np.roll(inp, 1, axis=2), W, b)    # a wrong horizontal offset with wrap-around
+
+
+def _transposed_channels(inp, W, b):
+    return _ORIG_FWD(inp, np.swapaxes(W, 2, 3), b)
+
+
+_ORIG_FWD = CO.conv3x3_forward
+
+
+@pytest.mark.parametrize("broken", [_flipped_forward, _no_padding_shift, _transposed_channels])
+def test_planted_forward_mistakes_are_noticed(monkeypatch, broken):
+    monkeypatch.setattr(CO, "conv3x3_forward", broken)
+    failures = 0
+    for check in (lambda: test_single_tap_kernel_is_a_shifted_copy_with_zero_border(0, 1),
+                  test_forward_and_backward_match_torch_conv2d, test_block_gradient_matches_central_finite_differences):
+        try:
+            check()
+        except (AssertionError, ValueError):      # a shape that no longer fits is a noticed mistake as well
+            failures += 1
+    assert failures >= 1
+
+
+def test_planted_backward_mistakes_are_noticed(monkeypatch):
+    orig = CO.conv3x3_backward
+
+    def no_relu_mask_equivalent(inp, W, dout):          # drops the bias gradient's sum over positions
+        d_inp, dW, db = orig(inp, W, dout)
+        return d_inp, dW, db / 2
+    monkeypatch.setattr(CO, "conv3x3_backward", no_relu_mask_equivalent)
+    with pytest.raises(AssertionError):
+        test_block_gradient_matches_central_finite_differences()
+
+    def swapped_taps(inp, W, dout):
+        d_inp, dW, db = orig(inp, W, dout)
+        return d_inp, dW[::-1, ::-1], db
+    monkeypatch.setattr(CO, "conv3x3_backward", swapped_taps)
+    with pytest.raises(AssertionError):
+        test_block_matches_torch_autograd_including_the_flat_layout()
