@@ -126,7 +126,12 @@ enum {
     OLS_K_DELAY = 15,     /* emulated communication latency (OLS_OPT_ANCHOR_DELAY_US) */
     OLS_K_LSQ_STEP = 16,  /* least squares, small problems: gradient and local step in one launch */
     OLS_K_STALE_SYNC = 17, /* stale-average synchronisation (ols_set_stale_average) */
-    OLS_K_COUNT = 18
+    OLS_K_CONV_FWD = 18,  /* 3 x 3 convolution forward (bias, shortcut, ReLU in the epilogue) */
+    OLS_K_CONV_DX = 19,   /* delta back-propagated through a 3 x 3 convolution, ReLU mask    */
+    OLS_K_CONV_DW = 20,   /* kernel and bias gradient of a 3 x 3 convolution                 */
+    OLS_K_POOL = 21,      /* global average pooling in front of the classifier               */
+    OLS_K_POOL_BWD = 22,  /* its backward                                                    */
+    OLS_K_COUNT = 23
 };
 
 typedef struct ols_trace_entry {
@@ -220,6 +225,19 @@ OLS_API int ols_attach_lsq(ols_handle h, int batch);
  *   weights and gradients.
  * Inputs per ols_set_batch: X [B][dims[0]] fp32, labels [B] int32 in [0, classes). */
 OLS_API int ols_attach_mlp(ols_handle h, int n_layers, const int* dims, int batch, int gemm_dtype);
+
+/* Residual convolutional block with a pooled linear classifier: the first residual stage of the network of Section 4
+ * ("Experimental setting": ResNet-18 on 32 x 32 inputs, mini-batch 128 per node), biases in place of batch
+ * normalisation:
+ *     a1 = relu(conv3x3(X; Wa) + ba);  a2 = relu(conv3x3(a1; Wb) + bb + X);  logits = mean_positions(a2) Wh + bh,
+ * softmax cross-entropy, mean over the batch.  3 x 3 kernels, stride 1, zero padding 1, cross-correlation
+ * (out[y][x] = sum_{kh,kw} in[y + kh - 1][x + kw - 1] W[kh][kw]).
+ *   channels: a multiple of 16, at most 256; classes <= 32; batch * height * width * channels < 2^31 - 2^16 channels.
+ *   Flat parameter layout: Wa [3][3][channels][channels] (kh, kw, input channel, output channel), ba [channels],
+ *   Wb, bb likewise, Wh [channels][classes], bh [classes]; d must equal the sum.
+ * Inputs per ols_set_batch: X [B][height][width][channels] fp32 (channel contiguous), labels [B] int32.
+ * Gradients go to g and the streaming kernels apply the update (the parameters are few: 74 k at 64 channels). */
+OLS_API int ols_attach_convblock(ols_handle h, int channels, int height, int width, int classes, int batch);
 
 /* Bytes of caller-provided device workspace the attached model needs (activations, deltas, per-sample
  * losses, bf16 operand copies).  0 when no model is attached. */

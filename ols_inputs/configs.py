@@ -20,7 +20,7 @@ BASE_SEED = 20200209
 @dataclass(frozen=True)
 class Config:
     name: str
-    kind: str                      # "lsq" | "mlp" | "stream"
+    kind: str                      # "lsq" | "mlp" | "stream" | "conv"
     m: int
     tau: int
     alpha: float
@@ -28,7 +28,7 @@ class Config:
     mu: float
     K: int                         # local iterations per worker
     batch: int = 0
-    dims: Tuple[int, ...] = ()     # MLP layer widths, input first
+    dims: Tuple[int, ...] = ()     # MLP layer widths, input first; conv: (channels, height, width, classes)
     d_flat: int = 0                # lsq / stream: parameter count
     nb: int = 0                    # fixed, unshuffled batches per worker (cycled)
     gemm_dtype: str = "f32"        # "f32" | "bf16"
@@ -45,6 +45,9 @@ class Config:
         if self.kind == "mlp":
             return sum(self.dims[l] * self.dims[l + 1] + self.dims[l + 1]
                        for l in range(len(self.dims) - 1))
+        if self.kind == "conv":    # two 3x3 kernels with biases, then the pooled linear classifier
+            c, _, _, classes = self.dims
+            return 2 * (9 * c * c + c) + c * classes + classes
         return self.d_flat
 
     @property
@@ -70,6 +73,10 @@ CONFIGS = {
               mu=0.9, K=200, d_flat=11_200_000),
     5: Config(name="cfg5_mlp_noniid_m64", kind="mlp", m=64, tau=8, alpha=0.5, gamma=0.05,
               mu=0.9, K=400, batch=64, dims=(3072, 1024, 10), nb=12, noniid_classes=2),
+    # Beyond the five benchmark configurations: the convolutional workload of Section 4's setting (ResNet-18 on
+    # 32 x 32 inputs, 16 nodes, batch 128 per node): the network's first residual stage, 64 channels.
+    6: Config(name="cfg6_convblock_m16", kind="conv", m=16, tau=2, alpha=0.6, gamma=0.05,
+              mu=0.9, K=100, batch=128, dims=(64, 32, 32, 10), nb=2),
 }
 
 

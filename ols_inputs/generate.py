@@ -29,6 +29,10 @@ TAG_STREAM_G = 8
 TAG_STREAM_X0 = 9
 TAG_NONIID = 10
 TAG_GENERIC = 11
+TAG_CONV_X = 12
+TAG_CONV_MEANS = 13
+TAG_CONV_LABELS = 14
+TAG_CONV_INIT = 15
 
 
 def rng(seed: int, tag: int, worker: int = 0, index: int = 0) -> np.random.Generator:
@@ -113,6 +117,42 @@ def mlp_init(cfg: Config):
         parts.append(normal_f32(cfg.seed, TAG_MLP_INIT, 0, l, (fan_in * fan_out,),
                                 sigma=1.0 / np.sqrt(fan_in)))
         parts.append(np.zeros(fan_out, dtype=np.float32))
+    return np.concatenate(parts)
+
+
+# ----------------------------------------------------------------------------
+# convolutional workload: feature maps [B][H][W][C] entering the first residual stage
+# ----------------------------------------------------------------------------
+def conv_data(cfg: Config, workers=None, nb=None):
+    """X [m][nb][B][H][W][C] fp32 and labels [m][nb][B] int32.
+
+    Same data law as the MLP configurations at the block's input shape: sample = N(0, I) + mean[label], class means
+    0.5 * N(0, I) drawn once, labels uniform over the classes; fixed batches per worker, never shuffled.
+    """
+    C, H, W, classes = cfg.dims
+    B = cfg.batch
+    nb = cfg.nb if nb is None else nb
+    workers = range(cfg.m) if workers is None else workers
+    means = normal_f32(cfg.seed, TAG_CONV_MEANS, 0, 0, (classes, H, W, C), sigma=0.5)
+    X = np.empty((len(workers), nb, B, H, W, C), dtype=np.float32)
+    labels = np.empty((len(workers), nb, B), dtype=np.int32)
+    for wi, i in enumerate(workers):
+        for j in range(nb):
+            lab = rng(cfg.seed, TAG_CONV_LABELS, i, j).integers(0, classes, size=B).astype(np.int32)
+            labels[wi, j] = lab
+            X[wi, j] = normal_f32(cfg.seed, TAG_CONV_X, i, j, (B, H, W, C))
+            X[wi, j] += means[lab]
+    return X, labels
+
+
+def conv_init(cfg: Config):
+    """Common starting point x0 [d] fp32 in the block's flat layout (Wa, ba, Wb, bb, Wh, bh): kernels N(0, 1/fan_in)
+    with fan_in = 9 C, classifier N(0, 1/C), biases zero."""
+    C, _, _, classes = cfg.dims
+    parts = []
+    for l, (count, fan_in, bias) in enumerate(((9 * C * C, 9 * C, C), (9 * C * C, 9 * C, C), (C * classes, C, classes))):
+        parts.append(normal_f32(cfg.seed, TAG_CONV_INIT, 0, l, (count,), sigma=1.0 / np.sqrt(fan_in)))
+        parts.append(np.zeros(bias, dtype=np.float32))
     return np.concatenate(parts)
 
 

@@ -7,6 +7,7 @@ iteration k uses its batch number k mod nb.
 """
 import numpy as np
 
+from . import conv_oracle as CO
 from . import ols_oracle as O
 
 
@@ -21,6 +22,12 @@ def mlp_grad_fn(dims, X, labels, bf16_operands=False):
     nb = X.shape[1]
     return lambda i, k, x: O.mlp_loss_grad(x, dims, X[i, k % nb], labels[i, k % nb],
                                            bf16_operands=bf16_operands)
+
+
+def conv_grad_fn(dims, X, labels):
+    """dims = (channels, height, width, classes); X [m][nb][B][H][W][C], labels [m][nb][B]."""
+    nb = X.shape[1]
+    return lambda i, k, x: CO.convblock_loss_grad(x, dims[0], dims[3], X[i, k % nb], labels[i, k % nb])
 
 
 def stream_grad_fn(grads):

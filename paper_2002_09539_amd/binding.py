@@ -17,7 +17,8 @@ OLS_OK, OLS_EINVAL, OLS_ESTATE, OLS_EHIP, OLS_ENOMEM = 0, -1, -2, -3, -4
 TUNE_FWD, TUNE_DW, TUNE_DA = 0, 256, 512    # OLS_OPT_TUNING value = one of these + the variant number
 (OLS_K_INIT, OLS_K_STEP, OLS_K_STEP_PULL, OLS_K_PULL, OLS_K_MEAN, OLS_K_STEP_PULL_MEAN, OLS_K_LSQ_RESID,
  OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_MIX,
- OLS_K_CAST, OLS_K_DELAY, OLS_K_LSQ_STEP, OLS_K_STALE_SYNC, OLS_K_COUNT) = range(19)
+ OLS_K_CAST, OLS_K_DELAY, OLS_K_LSQ_STEP, OLS_K_STALE_SYNC, OLS_K_CONV_FWD, OLS_K_CONV_DX, OLS_K_CONV_DW, OLS_K_POOL,
+ OLS_K_POOL_BWD, OLS_K_COUNT) = range(24)
 
 
 class ols_trace_entry(C.Structure):
@@ -45,6 +46,7 @@ _SIGNATURES = {
     "ols_set_lr": (C.c_int, [_H, C.c_float]),
     "ols_attach_lsq": (C.c_int, [_H, C.c_int]),
     "ols_attach_mlp": (C.c_int, [_H, C.c_int, C.POINTER(C.c_int), C.c_int, C.c_int]),
+    "ols_attach_convblock": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "ols_workspace_bytes": (C.c_int64, [_H]),
     "ols_bind_workspace": (C.c_int, [_H, _P, C.c_int64]),
     "ols_set_batch": (C.c_int, [_H, _P, C.c_int64, _P, C.c_int64]),
@@ -150,6 +152,10 @@ def ols_attach_lsq(h, batch):
 def ols_attach_mlp(h, dims, batch, gemm_dtype):
     arr = (C.c_int * len(dims))(*dims)
     _check(load().ols_attach_mlp(h, len(dims) - 1, arr, batch, gemm_dtype))
+
+
+def ols_attach_convblock(h, channels, height, width, classes, batch):
+    _check(load().ols_attach_convblock(h, channels, height, width, classes, batch))
 
 
 def ols_workspace_bytes(h):

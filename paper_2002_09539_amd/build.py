@@ -22,6 +22,7 @@ SOURCES = [
     "kernels_mlp_head.hip",
     "kernels_gemm_f32.hip",
     "kernels_gemm_bf16.hip",
+    "kernels_conv.hip",
 ]
 
 # packed-fp32 VALU forms stay disabled for every device translation unit

@@ -41,9 +41,9 @@ int fail(int code, const char* fmt, ...) {
 const char* kKernelNames[OLS_K_COUNT] = {
     "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
     "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16", "delay",    "lsq_step",
-    "stale_sync"};
+    "stale_sync", "conv_fwd",  "conv_dx",   "conv_dw",  "pool",     "pool_bwd"};
 
-enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2 };
+enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2, MODEL_CONV = 3 };
 
 struct TimedLaunch {
     int kind;
@@ -91,6 +91,9 @@ struct ols_ctx {
     // workspace sub-buffers (byte offsets)
     std::vector<int64_t> off_act, off_dz;
     int64_t off_dlogits = 0, off_loss = 0, off_resid = 0, off_shadow = 0, off_x0 = 0;
+    // residual convolutional block: channels, image size, classes; workspace sub-buffers
+    int cv_C = 0, cv_H = 0, cv_W = 0, cv_classes = 0;
+    int64_t off_a1 = 0, off_a2 = 0, off_dz1 = 0, off_dz2 = 0, off_pooled = 0, off_dpool = 0, off_cpartial = 0;
     const float* X = nullptr;
     const void* y = nullptr;
     int64_t xs = 0, ys = 0;
@@ -306,7 +309,95 @@ void plan_workspace(ols_ctx* c) {
         c->off_dlogits = take(m * B * c->dims[L] * 4);
         c->off_loss = take(m * B * 4);
     }
+    if (c->model == MODEL_CONV) {
+        const int64_t act = m * B * c->cv_H * c->cv_W * c->cv_C * 4;   // one activation / delta tensor
+        c->off_a1 = take(act);
+        c->off_a2 = take(act);
+        c->off_dz2 = take(act);
+        c->off_dz1 = take(act);
+        c->off_pooled = take(m * B * c->cv_C * 4);
+        c->off_dpool = take(m * B * c->cv_C * 4);
+        const int64_t splits = conv3x3_dw_splits(c->m, c->B, c->cv_H, c->cv_W, c->cv_C);
+        c->off_cpartial = take(splits * m * ((int64_t)9 * c->cv_C * c->cv_C + c->cv_C) * 4);
+        c->off_dlogits = take(m * B * c->cv_classes * 4);
+        c->off_loss = take(m * B * 4);
+    }
     c->ws_need = off;
+}
+
+// Forward + backward of the residual convolutional block on the main stream; gradients go to g.
+int conv_gradients(ols_ctx* c) {
+    const float* xc = c->x[c->cur];
+    const int m = c->m, B = c->B, C = c->cv_C, H = c->cv_H, W = c->cv_W;
+    const int64_t n_w = (int64_t)9 * C * C;
+    const int64_t wa = 0, ba = n_w, wb = n_w + C, bb = 2 * n_w + C, wh = 2 * (n_w + C), bh = wh + (int64_t)C * c->cv_classes;
+    const int64_t act = (int64_t)B * H * W * C;   // elements per worker
+    float* a1 = (float*)(c->ws + c->off_a1);
+    float* a2 = (float*)(c->ws + c->off_a2);
+    float* dz1 = (float*)(c->ws + c->off_dz1);
+    float* dz2 = (float*)(c->ws + c->off_dz2);
+    float* pooled = (float*)(c->ws + c->off_pooled);
+    float* dpool = (float*)(c->ws + c->off_dpool);
+    ConvArgs base = {};
+    base.groups = m; base.B = B; base.H = H; base.W = W; base.C = C;
+    base.s_w = c->ld; base.s_bias = c->ld;
+    base.ld = c->ld; base.g = c->g; base.partial = (float*)(c->ws + c->off_cpartial);
+    int rc;
+    {   // a1 = relu(conv(X; Wa) + ba)
+        ConvArgs a = base;
+        a.in = c->X; a.s_in = c->xs; a.w = xc + wa; a.bias = xc + ba; a.out = a1; a.s_out = act; a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_fwd(a, s); }))) return rc;
+    }
+    {   // a2 = relu(conv(a1; Wb) + bb + X)
+        ConvArgs a = base;
+        a.in = a1; a.s_in = act; a.w = xc + wb; a.bias = xc + bb; a.residual = c->X; a.s_res = c->xs; a.out = a2; a.s_out = act;
+        a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_fwd(a, s); }))) return rc;
+    }
+    if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
+             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, s);
+         })))
+        return rc;
+    HeadArgs ha = {};
+    ha.h = pooled;
+    ha.h_stride = (int64_t)B * C;
+    ha.h_bf16 = false;
+    ha.x = xc;
+    ha.g = c->g;
+    ha.ld = c->ld;
+    ha.w_off = wh;
+    ha.b_off = bh;
+    ha.labels = (const int32_t*)c->y;
+    ha.label_stride = c->ys;
+    ha.dlogits = (float*)(c->ws + c->off_dlogits);
+    ha.loss_parts = (float*)(c->ws + c->off_loss);
+    ha.dz = dpool;   // dlogits Wh^T where pooled > 0 (pooled = 0 means every position is 0: no gradient either way)
+    ha.m = m;
+    ha.B = B;
+    ha.H = C;
+    ha.C = c->cv_classes;
+    if ((rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); }))) return rc;
+    if ((rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); }))) return rc;
+    if ((rc = enqueue(c, OLS_K_POOL_BWD, 0, -1, -1, [&](hipStream_t s) {
+             return launch_pool_bwd(dpool, (int64_t)B * C, a2, act, dz2, act, m, B, H * W, C, s);
+         })))
+        return rc;
+    {   // delta at a1: transposed convolution of dz2 through Wb, gated by a1 > 0
+        ConvArgs a = base;
+        a.in = dz2; a.s_in = act; a.w = xc + wb; a.mask = a1; a.s_mask = act; a.out = dz1; a.s_out = act;
+        if ((rc = enqueue(c, OLS_K_CONV_DX, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_dx(a, s); }))) return rc;
+    }
+    {   // gradients of the second convolution
+        ConvArgs a = base;
+        a.in = a1; a.s_in = act; a.dout = dz2; a.s_dout = act; a.g_w_off = wb; a.g_b_off = bb;
+        if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_dw(a, s); }))) return rc;
+    }
+    {   // gradients of the first convolution (its input is data: no delta beyond it)
+        ConvArgs a = base;
+        a.in = c->X; a.s_in = c->xs; a.dout = dz1; a.s_dout = act; a.g_w_off = wa; a.g_b_off = ba;
+        if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_dw(a, s); }))) return rc;
+    }
+    return OLS_OK;
 }
 
 // Forward + backward of the attached model on the main stream.  Without `upd` the gradients go to g;
@@ -333,6 +424,7 @@ int compute_gradients(ols_ctx* c, const FusedUpdate* upd, int src_buf, int dst_b
         return enqueue(c, OLS_K_LSQ_GRAD, 0, c->cur, -1,
                        [&](hipStream_t s) { return launch_lsq_grad(c->X, c->xs, resid, c->g, c->ld, m, B, c->d, s); });
     }
+    if (c->model == MODEL_CONV) return conv_gradients(c);
     if (c->model != MODEL_MLP) return OLS_OK;
 
     const int L = (int)c->dims.size() - 1;
@@ -506,6 +598,13 @@ int pick_buffers(ols_ctx* c, int* src, int* dst, bool defer = false) {
         }
     }
     return OLS_OK;
+}
+
+// fp32 elements of one input sample of the attached model
+int64_t sample_elems(ols_ctx* c) {
+    if (c->model == MODEL_LSQ) return c->d;
+    if (c->model == MODEL_CONV) return (int64_t)c->cv_H * c->cv_W * c->cv_C;
+    return (int64_t)c->dims[0];
 }
 
 int need(ols_ctx* c) {
@@ -710,6 +809,31 @@ int ols_attach_mlp(ols_handle c, int n_layers, const int* dims, int batch, int g
     return OLS_OK;
 }
 
+int ols_attach_convblock(ols_handle c, int channels, int height, int width, int classes, int batch) {
+    if (int rc = need(c)) return rc;
+    if (c->k != 0) return fail(OLS_ESTATE, "models are attached before the first local step");
+    if (channels < 16 || channels % 16 != 0 || channels > 256) return fail(OLS_EINVAL, "channels must be a multiple of 16 in [16, 256], got %d", channels);
+    if (height < 1 || width < 1 || height > 4096 || width > 4096) return fail(OLS_EINVAL, "height and width must be in [1, 4096]");
+    if (classes < 1 || classes > 32) return fail(OLS_EINVAL, "the class count must be in [1, 32], got %d", classes);
+    if (batch < 1 || batch > 65536) return fail(OLS_EINVAL, "batch must be in [1, 65536]");
+    const int64_t elems = (int64_t)batch * height * width * channels;
+    if (elems >= ((int64_t)1 << 31) - ((int64_t)channels << 16))
+        return fail(OLS_EINVAL, "batch * height * width * channels = %lld is too large for one worker's activation tensor", (long long)elems);
+    const int64_t total = 2 * ((int64_t)9 * channels * channels + channels) + (int64_t)channels * classes + classes;
+    if (total != c->d) return fail(OLS_EINVAL, "the block has %lld parameters but d = %lld", (long long)total, (long long)c->d);
+    c->model = MODEL_CONV;
+    c->B = batch;
+    c->gemm_dtype = 0;
+    c->cv_C = channels;
+    c->cv_H = height;
+    c->cv_W = width;
+    c->cv_classes = classes;
+    c->ws = nullptr;
+    c->batch_set = false;
+    plan_workspace(c);
+    return OLS_OK;
+}
+
 int64_t ols_workspace_bytes(ols_handle c) { return c ? c->ws_need : 0; }
 
 int ols_bind_workspace(ols_handle c, void* ws, int64_t bytes) {
@@ -731,7 +855,7 @@ int ols_set_batch(ols_handle c, const float* X, int64_t x_worker_stride, const v
     if (!X || !y) return fail(OLS_EINVAL, "X and y must be non-null");
     if ((reinterpret_cast<uintptr_t>(X) & 15u) || (x_worker_stride % 4) != 0)
         return fail(OLS_EINVAL, "X must be 16-byte aligned with a worker stride that is a multiple of 4 elements");
-    const int64_t row = c->model == MODEL_LSQ ? c->d : (int64_t)c->dims[0];
+    const int64_t row = sample_elems(c);
     if (x_worker_stride < (int64_t)c->B * row && c->m > 1 && x_worker_stride != 0)
         return fail(OLS_EINVAL, "x_worker_stride %lld is smaller than one batch (%lld elements)",
                     (long long)x_worker_stride, (long long)(c->B * row));
@@ -937,7 +1061,7 @@ int ols_run_steps(ols_handle c, int64_t steps, const float* X, const void* y, in
     if (c->model == MODEL_NONE) return fail(OLS_ESTATE, "ols_run_steps needs an attached model");
     if (steps < 0 || nb < 1 || !X || !y) return fail(OLS_EINVAL, "steps >= 0, nb >= 1 and non-null data are required");
     if (c->pull_due || c->anchor_due) return fail(OLS_ESTATE, "a pull or an anchor refresh is due");
-    const int64_t row = c->model == MODEL_LSQ ? c->d : (int64_t)c->dims[0];
+    const int64_t row = sample_elems(c);
     const int64_t x_batch = (int64_t)c->B * row, y_batch = c->B;   // elements per batch
     const size_t y_elem = 4;                                          // int32 labels and fp32 targets alike
     for (int64_t it = 0; it < steps; ++it) {

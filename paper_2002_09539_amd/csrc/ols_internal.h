@@ -169,6 +169,33 @@ struct HeadArgs {
 };
 hipError_t launch_head_fwd(const HeadArgs& a, hipStream_t s);
 hipError_t launch_head_bwd(const HeadArgs& a, hipStream_t s);
+// 3 x 3 convolutions (stride 1, zero padding 1) grouped over the workers; activations [group][B H W][C] (channel
+// contiguous), kernels [group][9][C][C] as (tap, input channel, output channel).  C a multiple of 16.
+struct ConvArgs {
+    const float* in;        // fwd: layer input; dx: delta of the layer output; dw: layer input
+    const float* w;         // fwd, dx: kernels
+    const float* dout;      // dw: delta of the layer output
+    float* out;             // fwd: layer output; dx: delta of the layer input
+    const float* bias;      // fwd: [C] per group
+    const float* residual;  // fwd: added before the activation (same shape as out), or nullptr
+    const float* mask;      // dx: activations whose sign gates the result (same shape as out), or nullptr
+    float* partial;         // dw: scratch of conv3x3_dw_splits(...) * groups * (9 C C + C) floats
+    float* g;               // dw: gradients [groups][ld]; kernel gradient at g_w_off, bias gradient at g_b_off of a row
+    int64_t ld, g_w_off, g_b_off;
+    int64_t s_in, s_w, s_dout, s_out, s_bias, s_res, s_mask;   // group strides (elements)
+    int groups, B, H, W, C;
+    int relu;               // fwd: apply max(., 0)
+};
+hipError_t launch_conv3x3_fwd(const ConvArgs& a, hipStream_t s);
+hipError_t launch_conv3x3_dx(const ConvArgs& a, hipStream_t s);
+hipError_t launch_conv3x3_dw(const ConvArgs& a, hipStream_t s);   // weight + bias gradient (two launches)
+int conv3x3_dw_splits(int groups, int B, int H, int W, int C);   // pixel ranges the weight-gradient contraction is split into
+// global average pooling over the HW positions of every sample, and its backward through the ReLU in front of it
+hipError_t launch_pool_mean(const float* a, int64_t s_a, float* pooled, int64_t s_p, int groups, int B, int HW, int C,
+                            hipStream_t s);
+hipError_t launch_pool_bwd(const float* dpool, int64_t s_dp, const float* a, int64_t s_a, float* dz, int64_t s_dz,
+                           int groups, int B, int HW, int C, hipStream_t s);
+
 // raises a kernel's dynamic-LDS limit once per (device, kernel)
 hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes);
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }

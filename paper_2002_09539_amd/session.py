@@ -83,6 +83,10 @@ class Session:
         if workspace:
             self._workspace()
 
+    def attach_convblock(self, channels, height, width, classes, batch):
+        B.ols_attach_convblock(self.h, channels, height, width, classes, batch)
+        self._workspace()
+
     def _workspace(self):
         n = B.ols_workspace_bytes(self.h)
         self.ws = torch.zeros(max(n, 256), dtype=torch.uint8, device=self.device)
@@ -107,7 +111,7 @@ class Session:
     # ---- the iteration -----------------------------------------------------------------------
     def set_batch(self, X, y):
         """X: device [m][B][in] fp32 (worker axis may be strided), y: device [m][B] int32 / fp32."""
-        assert X.stride(-1) == 1 and X.stride(1) == X.shape[2] and y.stride(-1) == 1
+        assert X[0].is_contiguous() and y.stride(-1) == 1
         B.ols_set_batch(self.h, _ptr(X), X.stride(0) if self.m > 1 else X[0].numel(), _ptr(y),
                         y.stride(0) if self.m > 1 else y[0].numel())
 

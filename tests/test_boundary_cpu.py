@@ -513,3 +513,28 @@ def test_static_workspace_entry_point_checks_its_limits_without_a_device():
     h = dry(d=100)
     assert code_of(B.ols_run_steps_static, h, 1, FAKE, FAKE, 1) == B.OLS_ESTATE      # no model attached
     B.ols_destroy(h)
+
+
+def test_convblock_attachment_and_launch_plan():
+    C, H, W, classes, batch = 32, 8, 8, 10, 4
+    d = 2 * (9 * C * C + C) + C * classes + classes
+    h = dry(d=d, mu=0.9, tau=2)
+    assert code_of(B.ols_attach_convblock, h, 24, H, W, classes, batch) == B.OLS_EINVAL      # channels not a multiple of 16
+    assert code_of(B.ols_attach_convblock, h, C, H, W, 40, batch) == B.OLS_EINVAL            # too many classes
+    assert code_of(B.ols_attach_convblock, h, C, H, W, classes + 1, batch) == B.OLS_EINVAL   # d does not match
+    assert code_of(B.ols_attach_convblock, h, C, 0, W, classes, batch) == B.OLS_EINVAL
+    B.ols_attach_convblock(h, C, H, W, classes, batch)
+    need = B.ols_workspace_bytes(h)
+    assert need >= 4 * 4 * batch * H * W * C * 4                    # four activation / delta tensors for 4 workers
+    B.ols_bind_workspace(h, FAKE, need)
+    B.ols_init_params(h, FAKE)
+    assert code_of(B.ols_set_batch, h, FAKE, batch * H * W * C - 4, FAKE, batch) == B.OLS_EINVAL   # stride below one batch
+    B.ols_set_batch(h, FAKE, batch * H * W * C, FAKE, batch)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_local_step(h)
+    B.ols_local_step(h)
+    B.ols_sync_pull(h)
+    B.ols_anchor_update_async(h)
+    one = ["conv_fwd", "conv_fwd", "pool", "head_fwd", "head_bwd", "pool_bwd", "conv_dx", "conv_dw", "conv_dw"]
+    assert kinds(B.ols_trace(h)) == one + ["step"] + one + ["step_pull", "mean"]
+    B.ols_destroy(h)
