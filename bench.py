@@ -102,6 +102,15 @@ def algorithmic_work(cfg, ld, fused_update=True):
         da = [2.0 * m * B * dims[l] * dims[l + 1] for l in range(1, L - 1)]
         if da:
             work["gemm_da"] = ("mfma", sum(da) / len(da))
+    if cfg.kind == "conv":
+        C, H, W, _ = cfg.dims
+        flops = 2.0 * m * cfg.batch * H * W * 9 * C * C      # one 3 x 3 convolution as a GEMM, all workers
+        act = 4.0 * m * cfg.batch * H * W * C                # bytes of one activation tensor
+        work["conv_fwd"] = ("mfma", flops)
+        work["conv_dx"] = ("mfma", flops)
+        work["conv_dw"] = ("mfma", flops)
+        work["pool"] = ("hbm", act)
+        work["pool_bwd"] = ("hbm", 2 * act)
     return work
 
 
@@ -113,6 +122,13 @@ def build_workload(cfg, sess, torch):
         Xd, yd = sess.upload(X), sess.upload(labels)
         x0 = G.mlp_init(cfg)
         sess.attach_mlp(cfg.dims, cfg.batch, cfg.gemm_dtype)
+        sess.init_params(x0)
+        return (lambda k: sess.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb])), (X, labels, x0), (Xd, yd)
+    if cfg.kind == "conv":
+        X, labels = G.conv_data(cfg)
+        Xd, yd = sess.upload(X), sess.upload(labels)
+        x0 = G.conv_init(cfg)
+        sess.attach_convblock(*cfg.dims, cfg.batch)
         sess.init_params(x0)
         return (lambda k: sess.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb])), (X, labels, x0), (Xd, yd)
     if cfg.kind == "lsq":
@@ -152,6 +168,10 @@ def cpu_baseline(cfg, host_inputs, seconds):
     elif cfg.kind == "lsq":
         A, y, x0 = host_inputs
         grad_fn = OW.lsq_grad_fn(A, y)
+        m_eff, d_eff = cfg.m, cfg.d
+    elif cfg.kind == "conv":
+        X, labels, x0 = host_inputs
+        grad_fn = OW.conv_grad_fn(cfg.dims, X, labels)
         m_eff, d_eff = cfg.m, cfg.d
     else:  # the update is element-wise: time the oracle on a slice of the columns
         d_eff = 1 << 20
@@ -276,7 +296,7 @@ def measure(idx, args, K, W, cpu_seconds, side):
                     entry.update(bound="hbm", achieved=rate / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
                                  frac=rate / 1e9 / HBM_PEAK_GBS, per_launch=amount)
                 else:
-                    peak = MFMA_PEAK_TFLOPS[cfg.gemm_dtype]
+                    peak = MFMA_PEAK_TFLOPS[cfg.gemm_dtype if cfg.kind == "mlp" else "f32"]
                     entry.update(bound="mfma", achieved=rate / 1e12, peak=peak, unit="TFLOP/s",
                                  frac=rate / 1e12 / peak, per_launch=amount)
             if name + "_flops" in work:
