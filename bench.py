@@ -65,6 +65,8 @@ def parse():
                     help="synchronisation rule: the paper's pull-back + anchor average, or the stale-average "
                          "alternative of its related-work section (x <- z + (x - snapshot); the CPU baseline is then "
                          "not run, it times the paper's rule)")
+    ap.add_argument("--tau", type=int, default=None,
+                    help="override the configuration's tau (local steps per round), e.g. for the latency sweep at tau = 1")
     ap.add_argument("--opt", action="append", default=[], help="KEY=VALUE library option (numeric key), repeatable")
     return ap.parse_args()
 
@@ -89,6 +91,14 @@ def algorithmic_work(cfg, ld, fused_update=True):
         L = len(dims) - 1
         fwd = [2.0 * m * B * dims[l] * dims[l + 1] for l in range(L - 1)]
         work["gemm_fwd"] = ("mfma", sum(fwd) / max(len(fwd), 1))
+        # algorithmic bytes of the same launches (operands read once, output written once): the arithmetic intensity
+        # decides whether the matrix-core peak or AI x HBM peak is the lower ceiling (batch 256 in bf16: the latter)
+        es_ = 2 if cfg.gemm_dtype == "bf16" else 4
+        fb = [m * es_ * (B * dims[l] + dims[l] * dims[l + 1] + B * dims[l + 1]) for l in range(L - 1)]
+        work["gemm_fwd_bytes"] = sum(fb) / max(len(fb), 1)
+        db = [m * es_ * (B * dims[l + 1] + dims[l] * dims[l + 1] + 2 * B * dims[l]) for l in range(1, L - 1)]
+        if db:
+            work["gemm_da_bytes"] = sum(db) / len(db)
         work["gemm_dw"] = ("mfma", sum(fwd) / max(len(fwd), 1))
         if fused_update and L > 1:
             # the weight-gradient kernel also applies the local step: it reads and writes the layer's
@@ -218,6 +228,8 @@ def measure(idx, args, K, W, cpu_seconds, side):
     from paper_2002_09539_amd.session import Session
 
     cfg = I.get(idx)
+    if not side and args.tau is not None:
+        cfg = cfg.scaled(tau=args.tau)
     serialize = 0 if side else args.serialize
     mixing = "none" if side else args.mixing
     delay = 0 if side else args.anchor_delay_us
@@ -299,6 +311,9 @@ def measure(idx, args, K, W, cpu_seconds, side):
                     peak = MFMA_PEAK_TFLOPS[cfg.gemm_dtype if cfg.kind == "mlp" else "f32"]
                     entry.update(bound="mfma", achieved=rate / 1e12, peak=peak, unit="TFLOP/s",
                                  frac=rate / 1e12 / peak, per_launch=amount)
+                    if name + "_bytes" in work:   # fraction of min(matrix-core peak, arithmetic intensity x HBM peak)
+                        ceiling = min(peak, amount / work[name + "_bytes"] * HBM_PEAK_GBS / 1e3)
+                        entry.update(ceiling_tflops=ceiling, frac_of_ceiling=rate / 1e12 / ceiling)
             if name + "_flops" in work:
                 entry["mfma_tflops"] = work[name + "_flops"] / (ms / n * 1e-3) / 1e12
             kernels[name] = entry
@@ -365,6 +380,8 @@ def compact(rec):
             "achieved": r.get("achieved"), "unit": r.get("unit"), "avg_launch_us": r.get("avg_launch_us"),
             "kernels_avg_us": {k: round(v["avg_us"], 2) for k, v in rec["kernels"].items() if isinstance(v, dict)},
             "kernels_frac": {k: round(v["frac"], 4) for k, v in rec["kernels"].items() if isinstance(v, dict) and "frac" in v},
+            "kernels_frac_of_min_mfma_hbm_ceiling": {k: round(v["frac_of_ceiling"], 4) for k, v in rec["kernels"].items()
+                                                     if isinstance(v, dict) and "frac_of_ceiling" in v},
             "oracle_worker_iterations_per_s": None if rec["cpu_baseline"] is None else rec["cpu_baseline"]["value"],
             "oracle_sample": None if rec["cpu_baseline"] is None else rec["cpu_baseline"]["sample"]}
 
@@ -388,7 +405,7 @@ def main():
         sys.exit(2)
     default_options = (not args.serialize and args.fuse_mean is None and args.mixing == "none" and not args.anchor_delay_us
                        and args.sync_rule == "paper" and args.fuse_gemm_update == 1 and not args.no_second_buffer
-                       and not args.opt and args.loop == "library" and not args.no_kernel_timing
+                       and not args.opt and args.loop == "library" and not args.no_kernel_timing and args.tau is None
                        and not args.calibration_copy_mib)
     if args.side_configs is None:
         sides = [1, 2, 3, 5] if (args.config == 4 and default_options) else []

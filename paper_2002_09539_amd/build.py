@@ -10,8 +10,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "libols.so")
+OBJ = os.environ.get("OLS_BUILD_DIR", os.path.join(HERE, "_build"))
+LIB = os.environ.get("OLS_BUILD_OUTPUT", os.path.join(HERE, "libols.so"))   # override: an alternative build
 
 SOURCES = [
     "ols_api.hip",
@@ -43,7 +43,8 @@ def _hipcc():
 
 def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("OLS_EXTRA_FLAGS", "").split()   # e.g. -DOLS_TUNING_VARIANTS for a measurement build
+    cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, res.stdout, res.stderr))
