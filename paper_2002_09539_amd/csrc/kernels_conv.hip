@@ -13,12 +13,21 @@
 //   DX   din[p][ci] = ( sum_{tap, co} dout[p - shift(tap)][co] w[tap][ci][co] ) * [mask[p][ci] > 0]
 //        the same with the opposite shifts and the kernel read with its channel indices exchanged
 //   DW   dw[tap][ci][co] = sum_p in[p + shift(tap)][ci] dout[p][co];  db[co] = sum_p dout[p][co]
-//        per tap an M = C, N = C GEMM contracting over all P pixels; the pixel range is split over workgroups, the
+//        per kernel row an M = 3 C, N = C GEMM contracting over all P pixels; the pixel range is split over workgroups, the
 //        parts are written raw and summed in a fixed order by a second pass (no atomics: results do not depend on
 //        timing)
 //
 // Operand tiles go global -> registers -> LDS with 16-byte vectors and feed the MFMAs through the fragment layout of
-// gemm_f32_tile.h; one slice of global loads is in flight while the previous one feeds the matrix cores.
+// gemm_f32_tile.h; two slices of global loads are in flight while a third feeds the matrix cores.
+//
+// Measured at the benchmark shape (16 workers x 128 samples x 32 x 32 x 64 channels, 154.6 GFLOP per launch; us per
+// launch).  Forward / delta, tile rows x K slice x slices in flight: 128 x 32 x 1: 1622 / 1680; 128 x 32 x 2: 1682 /
+// 1713; 128 x 16 x 1: 1418 / 1404; 128 x 16 x 2: 1395 / 1386; 64 x 32 x 2: 1455 / 1461; 64 x 16 x 2: 1402 / 1450;
+// 256 x 16 x 2: 1591 / 1612 -- the short slice halves the LDS of a workgroup (29 KB: five workgroups per compute unit
+// instead of two), which matters more than the number of barriers.  Weight gradient: one tap per workgroup (64 x 64
+// output, 32 x 32 per wavefront) 1688 with slices of 32, 1637 / 1568 with slices of 16 and one / two in flight; a kernel
+// row per workgroup (192 x 64) 1626 / 1482 with one / two in flight, and 1420 with the register budget capped for three
+// wavefronts per SIMD (1733 when capped for four: spills).
 #include "gemm_f32_tile.h"
 #include "ols_internal.h"
 
@@ -57,7 +66,7 @@ __device__ __forceinline__ int xcd_tile(int chunk, int total) {
 // ---------------------------------------------------------------------------------------------
 // forward (MODE 0) and back-propagated delta (MODE 1)
 // ---------------------------------------------------------------------------------------------
-template <int MODE, int BM, int BK>
+template <int MODE, int BM, int BK, int DEPTH>
 __global__ __launch_bounds__(kThreads) void conv3x3_kernel(ConvDev p) {
     constexpr bool B_KC = MODE == 1;            // DX reads w[tap][n = ci][k = co]: contraction index contiguous
     using TA = Tile<BM, BK, true>;
@@ -158,17 +167,9 @@ __global__ __launch_bounds__(kThreads) void conv3x3_kernel(ConvDev p) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[buf][i][e], fb[buf][j][e], acc[i][j], 0, 0, 0);
     };
 
-    const int nk = 9 * C / BK;
-    f4 ra[TA::kPerThread], rb[TB::kPerThread];
-    unsigned oka = load_a(ra, 0), okb = load_b(rb, 0);
-    TA::store(lds_a(0), ra, oka);
-    TB::store(lds_b(0), rb, okb);
-    __syncthreads();
-    load_frags(0, 0, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        oka = load_a(ra, kt + 1);          // past the end: zero-filled dummies that are never consumed
-        okb = load_b(rb, kt + 1);
+    // One K slice out of lds[cur]; the staged registers of the next slice are published to lds[cur ^ 1] before the
+    // last octet's MFMAs, so the barrier and the first fragment reads of that slice hide behind them.
+    auto slice = [&](int cur, const f4 (&na)[TA::kPerThread], unsigned oka, const f4 (&nb)[TB::kPerThread], unsigned okb) {
 #pragma unroll
         for (int q = 0; q + 1 < Q; ++q) {
             load_frags((q + 1) & 1, cur, q + 1);
@@ -176,13 +177,48 @@ __global__ __launch_bounds__(kThreads) void conv3x3_kernel(ConvDev p) {
             mfmas(q & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        TA::store(lds_a(cur ^ 1), ra, oka);
-        TB::store(lds_b(cur ^ 1), rb, okb);
+        TA::store(lds_a(cur ^ 1), na, oka);
+        TB::store(lds_b(cur ^ 1), nb, okb);
         __syncthreads();
         load_frags(0, cur ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
         mfmas((Q - 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
+    };
+    // Slices past the end are zero-filled dummies (tap 9): what they publish is never consumed, or contributes zeros.
+    const int nk = 9 * C / BK;
+    if (DEPTH == 1) {
+        f4 ra[TA::kPerThread], rb[TB::kPerThread];
+        unsigned oka = load_a(ra, 0), okb = load_b(rb, 0);
+        TA::store(lds_a(0), ra, oka);
+        TB::store(lds_b(0), rb, okb);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            oka = load_a(ra, kt + 1);
+            okb = load_b(rb, kt + 1);
+            slice(kt & 1, ra, oka, rb, okb);
+        }
+    } else {
+        // Two slices of global loads in flight: while slice t feeds the matrix cores from LDS, slice t + 1 waits in
+        // registers and slice t + 2 is on its way.  Slices are consumed in pairs; an odd trailing one is paired with a
+        // dummy.
+        f4 ra0[TA::kPerThread], rb0[TB::kPerThread], ra1[TA::kPerThread], rb1[TB::kPerThread];
+        unsigned oka0 = load_a(ra0, 0), okb0 = load_b(rb0, 0);
+        unsigned oka1 = load_a(ra1, 1), okb1 = load_b(rb1, 1);
+        TA::store(lds_a(0), ra0, oka0);
+        TB::store(lds_b(0), rb0, okb0);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        const int nk2 = (nk + 1) & ~1;
+        for (int kt = 0; kt < nk2; kt += 2) {
+            oka0 = load_a(ra0, kt + 2);
+            okb0 = load_b(rb0, kt + 2);
+            slice(0, ra1, oka1, rb1, okb1);
+            oka1 = load_a(ra1, kt + 3);
+            okb1 = load_b(rb1, kt + 3);
+            slice(1, ra0, oka0, rb0, okb0);
+        }
     }
 
     // Epilogue.  Accumulator register r of a lane holds out[row][col] with col = lane % 32 and
@@ -216,13 +252,22 @@ __global__ __launch_bounds__(kThreads) void conv3x3_kernel(ConvDev p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// weight / bias gradient: one tile per (group, pixel range, tap, 64 x 64 block of the kernel)
+// weight / bias gradient: one tile per (group, pixel range, kernel row kh, 64 x 64 block of input x output channels).
+// A workgroup forms the gradient of the three taps of a kernel row at once: its A tile holds, side by side, the 64
+// input channels of the pixel shifted by kw - 1 = -1, 0, +1 (rows 64 kw + ci of a 192 x 64 output), so one tile of dout
+// serves three taps, a wavefront owns 96 x 32 (three MFMA blocks per fragment of dout), and the three shifted reads of
+// the input hit the same cache lines.
 // ---------------------------------------------------------------------------------------------
-template <int BK>
-__global__ __launch_bounds__(kThreads) void conv3x3_dw_kernel(ConvDev p) {
-    using TA = Tile<64, BK, false>;     // in[pixel + shift][ci]: rows (ci) contiguous, [BK][64 + 4] in LDS
+#ifndef OLS_CONV_DW_WAVES
+#define OLS_CONV_DW_WAVES 3
+#endif
+template <int BK, int DEPTH>
+__global__ __launch_bounds__(kThreads, OLS_CONV_DW_WAVES) void conv3x3_dw_kernel(ConvDev p) {
+    constexpr int kRowTaps = 3, kBMW = 64 * kRowTaps;   // 192 rows: (kw, ci)
+    using TA = Tile<kBMW, BK, false>;   // in[pixel + shift(kw)][ci]: [BK][192 + 4] in LDS
     using TB = Tile<kBN, BK, false>;    // dout[pixel][co]
-    static_assert(TA::kVecs % kThreads == 0 && BK % 16 == 0, "tile shape");
+    static_assert(DEPTH == 1 || DEPTH == 2, "slices of global loads in flight");
+    constexpr int TM = 3;               // 2 x 2 wavefronts of 96 x 32
     __shared__ __attribute__((aligned(16))) float lds_all[2 * TA::kFloats + 2 * TB::kFloats];
     auto lds_a = [&](int buf) { return lds_all + buf * TA::kFloats; };
     auto lds_b = [&](int buf) { return lds_all + 2 * TA::kFloats + buf * TB::kFloats; };
@@ -230,103 +275,135 @@ __global__ __launch_bounds__(kThreads) void conv3x3_dw_kernel(ConvDev p) {
     const int tile = xcd_tile(p.chunk, p.total_tiles);
     if (tile < 0) return;
     const int C = p.C, H = p.H, Wd = p.W;
-    // tile -> (group, split, tap, tm, tn), tn fastest: the nine taps of a pixel range are neighbours (they share dout)
+    // tile -> (group, split, kh, tm, tn), tn fastest: the kernel rows of a pixel range are neighbours (they share dout)
     int rest = tile;
     const int tn = rest % p.tiles_n; rest /= p.tiles_n;
     const int tm = rest % p.tiles_n; rest /= p.tiles_n;
-    const int tap = rest % 9; rest /= 9;
+    const int kh = rest % 3; rest /= 3;
     const int split = rest % p.splits;
     const int group = rest / p.splits;
     const int m0 = tm * 64, n0 = tn * kBN;
     const int k_lo = split * p.k_chunk, k_hi = min(p.P, k_lo + p.k_chunk);
-    const int dy = tap / 3 - 1, dx = tap % 3 - 1;
+    const int dy = kh - 1;
     const float* IN = p.in + (int64_t)group * p.s_in;
     const float* DOUT = p.dout + (int64_t)group * p.s_dout;
 
-    // Lines of the A tile are pixels that advance by BK per slice; (y, x) of each line is carried along.
-    int pix[TA::kPerThread], py[TA::kPerThread], px[TA::kPerThread];
-    int ch[TA::kPerThread];
+    // Lines of the operand tiles are pixels that advance by BK per slice.  A lane copies, for ONE pixel line and one
+    // group of four channels, the three shifted input vectors (kw = 0, 1, 2) and the vector of dout, so it carries a
+    // single pixel position (pix, y, x) along.
+    static_assert(BK == 16, "one pixel line per lane: 16 lines x 16 channel vectors = 256 lanes");
+    const int line = threadIdx.x / 16, c4 = (threadIdx.x % 16) * 4;
+    int pix = k_lo + line;
+    int py = (pix % (H * Wd)) / Wd, px = pix % Wd;
+    const bool ch_ok = m0 + c4 < C, co_ok = n0 + c4 < C;
+    struct Staged {
+        f4 a[kRowTaps];
+        f4 b;
+        unsigned ok;   // bits 0..2: the three taps, bit 3: dout
+    };
+    auto load_ab = [&](Staged& r) {   // loads the slice the carried pixel points at, then advances by BK pixels
+        const bool in_range = pix < k_hi;
+        const int y = py + dy;
+        const bool row_ok = in_range && ch_ok && y >= 0 && y < H;
+        const float* src = IN + (int64_t)(pix + dy * Wd) * C + m0 + c4;
+        r.ok = 0;
 #pragma unroll
-    for (int t = 0; t < TA::kPerThread; ++t) {
-        const int v = threadIdx.x + t * kThreads;
-        pix[t] = k_lo + v / TA::kVecPerLine;
-        ch[t] = m0 + (v % TA::kVecPerLine) * 4;
-        const int rem = pix[t] % (H * Wd);
-        py[t] = rem / Wd;
-        px[t] = rem % Wd;
-    }
-    auto load_a = [&](f4 (&r)[TA::kPerThread]) -> unsigned {   // loads the slice the carried pixels point at, then advances
-        unsigned okmask = 0;
-#pragma unroll
-        for (int t = 0; t < TA::kPerThread; ++t) {
-            const int y = py[t] + dy, x = px[t] + dx;
-            const bool ok = pix[t] < k_hi && ch[t] < C && y >= 0 && y < H && x >= 0 && x < Wd;
-            r[t] = *(const f4*)(IN + (ok ? (int64_t)(pix[t] + dy * Wd + dx) * C + ch[t] : 0));
-            okmask |= ok ? (1u << t) : 0u;
-            pix[t] += BK;
-            px[t] += BK;
-            while (px[t] >= Wd) {
-                px[t] -= Wd;
-                py[t] += 1;
-            }
-            while (py[t] >= H) py[t] -= H;
+        for (int kw = 0; kw < kRowTaps; ++kw) {
+            const int x = px + kw - 1;
+            const bool ok = row_ok && x >= 0 && x < Wd;
+            r.a[kw] = *(const f4*)(ok ? src + (kw - 1) * C : IN);
+            r.ok |= ok ? (1u << kw) : 0u;
         }
-        return okmask;
+        const bool okb = in_range && co_ok;
+        r.b = *(const f4*)(okb ? DOUT + (int64_t)pix * C + n0 + c4 : DOUT);
+        r.ok |= okb ? 8u : 0u;
+        pix += BK;
+        px += BK;
+        while (px >= Wd) {
+            px -= Wd;
+            py += 1;
+        }
+        while (py >= H) py -= H;
+    };
+    auto store_ab = [&](int buf, const Staged& r) {
+        const f4 zero = {0.f, 0.f, 0.f, 0.f};
+        float* qa = lds_a(buf) + line * TA::kPitch + c4;
+#pragma unroll
+        for (int kw = 0; kw < kRowTaps; ++kw) *(f4*)(qa + 64 * kw) = (r.ok >> kw) & 1u ? r.a[kw] : zero;
+        *(f4*)(lds_b(buf) + line * TB::kPitch + c4) = (r.ok & 8u) ? r.b : zero;
     };
 
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int lane32 = lane % 32, half = lane / 32;
-    const int wm0 = (wave / 2) * 32, wn0 = (wave % 2) * 32;    // 2 x 2 wavefronts of 32 x 32
+    const int wm0 = (wave / 2) * 96, wn0 = (wave % 2) * 32;
 
-    f16v acc;
+    f16v acc[TM];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-    // the bias gradient is the column sum of dout over the pixel range: formed once per range (tap 0, first row block)
-    const bool col_sums = tap == 0 && tm == 0 && threadIdx.x < kBN;
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    // the bias gradient is the column sum of dout over the pixel range: formed once per range (kernel row 0, first block)
+    const bool col_sums = kh == 0 && tm == 0 && threadIdx.x < kBN;
     float col_acc = 0.0f;
 
     constexpr int Q = BK / 8;
-    f4 fa[2], fb[2];
+    f4 fa[2][TM], fb[2];
     auto load_frags = [&](int buf, int cur, int q) {
-        fa[buf] = TA::frag(lds_a(cur), wm0, q, lane32, half);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[buf][i] = TA::frag(lds_a(cur), wm0 + 32 * i, q, lane32, half);
         fb[buf] = TB::frag(lds_b(cur), wn0, q, lane32, half);
     };
     auto mfmas = [&](int buf) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[buf][e], fb[buf][e], acc, 0, 0, 0);
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int i = 0; i < TM; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[buf][i][e], fb[buf][e], acc[i], 0, 0, 0);
     };
-
+    auto slice = [&](int cur, const Staged& next) {
+#pragma unroll
+        for (int q = 0; q + 1 < Q; ++q) {
+            load_frags((q + 1) & 1, cur, q + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(q & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (col_sums) {
+#pragma unroll
+            for (int k = 0; k < BK; ++k) col_acc += lds_b(cur)[k * TB::kPitch + threadIdx.x];
+        }
+        store_ab(cur ^ 1, next);
+        __syncthreads();
+        load_frags(0, cur ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas((Q - 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Slices past the pixel range are zero-filled: they add nothing to the sums.
     const int nk = k_hi > k_lo ? (k_hi - k_lo + BK - 1) / BK : 0;
-    if (nk > 0) {
-        f4 ra[TA::kPerThread], rb[TB::kPerThread];
-        unsigned oka = load_a(ra);
-        unsigned okb = TB::load(rb, DOUT, C, n0, k_lo, C, k_hi);
-        TA::store(lds_a(0), ra, oka);
-        TB::store(lds_b(0), rb, okb);
+    if (nk > 0 && DEPTH == 1) {
+        Staged r;
+        load_ab(r);
+        store_ab(0, r);
         __syncthreads();
         load_frags(0, 0, 0);
         for (int kt = 0; kt < nk; ++kt) {
-            const int cur = kt & 1;
-            oka = load_a(ra);                                            // slice kt + 1 (zero-filled past the range)
-            okb = TB::load(rb, DOUT, C, n0, k_lo + (kt + 1) * BK, C, k_hi);
-#pragma unroll
-            for (int q = 0; q + 1 < Q; ++q) {
-                load_frags((q + 1) & 1, cur, q + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                mfmas(q & 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            if (col_sums) {
-#pragma unroll
-                for (int k = 0; k < BK; ++k) col_acc += lds_b(cur)[k * TB::kPitch + threadIdx.x];
-            }
-            TA::store(lds_a(cur ^ 1), ra, oka);
-            TB::store(lds_b(cur ^ 1), rb, okb);
-            __syncthreads();
-            load_frags(0, cur ^ 1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            mfmas((Q - 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
+            load_ab(r);          // slice kt + 1
+            slice(kt & 1, r);
+        }
+    } else if (nk > 0) {
+        // two slices of global loads in flight; slices are consumed in pairs
+        Staged r0, r1;
+        load_ab(r0);
+        load_ab(r1);
+        store_ab(0, r0);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        const int nk2 = (nk + 1) & ~1;
+        for (int kt = 0; kt < nk2; kt += 2) {
+            load_ab(r0);         // slice kt + 2
+            slice(0, r1);
+            load_ab(r1);         // slice kt + 3
+            slice(1, r0);
         }
     }
     const int64_t per_group = (int64_t)9 * C * C + C;
@@ -335,9 +412,13 @@ __global__ __launch_bounds__(kThreads) void conv3x3_dw_kernel(ConvDev p) {
     const int col = n0 + wn0 + lane32;
     if (col < C) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm0 + 8 * (r / 4) + 4 * half + (r % 4);
-            if (row < C) PART[((int64_t)tap * C + row) * C + col] = acc[r];
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int trow = wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);   // 0 .. 191: (kw, ci inside the block)
+                const int kw = trow / 64, row = m0 + trow % 64;
+                if (row < C) PART[((int64_t)(kh * 3 + kw) * C + row) * C + col] = acc[i][r];
+            }
         }
     }
 }
@@ -420,7 +501,16 @@ hipError_t conv_launch(const ConvArgs& a, hipStream_t s) {
     p.s_in = a.s_in; p.s_w = a.s_w; p.s_out = a.s_out; p.s_bias = a.s_bias; p.s_res = a.s_res; p.s_mask = a.s_mask;
     p.groups = a.groups; p.B = a.B; p.H = a.H; p.W = a.W; p.C = a.C; p.P = a.B * a.H * a.W;
     p.relu = a.relu;
-    constexpr int BM = 128;
+#ifndef OLS_CONV_BM
+#define OLS_CONV_BM 128
+#endif
+#ifndef OLS_CONV_BK
+#define OLS_CONV_BK 16
+#endif
+#ifndef OLS_CONV_DEPTH
+#define OLS_CONV_DEPTH 2
+#endif
+    constexpr int BM = OLS_CONV_BM;
     p.tiles_m = (p.P + BM - 1) / BM;
     p.tiles_n = (a.C + kBN - 1) / kBN;
     const int64_t total = (int64_t)a.groups * p.tiles_m * p.tiles_n;
@@ -428,8 +518,8 @@ hipError_t conv_launch(const ConvArgs& a, hipStream_t s) {
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
     const unsigned grid = (unsigned)(p.chunk * kXcds);
-    if (a.C % 32 == 0) conv3x3_kernel<MODE, BM, 32><<<grid, kThreads, 0, s>>>(p);
-    else conv3x3_kernel<MODE, BM, 16><<<grid, kThreads, 0, s>>>(p);
+    if (a.C % OLS_CONV_BK == 0) conv3x3_kernel<MODE, BM, OLS_CONV_BK, OLS_CONV_DEPTH><<<grid, kThreads, 0, s>>>(p);
+    else conv3x3_kernel<MODE, BM, 16, OLS_CONV_DEPTH><<<grid, kThreads, 0, s>>>(p);
     return hipGetLastError();
 }
 
@@ -440,11 +530,11 @@ hipError_t launch_conv3x3_dx(const ConvArgs& a, hipStream_t s) { return conv_lau
 
 int conv3x3_dw_splits(int groups, int B, int H, int W, int C) {
     const int64_t P = (int64_t)B * H * W;
-    const int64_t tiles = (int64_t)groups * 9 * ((C + 63) / 64) * ((C + 63) / 64);
-    int64_t s = (2048 + tiles - 1) / tiles;                 // about eight workgroups per compute unit
+    const int64_t tiles = (int64_t)groups * 3 * ((C + 63) / 64) * ((C + 63) / 64);   // one per kernel row and 64 x 64 block
+    int64_t s = (1536 + tiles - 1) / tiles;                 // about six workgroups per compute unit
     const int64_t most = (P + 1023) / 1024;                 // a range covers at least 1024 pixels
     if (s > most) s = most;
-    if (s > 64) s = 64;
+    if (s > 32) s = 32;
     return s < 1 ? 1 : (int)s;
 }
 
@@ -456,15 +546,21 @@ hipError_t launch_conv3x3_dw(const ConvArgs& a, hipStream_t s) {
     p.s_in = a.s_in; p.s_dout = a.s_dout;
     p.groups = a.groups; p.B = a.B; p.H = a.H; p.W = a.W; p.C = a.C; p.P = a.B * a.H * a.W;
     p.splits = conv3x3_dw_splits(a.groups, a.B, a.H, a.W, a.C);
-    constexpr int BK = 32;
+#ifndef OLS_CONV_DW_BK
+#define OLS_CONV_DW_BK 16
+#endif
+#ifndef OLS_CONV_DW_DEPTH
+#define OLS_CONV_DW_DEPTH 2
+#endif
+    constexpr int BK = OLS_CONV_DW_BK;
     p.k_chunk = (int)(((((int64_t)p.P + p.splits - 1) / p.splits) + BK - 1) / BK * BK);
     p.tiles_n = (a.C + 63) / 64;
     p.tiles_m = p.tiles_n;
-    const int64_t total = (int64_t)a.groups * p.splits * 9 * p.tiles_n * p.tiles_n;
+    const int64_t total = (int64_t)a.groups * p.splits * 3 * p.tiles_n * p.tiles_n;
     if (total > (1 << 30)) return hipErrorInvalidValue;
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
-    conv3x3_dw_kernel<BK><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
+    conv3x3_dw_kernel<BK, OLS_CONV_DW_DEPTH><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t n_w = (int64_t)9 * a.C * a.C, per_group = n_w + a.C;
