@@ -40,7 +40,9 @@ def parse():
     ap.add_argument("--side-cpu-seconds", type=float, default=3.0,
                     help="target CPU time of the oracle baseline of each side configuration (at least one round)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
-    ap.add_argument("--serialize", type=int, default=0, help="1: anchor refresh on the main stream (no overlap)")
+    ap.add_argument("--serialize", type=int, default=2,
+                    help="0: anchor refresh on the side stream (overlapped), 1: on the main stream, 2 (default, the "
+                         "library's own): overlapped unless the refresh moves at most 1 MiB")
     ap.add_argument("--fuse-mean", type=int, default=None,
                     help="1: step + pull-back + anchor refresh in one pass.  Default: 1 on the update-only stream "
                          "(configuration 4 asks for the fused step + pull-back + mean, and an HBM-bound stream gains "
@@ -230,19 +232,21 @@ def measure(idx, args, K, W, cpu_seconds, side):
     cfg = I.get(idx)
     if not side and args.tau is not None:
         cfg = cfg.scaled(tau=args.tau)
-    serialize = 0 if side else args.serialize
+    serialize = 2 if side else args.serialize
     mixing = "none" if side else args.mixing
     delay = 0 if side else args.anchor_delay_us
     sync_rule = "paper" if side else args.sync_rule
     fuse_gemm_update = 1 if side else args.fuse_gemm_update
     second_buffer = True if side else not args.no_second_buffer
     fuse_mean = None if side else args.fuse_mean
-    plain = not serialize and mixing == "none" and not delay and sync_rule == "paper"
+    plain = serialize == 2 and mixing == "none" and not delay and sync_rule == "paper"
     if fuse_mean is None:
         fuse_mean = 1 if (cfg.kind == "stream" and plain) else 0
 
     sess = Session(cfg.m, cfg.d, cfg.tau, cfg.alpha, cfg.gamma, cfg.mu,
                    overlap_buffer=second_buffer, own_gradient=cfg.kind != "stream")
+    # what the library's default (2) resolves to: in line when the refresh moves at most 1 MiB
+    in_line = serialize == 1 or (serialize == 2 and (4 * cfg.m + 4) * sess.ld <= (1 << 20))
     sess.set_option(B.OLS_OPT_NESTEROV, int(cfg.nesterov))
     sess.set_option(B.OLS_OPT_SERIALIZE, serialize)
     sess.set_option(B.OLS_OPT_FUSE_MEAN, fuse_mean)
@@ -339,7 +343,7 @@ def measure(idx, args, K, W, cpu_seconds, side):
     if plain and (side or not args.no_kernel_timing):
         finish_round()
         for name, (fm, ser) in (("overlapped_side_stream", (0, 0)), ("serialized", (0, 1))):
-            if fm == fuse_mean and ser == serialize:
+            if fm == fuse_mean and ser == (1 if in_line else 0):
                 variants[name] = 1e3 * elapsed / K
                 continue
             sess.set_option(B.OLS_OPT_FUSE_MEAN, fm)
@@ -361,7 +365,7 @@ def measure(idx, args, K, W, cpu_seconds, side):
     config = {"workload": cfg.name, "m": cfg.m, "d": cfg.d, "tau": cfg.tau, "batch": cfg.batch,
               "dims": list(cfg.dims), "sync_rule": sync_rule,
               "overlap": ("mixing-kernel:" + mixing) if mixing != "none" else
-              ("serialized" if serialize else ("fused-mean" if fuse_mean else "side-stream")),
+              ("fused-mean" if fuse_mean else ("serialized" if in_line else "side-stream")),
               "second_buffer": second_buffer, "anchor_delay_us": delay,
               "loop": "library" if cfg.kind != "stream" and not (not side and args.loop == "python") else "python",
               "update": "in-gradient-kernels" if (fuse_gemm_update and cfg.kind != "stream") else "streaming"}
@@ -403,7 +407,7 @@ def main():
     if K < 1 or W < 0:
         print("bench.py: --steps must be >= 1 and --warmup >= 0", file=sys.stderr)
         sys.exit(2)
-    default_options = (not args.serialize and args.fuse_mean is None and args.mixing == "none" and not args.anchor_delay_us
+    default_options = (args.serialize == 2 and args.fuse_mean is None and args.mixing == "none" and not args.anchor_delay_us
                        and args.sync_rule == "paper" and args.fuse_gemm_update == 1 and not args.no_second_buffer
                        and not args.opt and args.loop == "library" and not args.no_kernel_timing and args.tau is None
                        and not args.calibration_copy_mib)

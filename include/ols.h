@@ -60,7 +60,11 @@ enum {
     OLS_OPT_FUSE_PULL = 2,     /* 1 (default): the tau-th local step of a round defers its parameter write and
                                   ols_sync_pull applies step + pull-back in ONE pass over HBM; 0: two passes.
                                   Both orders execute the same fp32 operation sequence per element.           */
-    OLS_OPT_SERIALIZE = 3,     /* 1: the anchor refresh runs on the main stream (no overlap); default 0       */
+    OLS_OPT_SERIALIZE = 3,     /* 0: the anchor refresh runs on the side stream, overlapped with the next round
+                                  (the paper's schedule); 1: on the main stream (blocking); 2 (default): overlapped
+                                  unless the refresh moves at most 1 MiB ((4 m + 4) ld bytes), where the two
+                                  cross-stream synchronisations of a round cost more than the refresh they would
+                                  hide.  Results are identical bit for bit in all three.                        */
     OLS_OPT_DRY_RUN = 4,       /* 1: advance the schedule and record the launch trace but launch nothing
                                   (host-logic tests on machines without a GPU); default 0                     */
     OLS_OPT_KERNEL_TIMING = 5, /* 1: bracket every kernel with HIP events on its own stream and accumulate

@@ -66,8 +66,9 @@ struct ols_ctx {
     hipStream_t stream[2] = {nullptr, nullptr};
     bool bound = false, inited = false, launched = false;
     // options
-    bool nesterov = true, fuse_pull = true, serialize = false, dry = false, timing = false, trace = false,
+    bool nesterov = true, fuse_pull = true, dry = false, timing = false, trace = false,
          fuse_mean = false, fuse_gemm_update = true;
+    int serialize_mode = 2;   // 0: refresh on the side stream, 1: on the main stream, 2: chosen from the refresh's size
     int mean_split = 0;
     int64_t anchor_delay_us = 0;   // emulated communication latency ahead of every anchor refresh
     int gemm_variant[3] = {0, 0, 0};  // fwd, dw, da
@@ -194,6 +195,14 @@ int enqueue(ols_ctx* c, int kind, int stream_id, int src_buf, int dst_buf, F&& l
         c->timed.push_back(t);
     }
     return OLS_OK;
+}
+
+// Whether the anchor refresh runs on the main stream.  Overlapping costs two cross-stream synchronisations per round
+// (about 10 us on the main stream); a refresh that moves less than a MiB takes less than that, so by default such
+// small problems run it in line -- the schedule of the paper pays once the refresh is longer than the hand-over.
+bool serialized(const ols_ctx* c) {
+    if (c->serialize_mode != 2) return c->serialize_mode == 1;
+    return (4 * (int64_t)c->m + 4) * c->ld <= (1 << 20);
 }
 
 // The main stream must not pass this point before the in-flight anchor refresh has finished.
@@ -588,7 +597,7 @@ int pick_buffers(ols_ctx* c, int* src, int* dst, bool defer = false) {
     *dst = c->cur;
     if (c->first_after_anchor) {
         c->first_after_anchor = false;
-        if (c->x[1] && !c->serialize) {
+        if (c->x[1] && !serialized(c)) {
             *dst = 1 - c->cur;  // the side stream may still be reading x[cur]
         } else if (defer) {
             c->wait_before_update = c->anchor_inflight;
@@ -1024,7 +1033,7 @@ int ols_anchor_update_async(ols_handle c) {
         c->anchor_precomputed = false;
         return OLS_OK;
     }
-    const int sid = (c->serialize || c->stream[1] == c->stream[0]) ? 0 : 1;
+    const int sid = (serialized(c) || c->stream[1] == c->stream[0]) ? 0 : 1;
     if (sid == 1 && !c->dry) {
         hipError_t e = hipStreamWaitEvent(c->stream[1], c->ev_pulled, 0);
         if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent");
@@ -1174,7 +1183,10 @@ int ols_set_option(ols_handle c, int key, int64_t value) {
             if (c->pending_update) return fail(OLS_ESTATE, "cannot change fusion while a deferred step is pending");
             c->fuse_pull = value != 0;
             break;
-        case OLS_OPT_SERIALIZE: c->serialize = value != 0; break;
+        case OLS_OPT_SERIALIZE:
+            if (value < 0 || value > 2) return fail(OLS_EINVAL, "OLS_OPT_SERIALIZE takes 0 (overlap), 1 (serialise) or 2 (from the size)");
+            c->serialize_mode = (int)value;
+            break;
         case OLS_OPT_DRY_RUN:
             if (c->launched) return fail(OLS_ESTATE, "dry-run mode must be chosen before anything is launched");
             c->dry = value != 0;

@@ -45,6 +45,7 @@ def test_create_rejects_bad_arguments(args):
 def dry(m=4, d=100, tau=2, alpha=0.6, gamma=0.1, mu=0.9, alt=True, trace=True):
     h = B.ols_create(m, d, tau, alpha, gamma, mu)
     B.ols_set_option(h, B.OLS_OPT_DRY_RUN, 1)
+    B.ols_set_option(h, B.OLS_OPT_SERIALIZE, 0)       # the paper's overlapped schedule, also for these tiny problems
     if trace:
         B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
     ld = B.ols_row_stride(d)
@@ -537,4 +538,18 @@ def test_convblock_attachment_and_launch_plan():
     B.ols_anchor_update_async(h)
     one = ["conv_fwd", "conv_fwd", "pool", "head_fwd", "head_bwd", "pool_bwd", "conv_dx", "conv_dw", "conv_dw"]
     assert kinds(B.ols_trace(h)) == one + ["step"] + one + ["step_pull", "mean"]
+    B.ols_destroy(h)
+
+
+def test_tiny_refreshes_run_in_line_by_default():
+    """OLS_OPT_SERIALIZE defaults to 2: the refresh is overlapped unless it moves at most 1 MiB."""
+    for d, stream in ((100, 0), (100000, 1)):
+        h = dry(m=4, d=d, tau=2)
+        B.ols_set_option(h, B.OLS_OPT_SERIALIZE, 2)
+        run_rounds(h, 2, 2)
+        means = [t for t in B.ols_trace(h) if B.ols_kernel_name(t["kind"]) == "mean"]
+        assert len(means) == 2 and all(t["stream"] == stream for t in means)
+        B.ols_destroy(h)
+    h = dry()
+    assert code_of(B.ols_set_option, h, B.OLS_OPT_SERIALIZE, 3) == B.OLS_EINVAL
     B.ols_destroy(h)
