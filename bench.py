@@ -10,8 +10,8 @@ HBM.  The headline workload is configuration 4, the update-only stream (m = 16 r
 it is the one the metric's "fused update / anchor-average HBM GB/s" is defined on.  Prints ONE JSON line:
 worker-iterations/s over exactly K timed steps after exactly W warm-up steps, the roofline of the dominant kernel
 from HIP-event timing on the kernel's own stream, the CPU oracle timed on a bounded sample of the same workload as a
-reported baseline, and under "configs" one compact record per other configuration (its own run length, stated in
-the record): ms per step overlapped and serialised, the dominant kernel and its roofline fraction, the oracle's rate.
+reported baseline, and under "configs" one compact record per other configuration (1, 2, 3, 5 and the convolutional
+workload 6; its own run length, stated in the record): ms per step overlapped and serialised, the dominant kernel and its roofline fraction, the oracle's rate.
 """
 import argparse
 import json
@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--config", type=int, default=4, help="headline workload number (BASELINE configs are 1-based)")
     ap.add_argument("--side-configs", type=str, default=None,
                     help="comma-separated configurations measured after the headline and reported under \"configs\" "
-                         "(default: 1,2,3,5 when the headline is configuration 4 with default options, else none)")
+                         "(default: 1,2,3,5,6 when the headline is configuration 4 with default options, else none)")
     ap.add_argument("--side-cpu-seconds", type=float, default=3.0,
                     help="target CPU time of the oracle baseline of each side configuration (at least one round)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
@@ -412,7 +412,7 @@ def main():
                        and not args.opt and args.loop == "library" and not args.no_kernel_timing and args.tau is None
                        and not args.calibration_copy_mib)
     if args.side_configs is None:
-        sides = [1, 2, 3, 5] if (args.config == 4 and default_options) else []
+        sides = [1, 2, 3, 5, 6] if (args.config == 4 and default_options) else []
     else:
         sides = [int(t) for t in args.side_configs.split(",") if t.strip()]
 
@@ -420,9 +420,11 @@ def main():
     configs = {}
     for idx in sides:
         c = I.get(idx)
-        # run length of a side record: the configuration's own iteration count, at least 1000 steps; 200 warm-up steps
+        # run length of a side record: the configuration's own iteration count, at least 1000 steps, after 200 warm-up
+        # steps; the convolutional workload (7 ms per step) runs its own 100 iterations after 20
+        k_side, w_side = (c.K, 20) if c.kind == "conv" else (max(c.K, 1000), 200)
         try:
-            configs[c.name] = compact(measure(idx, args, max(c.K, 1000), 200, args.side_cpu_seconds, side=True))
+            configs[c.name] = compact(measure(idx, args, k_side, w_side, args.side_cpu_seconds, side=True))
         except Exception as exc:   # a side record must not cost the headline
             configs[c.name] = {"workload": c.name, "error": "%s: %s" % (type(exc).__name__, exc)}
 
