@@ -10,20 +10,33 @@ from the definition of the operations, in double, with no blocking or fusion:
     pooled = mean over the H x W positions of a2
     logits = pooled Wh + bh;   loss = mean over the batch of softmax cross-entropy
 
+With batch normalisation (the block as the residual network has it; `convblock_bn_loss_grad`) the convolutions carry
+no bias and each is followed by a normalisation over the mini-batch and the positions, per channel, in training mode:
+
+    z1 = conv3x3(X; Wa);   a1 = relu(bn(z1; ga, ba))
+    z2 = conv3x3(a1; Wb);  a2 = relu(bn(z2; gb, bb) + X)
+    bn(z; g, b)[n][y][x][c] = g[c] (z[n][y][x][c] - mean_c) / sqrt(var_c + eps) + b[c]
+
+with mean_c and the (biased) variance var_c taken over all samples and positions of the worker's mini-batch.
+
 Readings (the paper names the architecture and nothing more): the block is the two-convolution residual block with
-identity shortcut, 3 x 3 kernels, stride 1, zero padding 1, biases in place of batch normalisation (batch statistics
-are not part of the data-parallel hot path this oracle serves); "convolution" is the cross-correlation every
+identity shortcut, 3 x 3 kernels, stride 1, zero padding 1; without batch normalisation biases take its place; with
+it, the statistics are those of the worker's own mini-batch (each worker normalises alone, as each node of the paper's
+cluster does), the variance is the biased one, eps = 1e-5 (the common framework default), and no running averages are
+kept (they play no part in training); "convolution" is the cross-correlation every
 deep-learning framework computes: out[y][x] = sum_{kh,kw} in[y + kh - 1][x + kw - 1] W[kh][kw]; the ReLU derivative
 at 0 is 0; the loss is the mean over the mini-batch (as for the other models).
 
 Layouts (an interface shared with the device path; each side computes its own offsets): activations are
 [batch][height][width][channel]; the flat parameter vector holds Wa [3][3][C][C] (kh, kw, input channel, output
-channel), ba [C], Wb [3][3][C][C], bb [C], Wh [C][classes], bh [classes], in that order.
+channel), ba [C], Wb [3][3][C][C], bb [C], Wh [C][classes], bh [classes], in that order; with batch normalisation
+Wa, ga [C], ba [C], Wb, gb [C], bb [C], Wh, bh (scale before shift).
 
 Only tests/, the smoke check and the benchmark's CPU-baseline leg may import this module.
-Pinned by tests/test_oracle_conv_pins.py: torch's CPU conv2d and autograd as library routines, a pure-Python
-brute-force convolution, single-tap kernels that pin the tap orientation and the zero padding, central finite
-differences of the whole loss, and planted mistakes that those pins must notice.
+Pinned by tests/test_oracle_conv_pins.py: torch's CPU conv2d, batch_norm and autograd as library routines, a pure-Python
+brute-force convolution, single-tap kernels that pin the tap orientation and the zero padding, the normalised output's
+per-channel mean and variance, central finite differences of the whole loss, and planted mistakes that those pins must
+notice.
 """
 import numpy as np
 
@@ -106,4 +119,89 @@ def convblock_loss_grad(x, C, classes, X, labels):
     _, dWa, dba = conv3x3_backward(X, Wa, d_z1)                         # the input is data: its gradient is not needed
     gWa[...] = dWa
     gba[...] = dba
+    return loss, g
+
+
+BN_EPS = 1e-5
+
+
+def batchnorm_forward(z, gamma, beta, eps=BN_EPS):
+    """Training-mode batch normalisation per channel (last axis) over all other axes: returns (out, xhat, inv_std)."""
+    z, gamma, beta = np.asarray(z, F64), np.asarray(gamma, F64), np.asarray(beta, F64)
+    axes = tuple(range(z.ndim - 1))
+    mean = z.mean(axis=axes)
+    var = ((z - mean) ** 2).mean(axis=axes)            # biased variance
+    inv_std = 1.0 / np.sqrt(var + eps)
+    xhat = (z - mean) * inv_std
+    return gamma * xhat + beta, xhat, inv_std
+
+
+def batchnorm_backward(dout, xhat, inv_std, gamma):
+    """Gradients of sum(out * dout) through batchnorm_forward: (d_z, d_gamma, d_beta).
+    d_z = gamma inv_std (dout - mean(dout) - xhat mean(dout xhat)), the means per channel over samples and positions."""
+    dout, xhat = np.asarray(dout, F64), np.asarray(xhat, F64)
+    axes = tuple(range(dout.ndim - 1))
+    d_beta = dout.sum(axis=axes)
+    d_gamma = (dout * xhat).sum(axis=axes)
+    count = dout.size // dout.shape[-1]
+    d_z = np.asarray(gamma, F64) * inv_std * (dout - d_beta / count - xhat * (d_gamma / count))
+    return d_z, d_gamma, d_beta
+
+
+def convblock_bn_param_count(C, classes):
+    return 2 * (9 * C * C + 2 * C) + C * classes + classes
+
+
+def convblock_bn_unpack(x, C, classes):
+    """Views (Wa, ga, ba, Wb, gb, bb, Wh, bh) of the flat parameter vector."""
+    out, off = [], 0
+    for shape in ((3, 3, C, C), (C,), (C,), (3, 3, C, C), (C,), (C,), (C, classes), (classes,)):
+        size = int(np.prod(shape))
+        out.append(x[off:off + size].reshape(shape))
+        off += size
+    assert off == x.shape[0]
+    return out
+
+
+def convblock_bn_loss_grad(x, C, classes, X, labels, eps=BN_EPS):
+    """The residual block with batch normalisation + pooled linear classifier: (mean cross-entropy over the batch,
+    flat gradient in x's layout).  X [B][H][W][C], labels [B]."""
+    x = np.asarray(x, F64)
+    X = np.asarray(X, F64)
+    Wa, ga, ba, Wb, gb, bb, Wh, bh = convblock_bn_unpack(x, C, classes)
+    B = X.shape[0]
+    zero = np.zeros(C)
+    z1 = conv3x3_forward(X, Wa, zero)
+    n1, xhat1, istd1 = batchnorm_forward(z1, ga, ba, eps)
+    a1 = np.maximum(n1, 0.0)
+    z2 = conv3x3_forward(a1, Wb, zero)
+    n2, xhat2, istd2 = batchnorm_forward(z2, gb, bb, eps)
+    a2 = np.maximum(n2 + X, 0.0)
+    pooled = a2.mean(axis=(1, 2))
+    logits = pooled @ Wh + bh
+    shifted = logits - logits.max(axis=1, keepdims=True)
+    logsumexp = np.log(np.exp(shifted).sum(axis=1))
+    rows = np.arange(B)
+    loss = float((logsumexp - shifted[rows, labels]).mean())
+    dlogits = np.exp(shifted - logsumexp[:, None])
+    dlogits[rows, labels] -= 1.0
+    dlogits /= B
+    g = np.empty_like(x)
+    gWa, gga, gba, gWb, ggb, gbb, gWh, gbh = convblock_bn_unpack(g, C, classes)
+    gWh[...] = pooled.T @ dlogits
+    gbh[...] = dlogits.sum(axis=0)
+    d_pooled = dlogits @ Wh.T
+    positions = X.shape[1] * X.shape[2]
+    d_n2 = (d_pooled[:, None, None, :] / positions) * (a2 > 0.0)       # through the mean and the second ReLU
+    d_z2, dgb, dbb = batchnorm_backward(d_n2, xhat2, istd2, gb)
+    ggb[...] = dgb
+    gbb[...] = dbb
+    d_a1, dWb, _ = conv3x3_backward(a1, Wb, d_z2)
+    gWb[...] = dWb
+    d_n1 = d_a1 * (a1 > 0.0)
+    d_z1, dga, dba = batchnorm_backward(d_n1, xhat1, istd1, ga)
+    gga[...] = dga
+    gba[...] = dba
+    _, dWa, _ = conv3x3_backward(X, Wa, d_z1)
+    gWa[...] = dWa
     return loss, g

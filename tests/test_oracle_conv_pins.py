@@ -194,3 +194,119 @@ def test_planted_backward_mistakes_are_noticed(monkeypatch):
     monkeypatch.setattr(CO, "conv3x3_backward", swapped_taps)
     with pytest.raises(AssertionError):
         test_block_matches_torch_autograd_including_the_flat_layout()
+
+
+# ---- batch normalisation ------------------------------------------------------------------------------------
+def test_batchnorm_output_has_the_prescribed_channel_statistics():
+    z, g, b = rand((4, 3, 5, 6), 40, 2.0) + 3.0, rand((6,), 41), rand((6,), 42)
+    out, xhat, inv_std = CO.batchnorm_forward(z, g, b)
+    np.testing.assert_allclose(xhat.mean(axis=(0, 1, 2)), 0.0, atol=1e-13)
+    np.testing.assert_allclose(out.mean(axis=(0, 1, 2)), b, atol=1e-12)
+    # biased variance of the normalised values is var / (var + eps): just below one
+    var = z.var(axis=(0, 1, 2))
+    np.testing.assert_allclose(xhat.var(axis=(0, 1, 2)), var / (var + CO.BN_EPS), rtol=1e-12)
+    np.testing.assert_allclose(inv_std, 1.0 / np.sqrt(var + CO.BN_EPS), rtol=1e-13)
+
+
+def test_batchnorm_matches_torch_forward_and_backward():
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    z, g, b, dout = rand((3, 4, 5, 6), 50), rand((6,), 51), rand((6,), 52), rand((3, 4, 5, 6), 53)
+    tz = torch.tensor(z).permute(0, 3, 1, 2).contiguous().requires_grad_(True)
+    tg, tb = torch.tensor(g, requires_grad=True), torch.tensor(b, requires_grad=True)
+    to = F.batch_norm(tz, None, None, tg, tb, training=True, eps=CO.BN_EPS)
+    out, xhat, inv_std = CO.batchnorm_forward(z, g, b)
+    np.testing.assert_allclose(out, to.detach().permute(0, 2, 3, 1).numpy(), atol=1e-12)
+    to.backward(torch.tensor(dout).permute(0, 3, 1, 2))
+    d_z, d_g, d_b = CO.batchnorm_backward(dout, xhat, inv_std, g)
+    np.testing.assert_allclose(d_z, tz.grad.permute(0, 2, 3, 1).numpy(), atol=1e-12)
+    np.testing.assert_allclose(d_g, tg.grad.numpy(), atol=1e-12)
+    np.testing.assert_allclose(d_b, tb.grad.numpy(), atol=1e-12)
+
+
+def bn_block_case(seed, B=3, C=4, H=5, Wd=4, classes=3):
+    d = CO.convblock_bn_param_count(C, classes)
+    x = rand((d,), seed, 0.3)
+    Wa, ga, ba, Wb, gb, bb, Wh, bh = CO.convblock_bn_unpack(x, C, classes)
+    ga += 1.0
+    gb += 1.0                                         # scales around one, as at initialisation
+    X = rand((B, H, Wd, C), seed + 1)
+    labels = np.random.default_rng(seed + 2).integers(0, classes, B)
+    return x, C, classes, X, labels
+
+
+def test_bn_block_gradient_matches_central_finite_differences():
+    x, C, classes, X, labels = bn_block_case(60)
+    loss, g = CO.convblock_bn_loss_grad(x, C, classes, X, labels)
+    rng = np.random.default_rng(1)
+    groups = CO.convblock_bn_unpack(np.arange(x.size), C, classes)
+    picks = np.concatenate([rng.choice(grp.ravel(), min(5, grp.size), replace=False) for grp in groups])
+    eps = 1e-6
+    for j in picks:
+        e = np.zeros_like(x)
+        e[j] = eps
+        fd = (CO.convblock_bn_loss_grad(x + e, C, classes, X, labels)[0] - CO.convblock_bn_loss_grad(x - e, C, classes, X, labels)[0]) / (2 * eps)
+        assert abs(fd - g[j]) <= 2e-7 * max(1.0, abs(g[j])), (j, fd, g[j])
+
+
+def test_bn_block_matches_torch_autograd_including_the_flat_layout():
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    x, C, classes, X, labels = bn_block_case(70, B=4, C=3, H=4, Wd=6, classes=5)
+    loss, g = CO.convblock_bn_loss_grad(x, C, classes, X, labels)
+    tx = torch.tensor(x, requires_grad=True)
+    off = 0
+
+    def take(shape):
+        nonlocal off
+        n = int(np.prod(shape))
+        t = tx[off:off + n].reshape(shape)
+        off += n
+        return t
+    Wa, ga, ba, Wb, gb, bb, Wh, bh = (take(s) for s in ((3, 3, C, C), (C,), (C,), (3, 3, C, C), (C,), (C,), (C, classes), (classes,)))
+    tX = torch.tensor(X).permute(0, 3, 1, 2)
+    bn = lambda z, g_, b_: F.batch_norm(z, None, None, g_, b_, training=True, eps=CO.BN_EPS)
+    a1 = F.relu(bn(F.conv2d(tX, Wa.permute(3, 2, 0, 1), None, padding=1), ga, ba))
+    a2 = F.relu(bn(F.conv2d(a1, Wb.permute(3, 2, 0, 1), None, padding=1), gb, bb) + tX)
+    logits = a2.mean(dim=(2, 3)) @ Wh + bh
+    tl = F.cross_entropy(logits, torch.tensor(labels), reduction="mean")
+    tl.backward()
+    assert abs(loss - tl.item()) <= 1e-12 * abs(loss)
+    np.testing.assert_allclose(g, tx.grad.numpy(), atol=1e-11)
+
+
+def test_bn_makes_the_loss_invariant_to_the_scale_of_a_kernel():
+    """A convolution followed by batch normalisation: scaling the kernel leaves the output (up to eps) and hence the
+    loss unchanged, and the kernel's gradient is orthogonal to the kernel."""
+    x, C, classes, X, labels = bn_block_case(80)
+    loss, g = CO.convblock_bn_loss_grad(x, C, classes, X, labels, eps=0.0)
+    x2 = x.copy()
+    Wa2 = CO.convblock_bn_unpack(x2, C, classes)[0]
+    Wa2 *= 3.0
+    loss2, _ = CO.convblock_bn_loss_grad(x2, C, classes, X, labels, eps=0.0)
+    assert abs(loss - loss2) <= 1e-12
+    Wa, gWa = CO.convblock_bn_unpack(x, C, classes)[0], CO.convblock_bn_unpack(g, C, classes)[0]
+    assert abs((Wa * gWa).sum()) <= 1e-12 * np.abs(Wa * gWa).sum()
+
+
+def test_planted_batchnorm_mistakes_are_noticed(monkeypatch):
+    orig_f, orig_b = CO.batchnorm_forward, CO.batchnorm_backward
+
+    def unbiased_variance(z, gamma, beta, eps=CO.BN_EPS):
+        z = np.asarray(z, np.float64)
+        axes = tuple(range(z.ndim - 1))
+        mean, var = z.mean(axis=axes), z.var(axis=axes, ddof=1)
+        inv = 1.0 / np.sqrt(var + eps)
+        xhat = (z - mean) * inv
+        return np.asarray(gamma) * xhat + np.asarray(beta), xhat, inv
+    monkeypatch.setattr(CO, "batchnorm_forward", unbiased_variance)
+    with pytest.raises(AssertionError):
+        test_batchnorm_matches_torch_forward_and_backward()
+    monkeypatch.setattr(CO, "batchnorm_forward", orig_f)
+
+    def drops_the_projection(dout, xhat, inv_std, gamma):     # treats mean and variance as constants
+        d_z, d_g, d_b = orig_b(dout, xhat, inv_std, gamma)
+        return np.asarray(gamma) * inv_std * np.asarray(dout), d_g, d_b
+    monkeypatch.setattr(CO, "batchnorm_backward", drops_the_projection)
+    with pytest.raises(AssertionError):
+        test_bn_block_gradient_matches_central_finite_differences()
