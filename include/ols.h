@@ -135,7 +135,9 @@ enum {
     OLS_K_CONV_DW = 20,   /* kernel and bias gradient of a 3 x 3 convolution                 */
     OLS_K_POOL = 21,      /* global average pooling in front of the classifier               */
     OLS_K_POOL_BWD = 22,  /* its backward                                                    */
-    OLS_K_COUNT = 23
+    OLS_K_BN_FWD = 23,    /* batch normalisation: statistics (two launches) + normalise, shortcut, ReLU */
+    OLS_K_BN_BWD = 24,    /* its backward: scale / shift gradients (two launches) + gradient at the input */
+    OLS_K_COUNT = 25
 };
 
 typedef struct ols_trace_entry {
@@ -242,6 +244,18 @@ OLS_API int ols_attach_mlp(ols_handle h, int n_layers, const int* dims, int batc
  * Inputs per ols_set_batch: X [B][height][width][channels] fp32 (channel contiguous), labels [B] int32.
  * Gradients go to g and the streaming kernels apply the update (the parameters are few: 74 k at 64 channels). */
 OLS_API int ols_attach_convblock(ols_handle h, int channels, int height, int width, int classes, int batch);
+
+/* The same block as the residual network of Section 4 has it, with batch normalisation: the convolutions carry no
+ * bias and each is followed by a normalisation per channel over all samples and positions of the worker's own
+ * mini-batch (training mode; every worker normalises alone, as every node of the paper's cluster does):
+ *     z1 = conv3x3(X; Wa);   a1 = relu(bn(z1; ga, ba));
+ *     z2 = conv3x3(a1; Wb);  a2 = relu(bn(z2; gb, bb) + X);   logits = mean_positions(a2) Wh + bh
+ *     bn(z; g, b)[c] = g[c] (z - mean_c) / sqrt(var_c + eps) + b[c],  var_c the biased variance.
+ * No running averages are kept (they play no part in training).  eps in (0, 1]; 1e-5 is the usual value.
+ *   Flat parameter layout: Wa, ga [channels], ba [channels], Wb, gb, bb, Wh, bh (scale before shift);
+ *   d = 2 (9 channels^2 + 2 channels) + channels classes + classes.  Other limits, inputs and errors as for
+ *   ols_attach_convblock.  The workspace keeps z1 and z2 for the backward pass beside the activations. */
+OLS_API int ols_attach_convblock_bn(ols_handle h, int channels, int height, int width, int classes, int batch, float eps);
 
 /* Bytes of caller-provided device workspace the attached model needs (activations, deltas, per-sample
  * losses, bf16 operand copies).  0 when no model is attached. */

@@ -39,15 +39,16 @@ class Config:
     seed: int = BASE_SEED
     beta_z: float = 0.0            # anchor momentum (0 = plain anchor average)
     nesterov: bool = True
+    batch_norm: bool = False       # conv: convolutions without bias, each followed by batch normalisation
 
     @property
     def d(self) -> int:
         if self.kind == "mlp":
             return sum(self.dims[l] * self.dims[l + 1] + self.dims[l + 1]
                        for l in range(len(self.dims) - 1))
-        if self.kind == "conv":    # two 3x3 kernels with biases, then the pooled linear classifier
+        if self.kind == "conv":    # two 3x3 kernels with biases (or scale + shift), then the pooled linear classifier
             c, _, _, classes = self.dims
-            return 2 * (9 * c * c + c) + c * classes + classes
+            return 2 * (9 * c * c + (2 * c if self.batch_norm else c)) + c * classes + classes
         return self.d_flat
 
     @property
@@ -77,6 +78,9 @@ CONFIGS = {
     # 32 x 32 inputs, 16 nodes, batch 128 per node): the network's first residual stage, 64 channels.
     6: Config(name="cfg6_convblock_m16", kind="conv", m=16, tau=2, alpha=0.6, gamma=0.05,
               mu=0.9, K=100, batch=128, dims=(64, 32, 32, 10), nb=2),
+    # the same stage as the residual network has it: batch normalisation after each convolution, no biases
+    7: Config(name="cfg7_convblock_bn_m16", kind="conv", m=16, tau=2, alpha=0.6, gamma=0.05,
+              mu=0.9, K=100, batch=128, dims=(64, 32, 32, 10), nb=2, batch_norm=True),
 }
 
 

@@ -147,11 +147,14 @@ def conv_data(cfg: Config, workers=None, nb=None):
 
 def conv_init(cfg: Config):
     """Common starting point x0 [d] fp32 in the block's flat layout (Wa, ba, Wb, bb, Wh, bh): kernels N(0, 1/fan_in)
-    with fan_in = 9 C, classifier N(0, 1/C), biases zero."""
+    with fan_in = 9 C, classifier N(0, 1/C), biases zero.  With batch normalisation (Wa, ga, ba, Wb, gb, bb, Wh, bh)
+    the scales start at one and the shifts at zero."""
     C, _, _, classes = cfg.dims
     parts = []
     for l, (count, fan_in, bias) in enumerate(((9 * C * C, 9 * C, C), (9 * C * C, 9 * C, C), (C * classes, C, classes))):
         parts.append(normal_f32(cfg.seed, TAG_CONV_INIT, 0, l, (count,), sigma=1.0 / np.sqrt(fan_in)))
+        if cfg.batch_norm and l < 2:
+            parts.append(np.ones(C, dtype=np.float32))
         parts.append(np.zeros(bias, dtype=np.float32))
     return np.concatenate(parts)
 

@@ -18,7 +18,7 @@ TUNE_FWD, TUNE_DW, TUNE_DA = 0, 256, 512    # OLS_OPT_TUNING value = one of thes
 (OLS_K_INIT, OLS_K_STEP, OLS_K_STEP_PULL, OLS_K_PULL, OLS_K_MEAN, OLS_K_STEP_PULL_MEAN, OLS_K_LSQ_RESID,
  OLS_K_LSQ_GRAD, OLS_K_GEMM_FWD, OLS_K_GEMM_DW, OLS_K_GEMM_DA, OLS_K_HEAD_FWD, OLS_K_HEAD_BWD, OLS_K_MIX,
  OLS_K_CAST, OLS_K_DELAY, OLS_K_LSQ_STEP, OLS_K_STALE_SYNC, OLS_K_CONV_FWD, OLS_K_CONV_DX, OLS_K_CONV_DW, OLS_K_POOL,
- OLS_K_POOL_BWD, OLS_K_COUNT) = range(24)
+ OLS_K_POOL_BWD, OLS_K_BN_FWD, OLS_K_BN_BWD, OLS_K_COUNT) = range(26)
 
 
 class ols_trace_entry(C.Structure):
@@ -47,6 +47,7 @@ _SIGNATURES = {
     "ols_attach_lsq": (C.c_int, [_H, C.c_int]),
     "ols_attach_mlp": (C.c_int, [_H, C.c_int, C.POINTER(C.c_int), C.c_int, C.c_int]),
     "ols_attach_convblock": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "ols_attach_convblock_bn": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]),
     "ols_workspace_bytes": (C.c_int64, [_H]),
     "ols_bind_workspace": (C.c_int, [_H, _P, C.c_int64]),
     "ols_set_batch": (C.c_int, [_H, _P, C.c_int64, _P, C.c_int64]),
@@ -156,6 +157,10 @@ def ols_attach_mlp(h, dims, batch, gemm_dtype):
 
 def ols_attach_convblock(h, channels, height, width, classes, batch):
     _check(load().ols_attach_convblock(h, channels, height, width, classes, batch))
+
+
+def ols_attach_convblock_bn(h, channels, height, width, classes, batch, eps=1e-5):
+    _check(load().ols_attach_convblock_bn(h, channels, height, width, classes, batch, eps))
 
 
 def ols_workspace_bytes(h):

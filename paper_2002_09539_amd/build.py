@@ -23,6 +23,7 @@ SOURCES = [
     "kernels_gemm_f32.hip",
     "kernels_gemm_bf16.hip",
     "kernels_conv.hip",
+    "kernels_bn.hip",
 ]
 
 # packed-fp32 VALU forms stay disabled for every device translation unit

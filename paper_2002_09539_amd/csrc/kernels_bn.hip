@@ -1,0 +1,257 @@
+// Batch normalisation of the residual block's convolution outputs (training mode: statistics of the worker's own
+// mini-batch, per channel over all samples and positions), forward and backward, grouped over the m workers.  Part of
+// the model that produces the stochastic gradients g_i of Section 2, arXiv 2002.09539 (Section 4 trains a residual
+// network, whose blocks normalise every convolution).
+//
+//   forward    mean_c, var_c over the P = B H W pixels;  inv_std_c = 1 / sqrt(var_c + eps)
+//              out = act( gamma_c (z - mean_c) inv_std_c + beta_c (+ shortcut) )
+//   backward   s1_c = sum_p dy,  s2_c = sum_p dy xhat   (= d beta, d gamma)
+//              dz = gamma_c inv_std_c (dy - s1_c / P - xhat s2_c / P)
+//
+// All four passes are HBM-bound streaming kernels over [group][P][C] tensors (channel contiguous, 16-byte vectors).
+// Reductions are deterministic: every workgroup reduces a contiguous pixel range in a fixed order, a second launch
+// combines the ranges in range order (no atomics).  The statistics use shifted sums -- each range subtracts the value of
+// its own first pixel before summing and squaring -- and the ranges are merged with the pairwise update of mean and
+// second moment, so nothing cancels when a channel's mean is large against its spread.
+#include "ols_internal.h"
+
+namespace ols {
+
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+constexpr int kThreads = 256;
+
+// pixel ranges per group: about 2048 pixels each, at most 256
+__host__ __device__ inline int bn_ranges(int P) {
+    int r = (P + 2047) / 2048;
+    return r < 1 ? 1 : (r > 256 ? 256 : r);
+}
+
+// Sums over the stripes of a workgroup, in stripe order; result valid for stripe 0.
+__device__ __forceinline__ f4 reduce_stripes(f4 v, f4* lds, int c4n, int stripes) {
+    lds[threadIdx.x] = v;
+    __syncthreads();
+    f4 acc = v;
+    if ((int)threadIdx.x < c4n)
+        for (int s = 1; s < stripes; ++s) acc = acc + lds[s * c4n + threadIdx.x];
+    __syncthreads();
+    return acc;
+}
+
+// part[group][range][3][C]: shift K (the range's first pixel), sum (z - K), sum (z - K)^2
+__global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float* __restrict__ z, int64_t s_z, float* part,
+                                                                    int P, int C, int ranges) {
+    __shared__ f4 lds[kThreads];
+    const int c4n = C / 4, stripes = kThreads / c4n;
+    const int c4 = threadIdx.x % c4n, stripe = threadIdx.x / c4n;
+    const int g = blockIdx.y, r = blockIdx.x;
+    const int chunk = (P + ranges - 1) / ranges;
+    const int p_lo = r * chunk, p_hi = min(P, p_lo + chunk);
+    const float* Z = z + (int64_t)g * s_z;
+    f4 K = {0.f, 0.f, 0.f, 0.f}, s1 = K, s2 = K;
+    if (p_lo < p_hi && stripe < stripes) {
+        K = *(const f4*)(Z + (int64_t)p_lo * C + 4 * c4);
+        for (int p = p_lo + stripe; p < p_hi; p += stripes) {
+            const f4 v = __builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C + 4 * c4)) - K;
+            s1 = s1 + v;
+            s2 = s2 + v * v;
+        }
+    }
+    s1 = reduce_stripes(s1, lds, c4n, stripes);
+    s2 = reduce_stripes(s2, lds, c4n, stripes);
+    if ((int)threadIdx.x < c4n) {
+        float* o = part + (((int64_t)g * ranges + r) * 3) * C + 4 * c4;
+        *(f4*)o = K;
+        *(f4*)(o + C) = s1;
+        *(f4*)(o + 2 * C) = s2;
+    }
+}
+
+// stats[group][2][C]: mean, 1 / sqrt(var + eps); the ranges are merged in range order
+__global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const float* __restrict__ part, float* stats, int P, int C,
+                                                                  int ranges, float eps) {
+    const int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= C) return;
+    const int g = blockIdx.y;
+    const int chunk = (P + ranges - 1) / ranges;
+    float n = 0.0f, mean = 0.0f, m2 = 0.0f;
+    for (int r = 0; r < ranges; ++r) {
+        const int p_lo = r * chunk, p_hi = min(P, p_lo + chunk);
+        if (p_lo >= p_hi) break;
+        const float nr = (float)(p_hi - p_lo);
+        const float* o = part + (((int64_t)g * ranges + r) * 3) * C + c;
+        const float K = o[0], s1 = o[C], s2 = o[2 * C];
+        const float mean_r = K + s1 / nr;
+        const float m2_r = s2 - s1 * (s1 / nr);
+        const float tot = n + nr, delta = mean_r - mean;
+        mean = mean + delta * (nr / tot);
+        m2 = m2 + m2_r + delta * delta * (n * (nr / tot));
+        n = tot;
+    }
+    const float var = fmaxf(m2 / n, 0.0f);
+    stats[((int64_t)g * 2) * C + c] = mean;
+    stats[((int64_t)g * 2 + 1) * C + c] = 1.0f / sqrtf(var + eps);
+}
+
+// out = act(gamma (z - mean) inv_std + beta (+ shortcut))
+__global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restrict__ z, int64_t s_z,
+                                                            const float* __restrict__ stats, const float* __restrict__ gamma,
+                                                            const float* __restrict__ beta, int64_t s_par,
+                                                            const float* __restrict__ shortcut, int64_t s_sc, float* out,
+                                                            int64_t s_out, int64_t vecs, int C, int relu) {
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= vecs) return;
+    const int g = blockIdx.y;
+    const int c = 4 * (int)(v % (C / 4));
+    const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + c);
+    const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + c);
+    const f4 ga = *(const f4*)(gamma + (int64_t)g * s_par + c);
+    const f4 be = *(const f4*)(beta + (int64_t)g * s_par + c);
+    const f4 zv = __builtin_nontemporal_load((const f4*)(z + (int64_t)g * s_z) + v);
+    f4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = __fmaf_rn(ga[e], (zv[e] - mean[e]) * istd[e], be[e]);
+    if (shortcut) o = o + __builtin_nontemporal_load((const f4*)(shortcut + (int64_t)g * s_sc) + v);
+    if (relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = fmaxf(o[e], 0.0f);
+    }
+    *((f4*)(out + (int64_t)g * s_out) + v) = o;
+}
+
+// part[group][range][2][C]: sum dy, sum dy xhat over the range
+__global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float* __restrict__ dy, int64_t s_dy,
+                                                                  const float* __restrict__ z, int64_t s_z,
+                                                                  const float* __restrict__ stats, float* part, int P, int C,
+                                                                  int ranges) {
+    __shared__ f4 lds[kThreads];
+    const int c4n = C / 4, stripes = kThreads / c4n;
+    const int c4 = threadIdx.x % c4n, stripe = threadIdx.x / c4n;
+    const int g = blockIdx.y, r = blockIdx.x;
+    const int chunk = (P + ranges - 1) / ranges;
+    const int p_lo = r * chunk, p_hi = min(P, p_lo + chunk);
+    const float* Z = z + (int64_t)g * s_z;
+    const float* D = dy + (int64_t)g * s_dy;
+    f4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = s1;
+    if (stripe < stripes) {
+        const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + 4 * c4);
+        const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + 4 * c4);
+        for (int p = p_lo + stripe; p < p_hi; p += stripes) {
+            const f4 d = __builtin_nontemporal_load((const f4*)(D + (int64_t)p * C + 4 * c4));
+            const f4 xh = (__builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C + 4 * c4)) - mean) * istd;
+            s1 = s1 + d;
+            s2 = s2 + d * xh;
+        }
+    }
+    s1 = reduce_stripes(s1, lds, c4n, stripes);
+    s2 = reduce_stripes(s2, lds, c4n, stripes);
+    if ((int)threadIdx.x < c4n) {
+        float* o = part + (((int64_t)g * ranges + r) * 2) * C + 4 * c4;
+        *(f4*)o = s1;
+        *(f4*)(o + C) = s2;
+    }
+}
+
+// sums[group][2][C] = the ranges' sums added in range order; d beta = sums[0], d gamma = sums[1] go to the gradient rows
+__global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const float* __restrict__ part, float* sums, float* g_out,
+                                                                int64_t ld, int64_t gamma_off, int64_t beta_off, int C,
+                                                                int ranges) {
+    const int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= C) return;
+    const int g = blockIdx.y;
+    float s1 = 0.0f, s2 = 0.0f;
+    for (int r = 0; r < ranges; ++r) {
+        const float* o = part + (((int64_t)g * ranges + r) * 2) * C + c;
+        s1 += o[0];
+        s2 += o[C];
+    }
+    sums[((int64_t)g * 2) * C + c] = s1;
+    sums[((int64_t)g * 2 + 1) * C + c] = s2;
+    g_out[(int64_t)g * ld + beta_off + c] = s1;
+    g_out[(int64_t)g * ld + gamma_off + c] = s2;
+}
+
+// dz = gamma inv_std (dy - s1 / P - xhat s2 / P), written over dy
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(float* dy, int64_t s_dy, const float* __restrict__ z,
+                                                                int64_t s_z, const float* __restrict__ stats,
+                                                                const float* __restrict__ sums,
+                                                                const float* __restrict__ gamma, int64_t s_par, int64_t vecs,
+                                                                int C, float inv_count) {
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= vecs) return;
+    const int g = blockIdx.y;
+    const int c = 4 * (int)(v % (C / 4));
+    const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + c);
+    const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + c);
+    const f4 s1 = *(const f4*)(sums + ((int64_t)g * 2) * C + c);
+    const f4 s2 = *(const f4*)(sums + ((int64_t)g * 2 + 1) * C + c);
+    const f4 ga = *(const f4*)(gamma + (int64_t)g * s_par + c);
+    f4* D = (f4*)(dy + (int64_t)g * s_dy) + v;
+    const f4 d = __builtin_nontemporal_load(D);
+    const f4 xh = (__builtin_nontemporal_load((const f4*)(z + (int64_t)g * s_z) + v) - mean) * istd;
+    f4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = ga[e] * istd[e] * (d[e] - s1[e] * inv_count - xh[e] * (s2[e] * inv_count));
+    *D = o;
+}
+
+bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+bool shape_ok(int groups, int P, int C) { return groups >= 1 && groups <= 65535 && P >= 1 && C >= 4 && C % 4 == 0 && C <= 1024; }
+
+bool vec_grid(int64_t vecs, unsigned* blocks) {
+    const int64_t b = (vecs + kThreads - 1) / kThreads;
+    if (b < 1 || b > 0x7FFFFFFF) return false;
+    *blocks = (unsigned)b;
+    return true;
+}
+
+}  // namespace
+
+int64_t bn_partial_floats(int groups, int P, int C) { return (int64_t)groups * bn_ranges(P) * 3 * C; }
+
+hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
+    if (!shape_ok(a.groups, a.P, a.C) || !a.z || !a.out || !a.stats || !a.part || !a.gamma || !a.beta) return hipErrorInvalidValue;
+    if (!aligned16(a.z) || !aligned16(a.out) || !aligned16(a.stats) || !aligned16(a.part) || !aligned16(a.gamma) ||
+        !aligned16(a.beta) || !aligned16(a.shortcut) || a.s_z % 4 || a.s_out % 4 || a.s_par % 4 || a.s_sc % 4)
+        return hipErrorInvalidValue;
+    const int ranges = bn_ranges(a.P);
+    bn_stats_partial_kernel<<<dim3((unsigned)ranges, (unsigned)a.groups), kThreads, 0, s>>>(a.z, a.s_z, a.part, a.P, a.C, ranges);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    bn_stats_final_kernel<<<dim3((unsigned)((a.C + kThreads - 1) / kThreads), (unsigned)a.groups), kThreads, 0, s>>>(
+        a.part, a.stats, a.P, a.C, ranges, a.eps);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    unsigned blocks;
+    const int64_t vecs = (int64_t)a.P * (a.C / 4);
+    if (!vec_grid(vecs, &blocks)) return hipErrorInvalidValue;
+    bn_apply_kernel<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.z, a.s_z, a.stats, a.gamma, a.beta, a.s_par, a.shortcut,
+                                                                          a.s_sc, a.out, a.s_out, vecs, a.C, a.relu);
+    return hipGetLastError();
+}
+
+hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s) {
+    if (!shape_ok(a.groups, a.P, a.C) || !a.z || !a.dy || !a.stats || !a.part || !a.sums || !a.gamma || !a.g) return hipErrorInvalidValue;
+    if (!aligned16(a.z) || !aligned16(a.dy) || !aligned16(a.stats) || !aligned16(a.part) || !aligned16(a.sums) ||
+        !aligned16(a.gamma) || a.s_z % 4 || a.s_dy % 4 || a.s_par % 4)
+        return hipErrorInvalidValue;
+    const int ranges = bn_ranges(a.P);
+    bn_bwd_partial_kernel<<<dim3((unsigned)ranges, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.part,
+                                                                                         a.P, a.C, ranges);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    bn_bwd_final_kernel<<<dim3((unsigned)((a.C + kThreads - 1) / kThreads), (unsigned)a.groups), kThreads, 0, s>>>(
+        a.part, a.sums, a.g, a.ld, a.g_gamma_off, a.g_beta_off, a.C, ranges);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    unsigned blocks;
+    const int64_t vecs = (int64_t)a.P * (a.C / 4);
+    if (!vec_grid(vecs, &blocks)) return hipErrorInvalidValue;
+    bn_bwd_apply_kernel<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.sums, a.gamma,
+                                                                              a.s_par, vecs, a.C, 1.0f / (float)a.P);
+    return hipGetLastError();
+}
+
+}  // namespace ols

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void conv3x3_kernel(ConvDev p) {
             const int col = n0 + wn0 + 32 * j + lane32;
             if (col >= C) continue;
             float bias = 0.0f;
-            if (MODE == 0) bias = p.bias[(int64_t)group * p.s_bias + col];
+            if (MODE == 0 && p.bias) bias = p.bias[(int64_t)group * p.s_bias + col];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
@@ -432,7 +432,8 @@ __global__ __launch_bounds__(256) void conv_dw_finish_kernel(const float* __rest
     const int group = blockIdx.y;
     float s = 0.0f;
     for (int sp = 0; sp < splits; ++sp) s += partial[((int64_t)sp * groups + group) * per_group + i];
-    g[(int64_t)group * ld + (i < n_w ? w_off + i : b_off + (i - n_w))] = s;
+    if (i < n_w) g[(int64_t)group * ld + w_off + i] = s;
+    else if (b_off >= 0) g[(int64_t)group * ld + b_off + (i - n_w)] = s;   // a convolution without bias has b_off < 0
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -493,7 +494,6 @@ bool shape_ok(const ConvArgs& a) {
 template <int MODE>
 hipError_t conv_launch(const ConvArgs& a, hipStream_t s) {
     if (!shape_ok(a) || !a.in || !a.w || !a.out || !aligned16(a.in) || !aligned16(a.w) || !aligned16(a.out)) return hipErrorInvalidValue;
-    if (MODE == 0 && !a.bias) return hipErrorInvalidValue;
     if (a.s_in % 4 || a.s_w % 4 || a.s_out % 4) return hipErrorInvalidValue;
     ConvDev p = {};
     p.in = a.in; p.w = a.w; p.out = a.out; p.bias = a.bias; p.residual = MODE == 0 ? a.residual : nullptr;

@@ -41,7 +41,7 @@ int fail(int code, const char* fmt, ...) {
 const char* kKernelNames[OLS_K_COUNT] = {
     "init",      "step",     "step_pull", "pull",     "mean",     "step_pull_mean", "lsq_resid", "lsq_grad",
     "gemm_fwd",  "gemm_dw",  "gemm_da",   "head_fwd", "head_bwd", "mix",            "cast_bf16", "delay",    "lsq_step",
-    "stale_sync", "conv_fwd",  "conv_dx",   "conv_dw",  "pool",     "pool_bwd"};
+    "stale_sync", "conv_fwd",  "conv_dx",   "conv_dw",  "pool",     "pool_bwd",      "bn_fwd",    "bn_bwd"};
 
 enum { MODEL_NONE = 0, MODEL_LSQ = 1, MODEL_MLP = 2, MODEL_CONV = 3 };
 
@@ -94,7 +94,10 @@ struct ols_ctx {
     int64_t off_dlogits = 0, off_loss = 0, off_resid = 0, off_shadow = 0, off_x0 = 0;
     // residual convolutional block: channels, image size, classes; workspace sub-buffers
     int cv_C = 0, cv_H = 0, cv_W = 0, cv_classes = 0;
+    bool cv_bn = false;     // convolutions without bias, each followed by batch normalisation
+    float cv_eps = 1e-5f;
     int64_t off_a1 = 0, off_a2 = 0, off_dz1 = 0, off_dz2 = 0, off_pooled = 0, off_dpool = 0, off_cpartial = 0;
+    int64_t off_z1 = 0, off_z2 = 0, off_bnstats = 0, off_bnsums = 0, off_bnpart = 0;
     const float* X = nullptr;
     const void* y = nullptr;
     int64_t xs = 0, ys = 0;
@@ -330,38 +333,74 @@ void plan_workspace(ols_ctx* c) {
         c->off_cpartial = take(splits * m * ((int64_t)9 * c->cv_C * c->cv_C + c->cv_C) * 4);
         c->off_dlogits = take(m * B * c->cv_classes * 4);
         c->off_loss = take(m * B * 4);
+        if (c->cv_bn) {   // the convolution outputs stay for the backward pass, with their statistics
+            c->off_z1 = take(act);
+            c->off_z2 = take(act);
+            c->off_bnstats = take(2 * m * 2 * c->cv_C * 4);
+            c->off_bnsums = take(m * 2 * c->cv_C * 4);
+            c->off_bnpart = take(bn_partial_floats(c->m, c->B * c->cv_H * c->cv_W, c->cv_C) * 4);
+        }
     }
     c->ws_need = off;
 }
 
 // Forward + backward of the residual convolutional block on the main stream; gradients go to g.
+// Plain block:       a1 = relu(conv(X; Wa) + ba);        a2 = relu(conv(a1; Wb) + bb + X)
+// Batch-normalised:  a1 = relu(bn(conv(X; Wa); ga, ba)); a2 = relu(bn(conv(a1; Wb); gb, bb) + X)
 int conv_gradients(ols_ctx* c) {
     const float* xc = c->x[c->cur];
     const int m = c->m, B = c->B, C = c->cv_C, H = c->cv_H, W = c->cv_W;
+    const bool bn = c->cv_bn;
     const int64_t n_w = (int64_t)9 * C * C;
-    const int64_t wa = 0, ba = n_w, wb = n_w + C, bb = 2 * n_w + C, wh = 2 * (n_w + C), bh = wh + (int64_t)C * c->cv_classes;
+    const int64_t per_conv = n_w + (bn ? 2 * C : C);   // kernels, then bias -- or scale and shift
+    const int64_t wa = 0, wb = per_conv, wh = 2 * per_conv, bh = wh + (int64_t)C * c->cv_classes;
+    const int64_t ba = wa + n_w + (bn ? C : 0), bb = wb + n_w + (bn ? C : 0);   // bias (plain) or shift (normalised)
+    const int64_t ga = wa + n_w, gb = wb + n_w;                                  // scale (normalised only)
     const int64_t act = (int64_t)B * H * W * C;   // elements per worker
     float* a1 = (float*)(c->ws + c->off_a1);
     float* a2 = (float*)(c->ws + c->off_a2);
     float* dz1 = (float*)(c->ws + c->off_dz1);
     float* dz2 = (float*)(c->ws + c->off_dz2);
+    float* z1 = (float*)(c->ws + c->off_z1);
+    float* z2 = (float*)(c->ws + c->off_z2);
     float* pooled = (float*)(c->ws + c->off_pooled);
     float* dpool = (float*)(c->ws + c->off_dpool);
     ConvArgs base = {};
     base.groups = m; base.B = B; base.H = H; base.W = W; base.C = C;
     base.s_w = c->ld; base.s_bias = c->ld;
     base.ld = c->ld; base.g = c->g; base.partial = (float*)(c->ws + c->off_cpartial);
+    BnArgs nbase = {};
+    nbase.groups = m; nbase.P = B * H * W; nbase.C = C; nbase.eps = c->cv_eps;
+    nbase.s_z = act; nbase.s_out = act; nbase.s_dy = act; nbase.s_par = c->ld;
+    nbase.ld = c->ld; nbase.g = c->g;
+    nbase.part = (float*)(c->ws + c->off_bnpart);
+    nbase.sums = (float*)(c->ws + c->off_bnsums);
+    float* stats1 = (float*)(c->ws + c->off_bnstats);
+    float* stats2 = stats1 + (int64_t)m * 2 * C;
     int rc;
-    {   // a1 = relu(conv(X; Wa) + ba)
+    {   // first convolution
         ConvArgs a = base;
-        a.in = c->X; a.s_in = c->xs; a.w = xc + wa; a.bias = xc + ba; a.out = a1; a.s_out = act; a.relu = 1;
+        a.in = c->X; a.s_in = c->xs; a.w = xc + wa;
+        if (bn) { a.out = z1; a.relu = 0; } else { a.bias = xc + ba; a.out = a1; a.relu = 1; }
+        a.s_out = act;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_fwd(a, s); }))) return rc;
     }
-    {   // a2 = relu(conv(a1; Wb) + bb + X)
+    if (bn) {
+        BnArgs a = nbase;
+        a.z = z1; a.out = a1; a.stats = stats1; a.gamma = xc + ga; a.beta = xc + ba; a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
+    }
+    {   // second convolution, with the shortcut
         ConvArgs a = base;
-        a.in = a1; a.s_in = act; a.w = xc + wb; a.bias = xc + bb; a.residual = c->X; a.s_res = c->xs; a.out = a2; a.s_out = act;
-        a.relu = 1;
+        a.in = a1; a.s_in = act; a.w = xc + wb; a.s_out = act;
+        if (bn) { a.out = z2; a.relu = 0; }
+        else { a.bias = xc + bb; a.residual = c->X; a.s_res = c->xs; a.out = a2; a.relu = 1; }
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_fwd(a, s); }))) return rc;
+    }
+    if (bn) {
+        BnArgs a = nbase;
+        a.z = z2; a.out = a2; a.stats = stats2; a.gamma = xc + gb; a.beta = xc + bb; a.shortcut = c->X; a.s_sc = c->xs; a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
     }
     if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
              return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, s);
@@ -391,6 +430,11 @@ int conv_gradients(ols_ctx* c) {
              return launch_pool_bwd(dpool, (int64_t)B * C, a2, act, dz2, act, m, B, H * W, C, s);
          })))
         return rc;
+    if (bn) {   // through the second normalisation: scale / shift gradients, then dz2 becomes the gradient at z2
+        BnArgs a = nbase;
+        a.z = z2; a.dy = dz2; a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
+        if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
+    }
     {   // delta at a1: transposed convolution of dz2 through Wb, gated by a1 > 0
         ConvArgs a = base;
         a.in = dz2; a.s_in = act; a.w = xc + wb; a.mask = a1; a.s_mask = act; a.out = dz1; a.s_out = act;
@@ -398,12 +442,17 @@ int conv_gradients(ols_ctx* c) {
     }
     {   // gradients of the second convolution
         ConvArgs a = base;
-        a.in = a1; a.s_in = act; a.dout = dz2; a.s_dout = act; a.g_w_off = wb; a.g_b_off = bb;
+        a.in = a1; a.s_in = act; a.dout = dz2; a.s_dout = act; a.g_w_off = wb; a.g_b_off = bn ? -1 : bb;
         if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_dw(a, s); }))) return rc;
+    }
+    if (bn) {   // through the first normalisation
+        BnArgs a = nbase;
+        a.z = z1; a.dy = dz1; a.stats = stats1; a.gamma = xc + ga; a.g_gamma_off = ga; a.g_beta_off = ba;
+        if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
     }
     {   // gradients of the first convolution (its input is data: no delta beyond it)
         ConvArgs a = base;
-        a.in = c->X; a.s_in = c->xs; a.dout = dz1; a.s_dout = act; a.g_w_off = wa; a.g_b_off = ba;
+        a.in = c->X; a.s_in = c->xs; a.dout = dz1; a.s_dout = act; a.g_w_off = wa; a.g_b_off = bn ? -1 : ba;
         if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_dw(a, s); }))) return rc;
     }
     return OLS_OK;
@@ -818,17 +867,20 @@ int ols_attach_mlp(ols_handle c, int n_layers, const int* dims, int batch, int g
     return OLS_OK;
 }
 
-int ols_attach_convblock(ols_handle c, int channels, int height, int width, int classes, int batch) {
+namespace {
+int attach_convblock(ols_ctx* c, int channels, int height, int width, int classes, int batch, bool bn, float eps) {
     if (int rc = need(c)) return rc;
     if (c->k != 0) return fail(OLS_ESTATE, "models are attached before the first local step");
     if (channels < 16 || channels % 16 != 0 || channels > 256) return fail(OLS_EINVAL, "channels must be a multiple of 16 in [16, 256], got %d", channels);
     if (height < 1 || width < 1 || height > 4096 || width > 4096) return fail(OLS_EINVAL, "height and width must be in [1, 4096]");
     if (classes < 1 || classes > 32) return fail(OLS_EINVAL, "the class count must be in [1, 32], got %d", classes);
     if (batch < 1 || batch > 65536) return fail(OLS_EINVAL, "batch must be in [1, 65536]");
+    if (bn && !(eps > 0.0f && eps <= 1.0f)) return fail(OLS_EINVAL, "eps must be in (0, 1], got %g", (double)eps);
     const int64_t elems = (int64_t)batch * height * width * channels;
     if (elems >= ((int64_t)1 << 31) - ((int64_t)channels << 16))
         return fail(OLS_EINVAL, "batch * height * width * channels = %lld is too large for one worker's activation tensor", (long long)elems);
-    const int64_t total = 2 * ((int64_t)9 * channels * channels + channels) + (int64_t)channels * classes + classes;
+    const int64_t total =
+        2 * ((int64_t)9 * channels * channels + (bn ? 2 : 1) * (int64_t)channels) + (int64_t)channels * classes + classes;
     if (total != c->d) return fail(OLS_EINVAL, "the block has %lld parameters but d = %lld", (long long)total, (long long)c->d);
     c->model = MODEL_CONV;
     c->B = batch;
@@ -837,10 +889,21 @@ int ols_attach_convblock(ols_handle c, int channels, int height, int width, int 
     c->cv_H = height;
     c->cv_W = width;
     c->cv_classes = classes;
+    c->cv_bn = bn;
+    c->cv_eps = eps;
     c->ws = nullptr;
     c->batch_set = false;
     plan_workspace(c);
     return OLS_OK;
+}
+}  // namespace
+
+int ols_attach_convblock(ols_handle c, int channels, int height, int width, int classes, int batch) {
+    return attach_convblock(c, channels, height, width, classes, batch, false, 0.0f);
+}
+
+int ols_attach_convblock_bn(ols_handle c, int channels, int height, int width, int classes, int batch, float eps) {
+    return attach_convblock(c, channels, height, width, classes, batch, true, eps);
 }
 
 int64_t ols_workspace_bytes(ols_handle c) { return c ? c->ws_need : 0; }

@@ -176,11 +176,12 @@ struct ConvArgs {
     const float* w;         // fwd, dx: kernels
     const float* dout;      // dw: delta of the layer output
     float* out;             // fwd: layer output; dx: delta of the layer input
-    const float* bias;      // fwd: [C] per group
+    const float* bias;      // fwd: [C] per group, or nullptr for a convolution without bias
     const float* residual;  // fwd: added before the activation (same shape as out), or nullptr
     const float* mask;      // dx: activations whose sign gates the result (same shape as out), or nullptr
     float* partial;         // dw: scratch of conv3x3_dw_splits(...) * groups * (9 C C + C) floats
     float* g;               // dw: gradients [groups][ld]; kernel gradient at g_w_off, bias gradient at g_b_off of a row
+                            // (g_b_off < 0: no bias, nothing written for it)
     int64_t ld, g_w_off, g_b_off;
     int64_t s_in, s_w, s_dout, s_out, s_bias, s_res, s_mask;   // group strides (elements)
     int groups, B, H, W, C;
@@ -195,6 +196,28 @@ hipError_t launch_pool_mean(const float* a, int64_t s_a, float* pooled, int64_t 
                             hipStream_t s);
 hipError_t launch_pool_bwd(const float* dpool, int64_t s_dp, const float* a, int64_t s_a, float* dz, int64_t s_dz,
                            int groups, int B, int HW, int C, hipStream_t s);
+
+// Batch normalisation in training mode over [group][P][C] tensors (statistics per group and channel over the P pixels).
+struct BnArgs {
+    const float* z;         // convolution output
+    float* out;             // fwd: act(gamma xhat + beta (+ shortcut))
+    const float* shortcut;  // fwd: added before the activation, or nullptr
+    float* dy;              // bwd: gradient at the normalised output on entry, gradient at z on return (in place)
+    float* stats;           // [group][2][C]: mean, 1 / sqrt(var + eps); written by fwd, read by bwd
+    float* sums;            // bwd: [group][2][C] scratch (sum dy, sum dy xhat)
+    float* part;            // scratch of bn_partial_floats(...) floats
+    const float* gamma;     // scale, [C] per group
+    const float* beta;      // shift (fwd)
+    float* g;               // bwd: gradients [groups][ld]; d gamma at g_gamma_off, d beta at g_beta_off of a row
+    int64_t ld, g_gamma_off, g_beta_off;
+    int64_t s_z, s_out, s_sc, s_dy, s_par;   // group strides (elements); s_par for gamma and beta
+    int groups, P, C;
+    int relu;
+    float eps;
+};
+hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s);    // statistics (two launches) + normalise
+hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s);   // sums (two launches) + gradient at z
+int64_t bn_partial_floats(int groups, int P, int C);
 
 // raises a kernel's dynamic-LDS limit once per (device, kernel)
 hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes);

@@ -83,8 +83,11 @@ class Session:
         if workspace:
             self._workspace()
 
-    def attach_convblock(self, channels, height, width, classes, batch):
-        B.ols_attach_convblock(self.h, channels, height, width, classes, batch)
+    def attach_convblock(self, channels, height, width, classes, batch, batch_norm=False, eps=1e-5):
+        if batch_norm:
+            B.ols_attach_convblock_bn(self.h, channels, height, width, classes, batch, eps)
+        else:
+            B.ols_attach_convblock(self.h, channels, height, width, classes, batch)
         self._workspace()
 
     def _workspace(self):

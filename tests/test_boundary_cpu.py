@@ -541,6 +541,35 @@ def test_convblock_attachment_and_launch_plan():
     B.ols_destroy(h)
 
 
+def test_convblock_with_batch_norm_attachment_and_launch_plan():
+    C, H, W, classes, batch = 32, 8, 8, 10, 4
+    d = 2 * (9 * C * C + 2 * C) + C * classes + classes
+    h = dry(d=d, mu=0.9, tau=2)
+    assert code_of(B.ols_attach_convblock, h, C, H, W, classes, batch) == B.OLS_EINVAL           # d is the normalised block's
+    assert code_of(B.ols_attach_convblock_bn, h, C, H, W, classes, batch, 0.0) == B.OLS_EINVAL   # eps must be positive
+    assert code_of(B.ols_attach_convblock_bn, h, C, H, W, classes, batch, float("nan")) == B.OLS_EINVAL
+    assert code_of(B.ols_attach_convblock_bn, h, 24, H, W, classes, batch, 1e-5) == B.OLS_EINVAL
+    B.ols_attach_convblock_bn(h, C, H, W, classes, batch, 1e-5)
+    need = B.ols_workspace_bytes(h)
+    assert need >= 6 * 4 * batch * H * W * C * 4        # activations, deltas and both convolution outputs, 4 workers
+    B.ols_bind_workspace(h, FAKE, need)
+    B.ols_init_params(h, FAKE)
+    B.ols_set_batch(h, FAKE, batch * H * W * C, FAKE, batch)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_local_step(h)
+    B.ols_local_step(h)
+    B.ols_sync_pull(h)
+    B.ols_anchor_update_async(h)
+    one = ["conv_fwd", "bn_fwd", "conv_fwd", "bn_fwd", "pool", "head_fwd", "head_bwd", "pool_bwd", "bn_bwd", "conv_dx",
+           "conv_dw", "bn_bwd", "conv_dw"]
+    assert kinds(B.ols_trace(h)) == one + ["step"] + one + ["step_pull", "mean"]
+    B.ols_destroy(h)
+    h = dry(d=d - 2 * C, mu=0.9, tau=2)                # the plain block needs two tensors less
+    B.ols_attach_convblock(h, C, H, W, classes, batch)
+    assert B.ols_workspace_bytes(h) <= need - 2 * 4 * batch * H * W * C * 4
+    B.ols_destroy(h)
+
+
 def test_tiny_refreshes_run_in_line_by_default():
     """OLS_OPT_SERIALIZE defaults to 2: the refresh is overlapped unless it moves at most 1 MiB."""
     for d, stream in ((100, 0), (100000, 1)):

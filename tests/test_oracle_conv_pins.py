@@ -310,3 +310,32 @@ def test_planted_batchnorm_mistakes_are_noticed(monkeypatch):
     monkeypatch.setattr(CO, "batchnorm_backward", drops_the_projection)
     with pytest.raises(AssertionError):
         test_bn_block_gradient_matches_central_finite_differences()
+
+
+@pytest.mark.parametrize("batch_norm", [False, True])
+def test_relu_margin_is_the_smallest_relu_input(batch_norm):
+    """Against torch's conv2d / batch_norm; and moving one bias (or shift) by the margin's own element puts a ReLU input
+    on zero, which the helper must then report."""
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    x, C, classes, X, labels = (bn_block_case if batch_norm else block_case)(80, B=2, C=3, H=4, Wd=3, classes=2)
+    tX = torch.tensor(X).permute(0, 3, 1, 2)
+    if batch_norm:
+        Wa, ga, ba, Wb, gb, bb, _, _ = (torch.tensor(np.array(v)) for v in CO.convblock_bn_unpack(x, C, classes))
+        bn = lambda z, g_, b_: F.batch_norm(z, None, None, g_, b_, training=True, eps=CO.BN_EPS)
+        n1 = bn(F.conv2d(tX, Wa.permute(3, 2, 0, 1), None, padding=1), ga, ba)
+        n2 = bn(F.conv2d(F.relu(n1), Wb.permute(3, 2, 0, 1), None, padding=1), gb, bb) + tX
+    else:
+        Wa, ba, Wb, bb, _, _ = (torch.tensor(np.array(v)) for v in CO.convblock_unpack(x, C, classes))
+        n1 = F.conv2d(tX, Wa.permute(3, 2, 0, 1), ba, padding=1)
+        n2 = F.conv2d(F.relu(n1), Wb.permute(3, 2, 0, 1), bb, padding=1) + tX
+    want = min(n1.abs().min().item(), n2.abs().min().item())
+    got = CO.convblock_relu_margin(x, C, classes, X, batch_norm=batch_norm)
+    assert got > 1e-4 and abs(got - want) <= 1e-12
+    # the second ReLU's inputs move one to one with the second bias / shift: cancel the smallest of them
+    flat = n2.permute(0, 2, 3, 1).reshape(-1, C).numpy()
+    pos = np.unravel_index(np.abs(flat).argmin(), flat.shape)
+    y = x.copy()
+    views = CO.convblock_bn_unpack(y, C, classes) if batch_norm else CO.convblock_unpack(y, C, classes)
+    views[5 if batch_norm else 3][pos[1]] -= flat[pos]
+    assert CO.convblock_relu_margin(y, C, classes, X, batch_norm=batch_norm) <= 1e-12
