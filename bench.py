@@ -11,7 +11,8 @@ it is the one the metric's "fused update / anchor-average HBM GB/s" is defined o
 worker-iterations/s over exactly K timed steps after exactly W warm-up steps, the roofline of the dominant kernel
 from HIP-event timing on the kernel's own stream, the CPU oracle timed on a bounded sample of the same workload as a
 reported baseline, and under "configs" one compact record per other configuration (1, 2, 3, 5 and the convolutional
-workload 6; its own run length, stated in the record): ms per step overlapped and serialised, the dominant kernel and its roofline fraction, the oracle's rate.
+workloads 6 and 7; its own run length, stated in the record): ms per step overlapped and serialised, the dominant
+kernel and its roofline fraction, the oracle's rate.
 """
 import argparse
 import json
@@ -36,7 +37,7 @@ def parse():
     ap.add_argument("--config", type=int, default=4, help="headline workload number (BASELINE configs are 1-based)")
     ap.add_argument("--side-configs", type=str, default=None,
                     help="comma-separated configurations measured after the headline and reported under \"configs\" "
-                         "(default: 1,2,3,5,6 when the headline is configuration 4 with default options, else none)")
+                         "(default: 1,2,3,5,6,7 when the headline is configuration 4 with default options, else none)")
     ap.add_argument("--side-cpu-seconds", type=float, default=3.0,
                     help="target CPU time of the oracle baseline of each side configuration (at least one round)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
@@ -123,6 +124,11 @@ def algorithmic_work(cfg, ld, fused_update=True):
         work["conv_dw"] = ("mfma", flops)
         work["pool"] = ("hbm", act)
         work["pool_bwd"] = ("hbm", 2 * act)
+        if cfg.batch_norm:
+            # statistics read z, the normalisation reads z (+ the shortcut in the second layer) and writes the activation
+            work["bn_fwd"] = ("hbm", 3.5 * act)
+            # the sums read dy and z, the gradient at z reads both again and writes over dy
+            work["bn_bwd"] = ("hbm", 5 * act)
     return work
 
 
@@ -140,7 +146,7 @@ def build_workload(cfg, sess, torch):
         X, labels = G.conv_data(cfg)
         Xd, yd = sess.upload(X), sess.upload(labels)
         x0 = G.conv_init(cfg)
-        sess.attach_convblock(*cfg.dims, cfg.batch)
+        sess.attach_convblock(*cfg.dims, cfg.batch, batch_norm=cfg.batch_norm)
         sess.init_params(x0)
         return (lambda k: sess.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb])), (X, labels, x0), (Xd, yd)
     if cfg.kind == "lsq":
@@ -162,10 +168,11 @@ def build_workload(cfg, sess, torch):
     return (lambda k: sess.set_gradient(pool[k % len(pool)])), (None, None, x0), None
 
 
-def cpu_baseline(cfg, host_inputs, seconds):
+def cpu_baseline(cfg, host_inputs, seconds, side=False):
     """The oracle as it stands, timed on this machine's host cores on a prefix of the same workload: one round to
     calibrate, then as many rounds as fit `seconds` (the calibration round itself where one round already takes
-    longer)."""
+    longer).  As a side record the convolutional workloads, whose single round takes the oracle most of a minute, are
+    timed on their first 4 workers."""
     from oracle import workloads as OW
     from ols_inputs import generate as G
     try:
@@ -173,6 +180,7 @@ def cpu_baseline(cfg, host_inputs, seconds):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
+    workers_note = "all %d workers" % cfg.m
     if cfg.kind == "mlp":
         X, labels, x0 = host_inputs
         grad_fn = OW.mlp_grad_fn(cfg.dims, X, labels)
@@ -183,7 +191,10 @@ def cpu_baseline(cfg, host_inputs, seconds):
         m_eff, d_eff = cfg.m, cfg.d
     elif cfg.kind == "conv":
         X, labels, x0 = host_inputs
-        grad_fn = OW.conv_grad_fn(cfg.dims, X, labels)
+        if side and cfg.m > 4:
+            workers_note = "workers 0-3 of %d" % cfg.m
+            cfg = cfg.scaled(m=4)
+        grad_fn = OW.conv_grad_fn(cfg.dims, X, labels, batch_norm=cfg.batch_norm)
         m_eff, d_eff = cfg.m, cfg.d
     else:  # the update is element-wise: time the oracle on a slice of the columns
         d_eff = 1 << 20
@@ -201,7 +212,7 @@ def cpu_baseline(cfg, host_inputs, seconds):
         OW.run_config(cfg, x0, grad_fn, K=rounds * cfg.tau)
         dt = time.perf_counter() - t0
     value = m_eff * rounds * cfg.tau / dt * (d_eff / cfg.d)
-    sample = "first %d iterations (%d rounds) of the workload, all %d workers" % (rounds * cfg.tau, rounds, cfg.m)
+    sample = "first %d iterations (%d rounds) of the workload, %s" % (rounds * cfg.tau, rounds, workers_note)
     if d_eff != cfg.d:
         sample += ", first %d of %d parameter columns (rate scaled by the column fraction)" % (d_eff, cfg.d)
     return {"value": value, "unit": "worker-iterations/s", "cores": cores, "kind": "oracle", "sample": sample,
@@ -357,7 +368,7 @@ def measure(idx, args, K, W, cpu_seconds, side):
         if fuse_mean:
             variants["fused_step_pull_mean"] = 1e3 * elapsed / K
 
-    base = cpu_baseline(cfg, host_inputs, cpu_seconds) if cpu_seconds > 0 and sync_rule == "paper" else None
+    base = cpu_baseline(cfg, host_inputs, cpu_seconds, side) if cpu_seconds > 0 and sync_rule == "paper" else None
     sess.close()
     del sess, feed, resident, host_inputs
     torch.cuda.empty_cache()
@@ -412,7 +423,7 @@ def main():
                        and not args.opt and args.loop == "library" and not args.no_kernel_timing and args.tau is None
                        and not args.calibration_copy_mib)
     if args.side_configs is None:
-        sides = [1, 2, 3, 5, 6] if (args.config == 4 and default_options) else []
+        sides = [1, 2, 3, 5, 6, 7] if (args.config == 4 and default_options) else []
     else:
         sides = [int(t) for t in args.side_configs.split(",") if t.strip()]
 

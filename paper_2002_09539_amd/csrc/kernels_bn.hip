@@ -52,6 +52,7 @@ __global__ __launch_bounds__(kThreads) void bn_stats_partial_kernel(const float*
     f4 K = {0.f, 0.f, 0.f, 0.f}, s1 = K, s2 = K;
     if (p_lo < p_hi && stripe < stripes) {
         K = *(const f4*)(Z + (int64_t)p_lo * C + 4 * c4);
+#pragma unroll 4
         for (int p = p_lo + stripe; p < p_hi; p += stripes) {
             const f4 v = __builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C + 4 * c4)) - K;
             s1 = s1 + v;
@@ -75,10 +76,11 @@ __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const float* _
     if (c >= C) return;
     const int g = blockIdx.y;
     const int chunk = (P + ranges - 1) / ranges;
+    const int filled = (P + chunk - 1) / chunk;   // ranges that hold pixels (the last ones may be empty)
     float n = 0.0f, mean = 0.0f, m2 = 0.0f;
-    for (int r = 0; r < ranges; ++r) {
+#pragma unroll 8
+    for (int r = 0; r < filled; ++r) {   // the loads do not depend on the running merge and are issued ahead of it
         const int p_lo = r * chunk, p_hi = min(P, p_lo + chunk);
-        if (p_lo >= p_hi) break;
         const float nr = (float)(p_hi - p_lo);
         const float* o = part + (((int64_t)g * ranges + r) * 3) * C + c;
         const float K = o[0], s1 = o[C], s2 = o[2 * C];
@@ -137,6 +139,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float* _
     if (stripe < stripes) {
         const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + 4 * c4);
         const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + 4 * c4);
+#pragma unroll 4
         for (int p = p_lo + stripe; p < p_hi; p += stripes) {
             const f4 d = __builtin_nontemporal_load((const f4*)(D + (int64_t)p * C + 4 * c4));
             const f4 xh = (__builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C + 4 * c4)) - mean) * istd;
@@ -161,6 +164,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const float* __r
     if (c >= C) return;
     const int g = blockIdx.y;
     float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll 8
     for (int r = 0; r < ranges; ++r) {
         const float* o = part + (((int64_t)g * ranges + r) * 2) * C + c;
         s1 += o[0];
