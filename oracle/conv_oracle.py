@@ -32,6 +32,14 @@ Layouts (an interface shared with the device path; each side computes its own of
 channel), ba [C], Wb [3][3][C][C], bb [C], Wh [C][classes], bh [classes], in that order; with batch normalisation
 Wa, ga [C], ba [C], Wb, gb [C], bb [C], Wh, bh (scale before shift).
 
+`bf16_operands=True` is a DIAGNOSTIC mode of the plain block for a device path that feeds its convolutions bf16
+operands (as `mlp_loss_grad` has one for the matrix products of the MLP): every tensor is rounded to bf16, to nearest
+even, at the point where it becomes an operand of a convolution's products -- the input batch, both kernels, a1, and
+the deltas d_z2 and d_z1 -- while sums, biases, the shortcut, pooling, classifier and the master parameters stay as they
+are.  The gradient it returns is what back-propagation computes from those rounded tensors (the rounding itself is
+passed through as the identity).  The target of the benchmark specification's bf16 gate is still the unrounded
+computation.
+
 Only tests/, the smoke check and the benchmark's CPU-baseline leg may import this module.
 Pinned by tests/test_oracle_conv_pins.py: torch's CPU conv2d, batch_norm and autograd as library routines, a pure-Python
 brute-force convolution, single-tap kernels that pin the tap orientation and the zero padding, the normalised output's
@@ -39,6 +47,8 @@ per-channel mean and variance, central finite differences of the whole loss, and
 notice.
 """
 import numpy as np
+
+from .ols_oracle import round_to_bf16
 
 F64 = np.float64
 
@@ -87,15 +97,17 @@ def convblock_unpack(x, C, classes):
     return out
 
 
-def convblock_loss_grad(x, C, classes, X, labels):
+def convblock_loss_grad(x, C, classes, X, labels, bf16_operands=False):
     """Residual block + pooled linear classifier: (mean cross-entropy over the batch, flat gradient in x's layout).
-    X [B][H][W][C], labels [B]."""
+    X [B][H][W][C], labels [B].  bf16_operands: the diagnostic mode of the module header."""
+    q = round_to_bf16 if bf16_operands else (lambda a: np.asarray(a, F64))
     x = np.asarray(x, F64)
     X = np.asarray(X, F64)
     Wa, ba, Wb, bb, Wh, bh = convblock_unpack(x, C, classes)
+    Xq, Wa, Wb = q(X), q(Wa), q(Wb)                                      # operands of the convolutions
     B = X.shape[0]
-    a1 = np.maximum(conv3x3_forward(X, Wa, ba), 0.0)
-    a2 = np.maximum(conv3x3_forward(a1, Wb, bb) + X, 0.0)
+    a1 = q(np.maximum(conv3x3_forward(Xq, Wa, ba), 0.0))
+    a2 = np.maximum(conv3x3_forward(a1, Wb, bb) + X, 0.0)                # the shortcut is not an operand
     pooled = a2.mean(axis=(1, 2))
     logits = pooled @ Wh + bh
     shifted = logits - logits.max(axis=1, keepdims=True)
@@ -111,12 +123,12 @@ def convblock_loss_grad(x, C, classes, X, labels):
     gbh[...] = dlogits.sum(axis=0)
     d_pooled = dlogits @ Wh.T
     positions = X.shape[1] * X.shape[2]
-    d_z2 = (d_pooled[:, None, None, :] / positions) * (a2 > 0.0)       # through the mean and the second ReLU
+    d_z2 = q((d_pooled[:, None, None, :] / positions) * (a2 > 0.0))    # through the mean and the second ReLU
     d_a1, dWb, dbb = conv3x3_backward(a1, Wb, d_z2)
     gWb[...] = dWb
     gbb[...] = dbb
-    d_z1 = d_a1 * (a1 > 0.0)
-    _, dWa, dba = conv3x3_backward(X, Wa, d_z1)                         # the input is data: its gradient is not needed
+    d_z1 = q(d_a1 * (a1 > 0.0))
+    _, dWa, dba = conv3x3_backward(Xq, Wa, d_z1)                        # the input is data: its gradient is not needed
     gWa[...] = dWa
     gba[...] = dba
     return loss, g

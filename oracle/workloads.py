@@ -24,11 +24,14 @@ def mlp_grad_fn(dims, X, labels, bf16_operands=False):
                                            bf16_operands=bf16_operands)
 
 
-def conv_grad_fn(dims, X, labels, batch_norm=False):
+def conv_grad_fn(dims, X, labels, batch_norm=False, bf16_operands=False):
     """dims = (channels, height, width, classes); X [m][nb][B][H][W][C], labels [m][nb][B]."""
     nb = X.shape[1]
-    block = CO.convblock_bn_loss_grad if batch_norm else CO.convblock_loss_grad
-    return lambda i, k, x: block(x, dims[0], dims[3], X[i, k % nb], labels[i, k % nb])
+    if batch_norm:
+        assert not bf16_operands
+        return lambda i, k, x: CO.convblock_bn_loss_grad(x, dims[0], dims[3], X[i, k % nb], labels[i, k % nb])
+    return lambda i, k, x: CO.convblock_loss_grad(x, dims[0], dims[3], X[i, k % nb], labels[i, k % nb],
+                                                  bf16_operands=bf16_operands)
 
 
 def stream_grad_fn(grads):

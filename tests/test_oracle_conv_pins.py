@@ -339,3 +339,71 @@ def test_relu_margin_is_the_smallest_relu_input(batch_norm):
     views = CO.convblock_bn_unpack(y, C, classes) if batch_norm else CO.convblock_unpack(y, C, classes)
     views[5 if batch_norm else 3][pos[1]] -= flat[pos]
     assert CO.convblock_relu_margin(y, C, classes, X, batch_norm=batch_norm) <= 1e-12
+
+
+# ---- the bf16-operand diagnostic mode of the plain block ------------------------------------------------------------
+def _torch_bf16_block(x, C, classes, X, labels, round_d_z1=True):
+    """The same rounding points in torch: values rounded through bfloat16 with the rounding passed through as the
+    identity in the backward pass, and the deltas at both convolution outputs rounded by gradient hooks."""
+    import torch
+    import torch.nn.functional as F
+
+    def rnd(t):
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    def ste(t):
+        return t + (rnd(t) - t).detach()
+    tx = torch.tensor(x, requires_grad=True)
+    off = 0
+
+    def take(shape):
+        nonlocal off
+        n = int(np.prod(shape))
+        t = tx[off:off + n].reshape(shape)
+        off += n
+        return t
+    Wa, ba, Wb, bb, Wh, bh = (take(s) for s in ((3, 3, C, C), (C,), (3, 3, C, C), (C,), (C, classes), (classes,)))
+    tX = torch.tensor(X).permute(0, 3, 1, 2)
+    z1 = F.conv2d(rnd(tX), ste(Wa).permute(3, 2, 0, 1), ba, padding=1)
+    if round_d_z1:
+        z1.register_hook(rnd)
+    a1 = ste(F.relu(z1))
+    z2 = F.conv2d(a1, ste(Wb).permute(3, 2, 0, 1), bb, padding=1) + tX
+    z2.register_hook(rnd)
+    logits = F.relu(z2).mean(dim=(2, 3)) @ Wh + bh
+    tl = F.cross_entropy(logits, torch.tensor(labels), reduction="mean")
+    tl.backward()
+    return tl.item(), tx.grad.numpy()
+
+
+def test_bf16_operand_mode_matches_torch_with_the_same_rounding_points():
+    pytest.importorskip("torch")
+    x, C, classes, X, labels = block_case(90, B=4, C=3, H=4, Wd=6, classes=5)
+    loss, g = CO.convblock_loss_grad(x, C, classes, X, labels, bf16_operands=True)
+    tl, tg = _torch_bf16_block(x, C, classes, X, labels)
+    assert abs(loss - tl) <= 1e-12 * abs(loss)
+    np.testing.assert_allclose(g, tg, atol=1e-12)
+    exact_loss, exact_g = CO.convblock_loss_grad(x, C, classes, X, labels)
+    assert 1e-5 < abs(loss - exact_loss) / abs(exact_loss) < 2e-2          # the mode rounds, and stays within the gate
+    assert 1e-4 < np.abs(g - exact_g).max() / np.abs(exact_g).max() < 5e-2
+    # teeth: leaving one delta unrounded is a different computation
+    _, tg_wrong = _torch_bf16_block(x, C, classes, X, labels, round_d_z1=False)
+    assert np.abs(g - tg_wrong).max() > 1e-6 * np.abs(g).max()
+
+
+def test_bf16_operand_mode_is_the_plain_block_on_bf16_exact_operands():
+    """Kernels of +-1 on one tap, inputs that are small integers, zero biases: every operand and every intermediate
+    sum is exactly representable, so the mode must not change the forward pass."""
+    C, classes, B, H, Wd = 2, 3, 2, 3, 3
+    x = np.zeros(CO.convblock_param_count(C, classes))
+    Wa, ba, Wb, bb, Wh, bh = CO.convblock_unpack(x, C, classes)
+    Wa[1, 1, 0, 1] = 1.0
+    Wa[0, 2, 1, 0] = -1.0
+    Wb[2, 0, 0, 0] = 1.0
+    Wb[1, 1, 1, 1] = 2.0
+    Wh[...] = np.array([[0.5, -0.25, 1.0], [1.0, 0.5, -0.5]])
+    X = np.random.default_rng(5).integers(-3, 4, (B, H, Wd, C)).astype(np.float64)
+    labels = np.array([0, 2])
+    a, _ = CO.convblock_loss_grad(x, C, classes, X, labels, bf16_operands=True)
+    b, _ = CO.convblock_loss_grad(x, C, classes, X, labels)
+    assert a == b
