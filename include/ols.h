@@ -257,6 +257,16 @@ OLS_API int ols_attach_convblock(ols_handle h, int channels, int height, int wid
  *   ols_attach_convblock.  The workspace keeps z1 and z2 for the backward pass beside the activations. */
 OLS_API int ols_attach_convblock_bn(ols_handle h, int channels, int height, int width, int classes, int batch, float eps);
 
+/* The block of ols_attach_convblock with bf16 operands on the matrix cores (fp32 accumulation), by the rule of the
+ * bf16 MLP: a tensor is rounded to bf16, to nearest even, where it becomes an operand of a convolution's products --
+ * the input batch, both kernels (through a bf16 copy of the parameters that the update kernels keep in the workspace),
+ * a1, and the deltas at both convolution outputs; biases, the shortcut, a2, pooling, classifier, gradients and the
+ * master parameters stay fp32.  Same parameter layout, inputs and errors as ols_attach_convblock, and in addition:
+ * channels a multiple of 64, width at most 128; attach (and bind the workspace) before ols_init_params, as for the
+ * bf16 MLP.  Internally the operand tensors are stored with their zero border, (height + 2) x (width + 2) per sample;
+ * the limit on batch * height * width * channels applies to those sizes. */
+OLS_API int ols_attach_convblock_bf16(ols_handle h, int channels, int height, int width, int classes, int batch);
+
 /* Bytes of caller-provided device workspace the attached model needs (activations, deltas, per-sample
  * losses, bf16 operand copies).  0 when no model is attached. */
 OLS_API int64_t ols_workspace_bytes(ols_handle h);

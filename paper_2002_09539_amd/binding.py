@@ -48,6 +48,7 @@ _SIGNATURES = {
     "ols_attach_mlp": (C.c_int, [_H, C.c_int, C.POINTER(C.c_int), C.c_int, C.c_int]),
     "ols_attach_convblock": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "ols_attach_convblock_bn": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]),
+    "ols_attach_convblock_bf16": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "ols_workspace_bytes": (C.c_int64, [_H]),
     "ols_bind_workspace": (C.c_int, [_H, _P, C.c_int64]),
     "ols_set_batch": (C.c_int, [_H, _P, C.c_int64, _P, C.c_int64]),
@@ -157,6 +158,10 @@ def ols_attach_mlp(h, dims, batch, gemm_dtype):
 
 def ols_attach_convblock(h, channels, height, width, classes, batch):
     _check(load().ols_attach_convblock(h, channels, height, width, classes, batch))
+
+
+def ols_attach_convblock_bf16(h, channels, height, width, classes, batch):
+    _check(load().ols_attach_convblock_bf16(h, channels, height, width, classes, batch))
 
 
 def ols_attach_convblock_bn(h, channels, height, width, classes, batch, eps=1e-5):

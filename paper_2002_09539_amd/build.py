@@ -24,6 +24,7 @@ SOURCES = [
     "kernels_gemm_bf16.hip",
     "kernels_conv.hip",
     "kernels_bn.hip",
+    "kernels_conv_bf16.hip",
 ]
 
 # packed-fp32 VALU forms stay disabled for every device translation unit

@@ -442,7 +442,7 @@ __global__ __launch_bounds__(256) void conv_dw_finish_kernel(const float* __rest
 // pooled[g][b][c] = (1 / HW) sum_pos a[g][b][pos][c].  One workgroup per (sample, group); thread = (channel vector,
 // position stripe); stripes are combined by a fixed-order LDS tree.
 __global__ __launch_bounds__(256) void pool_mean_kernel(const float* __restrict__ a, int64_t s_a, float* pooled,
-                                                        int64_t s_p, int HW, int C) {
+                                                        int64_t s_p, int HW, int C, float inv) {
     __shared__ f4 part[256];
     const int c4n = C / 4;                       // channel vectors (<= 64)
     const int stripes = 256 / c4n;               // >= 4
@@ -455,7 +455,6 @@ __global__ __launch_bounds__(256) void pool_mean_kernel(const float* __restrict_
     __syncthreads();
     if (stripe == 0) {
         for (int s = 1; s < stripes; ++s) acc = acc + part[s * c4n + c4];
-        const float inv = 1.0f / (float)HW;
         f4 o;
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = acc[e] * inv;
@@ -563,18 +562,24 @@ hipError_t launch_conv3x3_dw(const ConvArgs& a, hipStream_t s) {
     conv3x3_dw_kernel<BK, OLS_CONV_DW_DEPTH><<<(unsigned)(p.chunk * kXcds), kThreads, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int64_t n_w = (int64_t)9 * a.C * a.C, per_group = n_w + a.C;
-    dim3 grid((unsigned)((per_group + 255) / 256), (unsigned)a.groups);
-    conv_dw_finish_kernel<<<grid, 256, 0, s>>>(a.partial, p.splits, a.groups, per_group, n_w, a.g, a.ld, a.g_w_off, a.g_b_off);
+    return launch_conv_dw_finish(a.partial, p.splits, a.groups, a.C, a.g, a.ld, a.g_w_off, a.g_b_off, s);
+}
+
+hipError_t launch_conv_dw_finish(const float* partial, int splits, int groups, int C, float* g, int64_t ld, int64_t w_off,
+                                 int64_t b_off, hipStream_t s) {
+    if (!partial || !g || splits < 1 || groups < 1 || groups > 65535 || C < 1) return hipErrorInvalidValue;
+    const int64_t n_w = (int64_t)9 * C * C, per_group = n_w + C;
+    dim3 grid((unsigned)((per_group + 255) / 256), (unsigned)groups);
+    conv_dw_finish_kernel<<<grid, 256, 0, s>>>(partial, splits, groups, per_group, n_w, g, ld, w_off, b_off);
     return hipGetLastError();
 }
 
 hipError_t launch_pool_mean(const float* a, int64_t s_a, float* pooled, int64_t s_p, int groups, int B, int HW, int C,
-                            hipStream_t s) {
+                            float scale, hipStream_t s) {
     if (!a || !pooled || groups < 1 || groups > 65535 || B < 1 || HW < 1 || C < 4 || C % 4 || C > 256 || !aligned16(a) ||
         !aligned16(pooled) || s_a % 4 || s_p % 4)
         return hipErrorInvalidValue;
-    pool_mean_kernel<<<dim3((unsigned)B, (unsigned)groups), 256, 0, s>>>(a, s_a, pooled, s_p, HW, C);
+    pool_mean_kernel<<<dim3((unsigned)B, (unsigned)groups), 256, 0, s>>>(a, s_a, pooled, s_p, HW, C, scale);
     return hipGetLastError();
 }
 

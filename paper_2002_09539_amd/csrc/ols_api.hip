@@ -276,8 +276,11 @@ hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes) {
 
 namespace {
 
+// a model whose matrix products read a bf16 copy of the parameters, kept in the workspace by the update kernels
+bool bf16_model(const ols_ctx* c) { return (c->model == MODEL_MLP || c->model == MODEL_CONV) && c->gemm_dtype == 1; }
+
 uint16_t* shadow_ptr(ols_ctx* c) {
-    return (c->model == MODEL_MLP && c->gemm_dtype == 1 && c->ws) ? (uint16_t*)(c->ws + c->off_shadow) : nullptr;
+    return (bf16_model(c) && c->ws) ? (uint16_t*)(c->ws + c->off_shadow) : nullptr;
 }
 
 void plan_workspace(ols_ctx* c) {
@@ -321,7 +324,23 @@ void plan_workspace(ols_ctx* c) {
         c->off_dlogits = take(m * B * c->dims[L] * 4);
         c->off_loss = take(m * B * 4);
     }
-    if (c->model == MODEL_CONV) {
+    if (c->model == MODEL_CONV && c->gemm_dtype == 1) {
+        // operand tensors are bf16 and carry their zero border; the second activation (pooled, and the mask of the
+        // pooling backward) stays fp32, with the border as well
+        const int64_t padded = m * B * (c->cv_H + 2) * (c->cv_W + 2) * c->cv_C;
+        c->off_x0 = take(padded * 2);
+        c->off_a1 = take(padded * 2);
+        c->off_a2 = take(padded * 4);
+        c->off_dz2 = take(padded * 2);
+        c->off_dz1 = take(padded * 2);
+        c->off_pooled = take(m * B * c->cv_C * 4);
+        c->off_dpool = take(m * B * c->cv_C * 4);
+        const int64_t splits = conv3x3_bf16_dw_splits(c->m, c->B, c->cv_H, c->cv_W, c->cv_C);
+        c->off_cpartial = take(splits * m * ((int64_t)9 * c->cv_C * c->cv_C + c->cv_C) * 4);
+        c->off_dlogits = take(m * B * c->cv_classes * 4);
+        c->off_loss = take(m * B * 4);
+        c->off_shadow = take(m * c->ld * 2);
+    } else if (c->model == MODEL_CONV) {
         const int64_t act = m * B * c->cv_H * c->cv_W * c->cv_C * 4;   // one activation / delta tensor
         c->off_a1 = take(act);
         c->off_a2 = take(act);
@@ -344,10 +363,95 @@ void plan_workspace(ols_ctx* c) {
     c->ws_need = off;
 }
 
+// The plain residual block with bf16 operands: the input batch is converted (and given its zero border) first, the
+// kernels come from the bf16 copy of the parameters, a1 and both deltas are written as bf16; biases, shortcut, a2,
+// pooling and classifier stay fp32.
+int conv_gradients_bf16(ols_ctx* c) {
+    const float* xc = c->x[c->cur];
+    const uint16_t* shadow = shadow_ptr(c);
+    const int m = c->m, B = c->B, C = c->cv_C, H = c->cv_H, W = c->cv_W;
+    const int64_t n_w = (int64_t)9 * C * C;
+    const int64_t wa = 0, ba = n_w, wb = n_w + C, bb = 2 * n_w + C, wh = 2 * (n_w + C), bh = wh + (int64_t)C * c->cv_classes;
+    const int positions = (H + 2) * (W + 2);
+    const int64_t act = (int64_t)B * positions * C;   // elements of a padded tensor per worker
+    uint16_t* xb = (uint16_t*)(c->ws + c->off_x0);
+    uint16_t* a1 = (uint16_t*)(c->ws + c->off_a1);
+    float* a2 = (float*)(c->ws + c->off_a2);
+    uint16_t* dz1 = (uint16_t*)(c->ws + c->off_dz1);
+    uint16_t* dz2 = (uint16_t*)(c->ws + c->off_dz2);
+    float* pooled = (float*)(c->ws + c->off_pooled);
+    float* dpool = (float*)(c->ws + c->off_dpool);
+    ConvBArgs base = {};
+    base.groups = m; base.B = B; base.H = H; base.W = W; base.C = C;
+    base.s_w = c->ld; base.s_bias = c->ld;
+    base.ld = c->ld; base.g = c->g; base.partial = (float*)(c->ws + c->off_cpartial);
+    int rc;
+    if ((rc = enqueue(c, OLS_K_CAST, 0, -1, -1, [&](hipStream_t s) {
+             return launch_pad_cast_bf16(c->X, c->xs, xb, act, m, B, H, W, C, s);
+         })))
+        return rc;
+    {   // a1 = bf16(relu(conv(X; Wa) + ba))
+        ConvBArgs a = base;
+        a.in = xb; a.s_in = act; a.w = shadow + wa; a.bias = xc + ba; a.out = a1; a.s_out = act; a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
+    }
+    {   // a2 = relu(conv(a1; Wb) + bb + X), fp32
+        ConvBArgs a = base;
+        a.in = a1; a.s_in = act; a.w = shadow + wb; a.bias = xc + bb; a.residual = c->X; a.s_res = c->xs; a.out = a2; a.s_out = act;
+        a.out_f32 = 1; a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
+    }
+    if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {   // the border holds zeros: sum over it, divide by H W
+             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, positions, C, 1.0f / (float)(H * W), s);
+         })))
+        return rc;
+    HeadArgs ha = {};
+    ha.h = pooled;
+    ha.h_stride = (int64_t)B * C;
+    ha.h_bf16 = false;
+    ha.x = xc;
+    ha.g = c->g;
+    ha.ld = c->ld;
+    ha.w_off = wh;
+    ha.b_off = bh;
+    ha.labels = (const int32_t*)c->y;
+    ha.label_stride = c->ys;
+    ha.dlogits = (float*)(c->ws + c->off_dlogits);
+    ha.loss_parts = (float*)(c->ws + c->off_loss);
+    ha.dz = dpool;
+    ha.m = m;
+    ha.B = B;
+    ha.H = C;
+    ha.C = c->cv_classes;
+    if ((rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); }))) return rc;
+    if ((rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); }))) return rc;
+    if ((rc = enqueue(c, OLS_K_POOL_BWD, 0, -1, -1, [&](hipStream_t s) {
+             return launch_pool_bwd_bf16(dpool, (int64_t)B * C, a2, act, dz2, act, m, B, positions, C, 1.0f / (float)(H * W), s);
+         })))
+        return rc;
+    {   // delta at a1, gated by a1 > 0
+        ConvBArgs a = base;
+        a.in = dz2; a.s_in = act; a.w = shadow + wb; a.mask = a1; a.s_mask = act; a.out = dz1; a.s_out = act;
+        if ((rc = enqueue(c, OLS_K_CONV_DX, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_dx(a, s); }))) return rc;
+    }
+    {
+        ConvBArgs a = base;
+        a.in = a1; a.s_in = act; a.dout = dz2; a.s_dout = act; a.g_w_off = wb; a.g_b_off = bb;
+        if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_dw(a, s); }))) return rc;
+    }
+    {
+        ConvBArgs a = base;
+        a.in = xb; a.s_in = act; a.dout = dz1; a.s_dout = act; a.g_w_off = wa; a.g_b_off = ba;
+        if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_dw(a, s); }))) return rc;
+    }
+    return OLS_OK;
+}
+
 // Forward + backward of the residual convolutional block on the main stream; gradients go to g.
 // Plain block:       a1 = relu(conv(X; Wa) + ba);        a2 = relu(conv(a1; Wb) + bb + X)
 // Batch-normalised:  a1 = relu(bn(conv(X; Wa); ga, ba)); a2 = relu(bn(conv(a1; Wb); gb, bb) + X)
 int conv_gradients(ols_ctx* c) {
+    if (c->gemm_dtype == 1) return conv_gradients_bf16(c);
     const float* xc = c->x[c->cur];
     const int m = c->m, B = c->B, C = c->cv_C, H = c->cv_H, W = c->cv_W;
     const bool bn = c->cv_bn;
@@ -403,7 +507,7 @@ int conv_gradients(ols_ctx* c) {
         if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
     }
     if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
-             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, s);
+             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s);
          })))
         return rc;
     HeadArgs ha = {};
@@ -743,7 +847,7 @@ int ols_init_params(ols_handle c, const float* x0) {
     if (int rc = need(c)) return rc;
     if (!c->bound) return fail(OLS_ESTATE, "ols_bind must precede ols_init_params");
     if (!x0) return fail(OLS_EINVAL, "x0 is null");
-    if (c->model == MODEL_MLP && c->gemm_dtype == 1 && !c->ws)
+    if (bf16_model(c) && !c->ws)
         return fail(OLS_ESTATE, "with bf16 GEMMs the workspace (it holds the bf16 weights) is bound before ols_init_params");
     if (int rc = ensure_events(c)) return rc;
     if (c->launched && !c->dry) {  // re-initialisation: nothing may still be reading the old state
@@ -868,15 +972,20 @@ int ols_attach_mlp(ols_handle c, int n_layers, const int* dims, int batch, int g
 }
 
 namespace {
-int attach_convblock(ols_ctx* c, int channels, int height, int width, int classes, int batch, bool bn, float eps) {
+int attach_convblock(ols_ctx* c, int channels, int height, int width, int classes, int batch, bool bn, float eps, bool bf16) {
     if (int rc = need(c)) return rc;
     if (c->k != 0) return fail(OLS_ESTATE, "models are attached before the first local step");
+    if (bf16) {
+        if (c->inited) return fail(OLS_ESTATE, "a bf16 model is attached before ols_init_params (its bf16 weights are written there)");
+        if (channels % 64 != 0) return fail(OLS_EINVAL, "bf16 convolutions need the channels to be a multiple of 64, got %d", channels);
+        if (width > kConvBf16MaxWidth) return fail(OLS_EINVAL, "bf16 convolutions take widths up to %d, got %d", kConvBf16MaxWidth, width);
+    }
     if (channels < 16 || channels % 16 != 0 || channels > 256) return fail(OLS_EINVAL, "channels must be a multiple of 16 in [16, 256], got %d", channels);
     if (height < 1 || width < 1 || height > 4096 || width > 4096) return fail(OLS_EINVAL, "height and width must be in [1, 4096]");
     if (classes < 1 || classes > 32) return fail(OLS_EINVAL, "the class count must be in [1, 32], got %d", classes);
     if (batch < 1 || batch > 65536) return fail(OLS_EINVAL, "batch must be in [1, 65536]");
     if (bn && !(eps > 0.0f && eps <= 1.0f)) return fail(OLS_EINVAL, "eps must be in (0, 1], got %g", (double)eps);
-    const int64_t elems = (int64_t)batch * height * width * channels;
+    const int64_t elems = (int64_t)batch * (height + (bf16 ? 2 : 0)) * (width + (bf16 ? 2 : 0)) * channels;
     if (elems >= ((int64_t)1 << 31) - ((int64_t)channels << 16))
         return fail(OLS_EINVAL, "batch * height * width * channels = %lld is too large for one worker's activation tensor", (long long)elems);
     const int64_t total =
@@ -884,7 +993,7 @@ int attach_convblock(ols_ctx* c, int channels, int height, int width, int classe
     if (total != c->d) return fail(OLS_EINVAL, "the block has %lld parameters but d = %lld", (long long)total, (long long)c->d);
     c->model = MODEL_CONV;
     c->B = batch;
-    c->gemm_dtype = 0;
+    c->gemm_dtype = bf16 ? 1 : 0;
     c->cv_C = channels;
     c->cv_H = height;
     c->cv_W = width;
@@ -899,11 +1008,15 @@ int attach_convblock(ols_ctx* c, int channels, int height, int width, int classe
 }  // namespace
 
 int ols_attach_convblock(ols_handle c, int channels, int height, int width, int classes, int batch) {
-    return attach_convblock(c, channels, height, width, classes, batch, false, 0.0f);
+    return attach_convblock(c, channels, height, width, classes, batch, false, 0.0f, false);
+}
+
+int ols_attach_convblock_bf16(ols_handle c, int channels, int height, int width, int classes, int batch) {
+    return attach_convblock(c, channels, height, width, classes, batch, false, 0.0f, true);
 }
 
 int ols_attach_convblock_bn(ols_handle c, int channels, int height, int width, int classes, int batch, float eps) {
-    return attach_convblock(c, channels, height, width, classes, batch, true, eps);
+    return attach_convblock(c, channels, height, width, classes, batch, true, eps, false);
 }
 
 int64_t ols_workspace_bytes(ols_handle c) { return c ? c->ws_need : 0; }
@@ -914,7 +1027,7 @@ int ols_bind_workspace(ols_handle c, void* ws, int64_t bytes) {
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return fail(OLS_EINVAL, "workspace must be non-null and 256-byte aligned");
     if (bytes < c->ws_need) return fail(OLS_ENOMEM, "workspace has %lld bytes, %lld needed", (long long)bytes,
                                         (long long)c->ws_need);
-    if (c->inited && c->model == MODEL_MLP && c->gemm_dtype == 1)
+    if (c->inited && bf16_model(c))
         return fail(OLS_ESTATE, "with bf16 GEMMs the workspace (it holds the bf16 weights) is bound before ols_init_params");
     c->ws = (char*)ws;
     c->ws_bytes = bytes;
@@ -1158,7 +1271,7 @@ int64_t ols_static_workspace_bytes(void) { return kStaticWorkspaceBytes; }
 int ols_run_steps_static(ols_handle c, int64_t steps, const float* X, const void* y, int nb) {
     if (int rc = need(c)) return rc;
     if (c->model == MODEL_NONE) return fail(OLS_ESTATE, "ols_run_steps_static needs an attached model");
-    if (c->model == MODEL_MLP && c->gemm_dtype == 1)
+    if (bf16_model(c))
         return fail(OLS_EINVAL, "the bf16 model keeps its bf16 weights in the workspace, which must then outlive the call: "
                                 "bind a caller-owned workspace and use ols_run_steps");
     if (c->timing) return fail(OLS_ESTATE, "per-kernel timing creates events; switch OLS_OPT_KERNEL_TIMING off first");

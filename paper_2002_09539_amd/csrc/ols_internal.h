@@ -191,11 +191,45 @@ hipError_t launch_conv3x3_fwd(const ConvArgs& a, hipStream_t s);
 hipError_t launch_conv3x3_dx(const ConvArgs& a, hipStream_t s);
 hipError_t launch_conv3x3_dw(const ConvArgs& a, hipStream_t s);   // weight + bias gradient (two launches)
 int conv3x3_dw_splits(int groups, int B, int H, int W, int C);   // pixel ranges the weight-gradient contraction is split into
-// global average pooling over the HW positions of every sample, and its backward through the ReLU in front of it
+// second pass of the kernel gradient: sums the pixel ranges' parts [splits][groups][9 C C + C] in range order into g
+hipError_t launch_conv_dw_finish(const float* partial, int splits, int groups, int C, float* g, int64_t ld, int64_t w_off,
+                                 int64_t b_off, hipStream_t s);
+// pooled = scale * sum over the HW positions of every sample (scale = 1 / HW: global average pooling), and the backward
+// of the average through the ReLU in front of it
 hipError_t launch_pool_mean(const float* a, int64_t s_a, float* pooled, int64_t s_p, int groups, int B, int HW, int C,
-                            hipStream_t s);
+                            float scale, hipStream_t s);
 hipError_t launch_pool_bwd(const float* dpool, int64_t s_dp, const float* a, int64_t s_a, float* dz, int64_t s_dz,
                            int groups, int B, int HW, int C, hipStream_t s);
+
+// The same convolutions with bf16 operands.  Operand tensors carry their zero border: [group][B (H+2) (W+2)][C] bf16,
+// channel contiguous; kernels [group][9][C][C] bf16.  C a multiple of 64, W at most kConvBf16MaxWidth.
+constexpr int kConvBf16MaxWidth = 128;
+struct ConvBArgs {
+    const void* in;         // fwd: layer input; dx: delta of the layer output; dw: layer input (bf16, padded)
+    const void* w;          // fwd, dx: bf16 kernels
+    const void* dout;       // dw: delta of the layer output (bf16, padded)
+    void* out;              // fwd: layer output; dx: delta of the layer input; padded, bf16 or (fwd only) fp32
+    int out_f32;
+    const float* bias;      // fwd: [C] per group, or nullptr
+    const float* residual;  // fwd: fp32 [B H W][C] WITHOUT border, added before the activation, or nullptr
+    const void* mask;       // dx: padded bf16 activations whose sign gates the result, or nullptr
+    float* partial;         // dw: scratch of conv3x3_bf16_dw_splits(...) * groups * (9 C C + C) floats
+    float* g;               // dw: gradients [groups][ld]
+    int64_t ld, g_w_off, g_b_off;   // g_b_off < 0: no bias
+    int64_t s_in, s_w, s_dout, s_out, s_bias, s_res, s_mask;   // group strides (elements of the tensor's own type)
+    int groups, B, H, W, C;
+    int relu;
+};
+hipError_t launch_conv3x3_bf16_fwd(const ConvBArgs& a, hipStream_t s);
+hipError_t launch_conv3x3_bf16_dx(const ConvBArgs& a, hipStream_t s);
+hipError_t launch_conv3x3_bf16_dw(const ConvBArgs& a, hipStream_t s);
+int conv3x3_bf16_dw_splits(int groups, int B, int H, int W, int C);
+// fp32 [groups][B H W][C] -> bf16 [groups][B (H+2) (W+2)][C] with a zero border
+hipError_t launch_pad_cast_bf16(const float* src, int64_t s_src, uint16_t* dst, int64_t s_dst, int groups, int B, int H, int W,
+                                int C, hipStream_t s);
+// dz = bf16(dpool * scale) where a > 0 else 0; a fp32 and dz bf16, both over `positions` (padded) positions per sample
+hipError_t launch_pool_bwd_bf16(const float* dpool, int64_t s_dp, const float* a, int64_t s_a, uint16_t* dz, int64_t s_dz,
+                                int groups, int B, int positions, int C, float scale, hipStream_t s);
 
 // Batch normalisation in training mode over [group][P][C] tensors (statistics per group and channel over the P pixels).
 struct BnArgs {

@@ -83,8 +83,11 @@ class Session:
         if workspace:
             self._workspace()
 
-    def attach_convblock(self, channels, height, width, classes, batch, batch_norm=False, eps=1e-5):
-        if batch_norm:
+    def attach_convblock(self, channels, height, width, classes, batch, batch_norm=False, eps=1e-5, gemm_dtype="f32"):
+        if gemm_dtype == "bf16":
+            assert not batch_norm, "the batch-normalised block runs in fp32 only"
+            B.ols_attach_convblock_bf16(self.h, channels, height, width, classes, batch)
+        elif batch_norm:
             B.ols_attach_convblock_bn(self.h, channels, height, width, classes, batch, eps)
         else:
             B.ols_attach_convblock(self.h, channels, height, width, classes, batch)
