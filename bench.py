@@ -124,6 +124,15 @@ def algorithmic_work(cfg, ld, fused_update=True):
         work["conv_dw"] = ("mfma", flops)
         work["pool"] = ("hbm", act)
         work["pool_bwd"] = ("hbm", 2 * act)
+        if cfg.gemm_dtype == "bf16":
+            # bytes of the tensors each launch has to touch once (bf16 operands are half an fp32 tensor; the border the
+            # kernels store with them is overhead, not work): 288 flop per byte for a bf16-in, bf16-out convolution,
+            # just below the 312 flop per byte ridge, so min(matrix peak, AI x HBM peak) is reported beside the peak
+            work["cast_bf16"] = ("hbm", 1.5 * act)                      # fp32 batch in, bf16 batch out
+            work["conv_fwd_bytes"] = (1.0 * act + 2.5 * act) / 2        # first: bf16 in, bf16 out; second: bf16 in, fp32 shortcut in, fp32 out
+            work["conv_dx_bytes"] = 1.5 * act                           # bf16 delta in, bf16 mask in, bf16 delta out
+            work["conv_dw_bytes"] = 1.0 * act                           # bf16 input and bf16 delta
+            work["pool_bwd"] = ("hbm", 1.5 * act)                       # fp32 activation in, bf16 delta out
         if cfg.batch_norm:
             # statistics read z, the normalisation reads z (+ the shortcut in the second layer) and writes the activation
             work["bn_fwd"] = ("hbm", 3.5 * act)
@@ -146,7 +155,7 @@ def build_workload(cfg, sess, torch):
         X, labels = G.conv_data(cfg)
         Xd, yd = sess.upload(X), sess.upload(labels)
         x0 = G.conv_init(cfg)
-        sess.attach_convblock(*cfg.dims, cfg.batch, batch_norm=cfg.batch_norm)
+        sess.attach_convblock(*cfg.dims, cfg.batch, batch_norm=cfg.batch_norm, gemm_dtype=cfg.gemm_dtype)
         sess.init_params(x0)
         return (lambda k: sess.set_batch(Xd[:, k % cfg.nb], yd[:, k % cfg.nb])), (X, labels, x0), (Xd, yd)
     if cfg.kind == "lsq":
@@ -323,7 +332,7 @@ def measure(idx, args, K, W, cpu_seconds, side):
                     entry.update(bound="hbm", achieved=rate / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
                                  frac=rate / 1e9 / HBM_PEAK_GBS, per_launch=amount)
                 else:
-                    peak = MFMA_PEAK_TFLOPS[cfg.gemm_dtype if cfg.kind == "mlp" else "f32"]
+                    peak = MFMA_PEAK_TFLOPS[cfg.gemm_dtype if cfg.kind in ("mlp", "conv") else "f32"]
                     entry.update(bound="mfma", achieved=rate / 1e12, peak=peak, unit="TFLOP/s",
                                  frac=rate / 1e12 / peak, per_launch=amount)
                     if name + "_bytes" in work:   # fraction of min(matrix-core peak, arithmetic intensity x HBM peak)
@@ -381,7 +390,7 @@ def measure(idx, args, K, W, cpu_seconds, side):
               "loop": "library" if cfg.kind != "stream" and not (not side and args.loop == "python") else "python",
               "update": "in-gradient-kernels" if (fuse_gemm_update and cfg.kind != "stream") else "streaming"}
     return {"cfg": cfg, "value": value, "steps": K, "warmup": W, "ms_per_step": 1e3 * elapsed / K,
-            "dtype": cfg.gemm_dtype if cfg.kind == "mlp" else "f32", "config": config, "roofline": roofline,
+            "dtype": cfg.gemm_dtype if cfg.kind in ("mlp", "conv") else "f32", "config": config, "roofline": roofline,
             "cpu_baseline": base, "kernels": kernels, "ms_per_step_by_schedule": variants}
 
 

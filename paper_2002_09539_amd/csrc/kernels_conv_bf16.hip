@@ -76,7 +76,7 @@ __device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bi
 // forward (MODE 0) and back-propagated delta (MODE 1)
 // ---------------------------------------------------------------------------------------------
 template <int MODE, bool OUT_F32>
-__global__ __launch_bounds__(kThreads) void conv3x3_bf16_kernel(ConvBDev p) {
+__global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
     using TB = typename std::conditional<MODE == 0, TileRC<kCB, kCB>, TileKC<kCB, kCB>>::type;   // FWD w[k = ci][n = co]; DX w[n = ci][k = co]
     constexpr int SP = kCB + 8;                  // strip pitch (bf16 elements): 144 bytes, conflict-free 16-byte reads
     constexpr int TM = 2, TN = 2;                // a wavefront owns 64 pixels x 64 channels
@@ -180,28 +180,58 @@ __global__ __launch_bounds__(kThreads) void conv3x3_bf16_kernel(ConvBDev p) {
     // Epilogue.  Accumulator register r of a lane holds out[row][col] with col = lane % 32 and
     // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block.
     if constexpr (OUT_F32) {
+        // fp32 output (+ bias, shortcut, ReLU): the tile goes through LDS in two halves of 128 rows (two wavefronts each),
+        // so that every lane then moves 16-byte vectors and all its shortcut loads are in flight together
+        constexpr int FP = kCB + 8;                  // floats per staged row: the two half-waves hit disjoint banks
+        constexpr int kVecPerRow = kCB / 4, kPer = 128 * kVecPerRow / kThreads;
+        float* stage = (float*)lds_all;
         float* OUT = (float*)p.out + (int64_t)group * p.s_out;
+        const float* RES = p.residual ? p.residual + (int64_t)group * p.s_res : nullptr;
+        for (int h = 0; h < 2; ++h) {
+            if (h) __syncthreads();                  // the first half has been read
+            if (wave / 2 == h) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int q = m0 + wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
-                if (q >= p.Pp) continue;
-                int up;
-                const bool in_image = interior(p, q, &up);
+                    for (int j = 0; j < TN; ++j) {
+                        const int cl = 32 * j + lane32;
+                        const float bias = p.bias ? p.bias[(int64_t)group * p.s_bias + n0 + cl] : 0.0f;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int col = n0 + 32 * j + lane32;
-                    float v = 0.0f;
-                    if (in_image) {
-                        v = acc[i][j][r];
-                        if (MODE == 0) {
-                            if (p.bias) v += p.bias[(int64_t)group * p.s_bias + col];
-                            if (p.residual) v += p.residual[(int64_t)group * p.s_res + (int64_t)up * C + col];
-                            if (p.relu) v = fmaxf(v, 0.0f);
+                        for (int r = 0; r < 16; ++r) {
+                            const int rl = (wave % 2) * 64 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
+                            stage[rl * FP + cl] = acc[i][j][r] + bias;
                         }
                     }
-                    OUT[(int64_t)q * C + col] = v;
+            }
+            __syncthreads();
+#pragma unroll 1
+            for (int t0 = 0; t0 < kPer; t0 += 4) {   // four vectors per lane at a time: their shortcut loads overlap
+                f4 res[4];
+                int64_t at[4];
+                bool keep[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int v = threadIdx.x + (t0 + t) * kThreads;
+                    const int q = m0 + 128 * h + v / kVecPerRow, cl = (v % kVecPerRow) * 4;
+                    int up = 0;
+                    keep[t] = q < p.Pp && interior(p, q, &up);
+                    at[t] = q < p.Pp ? (int64_t)q * C + n0 + cl : -1;
+                    res[t] = f4{0.f, 0.f, 0.f, 0.f};
+                    if (RES && keep[t]) res[t] = __builtin_nontemporal_load((const f4*)(RES + (int64_t)up * C + n0 + cl));
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (at[t] < 0) continue;
+                    const int v = threadIdx.x + (t0 + t) * kThreads;
+                    f4 o = {0.f, 0.f, 0.f, 0.f};             // the zero border the pooling and its backward rely on
+                    if (keep[t]) {
+                        o = *(const f4*)(stage + (v / kVecPerRow) * FP + (v % kVecPerRow) * 4) + res[t];
+                        if (p.relu) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = fmaxf(o[e], 0.0f);
+                        }
+                    }
+                    *(f4*)(OUT + at[t]) = o;
                 }
             }
         }
@@ -477,7 +507,7 @@ hipError_t launch_conv3x3_bf16_dx(const ConvBArgs& a, hipStream_t s) { return co
 int conv3x3_bf16_dw_splits(int groups, int B, int H, int W, int C) {
     const int64_t Pp = (int64_t)B * (H + 2) * (W + 2);
     const int64_t tiles = (int64_t)groups * (C / kCB) * (C / kCB);
-    int64_t s = (2048 + tiles - 1) / tiles;                 // about eight workgroups per compute unit
+    int64_t s = (768 + tiles - 1) / tiles;                  // three workgroups per compute unit (their LDS allows three)
     const int64_t most = (Pp + 511) / 512;                  // a range covers at least 512 padded pixels
     if (s > most) s = most;
     if (s > 256) s = 256;
