@@ -39,19 +39,23 @@ constexpr int kCB = 64;     // channel block: contraction chunk and output-chann
 constexpr int kBM = 256;    // padded pixels per forward / delta tile
 constexpr int kDwBK = 32;   // pixels per slice of the kernel-gradient contraction
 
+struct FastDiv {
+    unsigned magic, shift;
+};
+
 struct ConvBDev {
     const uint16_t* in;      // FWD: layer input; DX: delta of the layer output; DW: layer input   [groups][Pp][C] bf16
     const uint16_t* w;       // FWD, DX: bf16 kernels [9][C][C]
     const uint16_t* dout;    // DW: delta of the layer output
     void* out;               // FWD, DX: [Pp][C], bf16 or fp32
     const float* bias;       // FWD
-    const float* residual;   // FWD: fp32, NOT padded ([B H W][C]); added before the activation, or nullptr
     const uint16_t* mask;    // DX: padded bf16 activations whose sign gates the result
     float* partial;          // DW
-    int64_t s_in, s_w, s_dout, s_out, s_bias, s_res, s_mask;
+    int64_t s_in, s_w, s_dout, s_out, s_bias, s_mask;
     int groups, B, H, W, C, Hp, Wp, Pp, halo;
     int relu;
     int tiles_m, tiles_n, total_tiles, chunk;
+    FastDiv div_per, div_wp; // division by (H + 2) (W + 2) and by W + 2
     int splits, k_chunk;
 };
 
@@ -61,11 +65,19 @@ __device__ __forceinline__ int xcd_tile(int chunk, int total) {
     return (slot >= chunk || tile >= total) ? -1 : tile;
 }
 
+// q / d for 0 <= q < 2^31 by multiplication: m = floor(2^32 (2^s - d) / d) + 1 with s = ceil(log2 d), and
+// q / d = (t + ((q - t) >> 1)) >> (s - 1) with t = mulhi(q, m)  (Granlund and Montgomery's round-up method)
+__device__ __forceinline__ unsigned fast_div(unsigned q, const FastDiv& d) {
+    if (d.shift == 0) return q;   // d = 1
+    const unsigned t = __umulhi(q, d.magic);
+    return (t + ((q - t) >> 1)) >> (d.shift - 1);
+}
+
 // padded pixel q -> is it an image pixel, and which (index in the unpadded [B H W] order)
 __device__ __forceinline__ bool interior(const ConvBDev& p, int q, int* unpadded) {
     const int per = p.Hp * p.Wp;
-    const int n = q / per, rem = q - n * per;
-    const int y = rem / p.Wp, x = rem - y * p.Wp;
+    const int n = (int)fast_div((unsigned)q, p.div_per), rem = q - n * per;
+    const int y = (int)fast_div((unsigned)rem, p.div_wp), x = rem - y * p.Wp;
     *unpadded = (n * p.H + (y - 1)) * p.W + (x - 1);
     return y >= 1 && y <= p.H && x >= 1 && x <= p.W;
 }
@@ -75,16 +87,18 @@ __device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bi
 // ---------------------------------------------------------------------------------------------
 // forward (MODE 0) and back-propagated delta (MODE 1)
 // ---------------------------------------------------------------------------------------------
-template <int MODE, bool OUT_F32>
+template <int MODE, bool OUT_F32, int NV>   // NV: strip vectors per lane (upper bound of (256 + 2 halo) * 8 / 256)
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
     using TB = typename std::conditional<MODE == 0, TileRC<kCB, kCB>, TileKC<kCB, kCB>>::type;   // FWD w[k = ci][n = co]; DX w[n = ci][k = co]
     constexpr int SP = kCB + 8;                  // strip pitch (bf16 elements): 144 bytes, conflict-free 16-byte reads
-    constexpr int TM = 2, TN = 2;                // a wavefront owns 64 pixels x 64 channels
+    constexpr int TM = 2, TN = 2, KS = kCB / 16; // a wavefront owns 64 pixels x 64 channels
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_all[];
     const int strip_rows = kBM + 2 * p.halo;
     uint16_t* strip = lds_all;
     uint16_t* lds_b0 = lds_all + strip_rows * SP;
     auto lds_b = [&](int buf) { return lds_b0 + buf * TB::kElems; };
+    float* bias_lds = (float*)(lds_b0 + 2 * TB::kElems);     // [64] the tile's slice of the bias (zeros without one)
+    uint8_t* row_flag = (uint8_t*)(bias_lds + kCB);          // [256] 1: image pixel, 0: border
 
     const int tile = xcd_tile(p.chunk, p.total_tiles);
     if (tile < 0) return;
@@ -100,6 +114,47 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
     const int lane32 = lane % 32, half = lane / 32;
     const int wm0 = wave * 64;
 
+    if (threadIdx.x < kCB) bias_lds[threadIdx.x] = (MODE == 0 && p.bias) ? p.bias[(int64_t)group * p.s_bias + n0 + threadIdx.x] : 0.0f;
+    {   // which rows of the tile are image pixels (the others get the zero border)
+        int up;
+        const int q = m0 + threadIdx.x;
+        row_flag[threadIdx.x] = q < p.Pp && interior(p, q, &up) ? 1 : 0;
+    }
+
+    // rows m0 - halo .. m0 + kBM + halo of channels c0 .. c0 + 63, zeros outside [0, Pp): every lane requests all its
+    // vectors at once (one round trip), then writes them to LDS
+    const int nvec = strip_rows * (kCB / 8);
+    auto load_strip = [&](u4 (&r)[NV], int c0) -> unsigned {
+        unsigned okmask = 0;
+#pragma unroll
+        for (int t = 0; t < NV; ++t) {
+            const int v = threadIdx.x + t * kThreads;
+            const int q = m0 - p.halo + v / (kCB / 8);
+            const bool ok = v < nvec && q >= 0 && q < p.Pp;
+            r[t] = *(const u4*)(IN + (ok ? (int64_t)q * C + c0 + (v % (kCB / 8)) * 8 : 0));
+            okmask |= ok ? (1u << t) : 0u;
+        }
+        return okmask;
+    };
+    auto store_strip = [&](const u4 (&r)[NV], unsigned okmask) {
+#pragma unroll
+        for (int t = 0; t < NV; ++t) {
+            const int v = threadIdx.x + t * kThreads;
+            if (v < nvec) {
+                const u4 zero = {0u, 0u, 0u, 0u};
+                *(u4*)(strip + (v / (kCB / 8)) * SP + (v % (kCB / 8)) * 8) = (okmask >> t) & 1u ? r[t] : zero;
+            }
+        }
+    };
+    // the 64 x 64 kernel slice of one tap.  Memory [ci][co]: FWD (row-contiguous tile) k = ci, rows = co; DX
+    // (K-contiguous tile) rows = ci, k = co
+    auto load_b = [&](u4 (&r)[TB::kPerThread], int tap, int c0) -> unsigned {
+        return TB::load(r, Wg + (int64_t)tap * C * C, C, n0, c0, C, C);
+    };
+
+    // The MFMA takes the KERNEL fragment first and the pixel fragment second, so the accumulator tile is out^T:
+    // register r of a lane holds pixel lane % 32 and channel 8 (r / 4) + 4 (lane / 32) + r % 4 of its 32 x 32 block --
+    // four consecutive channels per register quad, which the epilogue packs and stores as one piece.
     f16v acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -107,34 +162,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    // rows m0 - halo .. m0 + kBM + halo of channels c0 .. c0 + 63, zeros outside [0, Pp); four vectors in flight per lane
-    auto load_strip = [&](int c0) {
-        const int nvec = strip_rows * (kCB / 8);
-        for (int v0 = threadIdx.x; v0 < nvec; v0 += 4 * kThreads) {
-            u4 r[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int v = v0 + t * kThreads;
-                const int q = m0 - p.halo + v / (kCB / 8);
-                const bool ok = v < nvec && q >= 0 && q < p.Pp;
-                const u4 got = *(const u4*)(IN + (ok ? (int64_t)q * C + c0 + (v % (kCB / 8)) * 8 : 0));
-                const u4 zero = {0u, 0u, 0u, 0u};
-                r[t] = ok ? got : zero;
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int v = v0 + t * kThreads;
-                if (v < nvec) *(u4*)(strip + (v / (kCB / 8)) * SP + (v % (kCB / 8)) * 8) = r[t];
-            }
-        }
-    };
-    // the 64 x 64 kernel slice of one tap: rows k = contraction channel c0 .., columns n0 ..
-    auto load_b = [&](u4 (&r)[TB::kPerThread], int tap, int c0) -> unsigned {
-        // memory [ci][co].  FWD (row-contiguous tile): k = ci, rows = co; DX (K-contiguous tile): rows = ci, k = co
-        return TB::load(r, Wg + (int64_t)tap * C * C, C, n0, c0, C, C);
-    };
-
     bf16x8 fa[2][TM], fb[2][TN];
     auto load_frags = [&](int buf, const uint16_t* a_base, const uint16_t* b_tile, int s) {
 #pragma unroll
@@ -148,17 +175,22 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
     };
 
     u4 rb[TB::kPerThread];
     for (int c0 = 0; c0 < C; c0 += kCB) {
         // the previous chunk's last barrier has passed: nobody reads the strip or the kernel buffers any more
-        unsigned okb = load_b(rb, 0, c0);
-        load_strip(c0);
-        TB::store(lds_b(0), rb, okb);
+        {
+            u4 rs[NV];
+            unsigned okb = load_b(rb, 0, c0);
+            const unsigned oks = load_strip(rs, c0);
+            TB::store(lds_b(0), rb, okb);
+            store_strip(rs, oks);
+        }
         __syncthreads();
         for (int tap = 0; tap < 9; ++tap) {
+            unsigned okb = 0;
             if (tap + 1 < 9) okb = load_b(rb, tap + 1, c0);
             const int dy = tap / 3 - 1, dx = tap % 3 - 1;
             const int shift = (MODE == 0 ? 1 : -1) * (dy * p.Wp + dx);
@@ -166,8 +198,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
             const uint16_t* b_tile = lds_b(tap & 1);
             load_frags(0, a_base, b_tile, 0);
 #pragma unroll
-            for (int s = 0; s < kCB / 16; ++s) {
-                if (s + 1 < kCB / 16) load_frags((s + 1) & 1, a_base, b_tile, s + 1);
+            for (int s = 0; s < KS; ++s) {
+                if (s + 1 < KS) load_frags((s + 1) & 1, a_base, b_tile, s + 1);
                 __builtin_amdgcn_sched_barrier(0);
                 mfmas(s & 1);
                 __builtin_amdgcn_sched_barrier(0);
@@ -177,112 +209,106 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
         }
     }
 
-    // Epilogue.  Accumulator register r of a lane holds out[row][col] with col = lane % 32 and
-    // row = 8 (r / 4) + 4 (lane / 32) + r % 4 inside its 32 x 32 block.
+    // Epilogue: the tile goes through LDS (the strip's place) so that every lane then moves 16-byte vectors.
     if constexpr (OUT_F32) {
-        // fp32 output (+ bias, shortcut, ReLU): the tile goes through LDS in two halves of 128 rows (two wavefronts each),
-        // so that every lane then moves 16-byte vectors and all its shortcut loads are in flight together
-        constexpr int FP = kCB + 8;                  // floats per staged row: the two half-waves hit disjoint banks
-        constexpr int kVecPerRow = kCB / 4, kPer = 128 * kVecPerRow / kThreads;
+        // convolution + bias only (what follows it is another kernel's), staged in two passes of 128 rows.  Border rows
+        // are written as computed; their consumer skips them.
+        constexpr int FP = kCB + 8, HR = kBM / 2;
+        constexpr int kVecPerRow = kCB / 4, kPer = HR * kVecPerRow / kThreads;
         float* stage = (float*)lds_all;
         float* OUT = (float*)p.out + (int64_t)group * p.s_out;
-        const float* RES = p.residual ? p.residual + (int64_t)group * p.s_res : nullptr;
+#pragma unroll
         for (int h = 0; h < 2; ++h) {
             if (h) __syncthreads();                  // the first half has been read
-            if (wave / 2 == h) {
+            if (wm0 / HR == h) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const int cl = 32 * j + lane32;
-                        const float bias = p.bias ? p.bias[(int64_t)group * p.s_bias + n0 + cl] : 0.0f;
+                    for (int j = 0; j < TN; ++j)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int rl = (wave % 2) * 64 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
-                            stage[rl * FP + cl] = acc[i][j][r] + bias;
+                        for (int g4 = 0; g4 < 4; ++g4) {
+                            const f4 bq = *(const f4*)(bias_lds + 32 * j + 8 * g4 + 4 * half);
+                            const f4 o = {acc[i][j][4 * g4] + bq[0], acc[i][j][4 * g4 + 1] + bq[1], acc[i][j][4 * g4 + 2] + bq[2],
+                                          acc[i][j][4 * g4 + 3] + bq[3]};
+                            *(f4*)(stage + (wm0 % HR + 32 * i + lane32) * FP + 32 * j + 8 * g4 + 4 * half) = o;
                         }
-                    }
             }
             __syncthreads();
-#pragma unroll 1
-            for (int t0 = 0; t0 < kPer; t0 += 4) {   // four vectors per lane at a time: their shortcut loads overlap
-                f4 res[4];
-                int64_t at[4];
-                bool keep[4];
+            f4 val[kPer];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int v = threadIdx.x + (t0 + t) * kThreads;
-                    const int q = m0 + 128 * h + v / kVecPerRow, cl = (v % kVecPerRow) * 4;
-                    int up = 0;
-                    keep[t] = q < p.Pp && interior(p, q, &up);
-                    at[t] = q < p.Pp ? (int64_t)q * C + n0 + cl : -1;
-                    res[t] = f4{0.f, 0.f, 0.f, 0.f};
-                    if (RES && keep[t]) res[t] = __builtin_nontemporal_load((const f4*)(RES + (int64_t)up * C + n0 + cl));
-                }
+            for (int t = 0; t < kPer; ++t) {
+                const int v = threadIdx.x + t * kThreads;
+                val[t] = *(const f4*)(stage + (v / kVecPerRow) * FP + (v % kVecPerRow) * 4);
+            }
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    if (at[t] < 0) continue;
-                    const int v = threadIdx.x + (t0 + t) * kThreads;
-                    f4 o = {0.f, 0.f, 0.f, 0.f};             // the zero border the pooling and its backward rely on
-                    if (keep[t]) {
-                        o = *(const f4*)(stage + (v / kVecPerRow) * FP + (v % kVecPerRow) * 4) + res[t];
-                        if (p.relu) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = fmaxf(o[e], 0.0f);
-                        }
-                    }
-                    *(f4*)(OUT + at[t]) = o;
-                }
+            for (int t = 0; t < kPer; ++t) {
+                const int v = threadIdx.x + t * kThreads;
+                const int q = m0 + HR * h + v / kVecPerRow;
+                if (q < p.Pp) *(f4*)(OUT + (int64_t)q * C + n0 + (v % kVecPerRow) * 4) = val[t];
             }
         }
     } else {
-        // bf16 output: the tile goes through LDS (the strip's place) so that every lane then moves 16-byte vectors
-        uint16_t* stage = lds_all;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int cl = 32 * j + lane32;
-                float bias = 0.0f;
-                if (MODE == 0 && p.bias) bias = p.bias[(int64_t)group * p.s_bias + n0 + cl];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int rl = wm0 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
-                    float v = acc[i][j][r];
-                    if (MODE == 0) {
-                        v += bias;
-                        if (p.relu) v = fmaxf(v, 0.0f);
-                    }
-                    stage[rl * SP + cl] = (uint16_t)bf16_bits_rne(v);
-                }
-            }
-        }
-        __syncthreads();
+        constexpr int kVecPerRow = kCB / 8, kPer = kBM * kVecPerRow / kThreads;
         uint16_t* OUT = (uint16_t*)p.out + (int64_t)group * p.s_out;
         const uint16_t* Mk = MODE == 1 && p.mask ? p.mask + (int64_t)group * p.s_mask : nullptr;
-        constexpr int kVecPerRow = kCB / 8;
-#pragma unroll 4
-        for (int t = 0; t < kBM * kVecPerRow / kThreads; ++t) {
+        // the activations whose sign gates the delta are requested before the tile is staged
+        u4 mk[kPer];
+        if (MODE == 1) {
+#pragma unroll
+            for (int t = 0; t < kPer; ++t) {
+                const int v = threadIdx.x + t * kThreads;
+                const int q = m0 + v / kVecPerRow;
+                mk[t] = u4{~0u, ~0u, ~0u, ~0u};
+                if (Mk && q < p.Pp) mk[t] = *(const u4*)(Mk + (int64_t)q * C + n0 + (v % kVecPerRow) * 8);
+            }
+        }
+        uint16_t* stage = lds_all;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f4 bq = *(const f4*)(bias_lds + 32 * j + 8 * g4 + 4 * half);
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        v[e] = acc[i][j][4 * g4 + e];
+                        if (MODE == 0) {
+                            v[e] += bq[e];
+                            if (p.relu) v[e] = fmaxf(v[e], 0.0f);
+                        }
+                    }
+                    u2 o;   // round to nearest even (v_cvt_pk_bf16_f32)
+                    o.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{v[0], v[1]}, bf16x2));
+                    o.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{v[2], v[3]}, bf16x2));
+                    *(u2*)(stage + (wm0 + 32 * i + lane32) * SP + 32 * j + 8 * g4 + 4 * half) = o;
+                }
+        __syncthreads();
+        u4 val[kPer];
+#pragma unroll
+        for (int t = 0; t < kPer; ++t) {
             const int v = threadIdx.x + t * kThreads;
-            const int rl = v / kVecPerRow, cl = (v % kVecPerRow) * 8;
+            val[t] = *(const u4*)(stage + (v / kVecPerRow) * SP + (v % kVecPerRow) * 8);
+        }
+#pragma unroll
+        for (int t = 0; t < kPer; ++t) {
+            const int v = threadIdx.x + t * kThreads;
+            const int rl = v / kVecPerRow;
             const int q = m0 + rl;
             if (q >= p.Pp) continue;
-            u4 o = *(const u4*)(stage + rl * SP + cl);
-            const int64_t at = (int64_t)q * C + n0 + cl;
+            u4 o = val[t];
             if (MODE == 0) {
-                int up;
-                if (!interior(p, q, &up)) o = u4{0u, 0u, 0u, 0u};   // the zero border the next layer relies on
+                if (!row_flag[rl]) o = u4{0u, 0u, 0u, 0u};   // the zero border the next layer relies on
             } else if (Mk) {
-                const u4 mk = *(const u4*)(Mk + at);
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {   // a bf16 is positive iff its sign bit is clear and it is not zero
-                    const unsigned int lo = mk[w] & 0xFFFFu, hi = mk[w] >> 16;
-                    const unsigned int keep = ((lo != 0u && lo < 0x8000u) ? 0xFFFFu : 0u) |
-                                              ((hi != 0u && hi < 0x8000u) ? 0xFFFF0000u : 0u);
+                for (int w = 0; w < 4; ++w) {   // a bf16 is positive iff its bits are in [0x0001, 0x7FFF]
+                    const unsigned int lo = mk[t][w] & 0xFFFFu, hi = mk[t][w] >> 16;
+                    const unsigned int keep = ((lo - 1u) < 0x7FFFu ? 0xFFFFu : 0u) | ((hi - 1u) < 0x7FFFu ? 0xFFFF0000u : 0u);
                     o[w] &= keep;
                 }
             }
-            *(u4*)(OUT + at) = o;
+            *(u4*)(OUT + (int64_t)q * C + n0 + (v % kVecPerRow) * 8) = o;
         }
     }
 }
@@ -424,9 +450,69 @@ __global__ __launch_bounds__(kThreads) void pad_cast_bf16_kernel(const float* __
     *((u4*)(dst + (int64_t)g * s_dst) + v) = o;
 }
 
-// dz[g][q][c] = bf16(dpool[g][sample][c] * scale) where a[g][q][c] > 0, else 0; a fp32 padded, dz bf16 padded
+// The block's tail in one streaming pass: a2 = relu(y + X) for the image pixels of one (sample, worker), its mean over
+// the positions (global average pooling), and the sign of a2 for the backward pass -- a2 itself is needed nowhere else,
+// so it is never written.  y: convolution output + bias, fp32 [Pp][C] with border rows (skipped); X: the shortcut, fp32
+// [B H W][C]; sign[q][c / 4]: one byte per padded pixel and four channels, bit e set iff a2[q][4 (c / 4) + e] > 0 (border: 0).
+// One workgroup per (sample, worker); thread = (channel vector, position stripe); stripes combined in a fixed order.
+__global__ __launch_bounds__(kThreads) void shortcut_relu_pool_kernel(const float* __restrict__ y, int64_t s_y,
+                                                                      const float* __restrict__ X, int64_t s_x, float* pooled,
+                                                                      int64_t s_p, uint8_t* sign, int64_t s_sign, int H, int W, int C,
+                                                                      FastDiv div_wp, float inv) {
+    __shared__ f4 part[kThreads];
+    const int c4n = C / 4, stripes = kThreads / c4n;
+    const int c4 = threadIdx.x % c4n, stripe = threadIdx.x / c4n;
+    const int b = blockIdx.x, g = blockIdx.y;
+    const int Wp = W + 2, per = (H + 2) * Wp;
+    const float* Y = y + (int64_t)g * s_y + (int64_t)b * per * C + 4 * c4;
+    const float* Xs = X + (int64_t)g * s_x + (int64_t)b * H * W * C + 4 * c4;
+    uint8_t* S = sign + (int64_t)g * s_sign + (int64_t)b * per * c4n + c4;
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (stripe < stripes) {
+        for (int p0 = stripe; p0 < per; p0 += 4 * stripes) {   // four positions per thread in flight
+            f4 yv[4], xv[4];
+            bool in[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int pp = p0 + t * stripes;
+                const int yy = (int)fast_div((unsigned)pp, div_wp), xx = pp - yy * Wp;
+                in[t] = pp < per && yy >= 1 && yy <= H && xx >= 1 && xx <= W;
+                if (in[t]) {
+                    yv[t] = __builtin_nontemporal_load((const f4*)(Y + (int64_t)pp * C));
+                    xv[t] = __builtin_nontemporal_load((const f4*)(Xs + (int64_t)((yy - 1) * W + (xx - 1)) * C));
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int pp = p0 + t * stripes;
+                if (pp >= per) continue;
+                unsigned bits = 0;
+                if (in[t]) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float a = fmaxf(yv[t][e] + xv[t][e], 0.0f);
+                        acc[e] += a;
+                        bits |= a > 0.0f ? (1u << e) : 0u;
+                    }
+                }
+                S[(int64_t)pp * c4n] = (uint8_t)bits;
+            }
+        }
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (stripe == 0) {
+        for (int s = 1; s < stripes; ++s) acc = acc + part[s * c4n + c4];
+        f4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = acc[e] * inv;
+        *(f4*)(pooled + (int64_t)g * s_p + (int64_t)b * C + 4 * c4) = o;
+    }
+}
+
+// dz[g][q][c] = bf16(dpool[g][sample][c] * scale) where the sign bit of (q, c) is set, else 0; dz bf16 padded
 __global__ __launch_bounds__(kThreads) void pool_bwd_bf16_kernel(const float* __restrict__ dpool, int64_t s_dp,
-                                                                 const float* __restrict__ a, int64_t s_a, uint16_t* dz,
+                                                                 const uint8_t* __restrict__ sign, int64_t s_sign, uint16_t* dz,
                                                                  int64_t s_dz, int64_t vecs, int positions, int C, float scale) {
     const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (v >= vecs) return;
@@ -435,15 +521,14 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_bf16_kernel(const float* __
     const int64_t q = v / c8;
     const int cv = (int)(v % c8);
     const int64_t sample = q / positions;
-    const f4* A = (const f4*)(a + (int64_t)g * s_a) + 2 * v;
-    const f4 a0 = __builtin_nontemporal_load(A), a1 = __builtin_nontemporal_load(A + 1);
+    const unsigned bits = *(const uint16_t*)(sign + (int64_t)g * s_sign + 2 * v);   // two bytes: channels 8 cv .. 8 cv + 7
     const f4* D = (const f4*)(dpool + (int64_t)g * s_dp + sample * C) + 2 * cv;
     const f4 d0 = D[0], d1 = D[1];
     float o[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        o[e] = a0[e] > 0.0f ? d0[e] * scale : 0.0f;
-        o[4 + e] = a1[e] > 0.0f ? d1[e] * scale : 0.0f;
+        o[e] = (bits >> e) & 1u ? d0[e] * scale : 0.0f;
+        o[4 + e] = (bits >> (8 + e)) & 1u ? d1[e] * scale : 0.0f;
     }
     u4 w;
     w.x = pack2(o[0], o[1]);
@@ -463,10 +548,21 @@ bool shape_ok(const ConvBArgs& a) {
     return Pp * a.C < ((int64_t)1 << 31) - ((int64_t)(kBM + 2 * (a.W + 3)) * a.C);   // 32-bit pixel indices inside one group
 }
 
+FastDiv make_div(unsigned d) {
+    FastDiv f = {0u, 0u};
+    unsigned s = 0;
+    while ((1ull << s) < d) ++s;
+    f.shift = s;
+    if (s > 0) f.magic = (unsigned)((((1ull << s) - d) << 32) / d + 1);
+    return f;
+}
+
 void fill(ConvBDev* p, const ConvBArgs& a) {
     p->groups = a.groups; p->B = a.B; p->H = a.H; p->W = a.W; p->C = a.C;
     p->Hp = a.H + 2; p->Wp = a.W + 2; p->Pp = a.B * p->Hp * p->Wp; p->halo = p->Wp + 1;
     p->relu = a.relu;
+    p->div_per = make_div((unsigned)(p->Hp * p->Wp));
+    p->div_wp = make_div((unsigned)p->Wp);
 }
 
 template <int MODE>
@@ -474,23 +570,35 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     if (!shape_ok(a) || !a.in || !a.w || !a.out || !aligned16(a.in) || !aligned16(a.w) || !aligned16(a.out)) return hipErrorInvalidValue;
     if (a.s_in % 8 || a.s_w % 8 || a.s_out % 8 || (a.mask && (!aligned16(a.mask) || a.s_mask % 8))) return hipErrorInvalidValue;
     if (MODE == 1 && a.out_f32) return hipErrorInvalidValue;   // the delta is always an operand of the next product
+    if (a.out_f32 && a.relu) return hipErrorInvalidValue;      // the fp32 output is the bare convolution + bias
     ConvBDev p = {};
     fill(&p, a);
     p.in = (const uint16_t*)a.in; p.w = (const uint16_t*)a.w; p.out = a.out;
-    p.bias = MODE == 0 ? a.bias : nullptr; p.residual = MODE == 0 ? a.residual : nullptr;
+    p.bias = MODE == 0 ? a.bias : nullptr;
     p.mask = MODE == 1 ? (const uint16_t*)a.mask : nullptr;
-    p.s_in = a.s_in; p.s_w = a.s_w; p.s_out = a.s_out; p.s_bias = a.s_bias; p.s_res = a.s_res; p.s_mask = a.s_mask;
+    p.s_in = a.s_in; p.s_w = a.s_w; p.s_out = a.s_out; p.s_bias = a.s_bias; p.s_mask = a.s_mask;
     p.tiles_m = (p.Pp + kBM - 1) / kBM;
     p.tiles_n = a.C / kCB;
     const int64_t total = (int64_t)a.groups * p.tiles_m * p.tiles_n;
     if (total > (1 << 30)) return hipErrorInvalidValue;
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
+    const int strip_rows = kBM + 2 * p.halo;
     const size_t b_elems = MODE == 0 ? TileRC<kCB, kCB>::kElems : TileKC<kCB, kCB>::kElems;
-    const size_t lds = ((size_t)(kBM + 2 * p.halo) * (kCB + 8) + 2 * b_elems) * sizeof(uint16_t);
-    if (lds > 160 * 1024) return hipErrorInvalidValue;
-    void (*kern)(ConvBDev) = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true> : conv3x3_bf16_kernel<0, false>)
-                                       : conv3x3_bf16_kernel<1, false>;
+    const size_t lds = ((size_t)strip_rows * (kCB + 8) + 2 * b_elems) * sizeof(uint16_t) + kCB * sizeof(float) + kBM;   // strip, kernel slices, bias, row flags
+    constexpr int NV0 = ((kBM + 2 * 35) * (kCB / 8) + kThreads - 1) / kThreads;                        // widths up to 32
+    constexpr int NV1 = ((kBM + 2 * (kConvBf16MaxWidth + 3)) * (kCB / 8) + kThreads - 1) / kThreads;    // any width
+    const int nv = (strip_rows * (kCB / 8) + kThreads - 1) / kThreads;
+    // the output tile is staged in the strip's place: 256 x 72 bf16, or 128 x 72 floats per pass
+    static_assert((size_t)(kBM + 2 * 4) * (kCB + 8) * 2 >= (size_t)(kBM / 2) * (kCB + 8) * 4, "staging area");
+    if (lds > 160 * 1024 || nv > NV1) return hipErrorInvalidValue;
+    void (*kern)(ConvBDev);
+    if (nv <= NV0)
+        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV0> : conv3x3_bf16_kernel<0, false, NV0>)
+                         : conv3x3_bf16_kernel<1, false, NV0>;
+    else
+        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV1> : conv3x3_bf16_kernel<0, false, NV1>)
+                         : conv3x3_bf16_kernel<1, false, NV1>;
     if (lds > 64 * 1024) {
         hipError_t e = ensure_dynamic_lds((const void*)kern, 160 * 1024);
         if (e != hipSuccess) return e;
@@ -558,16 +666,27 @@ hipError_t launch_pad_cast_bf16(const float* src, int64_t s_src, uint16_t* dst, 
     return hipGetLastError();
 }
 
-hipError_t launch_pool_bwd_bf16(const float* dpool, int64_t s_dp, const float* a, int64_t s_a, uint16_t* dz, int64_t s_dz,
+hipError_t launch_shortcut_relu_pool(const float* y, int64_t s_y, const float* X, int64_t s_x, float* pooled, int64_t s_p,
+                                     uint8_t* sign, int64_t s_sign, int groups, int B, int H, int W, int C, hipStream_t s) {
+    if (!y || !X || !pooled || !sign || groups < 1 || groups > 65535 || B < 1 || H < 1 || W < 1 || C < 8 || C % 8 || C > 1024 ||
+        !aligned16(y) || !aligned16(X) || !aligned16(pooled) || (reinterpret_cast<uintptr_t>(sign) & 1u) || s_y % 4 || s_x % 4 ||
+        s_p % 4 || s_sign % 2)
+        return hipErrorInvalidValue;
+    shortcut_relu_pool_kernel<<<dim3((unsigned)B, (unsigned)groups), kThreads, 0, s>>>(
+        y, s_y, X, s_x, pooled, s_p, sign, s_sign, H, W, C, make_div((unsigned)(W + 2)), 1.0f / (float)(H * W));
+    return hipGetLastError();
+}
+
+hipError_t launch_pool_bwd_bf16(const float* dpool, int64_t s_dp, const uint8_t* sign, int64_t s_sign, uint16_t* dz, int64_t s_dz,
                                 int groups, int B, int positions, int C, float scale, hipStream_t s) {
-    if (!dpool || !a || !dz || groups < 1 || groups > 65535 || B < 1 || positions < 1 || C < 8 || C % 8 || !aligned16(dpool) ||
-        !aligned16(a) || !aligned16(dz) || s_dp % 4 || s_a % 4 || s_dz % 8)
+    if (!dpool || !sign || !dz || groups < 1 || groups > 65535 || B < 1 || positions < 1 || C < 8 || C % 8 || !aligned16(dpool) ||
+        (reinterpret_cast<uintptr_t>(sign) & 1u) || !aligned16(dz) || s_dp % 4 || s_sign % 2 || s_dz % 8)
         return hipErrorInvalidValue;
     const int64_t vecs = (int64_t)B * positions * (C / 8);
     const int64_t blocks = (vecs + kThreads - 1) / kThreads;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    pool_bwd_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)groups), kThreads, 0, s>>>(dpool, s_dp, a, s_a, dz, s_dz, vecs, positions,
-                                                                                      C, scale);
+    pool_bwd_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)groups), kThreads, 0, s>>>(dpool, s_dp, sign, s_sign, dz, s_dz, vecs,
+                                                                                      positions, C, scale);
     return hipGetLastError();
 }
 

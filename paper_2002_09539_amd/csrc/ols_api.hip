@@ -331,6 +331,7 @@ void plan_workspace(ols_ctx* c) {
         c->off_x0 = take(padded * 2);
         c->off_a1 = take(padded * 2);
         c->off_a2 = take(padded * 4);
+        c->off_z1 = take(padded / 4);     // sign bytes of a2
         c->off_dz2 = take(padded * 2);
         c->off_dz1 = take(padded * 2);
         c->off_pooled = take(m * B * c->cv_C * 4);
@@ -365,7 +366,8 @@ void plan_workspace(ols_ctx* c) {
 
 // The plain residual block with bf16 operands: the input batch is converted (and given its zero border) first, the
 // kernels come from the bf16 copy of the parameters, a1 and both deltas are written as bf16; biases, shortcut, a2,
-// pooling and classifier stay fp32.
+// pooling and classifier stay fp32.  The second convolution writes conv + bias in fp32; one streaming pass then adds
+// the shortcut, applies the ReLU, pools, and keeps only the sign of a2 (all the backward pass needs of it).
 int conv_gradients_bf16(ols_ctx* c) {
     const float* xc = c->x[c->cur];
     const uint16_t* shadow = shadow_ptr(c);
@@ -376,7 +378,8 @@ int conv_gradients_bf16(ols_ctx* c) {
     const int64_t act = (int64_t)B * positions * C;   // elements of a padded tensor per worker
     uint16_t* xb = (uint16_t*)(c->ws + c->off_x0);
     uint16_t* a1 = (uint16_t*)(c->ws + c->off_a1);
-    float* a2 = (float*)(c->ws + c->off_a2);
+    float* y2 = (float*)(c->ws + c->off_a2);          // second convolution + bias; a2 itself is never stored
+    uint8_t* sign = (uint8_t*)(c->ws + c->off_z1);    // sign of a2, one byte per padded pixel and four channels
     uint16_t* dz1 = (uint16_t*)(c->ws + c->off_dz1);
     uint16_t* dz2 = (uint16_t*)(c->ws + c->off_dz2);
     float* pooled = (float*)(c->ws + c->off_pooled);
@@ -395,14 +398,14 @@ int conv_gradients_bf16(ols_ctx* c) {
         a.in = xb; a.s_in = act; a.w = shadow + wa; a.bias = xc + ba; a.out = a1; a.s_out = act; a.relu = 1;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
     }
-    {   // a2 = relu(conv(a1; Wb) + bb + X), fp32
+    {   // y = conv(a1; Wb) + bb, fp32
         ConvBArgs a = base;
-        a.in = a1; a.s_in = act; a.w = shadow + wb; a.bias = xc + bb; a.residual = c->X; a.s_res = c->xs; a.out = a2; a.s_out = act;
-        a.out_f32 = 1; a.relu = 1;
+        a.in = a1; a.s_in = act; a.w = shadow + wb; a.bias = xc + bb; a.out = y2; a.s_out = act; a.out_f32 = 1;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
     }
-    if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {   // the border holds zeros: sum over it, divide by H W
-             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, positions, C, 1.0f / (float)(H * W), s);
+    // a2 = relu(y + X), pooled = its mean over the positions, and the sign of a2 for the backward pass, in one pass
+    if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
+             return launch_shortcut_relu_pool(y2, act, c->X, c->xs, pooled, (int64_t)B * C, sign, act / 4, m, B, H, W, C, s);
          })))
         return rc;
     HeadArgs ha = {};
@@ -426,7 +429,7 @@ int conv_gradients_bf16(ols_ctx* c) {
     if ((rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); }))) return rc;
     if ((rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); }))) return rc;
     if ((rc = enqueue(c, OLS_K_POOL_BWD, 0, -1, -1, [&](hipStream_t s) {
-             return launch_pool_bwd_bf16(dpool, (int64_t)B * C, a2, act, dz2, act, m, B, positions, C, 1.0f / (float)(H * W), s);
+             return launch_pool_bwd_bf16(dpool, (int64_t)B * C, sign, act / 4, dz2, act, m, B, positions, C, 1.0f / (float)(H * W), s);
          })))
         return rc;
     {   // delta at a1, gated by a1 > 0

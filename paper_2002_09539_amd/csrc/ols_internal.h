@@ -208,17 +208,17 @@ struct ConvBArgs {
     const void* in;         // fwd: layer input; dx: delta of the layer output; dw: layer input (bf16, padded)
     const void* w;          // fwd, dx: bf16 kernels
     const void* dout;       // dw: delta of the layer output (bf16, padded)
-    void* out;              // fwd: layer output; dx: delta of the layer input; padded, bf16 or (fwd only) fp32
+    void* out;              // fwd: layer output; dx: delta of the layer input; padded, bf16 -- or, fwd with out_f32, the
+                            // bare convolution + bias in fp32 with border rows as computed (their consumer skips them)
     int out_f32;
     const float* bias;      // fwd: [C] per group, or nullptr
-    const float* residual;  // fwd: fp32 [B H W][C] WITHOUT border, added before the activation, or nullptr
     const void* mask;       // dx: padded bf16 activations whose sign gates the result, or nullptr
     float* partial;         // dw: scratch of conv3x3_bf16_dw_splits(...) * groups * (9 C C + C) floats
     float* g;               // dw: gradients [groups][ld]
     int64_t ld, g_w_off, g_b_off;   // g_b_off < 0: no bias
-    int64_t s_in, s_w, s_dout, s_out, s_bias, s_res, s_mask;   // group strides (elements of the tensor's own type)
+    int64_t s_in, s_w, s_dout, s_out, s_bias, s_mask;   // group strides (elements of the tensor's own type)
     int groups, B, H, W, C;
-    int relu;
+    int relu;               // fwd with bf16 output: apply max(., 0)
 };
 hipError_t launch_conv3x3_bf16_fwd(const ConvBArgs& a, hipStream_t s);
 hipError_t launch_conv3x3_bf16_dx(const ConvBArgs& a, hipStream_t s);
@@ -227,8 +227,12 @@ int conv3x3_bf16_dw_splits(int groups, int B, int H, int W, int C);
 // fp32 [groups][B H W][C] -> bf16 [groups][B (H+2) (W+2)][C] with a zero border
 hipError_t launch_pad_cast_bf16(const float* src, int64_t s_src, uint16_t* dst, int64_t s_dst, int groups, int B, int H, int W,
                                 int C, hipStream_t s);
-// dz = bf16(dpool * scale) where a > 0 else 0; a fp32 and dz bf16, both over `positions` (padded) positions per sample
-hipError_t launch_pool_bwd_bf16(const float* dpool, int64_t s_dp, const float* a, int64_t s_a, uint16_t* dz, int64_t s_dz,
+// The block's tail: a2 = relu(y + X) on the image pixels (y fp32 padded, X fp32 not padded), pooled = its mean over the
+// positions, sign[padded pixel][C / 4] = one byte per four channels with bit e set iff a2 > 0 (border: 0).  a2 is not stored.
+hipError_t launch_shortcut_relu_pool(const float* y, int64_t s_y, const float* X, int64_t s_x, float* pooled, int64_t s_p,
+                                     uint8_t* sign, int64_t s_sign, int groups, int B, int H, int W, int C, hipStream_t s);
+// dz = bf16(dpool * scale) where the sign bit is set, else 0; dz bf16 over `positions` (padded) positions per sample
+hipError_t launch_pool_bwd_bf16(const float* dpool, int64_t s_dp, const uint8_t* sign, int64_t s_sign, uint16_t* dz, int64_t s_dz,
                                 int groups, int B, int positions, int C, float scale, hipStream_t s);
 
 // Batch normalisation in training mode over [group][P][C] tensors (statistics per group and channel over the P pixels).
