@@ -1,6 +1,7 @@
 // 3 x 3 convolutions (stride 1, zero padding 1) of the per-worker residual block with bf16 operands and fp32
 // accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16), grouped over the m workers: forward, back-propagated
-// delta, kernel / bias gradient; plus the conversion of the input batch and the pooling backward that feed them.  The
+// delta, kernel / bias gradient; plus the conversion of the input batch, the block's tail (shortcut, ReLU, pooling) and
+// the pooling backward.  The
 // model is the first residual stage of the network of Section 4 (arXiv 2002.09539, "Experimental setting") and produces
 // the stochastic gradients g_i of Section 2; every tensor is rounded to bf16 (to nearest even) where it becomes an
 // operand of a convolution's products, sums and everything else stay fp32.
@@ -18,11 +19,23 @@
 // FWD / DX: one workgroup per 256 padded pixels x 64 output channels.  The input rows m0 - (W + 3) .. m0 + 256 + (W + 3)
 // of a 64-channel chunk are copied to LDS ONCE (a strip, K-contiguous, pitch 64 + 8); the nine taps read their A
 // fragments from it at nine row offsets, so the operand crosses the LDS write port once instead of nine times.  The
-// 64 x 64 kernel slice of each tap is double-buffered through registers.  Four wavefronts of 64 x 64.
+// 64 x 64 kernel slice of each tap is double-buffered through registers.  Four wavefronts of 64 x 64; the MFMA takes the
+// kernel fragment first, so a lane's accumulators are four consecutive channels of one pixel, packed by the hardware
+// conversion and staged through LDS for 16-byte stores.  The second convolution writes conv + bias in fp32; a streaming
+// pass adds the shortcut, applies the ReLU, pools and keeps the activation's sign (one bit per element) for the backward
+// pass -- the activation itself is never stored.
 // DW: one workgroup per (pixel range, 64 x 64 block of input x output channels) holds all nine taps' accumulators
-// (9 x 64 x 64 fp32 = 144 registers per lane); per 32 pixels the input strip (32 + 2 (W + 3) rows, row-contiguous,
+// (9 x 64 x 64 fp32 = 144 registers per lane); per 64 pixels the input strip (64 + 2 (W + 3) rows, row-contiguous,
 // read with the transpose load at nine row offsets) and the delta tile pass through LDS; ranges are summed in range
 // order by the finish pass shared with the fp32 kernels (no atomics).
+//
+// Measured at the benchmark shape (16 workers x 128 samples x 32 x 32 x 64 channels, 154.6 GFLOP per launch): forward
+// 224 us (bf16 out) / 259 us (fp32 out), delta 249 us, kernel gradient 284 + 47 us, against 1390 - 1430 us for the fp32
+// kernels.  Tried and not kept: persistent workgroups that hold the whole kernel as 72 register fragments and walk the
+// tiles of a worker (one wavefront per SIMD, no barrier inside a tile: 280 - 400 us, nothing hides the epilogue's
+// latencies; with half the fragments per wavefront and two workgroups per compute unit 308 - 397 us); all nine kernel
+// slices requested at the start of a tile (no change); two slices of loads in flight in the kernel gradient (400
+// registers: one wavefront per SIMD, 349 us).
 #include <type_traits>
 
 #include "gemm_bf16_tile.h"
@@ -37,7 +50,7 @@ constexpr int kThreads = kTileThreads;
 constexpr int kXcds = 8;
 constexpr int kCB = 64;     // channel block: contraction chunk and output-channel tile
 constexpr int kBM = 256;    // padded pixels per forward / delta tile
-constexpr int kDwBK = 32;   // pixels per slice of the kernel-gradient contraction
+constexpr int kDwBK = 64;   // pixels per slice of the kernel-gradient contraction
 
 struct FastDiv {
     unsigned magic, shift;
@@ -317,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
 // kernel / bias gradient
 // ---------------------------------------------------------------------------------------------
 template <int NV>   // strip vectors per lane (upper bound of (32 + 2 halo) * 8 / 256)
-__global__ __launch_bounds__(kThreads) void conv3x3_dw_bf16_kernel(ConvBDev p) {
+__global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p) {
     using TD = TileRC<kCB, kDwBK>;               // delta tile: [32 pixels][64 channels + 32]
     constexpr int RP = TD::kPitch;               // the input strip uses the same pitch
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_all[];
@@ -641,8 +654,8 @@ hipError_t launch_conv3x3_bf16_dw(const ConvBArgs& a, hipStream_t s) {
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     const int nv = (strip_rows * (kCB / 8) + kThreads - 1) / kThreads;
     void (*kern)(ConvBDev) = nullptr;
-    if (nv <= 4) kern = conv3x3_dw_bf16_kernel<4>;
-    else if (nv <= 10) kern = conv3x3_dw_bf16_kernel<10>;
+    if (nv <= 5) kern = conv3x3_dw_bf16_kernel<5>;
+    else if (nv <= 11) kern = conv3x3_dw_bf16_kernel<11>;
     else return hipErrorInvalidValue;
     if (lds > 64 * 1024) {
         hipError_t e = ensure_dynamic_lds((const void*)kern, 160 * 1024);
