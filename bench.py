@@ -11,7 +11,7 @@ it is the one the metric's "fused update / anchor-average HBM GB/s" is defined o
 worker-iterations/s over exactly K timed steps after exactly W warm-up steps, the roofline of the dominant kernel
 from HIP-event timing on the kernel's own stream, the CPU oracle timed on a bounded sample of the same workload as a
 reported baseline, and under "configs" one compact record per other configuration (1, 2, 3, 5 and the convolutional
-workloads 6 and 7; its own run length, stated in the record): ms per step overlapped and serialised, the dominant
+workloads 6, 7 and 8; its own run length, stated in the record): ms per step overlapped and serialised, the dominant
 kernel and its roofline fraction, the oracle's rate.
 """
 import argparse
@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--config", type=int, default=4, help="headline workload number (BASELINE configs are 1-based)")
     ap.add_argument("--side-configs", type=str, default=None,
                     help="comma-separated configurations measured after the headline and reported under \"configs\" "
-                         "(default: 1,2,3,5,6,7 when the headline is configuration 4 with default options, else none)")
+                         "(default: 1,2,3,5,6,7,8 when the headline is configuration 4 with default options, else none)")
     ap.add_argument("--side-cpu-seconds", type=float, default=3.0,
                     help="target CPU time of the oracle baseline of each side configuration (at least one round)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
@@ -129,10 +129,11 @@ def algorithmic_work(cfg, ld, fused_update=True):
             # kernels store with them is overhead, not work): 288 flop per byte for a bf16-in, bf16-out convolution,
             # just below the 312 flop per byte ridge, so min(matrix peak, AI x HBM peak) is reported beside the peak
             work["cast_bf16"] = ("hbm", 1.5 * act)                      # fp32 batch in, bf16 batch out
-            work["conv_fwd_bytes"] = (1.0 * act + 2.5 * act) / 2        # first: bf16 in, bf16 out; second: bf16 in, fp32 shortcut in, fp32 out
+            work["conv_fwd_bytes"] = (1.0 * act + 1.5 * act) / 2        # first: bf16 in, bf16 out; second: bf16 in, fp32 out
             work["conv_dx_bytes"] = 1.5 * act                           # bf16 delta in, bf16 mask in, bf16 delta out
             work["conv_dw_bytes"] = 1.0 * act                           # bf16 input and bf16 delta
-            work["pool_bwd"] = ("hbm", 1.5 * act)                       # fp32 activation in, bf16 delta out
+            work["pool"] = ("hbm", 2.0 * act + act / 16)                # shortcut + ReLU + pooling: conv output and shortcut in, sign bytes out
+            work["pool_bwd"] = ("hbm", 0.5 * act + act / 16)            # sign bytes in, bf16 delta out
         if cfg.batch_norm:
             # statistics read z, the normalisation reads z (+ the shortcut in the second layer) and writes the activation
             work["bn_fwd"] = ("hbm", 3.5 * act)
@@ -432,7 +433,7 @@ def main():
                        and not args.opt and args.loop == "library" and not args.no_kernel_timing and args.tau is None
                        and not args.calibration_copy_mib)
     if args.side_configs is None:
-        sides = [1, 2, 3, 5, 6, 7] if (args.config == 4 and default_options) else []
+        sides = [1, 2, 3, 5, 6, 7, 8] if (args.config == 4 and default_options) else []
     else:
         sides = [int(t) for t in args.side_configs.split(",") if t.strip()]
 
