@@ -61,11 +61,39 @@ __device__ __forceinline__ void dw_consume(const DwOut& o, int N, int row, int c
     }
 }
 
+// The state of a tile requested ahead of the contraction: lane's vector k of the epilogue (pass k / kIters, iteration
+// k % kIters) is x[k] (and b[k], the momentum).  PF: 0 nothing, 1 parameters, 2 parameters and momentum.  Measured on
+// the bf16 weight-gradient GEMM of the 3072-2048-2048-2048-10 model (batch 256, 16 workers; us per launch): 269.6
+// without, 263.0 with the parameters (144 registers, three wavefronts per SIMD), 271.0 with parameters and momentum
+// (164 registers); on the fp32 kernel at batch 64 (64 workers) 584 / 595 / 605, so only the bf16 kernel uses it.
+#ifndef OLS_DW_PREFETCH
+#define OLS_DW_PREFETCH 1
+#endif
+template <int NVEC>
+struct DwState {
+    ep_f4 x[NVEC], b[NVEC];
+};
+template <int BM, int BN, int RP, int THREADS, int PF>
+__device__ __forceinline__ void dw_prefetch_state(DwState<BM * BN / 4 / THREADS>& st, const DwOut& o, int m0, int n0, int M, int N) {
+    constexpr int kVecPerRow = BN / 4, kIters = RP * kVecPerRow / THREADS;
+    if (PF == 0 || !o.upd.enabled) return;
+    const bool mom = o.upd.mu != 0.0f;
+#pragma unroll
+    for (int k = 0; k < BM * BN / 4 / THREADS; ++k) {
+        const int v = threadIdx.x + (k % kIters) * THREADS;
+        const int row = m0 + (k / kIters) * RP + v / kVecPerRow, col = n0 + 4 * (v % kVecPerRow);
+        const int64_t off = (row < M && col < N) ? (int64_t)row * N + col : 0;
+        st.x[k] = ep_load_stream((const ep_f4*)(o.upd.x_in + o.upd_base + off));
+        if (PF >= 2 && mom) st.b[k] = ep_load_stream((const ep_f4*)(o.upd.buf + o.upd_base + off));
+    }
+}
+
 // stage: LDS scratch of at least RP * (BN + 4) floats, RP a multiple of 32 dividing BM.
 // (m0, n0): tile origin; (wm0, wn0): this wavefront's origin inside the tile; M, N: matrix extents.
-template <int BM, int BN, int TM, int TN, int RP, int THREADS>
+template <int BM, int BN, int TM, int TN, int RP, int THREADS, int PF = 0>
 __device__ __forceinline__ void dw_epilogue_staged(float* stage, const ep_f16 (&acc)[TM][TN], const DwOut& o, int m0,
-                                                   int n0, int wm0, int wn0, int M, int N) {
+                                                   int n0, int wm0, int wn0, int M, int N,
+                                                   const DwState<BM * BN / 4 / THREADS>* st = nullptr) {
     constexpr int kPitch = BN + 4;
     constexpr int kVecPerRow = BN / 4;
     constexpr int kVecs = RP * kVecPerRow;
@@ -75,6 +103,7 @@ __device__ __forceinline__ void dw_epilogue_staged(float* stage, const ep_f16 (&
     const int lane = threadIdx.x % 64, lane32 = lane % 32, half = lane / 32;
     const bool fused = o.upd.enabled != 0;
     const bool mom = o.upd.mu != 0.0f, pull = o.upd.pull != 0;
+#pragma unroll
     for (int p0 = 0; p0 < BM; p0 += RP) {
         __syncthreads();   // the previous pass (or the main loop) has finished with the LDS
 #pragma unroll
@@ -89,6 +118,7 @@ __device__ __forceinline__ void dw_epilogue_staged(float* stage, const ep_f16 (&
             }
         }
         __syncthreads();
+#pragma unroll
         for (int it = 0; it < kIters; it += kUnroll) {
             ep_f4 gv[kUnroll], xv[kUnroll], bv[kUnroll], zv[kUnroll];
             int rows[kUnroll], cols[kUnroll];
@@ -103,8 +133,13 @@ __device__ __forceinline__ void dw_epilogue_staged(float* stage, const ep_f16 (&
                 if (!ok) rows[u] = -1;
                 if (fused) {   // every lane issues its loads (out-of-range lanes re-read element 0)
                     const int64_t off = ok ? (int64_t)rows[u] * N + cols[u] : 0;
-                    xv[u] = ep_load_stream((const ep_f4*)(o.upd.x_in + o.upd_base + off));
-                    if (mom) bv[u] = ep_load_stream((const ep_f4*)(o.upd.buf + o.upd_base + off));
+                    const int k = (p0 / RP) * kIters + it + u;
+                    if (PF >= 1) xv[u] = st->x[k];
+                    else xv[u] = ep_load_stream((const ep_f4*)(o.upd.x_in + o.upd_base + off));
+                    if (mom) {
+                        if (PF >= 2) bv[u] = st->b[k];
+                        else bv[u] = ep_load_stream((const ep_f4*)(o.upd.buf + o.upd_base + off));
+                    }
                     if (pull) zv[u] = *(const ep_f4*)(o.upd.z + o.col_base + off);
                 }
             }

@@ -119,6 +119,21 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    // DW with the fused update: the tile's parameters (and momentum) can be requested here, ahead of the contraction
+    constexpr int kDwPf = MODE == kDw ? OLS_DW_PREFETCH : 0;
+    constexpr int kDwFit = ((Shape::kLdsElems / 2) / (BN + 4)) / 32 * 32;
+    constexpr int kDwRP = kDwFit >= BM ? BM : (kDwFit >= 64 ? 64 : 32);   // rows per staging pass of the epilogue
+    DwState<BM * BN / 4 / kThreads> dw_state;
+    DwOut dw_out;
+    if constexpr (MODE == kDw) {
+        dw_out.g = (float*)p.c + (int64_t)group * p.sc;
+        dw_out.ldg = p.ldc;
+        dw_out.upd = p.upd;
+        dw_out.upd_base = (int64_t)group * p.upd.ld + p.upd_w_off;
+        dw_out.col_base = p.upd_w_off;
+        dw_prefetch_state<BM, BN, kDwRP, kThreads, kDwPf>(dw_state, dw_out, m0, n0, p.M, p.N);
+    }
+
     // DW only: the tiles of the first tile row also sum each column of B (a delta column over the batch),
     // which is the bias gradient of the layer, in sample order.
     const bool col_sums = MODE == kDw && p.colsum != nullptr && tm == 0 && threadIdx.x < BN;
@@ -219,16 +234,8 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
             }
         }
         // the gradient tile is staged through the (now idle) operand LDS, as many rows per pass as it holds
-        constexpr int kFit = ((Shape::kLdsElems / 2) / (BN + 4)) / 32 * 32;
-        constexpr int RP = kFit >= BM ? BM : (kFit >= 64 ? 64 : 32);   // a power-of-two share of the tile's rows
-        static_assert(kFit >= 32 && BM % RP == 0, "operand LDS too small to stage the gradient tile");
-        DwOut o;
-        o.g = (float*)p.c + (int64_t)group * p.sc;
-        o.ldg = p.ldc;
-        o.upd = p.upd;
-        o.upd_base = (int64_t)group * p.upd.ld + p.upd_w_off;
-        o.col_base = p.upd_w_off;
-        dw_epilogue_staged<BM, BN, TM, TN, RP, kThreads>((float*)lds_all, acc, o, m0, n0, wm0, wn0, p.M, p.N);
+        static_assert(kDwFit >= 32 && BM % kDwRP == 0, "operand LDS too small to stage the gradient tile");
+        dw_epilogue_staged<BM, BN, TM, TN, kDwRP, kThreads, kDwPf>((float*)lds_all, acc, dw_out, m0, n0, wm0, wn0, p.M, p.N, &dw_state);
     } else {
         // Epilogue of FWD / DA: the bf16 tile goes through LDS so that every lane then moves 16-byte vectors
         // of 8 consecutive columns (output, and the activations whose sign gates the delta).  Accumulator
