@@ -35,7 +35,11 @@
 // tiles of a worker (one wavefront per SIMD, no barrier inside a tile: 280 - 400 us, nothing hides the epilogue's
 // latencies; with half the fragments per wavefront and two workgroups per compute unit 308 - 397 us); all nine kernel
 // slices requested at the start of a tile (no change); two slices of loads in flight in the kernel gradient (400
-// registers: one wavefront per SIMD, 349 us).
+// registers: one wavefront per SIMD, 349 us); the present kernel made persistent, two workgroups per compute unit walking
+// ranges of tiles with the next tile's strip requested a tile ahead (the 44 extra live registers spill: 308 - 366 us).
+// Knock-outs on the forward kernel (218 us): one tap instead of nine 143 us, no epilogue 170 us, neither 87 us -- the
+// strip's round trip and the prologue cost as much as the matrix work, and only two workgroups per compute unit (71 KB
+// of LDS each) are there to overlap them.
 #include <type_traits>
 
 #include "gemm_bf16_tile.h"
@@ -191,20 +195,25 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
     };
 
-    u4 rb[TB::kPerThread];
+    // Kernel slices travel kAhead taps ahead of their use (a tap's 16 MFMAs per wavefront are shorter than a round trip
+    // to L2): a ring of kAhead register sets, slice t in set t % kAhead.
+    constexpr int kAhead = 3;
+    u4 rb[kAhead][TB::kPerThread];
+    unsigned okb[kAhead];
     for (int c0 = 0; c0 < C; c0 += kCB) {
         // the previous chunk's last barrier has passed: nobody reads the strip or the kernel buffers any more
         {
             u4 rs[NV];
-            unsigned okb = load_b(rb, 0, c0);
+#pragma unroll
+            for (int t = 0; t < kAhead; ++t) okb[t] = load_b(rb[t], t, c0);
             const unsigned oks = load_strip(rs, c0);
-            TB::store(lds_b(0), rb, okb);
+            TB::store(lds_b(0), rb[0], okb[0]);
             store_strip(rs, oks);
         }
         __syncthreads();
+#pragma unroll
         for (int tap = 0; tap < 9; ++tap) {
-            unsigned okb = 0;
-            if (tap + 1 < 9) okb = load_b(rb, tap + 1, c0);
+            if (tap + kAhead < 9) okb[tap % kAhead] = load_b(rb[tap % kAhead], tap + kAhead, c0);   // its slice is in LDS already
             const int dy = tap / 3 - 1, dx = tap % 3 - 1;
             const int shift = (MODE == 0 ? 1 : -1) * (dy * p.Wp + dx);
             const uint16_t* a_base = strip + (p.halo + shift) * SP;
@@ -217,7 +226,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
                 mfmas(s & 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (tap + 1 < 9) TB::store(lds_b((tap + 1) & 1), rb, okb);
+            if (tap + 1 < 9) TB::store(lds_b((tap + 1) & 1), rb[(tap + 1) % kAhead], okb[(tap + 1) % kAhead]);
             __syncthreads();
         }
     }
