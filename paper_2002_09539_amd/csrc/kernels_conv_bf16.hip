@@ -370,7 +370,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
     for (int t = 0; t < 9; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-    const bool col_sums = ci0 == 0 && threadIdx.x < kCB;
+    const bool col_sums = ci0 == 0;   // bias gradient: column lane of the delta, rows shared out over the four wavefronts
     float col_acc = 0.0f;
 
     const int nvec = strip_rows * (kCB / 8);
@@ -412,19 +412,30 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
         }
         const uint16_t* S = lds_s(cur) + p.halo * RP;
         const uint16_t* D = lds_d(cur);
+        // 4 k-steps x 9 taps = 12 groups of one kernel row: the fragments of group g + 1 are requested before the MFMAs
+        // of group g (a lone just-in-time read would expose the LDS latency on every MFMA)
+        constexpr int kGroups = (kDwBK / 16) * 3;
+        bf16x8 fi[2][3], fd[2];
+        auto load_group = [&](int g) {
+            const int s = g / 3, kh = g % 3;
+            if (kh == 0) fd[s & 1] = TD::frag(D, 32 * wj, s, lane);
 #pragma unroll
-        for (int s = 0; s < kDwBK / 16; ++s) {
-            const bf16x8 fd = TD::frag(D, 32 * wj, s, lane);
+            for (int kw = 0; kw < 3; ++kw) fi[g & 1][kw] = TD::frag(S + ((kh - 1) * p.Wp + (kw - 1)) * RP, 32 * wi, s, lane);
+        };
+        load_group(0);
 #pragma unroll
-            for (int tap = 0; tap < 9; ++tap) {
-                const int shift = (tap / 3 - 1) * p.Wp + (tap % 3 - 1);
-                const bf16x8 fi = TD::frag(S + shift * RP, 32 * wi, s, lane);
-                acc[tap] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fi, fd, acc[tap], 0, 0, 0);
-            }
+        for (int g = 0; g < kGroups; ++g) {
+            if (g + 1 < kGroups) load_group(g + 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw)
+                acc[3 * (g % 3) + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fi[g & 1][kw], fd[(g / 3) & 1], acc[3 * (g % 3) + kw], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (col_sums) {
-#pragma unroll 8
-            for (int k = 0; k < kDwBK; ++k) col_acc += __uint_as_float((unsigned)D[k * RP + threadIdx.x] << 16);
+        if (col_sums) {   // every wavefront sums a quarter of the slice's rows: the barrier waits for the slowest of them
+#pragma unroll
+            for (int k = 0; k < kDwBK / 4; ++k)
+                col_acc += __uint_as_float((unsigned)D[(wave * (kDwBK / 4) + k) * RP + lane] << 16);
         }
         if (t + 1 < nslices) {
             store_strip(lds_s(cur ^ 1), rs, oks);
@@ -443,7 +454,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
             PART[((int64_t)tap * C + ci) * C + co0 + 32 * wj + lane32] = acc[tap][r];
         }
     }
-    if (col_sums) PART[n_w + co0 + threadIdx.x] = col_acc;
+    if (col_sums) {   // the four wavefronts' shares, added in wavefront order
+        float* red = (float*)lds_all;
+        red[threadIdx.x] = col_acc;
+        __syncthreads();
+        if (threadIdx.x < kCB) PART[n_w + co0 + threadIdx.x] = ((red[threadIdx.x] + red[64 + threadIdx.x]) + red[128 + threadIdx.x]) + red[192 + threadIdx.x];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
