@@ -653,7 +653,7 @@ hipError_t launch_conv3x3_bf16_dx(const ConvBArgs& a, hipStream_t s) { return co
 int conv3x3_bf16_dw_splits(int groups, int B, int H, int W, int C) {
     const int64_t Pp = (int64_t)B * (H + 2) * (W + 2);
     const int64_t tiles = (int64_t)groups * (C / kCB) * (C / kCB);
-    int64_t s = (768 + tiles - 1) / tiles;                  // three workgroups per compute unit (their LDS allows three)
+    int64_t s = (512 + tiles - 1) / tiles;                  // two workgroups per compute unit (registers and LDS allow two)
     const int64_t most = (Pp + 511) / 512;                  // a range covers at least 512 padded pixels
     if (s > most) s = most;
     if (s > 256) s = 256;
