@@ -507,11 +507,12 @@ __global__ __launch_bounds__(kThreads) void shortcut_relu_pool_kernel(const floa
     uint8_t* S = sign + (int64_t)g * s_sign + (int64_t)b * per * c4n + c4;
     f4 acc = {0.f, 0.f, 0.f, 0.f};
     if (stripe < stripes) {
-        for (int p0 = stripe; p0 < per; p0 += 4 * stripes) {   // four positions per thread in flight
-            f4 yv[4], xv[4];
-            bool in[4];
+        constexpr int kFly = 8;
+        for (int p0 = stripe; p0 < per; p0 += kFly * stripes) {   // kFly positions per thread in flight
+            f4 yv[kFly], xv[kFly];
+            bool in[kFly];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < kFly; ++t) {
                 const int pp = p0 + t * stripes;
                 const int yy = (int)fast_div((unsigned)pp, div_wp), xx = pp - yy * Wp;
                 in[t] = pp < per && yy >= 1 && yy <= H && xx >= 1 && xx <= W;
@@ -521,7 +522,7 @@ __global__ __launch_bounds__(kThreads) void shortcut_relu_pool_kernel(const floa
                 }
             }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < kFly; ++t) {
                 const int pp = p0 + t * stripes;
                 if (pp >= per) continue;
                 unsigned bits = 0;
