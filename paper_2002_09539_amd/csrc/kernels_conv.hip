@@ -343,7 +343,9 @@ __global__ __launch_bounds__(kThreads, OLS_CONV_DW_WAVES) void conv3x3_dw_kernel
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
     // the bias gradient is the column sum of dout over the pixel range: formed once per range (kernel row 0, first block)
-    const bool col_sums = kh == 0 && tm == 0 && threadIdx.x < kBN;
+    // (the rows of a slice are shared out over the four wavefronts, which add their shares in wavefront order at the end:
+    // one wavefront summing alone would keep the other three at the slice's barrier)
+    const bool col_sums = kh == 0 && tm == 0;
     float col_acc = 0.0f;
 
     constexpr int Q = BK / 8;
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(kThreads, OLS_CONV_DW_WAVES) void conv3x3_dw_kernel
         }
         if (col_sums) {
 #pragma unroll
-            for (int k = 0; k < BK; ++k) col_acc += lds_b(cur)[k * TB::kPitch + threadIdx.x];
+            for (int k = 0; k < BK / 4; ++k) col_acc += lds_b(cur)[(wave * (BK / 4) + k) * TB::kPitch + lane];
         }
         store_ab(cur ^ 1, next);
         __syncthreads();
@@ -408,7 +410,14 @@ __global__ __launch_bounds__(kThreads, OLS_CONV_DW_WAVES) void conv3x3_dw_kernel
     }
     const int64_t per_group = (int64_t)9 * C * C + C;
     float* PART = p.partial + ((int64_t)split * p.groups + group) * per_group;
-    if (col_sums && n0 + (int)threadIdx.x < C) PART[(int64_t)9 * C * C + n0 + threadIdx.x] = col_acc;
+    if (col_sums) {
+        __syncthreads();   // the operand tiles are no longer read
+        float* red = lds_all;
+        red[threadIdx.x] = col_acc;
+        __syncthreads();
+        if (threadIdx.x < kBN && n0 + (int)threadIdx.x < C)
+            PART[(int64_t)9 * C * C + n0 + threadIdx.x] = ((red[threadIdx.x] + red[64 + threadIdx.x]) + red[128 + threadIdx.x]) + red[192 + threadIdx.x];
+    }
     const int col = n0 + wn0 + lane32;
     if (col < C) {
 #pragma unroll

@@ -30,16 +30,21 @@
 // order by the finish pass shared with the fp32 kernels (no atomics).
 //
 // Measured at the benchmark shape (16 workers x 128 samples x 32 x 32 x 64 channels, 154.6 GFLOP per launch): forward
-// 224 us (bf16 out) / 259 us (fp32 out), delta 249 us, kernel gradient 284 + 47 us, against 1390 - 1430 us for the fp32
-// kernels.  Tried and not kept: persistent workgroups that hold the whole kernel as 72 register fragments and walk the
-// tiles of a worker (one wavefront per SIMD, no barrier inside a tile: 280 - 400 us, nothing hides the epilogue's
-// latencies; with half the fragments per wavefront and two workgroups per compute unit 308 - 397 us); all nine kernel
-// slices requested at the start of a tile (no change); two slices of loads in flight in the kernel gradient (400
-// registers: one wavefront per SIMD, 349 us); the present kernel made persistent, two workgroups per compute unit walking
-// ranges of tiles with the next tile's strip requested a tile ahead (the 44 extra live registers spill: 308 - 366 us).
+// 221 us (bf16 out) / 245 us (fp32 out), delta 252 us, kernel gradient 186 + 22 us, against 1390 - 1430 us for the fp32
+// kernels.  What moved the kernel gradient from 289 us: fragment reads issued a kernel row ahead of the MFMAs (258), the
+// bias column sums shared out over the four wavefronts instead of one wavefront summing while three wait at the barrier
+// (219), and 512 workgroups -- one round at two per compute unit -- instead of 768 (185; the finish pass 46 -> 22).
 // Knock-outs on the forward kernel (218 us): one tap instead of nine 143 us, no epilogue 170 us, neither 87 us -- the
 // strip's round trip and the prologue cost as much as the matrix work, and only two workgroups per compute unit (71 KB
 // of LDS each) are there to overlap them.
+// Tried and not kept: persistent workgroups that hold the whole kernel as 72 register fragments and walk the tiles of a
+// worker (one wavefront per SIMD, no barrier inside a tile: 280 - 400 us; with half the fragments per wavefront and two
+// workgroups per compute unit 308 - 397 us); the present forward kernel made persistent with the next tile's strip
+// requested a tile ahead (the 44 extra live registers spill: 308 - 366 us); all nine kernel slices requested at the
+// start of a tile (no change); in the kernel gradient two slices of loads in flight (400 registers, one wavefront per
+// SIMD: 349 us), fragment reads two kernel rows ahead (259 against 258 us), and an LDS ring of input rows that fetches
+// only the 64 new rows per slice three slices ahead (the wrap-around address arithmetic per fragment read costs more
+// than the loads it saves: 325 us).
 #include <type_traits>
 
 #include "gemm_bf16_tile.h"
