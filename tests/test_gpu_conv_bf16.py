@@ -42,6 +42,9 @@ def groups_of(C, classes):
     (1, (64, 1, 1, 3), 2),         # a single position: every tap but the centre reads the border
     (2, (64, 40, 3, 5), 2),        # narrow images
     (1, (64, 3, 100, 4), 1),       # wide images: the long halo (the larger strip variant of the kernel gradient)
+    (1, (64, 2, 128, 3), 1),       # the widest image the kernels take
+    (2, (64, 7, 33, 5), 3),        # one column past the short-halo variants
+    (1, (192, 4, 5, 3), 2),        # three contraction chunks, three output tiles, 3 x 3 blocks of the gradient
 ])
 def test_gradient_and_loss(m, dims, batch):
     cfg, X, labels, x0 = conv_case(m, dims, batch, 1, seed=515)

@@ -64,6 +64,8 @@ def one_step(cfg, dims, batch, X, labels, x0, eps=1e-5):
     (2, (64, 32, 32, 10), 5),     # 5120 pixels: three ranges, the last one short
     (1, (16, 1, 1, 3), 2),        # two pixels per channel
     (2, (16, 40, 3, 5), 2),
+    (1, (256, 4, 4, 6), 2),       # the widest block: one stripe per channel vector row of the workgroup
+    (1, (112, 5, 3, 4), 3),       # 28 channel vectors: 9 stripes, four idle threads
 ])
 def test_gradient_and_loss_match_oracle(m, dims, batch):
     cfg, X, labels, x0 = bn_case(m, dims, batch, 1, seed=141)
