@@ -44,7 +44,8 @@
 // start of a tile (no change); in the kernel gradient two slices of loads in flight (400 registers, one wavefront per
 // SIMD: 349 us), fragment reads two kernel rows ahead (259 against 258 us), and an LDS ring of input rows that fetches
 // only the 64 new rows per slice three slices ahead (the wrap-around address arithmetic per fragment read costs more
-// than the loads it saves: 325 us).
+// than the loads it saves: 325 us); forward / delta tiles of 128 pixels (134 registers, 53 KB of LDS, three workgroups
+// per compute unit; the halo is then 1.55 x the tile: 260 / 291 / 271 us against 221 / 245 / 252).
 #include <type_traits>
 
 #include "gemm_bf16_tile.h"
@@ -109,13 +110,13 @@ __device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bi
 // ---------------------------------------------------------------------------------------------
 // forward (MODE 0) and back-propagated delta (MODE 1)
 // ---------------------------------------------------------------------------------------------
-template <int MODE, bool OUT_F32, int NV>   // NV: strip vectors per lane (upper bound of (256 + 2 halo) * 8 / 256)
-__global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
+template <int MODE, bool OUT_F32, int NV, int BM>   // NV: strip vectors per lane (upper bound of (BM + 2 halo) * 8 / 256); BM: pixels per tile
+__global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kernel(ConvBDev p) {
     using TB = typename std::conditional<MODE == 0, TileRC<kCB, kCB>, TileKC<kCB, kCB>>::type;   // FWD w[k = ci][n = co]; DX w[n = ci][k = co]
     constexpr int SP = kCB + 8;                  // strip pitch (bf16 elements): 144 bytes, conflict-free 16-byte reads
-    constexpr int TM = 2, TN = 2, KS = kCB / 16; // a wavefront owns 64 pixels x 64 channels
+    constexpr int TM = BM / 128, TN = 2, KS = kCB / 16; // a wavefront owns BM / 4 pixels x 64 channels
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_all[];
-    const int strip_rows = kBM + 2 * p.halo;
+    const int strip_rows = BM + 2 * p.halo;
     uint16_t* strip = lds_all;
     uint16_t* lds_b0 = lds_all + strip_rows * SP;
     auto lds_b = [&](int buf) { return lds_b0 + buf * TB::kElems; };
@@ -127,23 +128,23 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
     const int per_group = p.tiles_m * p.tiles_n;
     const int group = tile / per_group;
     const int tm = (tile % per_group) / p.tiles_n, tn = tile % p.tiles_n;
-    const int m0 = tm * kBM, n0 = tn * kCB;
+    const int m0 = tm * BM, n0 = tn * kCB;
     const uint16_t* IN = p.in + (int64_t)group * p.s_in;
     const uint16_t* Wg = p.w + (int64_t)group * p.s_w;
     const int C = p.C;
 
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int lane32 = lane % 32, half = lane / 32;
-    const int wm0 = wave * 64;
+    const int wm0 = wave * (BM / 4);
 
     if (threadIdx.x < kCB) bias_lds[threadIdx.x] = (MODE == 0 && p.bias) ? p.bias[(int64_t)group * p.s_bias + n0 + threadIdx.x] : 0.0f;
     {   // which rows of the tile are image pixels (the others get the zero border)
         int up;
         const int q = m0 + threadIdx.x;
-        row_flag[threadIdx.x] = q < p.Pp && interior(p, q, &up) ? 1 : 0;
+        if (threadIdx.x < BM) row_flag[threadIdx.x] = q < p.Pp && interior(p, q, &up) ? 1 : 0;
     }
 
-    // rows m0 - halo .. m0 + kBM + halo of channels c0 .. c0 + 63, zeros outside [0, Pp): every lane requests all its
+    // rows m0 - halo .. m0 + BM + halo of channels c0 .. c0 + 63, zeros outside [0, Pp): every lane requests all its
     // vectors at once (one round trip), then writes them to LDS
     const int nvec = strip_rows * (kCB / 8);
     auto load_strip = [&](u4 (&r)[NV], int c0) -> unsigned {
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
     if constexpr (OUT_F32) {
         // convolution + bias only (what follows it is another kernel's), staged in two passes of 128 rows.  Border rows
         // are written as computed; their consumer skips them.
-        constexpr int FP = kCB + 8, HR = kBM / 2;
+        constexpr int FP = kCB + 8, HR = BM / 2;
         constexpr int kVecPerRow = kCB / 4, kPer = HR * kVecPerRow / kThreads;
         float* stage = (float*)lds_all;
         float* OUT = (float*)p.out + (int64_t)group * p.s_out;
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_kernel(ConvBDev p) {
             }
         }
     } else {
-        constexpr int kVecPerRow = kCB / 8, kPer = kBM * kVecPerRow / kThreads;
+        constexpr int kVecPerRow = kCB / 8, kPer = BM * kVecPerRow / kThreads;
         uint16_t* OUT = (uint16_t*)p.out + (int64_t)group * p.s_out;
         const uint16_t* Mk = MODE == 1 && p.mask ? p.mask + (int64_t)group * p.s_mask : nullptr;
         // the activations whose sign gates the delta are requested before the tile is staged
@@ -621,28 +622,29 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     p.bias = MODE == 0 ? a.bias : nullptr;
     p.mask = MODE == 1 ? (const uint16_t*)a.mask : nullptr;
     p.s_in = a.s_in; p.s_w = a.s_w; p.s_out = a.s_out; p.s_bias = a.s_bias; p.s_mask = a.s_mask;
-    p.tiles_m = (p.Pp + kBM - 1) / kBM;
+    constexpr int BM = kBM;   // 128 (three workgroups per compute unit, 134 registers) measured 8 - 19 % slower: halo 1.55x
+    p.tiles_m = (p.Pp + BM - 1) / BM;
     p.tiles_n = a.C / kCB;
     const int64_t total = (int64_t)a.groups * p.tiles_m * p.tiles_n;
     if (total > (1 << 30)) return hipErrorInvalidValue;
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
-    const int strip_rows = kBM + 2 * p.halo;
+    const int strip_rows = BM + 2 * p.halo;
     const size_t b_elems = MODE == 0 ? TileRC<kCB, kCB>::kElems : TileKC<kCB, kCB>::kElems;
-    const size_t lds = ((size_t)strip_rows * (kCB + 8) + 2 * b_elems) * sizeof(uint16_t) + kCB * sizeof(float) + kBM;   // strip, kernel slices, bias, row flags
-    constexpr int NV0 = ((kBM + 2 * 35) * (kCB / 8) + kThreads - 1) / kThreads;                        // widths up to 32
-    constexpr int NV1 = ((kBM + 2 * (kConvBf16MaxWidth + 3)) * (kCB / 8) + kThreads - 1) / kThreads;    // any width
+    const size_t lds = ((size_t)strip_rows * (kCB + 8) + 2 * b_elems) * sizeof(uint16_t) + kCB * sizeof(float) + BM;   // strip, kernel slices, bias, row flags
+    constexpr int NV0 = ((BM + 2 * 35) * (kCB / 8) + kThreads - 1) / kThreads;                        // widths up to 32
+    constexpr int NV1 = ((BM + 2 * (kConvBf16MaxWidth + 3)) * (kCB / 8) + kThreads - 1) / kThreads;    // any width
     const int nv = (strip_rows * (kCB / 8) + kThreads - 1) / kThreads;
-    // the output tile is staged in the strip's place: 256 x 72 bf16, or 128 x 72 floats per pass
-    static_assert((size_t)(kBM + 2 * 4) * (kCB + 8) * 2 >= (size_t)(kBM / 2) * (kCB + 8) * 4, "staging area");
+    // the output tile is staged in the strip's place: BM x 72 bf16, or BM / 2 x 72 floats per pass
+    static_assert((size_t)(BM + 2 * 4) * (kCB + 8) * 2 >= (size_t)(BM / 2) * (kCB + 8) * 4, "staging area");
     if (lds > 160 * 1024 || nv > NV1) return hipErrorInvalidValue;
     void (*kern)(ConvBDev);
     if (nv <= NV0)
-        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV0> : conv3x3_bf16_kernel<0, false, NV0>)
-                         : conv3x3_bf16_kernel<1, false, NV0>;
+        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV0, BM> : conv3x3_bf16_kernel<0, false, NV0, BM>)
+                         : conv3x3_bf16_kernel<1, false, NV0, BM>;
     else
-        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV1> : conv3x3_bf16_kernel<0, false, NV1>)
-                         : conv3x3_bf16_kernel<1, false, NV1>;
+        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV1, BM> : conv3x3_bf16_kernel<0, false, NV1, BM>)
+                         : conv3x3_bf16_kernel<1, false, NV1, BM>;
     if (lds > 64 * 1024) {
         hipError_t e = ensure_dynamic_lds((const void*)kern, 160 * 1024);
         if (e != hipSuccess) return e;
