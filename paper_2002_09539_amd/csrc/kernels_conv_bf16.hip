@@ -79,6 +79,7 @@ struct ConvBDev {
     int relu;
     int tiles_m, tiles_n, total_tiles, chunk;
     FastDiv div_per, div_wp; // division by (H + 2) (W + 2) and by W + 2
+    FastDiv div_pg, div_tn;  // FWD, DX: division by tiles_m * tiles_n and by tiles_n
     int splits, k_chunk;
 };
 
@@ -105,29 +106,53 @@ __device__ __forceinline__ bool interior(const ConvBDev& p, int q, int* unpadded
     return y >= 1 && y <= p.H && x >= 1 && x <= p.W;
 }
 
+// Buffer addressing: a descriptor of [base, base + bytes) and 32-bit byte offsets.  The hardware checks the lane's offset
+// against the range: a load outside returns zeros and a store outside is dropped, so tiles that hang over either end of
+// a tensor (the strip's halo, the last tile's rows) need no per-lane predicates or 64-bit address arithmetic.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // raw buffer, 32-bit data format
+}
+__device__ __forceinline__ u4 buf_load(rsrc_t r, unsigned lane_off, unsigned uniform_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)uniform_off, 0);
+}
+__device__ __forceinline__ void buf_store(u4 v, rsrc_t r, unsigned lane_off) { __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, 0, 0); }
+
 __device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bits_rne(a) | (bf16_bits_rne(b) << 16); }
 
 // ---------------------------------------------------------------------------------------------
 // forward (MODE 0) and back-propagated delta (MODE 1)
 // ---------------------------------------------------------------------------------------------
+// LDS of the forward / delta kernel, in bf16 elements: the strip and two kernel slices -- or, if larger, the fp32 output
+// staging of the four wavefronts (BM / 4 rows of 64 + 4 floats each), which takes their place after the last tap.
+constexpr int kStagePitchF32 = kCB + 4;
+template <int BM, bool OUT_F32>
+__host__ __device__ constexpr int conv_main_elems(int strip_rows, int slice_elems) {
+    const int work = strip_rows * (kCB + 8) + 2 * slice_elems;
+    const int stage = OUT_F32 ? BM * kStagePitchF32 * 2 : 0;
+    return work > stage ? work : stage;
+}
+
 template <int MODE, bool OUT_F32, int NV, int BM>   // NV: strip vectors per lane (upper bound of (BM + 2 halo) * 8 / 256); BM: pixels per tile
 __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kernel(ConvBDev p) {
     using TB = typename std::conditional<MODE == 0, TileRC<kCB, kCB>, TileKC<kCB, kCB>>::type;   // FWD w[k = ci][n = co]; DX w[n = ci][k = co]
     constexpr int SP = kCB + 8;                  // strip pitch (bf16 elements): 144 bytes, conflict-free 16-byte reads
     constexpr int TM = BM / 128, TN = 2, KS = kCB / 16; // a wavefront owns BM / 4 pixels x 64 channels
+    static_assert(TB::kLineStep == 32 && TB::kPerThread == 2, "a lane's vectors are 32 rows apart in the strip and in a kernel slice");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_all[];
-    const int strip_rows = BM + 2 * p.halo;
+    constexpr int kStripRows = NV * 32;          // every lane moves NV vectors: rows past BM + 2 halo are loaded and never read
     uint16_t* strip = lds_all;
-    uint16_t* lds_b0 = lds_all + strip_rows * SP;
+    uint16_t* lds_b0 = lds_all + kStripRows * SP;
     auto lds_b = [&](int buf) { return lds_b0 + buf * TB::kElems; };
-    float* bias_lds = (float*)(lds_b0 + 2 * TB::kElems);     // [64] the tile's slice of the bias (zeros without one)
-    uint8_t* row_flag = (uint8_t*)(bias_lds + kCB);          // [256] 1: image pixel, 0: border
+    // the fp32 output is staged over the strip and the kernel slices together (conv_main_elems)
+    uint8_t* row_flag = (uint8_t*)(lds_all + conv_main_elems<BM, OUT_F32>(kStripRows, TB::kElems));   // [BM] 1: image pixel, 0: border
 
     const int tile = xcd_tile(p.chunk, p.total_tiles);
     if (tile < 0) return;
     const int per_group = p.tiles_m * p.tiles_n;
-    const int group = tile / per_group;
-    const int tm = (tile % per_group) / p.tiles_n, tn = tile % p.tiles_n;
+    const int group = (int)fast_div((unsigned)tile, p.div_pg);
+    const int in_group = tile - group * per_group;
+    const int tm = (int)fast_div((unsigned)in_group, p.div_tn), tn = in_group - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * kCB;
     const uint16_t* IN = p.in + (int64_t)group * p.s_in;
     const uint16_t* Wg = p.w + (int64_t)group * p.s_w;
@@ -137,42 +162,37 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
     const int lane32 = lane % 32, half = lane / 32;
     const int wm0 = wave * (BM / 4);
 
-    if (threadIdx.x < kCB) bias_lds[threadIdx.x] = (MODE == 0 && p.bias) ? p.bias[(int64_t)group * p.s_bias + n0 + threadIdx.x] : 0.0f;
-    {   // which rows of the tile are image pixels (the others get the zero border)
-        int up;
-        const int q = m0 + threadIdx.x;
-        if (threadIdx.x < BM) row_flag[threadIdx.x] = q < p.Pp && interior(p, q, &up) ? 1 : 0;
-    }
-
-    // rows m0 - halo .. m0 + BM + halo of channels c0 .. c0 + 63, zeros outside [0, Pp): every lane requests all its
-    // vectors at once (one round trip), then writes them to LDS
-    const int nvec = strip_rows * (kCB / 8);
-    auto load_strip = [&](u4 (&r)[NV], int c0) -> unsigned {
-        unsigned okmask = 0;
+    // Byte offsets in a [rows][C] bf16 tensor: lane t of the workgroup owns the 16-byte vector t % 8 of row t / 8, and its
+    // further vectors lie 32 rows below.  The same lane offset serves the strip and the kernel slices.
+    const unsigned row_bytes = 2u * (unsigned)C;
+    const unsigned lane_off = (threadIdx.x / 8) * row_bytes + (threadIdx.x % 8) * 16u;
+    const unsigned step32 = 32u * row_bytes;
+    const rsrc_t in_rs = make_rsrc(IN, (unsigned)p.Pp * row_bytes);
+    const rsrc_t w_rs = make_rsrc(Wg, 9u * (unsigned)C * row_bytes);
+    // rows m0 - halo .. of channels c0 .. c0 + 63: rows before the tensor wrap to offsets beyond its end, rows after it
+    // lie beyond it too -- both read as zeros.  Every lane requests all its vectors at once (one round trip), then
+    // writes them to LDS.
+    const unsigned strip_off = (unsigned)(m0 - p.halo) * row_bytes + lane_off;
+    uint16_t* strip_lane = strip + (threadIdx.x / 8) * SP + (threadIdx.x % 8) * 8;
+    auto load_strip = [&](u4 (&r)[NV], int c0) {
 #pragma unroll
-        for (int t = 0; t < NV; ++t) {
-            const int v = threadIdx.x + t * kThreads;
-            const int q = m0 - p.halo + v / (kCB / 8);
-            const bool ok = v < nvec && q >= 0 && q < p.Pp;
-            r[t] = *(const u4*)(IN + (ok ? (int64_t)q * C + c0 + (v % (kCB / 8)) * 8 : 0));
-            okmask |= ok ? (1u << t) : 0u;
-        }
-        return okmask;
+        for (int t = 0; t < NV; ++t) r[t] = buf_load(in_rs, strip_off + t * step32, 2u * c0);
     };
-    auto store_strip = [&](const u4 (&r)[NV], unsigned okmask) {
+    auto store_strip = [&](const u4 (&r)[NV]) {
 #pragma unroll
-        for (int t = 0; t < NV; ++t) {
-            const int v = threadIdx.x + t * kThreads;
-            if (v < nvec) {
-                const u4 zero = {0u, 0u, 0u, 0u};
-                *(u4*)(strip + (v / (kCB / 8)) * SP + (v % (kCB / 8)) * 8) = (okmask >> t) & 1u ? r[t] : zero;
-            }
-        }
+        for (int t = 0; t < NV; ++t) *(u4*)(strip_lane + t * 32 * SP) = r[t];
     };
     // the 64 x 64 kernel slice of one tap.  Memory [ci][co]: FWD (row-contiguous tile) k = ci, rows = co; DX
     // (K-contiguous tile) rows = ci, k = co
-    auto load_b = [&](u4 (&r)[TB::kPerThread], int tap, int c0) -> unsigned {
-        return TB::load(r, Wg + (int64_t)tap * C * C, C, n0, c0, C, C);
+    auto load_b = [&](u4 (&r)[TB::kPerThread], int tap, int c0) {
+        const unsigned first = 2u * (unsigned)((tap * C + (MODE == 0 ? c0 : n0)) * C + (MODE == 0 ? n0 : c0));
+#pragma unroll
+        for (int t = 0; t < TB::kPerThread; ++t) r[t] = buf_load(w_rs, lane_off + t * step32, first);
+    };
+    auto store_b = [&](int buf, const u4 (&r)[TB::kPerThread]) {
+        uint16_t* dst = TB::lane_lds(lds_b(buf));
+#pragma unroll
+        for (int t = 0; t < TB::kPerThread; ++t) *(u4*)(dst + t * TB::kLdsLineStep) = r[t];
     };
 
     // The MFMA takes the KERNEL fragment first and the pixel fragment second, so the accumulator tile is out^T:
@@ -205,21 +225,55 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
     // to L2): a ring of kAhead register sets, slice t in set t % kAhead.
     constexpr int kAhead = 3;
     u4 rb[kAhead][TB::kPerThread];
-    unsigned okb[kAhead];
+    // Delta: the activations whose sign gates the result -- the 16-byte vectors of the wavefront's own rows that this
+    // lane will write -- are requested kMaskTap taps into a chunk, when no kernel slice is in flight any more (with the
+    // long strips of wide images the registers do not allow it: there they are requested after the last tap).
+    constexpr int kVecB = kCB / 8, kPerB = (BM / 4) * kVecB / 64, kMaskTap = NV <= 12 ? 6 : 9;
+    u4 mk[MODE == 1 ? kPerB : 1];
+    const uint16_t* Mk = MODE == 1 && p.mask ? p.mask + (int64_t)group * p.s_mask : nullptr;
+    const rsrc_t mk_rs = make_rsrc(Mk ? Mk : IN, Mk ? (unsigned)p.Pp * row_bytes : 0u);
+    // the wavefront's own rows of the [Pp][C] bf16 output: lane l moves the vector l % 8 of rows wm0 + l / 8 + 8 t
+    const unsigned own_off = (unsigned)(m0 + wm0 + lane / kVecB) * row_bytes + 2u * (unsigned)n0 + (lane % kVecB) * 16u;
+    const unsigned step8 = (64 / kVecB) * row_bytes;
+    auto load_mask = [&]() {
+#pragma unroll
+        for (int t = 0; t < kPerB; ++t) mk[t] = buf_load(mk_rs, own_off + t * step8, 0u);
+    };
+    // Forward: the lane's channels of the bias (register quad g4 of block j: channels 32 j + 8 g4 + 4 (lane / 32) ..),
+    // requested at the same point and added in the epilogue.
+    f4 bq[MODE == 0 ? TN : 1][4];
+    // (an empty range without a bias: zeros, and no branch for the waits on the kernel slices to be merged over)
+    const rsrc_t bias_rs = make_rsrc(MODE == 0 && p.bias ? (const void*)(p.bias + (int64_t)group * p.s_bias + n0) : (const void*)IN,
+                                     MODE == 0 && p.bias ? kCB * 4u : 0u);
+    auto load_bias = [&]() {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) bq[j][g4] = __builtin_bit_cast(f4, buf_load(bias_rs, 16u * half + 128u * j + 32u * g4, 0u));
+    };
     for (int c0 = 0; c0 < C; c0 += kCB) {
         // the previous chunk's last barrier has passed: nobody reads the strip or the kernel buffers any more
         {
             u4 rs[NV];
+            load_b(rb[0], 0, c0);   // what the first tap needs goes first
+            load_strip(rs, c0);
 #pragma unroll
-            for (int t = 0; t < kAhead; ++t) okb[t] = load_b(rb[t], t, c0);
-            const unsigned oks = load_strip(rs, c0);
-            TB::store(lds_b(0), rb[0], okb[0]);
-            store_strip(rs, oks);
+            for (int t = 1; t < kAhead; ++t) load_b(rb[t], t, c0);
+            if (c0 == 0) {
+                int up;   // which rows of the tile are image pixels (the others get the zero border)
+                const int q = m0 + threadIdx.x;
+                if (threadIdx.x < BM) row_flag[threadIdx.x] = q < p.Pp && interior(p, q, &up) ? 1 : 0;
+            }
+            store_b(0, rb[0]);
+            store_strip(rs);
         }
         __syncthreads();
 #pragma unroll
         for (int tap = 0; tap < 9; ++tap) {
-            if (tap + kAhead < 9) okb[tap % kAhead] = load_b(rb[tap % kAhead], tap + kAhead, c0);   // its slice is in LDS already
+            if (tap + kAhead < 9) load_b(rb[tap % kAhead], tap + kAhead, c0);   // its slice is in LDS already
+            if (tap == kMaskTap) {   // in every chunk: a branch here would make the waits on the kernel slices wait for these too
+                if constexpr (MODE == 1) load_mask(); else load_bias();
+            }
             const int dy = tap / 3 - 1, dx = tap % 3 - 1;
             const int shift = (MODE == 0 ? 1 : -1) * (dy * p.Wp + dx);
             const uint16_t* a_base = strip + (p.halo + shift) * SP;
@@ -232,102 +286,83 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
                 mfmas(s & 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (tap + 1 < 9) TB::store(lds_b((tap + 1) & 1), rb[(tap + 1) % kAhead], okb[(tap + 1) % kAhead]);
+            if (tap + 1 < 9) store_b((tap + 1) & 1, rb[(tap + 1) % kAhead]);
             __syncthreads();
         }
     }
 
+    if (kMaskTap >= 9) {
+        if constexpr (MODE == 1) load_mask(); else load_bias();
+    }
     // Epilogue: the tile goes through LDS (the strip's place) so that every lane then moves 16-byte vectors.
     if constexpr (OUT_F32) {
-        // convolution + bias only (what follows it is another kernel's), staged in two passes of 128 rows.  Border rows
-        // are written as computed; their consumer skips them.
-        constexpr int FP = kCB + 8, HR = BM / 2;
-        constexpr int kVecPerRow = kCB / 4, kPer = HR * kVecPerRow / kThreads;
-        float* stage = (float*)lds_all;
-        float* OUT = (float*)p.out + (int64_t)group * p.s_out;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            if (h) __syncthreads();                  // the first half has been read
-            if (wm0 / HR == h) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int g4 = 0; g4 < 4; ++g4) {
-                            const f4 bq = *(const f4*)(bias_lds + 32 * j + 8 * g4 + 4 * half);
-                            const f4 o = {acc[i][j][4 * g4] + bq[0], acc[i][j][4 * g4 + 1] + bq[1], acc[i][j][4 * g4 + 2] + bq[2],
-                                          acc[i][j][4 * g4 + 3] + bq[3]};
-                            *(f4*)(stage + (wm0 % HR + 32 * i + lane32) * FP + 32 * j + 8 * g4 + 4 * half) = o;
-                        }
-            }
-            __syncthreads();
-            f4 val[kPer];
-#pragma unroll
-            for (int t = 0; t < kPer; ++t) {
-                const int v = threadIdx.x + t * kThreads;
-                val[t] = *(const f4*)(stage + (v / kVecPerRow) * FP + (v % kVecPerRow) * 4);
-            }
-#pragma unroll
-            for (int t = 0; t < kPer; ++t) {
-                const int v = threadIdx.x + t * kThreads;
-                const int q = m0 + HR * h + v / kVecPerRow;
-                if (q < p.Pp) *(f4*)(OUT + (int64_t)q * C + n0 + (v % kVecPerRow) * 4) = val[t];
-            }
-        }
-    } else {
-        constexpr int kVecPerRow = kCB / 8, kPer = BM * kVecPerRow / kThreads;
-        uint16_t* OUT = (uint16_t*)p.out + (int64_t)group * p.s_out;
-        const uint16_t* Mk = MODE == 1 && p.mask ? p.mask + (int64_t)group * p.s_mask : nullptr;
-        // the activations whose sign gates the delta are requested before the tile is staged
-        u4 mk[kPer];
-        if (MODE == 1) {
-#pragma unroll
-            for (int t = 0; t < kPer; ++t) {
-                const int v = threadIdx.x + t * kThreads;
-                const int q = m0 + v / kVecPerRow;
-                mk[t] = u4{~0u, ~0u, ~0u, ~0u};
-                if (Mk && q < p.Pp) mk[t] = *(const u4*)(Mk + (int64_t)q * C + n0 + (v % kVecPerRow) * 8);
-            }
-        }
-        uint16_t* stage = lds_all;
+        // convolution + bias only (what follows it is another kernel's).  Border rows are written as computed; their
+        // consumer skips them.  Every wavefront stages its own BM / 4 rows and moves them itself: the LDS operations of
+        // one wavefront complete in order, so no workgroup barrier is needed after the one that ended the last tap.
+        constexpr int FP = kStagePitchF32, WR = BM / 4;
+        constexpr int kVecPerRow = kCB / 4, kPer = WR * kVecPerRow / 64, kBatch = 8;
+        float* stage = (float*)lds_all + wave * WR * FP;
+        const rsrc_t out_rs = make_rsrc((const float*)p.out + (int64_t)group * p.s_out, (unsigned)p.Pp * 2u * row_bytes);
+        const unsigned out_off = (unsigned)(m0 + wm0 + lane / kVecPerRow) * 2u * row_bytes + 4u * (unsigned)n0 + (lane % kVecPerRow) * 16u;
+        const unsigned out_step = (64 / kVecPerRow) * 2u * row_bytes;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
-                    const f4 bq = *(const f4*)(bias_lds + 32 * j + 8 * g4 + 4 * half);
+                    const f4 o = {acc[i][j][4 * g4] + bq[j][g4][0], acc[i][j][4 * g4 + 1] + bq[j][g4][1], acc[i][j][4 * g4 + 2] + bq[j][g4][2],
+                                  acc[i][j][4 * g4 + 3] + bq[j][g4][3]};
+                    *(f4*)(stage + (32 * i + lane32) * FP + 32 * j + 8 * g4 + 4 * half) = o;
+                }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int t0 = 0; t0 < kPer; t0 += kBatch) {
+            u4 val[kBatch];
+#pragma unroll
+            for (int t = 0; t < kBatch; ++t) {
+                const int v = lane + (t0 + t) * 64;
+                val[t] = *(const u4*)(stage + (v / kVecPerRow) * FP + (v % kVecPerRow) * 4);
+            }
+#pragma unroll
+            for (int t = 0; t < kBatch; ++t) buf_store(val[t], out_rs, out_off + (t0 + t) * out_step);   // rows past the tensor are dropped
+        }
+    } else {
+        // wavefront-local like the fp32 epilogue: a wavefront stages and moves its own BM / 4 rows
+        const rsrc_t out_rs = make_rsrc((const uint16_t*)p.out + (int64_t)group * p.s_out, (unsigned)p.Pp * row_bytes);
+        uint16_t* stage = lds_all + wm0 * SP;
+        const float floor_v = p.relu ? 0.0f : -__builtin_huge_valf();   // max(., 0) or nothing
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
                     float v[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         v[e] = acc[i][j][4 * g4 + e];
-                        if (MODE == 0) {
-                            v[e] += bq[e];
-                            if (p.relu) v[e] = fmaxf(v[e], 0.0f);
-                        }
+                        if constexpr (MODE == 0) v[e] = fmaxf(v[e] + bq[j][g4][e], floor_v);
                     }
                     u2 o;   // round to nearest even (v_cvt_pk_bf16_f32)
                     o.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{v[0], v[1]}, bf16x2));
                     o.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{v[2], v[3]}, bf16x2));
-                    *(u2*)(stage + (wm0 + 32 * i + lane32) * SP + 32 * j + 8 * g4 + 4 * half) = o;
+                    *(u2*)(stage + (32 * i + lane32) * SP + 32 * j + 8 * g4 + 4 * half) = o;
                 }
-        __syncthreads();
-        u4 val[kPer];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        u4 val[kPerB];
 #pragma unroll
-        for (int t = 0; t < kPer; ++t) {
-            const int v = threadIdx.x + t * kThreads;
-            val[t] = *(const u4*)(stage + (v / kVecPerRow) * SP + (v % kVecPerRow) * 8);
+        for (int t = 0; t < kPerB; ++t) {
+            const int v = lane + t * 64;
+            val[t] = *(const u4*)(stage + (v / kVecB) * SP + (v % kVecB) * 8);
         }
 #pragma unroll
-        for (int t = 0; t < kPer; ++t) {
-            const int v = threadIdx.x + t * kThreads;
-            const int rl = v / kVecPerRow;
-            const int q = m0 + rl;
-            if (q >= p.Pp) continue;
+        for (int t = 0; t < kPerB; ++t) {
             u4 o = val[t];
             if (MODE == 0) {
-                if (!row_flag[rl]) o = u4{0u, 0u, 0u, 0u};   // the zero border the next layer relies on
+                if (!row_flag[wm0 + (lane + t * 64) / kVecB]) o = u4{0u, 0u, 0u, 0u};   // the zero border the next layer relies on
             } else if (Mk) {
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {   // a bf16 is positive iff its bits are in [0x0001, 0x7FFF]
@@ -336,7 +371,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
                     o[w] &= keep;
                 }
             }
-            *(u4*)(OUT + (int64_t)q * C + n0 + (v % kVecPerRow) * 8) = o;
+            buf_store(o, out_rs, own_off + t * step8);   // rows past the tensor are dropped
         }
     }
 }
@@ -379,43 +414,43 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
     const bool col_sums = ci0 == 0;   // bias gradient: column lane of the delta, rows shared out over the four wavefronts
     float col_acc = 0.0f;
 
+    // Buffer addressing as in the forward kernel: lane t of the workgroup owns the 16-byte vector t % 8 of row t / 8 of a
+    // [rows][C] tensor, its further vectors lie 32 rows below.  Input rows outside the tensor read as zeros, and so do the
+    // delta's rows from the end of this workgroup's pixel range on (its descriptor ends there), which removes the pixels
+    // past the range from the sums.
+    static_assert(TD::kLineStep == 32 && TD::kPerThread == 2, "a lane's vectors are 32 rows apart in the strip and in the delta tile");
+    const unsigned row_bytes = 2u * (unsigned)C;
+    const unsigned lane_off = (threadIdx.x / 8) * row_bytes + (threadIdx.x % 8) * 16u;
+    const unsigned step32 = 32u * row_bytes;
+    const rsrc_t in_rs = make_rsrc(IN, (unsigned)p.Pp * row_bytes);
+    const rsrc_t do_rs = make_rsrc(DO, (unsigned)hi * row_bytes);
     const int nvec = strip_rows * (kCB / 8);
-    auto load_strip = [&](u4 (&r)[NV], int k0) -> unsigned {
-        unsigned okmask = 0;
+    auto load_slice = [&](u4 (&r)[NV], u4 (&d)[TD::kPerThread], int k0) {
+        const unsigned first = (unsigned)(k0 - p.halo) * row_bytes + lane_off;
 #pragma unroll
-        for (int t = 0; t < NV; ++t) {
-            const int v = threadIdx.x + t * kThreads;
-            const int q = k0 - p.halo + v / (kCB / 8);
-            const bool ok = v < nvec && q >= 0 && q < p.Pp;
-            r[t] = *(const u4*)(IN + (ok ? (int64_t)q * C + ci0 + (v % (kCB / 8)) * 8 : 0));
-            okmask |= ok ? (1u << t) : 0u;
-        }
-        return okmask;
+        for (int t = 0; t < NV; ++t) r[t] = buf_load(in_rs, first + t * step32, 2u * ci0);
+        const unsigned dfirst = (unsigned)k0 * row_bytes + lane_off;
+#pragma unroll
+        for (int t = 0; t < TD::kPerThread; ++t) d[t] = buf_load(do_rs, dfirst + t * step32, 2u * co0);
     };
-    auto store_strip = [&](uint16_t* dst, const u4 (&r)[NV], unsigned okmask) {
+    auto store_slice = [&](int buf, const u4 (&r)[NV], const u4 (&d)[TD::kPerThread]) {
+        uint16_t* dst = lds_s(buf) + (threadIdx.x / 8) * RP + (threadIdx.x % 8) * 8;
 #pragma unroll
-        for (int t = 0; t < NV; ++t) {
-            const int v = threadIdx.x + t * kThreads;
-            if (v < nvec) {
-                const u4 zero = {0u, 0u, 0u, 0u};
-                *(u4*)(dst + (v / (kCB / 8)) * RP + (v % (kCB / 8)) * 8) = (okmask >> t) & 1u ? r[t] : zero;
-            }
-        }
+        for (int t = 0; t < NV; ++t)
+            if ((int)threadIdx.x + t * kThreads < nvec) *(u4*)(dst + t * 32 * RP) = r[t];   // the strip ends inside one of them
+        uint16_t* dd = TD::lane_lds(lds_d(buf));
+#pragma unroll
+        for (int t = 0; t < TD::kPerThread; ++t) *(u4*)(dd + t * TD::kLdsLineStep) = d[t];
     };
 
     u4 rs[NV], rd[TD::kPerThread];
-    unsigned oks = load_strip(rs, lo);
-    unsigned okd = TD::load(rd, DO, C, co0, lo, C, hi);
-    store_strip(lds_s(0), rs, oks);
-    TD::store(lds_d(0), rd, okd);
+    load_slice(rs, rd, lo);
+    store_slice(0, rs, rd);
     __syncthreads();
     const int nslices = (hi - lo + kDwBK - 1) / kDwBK;
     for (int t = 0; t < nslices; ++t) {
         const int cur = t & 1;
-        if (t + 1 < nslices) {
-            oks = load_strip(rs, lo + (t + 1) * kDwBK);
-            okd = TD::load(rd, DO, C, co0, lo + (t + 1) * kDwBK, C, hi);
-        }
+        if (t + 1 < nslices) load_slice(rs, rd, lo + (t + 1) * kDwBK);
         const uint16_t* S = lds_s(cur) + p.halo * RP;
         const uint16_t* D = lds_d(cur);
         // 4 k-steps x 9 taps = 12 groups of one kernel row: the fragments of group g + 1 are requested before the MFMAs
@@ -443,10 +478,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
             for (int k = 0; k < kDwBK / 4; ++k)
                 col_acc += __uint_as_float((unsigned)D[(wave * (kDwBK / 4) + k) * RP + lane] << 16);
         }
-        if (t + 1 < nslices) {
-            store_strip(lds_s(cur ^ 1), rs, oks);
-            TD::store(lds_d(cur ^ 1), rd, okd);
-        }
+        if (t + 1 < nslices) store_slice(cur ^ 1, rs, rd);
         __syncthreads();
     }
 
@@ -590,7 +622,8 @@ bool shape_ok(const ConvBArgs& a) {
         a.C > 1024)
         return false;
     const int64_t Pp = (int64_t)a.B * (a.H + 2) * (a.W + 2);
-    return Pp * a.C < ((int64_t)1 << 31) - ((int64_t)(kBM + 2 * (a.W + 3)) * a.C);   // 32-bit pixel indices inside one group
+    // 32-bit byte offsets inside one group's bf16 tensor, with room for the rows a tile's strip reaches past either end
+    return Pp * a.C < ((int64_t)1 << 31) - (int64_t)1024 * a.C;
 }
 
 FastDiv make_div(unsigned d) {
@@ -614,6 +647,7 @@ template <int MODE>
 hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     if (!shape_ok(a) || !a.in || !a.w || !a.out || !aligned16(a.in) || !aligned16(a.w) || !aligned16(a.out)) return hipErrorInvalidValue;
     if (a.s_in % 8 || a.s_w % 8 || a.s_out % 8 || (a.mask && (!aligned16(a.mask) || a.s_mask % 8))) return hipErrorInvalidValue;
+    if (MODE == 0 && a.bias && (!aligned16(a.bias) || a.s_bias % 4)) return hipErrorInvalidValue;   // read as 16-byte vectors
     if (MODE == 1 && a.out_f32) return hipErrorInvalidValue;   // the delta is always an operand of the next product
     if (a.out_f32 && a.relu) return hipErrorInvalidValue;      // the fp32 output is the bare convolution + bias
     ConvBDev p = {};
@@ -625,19 +659,24 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     constexpr int BM = kBM;   // 128 (three workgroups per compute unit, 134 registers) measured 8 - 19 % slower: halo 1.55x
     p.tiles_m = (p.Pp + BM - 1) / BM;
     p.tiles_n = a.C / kCB;
+    p.div_pg = make_div((unsigned)(p.tiles_m * p.tiles_n));
+    p.div_tn = make_div((unsigned)p.tiles_n);
     const int64_t total = (int64_t)a.groups * p.tiles_m * p.tiles_n;
     if (total > (1 << 30)) return hipErrorInvalidValue;
+    if (a.out_f32 && (int64_t)p.Pp * a.C >= ((int64_t)1 << 30)) return hipErrorInvalidValue;   // 32-bit byte offsets in the fp32 output
     p.total_tiles = (int)total;
     p.chunk = (int)((total + kXcds - 1) / kXcds);
     const int strip_rows = BM + 2 * p.halo;
     const size_t b_elems = MODE == 0 ? TileRC<kCB, kCB>::kElems : TileKC<kCB, kCB>::kElems;
-    const size_t lds = ((size_t)strip_rows * (kCB + 8) + 2 * b_elems) * sizeof(uint16_t) + kCB * sizeof(float) + BM;   // strip, kernel slices, bias, row flags
     constexpr int NV0 = ((BM + 2 * 35) * (kCB / 8) + kThreads - 1) / kThreads;                        // widths up to 32
     constexpr int NV1 = ((BM + 2 * (kConvBf16MaxWidth + 3)) * (kCB / 8) + kThreads - 1) / kThreads;    // any width
     const int nv = (strip_rows * (kCB / 8) + kThreads - 1) / kThreads;
-    // the output tile is staged in the strip's place: BM x 72 bf16, or BM / 2 x 72 floats per pass
-    static_assert((size_t)(BM + 2 * 4) * (kCB + 8) * 2 >= (size_t)(BM / 2) * (kCB + 8) * 4, "staging area");
-    if (lds > 160 * 1024 || nv > NV1) return hipErrorInvalidValue;
+    if (nv > NV1) return hipErrorInvalidValue;
+    const int lds_rows = 32 * (nv <= NV0 ? NV0 : NV1);   // the kernel's strip holds all the vectors its lanes move
+    // the bf16 output tile is staged in the strip's place (BM x 72 bf16); the fp32 one is sized by conv_main_elems
+    const size_t main_elems = a.out_f32 ? conv_main_elems<BM, true>(lds_rows, (int)b_elems) : conv_main_elems<BM, false>(lds_rows, (int)b_elems);
+    const size_t lds = main_elems * sizeof(uint16_t) + BM;   // strip and kernel slices (or the fp32 staging), row flags
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
     void (*kern)(ConvBDev);
     if (nv <= NV0)
         kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV0, BM> : conv3x3_bf16_kernel<0, false, NV0, BM>)
