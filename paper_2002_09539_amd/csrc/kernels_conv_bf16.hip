@@ -74,6 +74,10 @@ struct ConvBDev {
     const float* bias;       // FWD
     const uint16_t* mask;    // DX: padded bf16 activations whose sign gates the result
     float* partial;          // DW
+    const float* xres;       // FWD with the fused tail: the shortcut, fp32 [B H W][C]
+    uint8_t* sign;           // FWD with the fused tail: [Pp][C / 4] sign bytes
+    float* pool_part;        // FWD with the fused tail: [groups][tiles_m * 4 wavefronts][2][C] partial sums of the pooling
+    int64_t s_x, s_sign;
     int64_t s_in, s_w, s_dout, s_out, s_bias, s_mask;
     int groups, B, H, W, C, Hp, Wp, Pp, halo;
     int relu;
@@ -126,14 +130,18 @@ __device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bi
 // LDS of the forward / delta kernel, in bf16 elements: the strip and two kernel slices -- or, if larger, the fp32 output
 // staging of the four wavefronts (BM / 4 rows of 64 + 4 floats each), which takes their place after the last tap.
 constexpr int kStagePitchF32 = kCB + 4;
-template <int BM, bool OUT_F32>
+enum { kOutBf16 = 0, kOutF32 = 1, kOutTail = 2 };   // what the forward kernel's epilogue produces
+template <int BM, int OUT>
 __host__ __device__ constexpr int conv_main_elems(int strip_rows, int slice_elems) {
     const int work = strip_rows * (kCB + 8) + 2 * slice_elems;
-    const int stage = OUT_F32 ? BM * kStagePitchF32 * 2 : 0;
+    const int stage = OUT != kOutBf16 ? BM * kStagePitchF32 * 2 : 0;
     return work > stage ? work : stage;
 }
 
-template <int MODE, bool OUT_F32, int NV, int BM>   // NV: strip vectors per lane (upper bound of (BM + 2 halo) * 8 / 256); BM: pixels per tile
+// NV: strip vectors per lane (upper bound of (BM + 2 halo) * 8 / 256); BM: pixels per tile.  OUT: bf16 activations /
+// deltas; the bare convolution + bias in fp32; or the residual block's tail fused into the epilogue (shortcut, ReLU,
+// sign bytes and partial sums of the global average pooling -- the second convolution's output is then never stored).
+template <int MODE, int OUT, int NV, int BM>
 __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kernel(ConvBDev p) {
     using TB = typename std::conditional<MODE == 0, TileRC<kCB, kCB>, TileKC<kCB, kCB>>::type;   // FWD w[k = ci][n = co]; DX w[n = ci][k = co]
     constexpr int SP = kCB + 8;                  // strip pitch (bf16 elements): 144 bytes, conflict-free 16-byte reads
@@ -145,7 +153,8 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
     uint16_t* lds_b0 = lds_all + kStripRows * SP;
     auto lds_b = [&](int buf) { return lds_b0 + buf * TB::kElems; };
     // the fp32 output is staged over the strip and the kernel slices together (conv_main_elems)
-    uint8_t* row_flag = (uint8_t*)(lds_all + conv_main_elems<BM, OUT_F32>(kStripRows, TB::kElems));   // [BM] 1: image pixel, 0: border
+    uint8_t* row_flag = (uint8_t*)(lds_all + conv_main_elems<BM, OUT>(kStripRows, TB::kElems));   // [BM] 1: image pixel, 0: border
+    int* row_up = (int*)row_flag;   // fused tail instead: [BM] the pixel's index in the unpadded [B H W] order, -1 for the border
 
     const int tile = xcd_tile(p.chunk, p.total_tiles);
     if (tile < 0) return;
@@ -262,7 +271,10 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
             if (c0 == 0) {
                 int up;   // which rows of the tile are image pixels (the others get the zero border)
                 const int q = m0 + threadIdx.x;
-                if (threadIdx.x < BM) row_flag[threadIdx.x] = q < p.Pp && interior(p, q, &up) ? 1 : 0;
+                const bool img = q < p.Pp && interior(p, q, &up);
+                if (threadIdx.x < BM) {
+                    if constexpr (OUT == kOutTail) row_up[threadIdx.x] = img ? up : -1; else row_flag[threadIdx.x] = img ? 1 : 0;
+                }
             }
             store_b(0, rb[0]);
             store_strip(rs);
@@ -295,7 +307,75 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
         if constexpr (MODE == 1) load_mask(); else load_bias();
     }
     // Epilogue: the tile goes through LDS (the strip's place) so that every lane then moves 16-byte vectors.
-    if constexpr (OUT_F32) {
+    if constexpr (OUT == kOutTail) {
+        // a2 = relu(convolution + bias + shortcut) on the image pixels: its sign bytes and, per wavefront (64 consecutive
+        // padded pixels, which touch at most two samples because a padded image has at least 64), the channel sums of its
+        // rows in the first and in the second of those samples.  A later pass adds the wavefronts' sums per sample in
+        // wavefront order.  Staging as for the fp32 output; lane l then owns the channel quad l % 16 of rows l / 16 + 4 t.
+        constexpr int FP = kStagePitchF32, WR = BM / 4;
+        constexpr int kVecPerRow = kCB / 4, kPer = WR * kVecPerRow / 64, kBatch = 8;
+        static_assert(WR == 64, "the partial sums are kept per 64 rows");
+        float* stage = (float*)lds_all + wave * WR * FP;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f4 o = {acc[i][j][4 * g4] + bq[j][g4][0], acc[i][j][4 * g4 + 1] + bq[j][g4][1], acc[i][j][4 * g4 + 2] + bq[j][g4][2],
+                                  acc[i][j][4 * g4 + 3] + bq[j][g4][3]};
+                    *(f4*)(stage + (32 * i + lane32) * FP + 32 * j + 8 * g4 + 4 * half) = o;
+                }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int q0 = m0 + wm0;                                    // the wavefront's first padded pixel
+        const int per = p.Hp * p.Wp;
+        const int next_sample = ((int)fast_div((unsigned)q0, p.div_per) + 1) * per;   // first pixel of the second sample
+        const rsrc_t x_rs = make_rsrc(p.xres + (int64_t)group * p.s_x, (unsigned)(p.B * p.H * p.W) * 2u * row_bytes);
+        const rsrc_t sg_rs = make_rsrc(p.sign + (int64_t)group * p.s_sign, (unsigned)p.Pp * (unsigned)(C / 4));
+        const int r0 = lane / kVecPerRow, cq = lane % kVecPerRow;
+        f4 sum0 = {0.f, 0.f, 0.f, 0.f}, sum1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t0 = 0; t0 < kPer; t0 += kBatch) {
+            f4 yv[kBatch], xv[kBatch];
+            int up[kBatch];
+#pragma unroll
+            for (int t = 0; t < kBatch; ++t) up[t] = row_up[wm0 + r0 + 4 * (t0 + t)];
+#pragma unroll
+            for (int t = 0; t < kBatch; ++t)   // border rows: -1 wraps to an offset beyond the tensor, zeros come back
+                xv[t] = __builtin_bit_cast(f4, buf_load(x_rs, (unsigned)up[t] * 2u * row_bytes + 4u * n0 + cq * 16u, 0u));
+#pragma unroll
+            for (int t = 0; t < kBatch; ++t) yv[t] = *(const f4*)(stage + (r0 + 4 * (t0 + t)) * FP + cq * 4);
+#pragma unroll
+            for (int t = 0; t < kBatch; ++t) {
+                const int q = q0 + r0 + 4 * (t0 + t);
+                const bool img = up[t] >= 0;
+                unsigned bits = 0;
+                f4 a;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    a[e] = img ? fmaxf(yv[t][e] + xv[t][e], 0.0f) : 0.0f;
+                    bits |= a[e] > 0.0f ? (1u << e) : 0u;
+                }
+                if (q < next_sample) sum0 = sum0 + a; else sum1 = sum1 + a;
+                __builtin_amdgcn_raw_buffer_store_b8((unsigned char)bits, sg_rs, (int)((unsigned)q * (unsigned)(C / 4) + n0 / 4 + cq), 0, 0);   // rows past the tensor are dropped
+            }
+        }
+        // the four lanes of a channel quad, in lane order, through the staging area (all its reads are done)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        f4* red = (f4*)stage;
+        red[lane] = sum0;
+        red[64 + lane] = sum1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < 2 * kVecPerRow) {   // lanes 0 .. 15: first sample, 16 .. 31: second
+            const f4* r = red + 64 * (lane / kVecPerRow) + lane % kVecPerRow;
+            const f4 o = ((r[0] + r[16]) + r[32]) + r[48];
+            float* PP = p.pool_part + ((((int64_t)group * p.tiles_m + tm) * 4 + wave) * 2 + lane / kVecPerRow) * C + n0;
+            *(f4*)(PP + 4 * (lane % kVecPerRow)) = o;
+        }
+    } else if constexpr (OUT == kOutF32) {
         // convolution + bias only (what follows it is another kernel's).  Border rows are written as computed; their
         // consumer skips them.  Every wavefront stages its own BM / 4 rows and moves them itself: the LDS operations of
         // one wavefront complete in order, so no workgroup barrier is needed after the one that ended the last tap.
@@ -411,7 +491,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
     for (int t = 0; t < 9; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-    const bool col_sums = ci0 == 0;   // bias gradient: column lane of the delta, rows shared out over the four wavefronts
+    // bias gradient: column sums of the delta, taken from the delta fragments (a lane holds 8 pixels of one channel); the
+    // two wavefronts that read the same fragments share the k-steps
+    const bool col_sums = ci0 == 0;
     float col_acc = 0.0f;
 
     // Buffer addressing as in the forward kernel: lane t of the workgroup owns the 16-byte vector t % 8 of row t / 8 of a
@@ -471,12 +553,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
 #pragma unroll
             for (int kw = 0; kw < 3; ++kw)
                 acc[3 * (g % 3) + kw] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fi[g & 1][kw], fd[(g / 3) & 1], acc[3 * (g % 3) + kw], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (col_sums) {   // every wavefront sums a quarter of the slice's rows: the barrier waits for the slowest of them
+            if (g % 3 == 0 && col_sums && (g / 3) / 2 == wi) {
+                const u4 w = __builtin_bit_cast(u4, fd[(g / 3) & 1]);
 #pragma unroll
-            for (int k = 0; k < kDwBK / 4; ++k)
-                col_acc += __uint_as_float((unsigned)D[(wave * (kDwBK / 4) + k) * RP + lane] << 16);
+                for (int e = 0; e < 4; ++e) col_acc += __uint_as_float(w[e] << 16) + __uint_as_float(w[e] & 0xFFFF0000u);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (t + 1 < nslices) store_slice(cur ^ 1, rs, rd);
         __syncthreads();
@@ -492,11 +574,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
             PART[((int64_t)tap * C + ci) * C + co0 + 32 * wj + lane32] = acc[tap][r];
         }
     }
-    if (col_sums) {   // the four wavefronts' shares, added in wavefront order
+    if (col_sums) {   // channel c: wavefronts (wi, wj = c / 32), both halves of their lanes, added in a fixed order
         float* red = (float*)lds_all;
         red[threadIdx.x] = col_acc;
         __syncthreads();
-        if (threadIdx.x < kCB) PART[n_w + co0 + threadIdx.x] = ((red[threadIdx.x] + red[64 + threadIdx.x]) + red[128 + threadIdx.x]) + red[192 + threadIdx.x];
+        if (threadIdx.x < kCB) {
+            const float* r0 = red + 64 * (threadIdx.x / 32) + threadIdx.x % 32;   // wi = 0; wi = 1 is 128 lanes on
+            PART[n_w + co0 + threadIdx.x] = ((r0[0] + r0[32]) + r0[128]) + r0[160];
+        }
     }
 }
 
@@ -615,6 +700,28 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_bf16_kernel(const float* __
     *((u4*)(dz + (int64_t)g * s_dz) + v) = w;
 }
 
+// pooled[g][n][c] = inv * sum of the wavefront sums that the fused tail left for sample n: wavefront w covers the padded
+// pixels 64 w .. 64 w + 63, its first sample is floor(64 w / per), and its two slots are that sample and the next.
+// Added in wavefront order; one lane per (sample, channel quad).
+__global__ __launch_bounds__(kThreads) void pool_finish_kernel(const float* __restrict__ part, int64_t s_part, float* pooled,
+                                                               int64_t s_p, int B, int per, int C, float inv) {
+    const int v = blockIdx.x * kThreads + threadIdx.x;
+    const int c4n = C / 4;
+    if (v >= B * c4n) return;
+    const int n = v / c4n, c4 = v % c4n, g = blockIdx.y;
+    const f4* P = (const f4*)(part + (int64_t)g * s_part) + c4;
+    const int w_lo = (n * per) / 64, w_hi = ((n + 1) * per - 1) / 64;
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int w = w_lo; w <= w_hi; ++w) {
+        const int slot = n - (64 * w) / per;   // 0 or 1
+        acc = acc + P[(int64_t)(2 * w + slot) * c4n];
+    }
+    f4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = acc[e] * inv;
+    *(f4*)(pooled + (int64_t)g * s_p + (int64_t)n * C + 4 * c4) = o;
+}
+
 bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 bool shape_ok(const ConvBArgs& a) {
@@ -645,8 +752,15 @@ void fill(ConvBDev* p, const ConvBArgs& a) {
 
 template <int MODE>
 hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
-    if (!shape_ok(a) || !a.in || !a.w || !a.out || !aligned16(a.in) || !aligned16(a.w) || !aligned16(a.out)) return hipErrorInvalidValue;
-    if (a.s_in % 8 || a.s_w % 8 || a.s_out % 8 || (a.mask && (!aligned16(a.mask) || a.s_mask % 8))) return hipErrorInvalidValue;
+    const bool tail = MODE == 0 && a.tail;
+    if (!shape_ok(a) || !a.in || !a.w || !aligned16(a.in) || !aligned16(a.w)) return hipErrorInvalidValue;
+    if (!tail && (!a.out || !aligned16(a.out) || a.s_out % 8)) return hipErrorInvalidValue;
+    if (a.s_in % 8 || a.s_w % 8 || (a.mask && (!aligned16(a.mask) || a.s_mask % 8))) return hipErrorInvalidValue;
+    if (tail) {   // 16-byte vectors of the shortcut, 32-bit byte offsets in it, at most two samples per 64 padded pixels
+        if (a.out_f32 || a.relu || !a.xres || !a.sign || !a.pool_part || !aligned16(a.xres) || !aligned16(a.pool_part) || a.s_x % 4 ||
+            (a.H + 2) * (a.W + 2) < 64 || (int64_t)a.B * a.H * a.W * a.C >= ((int64_t)1 << 30) - 1024)
+            return hipErrorInvalidValue;
+    }
     if (MODE == 0 && a.bias && (!aligned16(a.bias) || a.s_bias % 4)) return hipErrorInvalidValue;   // read as 16-byte vectors
     if (MODE == 1 && a.out_f32) return hipErrorInvalidValue;   // the delta is always an operand of the next product
     if (a.out_f32 && a.relu) return hipErrorInvalidValue;      // the fp32 output is the bare convolution + bias
@@ -656,6 +770,7 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     p.bias = MODE == 0 ? a.bias : nullptr;
     p.mask = MODE == 1 ? (const uint16_t*)a.mask : nullptr;
     p.s_in = a.s_in; p.s_w = a.s_w; p.s_out = a.s_out; p.s_bias = a.s_bias; p.s_mask = a.s_mask;
+    if (tail) { p.xres = a.xres; p.s_x = a.s_x; p.sign = a.sign; p.s_sign = a.s_sign; p.pool_part = a.pool_part; }
     constexpr int BM = kBM;   // 128 (three workgroups per compute unit, 134 registers) measured 8 - 19 % slower: halo 1.55x
     p.tiles_m = (p.Pp + BM - 1) / BM;
     p.tiles_n = a.C / kCB;
@@ -674,16 +789,21 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     if (nv > NV1) return hipErrorInvalidValue;
     const int lds_rows = 32 * (nv <= NV0 ? NV0 : NV1);   // the kernel's strip holds all the vectors its lanes move
     // the bf16 output tile is staged in the strip's place (BM x 72 bf16); the fp32 one is sized by conv_main_elems
-    const size_t main_elems = a.out_f32 ? conv_main_elems<BM, true>(lds_rows, (int)b_elems) : conv_main_elems<BM, false>(lds_rows, (int)b_elems);
-    const size_t lds = main_elems * sizeof(uint16_t) + BM;   // strip and kernel slices (or the fp32 staging), row flags
+    const int out = tail ? kOutTail : a.out_f32 ? kOutF32 : kOutBf16;
+    const size_t main_elems = out != kOutBf16 ? conv_main_elems<BM, kOutF32>(lds_rows, (int)b_elems) : conv_main_elems<BM, kOutBf16>(lds_rows, (int)b_elems);
+    const size_t lds = main_elems * sizeof(uint16_t) + (tail ? BM * sizeof(int) : BM);   // strip and kernel slices (or the fp32 staging), row flags / indices
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     void (*kern)(ConvBDev);
     if (nv <= NV0)
-        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV0, BM> : conv3x3_bf16_kernel<0, false, NV0, BM>)
-                         : conv3x3_bf16_kernel<1, false, NV0, BM>;
+        kern = MODE == 1 ? conv3x3_bf16_kernel<1, kOutBf16, NV0, BM>
+               : out == kOutTail ? conv3x3_bf16_kernel<0, kOutTail, NV0, BM>
+               : out == kOutF32  ? conv3x3_bf16_kernel<0, kOutF32, NV0, BM>
+                                 : conv3x3_bf16_kernel<0, kOutBf16, NV0, BM>;
     else
-        kern = MODE == 0 ? (a.out_f32 ? conv3x3_bf16_kernel<0, true, NV1, BM> : conv3x3_bf16_kernel<0, false, NV1, BM>)
-                         : conv3x3_bf16_kernel<1, false, NV1, BM>;
+        kern = MODE == 1 ? conv3x3_bf16_kernel<1, kOutBf16, NV1, BM>
+               : out == kOutTail ? conv3x3_bf16_kernel<0, kOutTail, NV1, BM>
+               : out == kOutF32  ? conv3x3_bf16_kernel<0, kOutF32, NV1, BM>
+                                 : conv3x3_bf16_kernel<0, kOutBf16, NV1, BM>;
     if (lds > 64 * 1024) {
         hipError_t e = ensure_dynamic_lds((const void*)kern, 160 * 1024);
         if (e != hipSuccess) return e;
@@ -759,6 +879,22 @@ hipError_t launch_shortcut_relu_pool(const float* y, int64_t s_y, const float* X
         return hipErrorInvalidValue;
     shortcut_relu_pool_kernel<<<dim3((unsigned)B, (unsigned)groups), kThreads, 0, s>>>(
         y, s_y, X, s_x, pooled, s_p, sign, s_sign, H, W, C, make_div((unsigned)(W + 2)), 1.0f / (float)(H * W));
+    return hipGetLastError();
+}
+
+int64_t conv3x3_bf16_pool_part_floats(int B, int H, int W, int C) {
+    const int64_t Pp = (int64_t)B * (H + 2) * (W + 2);
+    return ((Pp + kBM - 1) / kBM) * 4 * 2 * C;   // per group
+}
+
+hipError_t launch_pool_finish(const float* part, float* pooled, int64_t s_p, int groups, int B, int H, int W, int C, hipStream_t s) {
+    if (!part || !pooled || groups < 1 || groups > 65535 || B < 1 || H < 1 || W < 1 || C < 4 || C % 4 || !aligned16(part) ||
+        !aligned16(pooled) || s_p % 4 || (H + 2) * (W + 2) < 64 || (int64_t)B * (H + 2) * (W + 2) >= ((int64_t)1 << 31) - 64)
+        return hipErrorInvalidValue;
+    const int64_t lanes = (int64_t)B * (C / 4);
+    if (lanes > 0x7FFFFFFF) return hipErrorInvalidValue;
+    pool_finish_kernel<<<dim3((unsigned)((lanes + kThreads - 1) / kThreads), (unsigned)groups), kThreads, 0, s>>>(
+        part, conv3x3_bf16_pool_part_floats(B, H, W, C), pooled, s_p, B, (H + 2) * (W + 2), C, 1.0f / (float)(H * W));
     return hipGetLastError();
 }
 

@@ -398,16 +398,30 @@ int conv_gradients_bf16(ols_ctx* c) {
         a.in = xb; a.s_in = act; a.w = shadow + wa; a.bias = xc + ba; a.out = a1; a.s_out = act; a.relu = 1;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
     }
-    {   // y = conv(a1; Wb) + bb, fp32
+    if (positions >= 64) {
+        // conv(a1; Wb) + bb with the block's tail in its epilogue: a2 = relu(. + X) is never stored -- its sign bytes and
+        // partial sums of the pooling are (the partial sums take the place the fp32 output has without the fusion)
         ConvBArgs a = base;
-        a.in = a1; a.s_in = act; a.w = shadow + wb; a.bias = xc + bb; a.out = y2; a.s_out = act; a.out_f32 = 1;
+        float* pool_part = y2;
+        a.in = a1; a.s_in = act; a.w = shadow + wb; a.bias = xc + bb; a.tail = 1;
+        a.xres = c->X; a.s_x = c->xs; a.sign = sign; a.s_sign = act / 4; a.pool_part = pool_part;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
+        if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
+                 return launch_pool_finish(pool_part, pooled, (int64_t)B * C, m, B, H, W, C, s);
+             })))
+            return rc;
+    } else {   // images too small for the fused tail's two-samples-per-wavefront bookkeeping
+        {   // y = conv(a1; Wb) + bb, fp32
+            ConvBArgs a = base;
+            a.in = a1; a.s_in = act; a.w = shadow + wb; a.bias = xc + bb; a.out = y2; a.s_out = act; a.out_f32 = 1;
+            if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
+        }
+        // a2 = relu(y + X), pooled = its mean over the positions, and the sign of a2 for the backward pass, in one pass
+        if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
+                 return launch_shortcut_relu_pool(y2, act, c->X, c->xs, pooled, (int64_t)B * C, sign, act / 4, m, B, H, W, C, s);
+             })))
+            return rc;
     }
-    // a2 = relu(y + X), pooled = its mean over the positions, and the sign of a2 for the backward pass, in one pass
-    if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
-             return launch_shortcut_relu_pool(y2, act, c->X, c->xs, pooled, (int64_t)B * C, sign, act / 4, m, B, H, W, C, s);
-         })))
-        return rc;
     HeadArgs ha = {};
     ha.h = pooled;
     ha.h_stride = (int64_t)B * C;

@@ -219,11 +219,23 @@ struct ConvBArgs {
     int64_t s_in, s_w, s_dout, s_out, s_bias, s_mask;   // group strides (elements of the tensor's own type)
     int groups, B, H, W, C;
     int relu;               // fwd with bf16 output: apply max(., 0)
+    // fwd with the residual block's tail fused in (tail != 0; out unused, no relu, padded images of at least 64 pixels):
+    // a2 = relu(convolution + bias + xres) is never stored -- sign[padded pixel][C / 4] gets one byte per four channels
+    // with bit e set iff a2 > 0 (border: 0), and pool_part (conv3x3_bf16_pool_part_floats(...) floats per group) the
+    // partial sums that launch_pool_finish turns into the mean over the positions.
+    int tail;
+    const float* xres;      // fp32 [B H W][C], not padded
+    uint8_t* sign;
+    float* pool_part;
+    int64_t s_x, s_sign;    // group strides
 };
 hipError_t launch_conv3x3_bf16_fwd(const ConvBArgs& a, hipStream_t s);
 hipError_t launch_conv3x3_bf16_dx(const ConvBArgs& a, hipStream_t s);
 hipError_t launch_conv3x3_bf16_dw(const ConvBArgs& a, hipStream_t s);
 int conv3x3_bf16_dw_splits(int groups, int B, int H, int W, int C);
+int64_t conv3x3_bf16_pool_part_floats(int B, int H, int W, int C);   // per group
+// pooled[g][sample][c] = mean over the positions of a2, from the partial sums of the forward kernel's fused tail
+hipError_t launch_pool_finish(const float* part, float* pooled, int64_t s_p, int groups, int B, int H, int W, int C, hipStream_t s);
 // fp32 [groups][B H W][C] -> bf16 [groups][B (H+2) (W+2)][C] with a zero border
 hipError_t launch_pad_cast_bf16(const float* src, int64_t s_src, uint16_t* dst, int64_t s_dst, int groups, int B, int H, int W,
                                 int C, hipStream_t s);
