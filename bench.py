@@ -129,10 +129,17 @@ def algorithmic_work(cfg, ld, fused_update=True):
             # kernels store with them is overhead, not work): 288 flop per byte for a bf16-in, bf16-out convolution,
             # just below the 312 flop per byte ridge, so min(matrix peak, AI x HBM peak) is reported beside the peak
             work["cast_bf16"] = ("hbm", 1.5 * act)                      # fp32 batch in, bf16 batch out
-            work["conv_fwd_bytes"] = (1.0 * act + 1.5 * act) / 2        # first: bf16 in, bf16 out; second: bf16 in, fp32 out
             work["conv_dx_bytes"] = 1.5 * act                           # bf16 delta in, bf16 mask in, bf16 delta out
             work["conv_dw_bytes"] = 1.0 * act                           # bf16 input and bf16 delta
-            work["pool"] = ("hbm", 2.0 * act + act / 16)                # shortcut + ReLU + pooling: conv output and shortcut in, sign bytes out
+            if (H + 2) * (W + 2) >= 64:
+                # the block's tail runs in the second convolution's epilogue: bf16 in, fp32 shortcut in, sign bytes out;
+                # what is left of the pooling is a pass over the wavefronts' partial sums (8 C floats per 256 padded pixels)
+                work["conv_fwd_bytes"] = (1.0 * act + (1.5 + 1.0 / 16) * act) / 2
+                tiles = -(-(cfg.batch * (H + 2) * (W + 2)) // 256)
+                work["pool"] = ("hbm", 4.0 * m * (tiles * 8 * C + cfg.batch * C))
+            else:
+                work["conv_fwd_bytes"] = (1.0 * act + 1.5 * act) / 2    # first: bf16 in, bf16 out; second: bf16 in, fp32 out
+                work["pool"] = ("hbm", 2.0 * act + act / 16)            # shortcut + ReLU + pooling: conv output and shortcut in, sign bytes out
             work["pool_bwd"] = ("hbm", 0.5 * act + act / 16)            # sign bytes in, bf16 delta out
         if cfg.batch_norm:
             # statistics read z, the normalisation reads z (+ the shortcut in the second layer) and writes the activation

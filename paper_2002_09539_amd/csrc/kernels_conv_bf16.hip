@@ -673,31 +673,48 @@ __global__ __launch_bounds__(kThreads) void shortcut_relu_pool_kernel(const floa
 }
 
 // dz[g][q][c] = bf16(dpool[g][sample][c] * scale) where the sign bit of (q, c) is set, else 0; dz bf16 padded
+constexpr int kPoolBwdFly = 4;   // 16-byte vectors per lane
 __global__ __launch_bounds__(kThreads) void pool_bwd_bf16_kernel(const float* __restrict__ dpool, int64_t s_dp,
                                                                  const uint8_t* __restrict__ sign, int64_t s_sign, uint16_t* dz,
-                                                                 int64_t s_dz, int64_t vecs, int positions, int C, float scale) {
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (v >= vecs) return;
+                                                                 int64_t s_dz, unsigned vecs, FastDiv div_c8, FastDiv div_pos,
+                                                                 int C, float scale) {
     const int g = blockIdx.y;
-    const int c8 = C / 8;
-    const int64_t q = v / c8;
-    const int cv = (int)(v % c8);
-    const int64_t sample = q / positions;
-    const unsigned bits = *(const uint16_t*)(sign + (int64_t)g * s_sign + 2 * v);   // two bytes: channels 8 cv .. 8 cv + 7
-    const f4* D = (const f4*)(dpool + (int64_t)g * s_dp + sample * C) + 2 * cv;
-    const f4 d0 = D[0], d1 = D[1];
-    float o[8];
+    const unsigned c8 = (unsigned)C / 8;
+    const uint8_t* SG = sign + (int64_t)g * s_sign;
+    const float* DP = dpool + (int64_t)g * s_dp;
+    u4* DZ = (u4*)(dz + (int64_t)g * s_dz);
+    unsigned bits[kPoolBwdFly];
+    f4 d0[kPoolBwdFly], d1[kPoolBwdFly];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        o[e] = (bits >> e) & 1u ? d0[e] * scale : 0.0f;
-        o[4 + e] = (bits >> (8 + e)) & 1u ? d1[e] * scale : 0.0f;
+    for (int t = 0; t < kPoolBwdFly; ++t) {   // all the loads of a lane's vectors before the first store
+        const unsigned v = (blockIdx.x * kPoolBwdFly + t) * kThreads + threadIdx.x;
+        if (v < vecs) {
+            const unsigned q = fast_div(v, div_c8);
+            const unsigned cv = v - q * c8;
+            const unsigned sample = fast_div(q, div_pos);
+            bits[t] = *(const uint16_t*)(SG + 2 * (int64_t)v);   // two bytes: channels 8 cv .. 8 cv + 7
+            const f4* D = (const f4*)(DP + (int64_t)sample * C) + 2 * cv;
+            d0[t] = D[0];
+            d1[t] = D[1];
+        }
     }
-    u4 w;
-    w.x = pack2(o[0], o[1]);
-    w.y = pack2(o[2], o[3]);
-    w.z = pack2(o[4], o[5]);
-    w.w = pack2(o[6], o[7]);
-    *((u4*)(dz + (int64_t)g * s_dz) + v) = w;
+#pragma unroll
+    for (int t = 0; t < kPoolBwdFly; ++t) {
+        const unsigned v = (blockIdx.x * kPoolBwdFly + t) * kThreads + threadIdx.x;
+        if (v >= vecs) continue;
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = (bits[t] >> e) & 1u ? d0[t][e] * scale : 0.0f;
+            o[4 + e] = (bits[t] >> (8 + e)) & 1u ? d1[t][e] * scale : 0.0f;
+        }
+        u4 w;   // round to nearest even (v_cvt_pk_bf16_f32)
+        w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{o[0], o[1]}, bf16x2));
+        w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{o[2], o[3]}, bf16x2));
+        w.z = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{o[4], o[5]}, bf16x2));
+        w.w = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{o[6], o[7]}, bf16x2));
+        DZ[v] = w;
+    }
 }
 
 // pooled[g][n][c] = inv * sum of the wavefront sums that the fused tail left for sample n: wavefront w covers the padded
@@ -904,10 +921,10 @@ hipError_t launch_pool_bwd_bf16(const float* dpool, int64_t s_dp, const uint8_t*
         (reinterpret_cast<uintptr_t>(sign) & 1u) || !aligned16(dz) || s_dp % 4 || s_sign % 2 || s_dz % 8)
         return hipErrorInvalidValue;
     const int64_t vecs = (int64_t)B * positions * (C / 8);
-    const int64_t blocks = (vecs + kThreads - 1) / kThreads;
-    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    pool_bwd_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)groups), kThreads, 0, s>>>(dpool, s_dp, sign, s_sign, dz, s_dz, vecs,
-                                                                                      positions, C, scale);
+    if (vecs >= ((int64_t)1 << 31) - kPoolBwdFly * kThreads) return hipErrorInvalidValue;   // the divisions by multiplication take 31-bit dividends
+    const int64_t blocks = (vecs + kPoolBwdFly * kThreads - 1) / (kPoolBwdFly * kThreads);
+    pool_bwd_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)groups), kThreads, 0, s>>>(
+        dpool, s_dp, sign, s_sign, dz, s_dz, (unsigned)vecs, make_div((unsigned)(C / 8)), make_div((unsigned)positions), C, scale);
     return hipGetLastError();
 }
 
