@@ -1,10 +1,9 @@
 // 3 x 3 convolutions (stride 1, zero padding 1) of the per-worker residual block with bf16 operands and fp32
 // accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16), grouped over the m workers: forward, back-propagated
 // delta, kernel / bias gradient; plus the conversion of the input batch, the block's tail (shortcut, ReLU, pooling) and
-// the pooling backward.  The
-// model is the first residual stage of the network of Section 4 (arXiv 2002.09539, "Experimental setting") and produces
-// the stochastic gradients g_i of Section 2; every tensor is rounded to bf16 (to nearest even) where it becomes an
-// operand of a convolution's products, sums and everything else stay fp32.
+// the pooling backward.  The model is the first residual stage of the network of Section 4 (arXiv 2002.09539,
+// "Experimental setting") and produces the stochastic gradients g_i of Section 2; every tensor is rounded to bf16 (to
+// nearest even) where it becomes an operand of a convolution's products, sums and everything else stay fp32.
 //
 // Layout: the bf16 operand tensors are stored WITH their zero border, [group][Pp][C] with Pp = B (H + 2) (W + 2) padded
 // pixels in (sample, row, column) order and the channel contiguous.  A tap (kh, kw) is then the same shift
@@ -21,22 +20,35 @@
 // fragments from it at nine row offsets, so the operand crosses the LDS write port once instead of nine times.  The
 // 64 x 64 kernel slice of each tap is double-buffered through registers.  Four wavefronts of 64 x 64; the MFMA takes the
 // kernel fragment first, so a lane's accumulators are four consecutive channels of one pixel, packed by the hardware
-// conversion and staged through LDS for 16-byte stores.  The second convolution writes conv + bias in fp32; a streaming
-// pass adds the shortcut, applies the ReLU, pools and keeps the activation's sign (one bit per element) for the backward
-// pass -- the activation itself is never stored.
+// conversion and staged through LDS for 16-byte stores; every wavefront stages and stores its own 64 rows, so the
+// epilogue has no workgroup barrier.  The second convolution's epilogue is the block's tail: it adds the shortcut,
+// applies the ReLU, keeps the activation's sign (one bit per element) for the backward pass and the wavefront's channel
+// sums for the pooling -- neither the convolution's output nor the activation is ever stored.  (Images of fewer than 64
+// padded pixels take the unfused route: conv + bias in fp32, then one streaming pass.)
 // DW: one workgroup per (pixel range, 64 x 64 block of input x output channels) holds all nine taps' accumulators
 // (9 x 64 x 64 fp32 = 144 registers per lane); per 64 pixels the input strip (64 + 2 (W + 3) rows, row-contiguous,
 // read with the transpose load at nine row offsets) and the delta tile pass through LDS; ranges are summed in range
 // order by the finish pass shared with the fp32 kernels (no atomics).
+// All three address global memory through buffer descriptors: the hardware's range check returns zeros for the rows a
+// strip reaches past either end of the tensor and drops the stores of a last tile's missing rows, so the loads and stores
+// carry no per-lane predicates, selects or 64-bit address arithmetic.
 //
 // Measured at the benchmark shape (16 workers x 128 samples x 32 x 32 x 64 channels, 154.6 GFLOP per launch): forward
-// 221 us (bf16 out) / 245 us (fp32 out), delta 252 us, kernel gradient 186 + 22 us, against 1390 - 1430 us for the fp32
-// kernels.  What moved the kernel gradient from 289 us: fragment reads issued a kernel row ahead of the MFMAs (258), the
-// bias column sums shared out over the four wavefronts instead of one wavefront summing while three wait at the barrier
-// (219), and 512 workgroups -- one round at two per compute unit -- instead of 768 (185; the finish pass 46 -> 22).
-// Knock-outs on the forward kernel (218 us): one tap instead of nine 143 us, no epilogue 170 us, neither 87 us -- the
-// strip's round trip and the prologue cost as much as the matrix work, and only two workgroups per compute unit (71 KB
-// of LDS each) are there to overlap them.
+// 200 us (bf16 out), 240 us with the fused tail (208 us for conv + bias in fp32 alone, which then needed a 224 us
+// streaming pass), delta 204 us, kernel gradient 170 + 22 us, against 1390 - 1430 us for the fp32 kernels.
+// Timestamps (s_memrealtime) taken inside an instrumented copy of the forward kernel showed where a tile's 11.3 us went
+// before the descriptors: 2.8 us from the first instruction to the last load issued -- some 1100 instructions of
+// predicates and addresses, issued by one wavefront per SIMD at a few cycles each -- 1.3 us for the loads to arrive,
+// 4.6 us for the nine taps (1.9 us of MFMA issue; the other workgroup of the compute unit shares the pipe) and 2.7 us of
+// epilogue.  With one workgroup per compute unit a tile takes 7.2 us, so the second one hides a third of the latencies.
+// Buffer addressing took the kernel from 2150 to 1330 instructions and the tile to 9.4 us (forward 221 -> 197 us,
+// fp32 out 245 -> 208, delta 252 -> 204 with the gate activations requested three taps before the end instead of after
+// it).  The same treatment of the kernel gradient's slice loads: 0.70 -> 0.33 us of a slice's 2.36 us for the
+// requests, 0.43 -> 0.29 for the LDS stores (186 -> 170 us); its bias column sums now come from the delta fragments the
+// MFMAs use anyway instead of sixteen more LDS reads per slice.
+// What moved the kernel gradient from 289 us before that: fragment reads issued a kernel row ahead of the MFMAs (258),
+// the bias column sums shared out over the four wavefronts instead of one wavefront summing while three wait at the
+// barrier (219), and 512 workgroups -- one round at two per compute unit -- instead of 768 (185; the finish pass 46 -> 22).
 // Tried and not kept: persistent workgroups that hold the whole kernel as 72 register fragments and walk the tiles of a
 // worker (one wavefront per SIMD, no barrier inside a tile: 280 - 400 us; with half the fragments per wavefront and two
 // workgroups per compute unit 308 - 397 us); the present forward kernel made persistent with the next tile's strip
@@ -45,7 +57,11 @@
 // SIMD: 349 us), fragment reads two kernel rows ahead (259 against 258 us), and an LDS ring of input rows that fetches
 // only the 64 new rows per slice three slices ahead (the wrap-around address arithmetic per fragment read costs more
 // than the loads it saves: 325 us); forward / delta tiles of 128 pixels (134 registers, 53 KB of LDS, three workgroups
-// per compute unit; the halo is then 1.55 x the tile: 260 / 291 / 271 us against 221 / 245 / 252).
+// per compute unit; the halo is then 1.55 x the tile: 260 / 291 / 271 us against 221 / 245 / 252); a raised wavefront
+// priority (s_setprio) outside or inside the tap loop (+-1 %); the bias loaded straight into the accumulators before the
+// first tap (the eight extra loads in the prologue cost what the epilogue's additions saved); a branch around the late
+// requests of bias / gate activations (the compiler then makes every later wait on a kernel slice wait for them too:
+// +0.8 us per tile).
 #include <type_traits>
 
 #include "gemm_bf16_tile.h"
