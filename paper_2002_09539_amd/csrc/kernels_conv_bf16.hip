@@ -126,18 +126,6 @@ __device__ __forceinline__ bool interior(const ConvBDev& p, int q, int* unpadded
     return y >= 1 && y <= p.H && x >= 1 && x <= p.W;
 }
 
-// Buffer addressing: a descriptor of [base, base + bytes) and 32-bit byte offsets.  The hardware checks the lane's offset
-// against the range: a load outside returns zeros and a store outside is dropped, so tiles that hang over either end of
-// a tensor (the strip's halo, the last tile's rows) need no per-lane predicates or 64-bit address arithmetic.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // raw buffer, 32-bit data format
-}
-__device__ __forceinline__ u4 buf_load(rsrc_t r, unsigned lane_off, unsigned uniform_off) {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)uniform_off, 0);
-}
-__device__ __forceinline__ void buf_store(u4 v, rsrc_t r, unsigned lane_off) { __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)lane_off, 0, 0); }
-
 __device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bits_rne(a) | (bf16_bits_rne(b) << 16); }
 
 // ---------------------------------------------------------------------------------------------

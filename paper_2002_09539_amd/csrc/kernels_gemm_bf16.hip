@@ -187,7 +187,43 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
     // The loop bodies below are free of data-dependent branches: loads past the end of K are zero-filled
     // dummies and the tile published after the last slice is never consumed.
     const int nk = (p.K + BK - 1) / BK;
-    if (DEPTH == 1) {
+    if constexpr (MODE == kDw && DEPTH == 1) {
+        // Both operands are [K][.] with K the row: the descriptor's range check zero-fills the rows from K on, and a lane
+        // whose columns lie past M (N) gets an offset beyond any range once, outside the loop -- so a slice's loads are
+        // one instruction per vector, with no predicates, selects or 64-bit address arithmetic (with eight slices of four
+        // MFMAs per wavefront those were most of the loop's instructions).
+        static_assert(TA::kVecs % kThreads == 0 && TB::kVecs % kThreads == 0, "whole vectors per lane");
+        const rsrc_t a_rs = make_rsrc(A, (unsigned)p.K * (unsigned)p.lda * 2u), b_rs = make_rsrc(B, (unsigned)p.K * (unsigned)p.ldb * 2u);
+        constexpr unsigned kOut = 0x80000000u;   // beyond every range the launcher admits
+        unsigned a_off[TA::kPerThread], b_off[TB::kPerThread];
+#pragma unroll
+        for (int t = 0; t < TA::kPerThread; ++t) {
+            const int v = threadIdx.x + t * kThreads, col = m0 + (v % TA::kVecPerLine) * 8;
+            a_off[t] = col < p.M ? 2u * ((unsigned)(v / TA::kVecPerLine) * (unsigned)p.lda + col) : kOut;
+        }
+#pragma unroll
+        for (int t = 0; t < TB::kPerThread; ++t) {
+            const int v = threadIdx.x + t * kThreads, col = n0 + (v % TB::kVecPerLine) * 8;
+            b_off[t] = col < p.N ? 2u * ((unsigned)(v / TB::kVecPerLine) * (unsigned)p.ldb + col) : kOut;
+        }
+        const unsigned a_step = 2u * BK * (unsigned)p.lda, b_step = 2u * BK * (unsigned)p.ldb;   // bytes per K slice
+        u4 ra[TA::kPerThread], rb[TB::kPerThread];
+        auto load_ab = [&](int kt) {
+#pragma unroll
+            for (int t = 0; t < TA::kPerThread; ++t) ra[t] = buf_load(a_rs, a_off[t] + kt * a_step, 0u);
+#pragma unroll
+            for (int t = 0; t < TB::kPerThread; ++t) rb[t] = buf_load(b_rs, b_off[t] + kt * b_step, 0u);
+        };
+        load_ab(0);
+        TA::store(lds_a(0), ra, ~0u);
+        TB::store(lds_b(0), rb, ~0u);
+        __syncthreads();
+        load_frags(0, 0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            load_ab(kt + 1);   // past the last slice: zeros, published and never read
+            slice(kt & 1, ra, ~0u, rb, ~0u);
+        }
+    } else if (DEPTH == 1) {
         u4 ra[TA::kPerThread], rb[TB::kPerThread];
         unsigned oka = TA::load(ra, A, p.lda, m0, 0, p.M, p.K);
         unsigned okb = TB::load(rb, B, p.ldb, n0, 0, p.N, p.K);
@@ -495,6 +531,8 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     if (!aligned16(g.a) || !aligned16(g.b) || g.lda % 8 || g.ldb % 8 || g.sa % 8 || g.sb % 8) return hipErrorInvalidValue;
     if (MODE == kDw) {   // A[K][M], B[K][N]
         if (g.M % 8 || g.N % 8 || g.lda < g.M || g.ldb < g.N) return hipErrorInvalidValue;
+        // 32-bit byte offsets inside a group's operand, with room for the slice requested past the end of K
+        if (((int64_t)g.K + 2 * BK) * g.lda >= ((int64_t)1 << 29) || ((int64_t)g.K + 2 * BK) * g.ldb >= ((int64_t)1 << 29)) return hipErrorInvalidValue;
     } else {
         if (g.K % 8 || g.N % 8 || g.lda < g.K) return hipErrorInvalidValue;
         if (MODE == kFwd && (g.ldb < g.N || !g.bias)) return hipErrorInvalidValue;
