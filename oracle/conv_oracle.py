@@ -38,7 +38,9 @@ even, at the point where it becomes an operand of a convolution's products -- th
 the deltas d_z2 and d_z1 -- while sums, biases, the shortcut, pooling, classifier and the master parameters stay as they
 are.  The gradient it returns is what back-propagation computes from those rounded tensors (the rounding itself is
 passed through as the identity).  The target of the benchmark specification's bf16 gate is still the unrounded
-computation.
+computation.  The batch-normalised block has the same mode with the same rule: the input batch, both kernels, a1, and
+the deltas at the two convolution outputs (which there are the normalisations' input gradients) are rounded; the
+convolution outputs, the normalisations, their statistics and their parameters are not operands of a convolution.
 
 Only tests/, the smoke check and the benchmark's CPU-baseline leg may import this module.
 Pinned by tests/test_oracle_conv_pins.py: torch's CPU conv2d, batch_norm and autograd as library routines, a pure-Python
@@ -175,17 +177,19 @@ def convblock_bn_unpack(x, C, classes):
     return out
 
 
-def convblock_bn_loss_grad(x, C, classes, X, labels, eps=BN_EPS):
+def convblock_bn_loss_grad(x, C, classes, X, labels, eps=BN_EPS, bf16_operands=False):
     """The residual block with batch normalisation + pooled linear classifier: (mean cross-entropy over the batch,
-    flat gradient in x's layout).  X [B][H][W][C], labels [B]."""
+    flat gradient in x's layout).  X [B][H][W][C], labels [B].  bf16_operands: the diagnostic mode of the module header."""
+    q = round_to_bf16 if bf16_operands else (lambda a: np.asarray(a, F64))
     x = np.asarray(x, F64)
     X = np.asarray(X, F64)
     Wa, ga, ba, Wb, gb, bb, Wh, bh = convblock_bn_unpack(x, C, classes)
+    Xq, Wa, Wb = q(X), q(Wa), q(Wb)                                      # operands of the convolutions
     B = X.shape[0]
     zero = np.zeros(C)
-    z1 = conv3x3_forward(X, Wa, zero)
+    z1 = conv3x3_forward(Xq, Wa, zero)
     n1, xhat1, istd1 = batchnorm_forward(z1, ga, ba, eps)
-    a1 = np.maximum(n1, 0.0)
+    a1 = q(np.maximum(n1, 0.0))
     z2 = conv3x3_forward(a1, Wb, zero)
     n2, xhat2, istd2 = batchnorm_forward(z2, gb, bb, eps)
     a2 = np.maximum(n2 + X, 0.0)
@@ -208,13 +212,14 @@ def convblock_bn_loss_grad(x, C, classes, X, labels, eps=BN_EPS):
     d_z2, dgb, dbb = batchnorm_backward(d_n2, xhat2, istd2, gb)
     ggb[...] = dgb
     gbb[...] = dbb
+    d_z2 = q(d_z2)
     d_a1, dWb, _ = conv3x3_backward(a1, Wb, d_z2)
     gWb[...] = dWb
     d_n1 = d_a1 * (a1 > 0.0)
     d_z1, dga, dba = batchnorm_backward(d_n1, xhat1, istd1, ga)
     gga[...] = dga
     gba[...] = dba
-    _, dWa, _ = conv3x3_backward(X, Wa, d_z1)
+    _, dWa, _ = conv3x3_backward(Xq, Wa, q(d_z1))                       # the input is data: its gradient is not needed
     gWa[...] = dWa
     return loss, g
 

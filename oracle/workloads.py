@@ -28,8 +28,8 @@ def conv_grad_fn(dims, X, labels, batch_norm=False, bf16_operands=False):
     """dims = (channels, height, width, classes); X [m][nb][B][H][W][C], labels [m][nb][B]."""
     nb = X.shape[1]
     if batch_norm:
-        assert not bf16_operands
-        return lambda i, k, x: CO.convblock_bn_loss_grad(x, dims[0], dims[3], X[i, k % nb], labels[i, k % nb])
+        return lambda i, k, x: CO.convblock_bn_loss_grad(x, dims[0], dims[3], X[i, k % nb], labels[i, k % nb],
+                                                         bf16_operands=bf16_operands)
     return lambda i, k, x: CO.convblock_loss_grad(x, dims[0], dims[3], X[i, k % nb], labels[i, k % nb],
                                                   bf16_operands=bf16_operands)
 

@@ -407,3 +407,55 @@ def test_bf16_operand_mode_is_the_plain_block_on_bf16_exact_operands():
     a, _ = CO.convblock_loss_grad(x, C, classes, X, labels, bf16_operands=True)
     b, _ = CO.convblock_loss_grad(x, C, classes, X, labels)
     assert a == b
+
+
+# ---- the same mode of the batch-normalised block -----------------------------------------------------------------------
+def _torch_bf16_bn_block(x, C, classes, X, labels, round_d_z2=True):
+    """Rounding points of the normalised block in torch: the batch, the kernels and a1 rounded with the rounding passed
+    through as the identity; the deltas at both convolution outputs rounded by gradient hooks (the hook on a
+    convolution's output sees the normalisation's input gradient, which is what becomes the operand)."""
+    import torch
+    import torch.nn.functional as F
+
+    def rnd(t):
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    def ste(t):
+        return t + (rnd(t) - t).detach()
+    tx = torch.tensor(x, requires_grad=True)
+    off = 0
+
+    def take(shape):
+        nonlocal off
+        n = int(np.prod(shape))
+        t = tx[off:off + n].reshape(shape)
+        off += n
+        return t
+    Wa, ga, ba, Wb, gb, bb, Wh, bh = (take(s) for s in ((3, 3, C, C), (C,), (C,), (3, 3, C, C), (C,), (C,), (C, classes), (classes,)))
+    tX = torch.tensor(X).permute(0, 3, 1, 2)
+    bn = lambda z, g_, b_: F.batch_norm(z, None, None, g_, b_, training=True, eps=CO.BN_EPS)
+    z1 = F.conv2d(rnd(tX), ste(Wa).permute(3, 2, 0, 1), None, padding=1)
+    z1.register_hook(rnd)
+    a1 = ste(F.relu(bn(z1, ga, ba)))
+    z2 = F.conv2d(a1, ste(Wb).permute(3, 2, 0, 1), None, padding=1)
+    if round_d_z2:
+        z2.register_hook(rnd)
+    logits = F.relu(bn(z2, gb, bb) + tX).mean(dim=(2, 3)) @ Wh + bh
+    tl = F.cross_entropy(logits, torch.tensor(labels), reduction="mean")
+    tl.backward()
+    return tl.item(), tx.grad.numpy()
+
+
+def test_bf16_operand_mode_of_the_bn_block_matches_torch_with_the_same_rounding_points():
+    pytest.importorskip("torch")
+    x, C, classes, X, labels = bn_block_case(91, B=4, C=3, H=4, Wd=6, classes=5)
+    loss, g = CO.convblock_bn_loss_grad(x, C, classes, X, labels, bf16_operands=True)
+    tl, tg = _torch_bf16_bn_block(x, C, classes, X, labels)
+    assert abs(loss - tl) <= 1e-12 * abs(loss)
+    np.testing.assert_allclose(g, tg, atol=1e-11)
+    exact_loss, exact_g = CO.convblock_bn_loss_grad(x, C, classes, X, labels)
+    assert 1e-6 < abs(loss - exact_loss) / abs(exact_loss) < 2e-2          # the mode rounds, and stays within the gate
+    assert 1e-4 < np.abs(g - exact_g).max() / np.abs(exact_g).max() < 1e-1
+    # teeth: leaving one delta unrounded is a different computation
+    _, tg_wrong = _torch_bf16_bn_block(x, C, classes, X, labels, round_d_z2=False)
+    assert np.abs(g - tg_wrong).max() > 1e-6 * np.abs(g).max()
