@@ -267,6 +267,14 @@ OLS_API int ols_attach_convblock_bn(ols_handle h, int channels, int height, int 
  * the limit on batch * height * width * channels applies to those sizes. */
 OLS_API int ols_attach_convblock_bf16(ols_handle h, int channels, int height, int width, int classes, int batch);
 
+/* The batch-normalised block of ols_attach_convblock_bn with bf16 operands, by the same rule: the input batch, both
+ * kernels, a1, and the gradients at the two convolution outputs are rounded to bf16 where they become operands of a
+ * convolution; the convolution outputs, the normalisations with their statistics, scales and shifts, the shortcut, a2,
+ * pooling, classifier, gradients and master parameters stay fp32 (the network of Section 4, "Experimental setting", has
+ * the normalisation).  Parameter layout, eps and errors as for ols_attach_convblock_bn; shape limits and call order as
+ * for ols_attach_convblock_bf16. */
+OLS_API int ols_attach_convblock_bn_bf16(ols_handle h, int channels, int height, int width, int classes, int batch, float eps);
+
 /* Bytes of caller-provided device workspace the attached model needs (activations, deltas, per-sample
  * losses, bf16 operand copies).  0 when no model is attached. */
 OLS_API int64_t ols_workspace_bytes(ols_handle h);

@@ -84,6 +84,9 @@ CONFIGS = {
     # configuration 6 with bf16 operands in the convolutions (fp32 accumulation, fp32 master parameters)
     8: Config(name="cfg8_convblock_bf16_m16", kind="conv", m=16, tau=2, alpha=0.6, gamma=0.05,
               mu=0.9, K=100, batch=128, dims=(64, 32, 32, 10), nb=2, gemm_dtype="bf16"),
+    # configuration 7 with bf16 operands in the convolutions: the residual network's own stage at matrix-core speed
+    9: Config(name="cfg9_convblock_bn_bf16_m16", kind="conv", m=16, tau=2, alpha=0.6, gamma=0.05,
+              mu=0.9, K=100, batch=128, dims=(64, 32, 32, 10), nb=2, batch_norm=True, gemm_dtype="bf16"),
 }
 
 

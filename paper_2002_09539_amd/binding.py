@@ -49,6 +49,7 @@ _SIGNATURES = {
     "ols_attach_convblock": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "ols_attach_convblock_bn": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]),
     "ols_attach_convblock_bf16": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "ols_attach_convblock_bn_bf16": (C.c_int, [_H, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_float]),
     "ols_workspace_bytes": (C.c_int64, [_H]),
     "ols_bind_workspace": (C.c_int, [_H, _P, C.c_int64]),
     "ols_set_batch": (C.c_int, [_H, _P, C.c_int64, _P, C.c_int64]),
@@ -166,6 +167,10 @@ def ols_attach_convblock_bf16(h, channels, height, width, classes, batch):
 
 def ols_attach_convblock_bn(h, channels, height, width, classes, batch, eps=1e-5):
     _check(load().ols_attach_convblock_bn(h, channels, height, width, classes, batch, eps))
+
+
+def ols_attach_convblock_bn_bf16(h, channels, height, width, classes, batch, eps=1e-5):
+    _check(load().ols_attach_convblock_bn_bf16(h, channels, height, width, classes, batch, eps))
 
 
 def ols_workspace_bytes(h):

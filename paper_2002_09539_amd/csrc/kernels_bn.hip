@@ -13,6 +13,8 @@
 // combines the ranges in range order (no atomics).  The statistics use shifted sums -- each range subtracts the value of
 // its own first pixel before summing and squaring -- and the ranges are merged with the pairwise update of mean and
 // second moment, so nothing cancels when a channel's mean is large against its spread.
+#include "fast_div.h"
+#include "gemm_bf16_tile.h"
 #include "ols_internal.h"
 
 namespace ols {
@@ -96,12 +98,32 @@ __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const float* _
     stats[((int64_t)g * 2 + 1) * C + c] = 1.0f / sqrtf(var + eps);
 }
 
+// Where a result becomes the operand of a bf16 convolution it is written as bf16 (to nearest even) into that operand's
+// layout: [B (H + 2) (W + 2)][C] with a border that nobody writes (it is zero from the start).  Vector v = four channels
+// of the unpadded pixel v / (C / 4).
+struct PaddedOut {
+    uint16_t* base;          // nullptr: the fp32 output is written instead
+    int64_t stride;          // per group, bf16 elements
+    FastDiv div_c4, div_hw, div_w;
+    int H, W;
+};
+__device__ __forceinline__ void store_padded_bf16(const PaddedOut& po, int g, unsigned v, int C, f4 o) {
+    const unsigned pix = fast_div(v, po.div_c4), c4 = v - pix * (unsigned)(C / 4);
+    const unsigned n = fast_div(pix, po.div_hw), rem = pix - n * (unsigned)(po.H * po.W);
+    const unsigned y = fast_div(rem, po.div_w), x = rem - y * (unsigned)po.W;
+    const int64_t q = ((int64_t)n * (po.H + 2) + y + 1) * (po.W + 2) + x + 1;
+    u2 w;   // v_cvt_pk_bf16_f32
+    w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{o[0], o[1]}, bf16x2));
+    w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{o[2], o[3]}, bf16x2));
+    *(u2*)(po.base + (int64_t)g * po.stride + q * C + 4 * c4) = w;
+}
+
 // out = act(gamma (z - mean) inv_std + beta (+ shortcut))
 __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restrict__ z, int64_t s_z,
                                                             const float* __restrict__ stats, const float* __restrict__ gamma,
                                                             const float* __restrict__ beta, int64_t s_par,
                                                             const float* __restrict__ shortcut, int64_t s_sc, float* out,
-                                                            int64_t s_out, int64_t vecs, int C, int relu) {
+                                                            int64_t s_out, int64_t vecs, int C, int relu, PaddedOut po) {
     const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (v >= vecs) return;
     const int g = blockIdx.y;
@@ -119,7 +141,8 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restr
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = fmaxf(o[e], 0.0f);
     }
-    *((f4*)(out + (int64_t)g * s_out) + v) = o;
+    if (po.base) store_padded_bf16(po, g, (unsigned)v, C, o);
+    else *((f4*)(out + (int64_t)g * s_out) + v) = o;
 }
 
 // part[group][range][2][C]: sum dy, sum dy xhat over the range
@@ -176,12 +199,12 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const float* __r
     g_out[(int64_t)g * ld + gamma_off + c] = s2;
 }
 
-// dz = gamma inv_std (dy - s1 / P - xhat s2 / P), written over dy
+// dz = gamma inv_std (dy - s1 / P - xhat s2 / P), written over dy -- or as a bf16 operand (see PaddedOut)
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(float* dy, int64_t s_dy, const float* __restrict__ z,
                                                                 int64_t s_z, const float* __restrict__ stats,
                                                                 const float* __restrict__ sums,
                                                                 const float* __restrict__ gamma, int64_t s_par, int64_t vecs,
-                                                                int C, float inv_count) {
+                                                                int C, float inv_count, PaddedOut po) {
     const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (v >= vecs) return;
     const int g = blockIdx.y;
@@ -197,12 +220,24 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(float* dy, int64
     f4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = ga[e] * istd[e] * (d[e] - s1[e] * inv_count - xh[e] * (s2[e] * inv_count));
-    *D = o;
+    if (po.base) store_padded_bf16(po, g, (unsigned)v, C, o);   // dy itself stays as it was
+    else *D = o;
 }
 
 bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 bool shape_ok(int groups, int P, int C) { return groups >= 1 && groups <= 65535 && P >= 1 && C >= 4 && C % 4 == 0 && C <= 1024; }
+
+// the optional bf16 output in the padded operand layout: P = B H W pixels, 8-byte stores, 31-bit vector indices
+bool padded_out(const BnArgs& a, int64_t vecs, PaddedOut* po) {
+    if (!a.out_bf16) return true;
+    if (a.H < 1 || a.W < 1 || a.P % (a.H * a.W) != 0 || (reinterpret_cast<uintptr_t>(a.out_bf16) & 7u) || a.s_outb % 4 ||
+        vecs >= ((int64_t)1 << 31))
+        return false;
+    po->base = a.out_bf16; po->stride = a.s_outb; po->H = a.H; po->W = a.W;
+    po->div_c4 = make_div((unsigned)(a.C / 4)); po->div_hw = make_div((unsigned)(a.H * a.W)); po->div_w = make_div((unsigned)a.W);
+    return true;
+}
 
 bool vec_grid(int64_t vecs, unsigned* blocks) {
     const int64_t b = (vecs + kThreads - 1) / kThreads;
@@ -216,7 +251,7 @@ bool vec_grid(int64_t vecs, unsigned* blocks) {
 int64_t bn_partial_floats(int groups, int P, int C) { return (int64_t)groups * bn_ranges(P) * 3 * C; }
 
 hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
-    if (!shape_ok(a.groups, a.P, a.C) || !a.z || !a.out || !a.stats || !a.part || !a.gamma || !a.beta) return hipErrorInvalidValue;
+    if (!shape_ok(a.groups, a.P, a.C) || !a.z || (!a.out && !a.out_bf16) || !a.stats || !a.part || !a.gamma || !a.beta) return hipErrorInvalidValue;
     if (!aligned16(a.z) || !aligned16(a.out) || !aligned16(a.stats) || !aligned16(a.part) || !aligned16(a.gamma) ||
         !aligned16(a.beta) || !aligned16(a.shortcut) || a.s_z % 4 || a.s_out % 4 || a.s_par % 4 || a.s_sc % 4)
         return hipErrorInvalidValue;
@@ -231,8 +266,10 @@ hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
     unsigned blocks;
     const int64_t vecs = (int64_t)a.P * (a.C / 4);
     if (!vec_grid(vecs, &blocks)) return hipErrorInvalidValue;
+    PaddedOut po = {};
+    if (!padded_out(a, vecs, &po)) return hipErrorInvalidValue;
     bn_apply_kernel<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.z, a.s_z, a.stats, a.gamma, a.beta, a.s_par, a.shortcut,
-                                                                          a.s_sc, a.out, a.s_out, vecs, a.C, a.relu);
+                                                                          a.s_sc, a.out, a.s_out, vecs, a.C, a.relu, po);
     return hipGetLastError();
 }
 
@@ -253,8 +290,10 @@ hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s) {
     unsigned blocks;
     const int64_t vecs = (int64_t)a.P * (a.C / 4);
     if (!vec_grid(vecs, &blocks)) return hipErrorInvalidValue;
+    PaddedOut po = {};
+    if (!padded_out(a, vecs, &po)) return hipErrorInvalidValue;
     bn_bwd_apply_kernel<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.sums, a.gamma,
-                                                                              a.s_par, vecs, a.C, 1.0f / (float)a.P);
+                                                                              a.s_par, vecs, a.C, 1.0f / (float)a.P, po);
     return hipGetLastError();
 }
 

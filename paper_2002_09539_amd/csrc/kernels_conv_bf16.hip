@@ -64,6 +64,7 @@
 // +0.8 us per tile).
 #include <type_traits>
 
+#include "fast_div.h"
 #include "gemm_bf16_tile.h"
 #include "ols_internal.h"
 #include "update_rule.h"
@@ -77,10 +78,6 @@ constexpr int kXcds = 8;
 constexpr int kCB = 64;     // channel block: contraction chunk and output-channel tile
 constexpr int kBM = 256;    // padded pixels per forward / delta tile
 constexpr int kDwBK = 64;   // pixels per slice of the kernel-gradient contraction
-
-struct FastDiv {
-    unsigned magic, shift;
-};
 
 struct ConvBDev {
     const uint16_t* in;      // FWD: layer input; DX: delta of the layer output; DW: layer input   [groups][Pp][C] bf16
@@ -109,14 +106,6 @@ __device__ __forceinline__ int xcd_tile(int chunk, int total) {
     return (slot >= chunk || tile >= total) ? -1 : tile;
 }
 
-// q / d for 0 <= q < 2^31 by multiplication: m = floor(2^32 (2^s - d) / d) + 1 with s = ceil(log2 d), and
-// q / d = (t + ((q - t) >> 1)) >> (s - 1) with t = mulhi(q, m)  (Granlund and Montgomery's round-up method)
-__device__ __forceinline__ unsigned fast_div(unsigned q, const FastDiv& d) {
-    if (d.shift == 0) return q;   // d = 1
-    const unsigned t = __umulhi(q, d.magic);
-    return (t + ((q - t) >> 1)) >> (d.shift - 1);
-}
-
 // padded pixel q -> is it an image pixel, and which (index in the unpadded [B H W] order)
 __device__ __forceinline__ bool interior(const ConvBDev& p, int q, int* unpadded) {
     const int per = p.Hp * p.Wp;
@@ -134,7 +123,10 @@ __device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bi
 // LDS of the forward / delta kernel, in bf16 elements: the strip and two kernel slices -- or, if larger, the fp32 output
 // staging of the four wavefronts (BM / 4 rows of 64 + 4 floats each), which takes their place after the last tap.
 constexpr int kStagePitchF32 = kCB + 4;
-enum { kOutBf16 = 0, kOutF32 = 1, kOutTail = 2 };   // what the forward kernel's epilogue produces
+// What the epilogue produces: bf16 in the padded operand layout; conv + bias in fp32, padded; the fused tail; or fp32 in
+// the UNPADDED [B H W][C] layout (image pixels only) -- the input of a batch normalisation (forward) or of its backward
+// pass (delta, gated by the sign of the bf16 activation as usual).
+enum { kOutBf16 = 0, kOutF32 = 1, kOutTail = 2, kOutF32U = 3 };
 template <int BM, int OUT>
 __host__ __device__ constexpr int conv_main_elems(int strip_rows, int slice_elems) {
     const int work = strip_rows * (kCB + 8) + 2 * slice_elems;
@@ -145,6 +137,9 @@ __host__ __device__ constexpr int conv_main_elems(int strip_rows, int slice_elem
 // NV: strip vectors per lane (upper bound of (BM + 2 halo) * 8 / 256); BM: pixels per tile.  OUT: bf16 activations /
 // deltas; the bare convolution + bias in fp32; or the residual block's tail fused into the epilogue (shortcut, ReLU,
 // sign bytes and partial sums of the global average pooling -- the second convolution's output is then never stored).
+template <int OUT>
+constexpr bool kRowIndex = OUT == kOutTail || OUT == kOutF32U;   // the epilogue needs the rows' unpadded pixel indices
+
 template <int MODE, int OUT, int NV, int BM>
 __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kernel(ConvBDev p) {
     using TB = typename std::conditional<MODE == 0, TileRC<kCB, kCB>, TileKC<kCB, kCB>>::type;   // FWD w[k = ci][n = co]; DX w[n = ci][k = co]
@@ -158,7 +153,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
     auto lds_b = [&](int buf) { return lds_b0 + buf * TB::kElems; };
     // the fp32 output is staged over the strip and the kernel slices together (conv_main_elems)
     uint8_t* row_flag = (uint8_t*)(lds_all + conv_main_elems<BM, OUT>(kStripRows, TB::kElems));   // [BM] 1: image pixel, 0: border
-    int* row_up = (int*)row_flag;   // fused tail instead: [BM] the pixel's index in the unpadded [B H W] order, -1 for the border
+    int* row_up = (int*)row_flag;   // fused tail / unpadded output instead: [BM] the pixel's index in the unpadded [B H W] order, -1 for the border
 
     const int tile = xcd_tile(p.chunk, p.total_tiles);
     if (tile < 0) return;
@@ -242,15 +237,25 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
     // lane will write -- are requested kMaskTap taps into a chunk, when no kernel slice is in flight any more (with the
     // long strips of wide images the registers do not allow it: there they are requested after the last tap).
     constexpr int kVecB = kCB / 8, kPerB = (BM / 4) * kVecB / 64, kMaskTap = NV <= 12 ? 6 : 9;
-    u4 mk[MODE == 1 ? kPerB : 1];
+    u4 mk[MODE == 1 && OUT == kOutBf16 ? kPerB : 1];
     const uint16_t* Mk = MODE == 1 && p.mask ? p.mask + (int64_t)group * p.s_mask : nullptr;
     const rsrc_t mk_rs = make_rsrc(Mk ? Mk : IN, Mk ? (unsigned)p.Pp * row_bytes : 0u);
     // the wavefront's own rows of the [Pp][C] bf16 output: lane l moves the vector l % 8 of rows wm0 + l / 8 + 8 t
     const unsigned own_off = (unsigned)(m0 + wm0 + lane / kVecB) * row_bytes + 2u * (unsigned)n0 + (lane % kVecB) * 16u;
     const unsigned step8 = (64 / kVecB) * row_bytes;
+    // with the fp32 output a lane moves four channels at a time (vector l % 16 of rows wm0 + l / 16 + 4 t): 8-byte pieces of
+    // the gate
+    constexpr int kPerF = (BM / 4) * (kCB / 4) / 64;
+    u2 mkf[MODE == 1 && OUT == kOutF32U ? kPerF : 1];
     auto load_mask = [&]() {
+        if constexpr (OUT == kOutF32U) {
+            const unsigned first = (unsigned)(m0 + wm0 + lane / (kCB / 4)) * row_bytes + 2u * (unsigned)n0 + (lane % (kCB / 4)) * 8u;
 #pragma unroll
-        for (int t = 0; t < kPerB; ++t) mk[t] = buf_load(mk_rs, own_off + t * step8, 0u);
+            for (int t = 0; t < kPerF; ++t) mkf[t] = __builtin_amdgcn_raw_buffer_load_b64(mk_rs, (int)(first + t * 4u * row_bytes), 0, 0);
+        } else {
+#pragma unroll
+            for (int t = 0; t < kPerB; ++t) mk[t] = buf_load(mk_rs, own_off + t * step8, 0u);
+        }
     };
     // Forward: the lane's channels of the bias (register quad g4 of block j: channels 32 j + 8 g4 + 4 (lane / 32) ..),
     // requested at the same point and added in the epilogue.
@@ -277,7 +282,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
                 const int q = m0 + threadIdx.x;
                 const bool img = q < p.Pp && interior(p, q, &up);
                 if (threadIdx.x < BM) {
-                    if constexpr (OUT == kOutTail) row_up[threadIdx.x] = img ? up : -1; else row_flag[threadIdx.x] = img ? 1 : 0;
+                    if constexpr (kRowIndex<OUT>) row_up[threadIdx.x] = img ? up : -1; else row_flag[threadIdx.x] = img ? 1 : 0;
                 }
             }
             store_b(0, rb[0]);
@@ -379,15 +384,20 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
             float* PP = p.pool_part + ((((int64_t)group * p.tiles_m + tm) * 4 + wave) * 2 + lane / kVecPerRow) * C + n0;
             *(f4*)(PP + 4 * (lane % kVecPerRow)) = o;
         }
-    } else if constexpr (OUT == kOutF32) {
-        // convolution + bias only (what follows it is another kernel's).  Border rows are written as computed; their
-        // consumer skips them.  Every wavefront stages its own BM / 4 rows and moves them itself: the LDS operations of
-        // one wavefront complete in order, so no workgroup barrier is needed after the one that ended the last tap.
+    } else if constexpr (OUT == kOutF32 || OUT == kOutF32U) {
+        // Convolution + bias only (what follows it is another kernel's).  Padded output: border rows are written as
+        // computed; their consumer skips them.  Unpadded output: a row goes to its pixel's place in the [B H W] order and a
+        // border row to offset -1, which the range check drops.  Every wavefront stages its own BM / 4 rows and moves them
+        // itself: the LDS operations of one wavefront complete in order, so no workgroup barrier is needed after the one
+        // that ended the last tap.
         constexpr int FP = kStagePitchF32, WR = BM / 4;
         constexpr int kVecPerRow = kCB / 4, kPer = WR * kVecPerRow / 64, kBatch = 8;
+        static_assert(kPer == kPerF, "vectors per lane");
         float* stage = (float*)lds_all + wave * WR * FP;
-        const rsrc_t out_rs = make_rsrc((const float*)p.out + (int64_t)group * p.s_out, (unsigned)p.Pp * 2u * row_bytes);
-        const unsigned out_off = (unsigned)(m0 + wm0 + lane / kVecPerRow) * 2u * row_bytes + 4u * (unsigned)n0 + (lane % kVecPerRow) * 16u;
+        const unsigned out_rows = OUT == kOutF32U ? (unsigned)(p.B * p.H * p.W) : (unsigned)p.Pp;
+        const rsrc_t out_rs = make_rsrc((const float*)p.out + (int64_t)group * p.s_out, out_rows * 2u * row_bytes);
+        const unsigned col_off = 4u * (unsigned)n0 + (lane % kVecPerRow) * 16u;
+        const unsigned out_off = (unsigned)(m0 + wm0 + lane / kVecPerRow) * 2u * row_bytes + col_off;
         const unsigned out_step = (64 / kVecPerRow) * 2u * row_bytes;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -395,8 +405,8 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
-                    const f4 o = {acc[i][j][4 * g4] + bq[j][g4][0], acc[i][j][4 * g4 + 1] + bq[j][g4][1], acc[i][j][4 * g4 + 2] + bq[j][g4][2],
-                                  acc[i][j][4 * g4 + 3] + bq[j][g4][3]};
+                    f4 o = {acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]};
+                    if constexpr (MODE == 0) o = o + bq[j][g4];
                     *(f4*)(stage + (32 * i + lane32) * FP + 32 * j + 8 * g4 + 4 * half) = o;
                 }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -404,13 +414,28 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
 #pragma unroll
         for (int t0 = 0; t0 < kPer; t0 += kBatch) {
             u4 val[kBatch];
+            int up[kBatch];
 #pragma unroll
             for (int t = 0; t < kBatch; ++t) {
                 const int v = lane + (t0 + t) * 64;
                 val[t] = *(const u4*)(stage + (v / kVecPerRow) * FP + (v % kVecPerRow) * 4);
+                if constexpr (OUT == kOutF32U) up[t] = row_up[wm0 + v / kVecPerRow];
             }
 #pragma unroll
-            for (int t = 0; t < kBatch; ++t) buf_store(val[t], out_rs, out_off + (t0 + t) * out_step);   // rows past the tensor are dropped
+            for (int t = 0; t < kBatch; ++t) {
+                u4 o = val[t];
+                if constexpr (MODE == 1 && OUT == kOutF32U) {
+                    if (Mk) {   // a bf16 is positive iff its bits are in [0x0001, 0x7FFF]
+                        const u2 g2 = mkf[t0 + t];
+                        o[0] = ((g2.x & 0xFFFFu) - 1u) < 0x7FFFu ? o[0] : 0u;
+                        o[1] = ((g2.x >> 16) - 1u) < 0x7FFFu ? o[1] : 0u;
+                        o[2] = ((g2.y & 0xFFFFu) - 1u) < 0x7FFFu ? o[2] : 0u;
+                        o[3] = ((g2.y >> 16) - 1u) < 0x7FFFu ? o[3] : 0u;
+                    }
+                }
+                if constexpr (OUT == kOutF32U) buf_store(o, out_rs, (unsigned)up[t] * 2u * row_bytes + col_off);   // border rows: dropped
+                else buf_store(o, out_rs, out_off + (t0 + t) * out_step);                                           // rows past the tensor are dropped
+            }
         }
     } else {
         // wavefront-local like the fp32 epilogue: a wavefront stages and moves its own BM / 4 rows
@@ -754,15 +779,6 @@ bool shape_ok(const ConvBArgs& a) {
     return Pp * a.C < ((int64_t)1 << 31) - (int64_t)1024 * a.C;
 }
 
-FastDiv make_div(unsigned d) {
-    FastDiv f = {0u, 0u};
-    unsigned s = 0;
-    while ((1ull << s) < d) ++s;
-    f.shift = s;
-    if (s > 0) f.magic = (unsigned)((((1ull << s) - d) << 32) / d + 1);
-    return f;
-}
-
 void fill(ConvBDev* p, const ConvBArgs& a) {
     p->groups = a.groups; p->B = a.B; p->H = a.H; p->W = a.W; p->C = a.C;
     p->Hp = a.H + 2; p->Wp = a.W + 2; p->Pp = a.B * p->Hp * p->Wp; p->halo = p->Wp + 1;
@@ -783,7 +799,8 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
             return hipErrorInvalidValue;
     }
     if (MODE == 0 && a.bias && (!aligned16(a.bias) || a.s_bias % 4)) return hipErrorInvalidValue;   // read as 16-byte vectors
-    if (MODE == 1 && a.out_f32) return hipErrorInvalidValue;   // the delta is always an operand of the next product
+    if (MODE == 1 && a.out_f32 && !a.out_unpadded) return hipErrorInvalidValue;   // a padded fp32 delta has no consumer
+    if (a.out_unpadded && (!a.out_f32 || tail || (int64_t)a.B * a.H * a.W * a.C >= ((int64_t)1 << 30) - 1024)) return hipErrorInvalidValue;
     if (a.out_f32 && a.relu) return hipErrorInvalidValue;      // the fp32 output is the bare convolution + bias
     ConvBDev p = {};
     fill(&p, a);
@@ -810,19 +827,21 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     if (nv > NV1) return hipErrorInvalidValue;
     const int lds_rows = 32 * (nv <= NV0 ? NV0 : NV1);   // the kernel's strip holds all the vectors its lanes move
     // the bf16 output tile is staged in the strip's place (BM x 72 bf16); the fp32 one is sized by conv_main_elems
-    const int out = tail ? kOutTail : a.out_f32 ? kOutF32 : kOutBf16;
+    const int out = tail ? kOutTail : a.out_unpadded ? kOutF32U : a.out_f32 ? kOutF32 : kOutBf16;
     const size_t main_elems = out != kOutBf16 ? conv_main_elems<BM, kOutF32>(lds_rows, (int)b_elems) : conv_main_elems<BM, kOutBf16>(lds_rows, (int)b_elems);
-    const size_t lds = main_elems * sizeof(uint16_t) + (tail ? BM * sizeof(int) : BM);   // strip and kernel slices (or the fp32 staging), row flags / indices
+    const size_t lds = main_elems * sizeof(uint16_t) + (out == kOutTail || out == kOutF32U ? BM * sizeof(int) : BM);   // strip and kernel slices (or the fp32 staging), row flags / indices
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     void (*kern)(ConvBDev);
     if (nv <= NV0)
-        kern = MODE == 1 ? conv3x3_bf16_kernel<1, kOutBf16, NV0, BM>
+        kern = MODE == 1 ? (out == kOutF32U ? conv3x3_bf16_kernel<1, kOutF32U, NV0, BM> : conv3x3_bf16_kernel<1, kOutBf16, NV0, BM>)
                : out == kOutTail ? conv3x3_bf16_kernel<0, kOutTail, NV0, BM>
+               : out == kOutF32U ? conv3x3_bf16_kernel<0, kOutF32U, NV0, BM>
                : out == kOutF32  ? conv3x3_bf16_kernel<0, kOutF32, NV0, BM>
                                  : conv3x3_bf16_kernel<0, kOutBf16, NV0, BM>;
     else
-        kern = MODE == 1 ? conv3x3_bf16_kernel<1, kOutBf16, NV1, BM>
+        kern = MODE == 1 ? (out == kOutF32U ? conv3x3_bf16_kernel<1, kOutF32U, NV1, BM> : conv3x3_bf16_kernel<1, kOutBf16, NV1, BM>)
                : out == kOutTail ? conv3x3_bf16_kernel<0, kOutTail, NV1, BM>
+               : out == kOutF32U ? conv3x3_bf16_kernel<0, kOutF32U, NV1, BM>
                : out == kOutF32  ? conv3x3_bf16_kernel<0, kOutF32, NV1, BM>
                                  : conv3x3_bf16_kernel<0, kOutBf16, NV1, BM>;
     if (lds > 64 * 1024) {

@@ -97,7 +97,7 @@ struct ols_ctx {
     bool cv_bn = false;     // convolutions without bias, each followed by batch normalisation
     float cv_eps = 1e-5f;
     int64_t off_a1 = 0, off_a2 = 0, off_dz1 = 0, off_dz2 = 0, off_pooled = 0, off_dpool = 0, off_cpartial = 0;
-    int64_t off_z1 = 0, off_z2 = 0, off_bnstats = 0, off_bnsums = 0, off_bnpart = 0;
+    int64_t off_z1 = 0, off_z2 = 0, off_bnstats = 0, off_bnsums = 0, off_bnpart = 0, off_dn = 0;
     const float* X = nullptr;
     const void* y = nullptr;
     int64_t xs = 0, ys = 0;
@@ -324,7 +324,30 @@ void plan_workspace(ols_ctx* c) {
         c->off_dlogits = take(m * B * c->dims[L] * 4);
         c->off_loss = take(m * B * 4);
     }
-    if (c->model == MODEL_CONV && c->gemm_dtype == 1) {
+    if (c->model == MODEL_CONV && c->gemm_dtype == 1 && c->cv_bn) {
+        // bf16 operand tensors with their zero border (batch, a1, both deltas); what the normalisations read and write is
+        // fp32 without a border (both convolution outputs, a2, the gradients at the normalised outputs)
+        const int64_t padded = m * B * (c->cv_H + 2) * (c->cv_W + 2) * c->cv_C;
+        const int64_t act = m * B * c->cv_H * c->cv_W * c->cv_C * 4;
+        c->off_x0 = take(padded * 2);
+        c->off_a1 = take(padded * 2);
+        c->off_dz2 = take(padded * 2);
+        c->off_dz1 = take(padded * 2);
+        c->off_z1 = take(act);
+        c->off_z2 = take(act);
+        c->off_a2 = take(act);
+        c->off_dn = take(act);            // gradient at a normalised output (second block, then first)
+        c->off_pooled = take(m * B * c->cv_C * 4);
+        c->off_dpool = take(m * B * c->cv_C * 4);
+        const int64_t splits = conv3x3_bf16_dw_splits(c->m, c->B, c->cv_H, c->cv_W, c->cv_C);
+        c->off_cpartial = take(splits * m * ((int64_t)9 * c->cv_C * c->cv_C + c->cv_C) * 4);
+        c->off_dlogits = take(m * B * c->cv_classes * 4);
+        c->off_loss = take(m * B * 4);
+        c->off_bnstats = take(2 * m * 2 * c->cv_C * 4);
+        c->off_bnsums = take(m * 2 * c->cv_C * 4);
+        c->off_bnpart = take(bn_partial_floats(c->m, c->B * c->cv_H * c->cv_W, c->cv_C) * 4);
+        c->off_shadow = take(m * c->ld * 2);
+    } else if (c->model == MODEL_CONV && c->gemm_dtype == 1) {
         // operand tensors are bf16 and carry their zero border; the second activation (pooled, and the mask of the
         // pooling backward) stays fp32, with the border as well
         const int64_t padded = m * B * (c->cv_H + 2) * (c->cv_W + 2) * c->cv_C;
@@ -465,10 +488,126 @@ int conv_gradients_bf16(ols_ctx* c) {
 }
 
 // Forward + backward of the residual convolutional block on the main stream; gradients go to g.
+// The batch-normalised block with bf16 operands.  The convolutions read bf16 tensors in the padded layout and write
+// fp32 without a border, which is what the normalisation kernels take; the normalisations write what becomes a
+// convolution's operand (a1, the gradients at both convolution outputs) as bf16 straight into the padded layout.
+// Statistics, the shortcut, a2, pooling and classifier are fp32 as in the fp32 block.
+int conv_gradients_bn_bf16(ols_ctx* c) {
+    const float* xc = c->x[c->cur];
+    const uint16_t* shadow = shadow_ptr(c);
+    const int m = c->m, B = c->B, C = c->cv_C, H = c->cv_H, W = c->cv_W;
+    const int64_t n_w = (int64_t)9 * C * C, per_conv = n_w + 2 * C;   // kernels, scale, shift
+    const int64_t wa = 0, ga = n_w, ba = n_w + C, wb = per_conv, gb = wb + n_w, bb = gb + C;
+    const int64_t wh = 2 * per_conv, bh = wh + (int64_t)C * c->cv_classes;
+    const int64_t padded = (int64_t)B * (H + 2) * (W + 2) * C;   // elements of a padded tensor per worker
+    const int64_t act = (int64_t)B * H * W * C;                  // elements of an unpadded one
+    uint16_t* xb = (uint16_t*)(c->ws + c->off_x0);
+    uint16_t* a1 = (uint16_t*)(c->ws + c->off_a1);
+    uint16_t* dz2 = (uint16_t*)(c->ws + c->off_dz2);
+    uint16_t* dz1 = (uint16_t*)(c->ws + c->off_dz1);
+    float* z1 = (float*)(c->ws + c->off_z1);
+    float* z2 = (float*)(c->ws + c->off_z2);
+    float* a2 = (float*)(c->ws + c->off_a2);
+    float* dn = (float*)(c->ws + c->off_dn);
+    float* pooled = (float*)(c->ws + c->off_pooled);
+    float* dpool = (float*)(c->ws + c->off_dpool);
+    ConvBArgs base = {};
+    base.groups = m; base.B = B; base.H = H; base.W = W; base.C = C;
+    base.s_w = c->ld; base.ld = c->ld; base.g = c->g; base.partial = (float*)(c->ws + c->off_cpartial);
+    BnArgs nbase = {};
+    nbase.groups = m; nbase.P = B * H * W; nbase.C = C; nbase.eps = c->cv_eps;
+    nbase.s_z = act; nbase.s_out = act; nbase.s_dy = act; nbase.s_par = c->ld;
+    nbase.ld = c->ld; nbase.g = c->g; nbase.H = H; nbase.W = W; nbase.s_outb = padded;
+    nbase.part = (float*)(c->ws + c->off_bnpart);
+    nbase.sums = (float*)(c->ws + c->off_bnsums);
+    float* stats1 = (float*)(c->ws + c->off_bnstats);
+    float* stats2 = stats1 + (int64_t)m * 2 * C;
+    int rc;
+    if ((rc = enqueue(c, OLS_K_CAST, 0, -1, -1, [&](hipStream_t s) {
+             return launch_pad_cast_bf16(c->X, c->xs, xb, padded, m, B, H, W, C, s);
+         })))
+        return rc;
+    {   // z1 = conv(X; Wa)
+        ConvBArgs a = base;
+        a.in = xb; a.s_in = padded; a.w = shadow + wa; a.out = z1; a.s_out = act; a.out_f32 = 1; a.out_unpadded = 1;
+        if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
+    }
+    {   // a1 = bf16(relu(bn(z1)))
+        BnArgs a = nbase;
+        a.z = z1; a.out_bf16 = a1; a.stats = stats1; a.gamma = xc + ga; a.beta = xc + ba; a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
+    }
+    {   // z2 = conv(a1; Wb)
+        ConvBArgs a = base;
+        a.in = a1; a.s_in = padded; a.w = shadow + wb; a.out = z2; a.s_out = act; a.out_f32 = 1; a.out_unpadded = 1;
+        if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
+    }
+    {   // a2 = relu(bn(z2) + X)
+        BnArgs a = nbase;
+        a.z = z2; a.out = a2; a.stats = stats2; a.gamma = xc + gb; a.beta = xc + bb; a.shortcut = c->X; a.s_sc = c->xs; a.relu = 1;
+        if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
+    }
+    if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
+             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s);
+         })))
+        return rc;
+    HeadArgs ha = {};
+    ha.h = pooled;
+    ha.h_stride = (int64_t)B * C;
+    ha.h_bf16 = false;
+    ha.x = xc;
+    ha.g = c->g;
+    ha.ld = c->ld;
+    ha.w_off = wh;
+    ha.b_off = bh;
+    ha.labels = (const int32_t*)c->y;
+    ha.label_stride = c->ys;
+    ha.dlogits = (float*)(c->ws + c->off_dlogits);
+    ha.loss_parts = (float*)(c->ws + c->off_loss);
+    ha.dz = dpool;
+    ha.m = m;
+    ha.B = B;
+    ha.H = C;
+    ha.C = c->cv_classes;
+    if ((rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); }))) return rc;
+    if ((rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); }))) return rc;
+    if ((rc = enqueue(c, OLS_K_POOL_BWD, 0, -1, -1, [&](hipStream_t s) {
+             return launch_pool_bwd(dpool, (int64_t)B * C, a2, act, dn, act, m, B, H * W, C, s);
+         })))
+        return rc;
+    {   // through the second normalisation: scale / shift gradients; the gradient at z2 goes out as the bf16 operand dz2
+        BnArgs a = nbase;
+        a.z = z2; a.dy = dn; a.out_bf16 = dz2; a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
+        if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
+    }
+    {   // gradient at the first normalised output: transposed convolution of dz2 through Wb, gated by a1 > 0
+        ConvBArgs a = base;
+        a.in = dz2; a.s_in = padded; a.w = shadow + wb; a.mask = a1; a.s_mask = padded; a.out = dn; a.s_out = act;
+        a.out_f32 = 1; a.out_unpadded = 1;
+        if ((rc = enqueue(c, OLS_K_CONV_DX, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_dx(a, s); }))) return rc;
+    }
+    {   // gradients of the second convolution
+        ConvBArgs a = base;
+        a.in = a1; a.s_in = padded; a.dout = dz2; a.s_dout = padded; a.g_w_off = wb; a.g_b_off = -1;
+        if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_dw(a, s); }))) return rc;
+    }
+    {   // through the first normalisation
+        BnArgs a = nbase;
+        a.z = z1; a.dy = dn; a.out_bf16 = dz1; a.stats = stats1; a.gamma = xc + ga; a.g_gamma_off = ga; a.g_beta_off = ba;
+        if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
+    }
+    {   // gradients of the first convolution (its input is data: no delta beyond it)
+        ConvBArgs a = base;
+        a.in = xb; a.s_in = padded; a.dout = dz1; a.s_dout = padded; a.g_w_off = wa; a.g_b_off = -1;
+        if ((rc = enqueue(c, OLS_K_CONV_DW, 0, -1, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_dw(a, s); }))) return rc;
+    }
+    return OLS_OK;
+}
+
 // Plain block:       a1 = relu(conv(X; Wa) + ba);        a2 = relu(conv(a1; Wb) + bb + X)
 // Batch-normalised:  a1 = relu(bn(conv(X; Wa); ga, ba)); a2 = relu(bn(conv(a1; Wb); gb, bb) + X)
 int conv_gradients(ols_ctx* c) {
-    if (c->gemm_dtype == 1) return conv_gradients_bf16(c);
+    if (c->gemm_dtype == 1) return c->cv_bn ? conv_gradients_bn_bf16(c) : conv_gradients_bf16(c);
     const float* xc = c->x[c->cur];
     const int m = c->m, B = c->B, C = c->cv_C, H = c->cv_H, W = c->cv_W;
     const bool bn = c->cv_bn;
@@ -872,6 +1011,14 @@ int ols_init_params(ols_handle c, const float* x0) {
         (void)hipStreamSynchronize(c->stream[1]);
     }
     c->cur = 0;
+    if (c->model == MODEL_CONV && c->gemm_dtype == 1 && c->cv_bn && !c->dry) {
+        // a1 and the two deltas are written by the normalisation kernels, image pixels only: their border is zeroed here, once
+        const size_t bytes = (size_t)c->m * c->B * (c->cv_H + 2) * (c->cv_W + 2) * c->cv_C * 2;
+        for (int64_t off : {c->off_a1, c->off_dz2, c->off_dz1}) {
+            hipError_t e = hipMemsetAsync(c->ws + off, 0, bytes, c->stream[0]);
+            if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(padded operands)");
+        }
+    }
     int rc = enqueue(c, OLS_K_INIT, 0, -1, 0, [&](hipStream_t s) {
         return launch_init(c->x[0], c->x[1], c->buf, c->z, shadow_ptr(c), x0, c->m, c->d, c->ld, s);
     });
@@ -1034,6 +1181,10 @@ int ols_attach_convblock_bf16(ols_handle c, int channels, int height, int width,
 
 int ols_attach_convblock_bn(ols_handle c, int channels, int height, int width, int classes, int batch, float eps) {
     return attach_convblock(c, channels, height, width, classes, batch, true, eps, false);
+}
+
+int ols_attach_convblock_bn_bf16(ols_handle c, int channels, int height, int width, int classes, int batch, float eps) {
+    return attach_convblock(c, channels, height, width, classes, batch, true, eps, true);
 }
 
 int64_t ols_workspace_bytes(ols_handle c) { return c ? c->ws_need : 0; }

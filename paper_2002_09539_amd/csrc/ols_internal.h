@@ -211,6 +211,7 @@ struct ConvBArgs {
     void* out;              // fwd: layer output; dx: delta of the layer input; padded, bf16 -- or, fwd with out_f32, the
                             // bare convolution + bias in fp32 with border rows as computed (their consumer skips them)
     int out_f32;
+    int out_unpadded;       // with out_f32 (fwd and dx): fp32 [B H W][C], image pixels only -- what a batch normalisation reads
     const float* bias;      // fwd: [C] per group, or nullptr
     const void* mask;       // dx: padded bf16 activations whose sign gates the result, or nullptr
     float* partial;         // dw: scratch of conv3x3_bf16_dw_splits(...) * groups * (9 C C + C) floats
@@ -264,6 +265,12 @@ struct BnArgs {
     int groups, P, C;
     int relu;
     float eps;
+    // Optional: the result (fwd: the activation; bwd: the gradient at z) goes out as bf16, to nearest even, in the padded
+    // operand layout of the bf16 convolutions, [B (H + 2) (W + 2)][C] per group with P = B H W -- only the image pixels
+    // are written (the border is zero from the start and stays so); `out` / the in-place update of dy are then skipped.
+    uint16_t* out_bf16;
+    int64_t s_outb;
+    int H, W;
 };
 hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s);    // statistics (two launches) + normalise
 hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s);   // sums (two launches) + gradient at z

@@ -84,8 +84,9 @@ class Session:
             self._workspace()
 
     def attach_convblock(self, channels, height, width, classes, batch, batch_norm=False, eps=1e-5, gemm_dtype="f32"):
-        if gemm_dtype == "bf16":
-            assert not batch_norm, "the batch-normalised block runs in fp32 only"
+        if gemm_dtype == "bf16" and batch_norm:
+            B.ols_attach_convblock_bn_bf16(self.h, channels, height, width, classes, batch, eps)
+        elif gemm_dtype == "bf16":
             B.ols_attach_convblock_bf16(self.h, channels, height, width, classes, batch)
         elif batch_norm:
             B.ols_attach_convblock_bn(self.h, channels, height, width, classes, batch, eps)

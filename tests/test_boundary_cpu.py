@@ -601,6 +601,33 @@ def test_convblock_bf16_attachment_and_launch_plan():
     B.ols_destroy(h)
 
 
+def test_convblock_bn_bf16_attachment_and_launch_plan():
+    C, H, W, classes, batch = 64, 8, 8, 10, 4
+    d = 2 * (9 * C * C + 2 * C) + C * classes + classes
+    h = dry(d=d, mu=0.9, tau=2)
+    assert code_of(B.ols_attach_convblock_bn_bf16, h, 32, H, W, classes, batch, 1e-5) == B.OLS_EINVAL    # channels not a multiple of 64
+    assert code_of(B.ols_attach_convblock_bn_bf16, h, C, H, W, classes, batch, 0.0) == B.OLS_EINVAL      # eps must be positive
+    assert code_of(B.ols_attach_convblock_bf16, h, C, H, W, classes, batch) == B.OLS_EINVAL              # d is the normalised block's
+    B.ols_attach_convblock_bn_bf16(h, C, H, W, classes, batch, 1e-5)
+    need = B.ols_workspace_bytes(h)
+    padded, plain = 4 * batch * (H + 2) * (W + 2) * C, 4 * batch * H * W * C
+    # four bf16 operand tensors with a border, four fp32 tensors without one, the bf16 parameters
+    assert need >= padded * 4 * 2 + plain * 4 * 4 + 4 * (d + 63) // 64 * 64 * 2
+    assert code_of(B.ols_init_params, h, FAKE) == B.OLS_ESTATE           # the workspace holds the bf16 parameters
+    B.ols_bind_workspace(h, FAKE, need)
+    B.ols_init_params(h, FAKE)
+    B.ols_set_batch(h, FAKE, batch * H * W * C, FAKE, batch)
+    B.ols_set_option(h, B.OLS_OPT_TRACE, 1)
+    B.ols_local_step(h)
+    B.ols_local_step(h)
+    B.ols_sync_pull(h)
+    B.ols_anchor_update_async(h)
+    one = ["cast_bf16", "conv_fwd", "bn_fwd", "conv_fwd", "bn_fwd", "pool", "head_fwd", "head_bwd", "pool_bwd", "bn_bwd", "conv_dx",
+           "conv_dw", "bn_bwd", "conv_dw"]
+    assert kinds(B.ols_trace(h)) == one + ["step"] + one + ["step_pull", "mean"]
+    B.ols_destroy(h)
+
+
 def test_tiny_refreshes_run_in_line_by_default():
     """OLS_OPT_SERIALIZE defaults to 2: the refresh is overlapped unless it moves at most 1 MiB."""
     for d, stream in ((100, 0), (100000, 1)):
