@@ -124,7 +124,13 @@ def algorithmic_work(cfg, ld, fused_update=True):
         work["conv_dw"] = ("mfma", flops)
         work["pool"] = ("hbm", act)
         work["pool_bwd"] = ("hbm", 2 * act)
-        if cfg.gemm_dtype == "bf16":
+        if cfg.gemm_dtype == "bf16" and cfg.batch_norm:
+            # convolutions: bf16 operands in, fp32 out (the normalisations' input); the delta also reads the bf16 gate
+            work["cast_bf16"] = ("hbm", 1.5 * act)
+            work["conv_fwd_bytes"] = 1.5 * act
+            work["conv_dx_bytes"] = 2.0 * act
+            work["conv_dw_bytes"] = 1.0 * act
+        elif cfg.gemm_dtype == "bf16":
             # bytes of the tensors each launch has to touch once (bf16 operands are half an fp32 tensor; the border the
             # kernels store with them is overhead, not work): 288 flop per byte for a bf16-in, bf16-out convolution,
             # just below the 312 flop per byte ridge, so min(matrix peak, AI x HBM peak) is reported beside the peak
@@ -146,6 +152,9 @@ def algorithmic_work(cfg, ld, fused_update=True):
             work["bn_fwd"] = ("hbm", 3.5 * act)
             # the sums read dy and z, the gradient at z reads both again and writes over dy
             work["bn_bwd"] = ("hbm", 5 * act)
+            if cfg.gemm_dtype == "bf16":   # a1 and the gradients at z leave as bf16 operands (half a tensor each)
+                work["bn_fwd"] = ("hbm", 3.25 * act)
+                work["bn_bwd"] = ("hbm", 4.5 * act)
     return work
 
 
@@ -440,7 +449,7 @@ def main():
                        and not args.opt and args.loop == "library" and not args.no_kernel_timing and args.tau is None
                        and not args.calibration_copy_mib)
     if args.side_configs is None:
-        sides = [1, 2, 3, 5, 6, 7, 8] if (args.config == 4 and default_options) else []
+        sides = [1, 2, 3, 5, 6, 7, 8, 9] if (args.config == 4 and default_options) else []
     else:
         sides = [int(t) for t in args.side_configs.split(",") if t.strip()]
 

@@ -104,11 +104,10 @@ __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const float* _
 struct PaddedOut {
     uint16_t* base;          // nullptr: the fp32 output is written instead
     int64_t stride;          // per group, bf16 elements
-    FastDiv div_c4, div_hw, div_w;
+    FastDiv div_hw, div_w;
     int H, W;
 };
-__device__ __forceinline__ void store_padded_bf16(const PaddedOut& po, int g, unsigned v, int C, f4 o) {
-    const unsigned pix = fast_div(v, po.div_c4), c4 = v - pix * (unsigned)(C / 4);
+__device__ __forceinline__ void store_padded_bf16(const PaddedOut& po, int g, unsigned pix, unsigned c4, int C, f4 o) {
     const unsigned n = fast_div(pix, po.div_hw), rem = pix - n * (unsigned)(po.H * po.W);
     const unsigned y = fast_div(rem, po.div_w), x = rem - y * (unsigned)po.W;
     const int64_t q = ((int64_t)n * (po.H + 2) + y + 1) * (po.W + 2) + x + 1;
@@ -123,11 +122,13 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restr
                                                             const float* __restrict__ stats, const float* __restrict__ gamma,
                                                             const float* __restrict__ beta, int64_t s_par,
                                                             const float* __restrict__ shortcut, int64_t s_sc, float* out,
-                                                            int64_t s_out, int64_t vecs, int C, int relu, PaddedOut po) {
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+                                                            int64_t s_out, unsigned vecs, int C, int relu, FastDiv div_c4,
+                                                            PaddedOut po) {
+    const unsigned v = blockIdx.x * kThreads + threadIdx.x;
     if (v >= vecs) return;
     const int g = blockIdx.y;
-    const int c = 4 * (int)(v % (C / 4));
+    const unsigned pixel = fast_div(v, div_c4);
+    const int c = 4 * (int)(v - pixel * (unsigned)(C / 4));
     const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + c);
     const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + c);
     const f4 ga = *(const f4*)(gamma + (int64_t)g * s_par + c);
@@ -141,15 +142,34 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restr
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = fmaxf(o[e], 0.0f);
     }
-    if (po.base) store_padded_bf16(po, g, (unsigned)v, C, o);
+    if (po.base) store_padded_bf16(po, g, pixel, c / 4, C, o);
     else *((f4*)(out + (int64_t)g * s_out) + v) = o;
+}
+
+// The gradient at a normalised output that sits under global average pooling and a ReLU need not be stored: it is
+// dpool[sample][c] * scale where the activation is positive, else 0 -- formed here from the activation and the pooled
+// gradient wherever the backward kernels would read dy.
+struct PooledDelta {
+    const float* gate;       // nullptr: dy is read instead
+    const float* dpool;      // [group][sample][C]
+    int64_t s_gate, s_dp;
+    float scale;             // 1 / positions
+    FastDiv div_pos;         // pixel -> sample
+};
+__device__ __forceinline__ f4 pooled_delta(const PooledDelta& pd, int g, unsigned pixel, int C, int c4) {
+    const f4 a = __builtin_nontemporal_load((const f4*)(pd.gate + (int64_t)g * pd.s_gate + (int64_t)pixel * C + 4 * c4));
+    const f4 d = *(const f4*)(pd.dpool + (int64_t)g * pd.s_dp + (int64_t)fast_div(pixel, pd.div_pos) * C + 4 * c4);
+    f4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = a[e] > 0.0f ? d[e] * pd.scale : 0.0f;
+    return o;
 }
 
 // part[group][range][2][C]: sum dy, sum dy xhat over the range
 __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float* __restrict__ dy, int64_t s_dy,
                                                                   const float* __restrict__ z, int64_t s_z,
                                                                   const float* __restrict__ stats, float* part, int P, int C,
-                                                                  int ranges) {
+                                                                  int ranges, PooledDelta pd) {
     __shared__ f4 lds[kThreads];
     const int c4n = C / 4, stripes = kThreads / c4n;
     const int c4 = threadIdx.x % c4n, stripe = threadIdx.x / c4n;
@@ -164,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float* _
         const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + 4 * c4);
 #pragma unroll 4
         for (int p = p_lo + stripe; p < p_hi; p += stripes) {
-            const f4 d = __builtin_nontemporal_load((const f4*)(D + (int64_t)p * C + 4 * c4));
+            const f4 d = pd.gate ? pooled_delta(pd, g, (unsigned)p, C, c4) : __builtin_nontemporal_load((const f4*)(D + (int64_t)p * C + 4 * c4));
             const f4 xh = (__builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C + 4 * c4)) - mean) * istd;
             s1 = s1 + d;
             s2 = s2 + d * xh;
@@ -203,24 +223,25 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const float* __r
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(float* dy, int64_t s_dy, const float* __restrict__ z,
                                                                 int64_t s_z, const float* __restrict__ stats,
                                                                 const float* __restrict__ sums,
-                                                                const float* __restrict__ gamma, int64_t s_par, int64_t vecs,
-                                                                int C, float inv_count, PaddedOut po) {
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+                                                                const float* __restrict__ gamma, int64_t s_par, unsigned vecs,
+                                                                int C, float inv_count, FastDiv div_c4, PaddedOut po, PooledDelta pd) {
+    const unsigned v = blockIdx.x * kThreads + threadIdx.x;
     if (v >= vecs) return;
     const int g = blockIdx.y;
-    const int c = 4 * (int)(v % (C / 4));
+    const unsigned pixel = fast_div(v, div_c4);
+    const int c = 4 * (int)(v - pixel * (unsigned)(C / 4));
     const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + c);
     const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + c);
     const f4 s1 = *(const f4*)(sums + ((int64_t)g * 2) * C + c);
     const f4 s2 = *(const f4*)(sums + ((int64_t)g * 2 + 1) * C + c);
     const f4 ga = *(const f4*)(gamma + (int64_t)g * s_par + c);
     f4* D = (f4*)(dy + (int64_t)g * s_dy) + v;
-    const f4 d = __builtin_nontemporal_load(D);
+    const f4 d = pd.gate ? pooled_delta(pd, g, pixel, C, c / 4) : __builtin_nontemporal_load(D);
     const f4 xh = (__builtin_nontemporal_load((const f4*)(z + (int64_t)g * s_z) + v) - mean) * istd;
     f4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = ga[e] * istd[e] * (d[e] - s1[e] * inv_count - xh[e] * (s2[e] * inv_count));
-    if (po.base) store_padded_bf16(po, g, (unsigned)v, C, o);   // dy itself stays as it was
+    if (po.base) store_padded_bf16(po, g, pixel, c / 4, C, o);   // dy itself stays as it was
     else *D = o;
 }
 
@@ -232,16 +253,16 @@ bool shape_ok(int groups, int P, int C) { return groups >= 1 && groups <= 65535 
 bool padded_out(const BnArgs& a, int64_t vecs, PaddedOut* po) {
     if (!a.out_bf16) return true;
     if (a.H < 1 || a.W < 1 || a.P % (a.H * a.W) != 0 || (reinterpret_cast<uintptr_t>(a.out_bf16) & 7u) || a.s_outb % 4 ||
-        vecs >= ((int64_t)1 << 31))
+        vecs >= ((int64_t)1 << 31) - kThreads)
         return false;
     po->base = a.out_bf16; po->stride = a.s_outb; po->H = a.H; po->W = a.W;
-    po->div_c4 = make_div((unsigned)(a.C / 4)); po->div_hw = make_div((unsigned)(a.H * a.W)); po->div_w = make_div((unsigned)a.W);
+    po->div_hw = make_div((unsigned)(a.H * a.W)); po->div_w = make_div((unsigned)a.W);
     return true;
 }
 
-bool vec_grid(int64_t vecs, unsigned* blocks) {
+bool vec_grid(int64_t vecs, unsigned* blocks) {   // 31-bit vector indices (the kernels divide them by multiplication)
     const int64_t b = (vecs + kThreads - 1) / kThreads;
-    if (b < 1 || b > 0x7FFFFFFF) return false;
+    if (b < 1 || vecs >= ((int64_t)1 << 31) - kThreads) return false;
     *blocks = (unsigned)b;
     return true;
 }
@@ -269,18 +290,26 @@ hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
     PaddedOut po = {};
     if (!padded_out(a, vecs, &po)) return hipErrorInvalidValue;
     bn_apply_kernel<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.z, a.s_z, a.stats, a.gamma, a.beta, a.s_par, a.shortcut,
-                                                                          a.s_sc, a.out, a.s_out, vecs, a.C, a.relu, po);
+                                                                          a.s_sc, a.out, a.s_out, (unsigned)vecs, a.C, a.relu, make_div((unsigned)(a.C / 4)), po);
     return hipGetLastError();
 }
 
 hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s) {
-    if (!shape_ok(a.groups, a.P, a.C) || !a.z || !a.dy || !a.stats || !a.part || !a.sums || !a.gamma || !a.g) return hipErrorInvalidValue;
+    if (!shape_ok(a.groups, a.P, a.C) || !a.z || (!a.dy && !(a.gate && a.out_bf16)) || !a.stats || !a.part || !a.sums || !a.gamma || !a.g) return hipErrorInvalidValue;
     if (!aligned16(a.z) || !aligned16(a.dy) || !aligned16(a.stats) || !aligned16(a.part) || !aligned16(a.sums) ||
         !aligned16(a.gamma) || a.s_z % 4 || a.s_dy % 4 || a.s_par % 4)
         return hipErrorInvalidValue;
     const int ranges = bn_ranges(a.P);
+    PooledDelta pd = {};
+    if (a.gate) {
+        if (!a.dpool || a.positions < 1 || a.P % a.positions != 0 || !aligned16(a.gate) || !aligned16(a.dpool) || a.s_gate % 4 || a.s_dp % 4)
+            return hipErrorInvalidValue;
+        pd.gate = a.gate; pd.dpool = a.dpool; pd.s_gate = a.s_gate; pd.s_dp = a.s_dp;
+        pd.scale = 1.0f / (float)a.positions;
+        pd.div_pos = make_div((unsigned)a.positions);
+    }
     bn_bwd_partial_kernel<<<dim3((unsigned)ranges, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.part,
-                                                                                         a.P, a.C, ranges);
+                                                                                         a.P, a.C, ranges, pd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     bn_bwd_final_kernel<<<dim3((unsigned)((a.C + kThreads - 1) / kThreads), (unsigned)a.groups), kThreads, 0, s>>>(
@@ -293,7 +322,7 @@ hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s) {
     PaddedOut po = {};
     if (!padded_out(a, vecs, &po)) return hipErrorInvalidValue;
     bn_bwd_apply_kernel<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.sums, a.gamma,
-                                                                              a.s_par, vecs, a.C, 1.0f / (float)a.P, po);
+                                                                              a.s_par, (unsigned)vecs, a.C, 1.0f / (float)a.P, make_div((unsigned)(a.C / 4)), po, pd);
     return hipGetLastError();
 }
 

@@ -571,13 +571,12 @@ int conv_gradients_bn_bf16(ols_ctx* c) {
     ha.C = c->cv_classes;
     if ((rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); }))) return rc;
     if ((rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); }))) return rc;
-    if ((rc = enqueue(c, OLS_K_POOL_BWD, 0, -1, -1, [&](hipStream_t s) {
-             return launch_pool_bwd(dpool, (int64_t)B * C, a2, act, dn, act, m, B, H * W, C, s);
-         })))
-        return rc;
-    {   // through the second normalisation: scale / shift gradients; the gradient at z2 goes out as the bf16 operand dz2
+    {   // through the pooling, the second ReLU and the second normalisation: the gradient at the normalised output is
+        // dpool / positions where a2 > 0 and is formed on the fly; scale / shift gradients; the gradient at z2 goes out as
+        // the bf16 operand dz2
         BnArgs a = nbase;
-        a.z = z2; a.dy = dn; a.out_bf16 = dz2; a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
+        a.z = z2; a.gate = a2; a.s_gate = act; a.dpool = dpool; a.s_dp = (int64_t)B * C; a.positions = H * W;
+        a.out_bf16 = dz2; a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
         if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
     }
     {   // gradient at the first normalised output: transposed convolution of dz2 through Wb, gated by a1 > 0
@@ -686,13 +685,16 @@ int conv_gradients(ols_ctx* c) {
     ha.C = c->cv_classes;
     if ((rc = enqueue(c, OLS_K_HEAD_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_fwd(ha, s); }))) return rc;
     if ((rc = enqueue(c, OLS_K_HEAD_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_head_bwd(ha, s); }))) return rc;
-    if ((rc = enqueue(c, OLS_K_POOL_BWD, 0, -1, -1, [&](hipStream_t s) {
-             return launch_pool_bwd(dpool, (int64_t)B * C, a2, act, dz2, act, m, B, H * W, C, s);
-         })))
-        return rc;
-    if (bn) {   // through the second normalisation: scale / shift gradients, then dz2 becomes the gradient at z2
+    if (!bn) {
+        if ((rc = enqueue(c, OLS_K_POOL_BWD, 0, -1, -1, [&](hipStream_t s) {
+                 return launch_pool_bwd(dpool, (int64_t)B * C, a2, act, dz2, act, m, B, H * W, C, s);
+             })))
+            return rc;
+    } else {   // through the pooling, the second ReLU and the second normalisation: the gradient at the normalised output
+               // (dpool / positions where a2 > 0) is formed on the fly; scale / shift gradients; dz2 = the gradient at z2
         BnArgs a = nbase;
-        a.z = z2; a.dy = dz2; a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
+        a.z = z2; a.dy = dz2; a.gate = a2; a.s_gate = act; a.dpool = dpool; a.s_dp = (int64_t)B * C; a.positions = H * W;
+        a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
         if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
     }
     {   // delta at a1: transposed convolution of dz2 through Wb, gated by a1 > 0

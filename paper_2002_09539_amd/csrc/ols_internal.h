@@ -271,6 +271,13 @@ struct BnArgs {
     uint16_t* out_bf16;
     int64_t s_outb;
     int H, W;
+    // Optional (bwd): the normalised output sits under a ReLU and global average pooling, so the gradient on entry is
+    // dpool[group][sample][c] / positions where gate (the activation, [group][P][C]) is positive and 0 elsewhere; it is
+    // formed on the fly and dy is only written (the gradient at z), or not touched at all with out_bf16.
+    const float* gate;
+    const float* dpool;
+    int64_t s_gate, s_dp;
+    int positions;
 };
 hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s);    // statistics (two launches) + normalise
 hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s);   // sums (two launches) + gradient at z

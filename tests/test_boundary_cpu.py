@@ -560,7 +560,7 @@ def test_convblock_with_batch_norm_attachment_and_launch_plan():
     B.ols_local_step(h)
     B.ols_sync_pull(h)
     B.ols_anchor_update_async(h)
-    one = ["conv_fwd", "bn_fwd", "conv_fwd", "bn_fwd", "pool", "head_fwd", "head_bwd", "pool_bwd", "bn_bwd", "conv_dx",
+    one = ["conv_fwd", "bn_fwd", "conv_fwd", "bn_fwd", "pool", "head_fwd", "head_bwd", "bn_bwd", "conv_dx",
            "conv_dw", "bn_bwd", "conv_dw"]
     assert kinds(B.ols_trace(h)) == one + ["step"] + one + ["step_pull", "mean"]
     B.ols_destroy(h)
@@ -622,7 +622,7 @@ def test_convblock_bn_bf16_attachment_and_launch_plan():
     B.ols_local_step(h)
     B.ols_sync_pull(h)
     B.ols_anchor_update_async(h)
-    one = ["cast_bf16", "conv_fwd", "bn_fwd", "conv_fwd", "bn_fwd", "pool", "head_fwd", "head_bwd", "pool_bwd", "bn_bwd", "conv_dx",
+    one = ["cast_bf16", "conv_fwd", "bn_fwd", "conv_fwd", "bn_fwd", "pool", "head_fwd", "head_bwd", "bn_bwd", "conv_dx",
            "conv_dw", "bn_bwd", "conv_dw"]
     assert kinds(B.ols_trace(h)) == one + ["step"] + one + ["step_pull", "mean"]
     B.ols_destroy(h)
