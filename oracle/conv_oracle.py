@@ -224,20 +224,22 @@ def convblock_bn_loss_grad(x, C, classes, X, labels, eps=BN_EPS, bf16_operands=F
     return loss, g
 
 
-def convblock_relu_margin(x, C, classes, X, batch_norm=False, eps=BN_EPS):
+def convblock_relu_margin(x, C, classes, X, batch_norm=False, eps=BN_EPS, bf16_operands=False):
     """Smallest |input of a ReLU| in the block's forward pass.  The loss is not differentiable where such an input is
     zero: a device computing in single precision may take the other branch when the margin is within its rounding, and
     one activation taken the other way moves the gradient by about 1 / sqrt(number of activations) of its norm.  Parity
-    cases use this to show that their inputs sit away from those points."""
+    cases use this to show that their inputs sit away from those points.  bf16_operands: the forward pass of the
+    diagnostic mode of the module header."""
+    q = round_to_bf16 if bf16_operands else (lambda a: np.asarray(a, F64))
     x = np.asarray(x, F64)
     X = np.asarray(X, F64)
     if batch_norm:
         Wa, ga, ba, Wb, gb, bb, _, _ = convblock_bn_unpack(x, C, classes)
         zero = np.zeros(C)
-        n1 = batchnorm_forward(conv3x3_forward(X, Wa, zero), ga, ba, eps)[0]
-        n2 = batchnorm_forward(conv3x3_forward(np.maximum(n1, 0.0), Wb, zero), gb, bb, eps)[0] + X
+        n1 = batchnorm_forward(conv3x3_forward(q(X), q(Wa), zero), ga, ba, eps)[0]
+        n2 = batchnorm_forward(conv3x3_forward(q(np.maximum(n1, 0.0)), q(Wb), zero), gb, bb, eps)[0] + X
     else:
         Wa, ba, Wb, bb, _, _ = convblock_unpack(x, C, classes)
-        n1 = conv3x3_forward(X, Wa, ba)
-        n2 = conv3x3_forward(np.maximum(n1, 0.0), Wb, bb) + X
+        n1 = conv3x3_forward(q(X), q(Wa), ba)
+        n2 = conv3x3_forward(q(np.maximum(n1, 0.0)), q(Wb), bb) + X
     return float(min(np.abs(n1).min(), np.abs(n2).min()))

@@ -98,6 +98,55 @@ __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const float* _
     stats[((int64_t)g * 2 + 1) * C + c] = 1.0f / sqrtf(var + eps);
 }
 
+// The same statistics from per-wavefront parts that a convolution's epilogue left: wpart[group][w][3][C] = count, mean
+// and sum of squared deviations of the image pixels among 64 consecutive padded pixels (count 0: none).  Thirty-two
+// lanes per channel merge every thirty-second part each, in order, by the parallel-variance rule (eight parts are
+// requested at a time: the merge itself is a dependent chain, the loads are not); lane 0 of the channel then merges
+// the thirty-two results in lane order.
+constexpr int kWaveStatChannels = 8, kWaveStatStripes = kThreads / kWaveStatChannels, kWaveStatBatch = 8;
+__global__ __launch_bounds__(kThreads) void bn_stats_waves_kernel(const float* __restrict__ wpart, int64_t s_wpart, float* stats,
+                                                                  int C, int waves, float eps) {
+    __shared__ float lds[3][kThreads];
+    const int cl = threadIdx.x % kWaveStatChannels, stripe = threadIdx.x / kWaveStatChannels;
+    const int c = blockIdx.x * kWaveStatChannels + cl, g = blockIdx.y;
+    float n = 0.0f, mean = 0.0f, m2 = 0.0f;
+    auto merge = [&](float nr, float mean_r, float m2_r) {
+        if (nr > 0.0f) {
+            const float tot = n + nr, delta = mean_r - mean;
+            mean = mean + delta * (nr / tot);
+            m2 = m2 + m2_r + delta * delta * (n * (nr / tot));
+            n = tot;
+        }
+    };
+    if (c < C) {
+        const float* P = wpart + (int64_t)g * s_wpart + c;
+        for (int w0 = stripe; w0 < waves; w0 += kWaveStatStripes * kWaveStatBatch) {
+            float nr[kWaveStatBatch], mr[kWaveStatBatch], qr[kWaveStatBatch];
+#pragma unroll
+            for (int u = 0; u < kWaveStatBatch; ++u) {
+                const int w = w0 + u * kWaveStatStripes;
+                const float* o = P + (int64_t)(w < waves ? w : 0) * 3 * C;
+                nr[u] = w < waves ? o[0] : 0.0f;
+                mr[u] = o[C];
+                qr[u] = o[2 * C];
+            }
+#pragma unroll
+            for (int u = 0; u < kWaveStatBatch; ++u) merge(nr[u], mr[u], qr[u]);
+        }
+    }
+    lds[0][threadIdx.x] = n;
+    lds[1][threadIdx.x] = mean;
+    lds[2][threadIdx.x] = m2;
+    __syncthreads();
+    if (stripe == 0 && c < C) {
+        for (int s = 1; s < kWaveStatStripes; ++s)
+            merge(lds[0][s * kWaveStatChannels + cl], lds[1][s * kWaveStatChannels + cl], lds[2][s * kWaveStatChannels + cl]);
+        const float var = fmaxf(m2 / n, 0.0f);
+        stats[((int64_t)g * 2) * C + c] = mean;
+        stats[((int64_t)g * 2 + 1) * C + c] = 1.0f / sqrtf(var + eps);
+    }
+}
+
 // Where a result becomes the operand of a bf16 convolution it is written as bf16 (to nearest even) into that operand's
 // layout: [B (H + 2) (W + 2)][C] with a border that nobody writes (it is zero from the start).  Vector v = four channels
 // of the unpadded pixel v / (C / 4).
@@ -276,14 +325,23 @@ hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
     if (!aligned16(a.z) || !aligned16(a.out) || !aligned16(a.stats) || !aligned16(a.part) || !aligned16(a.gamma) ||
         !aligned16(a.beta) || !aligned16(a.shortcut) || a.s_z % 4 || a.s_out % 4 || a.s_par % 4 || a.s_sc % 4)
         return hipErrorInvalidValue;
-    const int ranges = bn_ranges(a.P);
-    bn_stats_partial_kernel<<<dim3((unsigned)ranges, (unsigned)a.groups), kThreads, 0, s>>>(a.z, a.s_z, a.part, a.P, a.C, ranges);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    bn_stats_final_kernel<<<dim3((unsigned)((a.C + kThreads - 1) / kThreads), (unsigned)a.groups), kThreads, 0, s>>>(
-        a.part, a.stats, a.P, a.C, ranges, a.eps);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e;
+    if (a.wave_part) {   // the producer of z left per-wavefront statistics: z is not read for them
+        if (a.waves < 1 || !aligned16(a.wave_part)) return hipErrorInvalidValue;
+        bn_stats_waves_kernel<<<dim3((unsigned)((a.C + kWaveStatChannels - 1) / kWaveStatChannels), (unsigned)a.groups), kThreads, 0, s>>>(
+            a.wave_part, (int64_t)a.waves * 3 * a.C, a.stats, a.C, a.waves, a.eps);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    } else {
+        const int ranges = bn_ranges(a.P);
+        bn_stats_partial_kernel<<<dim3((unsigned)ranges, (unsigned)a.groups), kThreads, 0, s>>>(a.z, a.s_z, a.part, a.P, a.C, ranges);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        bn_stats_final_kernel<<<dim3((unsigned)((a.C + kThreads - 1) / kThreads), (unsigned)a.groups), kThreads, 0, s>>>(
+            a.part, a.stats, a.P, a.C, ranges, a.eps);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     unsigned blocks;
     const int64_t vecs = (int64_t)a.P * (a.C / 4);
     if (!vec_grid(vecs, &blocks)) return hipErrorInvalidValue;

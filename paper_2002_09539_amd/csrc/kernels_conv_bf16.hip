@@ -90,6 +90,8 @@ struct ConvBDev {
     const float* xres;       // FWD with the fused tail: the shortcut, fp32 [B H W][C]
     uint8_t* sign;           // FWD with the fused tail: [Pp][C / 4] sign bytes
     float* pool_part;        // FWD with the fused tail: [groups][tiles_m * 4 wavefronts][2][C] partial sums of the pooling
+    float* stat_part;        // FWD with the unpadded fp32 output, optional: [groups][tiles_m * 4 wavefronts][3][C] per-wavefront
+                             // statistics of the output's image pixels (count, mean, sum of squared deviations)
     int64_t s_x, s_sign;
     int64_t s_in, s_w, s_dout, s_out, s_bias, s_mask;
     int groups, B, H, W, C, Hp, Wp, Pp, halo;
@@ -435,6 +437,53 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
                 }
                 if constexpr (OUT == kOutF32U) buf_store(o, out_rs, (unsigned)up[t] * 2u * row_bytes + col_off);   // border rows: dropped
                 else buf_store(o, out_rs, out_off + (t0 + t) * out_step);                                           // rows past the tensor are dropped
+            }
+        }
+        if constexpr (MODE == 0 && OUT == kOutF32U) {
+            // Statistics of the wavefront's image pixels for the batch normalisation that follows (which then need not
+            // read the output again): count, mean, and the sum of squared deviations from that mean, per channel.  Two
+            // passes over the staged rows; the four lanes of a channel quad are combined through the staging area's
+            // tail in lane order.  A later pass merges the wavefronts in wavefront order (the parallel-variance rule).
+            if (p.stat_part) {
+                const int r0 = lane / kVecPerRow, cq = lane % kVecPerRow;
+                f4* red = (f4*)(stage + WR * FP) - 64;        // the last 64 vectors of the wavefront's staging rows ...
+                f4 sum = {0.f, 0.f, 0.f, 0.f};
+                float cnt = 0.0f;
+                f4 zv[kPer];
+                bool img[kPer];
+#pragma unroll
+                for (int t = 0; t < kPer; ++t) {
+                    zv[t] = *(const f4*)(stage + (r0 + 4 * t) * FP + cq * 4);
+                    img[t] = row_up[wm0 + r0 + 4 * t] >= 0;
+                    if (img[t]) { sum = sum + zv[t]; cnt += 1.0f; }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();              // ... which every lane has read by now
+                red[lane] = sum;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                const f4 tot = ((red[cq] + red[16 + cq]) + red[32 + cq]) + red[48 + cq];
+                const float n = ((__shfl(cnt, cq) + __shfl(cnt, 16 + cq)) + __shfl(cnt, 32 + cq)) + __shfl(cnt, 48 + cq);
+                const float inv_n = n > 0.0f ? 1.0f / n : 0.0f;
+                f4 mean;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) mean[e] = tot[e] * inv_n;
+                f4 dev = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int t = 0; t < kPer; ++t)
+                    if (img[t]) { const f4 d = zv[t] - mean; dev = dev + d * d; }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                red[lane] = dev;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                if (lane < kVecPerRow) {
+                    const f4 m2 = ((red[lane] + red[16 + lane]) + red[32 + lane]) + red[48 + lane];
+                    float* SP3 = p.stat_part + ((((int64_t)group * p.tiles_m + tm) * 4 + wave) * 3) * C + n0 + 4 * lane;
+                    *(f4*)SP3 = f4{n, n, n, n};
+                    *(f4*)(SP3 + C) = mean;
+                    *(f4*)(SP3 + 2 * C) = m2;
+                }
             }
         }
     } else {
@@ -809,6 +858,10 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
     p.mask = MODE == 1 ? (const uint16_t*)a.mask : nullptr;
     p.s_in = a.s_in; p.s_w = a.s_w; p.s_out = a.s_out; p.s_bias = a.s_bias; p.s_mask = a.s_mask;
     if (tail) { p.xres = a.xres; p.s_x = a.s_x; p.sign = a.sign; p.s_sign = a.s_sign; p.pool_part = a.pool_part; }
+    if (a.stat_part) {
+        if (MODE != 0 || !a.out_unpadded || !aligned16(a.stat_part)) return hipErrorInvalidValue;
+        p.stat_part = a.stat_part;
+    }
     constexpr int BM = kBM;   // 128 (three workgroups per compute unit, 134 registers) measured 8 - 19 % slower: halo 1.55x
     p.tiles_m = (p.Pp + BM - 1) / BM;
     p.tiles_n = a.C / kCB;
@@ -920,6 +973,11 @@ hipError_t launch_shortcut_relu_pool(const float* y, int64_t s_y, const float* X
     shortcut_relu_pool_kernel<<<dim3((unsigned)B, (unsigned)groups), kThreads, 0, s>>>(
         y, s_y, X, s_x, pooled, s_p, sign, s_sign, H, W, C, make_div((unsigned)(W + 2)), 1.0f / (float)(H * W));
     return hipGetLastError();
+}
+
+int64_t conv3x3_bf16_stat_part_floats(int B, int H, int W, int C) {
+    const int64_t Pp = (int64_t)B * (H + 2) * (W + 2);
+    return ((Pp + kBM - 1) / kBM) * 4 * 3 * C;   // per group
 }
 
 int64_t conv3x3_bf16_pool_part_floats(int B, int H, int W, int C) {

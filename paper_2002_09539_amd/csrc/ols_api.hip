@@ -97,7 +97,7 @@ struct ols_ctx {
     bool cv_bn = false;     // convolutions without bias, each followed by batch normalisation
     float cv_eps = 1e-5f;
     int64_t off_a1 = 0, off_a2 = 0, off_dz1 = 0, off_dz2 = 0, off_pooled = 0, off_dpool = 0, off_cpartial = 0;
-    int64_t off_z1 = 0, off_z2 = 0, off_bnstats = 0, off_bnsums = 0, off_bnpart = 0, off_dn = 0;
+    int64_t off_z1 = 0, off_z2 = 0, off_bnstats = 0, off_bnsums = 0, off_bnpart = 0, off_dn = 0, off_wstat = 0;
     const float* X = nullptr;
     const void* y = nullptr;
     int64_t xs = 0, ys = 0;
@@ -346,6 +346,7 @@ void plan_workspace(ols_ctx* c) {
         c->off_bnstats = take(2 * m * 2 * c->cv_C * 4);
         c->off_bnsums = take(m * 2 * c->cv_C * 4);
         c->off_bnpart = take(bn_partial_floats(c->m, c->B * c->cv_H * c->cv_W, c->cv_C) * 4);
+        c->off_wstat = take(m * conv3x3_bf16_stat_part_floats(c->B, c->cv_H, c->cv_W, c->cv_C) * 4);
         c->off_shadow = take(m * c->ld * 2);
     } else if (c->model == MODEL_CONV && c->gemm_dtype == 1) {
         // operand tensors are bf16 and carry their zero border; the second activation (pooled, and the mask of the
@@ -522,6 +523,9 @@ int conv_gradients_bn_bf16(ols_ctx* c) {
     nbase.sums = (float*)(c->ws + c->off_bnsums);
     float* stats1 = (float*)(c->ws + c->off_bnstats);
     float* stats2 = stats1 + (int64_t)m * 2 * C;
+    // the convolutions leave the statistics of their output per wavefront (64 padded pixels): the normalisations merge those
+    float* wstat = (float*)(c->ws + c->off_wstat);
+    const int waves = (int)(conv3x3_bf16_stat_part_floats(B, H, W, C) / (3 * C));
     int rc;
     if ((rc = enqueue(c, OLS_K_CAST, 0, -1, -1, [&](hipStream_t s) {
              return launch_pad_cast_bf16(c->X, c->xs, xb, padded, m, B, H, W, C, s);
@@ -529,22 +533,23 @@ int conv_gradients_bn_bf16(ols_ctx* c) {
         return rc;
     {   // z1 = conv(X; Wa)
         ConvBArgs a = base;
-        a.in = xb; a.s_in = padded; a.w = shadow + wa; a.out = z1; a.s_out = act; a.out_f32 = 1; a.out_unpadded = 1;
+        a.in = xb; a.s_in = padded; a.w = shadow + wa; a.out = z1; a.s_out = act; a.out_f32 = 1; a.out_unpadded = 1; a.stat_part = wstat;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
     }
     {   // a1 = bf16(relu(bn(z1)))
         BnArgs a = nbase;
-        a.z = z1; a.out_bf16 = a1; a.stats = stats1; a.gamma = xc + ga; a.beta = xc + ba; a.relu = 1;
+        a.z = z1; a.out_bf16 = a1; a.stats = stats1; a.gamma = xc + ga; a.beta = xc + ba; a.relu = 1; a.wave_part = wstat; a.waves = waves;
         if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
     }
     {   // z2 = conv(a1; Wb)
         ConvBArgs a = base;
-        a.in = a1; a.s_in = padded; a.w = shadow + wb; a.out = z2; a.s_out = act; a.out_f32 = 1; a.out_unpadded = 1;
+        a.in = a1; a.s_in = padded; a.w = shadow + wb; a.out = z2; a.s_out = act; a.out_f32 = 1; a.out_unpadded = 1; a.stat_part = wstat;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
     }
     {   // a2 = relu(bn(z2) + X)
         BnArgs a = nbase;
         a.z = z2; a.out = a2; a.stats = stats2; a.gamma = xc + gb; a.beta = xc + bb; a.shortcut = c->X; a.s_sc = c->xs; a.relu = 1;
+        a.wave_part = wstat; a.waves = waves;
         if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
     }
     if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {

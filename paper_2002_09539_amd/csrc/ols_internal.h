@@ -212,6 +212,9 @@ struct ConvBArgs {
                             // bare convolution + bias in fp32 with border rows as computed (their consumer skips them)
     int out_f32;
     int out_unpadded;       // with out_f32 (fwd and dx): fp32 [B H W][C], image pixels only -- what a batch normalisation reads
+    float* stat_part;       // fwd with out_unpadded, optional: conv3x3_bf16_stat_part_floats(...) floats per group; per 64
+                            // padded pixels (count, mean, sum of squared deviations) [3][C] of the output's image pixels,
+                            // which launch_bn_forward takes instead of reading the output for its statistics
     const float* bias;      // fwd: [C] per group, or nullptr
     const void* mask;       // dx: padded bf16 activations whose sign gates the result, or nullptr
     float* partial;         // dw: scratch of conv3x3_bf16_dw_splits(...) * groups * (9 C C + C) floats
@@ -235,6 +238,7 @@ hipError_t launch_conv3x3_bf16_dx(const ConvBArgs& a, hipStream_t s);
 hipError_t launch_conv3x3_bf16_dw(const ConvBArgs& a, hipStream_t s);
 int conv3x3_bf16_dw_splits(int groups, int B, int H, int W, int C);
 int64_t conv3x3_bf16_pool_part_floats(int B, int H, int W, int C);   // per group
+int64_t conv3x3_bf16_stat_part_floats(int B, int H, int W, int C);   // per group
 // pooled[g][sample][c] = mean over the positions of a2, from the partial sums of the forward kernel's fused tail
 hipError_t launch_pool_finish(const float* part, float* pooled, int64_t s_p, int groups, int B, int H, int W, int C, hipStream_t s);
 // fp32 [groups][B H W][C] -> bf16 [groups][B (H+2) (W+2)][C] with a zero border
@@ -278,6 +282,10 @@ struct BnArgs {
     const float* dpool;
     int64_t s_gate, s_dp;
     int positions;
+    // Optional (fwd): per-wavefront statistics that the producer of z left (ConvBArgs::stat_part), [group][waves][3][C]:
+    // the statistics are merged from them and z is read only once, by the normalisation itself.
+    const float* wave_part;
+    int waves;
 };
 hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s);    // statistics (two launches) + normalise
 hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s);   // sums (two launches) + gradient at z
