@@ -195,22 +195,90 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(const float* __restr
     else *((f4*)(out + (int64_t)g * s_out) + v) = o;
 }
 
+// The block's tail in the normalisation: a = relu(gamma (z - mean) inv_std + beta + shortcut) is not stored -- its sign
+// bytes and its channel sums per 64 consecutive pixels are (two slots per part: the sample of the part's first pixel and
+// the next one; H W >= 64, so there is no third).  A workgroup owns 64 pixels: lane = (channel quad, stripe), four
+// pixels per lane in flight, stripes combined in stripe order.
+constexpr int kTailPixels = 64;
+__global__ __launch_bounds__(kThreads) void bn_tail_kernel(const float* __restrict__ z, int64_t s_z, const float* __restrict__ stats,
+                                                           const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                           int64_t s_par, const float* __restrict__ shortcut, int64_t s_sc,
+                                                           uint8_t* sign, int64_t s_sign, float* pool_part, int P, int C, int relu,
+                                                           int per, FastDiv div_per) {
+    __shared__ f4 lds[kThreads];
+    const int c4n = C / 4, stripes = kThreads / c4n;
+    const int c4 = threadIdx.x % c4n, stripe = threadIdx.x / c4n;
+    const int g = blockIdx.y, w = blockIdx.x;
+    const int p0 = w * kTailPixels;
+    const int next_sample = ((int)fast_div((unsigned)p0, div_per) + 1) * per;   // first pixel of the second slot's sample
+    f4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
+    if (stripe < stripes) {
+        const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + 4 * c4);
+        const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + 4 * c4);
+        const f4 ga = *(const f4*)(gamma + (int64_t)g * s_par + 4 * c4);
+        const f4 be = *(const f4*)(beta + (int64_t)g * s_par + 4 * c4);
+        const float* Z = z + (int64_t)g * s_z + 4 * c4;
+        const float* S = shortcut ? shortcut + (int64_t)g * s_sc + 4 * c4 : nullptr;
+        uint8_t* SG = sign + (int64_t)g * s_sign + c4;
+        for (int q0 = stripe; q0 < kTailPixels; q0 += 4 * stripes) {
+            f4 zv[4], sv[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int p = p0 + q0 + t * stripes;
+                const bool in = q0 + t * stripes < kTailPixels && p < P;
+                zv[t] = in ? __builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C)) : f4{0.f, 0.f, 0.f, 0.f};
+                sv[t] = in && S ? __builtin_nontemporal_load((const f4*)(S + (int64_t)p * C)) : f4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int p = p0 + q0 + t * stripes;
+                if (q0 + t * stripes >= kTailPixels || p >= P) continue;
+                f4 o;
+                unsigned bits = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    o[e] = __fmaf_rn(ga[e], (zv[t][e] - mean[e]) * istd[e], be[e]) + sv[t][e];
+                    if (relu) o[e] = fmaxf(o[e], 0.0f);
+                    bits |= o[e] > 0.0f ? (1u << e) : 0u;
+                }
+                SG[(int64_t)p * c4n] = (uint8_t)bits;
+                if (p < next_sample) s0 = s0 + o; else s1 = s1 + o;
+            }
+        }
+    }
+    s0 = reduce_stripes(s0, lds, c4n, stripes);
+    s1 = reduce_stripes(s1, lds, c4n, stripes);
+    if ((int)threadIdx.x < c4n) {
+        float* o = pool_part + (((int64_t)g * gridDim.x + w) * 2) * C + 4 * c4;
+        *(f4*)o = s0;
+        *(f4*)(o + C) = s1;
+    }
+}
+
 // The gradient at a normalised output that sits under global average pooling and a ReLU need not be stored: it is
 // dpool[sample][c] * scale where the activation is positive, else 0 -- formed here from the activation and the pooled
 // gradient wherever the backward kernels would read dy.
 struct PooledDelta {
-    const float* gate;       // nullptr: dy is read instead
+    const float* gate;       // the activation, or
+    const uint8_t* sign;     // one byte per pixel and four channels, bit e set iff it is positive; both nullptr: dy is read
     const float* dpool;      // [group][sample][C]
     int64_t s_gate, s_dp;
     float scale;             // 1 / positions
     FastDiv div_pos;         // pixel -> sample
 };
+__device__ __forceinline__ bool has_pooled_delta(const PooledDelta& pd) { return pd.gate || pd.sign; }
 __device__ __forceinline__ f4 pooled_delta(const PooledDelta& pd, int g, unsigned pixel, int C, int c4) {
-    const f4 a = __builtin_nontemporal_load((const f4*)(pd.gate + (int64_t)g * pd.s_gate + (int64_t)pixel * C + 4 * c4));
     const f4 d = *(const f4*)(pd.dpool + (int64_t)g * pd.s_dp + (int64_t)fast_div(pixel, pd.div_pos) * C + 4 * c4);
     f4 o;
+    if (pd.sign) {
+        const unsigned bits = pd.sign[(int64_t)g * pd.s_gate + (int64_t)pixel * (C / 4) + c4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = a[e] > 0.0f ? d[e] * pd.scale : 0.0f;
+        for (int e = 0; e < 4; ++e) o[e] = (bits >> e) & 1u ? d[e] * pd.scale : 0.0f;
+    } else {
+        const f4 a = __builtin_nontemporal_load((const f4*)(pd.gate + (int64_t)g * pd.s_gate + (int64_t)pixel * C + 4 * c4));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = a[e] > 0.0f ? d[e] * pd.scale : 0.0f;
+    }
     return o;
 }
 
@@ -233,7 +301,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float* _
         const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + 4 * c4);
 #pragma unroll 4
         for (int p = p_lo + stripe; p < p_hi; p += stripes) {
-            const f4 d = pd.gate ? pooled_delta(pd, g, (unsigned)p, C, c4) : __builtin_nontemporal_load((const f4*)(D + (int64_t)p * C + 4 * c4));
+            const f4 d = has_pooled_delta(pd) ? pooled_delta(pd, g, (unsigned)p, C, c4) : __builtin_nontemporal_load((const f4*)(D + (int64_t)p * C + 4 * c4));
             const f4 xh = (__builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C + 4 * c4)) - mean) * istd;
             s1 = s1 + d;
             s2 = s2 + d * xh;
@@ -285,7 +353,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(float* dy, int64
     const f4 s2 = *(const f4*)(sums + ((int64_t)g * 2 + 1) * C + c);
     const f4 ga = *(const f4*)(gamma + (int64_t)g * s_par + c);
     f4* D = (f4*)(dy + (int64_t)g * s_dy) + v;
-    const f4 d = pd.gate ? pooled_delta(pd, g, pixel, C, c / 4) : __builtin_nontemporal_load(D);
+    const f4 d = has_pooled_delta(pd) ? pooled_delta(pd, g, pixel, C, c / 4) : __builtin_nontemporal_load(D);
     const f4 xh = (__builtin_nontemporal_load((const f4*)(z + (int64_t)g * s_z) + v) - mean) * istd;
     f4 o;
 #pragma unroll
@@ -321,7 +389,7 @@ bool vec_grid(int64_t vecs, unsigned* blocks) {   // 31-bit vector indices (the 
 int64_t bn_partial_floats(int groups, int P, int C) { return (int64_t)groups * bn_ranges(P) * 3 * C; }
 
 hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
-    if (!shape_ok(a.groups, a.P, a.C) || !a.z || (!a.out && !a.out_bf16) || !a.stats || !a.part || !a.gamma || !a.beta) return hipErrorInvalidValue;
+    if (!shape_ok(a.groups, a.P, a.C) || !a.z || (!a.out && !a.out_bf16 && !a.pool_part) || !a.stats || !a.part || !a.gamma || !a.beta) return hipErrorInvalidValue;
     if (!aligned16(a.z) || !aligned16(a.out) || !aligned16(a.stats) || !aligned16(a.part) || !aligned16(a.gamma) ||
         !aligned16(a.beta) || !aligned16(a.shortcut) || a.s_z % 4 || a.s_out % 4 || a.s_par % 4 || a.s_sc % 4)
         return hipErrorInvalidValue;
@@ -342,6 +410,13 @@ hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    if (a.pool_part) {   // the block's tail: sign bytes and partial sums instead of the activation
+        if (!a.sign || a.positions < kTailPixels || a.P % a.positions != 0 || !aligned16(a.pool_part) || a.C > 4 * kThreads) return hipErrorInvalidValue;
+        bn_tail_kernel<<<dim3((unsigned)((a.P + kTailPixels - 1) / kTailPixels), (unsigned)a.groups), kThreads, 0, s>>>(
+            a.z, a.s_z, a.stats, a.gamma, a.beta, a.s_par, a.shortcut, a.s_sc, a.sign, a.s_sign, a.pool_part, a.P, a.C, a.relu, a.positions,
+            make_div((unsigned)a.positions));
+        return hipGetLastError();
+    }
     unsigned blocks;
     const int64_t vecs = (int64_t)a.P * (a.C / 4);
     if (!vec_grid(vecs, &blocks)) return hipErrorInvalidValue;
@@ -353,16 +428,17 @@ hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s) {
-    if (!shape_ok(a.groups, a.P, a.C) || !a.z || (!a.dy && !(a.gate && a.out_bf16)) || !a.stats || !a.part || !a.sums || !a.gamma || !a.g) return hipErrorInvalidValue;
+    if (!shape_ok(a.groups, a.P, a.C) || !a.z || (!a.dy && !((a.gate || a.sign) && a.out_bf16)) || !a.stats || !a.part || !a.sums || !a.gamma || !a.g) return hipErrorInvalidValue;
     if (!aligned16(a.z) || !aligned16(a.dy) || !aligned16(a.stats) || !aligned16(a.part) || !aligned16(a.sums) ||
         !aligned16(a.gamma) || a.s_z % 4 || a.s_dy % 4 || a.s_par % 4)
         return hipErrorInvalidValue;
     const int ranges = bn_ranges(a.P);
     PooledDelta pd = {};
-    if (a.gate) {
+    if (a.gate || a.sign) {
         if (!a.dpool || a.positions < 1 || a.P % a.positions != 0 || !aligned16(a.gate) || !aligned16(a.dpool) || a.s_gate % 4 || a.s_dp % 4)
             return hipErrorInvalidValue;
-        pd.gate = a.gate; pd.dpool = a.dpool; pd.s_gate = a.s_gate; pd.s_dp = a.s_dp;
+        if (a.sign) { pd.sign = a.sign; pd.s_gate = a.s_sign; } else { pd.gate = a.gate; pd.s_gate = a.s_gate; }
+        pd.dpool = a.dpool; pd.s_dp = a.s_dp;
         pd.scale = 1.0f / (float)a.positions;
         pd.div_pos = make_div((unsigned)a.positions);
     }

@@ -795,9 +795,10 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_bf16_kernel(const float* __
     }
 }
 
-// pooled[g][n][c] = inv * sum of the wavefront sums that the fused tail left for sample n: wavefront w covers the padded
-// pixels 64 w .. 64 w + 63, its first sample is floor(64 w / per), and its two slots are that sample and the next.
-// Added in wavefront order; one lane per (sample, channel quad).
+// pooled[g][n][c] = inv * sum of the partial sums that a fused tail left for sample n: part w covers the pixels
+// 64 w .. 64 w + 63 (padded pixels for the convolution's tail, image pixels for the normalisation's), its first sample
+// is floor(64 w / per) with per pixels per sample, and its two slots are that sample and the next.
+// Added in order of w; one lane per (sample, channel quad).
 __global__ __launch_bounds__(kThreads) void pool_finish_kernel(const float* __restrict__ part, int64_t s_part, float* pooled,
                                                                int64_t s_p, int B, int per, int C, float inv) {
     const int v = blockIdx.x * kThreads + threadIdx.x;
@@ -985,14 +986,15 @@ int64_t conv3x3_bf16_pool_part_floats(int B, int H, int W, int C) {
     return ((Pp + kBM - 1) / kBM) * 4 * 2 * C;   // per group
 }
 
-hipError_t launch_pool_finish(const float* part, float* pooled, int64_t s_p, int groups, int B, int H, int W, int C, hipStream_t s) {
-    if (!part || !pooled || groups < 1 || groups > 65535 || B < 1 || H < 1 || W < 1 || C < 4 || C % 4 || !aligned16(part) ||
-        !aligned16(pooled) || s_p % 4 || (H + 2) * (W + 2) < 64 || (int64_t)B * (H + 2) * (W + 2) >= ((int64_t)1 << 31) - 64)
+hipError_t launch_pool_finish(const float* part, int64_t s_part, float* pooled, int64_t s_p, int groups, int B, int per, int C,
+                              float inv, hipStream_t s) {
+    if (!part || !pooled || groups < 1 || groups > 65535 || B < 1 || C < 4 || C % 4 || !aligned16(part) || !aligned16(pooled) ||
+        s_part % 4 || s_p % 4 || per < 64 || (int64_t)B * per >= ((int64_t)1 << 31) - 64)
         return hipErrorInvalidValue;
     const int64_t lanes = (int64_t)B * (C / 4);
     if (lanes > 0x7FFFFFFF) return hipErrorInvalidValue;
-    pool_finish_kernel<<<dim3((unsigned)((lanes + kThreads - 1) / kThreads), (unsigned)groups), kThreads, 0, s>>>(
-        part, conv3x3_bf16_pool_part_floats(B, H, W, C), pooled, s_p, B, (H + 2) * (W + 2), C, 1.0f / (float)(H * W));
+    pool_finish_kernel<<<dim3((unsigned)((lanes + kThreads - 1) / kThreads), (unsigned)groups), kThreads, 0, s>>>(part, s_part, pooled, s_p, B,
+                                                                                                             per, C, inv);
     return hipGetLastError();
 }
 

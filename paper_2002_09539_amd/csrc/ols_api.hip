@@ -431,7 +431,8 @@ int conv_gradients_bf16(ols_ctx* c) {
         a.xres = c->X; a.s_x = c->xs; a.sign = sign; a.s_sign = act / 4; a.pool_part = pool_part;
         if ((rc = enqueue(c, OLS_K_CONV_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_conv3x3_bf16_fwd(a, s); }))) return rc;
         if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
-                 return launch_pool_finish(pool_part, pooled, (int64_t)B * C, m, B, H, W, C, s);
+                 return launch_pool_finish(pool_part, conv3x3_bf16_pool_part_floats(B, H, W, C), pooled, (int64_t)B * C, m, B, positions, C,
+                                           1.0f / (float)(H * W), s);
              })))
             return rc;
     } else {   // images too small for the fused tail's two-samples-per-wavefront bookkeeping
@@ -526,6 +527,12 @@ int conv_gradients_bn_bf16(ols_ctx* c) {
     // the convolutions leave the statistics of their output per wavefront (64 padded pixels): the normalisations merge those
     float* wstat = (float*)(c->ws + c->off_wstat);
     const int waves = (int)(conv3x3_bf16_stat_part_floats(B, H, W, C) / (3 * C));
+    // Images of at least 64 pixels: a2 is never stored -- the second normalisation leaves its sign (a byte per pixel and
+    // four channels) and its sums per 64 pixels; both live in a2's place
+    const bool tail = H * W >= 64;
+    const int64_t tail_units = ((int64_t)B * H * W + 63) / 64;
+    uint8_t* sign = (uint8_t*)a2;
+    float* tail_part = a2 + ((int64_t)m * (act / 4) + 3) / 4;   // behind the sign bytes of all workers
     int rc;
     if ((rc = enqueue(c, OLS_K_CAST, 0, -1, -1, [&](hipStream_t s) {
              return launch_pad_cast_bf16(c->X, c->xs, xb, padded, m, B, H, W, C, s);
@@ -550,10 +557,12 @@ int conv_gradients_bn_bf16(ols_ctx* c) {
         BnArgs a = nbase;
         a.z = z2; a.out = a2; a.stats = stats2; a.gamma = xc + gb; a.beta = xc + bb; a.shortcut = c->X; a.s_sc = c->xs; a.relu = 1;
         a.wave_part = wstat; a.waves = waves;
+        if (tail) { a.out = nullptr; a.sign = sign; a.s_sign = act / 4; a.pool_part = tail_part; a.positions = H * W; }
         if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
     }
     if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
-             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s);
+             return tail ? launch_pool_finish(tail_part, tail_units * 2 * C, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s)
+                         : launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s);
          })))
         return rc;
     HeadArgs ha = {};
@@ -580,7 +589,8 @@ int conv_gradients_bn_bf16(ols_ctx* c) {
         // dpool / positions where a2 > 0 and is formed on the fly; scale / shift gradients; the gradient at z2 goes out as
         // the bf16 operand dz2
         BnArgs a = nbase;
-        a.z = z2; a.gate = a2; a.s_gate = act; a.dpool = dpool; a.s_dp = (int64_t)B * C; a.positions = H * W;
+        a.z = z2; a.dpool = dpool; a.s_dp = (int64_t)B * C; a.positions = H * W;
+        if (tail) { a.sign = sign; a.s_sign = act / 4; } else { a.gate = a2; a.s_gate = act; }
         a.out_bf16 = dz2; a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
         if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
     }

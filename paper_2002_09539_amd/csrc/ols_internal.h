@@ -239,8 +239,10 @@ hipError_t launch_conv3x3_bf16_dw(const ConvBArgs& a, hipStream_t s);
 int conv3x3_bf16_dw_splits(int groups, int B, int H, int W, int C);
 int64_t conv3x3_bf16_pool_part_floats(int B, int H, int W, int C);   // per group
 int64_t conv3x3_bf16_stat_part_floats(int B, int H, int W, int C);   // per group
-// pooled[g][sample][c] = mean over the positions of a2, from the partial sums of the forward kernel's fused tail
-hipError_t launch_pool_finish(const float* part, float* pooled, int64_t s_p, int groups, int B, int H, int W, int C, hipStream_t s);
+// pooled[g][sample][c] = inv * the sum over the sample's positions, from partial sums [group][w][2][C] per 64 consecutive
+// pixels (slot 0: the sample of pixel 64 w, slot 1: the next one) with `per` (>= 64) pixels per sample
+hipError_t launch_pool_finish(const float* part, int64_t s_part, float* pooled, int64_t s_p, int groups, int B, int per, int C,
+                              float inv, hipStream_t s);
 // fp32 [groups][B H W][C] -> bf16 [groups][B (H+2) (W+2)][C] with a zero border
 hipError_t launch_pad_cast_bf16(const float* src, int64_t s_src, uint16_t* dst, int64_t s_dst, int groups, int B, int H, int W,
                                 int C, hipStream_t s);
@@ -286,6 +288,13 @@ struct BnArgs {
     // the statistics are merged from them and z is read only once, by the normalisation itself.
     const float* wave_part;
     int waves;
+    // Optional (fwd, with shortcut / relu as given; H * W >= 64): the block's tail.  The activation is not stored: `sign`
+    // gets one byte per pixel and four channels ([group][P][C / 4], bit e set iff the activation is positive) and
+    // `pool_part` ([group][ceil(P / 64)][2][C] floats) the activation's sums per 64 pixels for launch_pool_finish.
+    // (bwd) `sign` in place of `gate`: the same bytes say where the activation was positive.
+    uint8_t* sign;
+    float* pool_part;
+    int64_t s_sign;
 };
 hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s);    // statistics (two launches) + normalise
 hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s);   // sums (two launches) + gradient at z
