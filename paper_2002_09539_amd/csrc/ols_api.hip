@@ -651,6 +651,12 @@ int conv_gradients(ols_ctx* c) {
     nbase.sums = (float*)(c->ws + c->off_bnsums);
     float* stats1 = (float*)(c->ws + c->off_bnstats);
     float* stats2 = stats1 + (int64_t)m * 2 * C;
+    // Normalised block on images of at least 64 pixels: a2 is never stored -- the second normalisation leaves its sign (a
+    // byte per pixel and four channels) and its sums per 64 pixels; both live in a2's place
+    const bool tail = bn && H * W >= 64;
+    const int64_t tail_units = ((int64_t)B * H * W + 63) / 64;
+    uint8_t* sign = (uint8_t*)a2;
+    float* tail_part = a2 + ((int64_t)m * (act / 4) + 3) / 4;   // behind the sign bytes of all workers
     int rc;
     {   // first convolution
         ConvArgs a = base;
@@ -674,10 +680,12 @@ int conv_gradients(ols_ctx* c) {
     if (bn) {
         BnArgs a = nbase;
         a.z = z2; a.out = a2; a.stats = stats2; a.gamma = xc + gb; a.beta = xc + bb; a.shortcut = c->X; a.s_sc = c->xs; a.relu = 1;
+        if (tail) { a.out = nullptr; a.sign = sign; a.s_sign = act / 4; a.pool_part = tail_part; a.positions = H * W; }
         if ((rc = enqueue(c, OLS_K_BN_FWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_forward(a, s); }))) return rc;
     }
     if ((rc = enqueue(c, OLS_K_POOL, 0, -1, -1, [&](hipStream_t s) {
-             return launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s);
+             return tail ? launch_pool_finish(tail_part, tail_units * 2 * C, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s)
+                         : launch_pool_mean(a2, act, pooled, (int64_t)B * C, m, B, H * W, C, 1.0f / (float)(H * W), s);
          })))
         return rc;
     HeadArgs ha = {};
@@ -708,7 +716,8 @@ int conv_gradients(ols_ctx* c) {
     } else {   // through the pooling, the second ReLU and the second normalisation: the gradient at the normalised output
                // (dpool / positions where a2 > 0) is formed on the fly; scale / shift gradients; dz2 = the gradient at z2
         BnArgs a = nbase;
-        a.z = z2; a.dy = dz2; a.gate = a2; a.s_gate = act; a.dpool = dpool; a.s_dp = (int64_t)B * C; a.positions = H * W;
+        a.z = z2; a.dy = dz2; a.dpool = dpool; a.s_dp = (int64_t)B * C; a.positions = H * W;
+        if (tail) { a.sign = sign; a.s_sign = act / 4; } else { a.gate = a2; a.s_gate = act; }
         a.stats = stats2; a.gamma = xc + gb; a.g_gamma_off = gb; a.g_beta_off = bb;
         if ((rc = enqueue(c, OLS_K_BN_BWD, 0, c->cur, -1, [&](hipStream_t s) { return launch_bn_backward(a, s); }))) return rc;
     }
