@@ -148,13 +148,24 @@ def algorithmic_work(cfg, ld, fused_update=True):
                 work["pool"] = ("hbm", 2.0 * act + act / 16)            # shortcut + ReLU + pooling: conv output and shortcut in, sign bytes out
             work["pool_bwd"] = ("hbm", 0.5 * act + act / 16)            # sign bytes in, bf16 delta out
         if cfg.batch_norm:
-            # statistics read z, the normalisation reads z (+ the shortcut in the second layer) and writes the activation
-            work["bn_fwd"] = ("hbm", 3.5 * act)
-            # the sums read dy and z, the gradient at z reads both again and writes over dy
-            work["bn_bwd"] = ("hbm", 5 * act)
-            if cfg.gemm_dtype == "bf16":   # a1 and the gradients at z leave as bf16 operands (half a tensor each)
-                work["bn_fwd"] = ("hbm", 3.25 * act)
-                work["bn_bwd"] = ("hbm", 4.5 * act)
+            bf = cfg.gemm_dtype == "bf16"
+            tail = H * W >= 64
+            # Forward, first layer: the statistics read z (not with bf16 operands: the convolution's epilogue left them per
+            # wavefront), the normalisation reads z and writes a1 (half a tensor as a bf16 operand).  Second layer: the
+            # statistics as before; the normalisation reads z and the shortcut and writes a2 -- or, as the block's tail
+            # (images of at least 64 pixels), only a2's sign bytes.  bench.py reports the mean of the two launches.
+            first = (0.0 if bf else 1.0) + 1.0 + (0.5 if bf else 1.0)
+            second = (0.0 if bf else 1.0) + 2.0 + (1.0 / 16 if tail else 1.0)
+            work["bn_fwd"] = ("hbm", (first + second) / 2 * act)
+            # Backward, second layer: the gradient under pooling and ReLU is formed from the pooled gradient and a2 (or its
+            # sign bytes), so the sums read that and z, and the gradient at z reads both again and is written (half a
+            # tensor as a bf16 operand).  First layer: the stored gradient instead of the gate.
+            gate = 1.0 / 16 if tail else 1.0
+            out = 0.5 if bf else 1.0
+            work["bn_bwd"] = ("hbm", ((2 * (gate + 1.0) + out) + (4.0 + out)) / 2 * act)
+            if tail:   # the pooling is a pass over the sums per 64 pixels
+                work["pool"] = ("hbm", 4.0 * m * (-(-(cfg.batch * H * W) // 64) * 2 * C + cfg.batch * C))
+            work.pop("pool_bwd", None)   # no such pass in the normalised blocks
     return work
 
 
