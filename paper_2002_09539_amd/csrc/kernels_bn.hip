@@ -13,6 +13,11 @@
 // combines the ranges in range order (no atomics).  The statistics use shifted sums -- each range subtracts the value of
 // its own first pixel before summing and squaring -- and the ranges are merged with the pairwise update of mean and
 // second moment, so nothing cancels when a channel's mean is large against its spread.
+// Options that take tensor passes out of the block: the statistics can be merged from per-wavefront parts that the
+// producing convolution left (z is then read once, not twice); the second normalisation can be the block's tail (sign
+// bytes and 64-pixel partial sums of the pooling instead of the stored activation); its backward pass can form the
+// gradient under pooling and ReLU on the fly from the pooled gradient and those sign bytes; and a result that becomes a
+// bf16 convolution's operand can be written as bf16 straight into that operand's padded layout.
 #include "fast_div.h"
 #include "gemm_bf16_tile.h"
 #include "ols_internal.h"

@@ -349,8 +349,8 @@ void plan_workspace(ols_ctx* c) {
         c->off_wstat = take(m * conv3x3_bf16_stat_part_floats(c->B, c->cv_H, c->cv_W, c->cv_C) * 4);
         c->off_shadow = take(m * c->ld * 2);
     } else if (c->model == MODEL_CONV && c->gemm_dtype == 1) {
-        // operand tensors are bf16 and carry their zero border; the second activation (pooled, and the mask of the
-        // pooling backward) stays fp32, with the border as well
+        // operand tensors are bf16 and carry their zero border; a2's place holds the pooling's partial sums (or, for
+        // images of fewer than 64 padded pixels, the second convolution's fp32 output with the border)
         const int64_t padded = m * B * (c->cv_H + 2) * (c->cv_W + 2) * c->cv_C;
         c->off_x0 = take(padded * 2);
         c->off_a1 = take(padded * 2);
@@ -390,8 +390,9 @@ void plan_workspace(ols_ctx* c) {
 
 // The plain residual block with bf16 operands: the input batch is converted (and given its zero border) first, the
 // kernels come from the bf16 copy of the parameters, a1 and both deltas are written as bf16; biases, shortcut, a2,
-// pooling and classifier stay fp32.  The second convolution writes conv + bias in fp32; one streaming pass then adds
-// the shortcut, applies the ReLU, pools, and keeps only the sign of a2 (all the backward pass needs of it).
+// pooling and classifier stay fp32.  The second convolution's epilogue adds the shortcut, applies the ReLU and keeps
+// only the sign of a2 (all the backward pass needs of it) and partial sums for the pooling; images of fewer than 64
+// padded pixels take conv + bias in fp32 followed by one streaming pass that does the same.
 int conv_gradients_bf16(ols_ctx* c) {
     const float* xc = c->x[c->cur];
     const uint16_t* shadow = shadow_ptr(c);
