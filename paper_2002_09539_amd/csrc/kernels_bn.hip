@@ -271,23 +271,31 @@ struct PooledDelta {
     float scale;             // 1 / positions
     FastDiv div_pos;         // pixel -> sample
 };
-__device__ __forceinline__ bool has_pooled_delta(const PooledDelta& pd) { return pd.gate || pd.sign; }
-__device__ __forceinline__ f4 pooled_delta(const PooledDelta& pd, int g, unsigned pixel, int C, int c4) {
-    const f4 d = *(const f4*)(pd.dpool + (int64_t)g * pd.s_dp + (int64_t)fast_div(pixel, pd.div_pos) * C + 4 * c4);
-    f4 o;
-    if (pd.sign) {
-        const unsigned bits = pd.sign[(int64_t)g * pd.s_gate + (int64_t)pixel * (C / 4) + c4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bits >> e) & 1u ? d[e] * pd.scale : 0.0f;
+// Where the backward kernels take the gradient at the normalised output from (a template parameter: a branch inside
+// their loops would serialise the loads of one pixel behind the other's)
+enum { kFromDy = 0, kFromGate = 1, kFromSign = 2 };
+template <int SRC>
+__device__ __forceinline__ f4 delta_at(const float* __restrict__ D, const PooledDelta& pd, int g, unsigned pixel, int C, int c4) {
+    if constexpr (SRC == kFromDy) {
+        return __builtin_nontemporal_load((const f4*)(D + (int64_t)pixel * C + 4 * c4));
     } else {
-        const f4 a = __builtin_nontemporal_load((const f4*)(pd.gate + (int64_t)g * pd.s_gate + (int64_t)pixel * C + 4 * c4));
+        const f4 d = *(const f4*)(pd.dpool + (int64_t)g * pd.s_dp + (int64_t)fast_div(pixel, pd.div_pos) * C + 4 * c4);
+        f4 o;
+        if constexpr (SRC == kFromSign) {
+            const unsigned bits = pd.sign[(int64_t)g * pd.s_gate + (int64_t)pixel * (C / 4) + c4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = a[e] > 0.0f ? d[e] * pd.scale : 0.0f;
+            for (int e = 0; e < 4; ++e) o[e] = (bits >> e) & 1u ? d[e] * pd.scale : 0.0f;
+        } else {
+            const f4 a = __builtin_nontemporal_load((const f4*)(pd.gate + (int64_t)g * pd.s_gate + (int64_t)pixel * C + 4 * c4));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = a[e] > 0.0f ? d[e] * pd.scale : 0.0f;
+        }
+        return o;
     }
-    return o;
 }
 
 // part[group][range][2][C]: sum dy, sum dy xhat over the range
+template <int SRC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float* __restrict__ dy, int64_t s_dy,
                                                                   const float* __restrict__ z, int64_t s_z,
                                                                   const float* __restrict__ stats, float* part, int P, int C,
@@ -304,12 +312,21 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_kernel(const float* _
     if (stripe < stripes) {
         const f4 mean = *(const f4*)(stats + ((int64_t)g * 2) * C + 4 * c4);
         const f4 istd = *(const f4*)(stats + ((int64_t)g * 2 + 1) * C + 4 * c4);
-#pragma unroll 4
-        for (int p = p_lo + stripe; p < p_hi; p += stripes) {
-            const f4 d = has_pooled_delta(pd) ? pooled_delta(pd, g, (unsigned)p, C, c4) : __builtin_nontemporal_load((const f4*)(D + (int64_t)p * C + 4 * c4));
-            const f4 xh = (__builtin_nontemporal_load((const f4*)(Z + (int64_t)p * C + 4 * c4)) - mean) * istd;
-            s1 = s1 + d;
-            s2 = s2 + d * xh;
+        for (int p0 = p_lo + stripe; p0 < p_hi; p0 += 4 * stripes) {   // four pixels per lane in flight
+            f4 d[4], zv[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int p = p0 + t * stripes;
+                const unsigned pc = (unsigned)(p < p_hi ? p : p0);       // a lane past the range re-reads its first pixel
+                d[t] = delta_at<SRC>(D, pd, g, pc, C, c4);
+                zv[t] = __builtin_nontemporal_load((const f4*)(Z + (int64_t)pc * C + 4 * c4));
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (p0 + t * stripes >= p_hi) continue;
+                s1 = s1 + d[t];
+                s2 = s2 + d[t] * ((zv[t] - mean) * istd);
+            }
         }
     }
     s1 = reduce_stripes(s1, lds, c4n, stripes);
@@ -342,6 +359,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_final_kernel(const float* __r
 }
 
 // dz = gamma inv_std (dy - s1 / P - xhat s2 / P), written over dy -- or as a bf16 operand (see PaddedOut)
+template <int SRC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(float* dy, int64_t s_dy, const float* __restrict__ z,
                                                                 int64_t s_z, const float* __restrict__ stats,
                                                                 const float* __restrict__ sums,
@@ -358,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(float* dy, int64
     const f4 s2 = *(const f4*)(sums + ((int64_t)g * 2 + 1) * C + c);
     const f4 ga = *(const f4*)(gamma + (int64_t)g * s_par + c);
     f4* D = (f4*)(dy + (int64_t)g * s_dy) + v;
-    const f4 d = has_pooled_delta(pd) ? pooled_delta(pd, g, pixel, C, c / 4) : __builtin_nontemporal_load(D);
+    const f4 d = delta_at<SRC>(dy + (int64_t)g * s_dy, pd, g, pixel, C, c / 4);
     const f4 xh = (__builtin_nontemporal_load((const f4*)(z + (int64_t)g * s_z) + v) - mean) * istd;
     f4 o;
 #pragma unroll
@@ -447,8 +465,10 @@ hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s) {
         pd.scale = 1.0f / (float)a.positions;
         pd.div_pos = make_div((unsigned)a.positions);
     }
-    bn_bwd_partial_kernel<<<dim3((unsigned)ranges, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.part,
-                                                                                         a.P, a.C, ranges, pd);
+    const int src = a.sign ? kFromSign : a.gate ? kFromGate : kFromDy;
+    auto partial = src == kFromSign ? bn_bwd_partial_kernel<kFromSign> : src == kFromGate ? bn_bwd_partial_kernel<kFromGate> : bn_bwd_partial_kernel<kFromDy>;
+    auto apply = src == kFromSign ? bn_bwd_apply_kernel<kFromSign> : src == kFromGate ? bn_bwd_apply_kernel<kFromGate> : bn_bwd_apply_kernel<kFromDy>;
+    partial<<<dim3((unsigned)ranges, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.part, a.P, a.C, ranges, pd);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     bn_bwd_final_kernel<<<dim3((unsigned)((a.C + kThreads - 1) / kThreads), (unsigned)a.groups), kThreads, 0, s>>>(
@@ -460,8 +480,8 @@ hipError_t launch_bn_backward(const BnArgs& a, hipStream_t s) {
     if (!vec_grid(vecs, &blocks)) return hipErrorInvalidValue;
     PaddedOut po = {};
     if (!padded_out(a, vecs, &po)) return hipErrorInvalidValue;
-    bn_bwd_apply_kernel<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.sums, a.gamma,
-                                                                              a.s_par, (unsigned)vecs, a.C, 1.0f / (float)a.P, make_div((unsigned)(a.C / 4)), po, pd);
+    apply<<<dim3(blocks, (unsigned)a.groups), kThreads, 0, s>>>(a.dy, a.s_dy, a.z, a.s_z, a.stats, a.sums, a.gamma, a.s_par, (unsigned)vecs, a.C,
+                                                                1.0f / (float)a.P, make_div((unsigned)(a.C / 4)), po, pd);
     return hipGetLastError();
 }
 
