@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--config", type=int, default=4, help="headline workload number (BASELINE configs are 1-based)")
     ap.add_argument("--side-configs", type=str, default=None,
                     help="comma-separated configurations measured after the headline and reported under \"configs\" "
-                         "(default: 1,2,3,5,6,7,8 when the headline is configuration 4 with default options, else none)")
+                         "(default: 1,2,3,5,6,7,8,9 when the headline is configuration 4 with default options, else none)")
     ap.add_argument("--side-cpu-seconds", type=float, default=3.0,
                     help="target CPU time of the oracle baseline of each side configuration (at least one round)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle baseline; 0 skips it")
