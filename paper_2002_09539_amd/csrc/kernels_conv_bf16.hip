@@ -61,7 +61,11 @@
 // priority (s_setprio) outside or inside the tap loop (+-1 %); the bias loaded straight into the accumulators before the
 // first tap (the eight extra loads in the prologue cost what the epilogue's additions saved); a branch around the late
 // requests of bias / gate activations (the compiler then makes every later wait on a kernel slice wait for them too:
-// +0.8 us per tile).
+// +0.8 us per tile); the first MFMAs of a tile with a zero third operand instead of cleared accumulators (200 instructions
+// less, no change), and all kernel arguments fetched in one scalar round trip at the top instead of five dependent ones
+// (no change either): what remains of the prologue's 2 us is the issue of its 17 vector loads per lane, about 0.1 us
+// each -- with 68 KB per workgroup in flight and 7 - 8 TB/s crossing the L2 during a launch (strips, the 73 KB of
+// kernel slices every tile fetches again, the outputs), the memory pipeline itself is what the loads queue for.
 #include <type_traits>
 
 #include "fast_div.h"
