@@ -47,6 +47,7 @@ def groups_of(C, classes):
     (1, (192, 4, 5, 3), 2),        # three contraction chunks, three output tiles, 3 x 3 blocks of the gradient
     (1, (128, 3, 40, 4), 2),       # the long-halo variants with two chunks / two output tiles, and the fused tail
     (2, (128, 8, 8, 5), 3),        # the fused tail on two output tiles; samples of 100 padded pixels straddle wavefronts
+    (1, (256, 6, 8, 3), 2),        # the widest channel count the block takes: four chunks, four output tiles
 ])
 def test_gradient_and_loss(m, dims, batch):
     cfg, X, labels, x0 = conv_case(m, dims, batch, 1, seed=515)

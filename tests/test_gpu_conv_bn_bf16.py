@@ -53,6 +53,7 @@ RELU_MARGIN = 8e-6          # every ReLU input of a single-step parity case is a
     (1, (192, 4, 5, 3), 2, 525),   # three contraction chunks, three output tiles, 3 x 3 blocks of the gradient
     (1, (128, 3, 40, 4), 2, 527),  # the long-halo variants with two chunks / two output tiles, and the fused tail
     (1, (128, 8, 8, 5), 3, 525),   # the fused tail (64 pixels per image exactly) with two output tiles
+    (1, (256, 6, 8, 3), 2, 526),   # the widest channel count the block takes: four chunks, four output tiles
 ])
 def test_gradient_and_loss(m, dims, batch, seed):
     cfg, X, labels, x0 = conv_case(m, dims, batch, 1, seed=seed)
