@@ -670,27 +670,40 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_dw_bf16_kernel(ConvBDev p
 // ---------------------------------------------------------------------------------------------
 // fp32 [B H W][C] -> bf16 [B (H+2) (W+2)][C] with a zero border; one lane per 8 channels of a padded pixel
 // ---------------------------------------------------------------------------------------------
+constexpr int kPadCastFly = 2;   // 16-byte output vectors per lane
 __global__ __launch_bounds__(kThreads) void pad_cast_bf16_kernel(const float* __restrict__ src, int64_t s_src,
-                                                                 uint16_t* __restrict__ dst, int64_t s_dst, int64_t vecs, int H,
-                                                                 int W, int C) {
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (v >= vecs) return;
+                                                                 uint16_t* __restrict__ dst, int64_t s_dst, unsigned vecs, int H,
+                                                                 int W, int C, FastDiv div_c8, FastDiv div_per, FastDiv div_wp) {
     const int g = blockIdx.y;
-    const int c8 = C / 8;
-    const int q = (int)(v / c8), cv = (int)(v % c8);
-    const int Wp = W + 2, per = (H + 2) * Wp;
-    const int n = q / per, rem = q - n * per;
-    const int y = rem / Wp, x = rem - y * Wp;
-    u4 o = {0u, 0u, 0u, 0u};
-    if (y >= 1 && y <= H && x >= 1 && x <= W) {
-        const f4* S = (const f4*)(src + (int64_t)g * s_src + ((int64_t)(n * H + y - 1) * W + (x - 1)) * C) + 2 * cv;
-        const f4 lo = __builtin_nontemporal_load(S), hi = __builtin_nontemporal_load(S + 1);
-        o.x = pack2(lo.x, lo.y);
-        o.y = pack2(lo.z, lo.w);
-        o.z = pack2(hi.x, hi.y);
-        o.w = pack2(hi.z, hi.w);
+    const unsigned c8 = (unsigned)C / 8, Wp = (unsigned)W + 2, per = (unsigned)(H + 2) * Wp;
+    f4 lo[kPadCastFly], hi[kPadCastFly];
+    bool img[kPadCastFly];
+#pragma unroll
+    for (int t = 0; t < kPadCastFly; ++t) {   // the loads of all the lane's vectors before the first store
+        const unsigned v = (blockIdx.x * kPadCastFly + t) * kThreads + threadIdx.x;
+        const unsigned q = fast_div(v < vecs ? v : 0u, div_c8), cv = (v < vecs ? v : 0u) - q * c8;
+        const unsigned n = fast_div(q, div_per), rem = q - n * per;
+        const unsigned y = fast_div(rem, div_wp), x = rem - y * Wp;
+        img[t] = v < vecs && y >= 1 && y <= (unsigned)H && x >= 1 && x <= (unsigned)W;
+        if (img[t]) {
+            const f4* S = (const f4*)(src + (int64_t)g * s_src + ((int64_t)(n * H + y - 1) * W + (x - 1)) * C) + 2 * cv;
+            lo[t] = __builtin_nontemporal_load(S);
+            hi[t] = __builtin_nontemporal_load(S + 1);
+        }
     }
-    *((u4*)(dst + (int64_t)g * s_dst) + v) = o;
+#pragma unroll
+    for (int t = 0; t < kPadCastFly; ++t) {
+        const unsigned v = (blockIdx.x * kPadCastFly + t) * kThreads + threadIdx.x;
+        if (v >= vecs) continue;
+        u4 o = {0u, 0u, 0u, 0u};
+        if (img[t]) {   // round to nearest even (v_cvt_pk_bf16_f32)
+            o.x = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{lo[t][0], lo[t][1]}, bf16x2));
+            o.y = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{lo[t][2], lo[t][3]}, bf16x2));
+            o.z = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{hi[t][0], hi[t][1]}, bf16x2));
+            o.w = __builtin_bit_cast(unsigned, __builtin_convertvector(f2v{hi[t][2], hi[t][3]}, bf16x2));
+        }
+        *((u4*)(dst + (int64_t)g * s_dst) + v) = o;
+    }
 }
 
 // The block's tail in one streaming pass: a2 = relu(y + X) for the image pixels of one (sample, worker), its mean over
@@ -963,9 +976,11 @@ hipError_t launch_pad_cast_bf16(const float* src, int64_t s_src, uint16_t* dst, 
         !aligned16(dst) || s_src % 4 || s_dst % 8)
         return hipErrorInvalidValue;
     const int64_t vecs = (int64_t)B * (H + 2) * (W + 2) * (C / 8);
-    const int64_t blocks = (vecs + kThreads - 1) / kThreads;
-    if (blocks > 0x7FFFFFFF || vecs / (C / 8) > 0x7FFFFFFF) return hipErrorInvalidValue;
-    pad_cast_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)groups), kThreads, 0, s>>>(src, s_src, dst, s_dst, vecs, H, W, C);
+    if (vecs >= ((int64_t)1 << 31) - kPadCastFly * kThreads) return hipErrorInvalidValue;   // the divisions by multiplication take 31-bit dividends
+    const int64_t blocks = (vecs + kPadCastFly * kThreads - 1) / (kPadCastFly * kThreads);
+    pad_cast_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)groups), kThreads, 0, s>>>(
+        src, s_src, dst, s_dst, (unsigned)vecs, H, W, C, make_div((unsigned)(C / 8)), make_div((unsigned)((H + 2) * (W + 2))),
+        make_div((unsigned)(W + 2)));
     return hipGetLastError();
 }
 
