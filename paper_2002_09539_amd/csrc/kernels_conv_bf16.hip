@@ -121,8 +121,6 @@ __device__ __forceinline__ bool interior(const ConvBDev& p, int q, int* unpadded
     return y >= 1 && y <= p.H && x >= 1 && x <= p.W;
 }
 
-__device__ __forceinline__ unsigned int pack2(float a, float b) { return bf16_bits_rne(a) | (bf16_bits_rne(b) << 16); }
-
 // ---------------------------------------------------------------------------------------------
 // forward (MODE 0) and back-propagated delta (MODE 1)
 // ---------------------------------------------------------------------------------------------
