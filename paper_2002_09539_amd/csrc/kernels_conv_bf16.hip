@@ -71,7 +71,6 @@
 #include "fast_div.h"
 #include "gemm_bf16_tile.h"
 #include "ols_internal.h"
-#include "update_rule.h"
 
 namespace ols {
 
