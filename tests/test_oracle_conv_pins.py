@@ -459,3 +459,27 @@ def test_bf16_operand_mode_of_the_bn_block_matches_torch_with_the_same_rounding_
     # teeth: leaving one delta unrounded is a different computation
     _, tg_wrong = _torch_bf16_bn_block(x, C, classes, X, labels, round_d_z2=False)
     assert np.abs(g - tg_wrong).max() > 1e-6 * np.abs(g).max()
+
+
+@pytest.mark.parametrize("batch_norm", [False, True])
+def test_relu_margin_in_the_bf16_mode_matches_torch_with_the_same_rounding_points(batch_norm):
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+
+    def rnd(t):
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    x, C, classes, X, labels = (bn_block_case if batch_norm else block_case)(92, B=3, C=4, H=5, Wd=4, classes=3)
+    tX = torch.tensor(X).permute(0, 3, 1, 2)
+    if batch_norm:
+        Wa, ga, ba, Wb, gb, bb, _, _ = (torch.tensor(np.array(v)) for v in CO.convblock_bn_unpack(x, C, classes))
+        bn = lambda z, g_, b_: F.batch_norm(z, None, None, g_, b_, training=True, eps=CO.BN_EPS)
+        n1 = bn(F.conv2d(rnd(tX), rnd(Wa).permute(3, 2, 0, 1), None, padding=1), ga, ba)
+        n2 = bn(F.conv2d(rnd(F.relu(n1)), rnd(Wb).permute(3, 2, 0, 1), None, padding=1), gb, bb) + tX
+    else:
+        Wa, ba, Wb, bb, _, _ = (torch.tensor(np.array(v)) for v in CO.convblock_unpack(x, C, classes))
+        n1 = F.conv2d(rnd(tX), rnd(Wa).permute(3, 2, 0, 1), ba, padding=1)
+        n2 = F.conv2d(rnd(F.relu(n1)), rnd(Wb).permute(3, 2, 0, 1), bb, padding=1) + tX
+    want = min(n1.abs().min().item(), n2.abs().min().item())
+    got = CO.convblock_relu_margin(x, C, classes, X, batch_norm=batch_norm, bf16_operands=True)
+    assert abs(got - want) <= 1e-12
+    assert got != CO.convblock_relu_margin(x, C, classes, X, batch_norm=batch_norm)      # the mode does round
