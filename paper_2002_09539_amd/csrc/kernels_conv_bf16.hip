@@ -74,6 +74,21 @@
 
 namespace ols {
 
+// Measurement builds only (-DOLS_CONV_PHASE_PROBE): lane 0 of every forward / delta workgroup leaves s_memrealtime
+// readings (100 MHz) at six points of its tile, which ols_debug_conv_phases() copies out.  [kernel: 0 forward with
+// bf16 output, 1 forward with another output, 2 delta][tile][point].  Without the flag nothing of this exists.
+#ifdef OLS_CONV_PHASE_PROBE
+constexpr int kProbeTiles = 16384;
+__device__ unsigned long long conv_phase_probe[3][kProbeTiles][8];
+#define OLS_TP(k)                                                                                             \
+    do {                                                                                                      \
+        if (threadIdx.x == 0 && tile < kProbeTiles)                                                           \
+            conv_phase_probe[MODE == 1 ? 2 : (OUT == kOutBf16 ? 0 : 1)][tile][k] = wall_clock64();            \
+    } while (0)
+#else
+#define OLS_TP(k) do { } while (0)
+#endif
+
 namespace {
 
 constexpr int kThreads = kTileThreads;
@@ -160,6 +175,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
 
     const int tile = xcd_tile(p.chunk, p.total_tiles);
     if (tile < 0) return;
+    OLS_TP(0);   // first instruction after the tile is known
     const int per_group = p.tiles_m * p.tiles_n;
     const int group = (int)fast_div((unsigned)tile, p.div_pg);
     const int in_group = tile - group * per_group;
@@ -280,6 +296,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
             load_strip(rs, c0);
 #pragma unroll
             for (int t = 1; t < kAhead; ++t) load_b(rb[t], t, c0);
+            OLS_TP(1);   // the chunk's loads are issued
             if (c0 == 0) {
                 int up;   // which rows of the tile are image pixels (the others get the zero border)
                 const int q = m0 + threadIdx.x;
@@ -292,6 +309,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
             store_strip(rs);
         }
         __syncthreads();
+        OLS_TP(2);   // the strip is in LDS
 #pragma unroll
         for (int tap = 0; tap < 9; ++tap) {
             if (tap + kAhead < 9) load_b(rb[tap % kAhead], tap + kAhead, c0);   // its slice is in LDS already
@@ -315,6 +333,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
         }
     }
 
+    OLS_TP(3);   // the taps are done
     if (kMaskTap >= 9) {
         if constexpr (MODE == 1) load_mask(); else load_bias();
     }
@@ -533,6 +552,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
             buf_store(o, out_rs, own_off + t * step8);   // rows past the tensor are dropped
         }
     }
+    OLS_TP(4);   // the tile's stores are issued
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -921,6 +941,19 @@ hipError_t conv_launch(const ConvBArgs& a, hipStream_t s) {
 }
 
 }  // namespace
+
+#ifdef OLS_CONV_PHASE_PROBE
+// dst[3][tiles][8] on the host: the readings of the last launch of each of the three kernels (see conv_phase_probe)
+extern "C" __attribute__((visibility("default"))) int ols_debug_conv_phases(unsigned long long* dst, int tiles) {
+    if (!dst || tiles < 1 || tiles > kProbeTiles) return -1;
+    if (hipDeviceSynchronize() != hipSuccess) return -2;
+    for (int k = 0; k < 3; ++k)
+        if (hipMemcpyFromSymbol(dst + (size_t)k * tiles * 8, HIP_SYMBOL(conv_phase_probe), (size_t)tiles * 8 * sizeof(unsigned long long),
+                                (size_t)k * kProbeTiles * 8 * sizeof(unsigned long long), hipMemcpyDeviceToHost) != hipSuccess)
+            return -3;
+    return 0;
+}
+#endif
 
 hipError_t launch_conv3x3_bf16_fwd(const ConvBArgs& a, hipStream_t s) { return conv_launch<0>(a, s); }
 hipError_t launch_conv3x3_bf16_dx(const ConvBArgs& a, hipStream_t s) { return conv_launch<1>(a, s); }
