@@ -20,9 +20,9 @@ inline FastDiv make_div(unsigned d) {
 }
 
 // q / d for 0 <= q < 2^31
-__device__ __forceinline__ unsigned fast_div(unsigned q, const FastDiv& d) {
+__host__ __device__ __forceinline__ unsigned fast_div(unsigned q, const FastDiv& d) {
     if (d.shift == 0) return q;   // d = 1
-    const unsigned t = __umulhi(q, d.magic);
+    const unsigned t = (unsigned)(((unsigned long long)q * d.magic) >> 32);   // one v_mul_hi_u32 on the device
     return (t + ((q - t) >> 1)) >> (d.shift - 1);
 }
 
