@@ -42,12 +42,12 @@ __device__ __forceinline__ void buf_store(u4 v, rsrc_t r, unsigned lane_off) { _
 
 
 // K-contiguous operand tile: memory [rows][K]; LDS [ROWS][BK + 8].
-template <int ROWS, int BK>
+template <int ROWS, int BK, int THREADS = kTileThreads>
 struct TileKC {
     static constexpr int kPitch = BK + 8;                 // bf16 elements; 16-byte aligned rows
     static constexpr int kVecPerLine = BK / 8;
     static constexpr int kVecs = ROWS * kVecPerLine;
-    static constexpr int kPerThread = (kVecs + kTileThreads - 1) / kTileThreads;
+    static constexpr int kPerThread = (kVecs + THREADS - 1) / THREADS;
     static constexpr int kElems = ROWS * kPitch;
     // Every lane ALWAYS issues its loads (out-of-range lanes re-read the operand's first vector) and the
     // zero fill is applied when the registers are written to LDS: no branch around the loads, so a later
@@ -57,9 +57,9 @@ struct TileKC {
         unsigned okmask = 0;
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
-            const int v = threadIdx.x + t * kTileThreads;
+            const int v = threadIdx.x + t * THREADS;
             const int row = row0 + v / kVecPerLine, k = k0 + (v % kVecPerLine) * 8;
-            const bool ok = (kVecs % kTileThreads == 0 || v < kVecs) && row < rows && k < klen;
+            const bool ok = (kVecs % THREADS == 0 || v < kVecs) && row < rows && k < klen;
             r[t] = *(const u4*)(base + (ok ? (int64_t)row * ld + k : 0));
             okmask |= ok ? (1u << t) : 0u;
         }
@@ -68,8 +68,8 @@ struct TileKC {
     __device__ static void store(uint16_t* lds, const u4 (&r)[kPerThread], unsigned okmask) {
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
-            const int v = threadIdx.x + t * kTileThreads;
-            if (kVecs % kTileThreads == 0 || v < kVecs) {
+            const int v = threadIdx.x + t * THREADS;
+            if (kVecs % THREADS == 0 || v < kVecs) {
                 const u4 zero = {0u, 0u, 0u, 0u};
                 *(u4*)(lds + (v / kVecPerLine) * kPitch + (v % kVecPerLine) * 8) = (okmask >> t) & 1u ? r[t] : zero;
             }
@@ -81,7 +81,7 @@ struct TileKC {
     }
     // Full tiles (no bounds): vector t of a lane is kLineStep lines below vector 0, so one 32-bit lane offset
     // plus wave-uniform bases address all of them and the loop carries no per-lane address arithmetic.
-    static constexpr int kLineStep = kTileThreads / kVecPerLine;
+    static constexpr int kLineStep = THREADS / kVecPerLine;
     __device__ static unsigned lane_offset_bytes(int ld) {
         return 2u * ((threadIdx.x / kVecPerLine) * (unsigned)ld + (threadIdx.x % kVecPerLine) * 8u);
     }
@@ -94,21 +94,21 @@ struct TileKC {
 };
 
 // Row-contiguous operand tile: memory [K][rows]; LDS [BK][ROWS + 32], read with the transpose load.
-template <int ROWS, int BK>
+template <int ROWS, int BK, int THREADS = kTileThreads>
 struct TileRC {
     static constexpr int kPitch = ROWS + 32;              // pitch = 64 bytes mod 256: the 4 k-rows of a read hit distinct banks
     static constexpr int kVecPerLine = ROWS / 8;
     static constexpr int kVecs = BK * kVecPerLine;
-    static constexpr int kPerThread = (kVecs + kTileThreads - 1) / kTileThreads;
+    static constexpr int kPerThread = (kVecs + THREADS - 1) / THREADS;
     static constexpr int kElems = BK * kPitch;
     __device__ static unsigned load(u4 (&r)[kPerThread], const uint16_t* __restrict__ base, int ld, int row0, int k0,
                                     int rows, int klen) {
         unsigned okmask = 0;
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
-            const int v = threadIdx.x + t * kTileThreads;
+            const int v = threadIdx.x + t * THREADS;
             const int k = k0 + v / kVecPerLine, row = row0 + (v % kVecPerLine) * 8;
-            const bool ok = (kVecs % kTileThreads == 0 || v < kVecs) && row < rows && k < klen;
+            const bool ok = (kVecs % THREADS == 0 || v < kVecs) && row < rows && k < klen;
             r[t] = *(const u4*)(base + (ok ? (int64_t)k * ld + row : 0));
             okmask |= ok ? (1u << t) : 0u;
         }
@@ -117,8 +117,8 @@ struct TileRC {
     __device__ static void store(uint16_t* lds, const u4 (&r)[kPerThread], unsigned okmask) {
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
-            const int v = threadIdx.x + t * kTileThreads;
-            if (kVecs % kTileThreads == 0 || v < kVecs) {
+            const int v = threadIdx.x + t * THREADS;
+            if (kVecs % THREADS == 0 || v < kVecs) {
                 const u4 zero = {0u, 0u, 0u, 0u};
                 *(u4*)(lds + (v / kVecPerLine) * kPitch + (v % kVecPerLine) * 8) = (okmask >> t) & 1u ? r[t] : zero;
             }
@@ -132,7 +132,7 @@ struct TileRC {
         const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(p + 4 * kPitch));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
-    static constexpr int kLineStep = kTileThreads / kVecPerLine;   // k-rows between consecutive vectors of a lane
+    static constexpr int kLineStep = THREADS / kVecPerLine;   // k-rows between consecutive vectors of a lane
     __device__ static unsigned lane_offset_bytes(int ld) {
         return 2u * ((threadIdx.x / kVecPerLine) * (unsigned)ld + (threadIdx.x % kVecPerLine) * 8u);
     }

@@ -42,6 +42,12 @@ enum GemmMode { kFwd = 0, kDw = 1, kDa = 2 };
 
 constexpr int kThreads = kTileThreads;
 constexpr int kXcds = 8;
+// Lanes of the full-tile forward / delta kernel.  Eight wavefronts of 64 x 64 (two per SIMD, which cover each other's
+// LDS waits, at 4/3 of the fragment bytes per MFMA) against four of 128 x 64, measured on 256 x 128 tiles at batch 256:
+// delta GEMM (both operands K-contiguous, 16-byte fragment reads) 48.7 against 54.0 us, forward GEMM (weights read with
+// the 8-byte transpose loads, twice as many read instructions per byte) 58.4 against 54.5 us.
+template <int MODE, int BM>
+constexpr int full_tile_threads() { return (MODE == kDa && BM == 256) ? 512 : 256; }
 
 __device__ __forceinline__ unsigned int bf16_rne(float f) { return bf16_bits_rne(f); }
 __device__ __forceinline__ float bf16_to_f32(unsigned int h) { return __uint_as_float(h << 16); }
@@ -61,10 +67,10 @@ struct GemmDevB {
     HeadDwDev guest;     // DW: output-layer gradients computed by the first guest.blocks workgroups (0: none)
 };
 
-template <int MODE, int BM, int BN, int BK>
+template <int MODE, int BM, int BN, int BK, int THREADS = kThreads>
 struct GemmShape {
-    using TA = typename std::conditional<MODE == kDw, TileRC<BM, BK>, TileKC<BM, BK>>::type;   // FWD, DA: A[M][K]; DW: A[K][M]
-    using TB = typename std::conditional<MODE == kDa, TileKC<BN, BK>, TileRC<BN, BK>>::type;   // DA: W[N][K]; FWD, DW: B[K][N]
+    using TA = typename std::conditional<MODE == kDw, TileRC<BM, BK, THREADS>, TileKC<BM, BK, THREADS>>::type;   // FWD, DA: A[M][K]; DW: A[K][M]
+    using TB = typename std::conditional<MODE == kDa, TileKC<BN, BK, THREADS>, TileRC<BN, BK, THREADS>>::type;   // DA: W[N][K]; FWD, DW: B[K][N]
     static constexpr int kOperandElems = 2 * TA::kElems + 2 * TB::kElems;
     static constexpr int kStagePitch = BN + 8;            // bf16 output tile staged for 16-byte stores
     static constexpr int kStageElems = MODE == kDw ? 0 : BM * kStagePitch;
@@ -324,25 +330,26 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_kernel(GemmDevB p) {
 
 
 // ---------------------------------------------------------------------------------------------
-// FWD / DA on full tiles: M % BM == 0, N % BN == 0, K % (NSETS BK) == 0.  One workgroup per compute unit, one
-// wavefront per SIMD: nothing else is resident to fill a stall, and a wavefront that has just issued an
-// MFMA cannot issue the next one for 32 cycles, so every other instruction of the loop (fragment reads,
-// the next slices' global loads, the LDS stores of the staged slice) is placed BETWEEN the MFMAs, one or
-// two per MFMA, with scheduling-group barriers.  Per K slice of 64 and wavefront: 32 MFMAs, 32 fragment
+// FWD / DA on full tiles: M % BM == 0, N % BN == 0, K % (NSETS BK) == 0.  One workgroup per compute unit with one
+// or two wavefronts per SIMD (THREADS = 256 or 512): little else is resident to fill a stall, and a wavefront that
+// has just issued an MFMA cannot issue the next one for 32 cycles, so every other instruction of the loop (fragment
+// reads, the next slices' global loads, the LDS stores of the staged slice) is placed BETWEEN the MFMAs, one or
+// two per MFMA, with scheduling-group barriers.  Per K slice of 64 and wavefront of 128 x 64: 32 MFMAs, 32 fragment
 // reads, 12 global loads, 12 LDS stores, one workgroup barrier; addresses are one lane offset plus
 // wave-uniform bases, so the loop has no vector address arithmetic.
 // ---------------------------------------------------------------------------------------------
-template <int MODE, int BM, int BN, int BK, int NSETS>
-__global__ __launch_bounds__(kThreads) void gemm_bf16_full_kernel(GemmDevB p) {
+template <int MODE, int BM, int BN, int BK, int NSETS, int THREADS>
+__global__ __launch_bounds__(THREADS) void gemm_bf16_full_kernel(GemmDevB p) {
     static_assert(MODE != kDw && BK == 64, "forward / delta GEMM, four k-steps per slice");
     static_assert(NSETS % 2 == 0, "the LDS buffer of a slice is its parity");
-    constexpr int WM = BM / 2, WN = BN / 2;     // 2 x 2 wavefronts
+    constexpr int kWaveRows = THREADS / 128;    // wavefronts: kWaveRows x 2
+    constexpr int WM = BM / kWaveRows, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
-    using Shape = GemmShape<MODE, BM, BN, BK>;
+    using Shape = GemmShape<MODE, BM, BN, BK, THREADS>;
     using TA = typename Shape::TA;
     using TB = typename Shape::TB;
     constexpr int NA = TA::kPerThread, NB = TB::kPerThread;
-    static_assert(TA::kVecs % kThreads == 0 && TB::kVecs % kThreads == 0, "whole vectors per lane");
+    static_assert(TA::kVecs % THREADS == 0 && TB::kVecs % THREADS == 0, "whole vectors per lane");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds_all[];
     auto lds_a = [&](int buf) { return lds_all + buf * TA::kElems; };
     auto lds_b = [&](int buf) { return lds_all + 2 * TA::kElems + buf * TB::kElems; };
@@ -503,8 +510,8 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_full_kernel(GemmDevB p) {
     uint16_t* C = (uint16_t*)p.c + (int64_t)group * p.sc + (int64_t)m0 * p.ldc + n0;
     const uint16_t* Mk = MODE == kDa ? p.mask + (int64_t)group * p.smask + (int64_t)m0 * p.ldc + n0 : nullptr;
 #pragma unroll 4
-    for (int t = 0; t < kVecs / kThreads; ++t) {
-        const int v = threadIdx.x + t * kThreads;
+    for (int t = 0; t < kVecs / THREADS; ++t) {
+        const int v = threadIdx.x + t * THREADS;
         const int rl = v / kVecPerRow, cl = (v % kVecPerRow) * 8;
         u4 o = *(const u4*)(lds_all + rl * SP + cl);
         if (MODE == kDa) {
@@ -573,20 +580,26 @@ static hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     constexpr size_t lds = GemmShape<MODE, BM, BN, BK>::kLdsBytes;
     static_assert(lds <= 160 * 1024, "LDS of a compute unit");
     void (*kern)(GemmDevB) = gemm_bf16_kernel<MODE, BM, BN, BK, DEPTH>;
+    unsigned threads = kThreads;
     if constexpr (MODE != kDw && BK == 64) {
         // full tiles and 32-bit lane offsets: the branch-free, interleaved kernel
         // Register sets of operand slices in flight.  Four sets (three slices of lead time) were measured equal to
-        // two on configuration 3: the loop is bound by the LDS pipe (fragment reads + tile stores), not by load latency.
+        // two on configuration 3 (also with eight wavefronts: 50.9 against 49.7 us): the loop is bound by the LDS pipe
+        // (fragment reads + tile stores), not by load latency.
         constexpr int kSets = 2;
         const bool full = g.M % BM == 0 && g.N % BN == 0 && g.K % (kSets * BK) == 0 &&
                           (int64_t)BM * g.lda < (1 << 29) && (int64_t)(MODE == kFwd ? BK : BN) * g.ldb < (1 << 29);
-        if (full && !g.force_general) kern = gemm_bf16_full_kernel<MODE, BM, BN, BK, kSets>;
+        if (full && !g.force_general) {
+            constexpr int kFullThreads = full_tile_threads<MODE, BM>();
+            kern = gemm_bf16_full_kernel<MODE, BM, BN, BK, kSets, kFullThreads>;
+            threads = kFullThreads;
+        }
     }
     if (lds > 64 * 1024) {
         hipError_t e = ensure_dynamic_lds((const void*)kern, lds);
         if (e != hipSuccess) return e;
     }
-    kern<<<(unsigned)(p.guest.blocks + p.chunk * kXcds), kThreads, lds, s>>>(p);
+    kern<<<(unsigned)(p.guest.blocks + p.chunk * kXcds), threads, lds, s>>>(p);
     return hipGetLastError();
 }
 
