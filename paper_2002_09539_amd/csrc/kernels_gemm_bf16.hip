@@ -45,7 +45,8 @@ constexpr int kXcds = 8;
 // Lanes of the full-tile forward / delta kernel.  Eight wavefronts of 64 x 64 (two per SIMD, which cover each other's
 // LDS waits, at 4/3 of the fragment bytes per MFMA) against four of 128 x 64, measured on 256 x 128 tiles at batch 256:
 // delta GEMM (both operands K-contiguous, 16-byte fragment reads) 48.7 against 54.0 us, forward GEMM (weights read with
-// the 8-byte transpose loads, twice as many read instructions per byte) 58.4 against 54.5 us.
+// the 8-byte transpose loads, twice as many read instructions per byte) 58.4 against 54.5 us, the same with the eight
+// wavefronts laid out 2 x 4 (128 x 32 each) instead of 4 x 2.
 template <int MODE, int BM>
 constexpr int full_tile_threads() { return (MODE == kDa && BM == 256) ? 512 : 256; }
 
