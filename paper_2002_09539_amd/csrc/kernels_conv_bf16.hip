@@ -46,6 +46,9 @@
 // it).  The same treatment of the kernel gradient's slice loads: 0.70 -> 0.33 us of a slice's 2.36 us for the
 // requests, 0.43 -> 0.29 for the LDS stores (186 -> 170 us); its bias column sums now come from the delta fragments the
 // MFMAs use anyway instead of sixteen more LDS reads per slice.
+// The fused tail's shortcut rows (fp32, 16 vectors per lane) are requested in two batches of eight, the first three
+// taps before the end and the second once the tile is staged, instead of both inside the epilogue's loop: 252 -> 241 us
+// (requesting the second batch before the staging as well: 248 us).
 // What moved the kernel gradient from 289 us before that: fragment reads issued a kernel row ahead of the MFMAs (258),
 // the bias column sums shared out over the four wavefronts instead of one wavefront summing while three wait at the
 // barrier (219), and 512 workgroups -- one round at two per compute unit -- instead of 768 (185; the finish pass 46 -> 22).
@@ -288,6 +291,23 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) bq[j][g4] = __builtin_bit_cast(f4, buf_load(bias_rs, 16u * half + 128u * j + 32u * g4, 0u));
     };
+    // Fused tail: the shortcut's fp32 rows that this lane will add (vector l % 16 of the unpadded rows behind the
+    // wavefront's padded rows l / 16 + 4 t) -- the first batch of eight is requested at the same point, the second in
+    // the epilogue while the first is consumed.
+    constexpr int kTailBatch = 8;
+    f4 xpre[OUT == kOutTail ? kTailBatch : 1];
+    int up_pre[OUT == kOutTail ? kTailBatch : 1];
+    const rsrc_t x_rs = make_rsrc(OUT == kOutTail ? (const void*)(p.xres + (int64_t)group * p.s_x) : (const void*)IN,
+                                  OUT == kOutTail ? (unsigned)(p.B * p.H * p.W) * 2u * row_bytes : 0u);
+    auto load_shortcut = [&]() {
+        if constexpr (OUT == kOutTail) {
+#pragma unroll
+            for (int t = 0; t < kTailBatch; ++t) up_pre[t] = row_up[wm0 + lane / (kCB / 4) + 4 * t];
+#pragma unroll
+            for (int t = 0; t < kTailBatch; ++t)   // border rows: -1 wraps to an offset beyond the tensor, zeros come back
+                xpre[t] = __builtin_bit_cast(f4, buf_load(x_rs, (unsigned)up_pre[t] * 2u * row_bytes + 4u * n0 + (lane % (kCB / 4)) * 16u, 0u));
+        }
+    };
     for (int c0 = 0; c0 < C; c0 += kCB) {
         // the previous chunk's last barrier has passed: nobody reads the strip or the kernel buffers any more
         {
@@ -315,6 +335,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
             if (tap + kAhead < 9) load_b(rb[tap % kAhead], tap + kAhead, c0);   // its slice is in LDS already
             if (tap == kMaskTap) {   // in every chunk: a branch here would make the waits on the kernel slices wait for these too
                 if constexpr (MODE == 1) load_mask(); else load_bias();
+                load_shortcut();
             }
             const int dy = tap / 3 - 1, dx = tap % 3 - 1;
             const int shift = (MODE == 0 ? 1 : -1) * (dy * p.Wp + dx);
@@ -336,6 +357,7 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
     OLS_TP(3);   // the taps are done
     if (kMaskTap >= 9) {
         if constexpr (MODE == 1) load_mask(); else load_bias();
+        load_shortcut();
     }
     // Epilogue: the tile goes through LDS (the strip's place) so that every lane then moves 16-byte vectors.
     if constexpr (OUT == kOutTail) {
@@ -344,9 +366,10 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
         // rows in the first and in the second of those samples.  A later pass adds the wavefronts' sums per sample in
         // wavefront order.  Staging as for the fp32 output; lane l then owns the channel quad l % 16 of rows l / 16 + 4 t.
         constexpr int FP = kStagePitchF32, WR = BM / 4;
-        constexpr int kVecPerRow = kCB / 4, kPer = WR * kVecPerRow / 64, kBatch = 8;
+        constexpr int kVecPerRow = kCB / 4, kPer = WR * kVecPerRow / 64, kBatch = kTailBatch;
         static_assert(WR == 64, "the partial sums are kept per 64 rows");
         float* stage = (float*)lds_all + wave * WR * FP;
+        const int r0 = lane / kVecPerRow, cq = lane % kVecPerRow;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -362,19 +385,25 @@ __global__ __launch_bounds__(kThreads, BM == 128 ? 3 : 2) void conv3x3_bf16_kern
         const int q0 = m0 + wm0;                                    // the wavefront's first padded pixel
         const int per = p.Hp * p.Wp;
         const int next_sample = ((int)fast_div((unsigned)q0, p.div_per) + 1) * per;   // first pixel of the second sample
-        const rsrc_t x_rs = make_rsrc(p.xres + (int64_t)group * p.s_x, (unsigned)(p.B * p.H * p.W) * 2u * row_bytes);
         const rsrc_t sg_rs = make_rsrc(p.sign + (int64_t)group * p.s_sign, (unsigned)p.Pp * (unsigned)(C / 4));
-        const int r0 = lane / kVecPerRow, cq = lane % kVecPerRow;
         f4 sum0 = {0.f, 0.f, 0.f, 0.f}, sum1 = {0.f, 0.f, 0.f, 0.f};
+        static_assert(kPer == 2 * kBatch, "two batches of shortcut rows per lane");
+        f4 xnext[kBatch];
+        int up_next[kBatch];
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t) up_next[t] = row_up[wm0 + r0 + 4 * (kBatch + t)];
+#pragma unroll
+        for (int t = 0; t < kBatch; ++t)   // the second batch travels while the first is consumed
+            xnext[t] = __builtin_bit_cast(f4, buf_load(x_rs, (unsigned)up_next[t] * 2u * row_bytes + 4u * n0 + cq * 16u, 0u));
 #pragma unroll
         for (int t0 = 0; t0 < kPer; t0 += kBatch) {
             f4 yv[kBatch], xv[kBatch];
             int up[kBatch];
 #pragma unroll
-            for (int t = 0; t < kBatch; ++t) up[t] = row_up[wm0 + r0 + 4 * (t0 + t)];
-#pragma unroll
-            for (int t = 0; t < kBatch; ++t)   // border rows: -1 wraps to an offset beyond the tensor, zeros come back
-                xv[t] = __builtin_bit_cast(f4, buf_load(x_rs, (unsigned)up[t] * 2u * row_bytes + 4u * n0 + cq * 16u, 0u));
+            for (int t = 0; t < kBatch; ++t) {
+                up[t] = t0 == 0 ? up_pre[t] : up_next[t];
+                xv[t] = t0 == 0 ? xpre[t] : xnext[t];
+            }
 #pragma unroll
             for (int t = 0; t < kBatch; ++t) yv[t] = *(const f4*)(stage + (r0 + 4 * (t0 + t)) * FP + cq * 4);
 #pragma unroll
