@@ -432,17 +432,32 @@ __global__ __launch_bounds__(kThreads, OLS_CONV_DW_WAVES) void conv3x3_dw_kernel
     }
 }
 
-// Sums the parts of every kernel / bias entry over the pixel ranges in range order and writes the gradient.
+// Sums the parts of every kernel / bias entry over the pixel ranges in range order and writes the gradient.  One lane per
+// four consecutive entries (the kernel's and the bias's counts are multiples of four), eight ranges' loads in flight.
 __global__ __launch_bounds__(256) void conv_dw_finish_kernel(const float* __restrict__ partial, int splits, int groups,
                                                              int64_t per_group, int64_t n_w, float* g, int64_t ld,
                                                              int64_t w_off, int64_t b_off) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= per_group) return;
     const int group = blockIdx.y;
-    float s = 0.0f;
-    for (int sp = 0; sp < splits; ++sp) s += partial[((int64_t)sp * groups + group) * per_group + i];
-    if (i < n_w) g[(int64_t)group * ld + w_off + i] = s;
-    else if (b_off >= 0) g[(int64_t)group * ld + b_off + (i - n_w)] = s;   // a convolution without bias has b_off < 0
+    const float* P = partial + (int64_t)group * per_group + i;
+    const int64_t step = (int64_t)groups * per_group;
+    f4 s = {0.f, 0.f, 0.f, 0.f};
+    constexpr int kFly = 8;
+    for (int sp0 = 0; sp0 < splits; sp0 += kFly) {
+        f4 v[kFly];
+#pragma unroll
+        for (int t = 0; t < kFly; ++t)
+            v[t] = sp0 + t < splits ? __builtin_nontemporal_load((const f4*)(P + (sp0 + t) * step)) : f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < kFly; ++t)
+            if (sp0 + t < splits) s = s + v[t];
+    }
+    float* dst = i < n_w ? g + (int64_t)group * ld + w_off + i : b_off >= 0 ? g + (int64_t)group * ld + b_off + (i - n_w) : nullptr;
+    if (dst) {   // a convolution without bias has b_off < 0
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[e] = s[e];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -578,7 +593,8 @@ hipError_t launch_conv_dw_finish(const float* partial, int splits, int groups, i
                                  int64_t b_off, hipStream_t s) {
     if (!partial || !g || splits < 1 || groups < 1 || groups > 65535 || C < 1) return hipErrorInvalidValue;
     const int64_t n_w = (int64_t)9 * C * C, per_group = n_w + C;
-    dim3 grid((unsigned)((per_group + 255) / 256), (unsigned)groups);
+    if (C % 4 || (reinterpret_cast<uintptr_t>(partial) & 15u)) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((per_group / 4 + 255) / 256), (unsigned)groups);
     conv_dw_finish_kernel<<<grid, 256, 0, s>>>(partial, splits, groups, per_group, n_w, g, ld, w_off, b_off);
     return hipGetLastError();
 }
