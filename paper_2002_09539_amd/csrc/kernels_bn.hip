@@ -107,52 +107,82 @@ __global__ __launch_bounds__(kThreads) void bn_stats_final_kernel(const float* _
 }
 
 // The same statistics from per-wavefront parts that a convolution's epilogue left: wpart[group][w][3][C] = count, mean
-// and sum of squared deviations of the image pixels among 64 consecutive padded pixels (count 0: none).  Thirty-two
-// lanes per channel merge every thirty-second part each, in order, by the parallel-variance rule (eight parts are
-// requested at a time: the merge itself is a dependent chain, the loads are not); lane 0 of the channel then merges
-// the thirty-two results in lane order.
-constexpr int kWaveStatChannels = 8, kWaveStatStripes = kThreads / kWaveStatChannels, kWaveStatBatch = 8;
-__global__ __launch_bounds__(kThreads) void bn_stats_waves_kernel(const float* __restrict__ wpart, int64_t s_wpart, float* stats,
-                                                                  int C, int waves, float eps) {
+// and sum of squared deviations of the image pixels among 64 consecutive padded pixels (count 0: none), merged by the
+// parallel-variance rule in a fixed order.  Two levels: a workgroup takes one of up to sixteen contiguous chunks of a
+// group's parts and 64 channels (a part's 64 counts, means or sums are one 256-byte run); each of its four stripes
+// merges every fourth part of the chunk in order, twelve parts requested at a time (the merge is a dependent chain, the
+// loads are not), and stripe 0 merges the four results in stripe order into cpart[group][chunk][3][C].  The second
+// launch merges a channel's chunks in chunk order.  (One level with 8 channels x 32 stripes per workgroup took 27 us at
+// the benchmark shape -- every workgroup touched all of a group's cache lines for an eighth of their bytes; with 4 x 64
+// 40 us.  The two levels take 10 + 5 us; 32 or 16 channels per workgroup and 10 - 19 parts in flight change nothing.)
+constexpr int kWaveStatChunks = 16, kWaveStatChannels = 64, kWaveStatStripes = kThreads / kWaveStatChannels, kWaveStatBatch = 12;
+__host__ __device__ inline int wave_stat_chunks(int P) { const int r = bn_ranges(P); return r < kWaveStatChunks ? r : kWaveStatChunks; }
+
+__device__ __forceinline__ void merge_moments(float& n, float& mean, float& m2, float nr, float mean_r, float m2_r) {
+    if (nr > 0.0f) {
+        const float tot = n + nr, delta = mean_r - mean;
+        mean = mean + delta * (nr / tot);
+        m2 = m2 + m2_r + delta * delta * (n * (nr / tot));
+        n = tot;
+    }
+}
+
+// grid (chunks, groups, C / 64)
+__global__ __launch_bounds__(kThreads) void bn_stats_waves_kernel(const float* __restrict__ wpart, int64_t s_wpart, float* cpart,
+                                                                  int C, int waves, int chunks) {
     __shared__ float lds[3][kThreads];
     const int cl = threadIdx.x % kWaveStatChannels, stripe = threadIdx.x / kWaveStatChannels;
-    const int c = blockIdx.x * kWaveStatChannels + cl, g = blockIdx.y;
+    const int c = blockIdx.z * kWaveStatChannels + cl, g = blockIdx.y, k = blockIdx.x;
+    const int per = (waves + chunks - 1) / chunks;
+    const int lo = k * per, hi = min(waves, lo + per);
     float n = 0.0f, mean = 0.0f, m2 = 0.0f;
-    auto merge = [&](float nr, float mean_r, float m2_r) {
-        if (nr > 0.0f) {
-            const float tot = n + nr, delta = mean_r - mean;
-            mean = mean + delta * (nr / tot);
-            m2 = m2 + m2_r + delta * delta * (n * (nr / tot));
-            n = tot;
-        }
-    };
-    if (c < C) {
-        const float* P = wpart + (int64_t)g * s_wpart + c;
-        for (int w0 = stripe; w0 < waves; w0 += kWaveStatStripes * kWaveStatBatch) {
-            float nr[kWaveStatBatch], mr[kWaveStatBatch], qr[kWaveStatBatch];
+    const float* P = wpart + (int64_t)g * s_wpart + c;
+    for (int w0 = lo + stripe; w0 < hi; w0 += kWaveStatStripes * kWaveStatBatch) {
+        float nr[kWaveStatBatch], mr[kWaveStatBatch], qr[kWaveStatBatch];
 #pragma unroll
-            for (int u = 0; u < kWaveStatBatch; ++u) {
-                const int w = w0 + u * kWaveStatStripes;
-                const float* o = P + (int64_t)(w < waves ? w : 0) * 3 * C;
-                nr[u] = w < waves ? o[0] : 0.0f;
-                mr[u] = o[C];
-                qr[u] = o[2 * C];
-            }
-#pragma unroll
-            for (int u = 0; u < kWaveStatBatch; ++u) merge(nr[u], mr[u], qr[u]);
+        for (int u = 0; u < kWaveStatBatch; ++u) {
+            const int w = w0 + u * kWaveStatStripes;
+            const float* o = P + (int64_t)(w < hi ? w : lo) * 3 * C;   // past the chunk: an in-range part, not merged
+            nr[u] = w < hi ? o[0] : 0.0f;
+            mr[u] = o[C];
+            qr[u] = o[2 * C];
         }
+#pragma unroll
+        for (int u = 0; u < kWaveStatBatch; ++u) merge_moments(n, mean, m2, nr[u], mr[u], qr[u]);
     }
     lds[0][threadIdx.x] = n;
     lds[1][threadIdx.x] = mean;
     lds[2][threadIdx.x] = m2;
     __syncthreads();
-    if (stripe == 0 && c < C) {
+    if (stripe == 0) {
         for (int s = 1; s < kWaveStatStripes; ++s)
-            merge(lds[0][s * kWaveStatChannels + cl], lds[1][s * kWaveStatChannels + cl], lds[2][s * kWaveStatChannels + cl]);
-        const float var = fmaxf(m2 / n, 0.0f);
-        stats[((int64_t)g * 2) * C + c] = mean;
-        stats[((int64_t)g * 2 + 1) * C + c] = 1.0f / sqrtf(var + eps);
+            merge_moments(n, mean, m2, lds[0][s * kWaveStatChannels + cl], lds[1][s * kWaveStatChannels + cl], lds[2][s * kWaveStatChannels + cl]);
+        float* o = cpart + (((int64_t)g * chunks + k) * 3) * C + c;
+        o[0] = n;
+        o[C] = mean;
+        o[2 * C] = m2;
     }
+}
+
+// grid (ceil(C / 256), groups): one lane per channel merges its chunks in chunk order
+__global__ __launch_bounds__(kThreads) void bn_stats_chunks_kernel(const float* __restrict__ cpart, float* stats, int C, int chunks, float eps) {
+    const int c = blockIdx.x * kThreads + threadIdx.x, g = blockIdx.y;
+    if (c >= C) return;
+    float n = 0.0f, mean = 0.0f, m2 = 0.0f;
+    const float* P = cpart + (int64_t)g * chunks * 3 * C + c;
+    float nr[kWaveStatChunks], mr[kWaveStatChunks], qr[kWaveStatChunks];
+#pragma unroll
+    for (int k = 0; k < kWaveStatChunks; ++k) {   // all loads first: only the merge is a dependent chain
+        const float* o = P + (int64_t)(k < chunks ? k : 0) * 3 * C;
+        nr[k] = k < chunks ? o[0] : 0.0f;
+        mr[k] = o[C];
+        qr[k] = o[2 * C];
+    }
+#pragma unroll
+    for (int k = 0; k < kWaveStatChunks; ++k) merge_moments(n, mean, m2, nr[k], mr[k], qr[k]);
+    const float var = fmaxf(m2 / n, 0.0f);
+    stats[((int64_t)g * 2) * C + c] = mean;
+    stats[((int64_t)g * 2 + 1) * C + c] = 1.0f / sqrtf(var + eps);
 }
 
 // Where a result becomes the operand of a bf16 convolution it is written as bf16 (to nearest even) into that operand's
@@ -421,9 +451,13 @@ hipError_t launch_bn_forward(const BnArgs& a, hipStream_t s) {
         return hipErrorInvalidValue;
     hipError_t e;
     if (a.wave_part) {   // the producer of z left per-wavefront statistics: z is not read for them
-        if (a.waves < 1 || !aligned16(a.wave_part)) return hipErrorInvalidValue;
-        bn_stats_waves_kernel<<<dim3((unsigned)((a.C + kWaveStatChannels - 1) / kWaveStatChannels), (unsigned)a.groups), kThreads, 0, s>>>(
-            a.wave_part, (int64_t)a.waves * 3 * a.C, a.stats, a.C, a.waves, a.eps);
+        if (a.waves < 1 || !aligned16(a.wave_part) || a.C % kWaveStatChannels) return hipErrorInvalidValue;
+        const int chunks = wave_stat_chunks(a.P);   // their results fit the ranges' buffer: chunks <= bn_ranges(P)
+        bn_stats_waves_kernel<<<dim3((unsigned)chunks, (unsigned)a.groups, (unsigned)(a.C / kWaveStatChannels)), kThreads, 0, s>>>(
+            a.wave_part, (int64_t)a.waves * 3 * a.C, a.part, a.C, a.waves, chunks);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        bn_stats_chunks_kernel<<<dim3((unsigned)((a.C + kThreads - 1) / kThreads), (unsigned)a.groups), kThreads, 0, s>>>(a.part, a.stats, a.C, chunks, a.eps);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     } else {
