@@ -871,9 +871,18 @@ __global__ __launch_bounds__(kThreads) void pool_finish_kernel(const float* __re
     const f4* P = (const f4*)(part + (int64_t)g * s_part) + c4;
     const int w_lo = (n * per) / 64, w_hi = ((n + 1) * per - 1) / 64;
     f4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int w = w_lo; w <= w_hi; ++w) {
-        const int slot = n - (64 * w) / per;   // 0 or 1
-        acc = acc + P[(int64_t)(2 * w + slot) * c4n];
+    constexpr int kFly = 8;   // the loads of eight parts ahead of their additions
+    for (int w0 = w_lo; w0 <= w_hi; w0 += kFly) {
+        f4 v[kFly];
+#pragma unroll
+        for (int t = 0; t < kFly; ++t) {
+            const int w = w0 + t <= w_hi ? w0 + t : w_hi;
+            const int slot = n - (64 * w) / per;   // 0 or 1
+            v[t] = P[(int64_t)(2 * w + slot) * c4n];
+        }
+#pragma unroll
+        for (int t = 0; t < kFly; ++t)
+            if (w0 + t <= w_hi) acc = acc + v[t];
     }
     f4 o;
 #pragma unroll
