@@ -18,7 +18,9 @@
 // bytes and 64-pixel partial sums of the pooling instead of the stored activation); its backward pass can form the
 // gradient under pooling and ReLU on the fly from the pooled gradient and those sign bytes; and a result that becomes a
 // bf16 convolution's operand can be written as bf16 straight into that operand's padded layout.
-// Measured and not kept: four vectors per lane in the two apply kernels (150 / 190 / 225 us either way); the first
+// Measured and not kept: four vectors per lane in the two apply kernels (150 / 190 / 225 us either way); eight channels
+// per lane with one 16-byte store of the bf16 result instead of 8-byte stores (the backward apply kernels 10 us slower
+// each); the first
 // normalisation's backward sums formed in the epilogue of the delta convolution that produces its gradient (the
 // convolution grows by the 86 us that the saved pass over gradient and input took beyond its own share).
 #include "fast_div.h"
