@@ -148,7 +148,9 @@ hipError_t launch_mean(const MeanArgs& a, hipStream_t s) {
 // loads in flight per lane): 256 x 4: 681, 64 x 4: 652, 128 x 4: 680, 512 x 4: 698, 256 x 16: 662,
 // 64 x 8: 644, 64 x 16: 634 -- single-wavefront workgroups with a whole 16-replica column in flight.
 // Two or four 16-byte columns per lane (2-4 KiB contiguous per wavefront and row) with proportionally fewer rows
-// in flight were slower (667-691).
+// in flight were slower (667-691).  Giving each XCD (workgroup id mod 8) a contiguous eighth of the columns instead of
+// every eighth 1 KiB span was slower too (681 against 635 us; the local step 561 against 552): HBM serves the chip best
+// when all its compute units work on neighbouring addresses.
 #ifndef OLS_SPM_THREADS
 #define OLS_SPM_THREADS 64
 #endif
